@@ -1,0 +1,18 @@
+"""Builds the plain-C oracle with gcc (test infrastructure; no GPU code involved)."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libmux_oracle.so")
+
+
+def build_oracle() -> str:
+    src = os.path.join(HERE, "mux_oracle.c")
+    tmp = LIB_PATH + f".tmp{os.getpid()}"
+    subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", tmp, src])
+    os.replace(tmp, LIB_PATH)
+    return LIB_PATH
+
+
+if __name__ == "__main__":
+    print(build_oracle())
