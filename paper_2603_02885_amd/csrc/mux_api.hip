@@ -1,0 +1,171 @@
+// Entry points of the layer: argument checks, buffer carving, kernel sequencing.
+#include <cstring>
+
+#include "mux_device_utils.h"
+
+namespace mux {
+
+// Launch-argument block for k_fill_tasks: adapter pointers of up to 16 tasks.
+struct TaskPtrArgs {
+  const void* A[16];
+  const void* B[16];
+  const void* L[16];
+  float* dA[16];
+  float* dB[16];
+  float* dL[16];
+};
+
+__global__ void k_fill_tasks(const int32_t* __restrict__ dtab, DevTask* __restrict__ out, TaskPtrArgs p, int base, int count) {
+  const int i = threadIdx.x;
+  if (i >= count) return;
+  const int32_t* te = dtab + dtab[DH_OFF_TASKS] + (base + i) * DT_WORDS;
+  DevTask d;
+  d.A = p.A[i]; d.B = p.B[i]; d.L = p.L[i];
+  d.dA = p.dA[i]; d.dB = p.dB[i]; d.dL = p.dL[i];
+  d.scale = __int_as_float(te[DT_SCALE_BITS]);
+  d.kind = te[DT_KIND];
+  d.rank = te[DT_RANK];
+  d.row_begin = te[DT_ROW_BEGIN];
+  d.row_count = te[DT_ROW_COUNT];
+  d.zrow0 = te[DT_ZROW0];
+  d.pad_ = 0;
+  out[base + i] = d;
+}
+
+namespace {
+
+struct Layout {
+  size_t esz;          // bytes per stored element
+  int RP;              // H / G row pitch in elements
+  size_t h_bytes, z_bytes, saved_bytes;
+  size_t tasks_bytes, g_bytes, part_bytes, ws_bytes;
+};
+
+Layout make_layout(const mux_layer_desc* L, const mux_segtab* st) {
+  Layout o{};
+  o.esz = L->dtype == MUX_DT_F32 ? 4 : 2;
+  o.RP = st->n_lora > 0 ? round_up(st->r_max, 16) : 0;
+  o.h_bytes = align256((size_t)st->T * o.RP * o.esz);
+  o.z_bytes = align256((size_t)st->z_rows * (size_t)L->N * o.esz);
+  o.saved_bytes = o.h_bytes + o.z_bytes;
+  o.tasks_bytes = align256((size_t)st->n_tasks * sizeof(DevTask));
+  o.g_bytes = o.h_bytes;
+  o.part_bytes = fast_partial_bytes(L->K, L->N, st);
+  o.ws_bytes = o.tasks_bytes + o.g_bytes + o.part_bytes;
+  return o;
+}
+
+mux_status check_layer(const char* fn, const mux_layer_desc* L, const mux_segtab* st) {
+  if (!L || !st) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": null layer or table");
+  if (L->K <= 0 || L->N <= 0) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": K and N must be positive");
+  if (L->dtype != MUX_DT_BF16 && L->dtype != MUX_DT_F32) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": unknown dtype");
+  if (L->flags & ~MUX_LAYER_REFERENCE_KERNELS) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": unknown layer flag");
+  if (!L->W) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": W is null");
+  if (L->ldw < L->N) return fail(MUX_ERR_SHAPE, std::string(fn) + ": ldw < N");
+  if (L->n_tasks != st->n_tasks) return fail(MUX_ERR_SHAPE, std::string(fn) + ": layer and table disagree on the number of tasks");
+  if ((int64_t)st->T * (int64_t)(L->K > L->N ? L->K : L->N) >= ((int64_t)1 << 40))
+    return fail(MUX_ERR_SHAPE, std::string(fn) + ": problem too large");
+  for (int t = 0; t < st->n_tasks; ++t) {
+    const HostTask& ht = st->tasks[t];
+    if (ht.kind == MUX_ADAPTER_LORA && (!L->A || !L->B || !L->A[t] || !L->B[t]))
+      return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": LoRA task without A or B");
+    if (ht.kind == MUX_ADAPTER_IA3_OUT && (!L->L || !L->L[t]))
+      return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": IA3 task without scale vector");
+  }
+  return MUX_OK;
+}
+
+mux_status check_hip(const char* fn) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(MUX_ERR_DEVICE, std::string(fn) + ": " + hipGetErrorString(e));
+  return MUX_OK;
+}
+
+void fill_tasks(const mux_layer_desc* L, const mux_segtab* st, const int32_t* dtab, DevTask* dtasks, void* const* dA,
+                void* const* dB, void* const* dL, hipStream_t stream) {
+  for (int base = 0; base < st->n_tasks; base += 16) {
+    TaskPtrArgs p;
+    std::memset(&p, 0, sizeof(p));
+    const int count = st->n_tasks - base < 16 ? st->n_tasks - base : 16;
+    for (int i = 0; i < count; ++i) {
+      const int t = base + i;
+      const int kind = st->tasks[t].kind;
+      p.A[i] = (kind == MUX_ADAPTER_LORA) ? L->A[t] : nullptr;
+      p.B[i] = (kind == MUX_ADAPTER_LORA) ? L->B[t] : nullptr;
+      p.L[i] = (kind == MUX_ADAPTER_IA3_OUT) ? L->L[t] : nullptr;
+      p.dA[i] = (kind == MUX_ADAPTER_LORA && dA) ? (float*)dA[t] : nullptr;
+      p.dB[i] = (kind == MUX_ADAPTER_LORA && dB) ? (float*)dB[t] : nullptr;
+      p.dL[i] = (kind == MUX_ADAPTER_IA3_OUT && dL) ? (float*)dL[t] : nullptr;
+    }
+    hipLaunchKernelGGL(k_fill_tasks, dim3(1), dim3(64), 0, stream, dtab, dtasks, p, base, count);
+  }
+}
+
+}  // namespace
+}  // namespace mux
+
+using namespace mux;
+
+extern "C" size_t mux_lora_saved_bytes(const mux_layer_desc* layer, const mux_segtab* st) {
+  if (!layer || !st || layer->N <= 0) return 0;
+  return make_layout(layer, st).saved_bytes;
+}
+
+extern "C" size_t mux_lora_workspace_bytes(const mux_layer_desc* layer, const mux_segtab* st) {
+  if (!layer || !st || layer->N <= 0 || layer->K <= 0) return 0;
+  return make_layout(layer, st).ws_bytes;
+}
+
+extern "C" mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_segtab* st, const void* dev_segtab,
+                                       const void* X, void* Y, void* saved, void* ws, size_t ws_bytes, void* hip_stream) {
+  static const char* fn = "mux_lora_forward";
+  if (mux_status s = check_layer(fn, layer, st)) return s;
+  if (st->T == 0) return MUX_OK;
+  if (!dev_segtab || !X || !Y || !ws) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": null device pointer");
+  const Layout lo = make_layout(layer, st);
+  if (ws_bytes < lo.ws_bytes) return fail(MUX_ERR_WORKSPACE, std::string(fn) + ": workspace too small");
+  if (!saved && st->n_lora > 0) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": saved is null but a task is LoRA");
+  hipStream_t stream = (hipStream_t)hip_stream;
+  DevTask* dtasks = (DevTask*)ws;
+  fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, nullptr, nullptr, nullptr, stream);
+  CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP, layer->W, stream};
+  void* H = saved;
+  void* Z = (saved && st->z_rows > 0) ? (char*)saved + lo.h_bytes : nullptr;
+  mux_status s;
+  if (layer->dtype == MUX_DT_F32 || (layer->flags & MUX_LAYER_REFERENCE_KERNELS))
+    s = ref_forward(c, layer->dtype, X, Y, H, Z);
+  else
+    s = fast_forward(c, X, Y, H, Z, (char*)ws + lo.tasks_bytes + lo.g_bytes);
+  if (s) return s;
+  return check_hip(fn);
+}
+
+extern "C" mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_segtab* st, const void* dev_segtab,
+                                        const void* X, const void* dY, const void* saved, void* dX, void* const* dA,
+                                        void* const* dB, void* const* dL, int accumulate, void* ws, size_t ws_bytes,
+                                        void* hip_stream) {
+  static const char* fn = "mux_lora_backward";
+  if (mux_status s = check_layer(fn, layer, st)) return s;
+  if (accumulate != 0 && accumulate != 1) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": accumulate must be 0 or 1");
+  if (st->T == 0 && st->n_tasks == 0) return MUX_OK;
+  if (!dev_segtab || !ws) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": null device pointer");
+  if (st->T > 0 && (!X || !dY)) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": null device pointer");
+  if (!saved && st->T > 0 && (st->n_lora > 0 || st->n_ia3 > 0))
+    return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": saved is null but a task has an adapter");
+  const Layout lo = make_layout(layer, st);
+  if (ws_bytes < lo.ws_bytes) return fail(MUX_ERR_WORKSPACE, std::string(fn) + ": workspace too small");
+  hipStream_t stream = (hipStream_t)hip_stream;
+  DevTask* dtasks = (DevTask*)ws;
+  fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, dA, dB, dL, stream);
+  CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP, layer->W, stream};
+  const void* H = saved;
+  const void* Z = (saved && st->z_rows > 0) ? (const char*)saved + lo.h_bytes : nullptr;
+  void* G = (char*)ws + lo.tasks_bytes;
+  mux_status s;
+  if (layer->dtype == MUX_DT_F32 || (layer->flags & MUX_LAYER_REFERENCE_KERNELS))
+    s = ref_backward(c, layer->dtype, X, dY, H, Z, G, dX, accumulate);
+  else
+    s = fast_backward(c, X, dY, H, Z, G, dX, accumulate, (char*)ws + lo.tasks_bytes + lo.g_bytes);
+  if (s) return s;
+  return check_hip(fn);
+}

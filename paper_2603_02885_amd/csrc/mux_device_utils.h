@@ -1,0 +1,49 @@
+// Small device helpers shared by the kernels: bf16 conversion, table access.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mux_internal.h"
+
+namespace mux {
+
+typedef uint16_t bf16_t;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float((uint32_t)v << 16); }
+
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x0040u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+template <class S> struct Store;
+template <> struct Store<float> {
+  static __device__ __forceinline__ float ld(const float* p, size_t i) { return p[i]; }
+  static __device__ __forceinline__ void st(float* p, size_t i, float v) { p[i] = v; }
+};
+template <> struct Store<bf16_t> {
+  static __device__ __forceinline__ float ld(const bf16_t* p, size_t i) { return bf16_to_f32(p[i]); }
+  static __device__ __forceinline__ void st(bf16_t* p, size_t i, float v) { p[i] = f32_to_bf16(v); }
+};
+
+// Row i is a real token iff (i mod chunk) < valid_rows[i div chunk]  (chunk is a power of two).
+__device__ __forceinline__ bool row_is_valid(const int32_t* __restrict__ dtab, int row) {
+  const int lg = dtab[DH_LOG2C];
+  const int ch = row >> lg;
+  return (row & ((1 << lg) - 1)) < dtab[dtab[DH_OFF_CHUNK_VALID] + ch];
+}
+
+struct ItemView { int task, row0, nrows, nvalid; };
+__device__ __forceinline__ ItemView load_item(const int32_t* __restrict__ dtab, int tile_size_index, int item) {
+  const int32_t* p = dtab + dtab[DH_NITEMS0 + 3 * tile_size_index + 1] + item * DI_WORDS;
+  return {p[DI_TASK], p[DI_ROW0], p[DI_NROWS], p[DI_NVALID]};
+}
+
+}  // namespace mux

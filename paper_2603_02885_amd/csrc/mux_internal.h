@@ -1,0 +1,101 @@
+// Internal declarations shared by the host code and the kernels of the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "mux.h"
+
+namespace mux {
+
+// ---- device image of the segment table (int32 words) ------------------------------------
+// hdr[32] followed by the sections whose word offsets the header gives.
+enum : int {
+  DH_MAGIC = 0, DH_T, DH_CHUNK, DH_LOG2C, DH_NTASKS, DH_NCHUNKS, DH_OFF_TASKS, DH_OFF_CHUNK_VALID,
+  DH_NITEMS0,            // + 3*i : n_items, off_items, off_task_items for tile size kTileRows[i]
+  DH_ZROWS = DH_NITEMS0 + 9, DH_RMAX, DH_WORDS, DH_HDR_WORDS = 32
+};
+constexpr int kNumTileSizes = 3;
+constexpr int kTileRows[kNumTileSizes] = {64, 128, 256};
+constexpr uint32_t kDevMagic = 0x4458554Du;  // "MUXD"
+
+// per task, 8 words
+enum : int { DT_ROW_BEGIN = 0, DT_ROW_COUNT, DT_VALID, DT_KIND, DT_RANK, DT_SCALE_BITS, DT_ZROW0, DT_ITEM_PAD, DT_WORDS };
+// per work item, 4 words: rows [row0, row0+nrows) all belong to `task` (-1: rows of no task)
+enum : int { DI_TASK = 0, DI_ROW0, DI_NROWS, DI_NVALID, DI_WORDS };
+
+// Per-call task parameters in device memory (filled by a small kernel from launch arguments).
+struct DevTask {
+  const void* A;
+  const void* B;
+  const void* L;
+  float* dA;
+  float* dB;
+  float* dL;
+  float scale;
+  int32_t kind;
+  int32_t rank;
+  int32_t row_begin;
+  int32_t row_count;
+  int32_t zrow0;      // first row of this task inside the saved x W region (IA3_OUT), else -1
+  int64_t pad_;
+};
+static_assert(sizeof(DevTask) == 80, "DevTask layout");
+
+struct HostTask {
+  int32_t kind, rank;
+  float scale;
+  int32_t row_begin, row_count, valid, zrow0;
+};
+
+struct Item { int32_t task, row0, nrows, nvalid; };
+
+}  // namespace mux
+
+struct mux_segtab {
+  int32_t n_tasks = 0, chunk = 0, log2c = 0, n_chunks = 0, T = 0, valid_total = 0;
+  int32_t max_pack_len = 0;
+  uint32_t flags = 0;
+  int32_t r_max = 0, z_rows = 0, n_lora = 0, n_ia3 = 0;
+  std::vector<int32_t> image;       // canonical serialisation
+  std::vector<int32_t> dev_image;   // device image (host copy, source of the upload)
+  std::vector<int32_t> row_task;    // T entries
+  std::vector<mux::HostTask> tasks;
+  std::vector<mux::Item> items[mux::kNumTileSizes];
+  std::vector<int32_t> task_item_begin[mux::kNumTileSizes], task_item_count[mux::kNumTileSizes];
+};
+
+namespace mux {
+
+mux_status fail(mux_status s, const std::string& msg);
+void clear_error();
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
+
+// Everything a kernel launcher needs about one call.
+struct CallCtx {
+  const mux_segtab* st;
+  const int32_t* dtab;     // device image
+  const DevTask* dtasks;   // device, in workspace
+  int K, N;
+  int64_t ldw;
+  int RP;                  // row pitch (elements) of the H / G buffers
+  const void* W;
+  hipStream_t stream;
+};
+
+// plain (non matrix-core) kernels, both storage types
+mux_status ref_forward(const CallCtx& c, int dtype, const void* X, void* Y, void* H, void* Z);
+mux_status ref_backward(const CallCtx& c, int dtype, const void* X, const void* dY, const void* H,
+                        const void* Z, void* G, void* dX, int accumulate);
+
+
+// matrix-core (MFMA) kernels, bf16 storage
+size_t fast_partial_bytes(int K, int N, const mux_segtab* st);
+mux_status fast_forward(const CallCtx& c, const void* X, void* Y, void* H, void* Z, void* part);
+mux_status fast_backward(const CallCtx& c, const void* X, const void* dY, const void* H, const void* Z, void* G, void* dX,
+                         int accumulate, void* part);
+
+}  // namespace mux

@@ -1,0 +1,161 @@
+"""GPU parity: the HIP path through the C ABI against the fp64 oracle, same seeded inputs."""
+import numpy as np
+import pytest
+
+import mux_workloads as wlm
+from tests import mux_harness as hz
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2603_02885_amd as mx
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    mx.load_library()
+    return mx, torch
+
+
+def oracle_table(wl, seg_flags=0, max_pack_len=None):
+    from oracle import segtab
+    return segtab.build([t.seq_lens for t in wl.tasks], wl.chunk,
+                        wl.max_pack_len if max_pack_len is None else max_pack_len, seg_flags)
+
+
+def run_case(env, wl, layer=0, seed=0, dtype=None, seg_flags=0, layer_flags=0, pad_fill=1e30, cols=None, kcols=None,
+             label=""):
+    mx, torch = env
+    dtype = mx.MUX_DT_BF16 if dtype is None else dtype
+    ot = oracle_table(wl, seg_flags)
+    bf16 = dtype == mx.MUX_DT_BF16
+    lt = wlm.layer_tensors(wl, layer, ot.T, seed=seed, bf16=bf16, pad_rows=ot.row_task < 0, pad_fill=pad_fill)
+    g = hz.GpuLayer(mx, torch, wl, lt, dtype, seg_flags=seg_flags, layer_flags=layer_flags)
+    assert np.array_equal(mx.mux_segtab_serialize(g.st), ot.image)          # table bit-exact
+    g.forward()
+    g.backward()
+    got = g.results()
+    ref = hz.oracle_results(wl, lt, ot.row_task, cols=cols, kcols=kcols)
+    tol = hz.TOL_BF16 if bf16 else hz.TOL_F32
+    errs = hz.compare(got, ref, tol, cols=cols, kcols=kcols, label=label or wl.name)
+    pad = ot.row_task < 0
+    assert np.all(got["Y"][pad] == 0) and np.all(got["dX"][pad] == 0)       # padding rows written as zero
+    return g, got, ref, errs
+
+
+def mixed_workload(K=320, N=200, chunk=64):
+    """All adapter kinds, ragged ranks and token counts, several 64-row tiles and ragged tails."""
+    tasks = [wlm.Task(wlm.KIND_LORA, 8, 2.0, [100]), wlm.Task(wlm.KIND_IA3, 0, 1.0, [70, 30, 45]),
+             wlm.Task(wlm.KIND_LORA, 33, 0.5, [150, 21]), wlm.Task(wlm.KIND_NONE, 0, 1.0, [64]),
+             wlm.Task(wlm.KIND_LORA, 64, 1.5, [5]), wlm.Task(wlm.KIND_LORA, 16, 2.0, [])]
+    return wlm.Workload(name="mixed", layers=[("w", K, N)], tasks=tasks, chunk=chunk, sigma_w=0.05, sigma_ab=0.05)
+
+
+@pytest.mark.parametrize("seg_flags", [0, 1])
+@pytest.mark.parametrize("mode", ["bf16", "bf16_ref", "f32"])
+def test_config1_tiny(env, mode, seg_flags):
+    mx, _ = env
+    dtype = mx.MUX_DT_F32 if mode == "f32" else mx.MUX_DT_BF16
+    lf = mx.MUX_LAYER_REFERENCE_KERNELS if mode == "bf16_ref" else 0
+    for seed in (0, 1, 2):
+        run_case(env, wlm.config(0), seed=seed, dtype=dtype, seg_flags=seg_flags, layer_flags=lf)
+
+
+@pytest.mark.parametrize("seg_flags", [0, 1])
+@pytest.mark.parametrize("mode", ["bf16", "bf16_ref", "f32"])
+def test_mixed_kinds_ragged(env, mode, seg_flags):
+    mx, _ = env
+    dtype = mx.MUX_DT_F32 if mode == "f32" else mx.MUX_DT_BF16
+    lf = mx.MUX_LAYER_REFERENCE_KERNELS if mode == "bf16_ref" else 0
+    run_case(env, mixed_workload(), dtype=dtype, seg_flags=seg_flags, layer_flags=lf)
+    run_case(env, mixed_workload(K=264, N=328, chunk=16), dtype=dtype, seg_flags=seg_flags, layer_flags=lf, seed=1)
+
+
+def test_accumulate_and_determinism(env):
+    mx, torch = env
+    wl = mixed_workload()
+    g, got, ref, _ = run_case(env, wl)
+    first = {k: [None if t is None else t.clone() for t in getattr(g, k)] for k in ("dA", "dB", "dL")}
+    y1, dx1 = g.Y.clone(), g.dX.clone()
+    g.forward(); g.backward()                     # same inputs again: bit-identical
+    torch.cuda.synchronize()
+    assert torch.equal(g.Y, y1) and torch.equal(g.dX, dx1)
+    for k in first:
+        for a, b in zip(first[k], getattr(g, k)):
+            assert a is None or torch.equal(a, b)
+    g.backward(accumulate=1)                      # adds to what the buffers hold
+    torch.cuda.synchronize()
+    for k in first:
+        for a, b in zip(first[k], getattr(g, k)):
+            assert a is None or torch.allclose(b, 2 * a, rtol=1e-6, atol=0)
+
+
+def test_nan_isolation(env):
+    """Poisoning one task's rows, adapters and every padding row with NaN/Inf leaves the other
+    tasks' outputs and gradients bit-identical (section 3.2)."""
+    mx, torch = env
+    wl = mixed_workload()
+    g, got, _, _ = run_case(env, wl)
+    ot = oracle_table(wl)
+    j = 2
+    rows = torch.from_numpy(ot.task_rows[j]).to("cuda:0")
+    pad = torch.from_numpy(np.nonzero(ot.row_task < 0)[0]).to("cuda:0")
+    g.X[rows] = float("nan"); g.dY[rows] = float("inf")
+    g.X[pad] = float("nan"); g.dY[pad] = float("nan")
+    g.A[j].fill_(float("nan")); g.B[j].fill_(float("nan"))
+    g.forward(); g.backward()
+    got2 = g.results()
+    for t in range(len(wl.tasks)):
+        if t == j:
+            continue
+        r = ot.task_rows[t]
+        assert np.array_equal(got2["Y"][r], got["Y"][r]) and np.array_equal(got2["dX"][r], got["dX"][r])
+        for k in ("dA", "dB", "dL"):
+            if got[k][t] is not None:
+                assert np.array_equal(got2[k][t], got[k][t])
+    p = ot.row_task < 0
+    assert np.all(got2["Y"][p] == 0) and np.all(got2["dX"][p] == 0)
+
+
+def test_dynamic_task_attach(env):
+    """A task arriving between calls (section 3.1, register_tasks): a new table and a longer layer
+    description; the tasks already there get bit-identical results."""
+    mx, torch = env
+    wl = mixed_workload()
+    g, got, _, _ = run_case(env, wl)
+    ot = oracle_table(wl)
+    wl2 = mixed_workload()
+    wl2.tasks = wl.tasks + [wlm.Task(wlm.KIND_LORA, 12, 1.0, [40, 40])]
+    ot2 = oracle_table(wl2)
+    lt2 = wlm.layer_tensors(wl2, 0, ot2.T, seed=0)
+    for t in range(len(wl.tasks)):            # same data for the old tasks
+        lt2.X[ot2.task_rows[t]] = g.lt.X[ot.task_rows[t]]
+        lt2.dY[ot2.task_rows[t]] = g.lt.dY[ot.task_rows[t]]
+        lt2.A[t], lt2.B[t], lt2.L[t] = g.lt.A[t], g.lt.B[t], g.lt.L[t]
+    lt2.W = g.lt.W
+    g2 = hz.GpuLayer(mx, torch, wl2, lt2, mx.MUX_DT_BF16)
+    g2.forward(); g2.backward()
+    got2 = g2.results()
+    for t in range(len(wl.tasks)):
+        assert np.array_equal(got2["Y"][ot2.task_rows[t]], got["Y"][ot.task_rows[t]])
+        assert np.array_equal(got2["dX"][ot2.task_rows[t]], got["dX"][ot.task_rows[t]])
+        for k in ("dA", "dB", "dL"):
+            if got[k][t] is not None:
+                assert np.array_equal(got2[k][t], got[k][t])
+    ref2 = hz.oracle_results(wl2, lt2, ot2.row_task)
+    hz.compare(got2, ref2, hz.TOL_BF16, label="attach")
+
+
+def test_errors_launch_nothing(env):
+    mx, torch = env
+    wl = wlm.config(0)
+    ot = oracle_table(wl)
+    lt = wlm.layer_tensors(wl, 0, ot.T)
+    g = hz.GpuLayer(mx, torch, wl, lt, mx.MUX_DT_BF16)
+    with pytest.raises(mx.MuxError) as e:
+        mx.mux_lora_forward(g.layer, g.st, g.dtab, g.X, g.Y, g.saved, g.ws, 16, torch.cuda.current_stream())
+    assert e.value.status == 4
+    with pytest.raises(mx.MuxError):
+        mx.mux_lora_forward(g.layer, g.st, g.dtab, None, g.Y, g.saved, g.ws, g.ws_bytes, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    assert torch.isnan(g.Y.float()).all()          # nothing was written
