@@ -92,6 +92,16 @@ mux_status ref_backward(const CallCtx& c, int dtype, const void* X, const void* 
                         const void* Z, void* G, void* dX, int accumulate);
 
 
+// the same plain kernels, step by step (bit mask)
+enum : unsigned { REF_DOWN = 1, REF_FWD = 2, REF_G = 4, REF_DB = 8, REF_DA = 16, REF_DL = 32, REF_DX = 64 };
+void ref_steps(const CallCtx& c, int dtype, unsigned which, const void* X, const void* dY, void* Y, void* dX, void* H,
+               void* Z, void* G, int accumulate);
+
+// matrix-core backbone GEMM (bf16)
+bool gemm_mfma_supported(const CallCtx& c);
+mux_status gemm_mfma_forward(const CallCtx& c, const void* X, const void* Hs, void* Y, void* Z);
+mux_status gemm_mfma_backward(const CallCtx& c, const void* dY, const void* Gs, void* dX);
+
 // matrix-core (MFMA) kernels, bf16 storage
 size_t fast_partial_bytes(int K, int N, const mux_segtab* st);
 mux_status fast_forward(const CallCtx& c, const void* X, void* Y, void* H, void* Z, void* part);

@@ -285,48 +285,52 @@ __global__ __launch_bounds__(256) void k_ref_dl(const int32_t* __restrict__ dtab
 }
 
 template <class S>
-mux_status fwd_impl(const CallCtx& c, const void* X, void* Y, void* H, void* Z) {
-  const int n_items = (int)c.st->items[TS64].size();
-  if (n_items == 0) return MUX_OK;
-  if (c.st->n_lora > 0)
-    hipLaunchKernelGGL(k_ref_down<S>, dim3(n_items), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)X, (S*)H, c.K, c.RP);
-  hipLaunchKernelGGL(k_ref_fwd<S>, dim3(n_items, (c.N + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)X,
-                     (const S*)c.W, c.ldw, (const S*)H, (S*)Y, (S*)Z, c.K, c.N, c.RP);
-  return MUX_OK;
-}
-
-template <class S>
-mux_status bwd_impl(const CallCtx& c, const void* X, const void* dY, const void* H, const void* Z, void* G, void* dX,
-                    int accumulate) {
+void steps(const CallCtx& c, unsigned which, const void* X, const void* dY, void* Y, void* dX, void* H, void* Z, void* G,
+           int accumulate) {
   const int n_items = (int)c.st->items[TS64].size();
   const int M = c.st->n_tasks;
-  if (n_items == 0) return MUX_OK;
-  if (c.st->n_lora > 0) {
+  if (n_items == 0) return;
+  const bool lora = c.st->n_lora > 0, ia3 = c.st->n_ia3 > 0;
+  if ((which & REF_DOWN) && lora)
+    hipLaunchKernelGGL(k_ref_down<S>, dim3(n_items), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)X, (S*)H, c.K, c.RP);
+  if (which & REF_FWD)
+    hipLaunchKernelGGL(k_ref_fwd<S>, dim3(n_items, (c.N + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)X,
+                       (const S*)c.W, c.ldw, (const S*)H, (S*)Y, (S*)Z, c.K, c.N, c.RP);
+  if ((which & REF_G) && lora)
     hipLaunchKernelGGL(k_ref_g<S>, dim3(n_items), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)dY, (S*)G, c.N, c.RP);
+  if ((which & REF_DB) && lora)
     hipLaunchKernelGGL(k_ref_db<S>, dim3(M, (c.N + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)dY,
                        (const S*)H, c.N, c.RP, accumulate);
+  if ((which & REF_DA) && lora)
     hipLaunchKernelGGL(k_ref_da<S>, dim3(M, (c.K + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)X,
                        (const S*)G, c.K, c.RP, accumulate);
-  }
-  if (c.st->n_ia3 > 0)
+  if ((which & REF_DL) && ia3)
     hipLaunchKernelGGL(k_ref_dl<S>, dim3(M, (c.N + 255) / 256), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)dY,
                        (const S*)Z, c.N, accumulate);
-  if (dX)
+  if ((which & REF_DX) && dX)
     hipLaunchKernelGGL(k_ref_dx<S>, dim3(n_items, (c.K + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks,
                        (const S*)dY, (const S*)c.W, c.ldw, (const S*)G, (S*)dX, c.K, c.N, c.RP);
-  return MUX_OK;
 }
 
 }  // namespace
 
+void ref_steps(const CallCtx& c, int dtype, unsigned which, const void* X, const void* dY, void* Y, void* dX, void* H,
+               void* Z, void* G, int accumulate) {
+  if (dtype == MUX_DT_F32)
+    steps<float>(c, which, X, dY, Y, dX, H, Z, G, accumulate);
+  else
+    steps<bf16_t>(c, which, X, dY, Y, dX, H, Z, G, accumulate);
+}
+
 mux_status ref_forward(const CallCtx& c, int dtype, const void* X, void* Y, void* H, void* Z) {
-  return dtype == MUX_DT_F32 ? fwd_impl<float>(c, X, Y, H, Z) : fwd_impl<bf16_t>(c, X, Y, H, Z);
+  ref_steps(c, dtype, REF_DOWN | REF_FWD, X, nullptr, Y, nullptr, H, Z, nullptr, 0);
+  return MUX_OK;
 }
 
 mux_status ref_backward(const CallCtx& c, int dtype, const void* X, const void* dY, const void* H, const void* Z, void* G,
                         void* dX, int accumulate) {
-  return dtype == MUX_DT_F32 ? bwd_impl<float>(c, X, dY, H, Z, G, dX, accumulate)
-                             : bwd_impl<bf16_t>(c, X, dY, H, Z, G, dX, accumulate);
+  ref_steps(c, dtype, REF_G | REF_DB | REF_DA | REF_DL | REF_DX, X, dY, nullptr, dX, (void*)H, (void*)Z, G, accumulate);
+  return MUX_OK;
 }
 
 }  // namespace mux
