@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the multiplexed LoRA linear layer: fwd+bwd over every projection of one
+synthetic multi-tenant workload, on ONE MI355X.
+
+One "step" = forward + backward of all layer calls of the workload (7 projections of a
+LLaMA-shaped block), inputs resident in HBM.  Prints one JSON line (see the design doc for the
+definition of every field).  `--gpus N` with N > 1 is refused: this build is single-GPU.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA = 2500.0    # TFLOP/s, MI355X dense bf16
+PEAK_HBM = 8000.0          # GB/s
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=1, help="index into BASELINE.json configs (default 1: LLaMA-7B shapes)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+class LayerState:
+    pass
+
+
+def setup(mx, torch, wl, seed):
+    """Allocates one LayerState per projection; values from torch's seeded device generator
+    (same distributions as the parity workloads: X, dY ~ N(0,1); W, A, B ~ N(0, 0.02); l ~ N(1, 0.02))."""
+    dev = "cuda:0"
+    bf = torch.bfloat16
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    st = mx.mux_segtab_build([mx.TaskDesc(t.kind, t.rank, t.scale, t.seq_lens) for t in wl.tasks], wl.chunk,
+                             wl.max_pack_len, 0)
+    T = mx.mux_segtab_rows(st)
+    nb = mx.mux_segtab_device_bytes(st)
+    dtab = torch.zeros(nb, dtype=torch.uint8, device=dev)
+    mx.mux_segtab_upload(st, dtab, nb)
+    randn = lambda shape, sigma=1.0, mean=0.0: (torch.randn(shape, device=dev, dtype=torch.float32, generator=gen) * sigma + mean).to(bf)
+    layers = []
+    ws_bytes = 0
+    for name, K, N in wl.layers:
+        L = LayerState()
+        L.name, L.K, L.N = name, K, N
+        L.W = randn((K, N), 0.02)
+        L.A = [randn((K, t.rank), 0.02) if t.kind == 1 else None for t in wl.tasks]
+        L.B = [randn((t.rank, N), 0.02) if t.kind == 1 else None for t in wl.tasks]
+        L.L = [randn((N,), 0.02, 1.0) if t.kind == 2 else None for t in wl.tasks]
+        L.X = randn((T, K))
+        L.dY = randn((T, N))
+        L.Y = torch.empty((T, N), device=dev, dtype=bf)
+        L.dX = torch.empty((T, K), device=dev, dtype=bf)
+        L.dA = [None if a is None else torch.zeros(a.shape, device=dev, dtype=torch.float32) for a in L.A]
+        L.dB = [None if b is None else torch.zeros(b.shape, device=dev, dtype=torch.float32) for b in L.B]
+        L.dL = [None if l is None else torch.zeros(l.shape, device=dev, dtype=torch.float32) for l in L.L]
+        L.desc = mx.LayerDesc(K, N, mx.MUX_DT_BF16, L.W, len(wl.tasks), L.A, L.B, L.L)
+        L.saved_bytes = mx.mux_lora_saved_bytes(L.desc, st)
+        L.saved = torch.zeros(max(L.saved_bytes, 256), dtype=torch.uint8, device=dev)
+        ws_bytes = max(ws_bytes, mx.mux_lora_workspace_bytes(L.desc, st))
+        layers.append(L)
+    ws = torch.zeros(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+    return st, dtab, T, layers, ws, ws_bytes
+
+
+def step(mx, st, dtab, layers, ws, ws_bytes, stream):
+    for L in layers:
+        mx.mux_lora_forward(L.desc, st, dtab, L.X, L.Y, L.saved, ws, ws_bytes, stream)
+    for L in reversed(layers):
+        mx.mux_lora_backward(L.desc, st, dtab, L.X, L.dY, L.saved, L.dX, L.dA, L.dB, L.dL, 0, ws, ws_bytes, stream)
+
+
+def algorithmic_work(wl, T):
+    """Per kernel family: (flops, bytes) of ONE step, from the layer shapes (bf16 = 2 bytes).
+    T = rows of the aligned batch; T_t = aligned rows of task t (padding rows included)."""
+    rows = {}
+    out = {"gemm_nn": [0.0, 0.0], "gemm_nt": [0.0, 0.0], "down": [0.0, 0.0], "g": [0.0, 0.0], "db": [0.0, 0.0],
+           "da": [0.0, 0.0], "dl": [0.0, 0.0]}
+    return out
+
+
+def cpu_baseline(wl, seconds, seed):
+    """The fp64 oracle, as it stands, on a bounded sample: the first m tokens of every task through
+    every projection (fwd+bwd), m sized from a short calibration so that the run takes about `seconds`."""
+    import numpy as np
+    import mux_workloads as wlm
+    import oracle
+    from oracle import segtab
+
+    def run(m):
+        tasks = [wlm.Task(t.kind, t.rank, t.scale, [min(m, t.tokens)] if t.tokens > 0 else []) for t in wl.tasks]
+        sub = wlm.Workload(name=wl.name + "_sample", layers=wl.layers, tasks=tasks, chunk=16)
+        ot = segtab.build([t.seq_lens for t in tasks], 16)
+        kinds, ranks, scales = [t.kind for t in tasks], [t.rank for t in tasks], [t.scale for t in tasks]
+        total = 0.0
+        for li in range(len(sub.layers)):
+            lt = wlm.layer_tensors(sub, li, ot.T, seed=seed)
+            t0 = time.perf_counter()
+            oracle.forward(lt.X, lt.W, ot.row_task, kinds, ranks, scales, lt.A, lt.B, lt.L)
+            oracle.backward(lt.X, lt.dY, lt.W, ot.row_task, kinds, ranks, scales, lt.A, lt.B, lt.L)
+            total += time.perf_counter() - t0
+        return ot.valid_total, total
+
+    n0, t0 = run(2)
+    per_tok = t0 / max(n0, 1)
+    m = int(max(2, min(4096, seconds / max(per_tok, 1e-9) / max(len(wl.tasks), 1))))
+    n, t = run(m)
+    return {"value": n / t, "unit": "tokens/s", "cores": oracle.max_threads(), "kind": "oracle",
+            "sample": f"first {m} tokens of each of the {len(wl.tasks)} tasks ({n} tokens) through all "
+                      f"{len(wl.layers)} projections fwd+bwd, fp64, {t:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on exactly one GPU (got --gpus {args.gpus}); "
+              "the layer has no multi-GPU path, see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import mux_workloads as wlm
+    import paper_2603_02885_amd as mx
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    mx.load_library()
+    wl = wlm.config(args.workload, seed=args.seed)
+    st, dtab, T, layers, ws, ws_bytes = setup(mx, torch, wl, args.seed)
+    stream = torch.cuda.current_stream()
+    valid = mx.mux_segtab_valid_tokens(st)
+
+    for _ in range(args.warmup):
+        step(mx, st, dtab, layers, ws, ws_bytes, stream)
+    torch.cuda.synchronize()
+
+    # timed region: K steps, per-kernel HIP events recorded by the library on the launch stream
+    mx.mux_profile_enable(True)
+    mx.mux_profile_collect()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(mx, st, dtab, layers, ws, ws_bytes, stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = mx.mux_profile_collect()
+    mx.mux_profile_enable(False)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = valid / (ms_per_step * 1e-3)
+
+    # algorithmic work of one step
+    sumKN = sum(K * N for _, K, N in wl.layers)
+    lora_rows = sum(t.rank * 0 for t in wl.tasks)
+    row_task = mx.mux_segtab_row_task(st)
+    import numpy as np
+    img = mx.mux_segtab_serialize(st)
+    M = len(wl.tasks)
+    task_rows = [int(img[16 + 8 * t + 1]) for t in range(M)]           # aligned rows per task
+    sum_tr = sum(task_rows[t] * wl.tasks[t].rank for t in range(M) if wl.tasks[t].kind == 1)
+    ia3_rows = sum(task_rows[t] for t in range(M) if wl.tasks[t].kind == 2)
+    flops_backbone = 4.0 * T * sumKN
+    flops_adapter = 6.0 * sum_tr * sum(K + N for _, K, N in wl.layers)
+    gemm_flops = {  # per step, per kernel family (all layers): 2TKN + 2 sum T_t r_t N (fwd) / K (bwd)
+        "gemm_nn": 2.0 * T * sumKN + 2.0 * sum_tr * sum(N for _, K, N in wl.layers),
+        "gemm_nt": 2.0 * T * sumKN + 2.0 * sum_tr * sum(K for _, K, N in wl.layers),
+    }
+    kernels = {}
+    for e in prof:
+        kernels[e["name"]] = {"launches": e["launches"], "avg_us": e["total_ms"] * 1e3 / max(e["launches"], 1),
+                              "total_ms_per_step": e["total_ms"] / args.steps}
+    gemm_names = [n for n in kernels if n in gemm_flops]
+    dom = max(gemm_names, key=lambda n: kernels[n]["total_ms_per_step"]) if gemm_names else None
+    roofline = None
+    if dom:
+        tf = gemm_flops[dom] / (kernels[dom]["total_ms_per_step"] * 1e-3) / 1e12
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": tf, "peak": PEAK_BF16_MFMA, "unit": "TFLOP/s",
+                    "frac": tf / PEAK_BF16_MFMA, "traffic": None,
+                    "launches_per_step": kernels[dom]["launches"] / args.steps, "avg_launch_us": kernels[dom]["avg_us"]}
+    for n in gemm_names:
+        kernels[n]["tflops"] = gemm_flops[n] / (kernels[n]["total_ms_per_step"] * 1e-3) / 1e12
+        kernels[n]["frac_of_bf16_mfma_peak"] = kernels[n]["tflops"] / PEAK_BF16_MFMA
+
+    out = {
+        "metric": "multiplexed LoRA-linear fwd+bwd tokens/s", "value": tokens_per_s, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"configs[{args.workload}] {wl.name}: {wl.notes}; layers " +
+                               ",".join(f"{n}:{K}x{N}" for n, K, N in wl.layers),
+                   "rows": T, "valid_tokens": valid, "chunk": wl.chunk, "tasks": M},
+        "tflops": (flops_backbone + flops_adapter) / (ms_per_step * 1e-3) / 1e12,
+        "frac_of_bf16_mfma_peak": (flops_backbone + flops_adapter) / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA,
+        "padded_rows_per_s": T / (ms_per_step * 1e-3),
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds, args.seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

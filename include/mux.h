@@ -161,6 +161,20 @@ mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_segtab* st,
                              void* const* dL, int accumulate, void* ws, size_t ws_bytes,
                              void* hip_stream);
 
+/* Per-kernel timing for benchmarks.  While enabled, every kernel the library launches is
+ * bracketed by two HIP events recorded on the launch stream (no synchronisation is added).
+ * mux_profile_collect waits for the recorded events, fills up to `cap` entries with one line
+ * per kernel (name, number of launches, summed duration in milliseconds), returns the number
+ * of distinct kernels in *n, and clears the record.  Process-wide, not thread-safe; leave it
+ * disabled under HIP graph capture. */
+typedef struct {
+  const char* name;   /* static string owned by the library */
+  int32_t launches;
+  double total_ms;
+} mux_profile_entry;
+mux_status mux_profile_enable(int on);
+mux_status mux_profile_collect(mux_profile_entry* host_out, int32_t cap, int32_t* n);
+
 const char* mux_last_error(void);
 const char* mux_version(void);
 

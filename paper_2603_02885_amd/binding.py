@@ -20,7 +20,7 @@ __all__ = [
     "mux_segtab_rows", "mux_segtab_n_chunks", "mux_segtab_n_tasks", "mux_segtab_valid_tokens",
     "mux_segtab_serialized_bytes", "mux_segtab_serialize", "mux_segtab_row_task", "mux_segtab_device_bytes",
     "mux_segtab_upload", "mux_lora_saved_bytes", "mux_lora_workspace_bytes", "mux_lora_forward",
-    "mux_lora_backward", "mux_last_error", "mux_version",
+    "mux_lora_backward", "mux_last_error", "mux_version", "mux_profile_enable", "mux_profile_collect",
 ]
 
 MUX_OK = 0
@@ -49,6 +49,10 @@ class _LayerDescC(ctypes.Structure):
     _fields_ = [("K", c_int32), ("N", c_int32), ("dtype", c_int32), ("flags", c_uint32), ("W", c_void_p),
                 ("ldw", c_int64), ("n_tasks", c_int32), ("A", POINTER(c_void_p)), ("B", POINTER(c_void_p)),
                 ("L", POINTER(c_void_p))]
+
+
+class _ProfileEntryC(ctypes.Structure):
+    _fields_ = [("name", c_char_p), ("launches", c_int32), ("total_ms", ctypes.c_double)]
 
 
 class TaskDesc:
@@ -95,6 +99,8 @@ def load_library() -> ctypes.CDLL:
         "mux_lora_forward": (c_int, [POINTER(_LayerDescC), vp, vp, vp, vp, vp, vp, c_size_t, vp]),
         "mux_lora_backward": (c_int, [POINTER(_LayerDescC), vp, vp, vp, vp, vp, vp, POINTER(vp), POINTER(vp),
                                       POINTER(vp), c_int, vp, c_size_t, vp]),
+        "mux_profile_enable": (c_int, [c_int]),
+        "mux_profile_collect": (c_int, [POINTER(_ProfileEntryC), c_int32, POINTER(c_int32)]),
         "mux_last_error": (c_char_p, []),
         "mux_version": (c_char_p, []),
     }
@@ -269,3 +275,16 @@ def mux_lora_backward(layer: LayerDesc, st: SegTab, dev_segtab, X, dY, saved, dX
         ctypes.byref(layer.c), st.handle, _ptr(dev_segtab), _ptr(X), _ptr(dY), _ptr(saved), _ptr(dX),
         ctypes.cast(pa, POINTER(c_void_p)), ctypes.cast(pb, POINTER(c_void_p)), ctypes.cast(pl, POINTER(c_void_p)),
         int(accumulate), _ptr(ws), int(ws_bytes), _stream(stream)))
+
+
+def mux_profile_enable(on: bool) -> None:
+    _check(load_library().mux_profile_enable(1 if on else 0))
+
+
+def mux_profile_collect(cap: int = 64) -> List[dict]:
+    """Per-kernel [{name, launches, total_ms}] since the last collect (waits for the events)."""
+    arr = (_ProfileEntryC * cap)()
+    n = c_int32(0)
+    _check(load_library().mux_profile_collect(arr, cap, ctypes.byref(n)))
+    return [{"name": arr[i].name.decode(), "launches": int(arr[i].launches), "total_ms": float(arr[i].total_ms)}
+            for i in range(min(n.value, cap))]

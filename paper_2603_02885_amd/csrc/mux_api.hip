@@ -97,7 +97,7 @@ void fill_tasks(const mux_layer_desc* L, const mux_segtab* st, const int32_t* dt
       p.dB[i] = (kind == MUX_ADAPTER_LORA && dB) ? (float*)dB[t] : nullptr;
       p.dL[i] = (kind == MUX_ADAPTER_IA3_OUT && dL) ? (float*)dL[t] : nullptr;
     }
-    hipLaunchKernelGGL(k_fill_tasks, dim3(1), dim3(64), 0, stream, dtab, dtasks, p, base, count);
+    MUX_LAUNCH("fill_tasks", k_fill_tasks, dim3(1), dim3(64), 0, stream, dtab, dtasks, p, base, count);
   }
 }
 

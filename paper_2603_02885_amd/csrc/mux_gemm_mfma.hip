@@ -348,7 +348,7 @@ mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t
   const int total = p.n_m * p.n_n;
   if (total == 0) return MUX_OK;
   p.per_xcd = (total + 7) / 8;
-  hipLaunchKernelGGL(k_gemm<NT>, dim3(p.per_xcd * 8), dim3(256), SMEM_BYTES, c.stream, p);
+  MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", k_gemm<NT>, dim3(p.per_xcd * 8), dim3(256), SMEM_BYTES, c.stream, p);
   return MUX_OK;
 }
 

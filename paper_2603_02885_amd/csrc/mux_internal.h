@@ -71,6 +71,21 @@ namespace mux {
 mux_status fail(mux_status s, const std::string& msg);
 void clear_error();
 
+// Optional event bracketing of kernel launches (see mux_profile_enable).
+void prof_begin(const char* name, hipStream_t stream);
+void prof_end(hipStream_t stream);
+struct ProfScope {
+  hipStream_t s;
+  ProfScope(const char* name, hipStream_t stream) : s(stream) { prof_begin(name, stream); }
+  ~ProfScope() { prof_end(s); }
+};
+
+#define MUX_LAUNCH(name, kernel, grid, block, smem, stream, ...)         \
+  do {                                                                   \
+    ::mux::ProfScope mux_prof_scope_(name, stream);                      \
+    hipLaunchKernelGGL(kernel, grid, block, smem, stream, __VA_ARGS__);  \
+  } while (0)
+
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 

@@ -292,23 +292,23 @@ void steps(const CallCtx& c, unsigned which, const void* X, const void* dY, void
   if (n_items == 0) return;
   const bool lora = c.st->n_lora > 0, ia3 = c.st->n_ia3 > 0;
   if ((which & REF_DOWN) && lora)
-    hipLaunchKernelGGL(k_ref_down<S>, dim3(n_items), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)X, (S*)H, c.K, c.RP);
+    MUX_LAUNCH("ref_down", k_ref_down<S>, dim3(n_items), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)X, (S*)H, c.K, c.RP);
   if (which & REF_FWD)
-    hipLaunchKernelGGL(k_ref_fwd<S>, dim3(n_items, (c.N + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)X,
+    MUX_LAUNCH("ref_fwd", k_ref_fwd<S>, dim3(n_items, (c.N + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)X,
                        (const S*)c.W, c.ldw, (const S*)H, (S*)Y, (S*)Z, c.K, c.N, c.RP);
   if ((which & REF_G) && lora)
-    hipLaunchKernelGGL(k_ref_g<S>, dim3(n_items), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)dY, (S*)G, c.N, c.RP);
+    MUX_LAUNCH("ref_g", k_ref_g<S>, dim3(n_items), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)dY, (S*)G, c.N, c.RP);
   if ((which & REF_DB) && lora)
-    hipLaunchKernelGGL(k_ref_db<S>, dim3(M, (c.N + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)dY,
+    MUX_LAUNCH("ref_db", k_ref_db<S>, dim3(M, (c.N + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)dY,
                        (const S*)H, c.N, c.RP, accumulate);
   if ((which & REF_DA) && lora)
-    hipLaunchKernelGGL(k_ref_da<S>, dim3(M, (c.K + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)X,
+    MUX_LAUNCH("ref_da", k_ref_da<S>, dim3(M, (c.K + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)X,
                        (const S*)G, c.K, c.RP, accumulate);
   if ((which & REF_DL) && ia3)
-    hipLaunchKernelGGL(k_ref_dl<S>, dim3(M, (c.N + 255) / 256), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)dY,
+    MUX_LAUNCH("ref_dl", k_ref_dl<S>, dim3(M, (c.N + 255) / 256), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)dY,
                        (const S*)Z, c.N, accumulate);
   if ((which & REF_DX) && dX)
-    hipLaunchKernelGGL(k_ref_dx<S>, dim3(n_items, (c.K + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks,
+    MUX_LAUNCH("ref_dx", k_ref_dx<S>, dim3(n_items, (c.K + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks,
                        (const S*)dY, (const S*)c.W, c.ldw, (const S*)G, (S*)dX, c.K, c.N, c.RP);
 }
 
