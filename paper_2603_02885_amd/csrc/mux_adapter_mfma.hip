@@ -1,0 +1,385 @@
+// Adapter kernels on the matrix cores (bf16 in, fp32 accumulate).  All of them stream a big
+// activation matrix once from HBM and are bound by that stream; the MFMA only keeps the
+// arithmetic (r FLOP per byte) off the vector ALUs.
+//
+//   down:  Out[T,RP] = s_t * In[T,C] P_t^T      S1: In = X,  P_t = A_t^T (pre-transposed, [r][K])
+//                                               S4: In = dY, P_t = B_t            ([r][N])
+//   grad:  part[item][r][C] = sum_{rows of item} Small[i][:]^T Big[i][:]
+//                                               S4: Small = Hs, Big = dY  -> dB_t[r][N]
+//                                               S6: Small = Gs, Big = X   -> dA_t[K][r] (transposed on reduce)
+//   dl:    part[item][N] = sum_{rows of item} dY[i][:] * Z[i][:]          (IA3_OUT)
+//   reduce: per task, partials summed in ascending item order (deterministic), optional accumulate.
+//
+// Padding rows are masked with out-of-range buffer offsets (the load returns zeros), never multiplied.
+#include "mux_device_utils.h"
+
+namespace mux {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+constexpr uint32_t OOB = 0x80000000u;
+constexpr int TS64 = 0, TS256 = 2, TS1024 = 3;
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)p, 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ u32x4 buf_load16(rsrc_t r, uint32_t byte_off) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
+}
+__device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)p);
+}
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// ------------------------------------------------------------------------------------------------
+// A_t [K][r]  ->  A_t^T [round_up(r,16)][K]  (rows beyond r are zero).  grid = (tasks, ceil(K/64)).
+__global__ __launch_bounds__(256) void k_pack_at(const DevTask* __restrict__ tasks, bf16_t* __restrict__ AT, int K) {
+  const DevTask tk = tasks[blockIdx.x];
+  if (tk.kind != MUX_ADAPTER_LORA) return;
+  __shared__ bf16_t t[64][66];
+  const int r = tk.rank, rp = (r + 15) & ~15, k0 = blockIdx.y * 64;
+  const bf16_t* A = (const bf16_t*)tk.A;
+  for (int e = threadIdx.x; e < 64 * rp; e += 256) {
+    const int kk = e / rp, j = e % rp;
+    t[j][kk] = (j < r && k0 + kk < K) ? A[(size_t)(k0 + kk) * r + j] : (bf16_t)0;
+  }
+  __syncthreads();
+  bf16_t* dst = AT + tk.at_off;
+  for (int e = threadIdx.x; e < 64 * rp; e += 256) {
+    const int j = e >> 6, kk = e & 63;
+    if (k0 + kk < K) dst[(size_t)j * K + k0 + kk] = t[j][kk];
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// down-projection.  One workgroup = 16 rows of one 64-row item, the 4 waves split the contraction;
+// 16x16x32 MFMA tiles, both operands read straight from global memory (each element of In is used
+// once, P_t stays in L2), partial sums of the 4 waves combined through LDS in a fixed order.
+struct DownParams {
+  const int32_t* dtab;
+  const DevTask* tasks;
+  const bf16_t* In;    // [T, C]
+  bf16_t* Out;         // [T, RP]
+  const bf16_t* AT;    // S1: base of the transposed A_t region; S4: null (use B_t)
+  int C, RP;
+};
+
+__global__ __launch_bounds__(256) void k_down(const DownParams p) {
+  __shared__ float red[4][16][68];
+  const int item = blockIdx.x >> 2, sub = blockIdx.x & 3;
+  const ItemView it = load_item(p.dtab, TS64, item);
+  const int r0 = sub * 16;
+  if (r0 >= it.nrows) return;
+  const int nr = it.nrows - r0 < 16 ? it.nrows - r0 : 16;
+  const int row0 = it.row0 + r0;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bool lora = it.task >= 0 && p.tasks[it.task].kind == MUX_ADAPTER_LORA;
+  if (!lora || it.nvalid == 0) {
+    for (int e = tid; e < nr * p.RP; e += 256) p.Out[(size_t)(row0 + e / p.RP) * p.RP + e % p.RP] = 0;
+    return;
+  }
+  const DevTask tk = p.tasks[it.task];
+  const int rank = tk.rank, NJ = (rank + 15) >> 4;
+  const bf16_t* P = p.AT ? p.AT + tk.at_off : (const bf16_t*)tk.B;
+  const int prow = p.AT ? NJ * 16 : rank;            // rows that exist in P
+
+  const int i = lane & 15, g = lane >> 4;
+  const bool rvalid = i < nr && row_is_valid(p.dtab, row0 + i);
+  const int per = ((p.C + 3) / 4 + 31) & ~31;
+  const int cbeg = wave * per, cend = cbeg + per < p.C ? cbeg + per : p.C;
+
+  const rsrc_t rIn = make_rsrc(p.In + (size_t)row0 * p.C, (uint32_t)nr * (uint32_t)p.C * 2u);
+  const rsrc_t rP = make_rsrc(P, (uint32_t)prow * (uint32_t)p.C * 2u);
+  const uint32_t in_off = ((uint32_t)i * (uint32_t)p.C + 8u * g) * 2u;
+  uint32_t p_off[4];
+  bool p_ok[4];
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt) {
+    p_ok[jt] = jt < NJ && jt * 16 + i < prow;
+    p_off[jt] = ((uint32_t)(jt * 16 + i) * (uint32_t)p.C + 8u * g) * 2u;
+  }
+
+  f32x4 acc[4];
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt) acc[jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  constexpr int U = 4;
+  for (int c = cbeg; c < cend; c += 32 * U) {
+    u32x4 a[U], b[U][4];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int cc = c + 32 * u;
+      const bool ok = cc + 8 * g < cend;
+      a[u] = buf_load16(rIn, (rvalid && ok) ? in_off + (uint32_t)cc * 2u : OOB);
+#pragma unroll
+      for (int jt = 0; jt < 4; ++jt)
+        if (jt < NJ) b[u][jt] = buf_load16(rP, (p_ok[jt] && ok) ? p_off[jt] + (uint32_t)cc * 2u : OOB);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int jt = 0; jt < 4; ++jt)
+        if (jt < NJ) acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a[u]), as_bf16x8(b[u][jt]), acc[jt], 0, 0, 0);
+  }
+  // acc[jt][v] = partial of Out[row0 + 4g + v][jt*16 + i]
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) red[wave][4 * g + v][jt * 16 + i] = acc[jt][v];
+  __syncthreads();
+  const int orow = tid >> 4, oj = tid & 15;
+  if (orow < nr) {
+    const bool ok = row_is_valid(p.dtab, row0 + orow);
+    for (int jt = 0; jt * 16 < p.RP; ++jt) {
+      const int j = jt * 16 + oj;
+      const float s = ((red[0][orow][j] + red[1][orow][j]) + red[2][orow][j]) + red[3][orow][j];
+      p.Out[(size_t)(row0 + orow) * p.RP + j] = f32_to_bf16(ok && j < rank ? tk.scale * s : 0.f);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// per-item gradient partial.  grid = (items of the chosen row-group size, ceil(C/256)); each wave owns
+// 64 columns and walks the item's rows 32 at a time: the 32x64 slab of Big and the 32xRP slab of Small
+// go through a wave-private LDS region in their natural layout and come back k-major per lane through
+// ds_read_b64_tr_b16.  No workgroup barrier: the four waves are independent streams.
+struct GradParams {
+  const int32_t* dtab;
+  const DevTask* tasks;
+  const bf16_t* Small;  // [T, RP]
+  const bf16_t* Big;    // [T, C]
+  float* part;          // [n_items][RP][C]
+  int C, RP, ts;
+};
+
+constexpr int GP = 72;   // LDS row pitch in elements (144 B)
+
+__global__ __launch_bounds__(256) void k_grad(const GradParams p) {
+  __shared__ __attribute__((aligned(16))) bf16_t lds[4][2][32 * GP];
+  const ItemView it = load_item(p.dtab, p.ts, blockIdx.x);
+  if (it.task < 0 || it.nvalid == 0) return;
+  const DevTask tk = p.tasks[it.task];
+  if (tk.kind != MUX_ADAPTER_LORA) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int cw0 = blockIdx.y * 256 + wave * 64;
+  if (cw0 >= p.C) return;
+  const int rank = tk.rank, NJ = (rank + 15) >> 4;
+  bf16_t* sBig = lds[wave][0];
+  bf16_t* sSm = lds[wave][1];
+
+  const rsrc_t rB = make_rsrc(p.Big + (size_t)it.row0 * p.C, (uint32_t)it.nrows * (uint32_t)p.C * 2u);
+  const rsrc_t rS = make_rsrc(p.Small + (size_t)it.row0 * p.RP, (uint32_t)it.nrows * (uint32_t)p.RP * 2u);
+  // Big slab: 4 loads per lane, row = 8q + lane/8, 16-byte piece = lane%8
+  const int b_row = lane >> 3, b_pc = (lane & 7) * 8;
+  const bool b_col_ok = cw0 + b_pc < p.C;
+  // Small slab: pieces per row = RP/8; idx = lane + 64 q -> row = idx / ppr, piece = idx % ppr
+  const int ppr = p.RP >> 3;
+  const int n_small = (32 * ppr + 63) >> 6;    // loads per lane (1..4)
+
+  u32x4 gb[4], gs[4];
+  auto load_step = [&](int s) {
+    const int base = s * 32;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int m = base + b_row + 8 * q;
+      const bool ok = b_col_ok && m < it.nrows && row_is_valid(p.dtab, it.row0 + m);
+      gb[q] = buf_load16(rB, ok ? (uint32_t)(((size_t)m * p.C + cw0 + b_pc) * 2) : OOB);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (q < n_small) {
+        const int idx = lane + 64 * q, m = base + idx / ppr, pc = (idx % ppr) * 8;
+        const bool ok = idx < 32 * ppr && m < it.nrows;
+        gs[q] = buf_load16(rS, ok ? (uint32_t)((m * p.RP + pc) * 2) : OOB);
+      }
+    }
+  };
+  auto store_step = [&]() {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) *(u32x4*)(sBig + (b_row + 8 * q) * GP + b_pc) = gb[q];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (q < n_small) {
+        const int idx = lane + 64 * q;
+        if (idx < 32 * ppr) *(u32x4*)(sSm + (idx / ppr) * GP + (idx % ppr) * 8) = gs[q];
+      }
+    }
+  };
+
+  f32x4 acc[4][4];
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) acc[jt][ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  const int l16 = lane & 15, g = lane >> 4;
+  const int tr_off = (8 * g + (l16 >> 2)) * GP + 4 * (l16 & 3);
+  const int steps = (it.nrows + 31) >> 5;
+  load_step(0);
+  for (int s = 0; s < steps; ++s) {
+    store_step();
+    if (s + 1 < steps) load_step(s + 1);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    bf16x8 a[4], b[4];
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt)
+      if (jt < NJ) {
+        const bf16x4 lo = lds_read_tr(sSm + tr_off + jt * 16), hi = lds_read_tr(sSm + tr_off + 4 * GP + jt * 16);
+        a[jt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+      const bf16x4 lo = lds_read_tr(sBig + tr_off + ct * 16), hi = lds_read_tr(sBig + tr_off + 4 * GP + ct * 16);
+      b[ct] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt)
+      if (jt < NJ)
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) acc[jt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[jt], b[ct], acc[jt][ct], 0, 0, 0);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+  // acc[jt][ct][v] = part[j = jt*16 + 4g + v][c = cw0 + ct*16 + l16]
+  float* dst = p.part + (size_t)blockIdx.x * p.RP * p.C;
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt)
+    if (jt < NJ)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int j = jt * 16 + 4 * g + v;
+        if (j < rank)
+#pragma unroll
+          for (int ct = 0; ct < 4; ++ct) {
+            const int c = cw0 + ct * 16 + l16;
+            if (c < p.C) dst[(size_t)j * p.C + c] = acc[jt][ct][v];
+          }
+      }
+}
+
+// ------------------------------------------------------------------------------------------------
+// IA3_OUT: part[item][n] = sum_{rows} g[i][n] * z[i][n].  grid = (256-row items, ceil(N/2048)); 8 columns per thread.
+__global__ __launch_bounds__(256) void k_dl(const int32_t* __restrict__ dtab, const DevTask* __restrict__ tasks,
+                                           const bf16_t* __restrict__ dY, const bf16_t* __restrict__ Z, float* __restrict__ part,
+                                           int N) {
+  const ItemView it = load_item(dtab, TS256, blockIdx.x);
+  if (it.task < 0 || it.nvalid == 0) return;
+  const DevTask tk = tasks[it.task];
+  if (tk.kind != MUX_ADAPTER_IA3_OUT) return;
+  const int n0 = (blockIdx.y * 256 + threadIdx.x) * 8;
+  if (n0 >= N) return;
+  float s[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) s[e] = 0.f;
+  for (int m = 0; m < it.nrows; ++m) {
+    const int row = it.row0 + m;
+    if (!row_is_valid(dtab, row)) continue;
+    const uint4 gv = *(const uint4*)(dY + (size_t)row * N + n0);
+    const uint4 zv = *(const uint4*)(Z + (size_t)(tk.zrow0 + row - tk.row_begin) * N + n0);
+    const uint32_t* pg = (const uint32_t*)&gv;
+    const uint32_t* pz = (const uint32_t*)&zv;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      s[2 * e] = fmaf(__uint_as_float(pg[e] << 16), __uint_as_float(pz[e] << 16), s[2 * e]);
+      s[2 * e + 1] = fmaf(__uint_as_float(pg[e] & 0xffff0000u), __uint_as_float(pz[e] & 0xffff0000u), s[2 * e + 1]);
+    }
+  }
+  float* dst = part + (size_t)blockIdx.x * N + n0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) dst[e] = s[e];
+}
+
+// ------------------------------------------------------------------------------------------------
+// out_t = (accumulate ? out_t : 0) + sum over the task's items, ascending.  grid = (tasks, blocks over rows*C).
+// which: 0 = dB [r][C], 1 = dA [C][r] (transposed store), 2 = dL [C] (one row per item, IA3_OUT tasks).
+__global__ __launch_bounds__(256) void k_reduce(const int32_t* __restrict__ dtab, const DevTask* __restrict__ tasks,
+                                               const float* __restrict__ part, int C, int RP, int ts, int which, int accumulate) {
+  const int t = blockIdx.x;
+  const DevTask tk = tasks[t];
+  const bool is_l = which == 2;
+  if (tk.kind != (is_l ? MUX_ADAPTER_IA3_OUT : MUX_ADAPTER_LORA)) return;
+  float* out = which == 0 ? tk.dB : (which == 1 ? tk.dA : tk.dL);
+  if (!out) return;
+  const int rows = is_l ? 1 : tk.rank;
+  const size_t e = (size_t)blockIdx.y * 256 + threadIdx.x;
+  if (e >= (size_t)rows * C) return;
+  const int j = (int)(e / C), c = (int)(e % C);
+  const int32_t* ti = dtab + dtab[DH_NITEMS0 + 3 * ts + 2] + 2 * t;
+  const int ib = ti[0], ic = ti[1];
+  const int32_t* items = dtab + dtab[DH_NITEMS0 + 3 * ts + 1];
+  float s = 0.f;
+  for (int q = 0; q < ic; ++q) {
+    if (items[(ib + q) * DI_WORDS + DI_NVALID] == 0) continue;
+    s += part[((size_t)(ib + q) * RP + j) * C + c];
+  }
+  float* dst = which == 1 ? out + (size_t)c * rows + j : out + e;
+  *dst = accumulate ? *dst + s : s;
+}
+
+int choose_group(const mux_segtab* st, int C) {
+  // bigger row groups mean fewer partial bytes; keep at least ~1024 workgroups in flight
+  const size_t wg1024 = st->items[TS1024].size() * (size_t)((C + 255) / 256);
+  return wg1024 >= 1024 ? TS1024 : TS256;
+}
+
+}  // namespace
+
+size_t adapter_partial_bytes(int K, int N, const mux_segtab* st) {
+  const int C = K > N ? K : N;
+  const int RP = st->n_lora > 0 ? round_up(st->r_max, 16) : 0;
+  size_t lora = (size_t)st->items[TS256].size() * RP * C * 4;
+  size_t ia3 = st->n_ia3 > 0 ? (size_t)st->items[TS256].size() * N * 4 : 0;
+  return align256(lora > ia3 ? lora : ia3);
+}
+
+mux_status adapter_down_x(const CallCtx& c, const void* X, void* Hs) {
+  if (c.st->n_lora == 0) return MUX_OK;
+  MUX_LAUNCH("pack_at", k_pack_at, dim3(c.st->n_tasks, (c.K + 63) / 64), dim3(256), 0, c.stream, c.dtasks, (bf16_t*)c.AT, c.K);
+  DownParams p{c.dtab, c.dtasks, (const bf16_t*)X, (bf16_t*)Hs, (const bf16_t*)c.AT, c.K, c.RP};
+  MUX_LAUNCH("down_x", k_down, dim3((unsigned)c.st->items[TS64].size() * 4), dim3(256), 0, c.stream, p);
+  return MUX_OK;
+}
+
+mux_status adapter_down_g(const CallCtx& c, const void* dY, void* Gs) {
+  if (c.st->n_lora == 0) return MUX_OK;
+  DownParams p{c.dtab, c.dtasks, (const bf16_t*)dY, (bf16_t*)Gs, nullptr, c.N, c.RP};
+  MUX_LAUNCH("down_g", k_down, dim3((unsigned)c.st->items[TS64].size() * 4), dim3(256), 0, c.stream, p);
+  return MUX_OK;
+}
+
+mux_status adapter_grads(const CallCtx& c, const void* X, const void* dY, const void* Hs, const void* Gs, const void* Z,
+                         void* part, int accumulate) {
+  const int M = c.st->n_tasks;
+  if (c.st->n_lora > 0) {
+    {  // dB_t = Hs^T dY
+      const int ts = choose_group(c.st, c.N);
+      GradParams p{c.dtab, c.dtasks, (const bf16_t*)Hs, (const bf16_t*)dY, (float*)part, c.N, c.RP, ts};
+      MUX_LAUNCH("grad_db", k_grad, dim3((unsigned)c.st->items[ts].size(), (c.N + 255) / 256), dim3(256), 0, c.stream, p);
+      const size_t elems = (size_t)c.st->r_max * c.N;
+      MUX_LAUNCH("reduce_db", k_reduce, dim3(M, (unsigned)((elems + 255) / 256)), dim3(256), 0, c.stream, c.dtab, c.dtasks,
+                 (const float*)part, c.N, c.RP, ts, 0, accumulate);
+    }
+    {  // dA_t = X^T Gs
+      const int ts = choose_group(c.st, c.K);
+      GradParams p{c.dtab, c.dtasks, (const bf16_t*)Gs, (const bf16_t*)X, (float*)part, c.K, c.RP, ts};
+      MUX_LAUNCH("grad_da", k_grad, dim3((unsigned)c.st->items[ts].size(), (c.K + 255) / 256), dim3(256), 0, c.stream, p);
+      const size_t elems = (size_t)c.st->r_max * c.K;
+      MUX_LAUNCH("reduce_da", k_reduce, dim3(M, (unsigned)((elems + 255) / 256)), dim3(256), 0, c.stream, c.dtab, c.dtasks,
+                 (const float*)part, c.K, c.RP, ts, 1, accumulate);
+    }
+  }
+  if (c.st->n_ia3 > 0) {
+    MUX_LAUNCH("grad_dl", k_dl, dim3((unsigned)c.st->items[TS256].size(), (c.N + 2047) / 2048), dim3(256), 0, c.stream,
+               c.dtab, c.dtasks, (const bf16_t*)dY, (const bf16_t*)Z, (float*)part, c.N);
+    MUX_LAUNCH("reduce_dl", k_reduce, dim3(M, (c.N + 255) / 256), dim3(256), 0, c.stream, c.dtab, c.dtasks,
+               (const float*)part, c.N, 1, TS256, 2, accumulate);
+  }
+  return MUX_OK;
+}
+
+}  // namespace mux

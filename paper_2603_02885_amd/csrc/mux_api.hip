@@ -13,6 +13,7 @@ struct TaskPtrArgs {
   float* dA[16];
   float* dB[16];
   float* dL[16];
+  int64_t at_off[16];
 };
 
 __global__ void k_fill_tasks(const int32_t* __restrict__ dtab, DevTask* __restrict__ out, TaskPtrArgs p, int base, int count) {
@@ -28,7 +29,7 @@ __global__ void k_fill_tasks(const int32_t* __restrict__ dtab, DevTask* __restri
   d.row_begin = te[DT_ROW_BEGIN];
   d.row_count = te[DT_ROW_COUNT];
   d.zrow0 = te[DT_ZROW0];
-  d.pad_ = 0;
+  d.at_off = p.at_off[i];
   out[base + i] = d;
 }
 
@@ -38,7 +39,7 @@ struct Layout {
   size_t esz;          // bytes per stored element
   int RP;              // H / G row pitch in elements
   size_t h_bytes, z_bytes, saved_bytes;
-  size_t tasks_bytes, g_bytes, part_bytes, ws_bytes;
+  size_t tasks_bytes, g_bytes, at_bytes, part_bytes, ws_bytes;
 };
 
 Layout make_layout(const mux_layer_desc* L, const mux_segtab* st) {
@@ -50,8 +51,12 @@ Layout make_layout(const mux_layer_desc* L, const mux_segtab* st) {
   o.saved_bytes = o.h_bytes + o.z_bytes;
   o.tasks_bytes = align256((size_t)st->n_tasks * sizeof(DevTask));
   o.g_bytes = o.h_bytes;
-  o.part_bytes = fast_partial_bytes(L->K, L->N, st);
-  o.ws_bytes = o.tasks_bytes + o.g_bytes + o.part_bytes;
+  size_t at_elems = 0;
+  for (const HostTask& ht : st->tasks)
+    if (ht.kind == MUX_ADAPTER_LORA) at_elems += (size_t)round_up(ht.rank, 16) * L->K;
+  o.at_bytes = L->dtype == MUX_DT_BF16 ? align256(at_elems * 2) : 0;
+  o.part_bytes = L->dtype == MUX_DT_BF16 ? fast_partial_bytes(L->K, L->N, st) : 0;
+  o.ws_bytes = o.tasks_bytes + o.g_bytes + o.at_bytes + o.part_bytes;
   return o;
 }
 
@@ -83,6 +88,7 @@ mux_status check_hip(const char* fn) {
 
 void fill_tasks(const mux_layer_desc* L, const mux_segtab* st, const int32_t* dtab, DevTask* dtasks, void* const* dA,
                 void* const* dB, void* const* dL, hipStream_t stream) {
+  int64_t at_off = 0;
   for (int base = 0; base < st->n_tasks; base += 16) {
     TaskPtrArgs p;
     std::memset(&p, 0, sizeof(p));
@@ -96,6 +102,8 @@ void fill_tasks(const mux_layer_desc* L, const mux_segtab* st, const int32_t* dt
       p.dA[i] = (kind == MUX_ADAPTER_LORA && dA) ? (float*)dA[t] : nullptr;
       p.dB[i] = (kind == MUX_ADAPTER_LORA && dB) ? (float*)dB[t] : nullptr;
       p.dL[i] = (kind == MUX_ADAPTER_IA3_OUT && dL) ? (float*)dL[t] : nullptr;
+      p.at_off[i] = at_off;
+      if (kind == MUX_ADAPTER_LORA) at_off += (int64_t)round_up(st->tasks[t].rank, 16) * L->K;
     }
     MUX_LAUNCH("fill_tasks", k_fill_tasks, dim3(1), dim3(64), 0, stream, dtab, dtasks, p, base, count);
   }
@@ -128,14 +136,15 @@ extern "C" mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_se
   hipStream_t stream = (hipStream_t)hip_stream;
   DevTask* dtasks = (DevTask*)ws;
   fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, nullptr, nullptr, nullptr, stream);
-  CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP, layer->W, stream};
+  CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP,
+            (char*)ws + lo.tasks_bytes + lo.g_bytes, layer->W, stream};
   void* H = saved;
   void* Z = (saved && st->z_rows > 0) ? (char*)saved + lo.h_bytes : nullptr;
   mux_status s;
   if (layer->dtype == MUX_DT_F32 || (layer->flags & MUX_LAYER_REFERENCE_KERNELS))
     s = ref_forward(c, layer->dtype, X, Y, H, Z);
   else
-    s = fast_forward(c, X, Y, H, Z, (char*)ws + lo.tasks_bytes + lo.g_bytes);
+    s = fast_forward(c, X, Y, H, Z, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes);
   if (s) return s;
   return check_hip(fn);
 }
@@ -157,7 +166,8 @@ extern "C" mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_s
   hipStream_t stream = (hipStream_t)hip_stream;
   DevTask* dtasks = (DevTask*)ws;
   fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, dA, dB, dL, stream);
-  CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP, layer->W, stream};
+  CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP,
+            (char*)ws + lo.tasks_bytes + lo.g_bytes, layer->W, stream};
   const void* H = saved;
   const void* Z = (saved && st->z_rows > 0) ? (const char*)saved + lo.h_bytes : nullptr;
   void* G = (char*)ws + lo.tasks_bytes;
@@ -165,7 +175,7 @@ extern "C" mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_s
   if (layer->dtype == MUX_DT_F32 || (layer->flags & MUX_LAYER_REFERENCE_KERNELS))
     s = ref_backward(c, layer->dtype, X, dY, H, Z, G, dX, accumulate);
   else
-    s = fast_backward(c, X, dY, H, Z, G, dX, accumulate, (char*)ws + lo.tasks_bytes + lo.g_bytes);
+    s = fast_backward(c, X, dY, H, Z, G, dX, accumulate, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes);
   if (s) return s;
   return check_hip(fn);
 }

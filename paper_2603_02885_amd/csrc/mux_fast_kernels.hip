@@ -3,22 +3,26 @@
 
 namespace mux {
 
-size_t fast_partial_bytes(int, int, const mux_segtab*) { return 0; }
+size_t fast_partial_bytes(int K, int N, const mux_segtab* st) { return adapter_partial_bytes(K, N, st); }
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
+// The 16-byte loads of the matrix-core kernels need 16-byte aligned rows everywhere.
+static bool fast_ok(const CallCtx& c) { return gemm_mfma_supported(c); }
+
 mux_status fast_forward(const CallCtx& c, const void* X, void* Y, void* H, void* Z, void*) {
-  if (!gemm_mfma_supported(c) || !aligned16(X) || !aligned16(Y) || !aligned16(H) || !aligned16(Z))
+  if (!fast_ok(c) || !aligned16(X) || !aligned16(Y) || !aligned16(H) || !aligned16(Z))
     return ref_forward(c, MUX_DT_BF16, X, Y, H, Z);    // shapes the 16-byte loads cannot take
-  ref_steps(c, MUX_DT_BF16, REF_DOWN, X, nullptr, nullptr, nullptr, H, nullptr, nullptr, 0);
+  if (mux_status s = adapter_down_x(c, X, H)) return s;
   return gemm_mfma_forward(c, X, H, Y, Z);
 }
 
 mux_status fast_backward(const CallCtx& c, const void* X, const void* dY, const void* H, const void* Z, void* G, void* dX,
-                         int accumulate, void*) {
-  if (!gemm_mfma_supported(c) || !aligned16(dY) || !aligned16(dX) || !aligned16(G))
+                         int accumulate, void* part) {
+  if (!fast_ok(c) || !aligned16(X) || !aligned16(dY) || !aligned16(dX) || !aligned16(G) || !aligned16(H) || !aligned16(Z))
     return ref_backward(c, MUX_DT_BF16, X, dY, H, Z, G, dX, accumulate);
-  ref_steps(c, MUX_DT_BF16, REF_G | REF_DB | REF_DA | REF_DL, X, dY, nullptr, nullptr, (void*)H, (void*)Z, G, accumulate);
+  if (mux_status s = adapter_down_g(c, dY, G)) return s;
+  if (mux_status s = adapter_grads(c, X, dY, H, G, Z, part, accumulate)) return s;
   if (dX) return gemm_mfma_backward(c, dY, G, dX);
   return MUX_OK;
 }

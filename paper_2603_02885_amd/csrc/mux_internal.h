@@ -14,10 +14,10 @@ namespace mux {
 enum : int {
   DH_MAGIC = 0, DH_T, DH_CHUNK, DH_LOG2C, DH_NTASKS, DH_NCHUNKS, DH_OFF_TASKS, DH_OFF_CHUNK_VALID,
   DH_NITEMS0,            // + 3*i : n_items, off_items, off_task_items for tile size kTileRows[i]
-  DH_ZROWS = DH_NITEMS0 + 9, DH_RMAX, DH_WORDS, DH_HDR_WORDS = 32
+  DH_ZROWS = DH_NITEMS0 + 12, DH_RMAX, DH_WORDS, DH_HDR_WORDS = 32
 };
-constexpr int kNumTileSizes = 3;
-constexpr int kTileRows[kNumTileSizes] = {64, 128, 256};
+constexpr int kNumTileSizes = 4;
+constexpr int kTileRows[kNumTileSizes] = {64, 128, 256, 1024};
 constexpr uint32_t kDevMagic = 0x4458554Du;  // "MUXD"
 
 // per task, 8 words
@@ -39,7 +39,7 @@ struct DevTask {
   int32_t row_begin;
   int32_t row_count;
   int32_t zrow0;      // first row of this task inside the saved x W region (IA3_OUT), else -1
-  int64_t pad_;
+  int64_t at_off;     // element offset of this task's transposed A_t inside the workspace region
 };
 static_assert(sizeof(DevTask) == 80, "DevTask layout");
 
@@ -97,6 +97,7 @@ struct CallCtx {
   int K, N;
   int64_t ldw;
   int RP;                  // row pitch (elements) of the H / G buffers
+  void* AT;                // workspace: per-task A_t^T [round_up(r_t,16)][K] bf16 (forward, fast path)
   const void* W;
   hipStream_t stream;
 };
@@ -116,6 +117,13 @@ void ref_steps(const CallCtx& c, int dtype, unsigned which, const void* X, const
 bool gemm_mfma_supported(const CallCtx& c);
 mux_status gemm_mfma_forward(const CallCtx& c, const void* X, const void* Hs, void* Y, void* Z);
 mux_status gemm_mfma_backward(const CallCtx& c, const void* dY, const void* Gs, void* dX);
+
+// matrix-core adapter kernels (bf16): down-projections and per-task gradient reductions
+mux_status adapter_down_x(const CallCtx& c, const void* X, void* Hs);                       // S1
+mux_status adapter_down_g(const CallCtx& c, const void* dY, void* Gs);                      // S4a
+mux_status adapter_grads(const CallCtx& c, const void* X, const void* dY, const void* Hs, const void* Gs, const void* Z,
+                         void* part, int accumulate);                                       // S4b, S6
+size_t adapter_partial_bytes(int K, int N, const mux_segtab* st);
 
 // matrix-core (MFMA) kernels, bf16 storage
 size_t fast_partial_bytes(int K, int N, const mux_segtab* st);
