@@ -263,31 +263,44 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// IA3_OUT: part[item][n] = sum_{rows} g[i][n] * z[i][n].  grid = (256-row items, ceil(N/2048)); 8 columns per thread.
+// IA3_OUT: part[item][n] = sum_{rows} g[i][n] * z[i][n], and dYs[i][n] = g[i][n] * l_t[n] (the operand of the
+// backbone backward for these rows).  grid = (256-row items, ceil(N/2048)); 8 columns per thread.
 __global__ __launch_bounds__(256) void k_dl(const int32_t* __restrict__ dtab, const DevTask* __restrict__ tasks,
                                            const bf16_t* __restrict__ dY, const bf16_t* __restrict__ Z, float* __restrict__ part,
-                                           int N) {
+                                           bf16_t* __restrict__ dYs, int N) {
   const ItemView it = load_item(dtab, TS256, blockIdx.x);
   if (it.task < 0 || it.nvalid == 0) return;
   const DevTask tk = tasks[it.task];
   if (tk.kind != MUX_ADAPTER_IA3_OUT) return;
   const int n0 = (blockIdx.y * 256 + threadIdx.x) * 8;
   if (n0 >= N) return;
-  float s[8];
+  float s[8], lv[8];
+  {
+    const uint4 l4 = *(const uint4*)((const bf16_t*)tk.L + n0);
+    const uint32_t* pl = (const uint32_t*)&l4;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { lv[2 * e] = __uint_as_float(pl[e] << 16); lv[2 * e + 1] = __uint_as_float(pl[e] & 0xffff0000u); }
+  }
 #pragma unroll
   for (int e = 0; e < 8; ++e) s[e] = 0.f;
   for (int m = 0; m < it.nrows; ++m) {
     const int row = it.row0 + m;
     if (!row_is_valid(dtab, row)) continue;
+    const size_t zoff = (size_t)(tk.zrow0 + row - tk.row_begin) * N + n0;
     const uint4 gv = *(const uint4*)(dY + (size_t)row * N + n0);
-    const uint4 zv = *(const uint4*)(Z + (size_t)(tk.zrow0 + row - tk.row_begin) * N + n0);
+    const uint4 zv = *(const uint4*)(Z + zoff);
     const uint32_t* pg = (const uint32_t*)&gv;
     const uint32_t* pz = (const uint32_t*)&zv;
+    uint4 sv;
+    uint32_t* ps = (uint32_t*)&sv;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      s[2 * e] = fmaf(__uint_as_float(pg[e] << 16), __uint_as_float(pz[e] << 16), s[2 * e]);
-      s[2 * e + 1] = fmaf(__uint_as_float(pg[e] & 0xffff0000u), __uint_as_float(pz[e] & 0xffff0000u), s[2 * e + 1]);
+      const float g0 = __uint_as_float(pg[e] << 16), g1 = __uint_as_float(pg[e] & 0xffff0000u);
+      s[2 * e] = fmaf(g0, __uint_as_float(pz[e] << 16), s[2 * e]);
+      s[2 * e + 1] = fmaf(g1, __uint_as_float(pz[e] & 0xffff0000u), s[2 * e + 1]);
+      ps[e] = pack_bf16x2(g0 * lv[2 * e], g1 * lv[2 * e + 1]);
     }
+    *(uint4*)(dYs + zoff) = sv;
   }
   float* dst = part + (size_t)blockIdx.x * N + n0;
 #pragma unroll
@@ -375,7 +388,7 @@ mux_status adapter_grads(const CallCtx& c, const void* X, const void* dY, const 
   }
   if (c.st->n_ia3 > 0) {
     MUX_LAUNCH("grad_dl", k_dl, dim3((unsigned)c.st->items[TS256].size(), (c.N + 2047) / 2048), dim3(256), 0, c.stream,
-               c.dtab, c.dtasks, (const bf16_t*)dY, (const bf16_t*)Z, (float*)part, c.N);
+               c.dtab, c.dtasks, (const bf16_t*)dY, (const bf16_t*)Z, (float*)part, (bf16_t*)c.dYs, c.N);
     MUX_LAUNCH("reduce_dl", k_reduce, dim3(M, (c.N + 255) / 256), dim3(256), 0, c.stream, c.dtab, c.dtasks,
                (const float*)part, c.N, 1, TS256, 2, accumulate);
   }

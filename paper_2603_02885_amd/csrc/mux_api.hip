@@ -39,7 +39,7 @@ struct Layout {
   size_t esz;          // bytes per stored element
   int RP;              // H / G row pitch in elements
   size_t h_bytes, z_bytes, saved_bytes;
-  size_t tasks_bytes, g_bytes, at_bytes, part_bytes, ws_bytes;
+  size_t tasks_bytes, g_bytes, at_bytes, dys_bytes, part_bytes, ws_bytes;
 };
 
 Layout make_layout(const mux_layer_desc* L, const mux_segtab* st) {
@@ -56,7 +56,8 @@ Layout make_layout(const mux_layer_desc* L, const mux_segtab* st) {
     if (ht.kind == MUX_ADAPTER_LORA) at_elems += (size_t)round_up(ht.rank, 16) * L->K;
   o.at_bytes = L->dtype == MUX_DT_BF16 ? align256(at_elems * 2) : 0;
   o.part_bytes = L->dtype == MUX_DT_BF16 ? fast_partial_bytes(L->K, L->N, st) : 0;
-  o.ws_bytes = o.tasks_bytes + o.g_bytes + o.at_bytes + o.part_bytes;
+  o.dys_bytes = L->dtype == MUX_DT_BF16 ? o.z_bytes : 0;
+  o.ws_bytes = o.tasks_bytes + o.g_bytes + o.at_bytes + o.dys_bytes + o.part_bytes;
   return o;
 }
 
@@ -137,14 +138,14 @@ extern "C" mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_se
   DevTask* dtasks = (DevTask*)ws;
   fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, nullptr, nullptr, nullptr, stream);
   CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP,
-            (char*)ws + lo.tasks_bytes + lo.g_bytes, layer->W, stream};
+            (char*)ws + lo.tasks_bytes + lo.g_bytes, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes, layer->W, stream};
   void* H = saved;
   void* Z = (saved && st->z_rows > 0) ? (char*)saved + lo.h_bytes : nullptr;
   mux_status s;
   if (layer->dtype == MUX_DT_F32 || (layer->flags & MUX_LAYER_REFERENCE_KERNELS))
     s = ref_forward(c, layer->dtype, X, Y, H, Z);
   else
-    s = fast_forward(c, X, Y, H, Z, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes);
+    s = fast_forward(c, X, Y, H, Z, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes + lo.dys_bytes);
   if (s) return s;
   return check_hip(fn);
 }
@@ -167,7 +168,7 @@ extern "C" mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_s
   DevTask* dtasks = (DevTask*)ws;
   fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, dA, dB, dL, stream);
   CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP,
-            (char*)ws + lo.tasks_bytes + lo.g_bytes, layer->W, stream};
+            (char*)ws + lo.tasks_bytes + lo.g_bytes, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes, layer->W, stream};
   const void* H = saved;
   const void* Z = (saved && st->z_rows > 0) ? (const char*)saved + lo.h_bytes : nullptr;
   void* G = (char*)ws + lo.tasks_bytes;
@@ -175,7 +176,7 @@ extern "C" mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_s
   if (layer->dtype == MUX_DT_F32 || (layer->flags & MUX_LAYER_REFERENCE_KERNELS))
     s = ref_backward(c, layer->dtype, X, dY, H, Z, G, dX, accumulate);
   else
-    s = fast_backward(c, X, dY, H, Z, G, dX, accumulate, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes);
+    s = fast_backward(c, X, dY, H, Z, G, dX, accumulate, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes + lo.dys_bytes);
   if (s) return s;
   return check_hip(fn);
 }

@@ -1,4 +1,6 @@
 // bf16 matrix-core path: sequences the MFMA kernels of one layer call.
+#include <cstdlib>
+
 #include "mux_device_utils.h"
 
 namespace mux {
@@ -14,6 +16,7 @@ mux_status fast_forward(const CallCtx& c, const void* X, void* Y, void* H, void*
   if (!fast_ok(c) || !aligned16(X) || !aligned16(Y) || !aligned16(H) || !aligned16(Z))
     return ref_forward(c, MUX_DT_BF16, X, Y, H, Z);    // shapes the 16-byte loads cannot take
   if (mux_status s = adapter_down_x(c, X, H)) return s;
+  if (gemm_dma_supported(c, false) && !getenv("MUX_GEMM_REGSTAGED")) return gemm_dma_forward(c, X, H, Y, Z);
   return gemm_mfma_forward(c, X, H, Y, Z);
 }
 
@@ -23,8 +26,12 @@ mux_status fast_backward(const CallCtx& c, const void* X, const void* dY, const 
     return ref_backward(c, MUX_DT_BF16, X, dY, H, Z, G, dX, accumulate);
   if (mux_status s = adapter_down_g(c, dY, G)) return s;
   if (mux_status s = adapter_grads(c, X, dY, H, G, Z, part, accumulate)) return s;
-  if (dX) return gemm_mfma_backward(c, dY, G, dX);
-  return MUX_OK;
+  if (!dX) return MUX_OK;
+  if (gemm_dma_supported(c, true) && !getenv("MUX_GEMM_REGSTAGED")) {
+    // IA3_OUT rows read dY * l_t, written by the dl kernel above
+    return gemm_dma_backward(c, dY, G, dX);
+  }
+  return gemm_mfma_backward(c, dY, G, dX, 0);
 }
 
 }  // namespace mux

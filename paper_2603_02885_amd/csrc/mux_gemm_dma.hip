@@ -1,0 +1,357 @@
+// Backbone GEMM, pipelined version: global -> LDS by direct buffer loads (no register staging),
+// four LDS stages of BK = 32, operand reads software-pipelined one MFMA step ahead.
+//
+//   forward  (NN):  Y[T,N]  = mask * ( X[T,K] W[K,N]      + Hs[T,r] B_t[r,N] )      Eq. 1 + LoRA + Add
+//   backward (NT):  dX[T,K] = mask * ( dY[T,N] W[K,N]^T   + Gs[T,r] A_t[K,r]^T )    Eq. 2 + LoRA
+//
+// Same tiling as the register-staged kernel (256x256 per workgroup, 128x128 per wave, 4x4
+// v_mfma_f32_32x32x16_bf16), but:
+//   * `buffer_load_dwordx4 ... lds` writes each lane's 16 bytes at LDS base + 16*lane, so a wave
+//     instruction fills 1 KB of a stage; loads for tile kt+3 are issued while tile kt is computed
+//     (three tiles in flight).  A masked piece gets an out-of-range offset and lands as zeros.
+//   * LDS rows cannot be padded under that rule, so 16-byte pieces are XOR-swizzled instead:
+//     [rows][32] tiles by row bits, the forward's [32][256] tile of W by k bits.
+//   * one workgroup barrier per K-tile, placed between the two MFMA steps: by then every read of
+//     the current stage is done (it may be refilled) and the next tile has landed (it may be read).
+// Every stage is its own __shared__ array so that the compiler's wait-count insertion can tell
+// the stage being filled from the stage being read.
+#include "mux_device_utils.h"
+
+namespace mux {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
+constexpr int BM = 256, BN = 256, BK = 32, NST = 4;
+constexpr int STAGE_ELEMS = BM * BK;          // 8192 bf16 = 16 KB per operand per stage
+constexpr int TS256 = 2;
+constexpr uint32_t OOB = 0x80000000u;
+constexpr int EPW = 128 + 8;                  // epilogue staging pitch (elements): 32 rows x 136 per wave
+
+struct GemmParams {
+  const int32_t* dtab;
+  const DevTask* tasks;
+  const bf16_t* Ain;   // [T, Kc]  activations (X or dY)
+  const bf16_t* W;     // [K, ldw]
+  int64_t ldw;
+  const bf16_t* Ext;   // [T, RP]  Hs or Gs
+  bf16_t* Out;         // [T, Nc]
+  bf16_t* Zsave;       // forward: x W of IA3_OUT rows (may be null)
+  int Kc, Nc, RP;
+  int n_m, n_n, per_xcd;
+  const bf16_t* AinScaled;  // backward: dY * l_t of the IA3_OUT rows, [z_rows, Kc], indexed like the saved x W
+};
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)p, 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ void dma16(rsrc_t r, bf16_t* lds_dst_uniform, uint32_t byte_off) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_ptr)lds_dst_uniform, 16, (int)byte_off, 0, 0, 0);
+}
+__device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)p);
+}
+// s_waitcnt vmcnt(n) only (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14])
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | 0x70 | 0xF00 | ((N >> 4) << 14));
+}
+__device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
+// swizzle of the 16-byte piece index inside a 64-byte row of a [rows][32] tile
+__device__ __forceinline__ int swz_row(int r) { return (((r >> 1) ^ (r >> 3)) & 1) | (((r >> 2) & 1) << 1); }
+
+template <bool NT>
+__global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
+  __shared__ __attribute__((aligned(1024))) bf16_t sA0[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sA1[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sA2[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sA3[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sB0[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sB1[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sB2[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sB3[STAGE_ELEMS];
+  __shared__ int sRow[256];
+
+  const int total = p.n_m * p.n_n;
+  const int L = (blockIdx.x & 7) * p.per_xcd + (blockIdx.x >> 3);
+  if (L >= total) return;
+  constexpr int GROUP = 4;
+  const int width = GROUP * p.n_n;
+  const int first_m = (L / width) * GROUP;
+  const int gsize = p.n_m - first_m < GROUP ? p.n_m - first_m : GROUP;
+  const int tm = first_m + (L % width) % gsize;
+  const int tn = (L % width) / gsize;
+
+  const ItemView it = load_item(p.dtab, TS256, tm);
+  const int c0 = tn * BN;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+
+  sRow[tid] = (it.task >= 0 && tid < it.nrows && row_is_valid(p.dtab, it.row0 + tid)) ? 1 : 0;
+
+  if (it.task < 0 || it.nvalid == 0) {             // rows of no task, or padding only: zeros out
+    for (int e = tid; e < it.nrows * (BN / 8); e += 256) {
+      const int m = e / (BN / 8), c = c0 + (e % (BN / 8)) * 8;
+      if (c < p.Nc) *(uint4*)(p.Out + (size_t)(it.row0 + m) * p.Nc + c) = make_uint4(0, 0, 0, 0);
+    }
+    return;
+  }
+
+  const DevTask tk = p.tasks[it.task];
+  const bool lora = tk.kind == MUX_ADAPTER_LORA;
+  const bool ia3 = tk.kind == MUX_ADAPTER_IA3_OUT;
+  const int rank = tk.rank;
+  const bf16_t* adapterB = NT ? (const bf16_t*)tk.A : (const bf16_t*)tk.B;
+  const bf16_t* Lvec = (const bf16_t*)tk.L;
+
+  const int KT = (p.Kc + BK - 1) / BK;
+  const int KT_ext = lora ? (rank + BK - 1) / BK : 0;
+  const int KT_total = KT + KT_ext;
+
+  // ---- DMA geometry.  A wave instruction fills 1 KB: 16 rows x 64 B of a [rows][32] tile
+  // (lane -> row lane/4, physical piece lane%4), or 2 k-rows x 512 B of the [32][256] tile
+  // (lane -> k-row lane/32, physical piece lane%32).  Wave w owns chunks 4w .. 4w+3 of each tile.
+  const int r_in = lane >> 2;                                   // row inside the 16-row chunk
+  const int r_piece = (lane & 3) ^ swz_row(r_in);               // logical k-piece this lane fetches
+  const uint32_t a_rows_bytes = (uint32_t)it.nrows * (uint32_t)p.Kc * 2u;
+  const bf16_t* a_base = (NT && ia3) ? p.AinScaled + (size_t)(tk.zrow0 + it.row0 - tk.row_begin) * p.Kc
+                                     : p.Ain + (size_t)it.row0 * p.Kc;
+  const rsrc_t rA = make_rsrc(a_base, a_rows_bytes);
+  const rsrc_t rW = make_rsrc(p.W, (uint32_t)((size_t)(NT ? p.Nc : p.Kc) * p.ldw * 2));
+  const rsrc_t rE = make_rsrc(lora ? p.Ext + (size_t)it.row0 * p.RP : p.Ain, lora ? (uint32_t)it.nrows * (uint32_t)p.RP * 2u : 0u);
+  const rsrc_t rP = make_rsrc(lora ? adapterB : p.Ain, lora ? (uint32_t)(NT ? (size_t)p.Nc * rank : (size_t)rank * p.Nc) * 2u : 0u);
+
+  const int a_row = wave * 64 + r_in;                           // + 16 q
+  // forward W tile: k-row = 8 wave + 2 q + lane/32, physical piece lane%32 -> logical n
+  const int nk_in = lane >> 5;
+  const int n_pp = lane & 31;
+
+  // Per-thread byte offsets of the 4 + 4 pieces this lane fetches per tile, without the K-tile term.
+  // Main tiles and adapter tiles have their own set; a piece that must read as zero is parked out of range.
+  uint32_t offA[4], offB[4], extA[4], extB[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int row = a_row + 16 * q;
+    offA[q] = ((uint32_t)row * (uint32_t)p.Kc + (uint32_t)(r_piece * 8)) * 2u;
+    extA[q] = (r_piece * 8 < p.RP) ? ((uint32_t)row * (uint32_t)p.RP + (uint32_t)(r_piece * 8)) * 2u : OOB;
+    if (NT) {
+      const int c = c0 + row;
+      offB[q] = (uint32_t)(((size_t)c * p.ldw + r_piece * 8) * 2);
+      extB[q] = (c < p.Nc && r_piece * 8 < rank) ? (uint32_t)(((size_t)c * rank + r_piece * 8) * 2) : OOB;
+    } else {
+      const int kk = wave * 8 + 2 * q + nk_in;               // k-row inside the tile
+      const int seg = (n_pp >> 1) ^ ((kk & 3) << 1);         // logical 32-byte segment
+      const int n = seg * 16 + (n_pp & 1) * 8;
+      const bool col_ok = c0 + n < p.Nc;
+      offB[q] = col_ok ? (uint32_t)(((size_t)kk * p.ldw + c0 + n) * 2) : OOB;
+      extB[q] = (col_ok && kk < rank) ? (uint32_t)(((size_t)kk * p.Nc + c0 + n) * 2) : OOB;
+    }
+  }
+  // K-tile term: advances by one tile per issue (scalar); the main tiles use (stepA, stepB), adapter tiles
+  // restart from zero with their own steps, and past the last tile everything is parked out of range.
+  const uint32_t stepA_main = BK * 2u;
+  const uint32_t stepB_main = NT ? BK * 2u : (uint32_t)((size_t)BK * p.ldw * 2);
+  const uint32_t stepA_ext = BK * 2u;
+  const uint32_t stepB_ext = NT ? BK * 2u : (uint32_t)((size_t)BK * p.Nc * 2);
+  rsrc_t curA = rA, curB = rW;
+  uint32_t kA = 0, kB = 0, stepA = stepA_main, stepB = stepB_main;
+  int next_tile = 0;                                          // index of the tile the next issue() fetches
+
+  auto issue = [&](bf16_t* dA, bf16_t* dB) {
+    if (next_tile == KT) {                                    // uniform, taken at most twice per workgroup
+      if (lora && next_tile < KT_total) {
+        curA = rE; curB = rP; kA = 0; kB = 0; stepA = stepA_ext; stepB = stepB_ext;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { offA[q] = extA[q]; offB[q] = extB[q]; }
+      }
+    }
+    if (next_tile >= KT_total) { kA = OOB; kB = OOB; }
+    if (next_tile > KT && next_tile < KT_total) {             // second adapter tile (rank > 32): re-mask the B side
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (NT) { if (!(BK + r_piece * 8 < rank)) offB[q] = OOB; }
+        else { if (!(BK + wave * 8 + 2 * q + nk_in < rank)) offB[q] = OOB; }
+        if (!(BK + r_piece * 8 < p.RP)) offA[q] = OOB;
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      dma16(curA, dA + (wave * 4 + q) * 512, offA[q] + kA);
+      dma16(curB, dB + (wave * 4 + q) * 512, offB[q] + kB);
+    }
+    kA += stepA; kB += stepB;
+    ++next_tile;
+  };
+
+  // ---- operand read geometry
+  const int li = lane & 31, lg = lane >> 5;
+  const int l16 = lane & 15, lhalf = (lane >> 4) & 1;
+  // [rows][32] tiles: row = (wm|wn)*128 + t*32 + li; logical piece 2*ks + lg
+  const int swz = swz_row(li);
+  const int a_rd = (wm * 128 + li) * BK;        // elements; + t*32*BK + ((2ks+lg)^swz)*8
+  const int bt_rd = (wn * 128 + li) * BK;
+  // forward W tile: k = ks*16 + 8 lg + 4 h + l16/4 ; logical seg = wn*8 + 2 t + lhalf ; + 4*(l16%4) elements
+  const int kq = l16 >> 2;                      // k & 3 of the rows this lane addresses
+  const int bn_col = 4 * (l16 & 3);
+
+  auto read_ops = [&](const bf16_t* cA, const bf16_t* cB, int ks, bf16x8 (&a)[4], bf16x8 (&b)[4]) {
+    const int pa = ((2 * ks + lg) ^ swz) * 8;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) a[t] = *(const bf16x8*)(cA + a_rd + t * 32 * BK + pa);
+    if (NT) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) b[t] = *(const bf16x8*)(cB + bt_rd + t * 32 * BK + pa);
+    } else {
+      const int krow = ks * 16 + 8 * lg + kq;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int seg = (wn * 8 + 2 * t + lhalf) ^ (kq << 1);
+        const bf16x4 lo = lds_read_tr(cB + krow * BN + seg * 16 + bn_col);
+        const bf16x4 hi = lds_read_tr(cB + (krow + 4) * BN + seg * 16 + bn_col);
+        b[t] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+    }
+  };
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+
+  auto mma = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[4]) {
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < 4; ++ni)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+  };
+
+  auto stA = [&](int s) -> bf16_t* { return s == 0 ? sA0 : (s == 1 ? sA1 : (s == 2 ? sA2 : sA3)); };
+  auto stB = [&](int s) -> bf16_t* { return s == 0 ? sB0 : (s == 1 ? sB1 : (s == 2 ? sB2 : sB3)); };
+
+  // ---- prologue: tiles 0, 1, 2 in flight; tile 0 landed and visible; its first operands in registers
+  issue(sA0, sB0);
+  issue(sA1, sB1);
+  issue(sA2, sB2);
+  wait_vmcnt<16>();
+  wait_lgkm0();
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+
+  bf16x8 a0[4], b0[4], a1[4], b1[4];
+  read_ops(sA0, sB0, 0, a0, b0);
+
+  for (int kt4 = 0; kt4 < KT_total; kt4 += NST) {
+#pragma unroll
+    for (int u = 0; u < NST; ++u) {
+      const int kt = kt4 + u;
+      if (kt < KT_total) {
+        bf16_t* cA = stA(u);
+        bf16_t* cB = stB(u);
+        // refill the stage that was computed from in the previous iteration with tile kt+3
+        issue(stA((u + 3) & 3), stB((u + 3) & 3));       // past the last tile this fetches zeros nobody reads
+        read_ops(cA, cB, 1, a1, b1);          // operands of the second step
+        mma(a0, b0);                          // first step
+        // tile kt+1 must have landed (everything newer may stay in flight), every read of this stage is done
+        wait_vmcnt<16>();
+        wait_lgkm0();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (kt + 1 < KT_total) read_ops(stA((u + 1) & 3), stB((u + 1) & 3), 0, a0, b0);   // first operands of the next tile
+        mma(a1, b1);                          // second step
+      }
+    }
+  }
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+
+  // ---- epilogue: aggregate, mask, store; 32 rows of the wave tile at a time through this wave's own array
+  bf16_t* stage = stA(wave);
+  float lcol[4];
+#pragma unroll
+  for (int ni = 0; ni < 4; ++ni) {
+    const int c = c0 + wn * 128 + ni * 32 + li;
+    lcol[ni] = (!NT && ia3 && c < p.Nc) ? bf16_to_f32(Lvec[c]) : 1.f;
+  }
+  const int passes = (!NT && ia3 && p.Zsave) ? 2 : 1;     // IA3 forward also saves x W before the scale
+  for (int pass = 0; pass < passes; ++pass) {
+    const bool to_z = passes == 2 && pass == 0;
+    bf16_t* dst = to_z ? p.Zsave + (size_t)(tk.zrow0 - tk.row_begin) * p.Nc : p.Out;
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+      for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = 8 * (v >> 2) + 4 * lg + (v & 3);
+          const float y = to_z ? acc[mi][ni][v] : acc[mi][ni][v] * lcol[ni];
+          stage[m * EPW + ni * 32 + li] = f32_to_bf16(y);
+        }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int rr = 0; rr < 8; ++rr) {
+        const int ml = rr * 4 + (lane >> 4);
+        const int m = wm * 128 + mi * 32 + ml;
+        const int c = c0 + wn * 128 + (lane & 15) * 8;
+        if (m < it.nrows && c < p.Nc) {
+          uint4 v = *(const uint4*)(stage + ml * EPW + (lane & 15) * 8);
+          if (sRow[m] == 0) v = make_uint4(0, 0, 0, 0);
+          *(uint4*)(dst + (size_t)(it.row0 + m) * p.Nc + c) = v;
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+}
+
+template <bool NT>
+mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t* Out, bf16_t* Zsave, int Kc, int Nc) {
+  GemmParams p;
+  p.dtab = c.dtab; p.tasks = c.dtasks; p.Ain = Ain; p.W = (const bf16_t*)c.W; p.ldw = c.ldw; p.Ext = Ext; p.Out = Out;
+  p.Zsave = Zsave; p.Kc = Kc; p.Nc = Nc; p.RP = c.RP;
+  p.n_m = (int)c.st->items[TS256].size();
+  p.n_n = (Nc + BN - 1) / BN;
+  p.AinScaled = (const bf16_t*)c.dYs;
+  const int total = p.n_m * p.n_n;
+  if (total == 0) return MUX_OK;
+  p.per_xcd = (total + 7) / 8;
+  MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", k_gemm_dma<NT>, dim3(p.per_xcd * 8), dim3(256), 0, c.stream, p);
+  return MUX_OK;
+}
+
+}  // namespace
+
+// The pipelined kernel needs what the register-staged one needs, a contraction length that is a multiple of 32,
+// and in the backward every LoRA rank a multiple of 8 (rows of A_t are read in 16-byte pieces).
+bool gemm_dma_supported(const CallCtx& c, bool backward) {
+  if (!gemm_mfma_supported(c)) return false;
+  if ((backward ? c.N : c.K) % BK != 0) return false;      // no K-tail masks in the pipelined loop
+  if (backward)
+    for (const HostTask& ht : c.st->tasks)
+      if (ht.kind == MUX_ADAPTER_LORA && (ht.rank & 7) != 0) return false;
+  return true;
+}
+
+mux_status gemm_dma_forward(const CallCtx& c, const void* X, const void* Hs, void* Y, void* Z) {
+  return launch<false>(c, (const bf16_t*)X, (const bf16_t*)Hs, (bf16_t*)Y, (bf16_t*)Z, c.K, c.N);
+}
+
+mux_status gemm_dma_backward(const CallCtx& c, const void* dY, const void* Gs, void* dX) {
+  return launch<true>(c, (const bf16_t*)dY, (const bf16_t*)Gs, (bf16_t*)dX, nullptr, c.N, c.K);
+}
+
+}  // namespace mux

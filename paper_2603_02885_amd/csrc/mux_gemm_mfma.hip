@@ -43,6 +43,7 @@ struct GemmParams {
   bf16_t* Zsave;       // forward: x W of IA3_OUT rows (may be null)
   int Kc, Nc, RP;
   int n_m, n_n, per_xcd;
+  int only_ia3;        // process IA3_OUT items only (the pipelined kernel took the rest)
 };
 
 __device__ __forceinline__ uint4 zero4() { return make_uint4(0, 0, 0, 0); }
@@ -104,6 +105,8 @@ __global__ __launch_bounds__(256, 1) void k_gemm(const GemmParams p) {
   const int c0 = tn * BN;                          // first output column
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
+
+  if (p.only_ia3 && !(it.task >= 0 && it.nvalid > 0 && p.tasks[it.task].kind == MUX_ADAPTER_IA3_OUT)) return;
 
   {
     const int row = it.row0 + tid;
@@ -333,7 +336,8 @@ __global__ __launch_bounds__(256, 1) void k_gemm(const GemmParams p) {
 }
 
 template <bool NT>
-mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t* Out, bf16_t* Zsave, int Kc, int Nc) {
+mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t* Out, bf16_t* Zsave, int Kc, int Nc,
+                  int only_ia3) {
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)k_gemm<NT>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
@@ -348,7 +352,8 @@ mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t
   const int total = p.n_m * p.n_n;
   if (total == 0) return MUX_OK;
   p.per_xcd = (total + 7) / 8;
-  MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", k_gemm<NT>, dim3(p.per_xcd * 8), dim3(256), SMEM_BYTES, c.stream, p);
+  p.only_ia3 = only_ia3;
+  MUX_LAUNCH(NT ? (only_ia3 ? "gemm_nt_ia3" : "gemm_nt_regstaged") : "gemm_nn_regstaged", k_gemm<NT>, dim3(p.per_xcd * 8), dim3(256), SMEM_BYTES, c.stream, p);
   return MUX_OK;
 }
 
@@ -363,11 +368,11 @@ bool gemm_mfma_supported(const CallCtx& c) {
 }
 
 mux_status gemm_mfma_forward(const CallCtx& c, const void* X, const void* Hs, void* Y, void* Z) {
-  return launch<false>(c, (const bf16_t*)X, (const bf16_t*)Hs, (bf16_t*)Y, (bf16_t*)Z, c.K, c.N);
+  return launch<false>(c, (const bf16_t*)X, (const bf16_t*)Hs, (bf16_t*)Y, (bf16_t*)Z, c.K, c.N, 0);
 }
 
-mux_status gemm_mfma_backward(const CallCtx& c, const void* dY, const void* Gs, void* dX) {
-  return launch<true>(c, (const bf16_t*)dY, (const bf16_t*)Gs, (bf16_t*)dX, nullptr, c.N, c.K);
+mux_status gemm_mfma_backward(const CallCtx& c, const void* dY, const void* Gs, void* dX, int only_ia3) {
+  return launch<true>(c, (const bf16_t*)dY, (const bf16_t*)Gs, (bf16_t*)dX, nullptr, c.N, c.K, only_ia3);
 }
 
 }  // namespace mux

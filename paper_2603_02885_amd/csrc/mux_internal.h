@@ -98,6 +98,7 @@ struct CallCtx {
   int64_t ldw;
   int RP;                  // row pitch (elements) of the H / G buffers
   void* AT;                // workspace: per-task A_t^T [round_up(r_t,16)][K] bf16 (forward, fast path)
+  void* dYs;               // workspace: dY * l_t of the IA3_OUT rows [z_rows][N] bf16 (backward, fast path)
   const void* W;
   hipStream_t stream;
 };
@@ -116,7 +117,11 @@ void ref_steps(const CallCtx& c, int dtype, unsigned which, const void* X, const
 // matrix-core backbone GEMM (bf16)
 bool gemm_mfma_supported(const CallCtx& c);
 mux_status gemm_mfma_forward(const CallCtx& c, const void* X, const void* Hs, void* Y, void* Z);
-mux_status gemm_mfma_backward(const CallCtx& c, const void* dY, const void* Gs, void* dX);
+mux_status gemm_mfma_backward(const CallCtx& c, const void* dY, const void* Gs, void* dX, int only_ia3);
+// pipelined variant (direct-to-LDS loads, 4 stages)
+bool gemm_dma_supported(const CallCtx& c, bool backward);
+mux_status gemm_dma_forward(const CallCtx& c, const void* X, const void* Hs, void* Y, void* Z);
+mux_status gemm_dma_backward(const CallCtx& c, const void* dY, const void* Gs, void* dX);
 
 // matrix-core adapter kernels (bf16): down-projections and per-task gradient reductions
 mux_status adapter_down_x(const CallCtx& c, const void* X, void* Hs);                       // S1
