@@ -74,11 +74,18 @@ class GpuLayer:
                                   self.dX if want_dx else None, self.dA, self.dB, self.dL, accumulate, self.ws,
                                   self.ws_bytes, self.torch.cuda.current_stream())
 
-    def results(self) -> Dict[str, object]:
-        self.torch.cuda.synchronize()
+    def results(self, cols=None, kcols=None) -> Dict[str, object]:
+        """Outputs as float64 numpy; with cols / kcols only those columns of Y / dX are brought back."""
+        torch = self.torch
+        torch.cuda.synchronize()
         f = lambda t: None if t is None else t.float().cpu().numpy().astype(np.float64)
-        return {"Y": f(self.Y), "dX": f(self.dX), "dA": [f(t) for t in self.dA], "dB": [f(t) for t in self.dB],
-                "dL": [f(t) for t in self.dL]}
+        Y, dX = self.Y, self.dX
+        if cols is not None:
+            Y = Y[:, torch.as_tensor(np.asarray(cols, dtype=np.int64), device=Y.device)]
+        if kcols is not None:
+            dX = dX[:, torch.as_tensor(np.asarray(kcols, dtype=np.int64), device=dX.device)]
+        return {"Y": f(Y), "dX": f(dX), "dA": [f(t) for t in self.dA], "dB": [f(t) for t in self.dB],
+                "dL": [f(t) for t in self.dL], "sampled": (cols is not None, kcols is not None)}
 
 
 def oracle_results(wl: wlm.Workload, lt: wlm.LayerTensors, row_task: np.ndarray, cols=None, kcols=None):
@@ -94,8 +101,9 @@ def oracle_results(wl: wlm.Workload, lt: wlm.LayerTensors, row_task: np.ndarray,
 def compare(got: Dict[str, object], ref: Dict[str, object], tol: float, cols=None, kcols=None, label: str = "") -> Dict[str, float]:
     """Asserts every tensor within tol; returns the errors found."""
     errs: Dict[str, float] = {}
-    gy = got["Y"] if cols is None else got["Y"][:, cols]
-    gx = got["dX"] if kcols is None else got["dX"][:, kcols]
+    y_sampled, x_sampled = got.get("sampled", (False, False))
+    gy = got["Y"] if (cols is None or y_sampled) else got["Y"][:, cols]
+    gx = got["dX"] if (kcols is None or x_sampled) else got["dX"][:, kcols]
     errs["Y"] = norm_err(gy, ref["Y"])
     errs["dX"] = norm_err(gx, ref["dX"])
     for name in ("dA", "dB", "dL"):
