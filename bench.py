@@ -84,15 +84,6 @@ def step(mx, st, dtab, layers, ws, ws_bytes, stream):
         mx.mux_lora_backward(L.desc, st, dtab, L.X, L.dY, L.saved, L.dX, L.dA, L.dB, L.dL, 0, ws, ws_bytes, stream)
 
 
-def algorithmic_work(wl, T):
-    """Per kernel family: (flops, bytes) of ONE step, from the layer shapes (bf16 = 2 bytes).
-    T = rows of the aligned batch; T_t = aligned rows of task t (padding rows included)."""
-    rows = {}
-    out = {"gemm_nn": [0.0, 0.0], "gemm_nt": [0.0, 0.0], "down": [0.0, 0.0], "g": [0.0, 0.0], "db": [0.0, 0.0],
-           "da": [0.0, 0.0], "dl": [0.0, 0.0]}
-    return out
-
-
 def cpu_baseline(wl, seconds, seed):
     """The fp64 oracle, as it stands, on a bounded sample: the first m tokens of every task through
     every projection (fwd+bwd), m sized from a short calibration so that the run takes about `seconds`."""
@@ -115,7 +106,8 @@ def cpu_baseline(wl, seconds, seed):
             total += time.perf_counter() - t0
         return ot.valid_total, total
 
-    n0, t0 = run(2)
+    run(1)                                  # warm up (library load, OpenMP pool)
+    n0, t0 = run(8)
     per_tok = t0 / max(n0, 1)
     m = int(max(2, min(4096, seconds / max(per_tok, 1e-9) / max(len(wl.tasks), 1))))
     n, t = run(m)
@@ -162,9 +154,6 @@ def main():
 
     # algorithmic work of one step
     sumKN = sum(K * N for _, K, N in wl.layers)
-    lora_rows = sum(t.rank * 0 for t in wl.tasks)
-    row_task = mx.mux_segtab_row_task(st)
-    import numpy as np
     img = mx.mux_segtab_serialize(st)
     M = len(wl.tasks)
     task_rows = [int(img[16 + 8 * t + 1]) for t in range(M)]           # aligned rows per task
@@ -180,6 +169,20 @@ def main():
     for e in prof:
         kernels[e["name"]] = {"launches": e["launches"], "avg_us": e["total_ms"] * 1e3 / max(e["launches"], 1),
                               "total_ms_per_step": e["total_ms"] / args.steps}
+    # HBM-bound adapter kernels: algorithmic bytes per step (bf16 = 2 B, fp32 gradients = 4 B)
+    RP = ((max([t.rank for t in wl.tasks if t.kind == 1] + [1]) + 15) // 16) * 16
+    sum_r = sum(t.rank for t in wl.tasks if t.kind == 1)
+    stream_bytes = {
+        "down_x": sum(2.0 * T * K + 2.0 * K * sum_r + 2.0 * T * RP for _, K, N in wl.layers),
+        "down_g": sum(2.0 * T * N + 2.0 * N * sum_r + 2.0 * T * RP for _, K, N in wl.layers),
+        "grad_db": sum(2.0 * T * N + 2.0 * T * RP + 4.0 * N * sum_r for _, K, N in wl.layers),
+        "grad_da": sum(2.0 * T * K + 2.0 * T * RP + 4.0 * K * sum_r for _, K, N in wl.layers),
+        "grad_dl": sum(4.0 * ia3_rows * N for _, K, N in wl.layers),
+    }
+    for n, b in stream_bytes.items():
+        if n in kernels and kernels[n]["total_ms_per_step"] > 0:
+            kernels[n]["gbps"] = b / (kernels[n]["total_ms_per_step"] * 1e-3) / 1e9
+            kernels[n]["frac_of_hbm_peak"] = kernels[n]["gbps"] / PEAK_HBM
     gemm_names = [n for n in kernels if n in gemm_flops]
     dom = max(gemm_names, key=lambda n: kernels[n]["total_ms_per_step"]) if gemm_names else None
     roofline = None

@@ -10,7 +10,7 @@ SOURCES = ["mux_segtab.cpp", "mux_api.hip", "mux_ref_kernels.hip", "mux_fast_ker
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]
+         "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option", "-Wno-inline-asm"]
 
 
 def build_library(verbose: bool = False, jobs: int = 4) -> str:

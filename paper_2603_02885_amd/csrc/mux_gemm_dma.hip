@@ -23,7 +23,6 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 constexpr int BM = 256, BN = 256, BK = 32, NST = 4;
@@ -46,11 +45,21 @@ struct GemmParams {
   const bf16_t* AinScaled;  // backward: dY * l_t of the IA3_OUT rows, [z_rows, Kc], indexed like the saved x W
 };
 
+// Raw buffer descriptor (stride 0) over `bytes` bytes starting at p, as four dwords.
+typedef __attribute__((ext_vector_type(4))) int rsrc_t;
 __device__ __forceinline__ rsrc_t make_rsrc(const void* p, uint32_t bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc((void*)p, 0, (int)bytes, 0x00020000);
+  const uint64_t a = (uint64_t)p;
+  return (rsrc_t){(int)(uint32_t)a, (int)(uint32_t)(a >> 32), (int)bytes, 0x00020000};
 }
+// One direct-to-LDS load: lane l's 16 bytes from buffer offset byte_off land at lds_dst_uniform + 16*l.
+// Written as inline assembly on purpose: the wait counts of these loads are managed by hand (vmcnt) around
+// the workgroup barrier, and the compiler must not pair them with the LDS reads of other stages.
 __device__ __forceinline__ void dma16(rsrc_t r, bf16_t* lds_dst_uniform, uint32_t byte_off) {
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_ptr)lds_dst_uniform, 16, (int)byte_off, 0, 0, 0);
+  const uint32_t lds_addr = (uint32_t)(uintptr_t)(lds_void_ptr)lds_dst_uniform;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :
+               : "s"(lds_addr), "v"(byte_off), "s"(r)
+               : "m0");
 }
 __device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)p);
@@ -133,53 +142,56 @@ __global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
   const int n_pp = lane & 31;
 
   // Per-thread byte offsets of the 4 + 4 pieces this lane fetches per tile, without the K-tile term.
-  // Main tiles and adapter tiles have their own set; a piece that must read as zero is parked out of range.
-  uint32_t offA[4], offB[4], extA[4], extB[4];
+  // A piece that must read as zero is parked out of range.
+  uint32_t offA[4], offB[4];
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int row = a_row + 16 * q;
     offA[q] = ((uint32_t)row * (uint32_t)p.Kc + (uint32_t)(r_piece * 8)) * 2u;
-    extA[q] = (r_piece * 8 < p.RP) ? ((uint32_t)row * (uint32_t)p.RP + (uint32_t)(r_piece * 8)) * 2u : OOB;
     if (NT) {
-      const int c = c0 + row;
-      offB[q] = (uint32_t)(((size_t)c * p.ldw + r_piece * 8) * 2);
-      extB[q] = (c < p.Nc && r_piece * 8 < rank) ? (uint32_t)(((size_t)c * rank + r_piece * 8) * 2) : OOB;
+      offB[q] = (uint32_t)(((size_t)(c0 + row) * p.ldw + r_piece * 8) * 2);
     } else {
       const int kk = wave * 8 + 2 * q + nk_in;               // k-row inside the tile
       const int seg = (n_pp >> 1) ^ ((kk & 3) << 1);         // logical 32-byte segment
       const int n = seg * 16 + (n_pp & 1) * 8;
-      const bool col_ok = c0 + n < p.Nc;
-      offB[q] = col_ok ? (uint32_t)(((size_t)kk * p.ldw + c0 + n) * 2) : OOB;
-      extB[q] = (col_ok && kk < rank) ? (uint32_t)(((size_t)kk * p.Nc + c0 + n) * 2) : OOB;
+      offB[q] = (c0 + n < p.Nc) ? (uint32_t)(((size_t)kk * p.ldw + c0 + n) * 2) : OOB;
     }
   }
-  // K-tile term: advances by one tile per issue (scalar); the main tiles use (stepA, stepB), adapter tiles
-  // restart from zero with their own steps, and past the last tile everything is parked out of range.
-  const uint32_t stepA_main = BK * 2u;
-  const uint32_t stepB_main = NT ? BK * 2u : (uint32_t)((size_t)BK * p.ldw * 2);
-  const uint32_t stepA_ext = BK * 2u;
-  const uint32_t stepB_ext = NT ? BK * 2u : (uint32_t)((size_t)BK * p.Nc * 2);
+  // K-tile term: advances by one tile per issue (scalar).  After the last backbone tile the sources switch
+  // to the adapter operands (Ext rows and B_t / A_t), whose offsets restart from zero; past the last tile
+  // everything is parked out of range (zeros land in a stage nobody reads).
   rsrc_t curA = rA, curB = rW;
-  uint32_t kA = 0, kB = 0, stepA = stepA_main, stepB = stepB_main;
+  uint32_t kA = 0, kB = 0, stepA = BK * 2u, stepB = NT ? BK * 2u : (uint32_t)((size_t)BK * p.ldw * 2);
   int next_tile = 0;                                          // index of the tile the next issue() fetches
 
+  // uniform, rarely taken: everything that changes at a tile-kind boundary
+  auto prepare = [&]() {
+    if (next_tile >= KT) {
+      if (next_tile >= KT_total) {
+        kA = OOB; kB = OOB;
+      } else {
+        const int j0 = (next_tile - KT) * BK;                 // first contraction index of this adapter tile
+        curA = rE; curB = rP; kA = 0; kB = 0; stepA = 0; stepB = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int row = a_row + 16 * q;
+          const int j = j0 + r_piece * 8;
+          offA[q] = (j < p.RP) ? ((uint32_t)row * (uint32_t)p.RP + (uint32_t)j) * 2u : OOB;
+          if (NT) {
+            const int c = c0 + row;
+            offB[q] = (c < p.Nc && j < rank) ? (uint32_t)(((size_t)c * rank + j) * 2) : OOB;
+          } else {
+            const int kk = wave * 8 + 2 * q + nk_in;
+            const int seg = (n_pp >> 1) ^ ((kk & 3) << 1);
+            const int n = seg * 16 + (n_pp & 1) * 8;
+            offB[q] = (c0 + n < p.Nc && j0 + kk < rank) ? (uint32_t)(((size_t)(j0 + kk) * p.Nc + c0 + n) * 2) : OOB;
+          }
+        }
+      }
+    }
+  };
+  // straight-line: 8 address adds, 8 loads
   auto issue = [&](bf16_t* dA, bf16_t* dB) {
-    if (next_tile == KT) {                                    // uniform, taken at most twice per workgroup
-      if (lora && next_tile < KT_total) {
-        curA = rE; curB = rP; kA = 0; kB = 0; stepA = stepA_ext; stepB = stepB_ext;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) { offA[q] = extA[q]; offB[q] = extB[q]; }
-      }
-    }
-    if (next_tile >= KT_total) { kA = OOB; kB = OOB; }
-    if (next_tile > KT && next_tile < KT_total) {             // second adapter tile (rank > 32): re-mask the B side
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        if (NT) { if (!(BK + r_piece * 8 < rank)) offB[q] = OOB; }
-        else { if (!(BK + wave * 8 + 2 * q + nk_in < rank)) offB[q] = OOB; }
-        if (!(BK + r_piece * 8 < p.RP)) offA[q] = OOB;
-      }
-    }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       dma16(curA, dA + (wave * 4 + q) * 512, offA[q] + kA);
@@ -239,9 +251,9 @@ __global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
   auto stB = [&](int s) -> bf16_t* { return s == 0 ? sB0 : (s == 1 ? sB1 : (s == 2 ? sB2 : sB3)); };
 
   // ---- prologue: tiles 0, 1, 2 in flight; tile 0 landed and visible; its first operands in registers
-  issue(sA0, sB0);
-  issue(sA1, sB1);
-  issue(sA2, sB2);
+  prepare(); issue(sA0, sB0);
+  prepare(); issue(sA1, sB1);
+  prepare(); issue(sA2, sB2);
   wait_vmcnt<16>();
   wait_lgkm0();
   asm volatile("" ::: "memory");
@@ -258,18 +270,38 @@ __global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
       if (kt < KT_total) {
         bf16_t* cA = stA(u);
         bf16_t* cB = stB(u);
-        // refill the stage that was computed from in the previous iteration with tile kt+3
-        issue(stA((u + 3) & 3), stB((u + 3) & 3));       // past the last tile this fetches zeros nobody reads
-        read_ops(cA, cB, 1, a1, b1);          // operands of the second step
-        mma(a0, b0);                          // first step
-        // tile kt+1 must have landed (everything newer may stay in flight), every read of this stage is done
+        prepare();
+        __builtin_amdgcn_sched_barrier(0);
+        // first MFMA step; spread among its 16 MFMAs: the refill of the stage computed from in the previous
+        // iteration with tile kt+3 (past the last tile this fetches zeros nobody reads) and the operand reads
+        // of the second step
+        issue(stA((u + 3) & 3), stB((u + 3) & 3));
+        read_ops(cA, cB, 1, a1, b1);
+        mma(a0, b0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);             // 2 MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, NT ? 1 : 2, 0);    // operand reads
+          __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);             // address add
+          __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // direct-to-LDS load
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // tile kt+1 must have landed (the two newer ones may stay in flight) and every read of this stage be done
         wait_vmcnt<16>();
         wait_lgkm0();
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        if (kt + 1 < KT_total) read_ops(stA((u + 1) & 3), stB((u + 1) & 3), 0, a0, b0);   // first operands of the next tile
-        mma(a1, b1);                          // second step
+        __builtin_amdgcn_sched_barrier(0);
+        // second MFMA step, with the first operands of the next tile read under it
+        if (kt + 1 < KT_total) read_ops(stA((u + 1) & 3), stB((u + 1) & 3), 0, a0, b0);
+        mma(a1, b1);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, NT ? 1 : 2, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
