@@ -15,6 +15,8 @@
 //     the current stage is done (it may be refilled) and the next tile has landed (it may be read).
 // Every stage is its own __shared__ array so that the compiler's wait-count insertion can tell
 // the stage being filled from the stage being read.
+#include <cstdlib>
+
 #include "mux_device_utils.h"
 
 namespace mux {
@@ -25,11 +27,10 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
-constexpr int BM = 256, BN = 256, BK = 32, NST = 4;
+constexpr int BM = 256, BN = 256, BK = 32, NST = 4;   // BN = WNW * NI * 32 in both wave layouts
 constexpr int STAGE_ELEMS = BM * BK;          // 8192 bf16 = 16 KB per operand per stage
 constexpr int TS256 = 2;
 constexpr uint32_t OOB = 0x80000000u;
-constexpr int EPW = 128 + 8;                  // epilogue staging pitch (elements): 32 rows x 136 per wave
 
 struct GemmParams {
   const int32_t* dtab;
@@ -74,8 +75,15 @@ __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F
 // swizzle of the 16-byte piece index inside a 64-byte row of a [rows][32] tile
 __device__ __forceinline__ int swz_row(int r) { return (((r >> 1) ^ (r >> 3)) & 1) | (((r >> 2) & 1) << 1); }
 
-template <bool NT>
-__global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
+// WNW = waves along N (2: four waves of 128x128, 4: eight waves of 128x64, two per SIMD), NI = 32-column MFMA
+// tiles per wave.
+template <bool NT, int WNW, int NI>
+__global__ __launch_bounds__(128 * WNW, 1) void k_gemm_dma(const GemmParams p) {
+  static_assert(WNW * NI * 32 == BN, "wave layout must cover the tile");
+  constexpr int NW = 2 * WNW, NTHR = 64 * NW;
+  constexpr int ACH = 16 / NW, BCH = 16 / NW;     // 1 KB chunks of the A / B tile each wave fetches per K-tile
+  constexpr int WCOLS = NI * 32;                  // columns of the wave tile
+  constexpr int EPW = WCOLS + 8;                  // epilogue staging pitch (elements)
   __shared__ __attribute__((aligned(1024))) bf16_t sA0[STAGE_ELEMS];
   __shared__ __attribute__((aligned(1024))) bf16_t sA1[STAGE_ELEMS];
   __shared__ __attribute__((aligned(1024))) bf16_t sA2[STAGE_ELEMS];
@@ -100,12 +108,12 @@ __global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
   const int c0 = tn * BN;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WNW, wn = wave % WNW;
 
-  sRow[tid] = (it.task >= 0 && tid < it.nrows && row_is_valid(p.dtab, it.row0 + tid)) ? 1 : 0;
+  if (tid < 256) sRow[tid] = (it.task >= 0 && tid < it.nrows && row_is_valid(p.dtab, it.row0 + tid)) ? 1 : 0;
 
   if (it.task < 0 || it.nvalid == 0) {             // rows of no task, or padding only: zeros out
-    for (int e = tid; e < it.nrows * (BN / 8); e += 256) {
+    for (int e = tid; e < it.nrows * (BN / 8); e += NTHR) {
       const int m = e / (BN / 8), c = c0 + (e % (BN / 8)) * 8;
       if (c < p.Nc) *(uint4*)(p.Out + (size_t)(it.row0 + m) * p.Nc + c) = make_uint4(0, 0, 0, 0);
     }
@@ -136,22 +144,22 @@ __global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
   const rsrc_t rE = make_rsrc(lora ? p.Ext + (size_t)it.row0 * p.RP : p.Ain, lora ? (uint32_t)it.nrows * (uint32_t)p.RP * 2u : 0u);
   const rsrc_t rP = make_rsrc(lora ? adapterB : p.Ain, lora ? (uint32_t)(NT ? (size_t)p.Nc * rank : (size_t)rank * p.Nc) * 2u : 0u);
 
-  const int a_row = wave * 64 + r_in;                           // + 16 q
+  const int a_row = wave * (16 * ACH) + r_in;                   // + 16 q
   // forward W tile: k-row = 8 wave + 2 q + lane/32, physical piece lane%32 -> logical n
   const int nk_in = lane >> 5;
   const int n_pp = lane & 31;
 
   // Per-thread byte offsets of the 4 + 4 pieces this lane fetches per tile, without the K-tile term.
   // A piece that must read as zero is parked out of range.
-  uint32_t offA[4], offB[4];
+  uint32_t offA[ACH], offB[BCH];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
+  for (int q = 0; q < ACH; ++q) {
     const int row = a_row + 16 * q;
     offA[q] = ((uint32_t)row * (uint32_t)p.Kc + (uint32_t)(r_piece * 8)) * 2u;
     if (NT) {
       offB[q] = (uint32_t)(((size_t)(c0 + row) * p.ldw + r_piece * 8) * 2);
     } else {
-      const int kk = wave * 8 + 2 * q + nk_in;               // k-row inside the tile
+      const int kk = wave * (2 * BCH) + 2 * q + nk_in;       // k-row inside the tile
       const int seg = (n_pp >> 1) ^ ((kk & 3) << 1);         // logical 32-byte segment
       const int n = seg * 16 + (n_pp & 1) * 8;
       offB[q] = (c0 + n < p.Nc) ? (uint32_t)(((size_t)kk * p.ldw + c0 + n) * 2) : OOB;
@@ -173,7 +181,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
         const int j0 = (next_tile - KT) * BK;                 // first contraction index of this adapter tile
         curA = rE; curB = rP; kA = 0; kB = 0; stepA = 0; stepB = 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < ACH; ++q) {
           const int row = a_row + 16 * q;
           const int j = j0 + r_piece * 8;
           offA[q] = (j < p.RP) ? ((uint32_t)row * (uint32_t)p.RP + (uint32_t)j) * 2u : OOB;
@@ -181,7 +189,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
             const int c = c0 + row;
             offB[q] = (c < p.Nc && j < rank) ? (uint32_t)(((size_t)c * rank + j) * 2) : OOB;
           } else {
-            const int kk = wave * 8 + 2 * q + nk_in;
+            const int kk = wave * (2 * BCH) + 2 * q + nk_in;
             const int seg = (n_pp >> 1) ^ ((kk & 3) << 1);
             const int n = seg * 16 + (n_pp & 1) * 8;
             offB[q] = (c0 + n < p.Nc && j0 + kk < rank) ? (uint32_t)(((size_t)(j0 + kk) * p.Nc + c0 + n) * 2) : OOB;
@@ -193,9 +201,9 @@ __global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
   // straight-line: 8 address adds, 8 loads
   auto issue = [&](bf16_t* dA, bf16_t* dB) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      dma16(curA, dA + (wave * 4 + q) * 512, offA[q] + kA);
-      dma16(curB, dB + (wave * 4 + q) * 512, offB[q] + kB);
+    for (int q = 0; q < ACH; ++q) {
+      dma16(curA, dA + (wave * ACH + q) * 512, offA[q] + kA);
+      dma16(curB, dB + (wave * BCH + q) * 512, offB[q] + kB);
     }
     kA += stepA; kB += stepB;
     ++next_tile;
@@ -207,23 +215,23 @@ __global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
   // [rows][32] tiles: row = (wm|wn)*128 + t*32 + li; logical piece 2*ks + lg
   const int swz = swz_row(li);
   const int a_rd = (wm * 128 + li) * BK;        // elements; + t*32*BK + ((2ks+lg)^swz)*8
-  const int bt_rd = (wn * 128 + li) * BK;
+  const int bt_rd = (wn * WCOLS + li) * BK;
   // forward W tile: k = ks*16 + 8 lg + 4 h + l16/4 ; logical seg = wn*8 + 2 t + lhalf ; + 4*(l16%4) elements
   const int kq = l16 >> 2;                      // k & 3 of the rows this lane addresses
   const int bn_col = 4 * (l16 & 3);
 
-  auto read_ops = [&](const bf16_t* cA, const bf16_t* cB, int ks, bf16x8 (&a)[4], bf16x8 (&b)[4]) {
+  auto read_ops = [&](const bf16_t* cA, const bf16_t* cB, int ks, bf16x8 (&a)[4], bf16x8 (&b)[NI]) {
     const int pa = ((2 * ks + lg) ^ swz) * 8;
 #pragma unroll
     for (int t = 0; t < 4; ++t) a[t] = *(const bf16x8*)(cA + a_rd + t * 32 * BK + pa);
     if (NT) {
 #pragma unroll
-      for (int t = 0; t < 4; ++t) b[t] = *(const bf16x8*)(cB + bt_rd + t * 32 * BK + pa);
+      for (int t = 0; t < NI; ++t) b[t] = *(const bf16x8*)(cB + bt_rd + t * 32 * BK + pa);
     } else {
       const int krow = ks * 16 + 8 * lg + kq;
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const int seg = (wn * 8 + 2 * t + lhalf) ^ (kq << 1);
+      for (int t = 0; t < NI; ++t) {
+        const int seg = (wn * (2 * NI) + 2 * t + lhalf) ^ (kq << 1);
         const bf16x4 lo = lds_read_tr(cB + krow * BN + seg * 16 + bn_col);
         const bf16x4 hi = lds_read_tr(cB + (krow + 4) * BN + seg * 16 + bn_col);
         b[t] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -231,19 +239,19 @@ __global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
     }
   };
 
-  f32x16 acc[4][4];
+  f32x16 acc[4][NI];
 #pragma unroll
   for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-    for (int ni = 0; ni < 4; ++ni)
+    for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-  auto mma = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[4]) {
+  auto mma = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[NI]) {
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-      for (int ni = 0; ni < 4; ++ni)
+      for (int ni = 0; ni < NI; ++ni)
         acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
   };
 
@@ -254,13 +262,13 @@ __global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
   prepare(); issue(sA0, sB0);
   prepare(); issue(sA1, sB1);
   prepare(); issue(sA2, sB2);
-  wait_vmcnt<16>();
+  wait_vmcnt<2 * (ACH + BCH)>();
   wait_lgkm0();
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 
-  bf16x8 a0[4], b0[4], a1[4], b1[4];
+  bf16x8 a0[4], b0[NI], a1[4], b1[NI];
   read_ops(sA0, sB0, 0, a0, b0);
 
   for (int kt4 = 0; kt4 < KT_total; kt4 += NST) {
@@ -279,15 +287,15 @@ __global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
         read_ops(cA, cB, 1, a1, b1);
         mma(a0, b0);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);             // 2 MFMA
-          __builtin_amdgcn_sched_group_barrier(0x100, NT ? 1 : 2, 0);    // operand reads
-          __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);             // address add
-          __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // direct-to-LDS load
+        for (int i = 0; i < 2 * NI; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                       // 2 MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, (NT && NI == 4) ? 1 : 2, 0); // operand reads
+          __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);                       // address add
+          __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                       // direct-to-LDS load
         }
         __builtin_amdgcn_sched_barrier(0);
         // tile kt+1 must have landed (the two newer ones may stay in flight) and every read of this stage be done
-        wait_vmcnt<16>();
+        wait_vmcnt<2 * (ACH + BCH)>();
         wait_lgkm0();
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
@@ -297,9 +305,9 @@ __global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
         if (kt + 1 < KT_total) read_ops(stA((u + 1) & 3), stB((u + 1) & 3), 0, a0, b0);
         mma(a1, b1);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < 2 * NI; ++i) {
           __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-          __builtin_amdgcn_sched_group_barrier(0x100, NT ? 1 : 2, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, (NT && NI == 4) ? 1 : 2, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -310,13 +318,16 @@ __global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
   asm volatile("" ::: "memory");
 
   // ---- epilogue: aggregate, mask, store; 32 rows of the wave tile at a time through this wave's own array
-  bf16_t* stage = stA(wave);
-  float lcol[4];
+  bf16_t* stage = wave < 4 ? stA(wave) : stB(wave - 4);
+  float lcol[NI];
 #pragma unroll
-  for (int ni = 0; ni < 4; ++ni) {
-    const int c = c0 + wn * 128 + ni * 32 + li;
+  for (int ni = 0; ni < NI; ++ni) {
+    const int c = c0 + wn * WCOLS + ni * 32 + li;
     lcol[ni] = (!NT && ia3 && c < p.Nc) ? bf16_to_f32(Lvec[c]) : 1.f;
   }
+  constexpr int PPR = WCOLS / 8;                 // 16-byte pieces per staged row
+  constexpr int RPI = 64 / PPR;                  // rows one wave instruction moves
+  const int e_row = lane / PPR, e_pc = (lane % PPR) * 8;
   const int passes = (!NT && ia3 && p.Zsave) ? 2 : 1;     // IA3 forward also saves x W before the scale
   for (int pass = 0; pass < passes; ++pass) {
     const bool to_z = passes == 2 && pass == 0;
@@ -324,7 +335,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
 #pragma unroll
-      for (int ni = 0; ni < 4; ++ni)
+      for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int m = 8 * (v >> 2) + 4 * lg + (v & 3);
@@ -334,12 +345,12 @@ __global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int rr = 0; rr < 8; ++rr) {
-        const int ml = rr * 4 + (lane >> 4);
+      for (int rr = 0; rr < 32 / RPI; ++rr) {
+        const int ml = rr * RPI + e_row;
         const int m = wm * 128 + mi * 32 + ml;
-        const int c = c0 + wn * 128 + (lane & 15) * 8;
+        const int c = c0 + wn * WCOLS + e_pc;
         if (m < it.nrows && c < p.Nc) {
-          uint4 v = *(const uint4*)(stage + ml * EPW + (lane & 15) * 8);
+          uint4 v = *(const uint4*)(stage + ml * EPW + e_pc);
           if (sRow[m] == 0) v = make_uint4(0, 0, 0, 0);
           *(uint4*)(dst + (size_t)(it.row0 + m) * p.Nc + c) = v;
         }
@@ -350,7 +361,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_dma(const GemmParams p) {
   }
 }
 
-template <bool NT>
+template <bool NT, int WNW, int NI>
 mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t* Out, bf16_t* Zsave, int Kc, int Nc) {
   GemmParams p;
   p.dtab = c.dtab; p.tasks = c.dtasks; p.Ain = Ain; p.W = (const bf16_t*)c.W; p.ldw = c.ldw; p.Ext = Ext; p.Out = Out;
@@ -361,7 +372,7 @@ mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t
   const int total = p.n_m * p.n_n;
   if (total == 0) return MUX_OK;
   p.per_xcd = (total + 7) / 8;
-  MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", k_gemm_dma<NT>, dim3(p.per_xcd * 8), dim3(256), 0, c.stream, p);
+  MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", (k_gemm_dma<NT, WNW, NI>), dim3(p.per_xcd * 8), dim3(128 * WNW), 0, c.stream, p);
   return MUX_OK;
 }
 
@@ -378,12 +389,16 @@ bool gemm_dma_supported(const CallCtx& c, bool backward) {
   return true;
 }
 
+static bool eight_waves() { static const bool v = getenv("MUX_GEMM_4WAVES") == nullptr; return v; }
+
 mux_status gemm_dma_forward(const CallCtx& c, const void* X, const void* Hs, void* Y, void* Z) {
-  return launch<false>(c, (const bf16_t*)X, (const bf16_t*)Hs, (bf16_t*)Y, (bf16_t*)Z, c.K, c.N);
+  if (eight_waves()) return launch<false, 4, 2>(c, (const bf16_t*)X, (const bf16_t*)Hs, (bf16_t*)Y, (bf16_t*)Z, c.K, c.N);
+  return launch<false, 2, 4>(c, (const bf16_t*)X, (const bf16_t*)Hs, (bf16_t*)Y, (bf16_t*)Z, c.K, c.N);
 }
 
 mux_status gemm_dma_backward(const CallCtx& c, const void* dY, const void* Gs, void* dX) {
-  return launch<true>(c, (const bf16_t*)dY, (const bf16_t*)Gs, (bf16_t*)dX, nullptr, c.N, c.K);
+  if (eight_waves()) return launch<true, 4, 2>(c, (const bf16_t*)dY, (const bf16_t*)Gs, (bf16_t*)dX, nullptr, c.N, c.K);
+  return launch<true, 2, 4>(c, (const bf16_t*)dY, (const bf16_t*)Gs, (bf16_t*)dX, nullptr, c.N, c.K);
 }
 
 }  // namespace mux
