@@ -11,6 +11,8 @@
 //   reduce: per task, partials summed in ascending item order (deterministic), optional accumulate.
 //
 // Padding rows are masked with out-of-range buffer offsets (the load returns zeros), never multiplied.
+#include <type_traits>
+
 #include "mux_device_utils.h"
 
 namespace mux {
@@ -56,9 +58,11 @@ __global__ __launch_bounds__(256) void k_pack_at(const DevTask* __restrict__ tas
 }
 
 // ------------------------------------------------------------------------------------------------
-// down-projection.  One workgroup = 16 rows of one 64-row item, the 4 waves split the contraction;
-// 16x16x32 MFMA tiles, both operands read straight from global memory (each element of In is used
-// once, P_t stays in L2), partial sums of the 4 waves combined through LDS in a fixed order.
+// down-projection.  One workgroup = RT*16 rows of one 64-row item; its NWV waves split the contraction.
+// 16x16x32 MFMA tiles, both operands read straight from global memory into registers (each element of In
+// is used once; P_t stays in L2 and is reused by the RT row tiles of a wave); the loads of the next group
+// of steps are in flight while the current group is multiplied; the partial sums of the waves are combined
+// through LDS in a fixed order.
 struct DownParams {
   const int32_t* dtab;
   const DevTask* tasks;
@@ -68,18 +72,20 @@ struct DownParams {
   int C, RP;
 };
 
-__global__ __launch_bounds__(256) void k_down(const DownParams p) {
-  __shared__ float red[4][16][68];
-  const int item = blockIdx.x >> 2, sub = blockIdx.x & 3;
+template <int RT, int NWV>
+__global__ __launch_bounds__(64 * NWV) void k_down(const DownParams p) {
+  constexpr int ROWS = RT * 16, SUBS = 64 / ROWS, NTHR = 64 * NWV;
+  __shared__ float red[NWV][ROWS][68];
+  const int item = blockIdx.x / SUBS, sub = blockIdx.x % SUBS;
   const ItemView it = load_item(p.dtab, TS64, item);
-  const int r0 = sub * 16;
+  const int r0 = sub * ROWS;
   if (r0 >= it.nrows) return;
-  const int nr = it.nrows - r0 < 16 ? it.nrows - r0 : 16;
+  const int nr = it.nrows - r0 < ROWS ? it.nrows - r0 : ROWS;
   const int row0 = it.row0 + r0;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const bool lora = it.task >= 0 && p.tasks[it.task].kind == MUX_ADAPTER_LORA;
   if (!lora || it.nvalid == 0) {
-    for (int e = tid; e < nr * p.RP; e += 256) p.Out[(size_t)(row0 + e / p.RP) * p.RP + e % p.RP] = 0;
+    for (int e = tid; e < nr * p.RP; e += NTHR) p.Out[(size_t)(row0 + e / p.RP) * p.RP + e % p.RP] = 0;
     return;
   }
   const DevTask tk = p.tasks[it.task];
@@ -88,58 +94,91 @@ __global__ __launch_bounds__(256) void k_down(const DownParams p) {
   const int prow = p.AT ? NJ * 16 : rank;            // rows that exist in P
 
   const int i = lane & 15, g = lane >> 4;
-  const bool rvalid = i < nr && row_is_valid(p.dtab, row0 + i);
-  const int per = ((p.C + 3) / 4 + 31) & ~31;
+  const int per = ((p.C + NWV - 1) / NWV + 31) & ~31;
   const int cbeg = wave * per, cend = cbeg + per < p.C ? cbeg + per : p.C;
 
   const rsrc_t rIn = make_rsrc(p.In + (size_t)row0 * p.C, (uint32_t)nr * (uint32_t)p.C * 2u);
   const rsrc_t rP = make_rsrc(P, (uint32_t)prow * (uint32_t)p.C * 2u);
-  const uint32_t in_off = ((uint32_t)i * (uint32_t)p.C + 8u * g) * 2u;
+  uint32_t in_off[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int m = rt * 16 + i;
+    in_off[rt] = (m < nr && row_is_valid(p.dtab, row0 + m)) ? ((uint32_t)m * (uint32_t)p.C + 8u * g) * 2u : OOB;
+  }
   uint32_t p_off[4];
-  bool p_ok[4];
-#pragma unroll
-  for (int jt = 0; jt < 4; ++jt) {
-    p_ok[jt] = jt < NJ && jt * 16 + i < prow;
-    p_off[jt] = ((uint32_t)(jt * 16 + i) * (uint32_t)p.C + 8u * g) * 2u;
-  }
-
-  f32x4 acc[4];
-#pragma unroll
-  for (int jt = 0; jt < 4; ++jt) acc[jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-
-  constexpr int U = 4;
-  for (int c = cbeg; c < cend; c += 32 * U) {
-    u32x4 a[U], b[U][4];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int cc = c + 32 * u;
-      const bool ok = cc + 8 * g < cend;
-      a[u] = buf_load16(rIn, (rvalid && ok) ? in_off + (uint32_t)cc * 2u : OOB);
-#pragma unroll
-      for (int jt = 0; jt < 4; ++jt)
-        if (jt < NJ) b[u][jt] = buf_load16(rP, (p_ok[jt] && ok) ? p_off[jt] + (uint32_t)cc * 2u : OOB);
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-      for (int jt = 0; jt < 4; ++jt)
-        if (jt < NJ) acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a[u]), as_bf16x8(b[u][jt]), acc[jt], 0, 0, 0);
-  }
-  // acc[jt][v] = partial of Out[row0 + 4g + v][jt*16 + i]
 #pragma unroll
   for (int jt = 0; jt < 4; ++jt)
+    p_off[jt] = (jt < NJ && jt * 16 + i < prow) ? ((uint32_t)(jt * 16 + i) * (uint32_t)p.C + 8u * g) * 2u : OOB;
+
+  f32x4 acc[RT][4];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) red[wave][4 * g + v][jt * 16 + i] = acc[jt][v];
-  __syncthreads();
-  const int orow = tid >> 4, oj = tid & 15;
-  if (orow < nr) {
-    const bool ok = row_is_valid(p.dtab, row0 + orow);
-    for (int jt = 0; jt * 16 < p.RP; ++jt) {
-      const int j = jt * 16 + oj;
-      const float s = ((red[0][orow][j] + red[1][orow][j]) + red[2][orow][j]) + red[3][orow][j];
-      p.Out[(size_t)(row0 + orow) * p.RP + j] = f32_to_bf16(ok && j < rank ? tk.scale * s : 0.f);
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt) acc[rt][jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  // U steps of 32 per group; with more than two rank tiles the group is halved to stay within registers
+  auto run = [&](auto UC, auto JC) {
+    constexpr int U = decltype(UC)::value, NJM = decltype(JC)::value;
+    u32x4 a[2][U][RT], b[2][U][NJM];
+    auto load = [&](int c, int buf) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int cc = c + 32 * u;
+        const uint32_t k = (cc + 8 * g < cend) ? (uint32_t)cc * 2u : OOB;     // OOB + OOB wraps into range: mask on k only
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) a[buf][u][rt] = buf_load16(rIn, (in_off[rt] == OOB || k == OOB) ? OOB : in_off[rt] + k);
+#pragma unroll
+        for (int jt = 0; jt < NJM; ++jt)
+          if (jt < NJ) b[buf][u][jt] = buf_load16(rP, (p_off[jt] == OOB || k == OOB) ? OOB : p_off[jt] + k);
+      }
+    };
+    auto mul = [&](int buf) {
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+          for (int jt = 0; jt < NJM; ++jt)
+            if (jt < NJ)
+              acc[rt][jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a[buf][u][rt]), as_bf16x8(b[buf][u][jt]), acc[rt][jt], 0, 0, 0);
+    };
+    load(cbeg, 0);
+    for (int c = cbeg; c < cend; c += 64 * U) {
+      load(c + 32 * U, 1);      // past cend every piece is masked
+      mul(0);
+      load(c + 64 * U, 0);
+      mul(1);
     }
+  };
+  if (NJ <= 2) run(std::integral_constant<int, 4>{}, std::integral_constant<int, 2>{});
+  else run(std::integral_constant<int, 2>{}, std::integral_constant<int, 4>{});
+
+  // acc[rt][jt][v] = partial of Out[row0 + rt*16 + 4g + v][jt*16 + i]
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) red[wave][rt * 16 + 4 * g + v][jt * 16 + i] = acc[rt][jt][v];
+  __syncthreads();
+  for (int e = tid; e < ROWS * p.RP; e += NTHR) {
+    const int orow = e / p.RP, j = e % p.RP;
+    if (orow >= nr) continue;
+    float s = 0.f;
+#pragma unroll
+    for (int w = 0; w < NWV; ++w) s += red[w][orow][j];
+    const bool ok = row_is_valid(p.dtab, row0 + orow);
+    p.Out[(size_t)(row0 + orow) * p.RP + j] = f32_to_bf16(ok && j < rank ? tk.scale * s : 0.f);
   }
+}
+
+// few rows: many narrow workgroups (16 rows, 8 waves); many rows: 32 rows per workgroup, P_t read half as often
+void launch_down(const CallCtx& c, const char* name, const DownParams& p) {
+  const unsigned items = (unsigned)c.st->items[TS64].size();
+  if (c.st->T >= 16384)
+    MUX_LAUNCH(name, (k_down<2, 4>), dim3(items * 2), dim3(256), 0, c.stream, p);
+  else
+    MUX_LAUNCH(name, (k_down<1, 8>), dim3(items * 4), dim3(512), 0, c.stream, p);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -158,6 +197,7 @@ struct GradParams {
 
 constexpr int GP = 72;   // LDS row pitch in elements (144 B)
 
+template <int NJM>
 __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
   __shared__ __attribute__((aligned(16))) bf16_t lds[4][2][32 * GP];
   const ItemView it = load_item(p.dtab, p.ts, blockIdx.x);
@@ -181,12 +221,15 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
   const int n_small = (32 * ppr + 63) >> 6;    // loads per lane (1..4)
 
   u32x4 gb[4], gs[4];
+  const int total_rows = p.dtab[DH_T];
   auto load_step = [&](int s) {
     const int base = s * 32;
+    // validity of the 32 rows of this step, wave-uniform (rows past the end of the batch are never valid)
+    const uint32_t vbits = it.row0 + base < total_rows ? row_valid_bits32(p.dtab, it.row0 + base) : 0u;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int m = base + b_row + 8 * q;
-      const bool ok = b_col_ok && m < it.nrows && row_is_valid(p.dtab, it.row0 + m);
+      const bool ok = b_col_ok && m < it.nrows && ((vbits >> (b_row + 8 * q)) & 1u);
       gb[q] = buf_load16(rB, ok ? (uint32_t)(((size_t)m * p.C + cw0 + b_pc) * 2) : OOB);
     }
 #pragma unroll
@@ -210,9 +253,9 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
     }
   };
 
-  f32x4 acc[4][4];
+  f32x4 acc[NJM][4];
 #pragma unroll
-  for (int jt = 0; jt < 4; ++jt)
+  for (int jt = 0; jt < NJM; ++jt)
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct) acc[jt][ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
@@ -225,9 +268,9 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
     if (s + 1 < steps) load_step(s + 1);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    bf16x8 a[4], b[4];
+    bf16x8 a[NJM], b[4];
 #pragma unroll
-    for (int jt = 0; jt < 4; ++jt)
+    for (int jt = 0; jt < NJM; ++jt)
       if (jt < NJ) {
         const bf16x4 lo = lds_read_tr(sSm + tr_off + jt * 16), hi = lds_read_tr(sSm + tr_off + 4 * GP + jt * 16);
         a[jt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -238,7 +281,7 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
       b[ct] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     }
 #pragma unroll
-    for (int jt = 0; jt < 4; ++jt)
+    for (int jt = 0; jt < NJM; ++jt)
       if (jt < NJ)
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct) acc[jt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[jt], b[ct], acc[jt][ct], 0, 0, 0);
@@ -248,7 +291,7 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
   // acc[jt][ct][v] = part[j = jt*16 + 4g + v][c = cw0 + ct*16 + l16]
   float* dst = p.part + (size_t)blockIdx.x * p.RP * p.C;
 #pragma unroll
-  for (int jt = 0; jt < 4; ++jt)
+  for (int jt = 0; jt < NJM; ++jt)
     if (jt < NJ)
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
@@ -264,11 +307,11 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
 
 // ------------------------------------------------------------------------------------------------
 // IA3_OUT: part[item][n] = sum_{rows} g[i][n] * z[i][n], and dYs[i][n] = g[i][n] * l_t[n] (the operand of the
-// backbone backward for these rows).  grid = (256-row items, ceil(N/2048)); 8 columns per thread.
+// backbone backward for these rows).  grid = (64-row items, ceil(N/2048)); 8 columns per thread, 4 rows in flight.
 __global__ __launch_bounds__(256) void k_dl(const int32_t* __restrict__ dtab, const DevTask* __restrict__ tasks,
                                            const bf16_t* __restrict__ dY, const bf16_t* __restrict__ Z, float* __restrict__ part,
                                            bf16_t* __restrict__ dYs, int N) {
-  const ItemView it = load_item(dtab, TS256, blockIdx.x);
+  const ItemView it = load_item(dtab, TS64, blockIdx.x);
   if (it.task < 0 || it.nvalid == 0) return;
   const DevTask tk = tasks[it.task];
   if (tk.kind != MUX_ADAPTER_IA3_OUT) return;
@@ -283,24 +326,34 @@ __global__ __launch_bounds__(256) void k_dl(const int32_t* __restrict__ dtab, co
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) s[e] = 0.f;
-  for (int m = 0; m < it.nrows; ++m) {
-    const int row = it.row0 + m;
-    if (!row_is_valid(dtab, row)) continue;
-    const size_t zoff = (size_t)(tk.zrow0 + row - tk.row_begin) * N + n0;
-    const uint4 gv = *(const uint4*)(dY + (size_t)row * N + n0);
-    const uint4 zv = *(const uint4*)(Z + zoff);
-    const uint32_t* pg = (const uint32_t*)&gv;
-    const uint32_t* pz = (const uint32_t*)&zv;
-    uint4 sv;
-    uint32_t* ps = (uint32_t*)&sv;
+  for (int m0 = 0; m0 < it.nrows; m0 += 4) {
+    uint4 gv[4], zv[4];
+    bool ok[4];
+    size_t zoff[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float g0 = __uint_as_float(pg[e] << 16), g1 = __uint_as_float(pg[e] & 0xffff0000u);
-      s[2 * e] = fmaf(g0, __uint_as_float(pz[e] << 16), s[2 * e]);
-      s[2 * e + 1] = fmaf(g1, __uint_as_float(pz[e] & 0xffff0000u), s[2 * e + 1]);
-      ps[e] = pack_bf16x2(g0 * lv[2 * e], g1 * lv[2 * e + 1]);
+    for (int u = 0; u < 4; ++u) {
+      const int row = it.row0 + m0 + u;
+      ok[u] = m0 + u < it.nrows && row_is_valid(dtab, row);
+      zoff[u] = (size_t)(tk.zrow0 + row - tk.row_begin) * N + n0;
+      gv[u] = ok[u] ? *(const uint4*)(dY + (size_t)row * N + n0) : make_uint4(0, 0, 0, 0);
+      zv[u] = ok[u] ? *(const uint4*)(Z + zoff[u]) : make_uint4(0, 0, 0, 0);
     }
-    *(uint4*)(dYs + zoff) = sv;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (!ok[u]) continue;
+      const uint32_t* pg = (const uint32_t*)&gv[u];
+      const uint32_t* pz = (const uint32_t*)&zv[u];
+      uint4 sv;
+      uint32_t* ps = (uint32_t*)&sv;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float g0 = __uint_as_float(pg[e] << 16), g1 = __uint_as_float(pg[e] & 0xffff0000u);
+        s[2 * e] = fmaf(g0, __uint_as_float(pz[e] << 16), s[2 * e]);
+        s[2 * e + 1] = fmaf(g1, __uint_as_float(pz[e] & 0xffff0000u), s[2 * e + 1]);
+        ps[e] = pack_bf16x2(g0 * lv[2 * e], g1 * lv[2 * e + 1]);
+      }
+      *(uint4*)(dYs + zoff[u]) = sv;
+    }
   }
   float* dst = part + (size_t)blockIdx.x * N + n0;
 #pragma unroll
@@ -334,6 +387,12 @@ __global__ __launch_bounds__(256) void k_reduce(const int32_t* __restrict__ dtab
   *dst = accumulate ? *dst + s : s;
 }
 
+void launch_grad(const CallCtx& c, const char* name, const GradParams& p, dim3 grid) {
+  if (c.st->r_max <= 16) MUX_LAUNCH(name, (k_grad<1>), grid, dim3(256), 0, c.stream, p);
+  else if (c.st->r_max <= 32) MUX_LAUNCH(name, (k_grad<2>), grid, dim3(256), 0, c.stream, p);
+  else MUX_LAUNCH(name, (k_grad<4>), grid, dim3(256), 0, c.stream, p);
+}
+
 int choose_group(const mux_segtab* st, int C) {
   // bigger row groups mean fewer partial bytes; keep at least ~1024 workgroups in flight
   const size_t wg1024 = st->items[TS1024].size() * (size_t)((C + 255) / 256);
@@ -346,7 +405,7 @@ size_t adapter_partial_bytes(int K, int N, const mux_segtab* st) {
   const int C = K > N ? K : N;
   const int RP = st->n_lora > 0 ? round_up(st->r_max, 16) : 0;
   size_t lora = (size_t)st->items[TS256].size() * RP * C * 4;
-  size_t ia3 = st->n_ia3 > 0 ? (size_t)st->items[TS256].size() * N * 4 : 0;
+  size_t ia3 = st->n_ia3 > 0 ? (size_t)st->items[TS64].size() * N * 4 : 0;
   return align256(lora > ia3 ? lora : ia3);
 }
 
@@ -354,14 +413,14 @@ mux_status adapter_down_x(const CallCtx& c, const void* X, void* Hs) {
   if (c.st->n_lora == 0) return MUX_OK;
   MUX_LAUNCH("pack_at", k_pack_at, dim3(c.st->n_tasks, (c.K + 63) / 64), dim3(256), 0, c.stream, c.dtasks, (bf16_t*)c.AT, c.K);
   DownParams p{c.dtab, c.dtasks, (const bf16_t*)X, (bf16_t*)Hs, (const bf16_t*)c.AT, c.K, c.RP};
-  MUX_LAUNCH("down_x", k_down, dim3((unsigned)c.st->items[TS64].size() * 4), dim3(256), 0, c.stream, p);
+  launch_down(c, "down_x", p);
   return MUX_OK;
 }
 
 mux_status adapter_down_g(const CallCtx& c, const void* dY, void* Gs) {
   if (c.st->n_lora == 0) return MUX_OK;
   DownParams p{c.dtab, c.dtasks, (const bf16_t*)dY, (bf16_t*)Gs, nullptr, c.N, c.RP};
-  MUX_LAUNCH("down_g", k_down, dim3((unsigned)c.st->items[TS64].size() * 4), dim3(256), 0, c.stream, p);
+  launch_down(c, "down_g", p);
   return MUX_OK;
 }
 
@@ -372,7 +431,7 @@ mux_status adapter_grads(const CallCtx& c, const void* X, const void* dY, const 
     {  // dB_t = Hs^T dY
       const int ts = choose_group(c.st, c.N);
       GradParams p{c.dtab, c.dtasks, (const bf16_t*)Hs, (const bf16_t*)dY, (float*)part, c.N, c.RP, ts};
-      MUX_LAUNCH("grad_db", k_grad, dim3((unsigned)c.st->items[ts].size(), (c.N + 255) / 256), dim3(256), 0, c.stream, p);
+      launch_grad(c, "grad_db", p, dim3((unsigned)c.st->items[ts].size(), (c.N + 255) / 256));
       const size_t elems = (size_t)c.st->r_max * c.N;
       MUX_LAUNCH("reduce_db", k_reduce, dim3(M, (unsigned)((elems + 255) / 256)), dim3(256), 0, c.stream, c.dtab, c.dtasks,
                  (const float*)part, c.N, c.RP, ts, 0, accumulate);
@@ -380,17 +439,17 @@ mux_status adapter_grads(const CallCtx& c, const void* X, const void* dY, const 
     {  // dA_t = X^T Gs
       const int ts = choose_group(c.st, c.K);
       GradParams p{c.dtab, c.dtasks, (const bf16_t*)Gs, (const bf16_t*)X, (float*)part, c.K, c.RP, ts};
-      MUX_LAUNCH("grad_da", k_grad, dim3((unsigned)c.st->items[ts].size(), (c.K + 255) / 256), dim3(256), 0, c.stream, p);
+      launch_grad(c, "grad_da", p, dim3((unsigned)c.st->items[ts].size(), (c.K + 255) / 256));
       const size_t elems = (size_t)c.st->r_max * c.K;
       MUX_LAUNCH("reduce_da", k_reduce, dim3(M, (unsigned)((elems + 255) / 256)), dim3(256), 0, c.stream, c.dtab, c.dtasks,
                  (const float*)part, c.K, c.RP, ts, 1, accumulate);
     }
   }
   if (c.st->n_ia3 > 0) {
-    MUX_LAUNCH("grad_dl", k_dl, dim3((unsigned)c.st->items[TS256].size(), (c.N + 2047) / 2048), dim3(256), 0, c.stream,
+    MUX_LAUNCH("grad_dl", k_dl, dim3((unsigned)c.st->items[TS64].size(), (c.N + 2047) / 2048), dim3(256), 0, c.stream,
                c.dtab, c.dtasks, (const bf16_t*)dY, (const bf16_t*)Z, (float*)part, (bf16_t*)c.dYs, c.N);
     MUX_LAUNCH("reduce_dl", k_reduce, dim3(M, (c.N + 255) / 256), dim3(256), 0, c.stream, c.dtab, c.dtasks,
-               (const float*)part, c.N, 1, TS256, 2, accumulate);
+               (const float*)part, c.N, 1, TS64, 2, accumulate);
   }
   return MUX_OK;
 }

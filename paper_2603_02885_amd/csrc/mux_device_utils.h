@@ -39,6 +39,14 @@ __device__ __forceinline__ bool row_is_valid(const int32_t* __restrict__ dtab, i
   return (row & ((1 << lg) - 1)) < dtab[dtab[DH_OFF_CHUNK_VALID] + ch];
 }
 
+// Validity bits of rows row_base .. row_base+31 (bit r = row row_base + r is a real token).
+__device__ __forceinline__ uint32_t row_valid_bits32(const int32_t* __restrict__ dtab, int row_base) {
+  const uint32_t* bm = (const uint32_t*)(dtab + dtab[DH_OFF_ROWBITS]);
+  const int w = row_base >> 5, sh = row_base & 31;
+  const uint64_t two = (uint64_t)bm[w] | ((uint64_t)bm[w + 1] << 32);
+  return (uint32_t)(two >> sh);
+}
+
 struct ItemView { int task, row0, nrows, nvalid; };
 __device__ __forceinline__ ItemView load_item(const int32_t* __restrict__ dtab, int tile_size_index, int item) {
   const int32_t* p = dtab + dtab[DH_NITEMS0 + 3 * tile_size_index + 1] + item * DI_WORDS;

@@ -14,7 +14,7 @@ namespace mux {
 enum : int {
   DH_MAGIC = 0, DH_T, DH_CHUNK, DH_LOG2C, DH_NTASKS, DH_NCHUNKS, DH_OFF_TASKS, DH_OFF_CHUNK_VALID,
   DH_NITEMS0,            // + 3*i : n_items, off_items, off_task_items for tile size kTileRows[i]
-  DH_ZROWS = DH_NITEMS0 + 12, DH_RMAX, DH_WORDS, DH_HDR_WORDS = 32
+  DH_ZROWS = DH_NITEMS0 + 12, DH_RMAX, DH_WORDS, DH_OFF_ROWBITS, DH_HDR_WORDS = 32
 };
 constexpr int kNumTileSizes = 4;
 constexpr int kTileRows[kNumTileSizes] = {64, 128, 256, 1024};

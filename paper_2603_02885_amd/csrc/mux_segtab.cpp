@@ -216,6 +216,15 @@ extern "C" mux_status mux_segtab_build(const mux_task_desc* tasks, int32_t n_tas
       dv[DH_NITEMS0 + 3 * ts + 2] = (int32_t)dv.size();
       for (int32_t t = 0; t < n_tasks; ++t) { dv.push_back(st->task_item_begin[ts][t]); dv.push_back(st->task_item_count[ts][t]); }
     }
+    // one bit per row (1 = real token), 32 rows per word, one spare word so that two-word windows never run out
+    dv[DH_OFF_ROWBITS] = (int32_t)dv.size();
+    {
+      const size_t words = (size_t)(st->T + 31) / 32 + 1;
+      const size_t base = dv.size();
+      dv.resize(base + words, 0);
+      for (int32_t i = 0; i < st->T; ++i)
+        if (st->row_task[i] >= 0) dv[base + (i >> 5)] |= (int32_t)(1u << (i & 31));
+    }
     while (dv.size() % 64) dv.push_back(0);
     dv[DH_WORDS] = (int32_t)dv.size();
   } catch (const std::bad_alloc&) {
