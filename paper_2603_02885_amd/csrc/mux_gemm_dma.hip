@@ -198,15 +198,17 @@ __global__ __launch_bounds__(128 * WNW, 1) void k_gemm_dma(const GemmParams p) {
       }
     }
   };
-  // straight-line: 8 address adds, 8 loads
+  // one load of the tile being fetched: i = 0 .. ACH+BCH-1, A and B pieces alternating
+  auto issue_one = [&](bf16_t* dA, bf16_t* dB, int i) {
+    const int q = i >> 1;
+    if ((i & 1) == 0) dma16(curA, dA + (wave * ACH + q) * 512, offA[q] + kA);
+    else dma16(curB, dB + (wave * BCH + q) * 512, offB[q] + kB);
+  };
+  auto issue_done = [&]() { kA += stepA; kB += stepB; ++next_tile; };
   auto issue = [&](bf16_t* dA, bf16_t* dB) {
 #pragma unroll
-    for (int q = 0; q < ACH; ++q) {
-      dma16(curA, dA + (wave * ACH + q) * 512, offA[q] + kA);
-      dma16(curB, dB + (wave * BCH + q) * 512, offB[q] + kB);
-    }
-    kA += stepA; kB += stepB;
-    ++next_tile;
+    for (int i = 0; i < ACH + BCH; ++i) issue_one(dA, dB, i);
+    issue_done();
   };
 
   // ---- operand read geometry
@@ -255,6 +257,11 @@ __global__ __launch_bounds__(128 * WNW, 1) void k_gemm_dma(const GemmParams p) {
         acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
   };
 
+  auto mma_one = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[NI], int m) {
+    const int mi = m / NI, ni = m % NI;
+    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+  };
+
   auto stA = [&](int s) -> bf16_t* { return s == 0 ? sA0 : (s == 1 ? sA1 : (s == 2 ? sA2 : sA3)); };
   auto stB = [&](int s) -> bf16_t* { return s == 0 ? sB0 : (s == 1 ? sB1 : (s == 2 ? sB2 : sB3)); };
 
@@ -280,20 +287,19 @@ __global__ __launch_bounds__(128 * WNW, 1) void k_gemm_dma(const GemmParams p) {
         bf16_t* cB = stB(u);
         prepare();
         __builtin_amdgcn_sched_barrier(0);
-        // first MFMA step; spread among its 16 MFMAs: the refill of the stage computed from in the previous
-        // iteration with tile kt+3 (past the last tile this fetches zeros nobody reads) and the operand reads
-        // of the second step
-        issue(stA((u + 3) & 3), stB((u + 3) & 3));
+        // first MFMA step.  The operand reads of the second step go out first (their latency hides under the
+        // MFMAs); the refill of the stage computed from in the previous iteration with tile kt+3 (past the last
+        // tile: zeros nobody reads) is spread between the MFMA pairs.
         read_ops(cA, cB, 1, a1, b1);
-        mma(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < 2 * NI; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                       // 2 MFMA
-          __builtin_amdgcn_sched_group_barrier(0x100, (NT && NI == 4) ? 1 : 2, 0); // operand reads
-          __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);                       // address add
-          __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                       // direct-to-LDS load
+          mma_one(a0, b0, 2 * i);
+          mma_one(a0, b0, 2 * i + 1);
+          if (i < ACH + BCH) issue_one(stA((u + 3) & 3), stB((u + 3) & 3), i);
+          __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
+        issue_done();
         // tile kt+1 must have landed (the two newer ones may stay in flight) and every read of this stage be done
         wait_vmcnt<2 * (ACH + BCH)>();
         wait_lgkm0();
@@ -303,12 +309,8 @@ __global__ __launch_bounds__(128 * WNW, 1) void k_gemm_dma(const GemmParams p) {
         __builtin_amdgcn_sched_barrier(0);
         // second MFMA step, with the first operands of the next tile read under it
         if (kt + 1 < KT_total) read_ops(stA((u + 1) & 3), stB((u + 1) & 3), 0, a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
         mma(a1, b1);
-#pragma unroll
-        for (int i = 0; i < 2 * NI; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-          __builtin_amdgcn_sched_group_barrier(0x100, (NT && NI == 4) ? 1 : 2, 0);
-        }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
