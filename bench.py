@@ -31,6 +31,8 @@ def parse():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain 512 MiB device copy (known traffic) for scaling rocprofv3 byte counters")
     return ap.parse_args()
 
 
@@ -191,6 +193,15 @@ def main():
         roofline = {"kernel": dom, "bound": "mfma", "achieved": tf, "peak": PEAK_BF16_MFMA, "unit": "TFLOP/s",
                     "frac": tf / PEAK_BF16_MFMA, "traffic": None,
                     "launches_per_step": kernels[dom]["launches"] / args.steps, "avg_launch_us": kernels[dom]["avg_us"]}
+    # HBM bytes per launch of that kernel from the committed rocprofv3 --pmc summary of this workload (two separate
+    # counter runs, scaled by a plain copy of known size); null when no summary for this workload is there
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{wl.name}.txt")
+    if roofline and os.path.exists(tpath):
+        for line in open(tpath):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and f[1] == dom:
+                roofline["traffic"] = float(f[2])
+                roofline["algorithmic_bytes_per_launch"] = sum(2.0 * (T * K + K * N + T * N) for _, K, N in wl.layers) / len(wl.layers)
     for n in gemm_names:
         kernels[n]["tflops"] = gemm_flops[n] / (kernels[n]["total_ms_per_step"] * 1e-3) / 1e12
         kernels[n]["frac_of_bf16_mfma_peak"] = kernels[n]["tflops"] / PEAK_BF16_MFMA
@@ -208,6 +219,13 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    if args.calibrate_copy:
+        src = torch.zeros(512 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calibration_copy_bytes"] = int(src.numel())
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds, args.seed)
     print(json.dumps(out))
