@@ -161,8 +161,10 @@ mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_segtab* st,
                              void* const* dL, int accumulate, void* ws, size_t ws_bytes,
                              void* hip_stream);
 
-/* Per-kernel timing for benchmarks.  While enabled, every kernel the library launches is
- * bracketed by two HIP events recorded on the launch stream (no synchronisation is added).
+/* Per-kernel timing for benchmarks.  While enabled (on = 1: every kernel, on = 2: only the
+ * backbone GEMM kernels, on = 0: off), each such launch is bracketed by two HIP events
+ * recorded on the launch stream (no synchronisation is added; an event pair costs a few
+ * microseconds of stream time, which is why mode 2 exists).
  * mux_profile_collect waits for the recorded events, fills up to `cap` entries with one line
  * per kernel (name, number of launches, summed duration in milliseconds), returns the number
  * of distinct kernels in *n, and clears the record.  Process-wide, not thread-safe; leave it

@@ -277,8 +277,9 @@ def mux_lora_backward(layer: LayerDesc, st: SegTab, dev_segtab, X, dY, saved, dX
         int(accumulate), _ptr(ws), int(ws_bytes), _stream(stream)))
 
 
-def mux_profile_enable(on: bool) -> None:
-    _check(load_library().mux_profile_enable(1 if on else 0))
+def mux_profile_enable(on) -> None:
+    """0/False off, 1/True every kernel, 2 backbone GEMM kernels only."""
+    _check(load_library().mux_profile_enable(int(on)))
 
 
 def mux_profile_collect(cap: int = 64) -> List[dict]:

@@ -38,26 +38,6 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t* p) {
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // ------------------------------------------------------------------------------------------------
-// A_t [K][r]  ->  A_t^T [round_up(r,16)][K]  (rows beyond r are zero).  grid = (tasks, ceil(K/64)).
-__global__ __launch_bounds__(256) void k_pack_at(const DevTask* __restrict__ tasks, bf16_t* __restrict__ AT, int K) {
-  const DevTask tk = tasks[blockIdx.x];
-  if (tk.kind != MUX_ADAPTER_LORA) return;
-  __shared__ bf16_t t[64][66];
-  const int r = tk.rank, rp = (r + 15) & ~15, k0 = blockIdx.y * 64;
-  const bf16_t* A = (const bf16_t*)tk.A;
-  for (int e = threadIdx.x; e < 64 * rp; e += 256) {
-    const int kk = e / rp, j = e % rp;
-    t[j][kk] = (j < r && k0 + kk < K) ? A[(size_t)(k0 + kk) * r + j] : (bf16_t)0;
-  }
-  __syncthreads();
-  bf16_t* dst = AT + tk.at_off;
-  for (int e = threadIdx.x; e < 64 * rp; e += 256) {
-    const int j = e >> 6, kk = e & 63;
-    if (k0 + kk < K) dst[(size_t)j * K + k0 + kk] = t[j][kk];
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
 // down-projection.  One workgroup = RT*16 rows of one 64-row item; its NWV waves split the contraction.
 // 16x16x32 MFMA tiles, both operands read straight from global memory into registers (each element of In
 // is used once; P_t stays in L2 and is reused by the RT row tiles of a wave); the loads of the next group
@@ -186,13 +166,14 @@ void launch_down(const CallCtx& c, const char* name, const DownParams& p) {
 // 64 columns and walks the item's rows 32 at a time: the 32x64 slab of Big and the 32xRP slab of Small
 // go through a wave-private LDS region in their natural layout and come back k-major per lane through
 // ds_read_b64_tr_b16.  No workgroup barrier: the four waves are independent streams.
-struct GradParams {
+struct GradParams {     // blockIdx.z picks the problem: 0 = dB (Small = Hs, Big = dY), 1 = dA (Small = Gs, Big = X)
   const int32_t* dtab;
   const DevTask* tasks;
-  const bf16_t* Small;  // [T, RP]
-  const bf16_t* Big;    // [T, C]
-  float* part;          // [n_items][RP][C]
-  int C, RP, ts;
+  const bf16_t* Small[2];  // [T, RP]
+  const bf16_t* Big[2];    // [T, C]
+  float* part[2];          // [n_items][RP][C]
+  int C[2];
+  int RP, ts;
 };
 
 constexpr int GP = 72;   // LDS row pitch in elements (144 B)
@@ -205,17 +186,19 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
   const DevTask tk = p.tasks[it.task];
   if (tk.kind != MUX_ADAPTER_LORA) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int z = blockIdx.z;
+  const int C = p.C[z];
   const int cw0 = blockIdx.y * 256 + wave * 64;
-  if (cw0 >= p.C) return;
+  if (cw0 >= C) return;
   const int rank = tk.rank, NJ = (rank + 15) >> 4;
   bf16_t* sBig = lds[wave][0];
   bf16_t* sSm = lds[wave][1];
 
-  const rsrc_t rB = make_rsrc(p.Big + (size_t)it.row0 * p.C, (uint32_t)it.nrows * (uint32_t)p.C * 2u);
-  const rsrc_t rS = make_rsrc(p.Small + (size_t)it.row0 * p.RP, (uint32_t)it.nrows * (uint32_t)p.RP * 2u);
+  const rsrc_t rB = make_rsrc(p.Big[z] + (size_t)it.row0 * C, (uint32_t)it.nrows * (uint32_t)C * 2u);
+  const rsrc_t rS = make_rsrc(p.Small[z] + (size_t)it.row0 * p.RP, (uint32_t)it.nrows * (uint32_t)p.RP * 2u);
   // Big slab: 4 loads per lane, row = 8q + lane/8, 16-byte piece = lane%8
   const int b_row = lane >> 3, b_pc = (lane & 7) * 8;
-  const bool b_col_ok = cw0 + b_pc < p.C;
+  const bool b_col_ok = cw0 + b_pc < C;
   // Small slab: pieces per row = RP/8; idx = lane + 64 q -> row = idx / ppr, piece = idx % ppr
   const int ppr = p.RP >> 3;
   const int n_small = (32 * ppr + 63) >> 6;    // loads per lane (1..4)
@@ -230,7 +213,7 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
     for (int q = 0; q < 4; ++q) {
       const int m = base + b_row + 8 * q;
       const bool ok = b_col_ok && m < it.nrows && ((vbits >> (b_row + 8 * q)) & 1u);
-      gb[q] = buf_load16(rB, ok ? (uint32_t)(((size_t)m * p.C + cw0 + b_pc) * 2) : OOB);
+      gb[q] = buf_load16(rB, ok ? (uint32_t)(((size_t)m * C + cw0 + b_pc) * 2) : OOB);
     }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -289,7 +272,7 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
     __builtin_amdgcn_wave_barrier();
   }
   // acc[jt][ct][v] = part[j = jt*16 + 4g + v][c = cw0 + ct*16 + l16]
-  float* dst = p.part + (size_t)blockIdx.x * p.RP * p.C;
+  float* dst = p.part[z] + (size_t)blockIdx.x * p.RP * C;
 #pragma unroll
   for (int jt = 0; jt < NJM; ++jt)
     if (jt < NJ)
@@ -300,7 +283,7 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
 #pragma unroll
           for (int ct = 0; ct < 4; ++ct) {
             const int c = cw0 + ct * 16 + l16;
-            if (c < p.C) dst[(size_t)j * p.C + c] = acc[jt][ct][v];
+            if (c < C) dst[(size_t)j * C + c] = acc[jt][ct][v];
           }
       }
 }
@@ -361,19 +344,26 @@ __global__ __launch_bounds__(256) void k_dl(const int32_t* __restrict__ dtab, co
 }
 
 // ------------------------------------------------------------------------------------------------
-// out_t = (accumulate ? out_t : 0) + sum over the task's items, ascending.  grid = (tasks, blocks over rows*C).
-// which: 0 = dB [r][C], 1 = dA [C][r] (transposed store), 2 = dL [C] (one row per item, IA3_OUT tasks).
+// out_t = (accumulate ? out_t : 0) + sum over the task's items, ascending.  grid = (tasks, blocks over the elements).
+// mode 0: LoRA, elements [0, r*N) are dB_t [r][N] from part0, elements [r*N, r*(N+K)) are dA_t from part1, stored
+// transposed as [K][r].  mode 1: IA3_OUT, dl_t [N] from part0 (one row per item).
 __global__ __launch_bounds__(256) void k_reduce(const int32_t* __restrict__ dtab, const DevTask* __restrict__ tasks,
-                                               const float* __restrict__ part, int C, int RP, int ts, int which, int accumulate) {
+                                               const float* __restrict__ part0, const float* __restrict__ part1, int N, int K,
+                                               int RP, int ts, int mode, int accumulate) {
   const int t = blockIdx.x;
   const DevTask tk = tasks[t];
-  const bool is_l = which == 2;
-  if (tk.kind != (is_l ? MUX_ADAPTER_IA3_OUT : MUX_ADAPTER_LORA)) return;
-  float* out = which == 0 ? tk.dB : (which == 1 ? tk.dA : tk.dL);
-  if (!out) return;
-  const int rows = is_l ? 1 : tk.rank;
-  const size_t e = (size_t)blockIdx.y * 256 + threadIdx.x;
-  if (e >= (size_t)rows * C) return;
+  if (tk.kind != (mode == 1 ? MUX_ADAPTER_IA3_OUT : MUX_ADAPTER_LORA)) return;
+  const int rows = mode == 1 ? 1 : tk.rank;
+  size_t e = (size_t)blockIdx.y * 256 + threadIdx.x;
+  const float* part = part0;
+  int C = N;
+  float* out = mode == 1 ? tk.dL : tk.dB;
+  bool transposed = false;
+  if (mode == 0 && e >= (size_t)rows * N) {
+    e -= (size_t)rows * N;
+    part = part1; C = K; out = tk.dA; transposed = true;
+  }
+  if (!out || e >= (size_t)rows * C) return;
   const int j = (int)(e / C), c = (int)(e % C);
   const int32_t* ti = dtab + dtab[DH_NITEMS0 + 3 * ts + 2] + 2 * t;
   const int ib = ti[0], ic = ti[1];
@@ -383,7 +373,7 @@ __global__ __launch_bounds__(256) void k_reduce(const int32_t* __restrict__ dtab
     if (items[(ib + q) * DI_WORDS + DI_NVALID] == 0) continue;
     s += part[((size_t)(ib + q) * RP + j) * C + c];
   }
-  float* dst = which == 1 ? out + (size_t)c * rows + j : out + e;
+  float* dst = transposed ? out + (size_t)c * rows + j : out + e;
   *dst = accumulate ? *dst + s : s;
 }
 
@@ -393,9 +383,9 @@ void launch_grad(const CallCtx& c, const char* name, const GradParams& p, dim3 g
   else MUX_LAUNCH(name, (k_grad<4>), grid, dim3(256), 0, c.stream, p);
 }
 
-int choose_group(const mux_segtab* st, int C) {
+int choose_group(const mux_segtab* st, int K, int N) {
   // bigger row groups mean fewer partial bytes; keep at least ~1024 workgroups in flight
-  const size_t wg1024 = st->items[TS1024].size() * (size_t)((C + 255) / 256);
+  const size_t wg1024 = st->items[TS1024].size() * (size_t)((K + 255) / 256 + (N + 255) / 256);
   return wg1024 >= 1024 ? TS1024 : TS256;
 }
 
@@ -404,14 +394,15 @@ int choose_group(const mux_segtab* st, int C) {
 size_t adapter_partial_bytes(int K, int N, const mux_segtab* st) {
   const int C = K > N ? K : N;
   const int RP = st->n_lora > 0 ? round_up(st->r_max, 16) : 0;
-  size_t lora = (size_t)st->items[TS256].size() * RP * C * 4;
+  size_t lora = align256((size_t)st->items[TS256].size() * RP * N * 4) + align256((size_t)st->items[TS256].size() * RP * K * 4);
+  (void)C;
   size_t ia3 = st->n_ia3 > 0 ? (size_t)st->items[TS64].size() * N * 4 : 0;
   return align256(lora > ia3 ? lora : ia3);
 }
 
 mux_status adapter_down_x(const CallCtx& c, const void* X, void* Hs) {
   if (c.st->n_lora == 0) return MUX_OK;
-  MUX_LAUNCH("pack_at", k_pack_at, dim3(c.st->n_tasks, (c.K + 63) / 64), dim3(256), 0, c.stream, c.dtasks, (bf16_t*)c.AT, c.K);
+  // A_t^T was written into c.AT by the task-table kernel of this call
   DownParams p{c.dtab, c.dtasks, (const bf16_t*)X, (bf16_t*)Hs, (const bf16_t*)c.AT, c.K, c.RP};
   launch_down(c, "down_x", p);
   return MUX_OK;
@@ -428,28 +419,24 @@ mux_status adapter_grads(const CallCtx& c, const void* X, const void* dY, const 
                          void* part, int accumulate) {
   const int M = c.st->n_tasks;
   if (c.st->n_lora > 0) {
-    {  // dB_t = Hs^T dY
-      const int ts = choose_group(c.st, c.N);
-      GradParams p{c.dtab, c.dtasks, (const bf16_t*)Hs, (const bf16_t*)dY, (float*)part, c.N, c.RP, ts};
-      launch_grad(c, "grad_db", p, dim3((unsigned)c.st->items[ts].size(), (c.N + 255) / 256));
-      const size_t elems = (size_t)c.st->r_max * c.N;
-      MUX_LAUNCH("reduce_db", k_reduce, dim3(M, (unsigned)((elems + 255) / 256)), dim3(256), 0, c.stream, c.dtab, c.dtasks,
-                 (const float*)part, c.N, c.RP, ts, 0, accumulate);
-    }
-    {  // dA_t = X^T Gs
-      const int ts = choose_group(c.st, c.K);
-      GradParams p{c.dtab, c.dtasks, (const bf16_t*)Gs, (const bf16_t*)X, (float*)part, c.K, c.RP, ts};
-      launch_grad(c, "grad_da", p, dim3((unsigned)c.st->items[ts].size(), (c.K + 255) / 256));
-      const size_t elems = (size_t)c.st->r_max * c.K;
-      MUX_LAUNCH("reduce_da", k_reduce, dim3(M, (unsigned)((elems + 255) / 256)), dim3(256), 0, c.stream, c.dtab, c.dtasks,
-                 (const float*)part, c.K, c.RP, ts, 1, accumulate);
-    }
+    // dB_t = Hs^T dY and dA_t = X^T Gs: one launch for the partials of both, one for the two reductions
+    const int ts = choose_group(c.st, c.K, c.N);
+    const size_t n_items = c.st->items[ts].size();
+    float* part0 = (float*)part;
+    float* part1 = (float*)((char*)part + align256(c.st->items[TS256].size() * (size_t)c.RP * c.N * 4));
+    GradParams p{c.dtab, c.dtasks, {(const bf16_t*)Hs, (const bf16_t*)Gs}, {(const bf16_t*)dY, (const bf16_t*)X}, {part0, part1},
+                 {c.N, c.K}, c.RP, ts};
+    const int cmax = c.N > c.K ? c.N : c.K;
+    launch_grad(c, "grad_dbda", p, dim3((unsigned)n_items, (cmax + 255) / 256, 2));
+    const size_t elems = (size_t)c.st->r_max * ((size_t)c.N + c.K);
+    MUX_LAUNCH("reduce_dbda", k_reduce, dim3(M, (unsigned)((elems + 255) / 256)), dim3(256), 0, c.stream, c.dtab, c.dtasks,
+               (const float*)part0, (const float*)part1, c.N, c.K, c.RP, ts, 0, accumulate);
   }
   if (c.st->n_ia3 > 0) {
     MUX_LAUNCH("grad_dl", k_dl, dim3((unsigned)c.st->items[TS64].size(), (c.N + 2047) / 2048), dim3(256), 0, c.stream,
                c.dtab, c.dtasks, (const bf16_t*)dY, (const bf16_t*)Z, (float*)part, (bf16_t*)c.dYs, c.N);
     MUX_LAUNCH("reduce_dl", k_reduce, dim3(M, (c.N + 255) / 256), dim3(256), 0, c.stream, c.dtab, c.dtasks,
-               (const float*)part, c.N, 1, TS64, 2, accumulate);
+               (const float*)part, (const float*)nullptr, c.N, c.K, 1, TS64, 1, accumulate);
   }
   return MUX_OK;
 }

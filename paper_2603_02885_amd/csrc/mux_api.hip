@@ -16,21 +16,46 @@ struct TaskPtrArgs {
   int64_t at_off[16];
 };
 
-__global__ void k_fill_tasks(const int32_t* __restrict__ dtab, DevTask* __restrict__ out, TaskPtrArgs p, int base, int count) {
-  const int i = threadIdx.x;
+// Block 0 writes the per-call task table.  With pack_at, blocks 1.. also write A_t^T [round_up(r,16)][K] (zero rows
+// beyond r) for the forward's down-projection: block b handles 64 k-values of task base + (b-1)/ceil(K/64), reading
+// the pointers from the launch arguments (not from the table block 0 is writing).
+__global__ __launch_bounds__(256) void k_fill_tasks(const int32_t* __restrict__ dtab, DevTask* __restrict__ out, TaskPtrArgs p,
+                                                     int base, int count, uint16_t* __restrict__ pack_at, int K) {
+  if (blockIdx.x == 0) {
+    const int i = threadIdx.x;
+    if (i >= count) return;
+    const int32_t* te = dtab + dtab[DH_OFF_TASKS] + (base + i) * DT_WORDS;
+    DevTask d;
+    d.A = p.A[i]; d.B = p.B[i]; d.L = p.L[i];
+    d.dA = p.dA[i]; d.dB = p.dB[i]; d.dL = p.dL[i];
+    d.scale = __int_as_float(te[DT_SCALE_BITS]);
+    d.kind = te[DT_KIND];
+    d.rank = te[DT_RANK];
+    d.row_begin = te[DT_ROW_BEGIN];
+    d.row_count = te[DT_ROW_COUNT];
+    d.zrow0 = te[DT_ZROW0];
+    d.at_off = p.at_off[i];
+    out[base + i] = d;
+    return;
+  }
+  __shared__ uint16_t t[64][66];
+  const int nkb = (K + 63) / 64;
+  const int i = (blockIdx.x - 1) / nkb, k0 = ((blockIdx.x - 1) % nkb) * 64;
   if (i >= count) return;
   const int32_t* te = dtab + dtab[DH_OFF_TASKS] + (base + i) * DT_WORDS;
-  DevTask d;
-  d.A = p.A[i]; d.B = p.B[i]; d.L = p.L[i];
-  d.dA = p.dA[i]; d.dB = p.dB[i]; d.dL = p.dL[i];
-  d.scale = __int_as_float(te[DT_SCALE_BITS]);
-  d.kind = te[DT_KIND];
-  d.rank = te[DT_RANK];
-  d.row_begin = te[DT_ROW_BEGIN];
-  d.row_count = te[DT_ROW_COUNT];
-  d.zrow0 = te[DT_ZROW0];
-  d.at_off = p.at_off[i];
-  out[base + i] = d;
+  if (te[DT_KIND] != MUX_ADAPTER_LORA) return;
+  const int r = te[DT_RANK], rp = (r + 15) & ~15;
+  const uint16_t* A = (const uint16_t*)p.A[i];
+  for (int e = threadIdx.x; e < 64 * rp; e += 256) {
+    const int kk = e / rp, j = e % rp;
+    t[j][kk] = (j < r && k0 + kk < K) ? A[(size_t)(k0 + kk) * r + j] : (uint16_t)0;
+  }
+  __syncthreads();
+  uint16_t* dst = pack_at + p.at_off[i];
+  for (int e = threadIdx.x; e < 64 * rp; e += 256) {
+    const int j = e >> 6, kk = e & 63;
+    if (k0 + kk < K) dst[(size_t)j * K + k0 + kk] = t[j][kk];
+  }
 }
 
 namespace {
@@ -88,7 +113,7 @@ mux_status check_hip(const char* fn) {
 }
 
 void fill_tasks(const mux_layer_desc* L, const mux_segtab* st, const int32_t* dtab, DevTask* dtasks, void* const* dA,
-                void* const* dB, void* const* dL, hipStream_t stream) {
+                void* const* dB, void* const* dL, hipStream_t stream, void* pack_at) {
   int64_t at_off = 0;
   for (int base = 0; base < st->n_tasks; base += 16) {
     TaskPtrArgs p;
@@ -106,7 +131,9 @@ void fill_tasks(const mux_layer_desc* L, const mux_segtab* st, const int32_t* dt
       p.at_off[i] = at_off;
       if (kind == MUX_ADAPTER_LORA) at_off += (int64_t)round_up(st->tasks[t].rank, 16) * L->K;
     }
-    MUX_LAUNCH("fill_tasks", k_fill_tasks, dim3(1), dim3(64), 0, stream, dtab, dtasks, p, base, count);
+    const unsigned pack_blocks = pack_at ? (unsigned)count * (unsigned)((L->K + 63) / 64) : 0u;
+    MUX_LAUNCH("fill_tasks", k_fill_tasks, dim3(1 + pack_blocks), dim3(256), 0, stream, dtab, dtasks, p, base, count,
+               (uint16_t*)pack_at, L->K);
   }
 }
 
@@ -136,7 +163,10 @@ extern "C" mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_se
   if (!saved && st->n_lora > 0) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": saved is null but a task is LoRA");
   hipStream_t stream = (hipStream_t)hip_stream;
   DevTask* dtasks = (DevTask*)ws;
-  fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, nullptr, nullptr, nullptr, stream);
+  const bool fast = layer->dtype == MUX_DT_BF16 && !(layer->flags & MUX_LAYER_REFERENCE_KERNELS);
+  void* at_region = (char*)ws + lo.tasks_bytes + lo.g_bytes;
+  fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, nullptr, nullptr, nullptr, stream,
+             (fast && st->n_lora > 0) ? at_region : nullptr);
   CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP,
             (char*)ws + lo.tasks_bytes + lo.g_bytes, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes, layer->W, stream};
   void* H = saved;
@@ -166,7 +196,7 @@ extern "C" mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_s
   if (ws_bytes < lo.ws_bytes) return fail(MUX_ERR_WORKSPACE, std::string(fn) + ": workspace too small");
   hipStream_t stream = (hipStream_t)hip_stream;
   DevTask* dtasks = (DevTask*)ws;
-  fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, dA, dB, dL, stream);
+  fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, dA, dB, dL, stream, nullptr);
   CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP,
             (char*)ws + lo.tasks_bytes + lo.g_bytes, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes, layer->W, stream};
   const void* H = saved;

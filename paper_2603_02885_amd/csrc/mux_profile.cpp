@@ -11,7 +11,7 @@
 namespace mux {
 namespace {
 struct Rec { const char* name; hipEvent_t a, b; };
-bool g_on = false;
+int g_on = 0;            // 0 off, 1 every kernel, 2 backbone GEMM kernels only
 std::vector<Rec> g_recs;
 std::vector<hipEvent_t> g_pool;
 hipEvent_t g_open = nullptr;
@@ -27,6 +27,7 @@ hipEvent_t get_event() {
 
 void prof_begin(const char* name, hipStream_t stream) {
   if (!g_on) return;
+  if (g_on == 2 && std::strncmp(name, "gemm", 4) != 0) return;
   g_open = get_event();
   g_open_name = name;
   if (g_open) (void)hipEventRecord(g_open, stream);
@@ -48,7 +49,8 @@ void prof_end(hipStream_t stream) {
 using namespace mux;
 
 extern "C" mux_status mux_profile_enable(int on) {
-  g_on = on != 0;
+  if (on < 0 || on > 2) return fail(MUX_ERR_INVALID_ARG, "mux_profile_enable: mode must be 0, 1 or 2");
+  g_on = on;
   return MUX_OK;
 }
 
