@@ -152,13 +152,11 @@ __global__ __launch_bounds__(64 * NWV) void k_down(const DownParams p) {
   }
 }
 
-// few rows: many narrow workgroups (16 rows, 8 waves); many rows: 32 rows per workgroup, P_t read half as often
+// 32 rows per workgroup, four waves splitting the contraction: the fastest of the shapes tried (16/32/64 rows,
+// 4 or 8 waves) on both the 5k-row and the 20k-row workloads.
 void launch_down(const CallCtx& c, const char* name, const DownParams& p) {
   const unsigned items = (unsigned)c.st->items[TS64].size();
-  if (c.st->T >= 16384)
-    MUX_LAUNCH(name, (k_down<2, 4>), dim3(items * 2), dim3(256), 0, c.stream, p);
-  else
-    MUX_LAUNCH(name, (k_down<1, 8>), dim3(items * 4), dim3(512), 0, c.stream, p);
+  MUX_LAUNCH(name, (k_down<2, 4>), dim3(items * 2), dim3(256), 0, c.stream, p);
 }
 
 // ------------------------------------------------------------------------------------------------
