@@ -55,7 +55,8 @@ struct DownParams {
 template <int RT, int NWV>
 __global__ __launch_bounds__(64 * NWV) void k_down(const DownParams p) {
   constexpr int ROWS = RT * 16, SUBS = 64 / ROWS, NTHR = 64 * NWV;
-  __shared__ float red[NWV][ROWS][68];
+  // partial sums, column-major per wave (a lane's four accumulator rows are contiguous: one 16-byte LDS store)
+  __shared__ __attribute__((aligned(16))) float red[NWV][64][ROWS + 4];
   const int item = blockIdx.x / SUBS, sub = blockIdx.x % SUBS;
   const ItemView it = load_item(p.dtab, TS64, item);
   const int r0 = sub * ROWS;
@@ -138,15 +139,14 @@ __global__ __launch_bounds__(64 * NWV) void k_down(const DownParams p) {
   for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
     for (int jt = 0; jt < 4; ++jt)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) red[wave][rt * 16 + 4 * g + v][jt * 16 + i] = acc[rt][jt][v];
+      *(f32x4*)&red[wave][jt * 16 + i][rt * 16 + 4 * g] = acc[rt][jt];
   __syncthreads();
   for (int e = tid; e < ROWS * p.RP; e += NTHR) {
     const int orow = e / p.RP, j = e % p.RP;
     if (orow >= nr) continue;
     float s = 0.f;
 #pragma unroll
-    for (int w = 0; w < NWV; ++w) s += red[w][orow][j];
+    for (int w = 0; w < NWV; ++w) s += red[w][j][orow];
     const bool ok = row_is_valid(p.dtab, row0 + orow);
     p.Out[(size_t)(row0 + orow) * p.RP + j] = f32_to_bf16(ok && j < rank ? tk.scale * s : 0.f);
   }

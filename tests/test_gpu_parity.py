@@ -71,6 +71,21 @@ def test_mixed_kinds_ragged(env, mode, seg_flags):
     run_case(env, mixed_workload(K=264, N=328, chunk=16), dtype=dtype, seg_flags=seg_flags, layer_flags=lf, seed=1)
 
 
+def test_long_contraction_mixed_ranks(env):
+    """Long contraction (64 K-tiles), ranks on both sides of 32 (one and two adapter K-tiles), all adapter kinds;
+    results must match the oracle and repeat bit for bit."""
+    mx, torch = env
+    tasks = [wlm.Task(wlm.KIND_LORA, 16, 2.0, [300]), wlm.Task(wlm.KIND_IA3, 0, 1.0, [200]),
+             wlm.Task(wlm.KIND_LORA, 40, 1.0, [129]), wlm.Task(wlm.KIND_NONE, 0, 1.0, [77])]
+    wl = wlm.Workload(name="ksplit", layers=[("w", 2048, 768)], tasks=tasks, chunk=64, sigma_w=0.03, sigma_ab=0.05)
+    g, got, ref, errs = run_case(env, wl)
+    y1, dx1 = g.Y.clone(), g.dX.clone()
+    for _ in range(3):
+        g.forward(); g.backward()
+        torch.cuda.synchronize()
+        assert torch.equal(g.Y, y1) and torch.equal(g.dX, dx1)
+
+
 def test_accumulate_and_determinism(env):
     mx, torch = env
     wl = mixed_workload()
