@@ -58,6 +58,18 @@ __global__ __launch_bounds__(256) void k_fill_tasks(const int32_t* __restrict__ 
   }
 }
 
+// A table without rows: every task's gradient is zero.  grid = (tasks, blocks over the largest gradient).
+__global__ __launch_bounds__(256) void k_zero_grads(const DevTask* __restrict__ tasks, int K, int N) {
+  const DevTask tk = tasks[blockIdx.x];
+  const size_t e = (size_t)blockIdx.y * 256 + threadIdx.x;
+  if (tk.kind == MUX_ADAPTER_LORA) {
+    if (tk.dA && e < (size_t)K * tk.rank) tk.dA[e] = 0.f;
+    if (tk.dB && e < (size_t)tk.rank * N) tk.dB[e] = 0.f;
+  } else if (tk.kind == MUX_ADAPTER_IA3_OUT) {
+    if (tk.dL && e < (size_t)N) tk.dL[e] = 0.f;
+  }
+}
+
 namespace {
 
 struct Layout {
@@ -199,6 +211,14 @@ extern "C" mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_s
   fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, dA, dB, dL, stream, nullptr);
   CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP,
             (char*)ws + lo.tasks_bytes + lo.g_bytes, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes, layer->W, stream};
+  if (st->T == 0) {                 // no rows at all: zero gradients (or leave the accumulators as they are)
+    if (!accumulate) {
+      const size_t big = (size_t)(st->r_max > 0 ? st->r_max : 1) * (size_t)(layer->K > layer->N ? layer->K : layer->N);
+      MUX_LAUNCH("zero_grads", k_zero_grads, dim3(st->n_tasks, (unsigned)((big + 255) / 256)), dim3(256), 0, stream, dtasks,
+                 layer->K, layer->N);
+    }
+    return check_hip(fn);
+  }
   const void* H = saved;
   const void* Z = (saved && st->z_rows > 0) ? (const char*)saved + lo.h_bytes : nullptr;
   void* G = (char*)ws + lo.tasks_bytes;

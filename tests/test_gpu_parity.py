@@ -174,3 +174,52 @@ def test_errors_launch_nothing(env):
         mx.mux_lora_forward(g.layer, g.st, g.dtab, None, g.Y, g.saved, g.ws, g.ws_bytes, torch.cuda.current_stream())
     torch.cuda.synchronize()
     assert torch.isnan(g.Y.float()).all()          # nothing was written
+
+
+def test_leading_dimension_packs_and_skipped_outputs(env):
+    """W as a column window of a wider matrix (ldw > N), several packs per task (max_pack_len), dX and some
+    gradients not requested, and an empty table."""
+    mx, torch = env
+    from oracle import segtab
+    tasks = [wlm.Task(wlm.KIND_LORA, 16, 2.0, [40, 50, 30, 90]), wlm.Task(wlm.KIND_IA3, 0, 1.0, [64, 64, 10]),
+             wlm.Task(wlm.KIND_LORA, 24, 1.0, [200])]
+    wl = wlm.Workload(name="ldw", layers=[("w", 512, 384)], tasks=tasks, chunk=32, max_pack_len=100, sigma_w=0.05,
+                      sigma_ab=0.05)
+    ot = segtab.build([t.seq_lens for t in tasks], 32, 100)
+    lt = wlm.layer_tensors(wl, 0, ot.T, seed=4, pad_rows=ot.row_task < 0, pad_fill=1e30)
+    g = hz.GpuLayer(mx, torch, wl, lt, mx.MUX_DT_BF16)
+    assert np.array_equal(mx.mux_segtab_serialize(g.st), ot.image)
+    # re-home W inside a wider buffer and describe it with ldw
+    wide = torch.full((lt.K, 640), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    wide[:, 128:128 + lt.N] = g.W
+    view = wide[:, 128:128 + lt.N]
+    g.layer = mx.LayerDesc(lt.K, lt.N, mx.MUX_DT_BF16, view.data_ptr(), len(tasks), g.A, g.B, g.L, ldw=640)
+    g.forward(); g.backward()
+    got = g.results()
+    ref = hz.oracle_results(wl, lt, ot.row_task)
+    hz.compare(got, ref, hz.TOL_BF16, label="ldw")
+    # dX and task 0's dA not requested: the rest is unchanged, the skipped buffers untouched
+    keep = g.dX.clone(); g.dX.fill_(7.0)
+    dA0 = g.dA[0]; dA0.fill_(5.0)
+    saved_dA = list(g.dA); g.dA = [None] + saved_dA[1:]
+    before = {k: [None if t is None else t.clone() for t in getattr(g, k)] for k in ("dB", "dL")}
+    g.backward(want_dx=False)
+    torch.cuda.synchronize()
+    assert torch.all(g.dX == 7.0) and torch.all(dA0 == 5.0)
+    for k in before:
+        for a, b in zip(before[k], getattr(g, k)):
+            assert a is None or torch.equal(a, b)
+    assert torch.equal(g.dA[2], saved_dA[2])
+    # empty table: both calls return without touching anything
+    st0 = mx.mux_segtab_build([mx.TaskDesc(1, 8, 1.0, [])], 64)
+    A0 = [torch.zeros(lt.K, 8, dtype=torch.bfloat16, device="cuda:0")]
+    B0 = [torch.zeros(8, lt.N, dtype=torch.bfloat16, device="cuda:0")]
+    l0 = mx.LayerDesc(lt.K, lt.N, mx.MUX_DT_BF16, g.W, 1, A0, B0, [None])
+    ws0 = torch.zeros(max(mx.mux_lora_workspace_bytes(l0, st0), 256), dtype=torch.uint8, device="cuda:0")
+    dt0 = torch.zeros(max(mx.mux_segtab_device_bytes(st0), 256), dtype=torch.uint8, device="cuda:0")
+    mx.mux_segtab_upload(st0, dt0, dt0.numel())
+    mx.mux_lora_forward(l0, st0, dt0, keep, keep, ws0, ws0, ws0.numel())
+    dA = [torch.full((lt.K, 8), 3.0, device="cuda:0")]; dB = [torch.full((8, lt.N), 3.0, device="cuda:0")]
+    mx.mux_lora_backward(l0, st0, dt0, keep, keep, ws0, keep, dA, dB, [None], 0, ws0, ws0.numel())
+    torch.cuda.synchronize()
+    assert torch.all(dA[0] == 0) and torch.all(dB[0] == 0)      # a task without tokens has zero gradients
