@@ -24,6 +24,13 @@ _lib = None
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
+        override = os.environ.get("MUX_ORACLE_LIB")      # used only by the test that plants mistakes in a copy
+        if override:
+            _lib = ctypes.CDLL(override)
+            _lib.mux_oracle_forward.restype = ctypes.c_int
+            _lib.mux_oracle_backward.restype = ctypes.c_int
+            _lib.mux_oracle_max_threads.restype = ctypes.c_int
+            return _lib
         if not os.path.exists(LIB_PATH) or os.path.getmtime(LIB_PATH) < os.path.getmtime(
                 os.path.join(os.path.dirname(__file__), "mux_oracle.c")):
             build_oracle()
