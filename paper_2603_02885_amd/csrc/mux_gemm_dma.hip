@@ -27,7 +27,8 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
-constexpr int BM = 256, BN = 256, BK = 32, NST = 4;   // BN = WNW * NI * 32 in both wave layouts
+constexpr int BM = 256, BK = 32, NST = 4;
+constexpr int TILE_N = 256;                     // width of a tile in the launch's tile index space
 constexpr int STAGE_ELEMS = BM * BK;          // 8192 bf16 = 16 KB per operand per stage
 constexpr int TS256 = 2;
 constexpr uint32_t OOB = 0x80000000u;
@@ -42,7 +43,8 @@ struct GemmParams {
   bf16_t* Out;         // [T, Nc]
   bf16_t* Zsave;       // forward: x W of IA3_OUT rows (may be null)
   int Kc, Nc, RP;
-  int n_m, n_n, per_xcd;
+  int n_m, n_n, per_xcd;   // tile grid in units of 256 x TILE_N tiles; workgroups per XCD over the whole grid
+  int n_full;              // workgroups that compute full-width tiles (a multiple of 8); the rest compute halves
   const bf16_t* AinScaled;  // backward: dY * l_t of the IA3_OUT rows, [z_rows, Kc], indexed like the saved x W
 };
 
@@ -50,7 +52,9 @@ struct GemmParams {
 typedef __attribute__((ext_vector_type(4))) int rsrc_t;
 __device__ __forceinline__ rsrc_t make_rsrc(const void* p, uint32_t bytes) {
   const uint64_t a = (uint64_t)p;
-  return (rsrc_t){(int)(uint32_t)a, (int)(uint32_t)(a >> 32), (int)bytes, 0x00020000};
+  // wave-uniform by construction; said explicitly so that the descriptor always lives in scalar registers
+  return (rsrc_t){__builtin_amdgcn_readfirstlane((int)(uint32_t)a), __builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32)),
+                  __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000};
 }
 // One direct-to-LDS load: lane l's 16 bytes from buffer offset byte_off land at lds_dst_uniform + 16*l.
 // Written as inline assembly on purpose: the wait counts of these loads are managed by hand (vmcnt) around
@@ -75,27 +79,37 @@ __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F
 // swizzle of the 16-byte piece index inside a 64-byte row of a [rows][32] tile
 __device__ __forceinline__ int swz_row(int r) { return (((r >> 1) ^ (r >> 3)) & 1) | (((r >> 2) & 1) << 1); }
 
-// WNW = waves along N (2: four waves of 128x128, 4: eight waves of 128x64, two per SIMD), NI = 32-column MFMA
-// tiles per wave.
+// The four A stages, the four B stages and the per-row validity flags of one workgroup.
+struct Smem {
+  bf16_t *a0, *a1, *a2, *a3, *b0, *b1, *b2, *b3;
+  int* row;
+};
+
+// One output tile.  WNW = waves along N, NI = 32-column MFMA tiles per wave; eight waves (two per SIMD) on a
+// 256 x BN tile with BN = WNW*NI*32:
+//   <4,2> 128x64 per wave, the full 256x256 tile;
+//   <4,1> 128x32 per wave, a 256x128 half of a tile: for what is left after the last full round of workgroups.
+// `xcd_slot` = (per-XCD tile slot) * 8 + XCD; `half` selects the 128 columns of a half-width tile.
 template <bool NT, int WNW, int NI>
-__global__ __launch_bounds__(128 * WNW, 1) void k_gemm_dma(const GemmParams p) {
-  static_assert(WNW * NI * 32 == BN, "wave layout must cover the tile");
+__device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slot, const int half, const Smem sm) {
+  constexpr int BN = WNW * NI * 32;
+  static_assert(BN == 256 || BN == 128, "tile width");
   constexpr int NW = 2 * WNW, NTHR = 64 * NW;
-  constexpr int ACH = 16 / NW, BCH = 16 / NW;     // 1 KB chunks of the A / B tile each wave fetches per K-tile
+  static_assert(NTHR == 512, "launched with eight waves");
+  constexpr int ACH = 16 / NW, BCH = (BN / 16) / NW;   // 1 KB chunks of the A / B tile each wave fetches per K-tile
+  static_assert(ACH >= 1 && BCH >= 1, "every wave fetches at least one chunk of each tile");
+  constexpr int PPRB = BN / 8;                    // forward: 16-byte pieces per k-row of the [32][BN] tile
+  constexpr int RPCB = 64 / PPRB;                 // forward: k-rows per 1 KB chunk
   constexpr int WCOLS = NI * 32;                  // columns of the wave tile
   constexpr int EPW = WCOLS + 8;                  // epilogue staging pitch (elements)
-  __shared__ __attribute__((aligned(1024))) bf16_t sA0[STAGE_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sA1[STAGE_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sA2[STAGE_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sA3[STAGE_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sB0[STAGE_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sB1[STAGE_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sB2[STAGE_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sB3[STAGE_ELEMS];
-  __shared__ int sRow[256];
+  bf16_t* const sA0 = sm.a0; bf16_t* const sA1 = sm.a1; bf16_t* const sA2 = sm.a2; bf16_t* const sA3 = sm.a3;
+  bf16_t* const sB0 = sm.b0; bf16_t* const sB1 = sm.b1; bf16_t* const sB2 = sm.b2; bf16_t* const sB3 = sm.b3;
+  int* const sRow = sm.row;
 
   const int total = p.n_m * p.n_n;
-  const int L = (blockIdx.x & 7) * p.per_xcd + (blockIdx.x >> 3);
+  const int jslot = xcd_slot >> 3;
+  if (jslot >= p.per_xcd) return;
+  const int L = (xcd_slot & 7) * p.per_xcd + jslot;
   if (L >= total) return;
   constexpr int GROUP = 4;
   const int width = GROUP * p.n_n;
@@ -105,7 +119,7 @@ __global__ __launch_bounds__(128 * WNW, 1) void k_gemm_dma(const GemmParams p) {
   const int tn = (L % width) / gsize;
 
   const ItemView it = load_item(p.dtab, TS256, tm);
-  const int c0 = tn * BN;
+  const int c0 = tn * TILE_N + half * BN;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WNW, wn = wave % WNW;
@@ -146,20 +160,22 @@ __global__ __launch_bounds__(128 * WNW, 1) void k_gemm_dma(const GemmParams p) {
 
   const int a_row = wave * (16 * ACH) + r_in;                   // + 16 q
   // forward W tile: k-row = 8 wave + 2 q + lane/32, physical piece lane%32 -> logical n
-  const int nk_in = lane >> 5;
-  const int n_pp = lane & 31;
+  const int nk_in = lane / PPRB;
+  const int n_pp = lane % PPRB;
+  const int b_row = wave * (16 * BCH) + r_in;                   // backward: row of W inside the tile, + 16 q
 
   // Per-thread byte offsets of the 4 + 4 pieces this lane fetches per tile, without the K-tile term.
   // A piece that must read as zero is parked out of range.
   uint32_t offA[ACH], offB[BCH];
 #pragma unroll
-  for (int q = 0; q < ACH; ++q) {
-    const int row = a_row + 16 * q;
-    offA[q] = ((uint32_t)row * (uint32_t)p.Kc + (uint32_t)(r_piece * 8)) * 2u;
+  for (int q = 0; q < ACH; ++q)
+    offA[q] = ((uint32_t)(a_row + 16 * q) * (uint32_t)p.Kc + (uint32_t)(r_piece * 8)) * 2u;
+#pragma unroll
+  for (int q = 0; q < BCH; ++q) {
     if (NT) {
-      offB[q] = (uint32_t)(((size_t)(c0 + row) * p.ldw + r_piece * 8) * 2);
+      offB[q] = (uint32_t)(((size_t)(c0 + b_row + 16 * q) * p.ldw + r_piece * 8) * 2);
     } else {
-      const int kk = wave * (2 * BCH) + 2 * q + nk_in;       // k-row inside the tile
+      const int kk = (wave * BCH + q) * RPCB + nk_in;        // k-row inside the tile
       const int seg = (n_pp >> 1) ^ ((kk & 3) << 1);         // logical 32-byte segment
       const int n = seg * 16 + (n_pp & 1) * 8;
       offB[q] = (c0 + n < p.Nc) ? (uint32_t)(((size_t)kk * p.ldw + c0 + n) * 2) : OOB;
@@ -180,16 +196,17 @@ __global__ __launch_bounds__(128 * WNW, 1) void k_gemm_dma(const GemmParams p) {
       } else {
         const int j0 = (next_tile - KT) * BK;                 // first contraction index of this adapter tile
         curA = rE; curB = rP; kA = 0; kB = 0; stepA = 0; stepB = 0;
+        const int j = j0 + r_piece * 8;
 #pragma unroll
-        for (int q = 0; q < ACH; ++q) {
-          const int row = a_row + 16 * q;
-          const int j = j0 + r_piece * 8;
-          offA[q] = (j < p.RP) ? ((uint32_t)row * (uint32_t)p.RP + (uint32_t)j) * 2u : OOB;
+        for (int q = 0; q < ACH; ++q)
+          offA[q] = (j < p.RP) ? ((uint32_t)(a_row + 16 * q) * (uint32_t)p.RP + (uint32_t)j) * 2u : OOB;
+#pragma unroll
+        for (int q = 0; q < BCH; ++q) {
           if (NT) {
-            const int c = c0 + row;
+            const int c = c0 + b_row + 16 * q;
             offB[q] = (c < p.Nc && j < rank) ? (uint32_t)(((size_t)c * rank + j) * 2) : OOB;
           } else {
-            const int kk = wave * (2 * BCH) + 2 * q + nk_in;
+            const int kk = (wave * BCH + q) * RPCB + nk_in;
             const int seg = (n_pp >> 1) ^ ((kk & 3) << 1);
             const int n = seg * 16 + (n_pp & 1) * 8;
             offB[q] = (c0 + n < p.Nc && j0 + kk < rank) ? (uint32_t)(((size_t)(j0 + kk) * p.Nc + c0 + n) * 2) : OOB;
@@ -198,11 +215,10 @@ __global__ __launch_bounds__(128 * WNW, 1) void k_gemm_dma(const GemmParams p) {
       }
     }
   };
-  // one load of the tile being fetched: i = 0 .. ACH+BCH-1, A and B pieces alternating
+  // one load of the tile being fetched: i = 0 .. ACH+BCH-1, the A pieces first
   auto issue_one = [&](bf16_t* dA, bf16_t* dB, int i) {
-    const int q = i >> 1;
-    if ((i & 1) == 0) dma16(curA, dA + (wave * ACH + q) * 512, offA[q] + kA);
-    else dma16(curB, dB + (wave * BCH + q) * 512, offB[q] + kB);
+    if (i < ACH) dma16(curA, dA + (wave * ACH + i) * 512, offA[i] + kA);
+    else dma16(curB, dB + (wave * BCH + (i - ACH)) * 512, offB[i - ACH] + kB);
   };
   auto issue_done = [&]() { kA += stepA; kB += stepB; ++next_tile; };
   auto issue = [&](bf16_t* dA, bf16_t* dB) {
@@ -254,12 +270,12 @@ __global__ __launch_bounds__(128 * WNW, 1) void k_gemm_dma(const GemmParams p) {
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ni], a[mi], acc[mi][ni], 0, 0, 0);
   };
 
   auto mma_one = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[NI], int m) {
     const int mi = m / NI, ni = m % NI;
-    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ni], a[mi], acc[mi][ni], 0, 0, 0);
   };
 
   auto stA = [&](int s) -> bf16_t* { return s == 0 ? sA0 : (s == 1 ? sA1 : (s == 2 ? sA2 : sA3)); };
@@ -296,7 +312,9 @@ __global__ __launch_bounds__(128 * WNW, 1) void k_gemm_dma(const GemmParams p) {
         for (int i = 0; i < 2 * NI; ++i) {
           mma_one(a0, b0, 2 * i);
           mma_one(a0, b0, 2 * i + 1);
-          if (i < ACH + BCH) issue_one(stA((u + 3) & 3), stB((u + 3) & 3), i);
+#pragma unroll
+          for (int d = (i * (ACH + BCH)) / (2 * NI); d < ((i + 1) * (ACH + BCH)) / (2 * NI); ++d)
+            issue_one(stA((u + 3) & 3), stB((u + 3) & 3), d);
           __builtin_amdgcn_sched_barrier(0);
         }
         issue_done();
@@ -315,34 +333,52 @@ __global__ __launch_bounds__(128 * WNW, 1) void k_gemm_dma(const GemmParams p) {
       }
     }
   }
+  // the refills issued past the last tile (zeros) must have landed before the stages are reused below
+  wait_vmcnt<0>();
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 
-  // ---- epilogue: aggregate, mask, store; 32 rows of the wave tile at a time through this wave's own array
+  // ---- epilogue: aggregate, mask, store; 32 rows of the wave tile at a time through this wave's own array.
+  // The MFMAs were issued with the operands exchanged, so acc[mi][ni] holds the transposed 32x32 block:
+  // this lane has row 32 mi + li and the four consecutive columns 32 ni + 8 j + 4 lg .. + 3 in registers 4j .. 4j+3.
   bf16_t* stage = wave < 4 ? stA(wave) : stB(wave - 4);
-  float lcol[NI];
-#pragma unroll
-  for (int ni = 0; ni < NI; ++ni) {
-    const int c = c0 + wn * WCOLS + ni * 32 + li;
-    lcol[ni] = (!NT && ia3 && c < p.Nc) ? bf16_to_f32(Lvec[c]) : 1.f;
-  }
   constexpr int PPR = WCOLS / 8;                 // 16-byte pieces per staged row
   constexpr int RPI = 64 / PPR;                  // rows one wave instruction moves
   const int e_row = lane / PPR, e_pc = (lane % PPR) * 8;
-  const int passes = (!NT && ia3 && p.Zsave) ? 2 : 1;     // IA3 forward also saves x W before the scale
+  const bool scale_out = !NT && ia3;             // IA3 forward: Z = x W is saved first, then Y = Z * l_t
+  const int passes = (scale_out && p.Zsave) ? 2 : 1;
   for (int pass = 0; pass < passes; ++pass) {
-    const bool to_z = passes == 2 && pass == 0;
+    const bool to_z = pass + 1 < passes;
     bf16_t* dst = to_z ? p.Zsave + (size_t)(tk.zrow0 - tk.row_begin) * p.Nc : p.Out;
+    if (scale_out && !to_z) {
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int c = c0 + wn * WCOLS + ni * 32 + 8 * j + 4 * lg;
+          const bool in = c < p.Nc;                           // Nc is a multiple of 8: the four columns together
+          const float l0 = in ? bf16_to_f32(Lvec[c]) : 0.f, l1 = in ? bf16_to_f32(Lvec[c + 1]) : 0.f;
+          const float l2 = in ? bf16_to_f32(Lvec[c + 2]) : 0.f, l3 = in ? bf16_to_f32(Lvec[c + 3]) : 0.f;
+#pragma unroll
+          for (int mi = 0; mi < 4; ++mi) {
+            acc[mi][ni][4 * j + 0] *= l0;
+            acc[mi][ni][4 * j + 1] *= l1;
+            acc[mi][ni][4 * j + 2] *= l2;
+            acc[mi][ni][4 * j + 3] *= l3;
+          }
+        }
+    }
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = 8 * (v >> 2) + 4 * lg + (v & 3);
-          const float y = to_z ? acc[mi][ni][v] : acc[mi][ni][v] * lcol[ni];
-          stage[m * EPW + ni * 32 + li] = f32_to_bf16(y);
+        for (int j = 0; j < 4; ++j) {
+          uint2 v;
+          v.x = pack_bf16x2(acc[mi][ni][4 * j + 0], acc[mi][ni][4 * j + 1]);
+          v.y = pack_bf16x2(acc[mi][ni][4 * j + 2], acc[mi][ni][4 * j + 3]);
+          *(uint2*)(stage + li * EPW + ni * 32 + 8 * j + 4 * lg) = v;
         }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
@@ -363,18 +399,65 @@ __global__ __launch_bounds__(128 * WNW, 1) void k_gemm_dma(const GemmParams p) {
   }
 }
 
-template <bool NT, int WNW, int NI>
+// Workgroups 0 .. n_full-1 compute full tiles, slot by slot with the XCD in the low three bits of the index (the
+// hardware deals consecutive workgroups round-robin to the eight XCDs, so one XCD's L2 sees neighbouring tiles).
+// The workgroups after them compute the remaining tiles as two half-width tiles each; both halves of a tile
+// run on the same XCD.  The dispatcher hands out workgroups in index order, so the halves start as the compute
+// units finish their last full tile.
+template <bool NT>
+__global__ __launch_bounds__(512, 1) void k_gemm_dma(const GemmParams p) {
+  __shared__ __attribute__((aligned(1024))) bf16_t sA0[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sA1[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sA2[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sA3[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sB0[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sB1[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sB2[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sB3[STAGE_ELEMS];
+  __shared__ int sRow[256];
+  const Smem sm = {sA0, sA1, sA2, sA3, sB0, sB1, sB2, sB3, sRow};
+  const int b = blockIdx.x;
+  if (b < p.n_full) {
+    gemm_tile<NT, 4, 2>(p, b, 0, sm);
+  } else {
+    const int t = b - p.n_full;                                       // n_full is a multiple of 8
+    gemm_tile<NT, 4, 1>(p, p.n_full + (((t >> 4) << 3) | (t & 7)), (t >> 3) & 1, sm);
+  }
+}
+
+// Number of compute units, asked once.
+int compute_units() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) n = v;
+    else n = 256;
+  }
+  return n;
+}
+
+template <bool NT>
 mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t* Out, bf16_t* Zsave, int Kc, int Nc) {
   GemmParams p;
   p.dtab = c.dtab; p.tasks = c.dtasks; p.Ain = Ain; p.W = (const bf16_t*)c.W; p.ldw = c.ldw; p.Ext = Ext; p.Out = Out;
   p.Zsave = Zsave; p.Kc = Kc; p.Nc = Nc; p.RP = c.RP;
   p.n_m = (int)c.st->items[TS256].size();
-  p.n_n = (Nc + BN - 1) / BN;
+  p.n_n = (Nc + TILE_N - 1) / TILE_N;
   p.AinScaled = (const bf16_t*)c.dYs;
   const int total = p.n_m * p.n_n;
   if (total == 0) return MUX_OK;
   p.per_xcd = (total + 7) / 8;
-  MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", (k_gemm_dma<NT, WNW, NI>), dim3(p.per_xcd * 8), dim3(128 * WNW), 0, c.stream, p);
+  // One workgroup per compute unit at a time: the tiles left after the last full round would keep a fraction of
+  // the units busy for a whole tile time.  When they fit twice, they run as half-width tiles.
+  static const bool no_halves = getenv("MUX_GEMM_NO_HALF_TILES") != nullptr;
+  const int ncu = compute_units();
+  const int full_slots = (total / ncu) * (ncu / 8);          // per-XCD slots covered by whole rounds
+  const int rem = total - full_slots * 8;
+  int tail_slots = 0;
+  if (!no_halves && ncu % 8 == 0 && rem > 0 && 2 * rem <= ncu) tail_slots = p.per_xcd - full_slots;
+  p.n_full = 8 * (p.per_xcd - tail_slots);
+  const int grid = p.n_full + 16 * tail_slots;
+  MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", (k_gemm_dma<NT>), dim3(grid), dim3(512), 0, c.stream, p);
   return MUX_OK;
 }
 
@@ -391,16 +474,12 @@ bool gemm_dma_supported(const CallCtx& c, bool backward) {
   return true;
 }
 
-static bool eight_waves() { static const bool v = getenv("MUX_GEMM_4WAVES") == nullptr; return v; }
-
 mux_status gemm_dma_forward(const CallCtx& c, const void* X, const void* Hs, void* Y, void* Z) {
-  if (eight_waves()) return launch<false, 4, 2>(c, (const bf16_t*)X, (const bf16_t*)Hs, (bf16_t*)Y, (bf16_t*)Z, c.K, c.N);
-  return launch<false, 2, 4>(c, (const bf16_t*)X, (const bf16_t*)Hs, (bf16_t*)Y, (bf16_t*)Z, c.K, c.N);
+  return launch<false>(c, (const bf16_t*)X, (const bf16_t*)Hs, (bf16_t*)Y, (bf16_t*)Z, c.K, c.N);
 }
 
 mux_status gemm_dma_backward(const CallCtx& c, const void* dY, const void* Gs, void* dX) {
-  if (eight_waves()) return launch<true, 4, 2>(c, (const bf16_t*)dY, (const bf16_t*)Gs, (bf16_t*)dX, nullptr, c.N, c.K);
-  return launch<true, 2, 4>(c, (const bf16_t*)dY, (const bf16_t*)Gs, (bf16_t*)dX, nullptr, c.N, c.K);
+  return launch<true>(c, (const bf16_t*)dY, (const bf16_t*)Gs, (bf16_t*)dX, nullptr, c.N, c.K);
 }
 
 }  // namespace mux
