@@ -1,17 +1,22 @@
 // Backbone GEMM, pipelined version: global -> LDS by direct buffer loads (no register staging),
-// four LDS stages of BK = 32, operand reads software-pipelined one MFMA step ahead.
+// operand reads software-pipelined one MFMA step ahead.
 //
 //   forward  (NN):  Y[T,N]  = mask * ( X[T,K] W[K,N]      + Hs[T,r] B_t[r,N] )      Eq. 1 + LoRA + Add
 //   backward (NT):  dX[T,K] = mask * ( dY[T,N] W[K,N]^T   + Gs[T,r] A_t[K,r]^T )    Eq. 2 + LoRA
 //
-// Same tiling as the register-staged kernel (256x256 per workgroup, 128x128 per wave, 4x4
-// v_mfma_f32_32x32x16_bf16), but:
+// 256x256 output tile per workgroup of eight waves (two per SIMD), 128x64 per wave as 4x2
+// v_mfma_f32_32x32x16_bf16.
 //   * `buffer_load_dwordx4 ... lds` writes each lane's 16 bytes at LDS base + 16*lane, so a wave
-//     instruction fills 1 KB of a stage; loads for tile kt+3 are issued while tile kt is computed
-//     (three tiles in flight).  A masked piece gets an out-of-range offset and lands as zeros.
-//   * LDS rows cannot be padded under that rule, so 16-byte pieces are XOR-swizzled instead:
-//     [rows][32] tiles by row bits, the forward's [32][256] tile of W by k bits.
-//   * one workgroup barrier per K-tile, placed between the two MFMA steps: by then every read of
+//     instruction fills 1 KB of a stage.  A masked piece gets an out-of-range offset and lands as zeros.
+//   * K-tiles are 64 deep whenever the contraction length allows: a row of a [rows][64] tile is one whole
+//     128-byte line of X, dY or W.  Measured on this part, the L2 -> LDS path moves half-lines (the 64-byte rows
+//     of a 32-deep tile) at half the rate of whole lines, at every level of the hierarchy, and that rate, not the
+//     matrix cores, was the limit of the 32-deep version.  Two stages of 64 KB; the loads of tile kt+2 go out
+//     right after the barrier that frees the stage of tile kt.  The 32-deep version (four stages, three tiles
+//     in flight) remains for contraction lengths that are multiples of 32 only.
+//   * LDS rows cannot be padded under the DMA rule, so 16-byte pieces are XOR-swizzled instead:
+//     [rows][BK] tiles by row bits, the forward's [BK][256] tile of W by k bits.
+//   * one workgroup barrier per K-tile, placed before the last MFMA step: by then every read of
 //     the current stage is done (it may be refilled) and the next tile has landed (it may be read).
 // Every stage is its own __shared__ array so that the compiler's wait-count insertion can tell
 // the stage being filled from the stage being read.
@@ -27,9 +32,8 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
-constexpr int BM = 256, BK = 32, NST = 4;
+constexpr int BM = 256;
 constexpr int TILE_N = 256;                     // width of a tile in the launch's tile index space
-constexpr int STAGE_ELEMS = BM * BK;          // 8192 bf16 = 16 KB per operand per stage
 constexpr int TS256 = 2;
 constexpr uint32_t OOB = 0x80000000u;
 
@@ -76,10 +80,15 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
-// swizzle of the 16-byte piece index inside a 64-byte row of a [rows][32] tile
-__device__ __forceinline__ int swz_row(int r) { return (((r >> 1) ^ (r >> 3)) & 1) | (((r >> 2) & 1) << 1); }
+// Swizzle of the 16-byte piece index inside a row of a [rows][BK] tile: sixteen consecutive rows read the same
+// logical piece with one ds_read_b128 and must land in sixteen different 16-byte bank groups.
+template <int BK>
+__device__ __forceinline__ int swz_row(int r) {
+  if (BK == 32) return (((r >> 1) ^ (r >> 3)) & 1) | (((r >> 2) & 1) << 1);   // 64-byte rows: 4 pieces
+  return (r >> 1) & 7;                                                          // 128-byte rows: 8 pieces
+}
 
-// The four A stages, the four B stages and the per-row validity flags of one workgroup.
+// Up to four A stages, four B stages and the per-row validity flags of one workgroup.
 struct Smem {
   bf16_t *a0, *a1, *a2, *a3, *b0, *b1, *b2, *b3;
   int* row;
@@ -89,16 +98,21 @@ struct Smem {
 // 256 x BN tile with BN = WNW*NI*32:
 //   <4,2> 128x64 per wave, the full 256x256 tile;
 //   <4,1> 128x32 per wave, a 256x128 half of a tile: for what is left after the last full round of workgroups.
+// BK = 64 with two stages, or BK = 32 with four.
 // `xcd_slot` = (per-XCD tile slot) * 8 + XCD; `half` selects the 128 columns of a half-width tile.
-template <bool NT, int WNW, int NI>
+template <bool NT, int WNW, int NI, int BK>
 __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slot, const int half, const Smem sm) {
   constexpr int BN = WNW * NI * 32;
   static_assert(BN == 256 || BN == 128, "tile width");
+  static_assert(BK == 32 || BK == 64, "K-tile depth");
+  constexpr int NST = BK == 64 ? 2 : 4;           // LDS stages
   constexpr int NW = 2 * WNW, NTHR = 64 * NW;
-  static_assert(NTHR == 512, "launched with eight waves");
-  constexpr int ACH = 16 / NW, BCH = (BN / 16) / NW;   // 1 KB chunks of the A / B tile each wave fetches per K-tile
+  constexpr int A_ELEMS = BM * BK;                // elements of one A stage
+  constexpr int ACH = (A_ELEMS / 512) / NW, BCH = (BN * BK / 512) / NW;   // 1 KB chunks each wave fetches per K-tile
   static_assert(ACH >= 1 && BCH >= 1, "every wave fetches at least one chunk of each tile");
-  constexpr int PPRB = BN / 8;                    // forward: 16-byte pieces per k-row of the [32][BN] tile
+  constexpr int LPR = BK / 8;                     // [rows][BK] tiles: lanes (16-byte pieces) per row
+  constexpr int RPC = 64 / LPR;                   //                   rows per 1 KB chunk
+  constexpr int PPRB = BN / 8;                    // forward: 16-byte pieces per k-row of the [BK][BN] tile
   constexpr int RPCB = 64 / PPRB;                 // forward: k-rows per 1 KB chunk
   constexpr int WCOLS = NI * 32;                  // columns of the wave tile
   constexpr int EPW = WCOLS + 8;                  // epilogue staging pitch (elements)
@@ -141,15 +155,14 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   const bf16_t* adapterB = NT ? (const bf16_t*)tk.A : (const bf16_t*)tk.B;
   const bf16_t* Lvec = (const bf16_t*)tk.L;
 
-  const int KT = (p.Kc + BK - 1) / BK;
+  const int KT = p.Kc / BK;                         // the contraction length is a multiple of BK
   const int KT_ext = lora ? (rank + BK - 1) / BK : 0;
   const int KT_total = KT + KT_ext;
 
-  // ---- DMA geometry.  A wave instruction fills 1 KB: 16 rows x 64 B of a [rows][32] tile
-  // (lane -> row lane/4, physical piece lane%4), or 2 k-rows x 512 B of the [32][256] tile
-  // (lane -> k-row lane/32, physical piece lane%32).  Wave w owns chunks 4w .. 4w+3 of each tile.
-  const int r_in = lane >> 2;                                   // row inside the 16-row chunk
-  const int r_piece = (lane & 3) ^ swz_row(r_in);               // logical k-piece this lane fetches
+  // ---- DMA geometry.  A wave instruction fills 1 KB: RPC rows x 2 BK bytes of a [rows][BK] tile
+  // (lane -> row lane/LPR, physical piece lane%LPR), or RPCB k-rows of the forward's [BK][BN] tile of W
+  // (lane -> k-row lane/PPRB, physical piece lane%PPRB).  Wave w owns chunks w*ACH .. of A and w*BCH .. of B.
+  const int r_in = lane / LPR;                                  // row inside the chunk
   const uint32_t a_rows_bytes = (uint32_t)it.nrows * (uint32_t)p.Kc * 2u;
   const bf16_t* a_base = (NT && ia3) ? p.AinScaled + (size_t)(tk.zrow0 + it.row0 - tk.row_begin) * p.Kc
                                      : p.Ain + (size_t)it.row0 * p.Kc;
@@ -158,22 +171,24 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   const rsrc_t rE = make_rsrc(lora ? p.Ext + (size_t)it.row0 * p.RP : p.Ain, lora ? (uint32_t)it.nrows * (uint32_t)p.RP * 2u : 0u);
   const rsrc_t rP = make_rsrc(lora ? adapterB : p.Ain, lora ? (uint32_t)(NT ? (size_t)p.Nc * rank : (size_t)rank * p.Nc) * 2u : 0u);
 
-  const int a_row = wave * (16 * ACH) + r_in;                   // + 16 q
-  // forward W tile: k-row = 8 wave + 2 q + lane/32, physical piece lane%32 -> logical n
+  // row of the [rows][BK] tile chunk q of this wave puts this lane on, and the logical k-piece it fetches there
+  auto a_row_of = [&](int q) { return wave * (RPC * ACH) + RPC * q + r_in; };
+  auto b_row_of = [&](int q) { return wave * (RPC * BCH) + RPC * q + r_in; };   // backward: row of W inside the tile
+  auto piece_of = [&](int row) { return (lane % LPR) ^ swz_row<BK>(row); };
+  // forward W tile: k-row = (wave*BCH + q)*RPCB + lane/PPRB, physical piece lane%PPRB -> logical n
   const int nk_in = lane / PPRB;
   const int n_pp = lane % PPRB;
-  const int b_row = wave * (16 * BCH) + r_in;                   // backward: row of W inside the tile, + 16 q
 
-  // Per-thread byte offsets of the 4 + 4 pieces this lane fetches per tile, without the K-tile term.
+  // Per-thread byte offsets of the pieces this lane fetches per tile, without the K-tile term.
   // A piece that must read as zero is parked out of range.
   uint32_t offA[ACH], offB[BCH];
 #pragma unroll
   for (int q = 0; q < ACH; ++q)
-    offA[q] = ((uint32_t)(a_row + 16 * q) * (uint32_t)p.Kc + (uint32_t)(r_piece * 8)) * 2u;
+    offA[q] = ((uint32_t)a_row_of(q) * (uint32_t)p.Kc + (uint32_t)(piece_of(a_row_of(q)) * 8)) * 2u;
 #pragma unroll
   for (int q = 0; q < BCH; ++q) {
     if (NT) {
-      offB[q] = (uint32_t)(((size_t)(c0 + b_row + 16 * q) * p.ldw + r_piece * 8) * 2);
+      offB[q] = (uint32_t)(((size_t)(c0 + b_row_of(q)) * p.ldw + piece_of(b_row_of(q)) * 8) * 2);
     } else {
       const int kk = (wave * BCH + q) * RPCB + nk_in;        // k-row inside the tile
       const int seg = (n_pp >> 1) ^ ((kk & 3) << 1);         // logical 32-byte segment
@@ -196,14 +211,16 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
       } else {
         const int j0 = (next_tile - KT) * BK;                 // first contraction index of this adapter tile
         curA = rE; curB = rP; kA = 0; kB = 0; stepA = 0; stepB = 0;
-        const int j = j0 + r_piece * 8;
 #pragma unroll
-        for (int q = 0; q < ACH; ++q)
-          offA[q] = (j < p.RP) ? ((uint32_t)(a_row + 16 * q) * (uint32_t)p.RP + (uint32_t)j) * 2u : OOB;
+        for (int q = 0; q < ACH; ++q) {
+          const int j = j0 + piece_of(a_row_of(q)) * 8;
+          offA[q] = (j < p.RP) ? ((uint32_t)a_row_of(q) * (uint32_t)p.RP + (uint32_t)j) * 2u : OOB;
+        }
 #pragma unroll
         for (int q = 0; q < BCH; ++q) {
           if (NT) {
-            const int c = c0 + b_row + 16 * q;
+            const int c = c0 + b_row_of(q);
+            const int j = j0 + piece_of(b_row_of(q)) * 8;
             offB[q] = (c < p.Nc && j < rank) ? (uint32_t)(((size_t)c * rank + j) * 2) : OOB;
           } else {
             const int kk = (wave * BCH + q) * RPCB + nk_in;
@@ -230,8 +247,8 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   // ---- operand read geometry
   const int li = lane & 31, lg = lane >> 5;
   const int l16 = lane & 15, lhalf = (lane >> 4) & 1;
-  // [rows][32] tiles: row = (wm|wn)*128 + t*32 + li; logical piece 2*ks + lg
-  const int swz = swz_row(li);
+  // [rows][BK] tiles: row = (wm|wn)*128 + t*32 + li; logical piece 2*ks + lg (the swizzle depends on li only)
+  const int swz = swz_row<BK>(li);
   const int a_rd = (wm * 128 + li) * BK;        // elements; + t*32*BK + ((2ks+lg)^swz)*8
   const int bt_rd = (wn * WCOLS + li) * BK;
   // forward W tile: k = ks*16 + 8 lg + 4 h + l16/4 ; logical seg = wn*8 + 2 t + lhalf ; + 4*(l16%4) elements
@@ -257,6 +274,9 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
     }
   };
 
+  // Accumulators.  The MFMAs are issued with the operands exchanged, so acc[mi][ni] holds the transposed 32x32
+  // block: this lane has row 32 mi + li and the four consecutive columns 32 ni + 8 j + 4 lg .. + 3 in registers
+  // 4j .. 4j+3, which the epilogue packs into one 8-byte LDS store.
   f32x16 acc[4][NI];
 #pragma unroll
   for (int mi = 0; mi < 4; ++mi)
@@ -277,59 +297,101 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
     const int mi = m / NI, ni = m % NI;
     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ni], a[mi], acc[mi][ni], 0, 0, 0);
   };
+  // one MFMA step with the loads of one tile (all ACH+BCH of them) spread between its MFMA pairs
+  auto mma_with_loads = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[NI], bf16_t* dA, bf16_t* dB) {
+#pragma unroll
+    for (int i = 0; i < 2 * NI; ++i) {
+      mma_one(a, b, 2 * i);
+      mma_one(a, b, 2 * i + 1);
+#pragma unroll
+      for (int d = (i * (ACH + BCH)) / (2 * NI); d < ((i + 1) * (ACH + BCH)) / (2 * NI); ++d) issue_one(dA, dB, d);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
 
   auto stA = [&](int s) -> bf16_t* { return s == 0 ? sA0 : (s == 1 ? sA1 : (s == 2 ? sA2 : sA3)); };
   auto stB = [&](int s) -> bf16_t* { return s == 0 ? sB0 : (s == 1 ? sB1 : (s == 2 ? sB2 : sB3)); };
+  auto tile_barrier = [&]() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
 
-  // ---- prologue: tiles 0, 1, 2 in flight; tile 0 landed and visible; its first operands in registers
-  prepare(); issue(sA0, sB0);
-  prepare(); issue(sA1, sB1);
-  prepare(); issue(sA2, sB2);
-  wait_vmcnt<2 * (ACH + BCH)>();
+  // ---- prologue: tiles 0 .. NST-2 in flight; tile 0 landed and visible; its first operands in registers
+#pragma unroll
+  for (int s0 = 0; s0 < (NST == 2 ? 2 : NST - 1); ++s0) { prepare(); issue(stA(s0), stB(s0)); }
+  wait_vmcnt<(NST == 2 ? 1 : NST - 2) * (ACH + BCH)>();
   wait_lgkm0();
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
+  tile_barrier();
 
   bf16x8 a0[4], b0[NI], a1[4], b1[NI];
   read_ops(sA0, sB0, 0, a0, b0);
 
-  for (int kt4 = 0; kt4 < KT_total; kt4 += NST) {
+  if (BK == 64) {
+    // Two stages.  Steps 0..2 run from registers read one step ahead; before the last step every wave has read
+    // all of this stage and tile kt+1 has landed (the only loads in flight): barrier; then, under the last
+    // step's MFMAs, the first operands of tile kt+1 are read and all loads of tile kt+2 are issued into the
+    // stage just freed.
+    for (int kt2 = 0; kt2 < KT_total; kt2 += 2) {
 #pragma unroll
-    for (int u = 0; u < NST; ++u) {
-      const int kt = kt4 + u;
-      if (kt < KT_total) {
-        bf16_t* cA = stA(u);
-        bf16_t* cB = stB(u);
-        prepare();
-        __builtin_amdgcn_sched_barrier(0);
-        // first MFMA step.  The operand reads of the second step go out first (their latency hides under the
-        // MFMAs); the refill of the stage computed from in the previous iteration with tile kt+3 (past the last
-        // tile: zeros nobody reads) is spread between the MFMA pairs.
-        read_ops(cA, cB, 1, a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
+      for (int u = 0; u < 2; ++u) {
+        const int kt = kt2 + u;
+        if (kt < KT_total) {
+          bf16_t* cA = stA(u);
+          bf16_t* cB = stB(u);
+          prepare();
+          __builtin_amdgcn_sched_barrier(0);
+          read_ops(cA, cB, 1, a1, b1);
+          __builtin_amdgcn_sched_barrier(0);
+          mma(a0, b0);
+          __builtin_amdgcn_sched_barrier(0);
+          read_ops(cA, cB, 2, a0, b0);
+          __builtin_amdgcn_sched_barrier(0);
+          mma(a1, b1);
+          __builtin_amdgcn_sched_barrier(0);
+          read_ops(cA, cB, 3, a1, b1);
+          __builtin_amdgcn_sched_barrier(0);
+          mma(a0, b0);
+          __builtin_amdgcn_sched_barrier(0);
+          wait_vmcnt<0>();
+          wait_lgkm0();
+          tile_barrier();
+          __builtin_amdgcn_sched_barrier(0);
+          if (kt + 1 < KT_total) read_ops(stA(u ^ 1), stB(u ^ 1), 0, a0, b0);
+          __builtin_amdgcn_sched_barrier(0);
+          mma_with_loads(a1, b1, cA, cB);
+          issue_done();
+        }
+      }
+    }
+  } else {
+    for (int kt4 = 0; kt4 < KT_total; kt4 += NST) {
 #pragma unroll
-        for (int i = 0; i < 2 * NI; ++i) {
-          mma_one(a0, b0, 2 * i);
-          mma_one(a0, b0, 2 * i + 1);
-#pragma unroll
-          for (int d = (i * (ACH + BCH)) / (2 * NI); d < ((i + 1) * (ACH + BCH)) / (2 * NI); ++d)
-            issue_one(stA((u + 3) & 3), stB((u + 3) & 3), d);
+      for (int u = 0; u < NST; ++u) {
+        const int kt = kt4 + u;
+        if (kt < KT_total) {
+          bf16_t* cA = stA(u);
+          bf16_t* cB = stB(u);
+          prepare();
+          __builtin_amdgcn_sched_barrier(0);
+          // first MFMA step.  The operand reads of the second step go out first (their latency hides under the
+          // MFMAs); the refill of the stage computed from in the previous iteration with tile kt+3 (past the last
+          // tile: zeros nobody reads) is spread between the MFMA pairs.
+          read_ops(cA, cB, 1, a1, b1);
+          __builtin_amdgcn_sched_barrier(0);
+          mma_with_loads(a0, b0, stA((u + NST - 1) % NST), stB((u + NST - 1) % NST));
+          issue_done();
+          // tile kt+1 must have landed (the two newer ones may stay in flight) and every read of this stage be done
+          wait_vmcnt<(NST - 2) * (ACH + BCH)>();
+          wait_lgkm0();
+          tile_barrier();
+          __builtin_amdgcn_sched_barrier(0);
+          // second MFMA step, with the first operands of the next tile read under it
+          if (kt + 1 < KT_total) read_ops(stA((u + 1) % NST), stB((u + 1) % NST), 0, a0, b0);
+          __builtin_amdgcn_sched_barrier(0);
+          mma(a1, b1);
           __builtin_amdgcn_sched_barrier(0);
         }
-        issue_done();
-        // tile kt+1 must have landed (the two newer ones may stay in flight) and every read of this stage be done
-        wait_vmcnt<2 * (ACH + BCH)>();
-        wait_lgkm0();
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);
-        // second MFMA step, with the first operands of the next tile read under it
-        if (kt + 1 < KT_total) read_ops(stA((u + 1) & 3), stB((u + 1) & 3), 0, a0, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
@@ -340,9 +402,9 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   asm volatile("" ::: "memory");
 
   // ---- epilogue: aggregate, mask, store; 32 rows of the wave tile at a time through this wave's own array.
-  // The MFMAs were issued with the operands exchanged, so acc[mi][ni] holds the transposed 32x32 block:
-  // this lane has row 32 mi + li and the four consecutive columns 32 ni + 8 j + 4 lg .. + 3 in registers 4j .. 4j+3.
-  bf16_t* stage = wave < 4 ? stA(wave) : stB(wave - 4);
+  constexpr int AREAS = A_ELEMS / 2560;           // 5 KB staging areas per A stage
+  static_assert(32 * EPW <= 2560 && NW <= AREAS * NST, "every wave has its own staging area");
+  bf16_t* stage = stA(wave / AREAS) + (wave % AREAS) * 2560;
   constexpr int PPR = WCOLS / 8;                 // 16-byte pieces per staged row
   constexpr int RPI = 64 / PPR;                  // rows one wave instruction moves
   const int e_row = lane / PPR, e_pc = (lane % PPR) * 8;
@@ -404,24 +466,25 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
 // The workgroups after them compute the remaining tiles as two half-width tiles each; both halves of a tile
 // run on the same XCD.  The dispatcher hands out workgroups in index order, so the halves start as the compute
 // units finish their last full tile.
-template <bool NT>
+template <bool NT, int BK>
 __global__ __launch_bounds__(512, 1) void k_gemm_dma(const GemmParams p) {
+  constexpr int STAGE_ELEMS = BM * BK;            // 16 KB (BK = 32, four stages) or 32 KB (BK = 64, two) per operand
   __shared__ __attribute__((aligned(1024))) bf16_t sA0[STAGE_ELEMS];
   __shared__ __attribute__((aligned(1024))) bf16_t sA1[STAGE_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sA2[STAGE_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sA3[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sA2[BK == 32 ? STAGE_ELEMS : 8];
+  __shared__ __attribute__((aligned(1024))) bf16_t sA3[BK == 32 ? STAGE_ELEMS : 8];
   __shared__ __attribute__((aligned(1024))) bf16_t sB0[STAGE_ELEMS];
   __shared__ __attribute__((aligned(1024))) bf16_t sB1[STAGE_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sB2[STAGE_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sB3[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sB2[BK == 32 ? STAGE_ELEMS : 8];
+  __shared__ __attribute__((aligned(1024))) bf16_t sB3[BK == 32 ? STAGE_ELEMS : 8];
   __shared__ int sRow[256];
   const Smem sm = {sA0, sA1, sA2, sA3, sB0, sB1, sB2, sB3, sRow};
   const int b = blockIdx.x;
   if (b < p.n_full) {
-    gemm_tile<NT, 4, 2>(p, b, 0, sm);
+    gemm_tile<NT, 4, 2, BK>(p, b, 0, sm);
   } else {
     const int t = b - p.n_full;                                       // n_full is a multiple of 8
-    gemm_tile<NT, 4, 1>(p, p.n_full + (((t >> 4) << 3) | (t & 7)), (t >> 3) & 1, sm);
+    gemm_tile<NT, 4, 1, BK>(p, p.n_full + (((t >> 4) << 3) | (t & 7)), (t >> 3) & 1, sm);
   }
 }
 
@@ -450,6 +513,7 @@ mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t
   // One workgroup per compute unit at a time: the tiles left after the last full round would keep a fraction of
   // the units busy for a whole tile time.  When they fit twice, they run as half-width tiles.
   static const bool no_halves = getenv("MUX_GEMM_NO_HALF_TILES") != nullptr;
+  static const bool narrow = getenv("MUX_GEMM_BK32") != nullptr;
   const int ncu = compute_units();
   const int full_slots = (total / ncu) * (ncu / 8);          // per-XCD slots covered by whole rounds
   const int rem = total - full_slots * 8;
@@ -457,7 +521,11 @@ mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t
   if (!no_halves && ncu % 8 == 0 && rem > 0 && 2 * rem <= ncu) tail_slots = p.per_xcd - full_slots;
   p.n_full = 8 * (p.per_xcd - tail_slots);
   const int grid = p.n_full + 16 * tail_slots;
-  MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", (k_gemm_dma<NT>), dim3(grid), dim3(512), 0, c.stream, p);
+  if (Kc % 64 == 0 && !narrow) {
+    MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", (k_gemm_dma<NT, 64>), dim3(grid), dim3(512), 0, c.stream, p);
+  } else {
+    MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", (k_gemm_dma<NT, 32>), dim3(grid), dim3(512), 0, c.stream, p);
+  }
   return MUX_OK;
 }
 
@@ -467,7 +535,7 @@ mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t
 // and in the backward every LoRA rank a multiple of 8 (rows of A_t are read in 16-byte pieces).
 bool gemm_dma_supported(const CallCtx& c, bool backward) {
   if (!gemm_mfma_supported(c)) return false;
-  if ((backward ? c.N : c.K) % BK != 0) return false;      // no K-tail masks in the pipelined loop
+  if ((backward ? c.N : c.K) % 32 != 0) return false;      // no K-tail masks in the pipelined loop
   if (backward)
     for (const HostTask& ht : c.st->tasks)
       if (ht.kind == MUX_ADAPTER_LORA && (ht.rank & 7) != 0) return false;
