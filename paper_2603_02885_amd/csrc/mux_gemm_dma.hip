@@ -21,6 +21,7 @@
 // Every stage is its own __shared__ array so that the compiler's wait-count insertion can tell
 // the stage being filled from the stage being read.
 #include <cstdlib>
+#include <type_traits>
 
 #include "mux_device_utils.h"
 
@@ -309,6 +310,51 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
     }
   };
 
+  // One operand fragment of step ks: r = 0, 1 .. in the order the next step's MFMAs first need them
+  // (A0, B0 .. B(NI-1), A1, A2, A3).
+  auto read_one = [&](const bf16_t* cA, const bf16_t* cB, int ks, int r, bf16x8 (&a)[4], bf16x8 (&b)[NI]) {
+    const int pa = ((2 * ks + lg) ^ swz) * 8;
+    if (r == 0 || r > NI) {
+      const int t = r == 0 ? 0 : r - NI;
+      a[t] = *(const bf16x8*)(cA + a_rd + t * 32 * BK + pa);
+    } else {
+      const int t = r - 1;
+      if (NT) {
+        b[t] = *(const bf16x8*)(cB + bt_rd + t * 32 * BK + pa);
+      } else {
+        const int krow = ks * 16 + 8 * lg + kq;
+        const int seg = (wn * (2 * NI) + 2 * t + lhalf) ^ (kq << 1);
+        const bf16x4 lo = lds_read_tr(cB + krow * BN + seg * 16 + bn_col);
+        const bf16x4 hi = lds_read_tr(cB + (krow + 4) * BN + seg * 16 + bn_col);
+        b[t] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+    }
+  };
+  // One MFMA step from (a, b) with the operand reads of step ks_next of (cA, cB) into (an, bn) issued one per
+  // MFMA in its shadow (skipped when rd is false), and, when LOADS, the loads of one tile into (dA, dB) spread
+  // over the MFMAs after them.
+  auto fused_step = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[NI], const bf16_t* cA, const bf16_t* cB, int ks_next,
+                        bf16x8 (&an)[4], bf16x8 (&bn)[NI], bool rd, auto LOADS, bf16_t* dA, bf16_t* dB) {
+    constexpr bool loads = decltype(LOADS)::value;
+    constexpr int NM = 4 * NI, NR = 4 + NI, NL = ACH + BCH;
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      mma_one(a, b, m);
+      if (rd) {
+        if (m < NR) read_one(cA, cB, ks_next, m, an, bn);
+        if (m == NM - 1) {                                   // a half-width tile has more fragments than MFMAs
+#pragma unroll
+          for (int r = NM; r < NR; ++r) read_one(cA, cB, ks_next, r, an, bn);
+        }
+      }
+      if (loads) {
+#pragma unroll
+        for (int d = (m * NL) / NM; d < ((m + 1) * NL) / NM; ++d) issue_one(dA, dB, d);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
   auto stA = [&](int s) -> bf16_t* { return s == 0 ? sA0 : (s == 1 ? sA1 : (s == 2 ? sA2 : sA3)); };
   auto stB = [&](int s) -> bf16_t* { return s == 0 ? sB0 : (s == 1 ? sB1 : (s == 2 ? sB2 : sB3)); };
   auto tile_barrier = [&]() {
@@ -341,25 +387,14 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
           bf16_t* cB = stB(u);
           prepare();
           __builtin_amdgcn_sched_barrier(0);
-          read_ops(cA, cB, 1, a1, b1);
-          __builtin_amdgcn_sched_barrier(0);
-          mma(a0, b0);
-          __builtin_amdgcn_sched_barrier(0);
-          read_ops(cA, cB, 2, a0, b0);
-          __builtin_amdgcn_sched_barrier(0);
-          mma(a1, b1);
-          __builtin_amdgcn_sched_barrier(0);
-          read_ops(cA, cB, 3, a1, b1);
-          __builtin_amdgcn_sched_barrier(0);
-          mma(a0, b0);
-          __builtin_amdgcn_sched_barrier(0);
+          fused_step(a0, b0, cA, cB, 1, a1, b1, true, std::false_type{}, nullptr, nullptr);
+          fused_step(a1, b1, cA, cB, 2, a0, b0, true, std::false_type{}, nullptr, nullptr);
+          fused_step(a0, b0, cA, cB, 3, a1, b1, true, std::false_type{}, nullptr, nullptr);
           wait_vmcnt<0>();
           wait_lgkm0();
           tile_barrier();
           __builtin_amdgcn_sched_barrier(0);
-          if (kt + 1 < KT_total) read_ops(stA(u ^ 1), stB(u ^ 1), 0, a0, b0);
-          __builtin_amdgcn_sched_barrier(0);
-          mma_with_loads(a1, b1, cA, cB);
+          fused_step(a1, b1, stA(u ^ 1), stB(u ^ 1), 0, a0, b0, true, std::true_type{}, cA, cB);   // past the last tile: read, unused
           issue_done();
         }
       }
