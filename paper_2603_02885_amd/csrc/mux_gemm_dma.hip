@@ -109,8 +109,13 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   constexpr int NST = BK == 64 ? 2 : 4;           // LDS stages
   constexpr int NW = 2 * WNW, NTHR = 64 * NW;
   constexpr int A_ELEMS = BM * BK;                // elements of one A stage
-  constexpr int ACH = (A_ELEMS / 512) / NW, BCH = (BN * BK / 512) / NW;   // 1 KB chunks each wave fetches per K-tile
-  static_assert(ACH >= 1 && BCH >= 1, "every wave fetches at least one chunk of each tile");
+  // The loads are issued by the first half of the waves only.  Each SIMD hosts waves w and w + NW/2 and serves the
+  // older one first, so wave w runs ahead and then idles at the barrier; a wave that cannot issue a load (the
+  // vector memory pipeline takes 16 cycles per instruction, 1 KB) cannot issue the MFMA behind it either.
+  // Giving wave w all the loads uses its slack and leaves wave w + NW/2 a pure MFMA / LDS-read stream.
+  constexpr int LW = NW / 2;
+  constexpr int ACH = (A_ELEMS / 512) / LW, BCH = (BN * BK / 512) / LW;   // 1 KB chunks a loading wave fetches per K-tile
+  static_assert(ACH >= 1 && BCH >= 1, "every loading wave fetches at least one chunk of each tile");
   constexpr int LPR = BK / 8;                     // [rows][BK] tiles: lanes (16-byte pieces) per row
   constexpr int RPC = 64 / LPR;                   //                   rows per 1 KB chunk
   constexpr int PPRB = BN / 8;                    // forward: 16-byte pieces per k-row of the [BK][BN] tile
@@ -138,6 +143,8 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WNW, wn = wave % WNW;
+  const bool loader = wave < LW;
+  const int lw = wave % LW;                       // chunk owner index (meaningful for loading waves)
 
   if (tid < 256) sRow[tid] = (it.task >= 0 && tid < it.nrows && row_is_valid(p.dtab, it.row0 + tid)) ? 1 : 0;
 
@@ -162,7 +169,7 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
 
   // ---- DMA geometry.  A wave instruction fills 1 KB: RPC rows x 2 BK bytes of a [rows][BK] tile
   // (lane -> row lane/LPR, physical piece lane%LPR), or RPCB k-rows of the forward's [BK][BN] tile of W
-  // (lane -> k-row lane/PPRB, physical piece lane%PPRB).  Wave w owns chunks w*ACH .. of A and w*BCH .. of B.
+  // (lane -> k-row lane/PPRB, physical piece lane%PPRB).  Loading wave w owns chunks w*ACH .. of A and w*BCH .. of B.
   const int r_in = lane / LPR;                                  // row inside the chunk
   const uint32_t a_rows_bytes = (uint32_t)it.nrows * (uint32_t)p.Kc * 2u;
   const bf16_t* a_base = (NT && ia3) ? p.AinScaled + (size_t)(tk.zrow0 + it.row0 - tk.row_begin) * p.Kc
@@ -173,10 +180,10 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   const rsrc_t rP = make_rsrc(lora ? adapterB : p.Ain, lora ? (uint32_t)(NT ? (size_t)p.Nc * rank : (size_t)rank * p.Nc) * 2u : 0u);
 
   // row of the [rows][BK] tile chunk q of this wave puts this lane on, and the logical k-piece it fetches there
-  auto a_row_of = [&](int q) { return wave * (RPC * ACH) + RPC * q + r_in; };
-  auto b_row_of = [&](int q) { return wave * (RPC * BCH) + RPC * q + r_in; };   // backward: row of W inside the tile
+  auto a_row_of = [&](int q) { return lw * (RPC * ACH) + RPC * q + r_in; };
+  auto b_row_of = [&](int q) { return lw * (RPC * BCH) + RPC * q + r_in; };   // backward: row of W inside the tile
   auto piece_of = [&](int row) { return (lane % LPR) ^ swz_row<BK>(row); };
-  // forward W tile: k-row = (wave*BCH + q)*RPCB + lane/PPRB, physical piece lane%PPRB -> logical n
+  // forward W tile: k-row = (lw*BCH + q)*RPCB + lane/PPRB, physical piece lane%PPRB -> logical n
   const int nk_in = lane / PPRB;
   const int n_pp = lane % PPRB;
 
@@ -191,7 +198,7 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
     if (NT) {
       offB[q] = (uint32_t)(((size_t)(c0 + b_row_of(q)) * p.ldw + piece_of(b_row_of(q)) * 8) * 2);
     } else {
-      const int kk = (wave * BCH + q) * RPCB + nk_in;        // k-row inside the tile
+      const int kk = (lw * BCH + q) * RPCB + nk_in;          // k-row inside the tile
       const int seg = (n_pp >> 1) ^ ((kk & 3) << 1);         // logical 32-byte segment
       const int n = seg * 16 + (n_pp & 1) * 8;
       offB[q] = (c0 + n < p.Nc) ? (uint32_t)(((size_t)kk * p.ldw + c0 + n) * 2) : OOB;
@@ -224,7 +231,7 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
             const int j = j0 + piece_of(b_row_of(q)) * 8;
             offB[q] = (c < p.Nc && j < rank) ? (uint32_t)(((size_t)c * rank + j) * 2) : OOB;
           } else {
-            const int kk = (wave * BCH + q) * RPCB + nk_in;
+            const int kk = (lw * BCH + q) * RPCB + nk_in;
             const int seg = (n_pp >> 1) ^ ((kk & 3) << 1);
             const int n = seg * 16 + (n_pp & 1) * 8;
             offB[q] = (c0 + n < p.Nc && j0 + kk < rank) ? (uint32_t)(((size_t)(j0 + kk) * p.Nc + c0 + n) * 2) : OOB;
@@ -235,8 +242,9 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   };
   // one load of the tile being fetched: i = 0 .. ACH+BCH-1, the A pieces first
   auto issue_one = [&](bf16_t* dA, bf16_t* dB, int i) {
-    if (i < ACH) dma16(curA, dA + (wave * ACH + i) * 512, offA[i] + kA);
-    else dma16(curB, dB + (wave * BCH + (i - ACH)) * 512, offB[i - ACH] + kB);
+    if (!loader) return;
+    if (i < ACH) dma16(curA, dA + (lw * ACH + i) * 512, offA[i] + kA);
+    else dma16(curB, dB + (lw * BCH + (i - ACH)) * 512, offB[i - ACH] + kB);
   };
   auto issue_done = [&]() { kA += stepA; kB += stepB; ++next_tile; };
   auto issue = [&](bf16_t* dA, bf16_t* dB) {
