@@ -38,11 +38,12 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t* p) {
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // ------------------------------------------------------------------------------------------------
-// down-projection.  One workgroup = RT*16 rows of one 64-row item; its NWV waves split the contraction.
-// 16x16x32 MFMA tiles, both operands read straight from global memory into registers (each element of In
-// is used once; P_t stays in L2 and is reused by the RT row tiles of a wave); the loads of the next group
-// of steps are in flight while the current group is multiplied; the partial sums of the waves are combined
-// through LDS in a fixed order.
+// down-projection.  One workgroup = 32 rows of one 64-row item; its waves split the contraction.
+// A wave walks its share 64 columns at a time: the 32x64 slab of In and the rank x 64 slab of P_t are fetched with
+// loads that cover whole 128-byte lines (8 rows x 128 B per wave instruction: rows of 64 B move at half the rate
+// on this memory system), two slabs ahead in registers, pass through a wave-private LDS region in their natural
+// layout and come back in the 16x16x32 MFMA operand layout.  No workgroup barrier in the loop.  The partial sums
+// of the waves are combined through LDS in a fixed order.
 struct DownParams {
   const int32_t* dtab;
   const DevTask* tasks;
@@ -52,12 +53,16 @@ struct DownParams {
   int C, RP;
 };
 
-template <int RT, int NWV>
+constexpr int GP = 72;   // LDS row pitch in elements (144 B): 16 consecutive rows of one 16-byte piece hit 64 different banks
+
+template <int NJM, int NWV, int DEPTH>
 __global__ __launch_bounds__(64 * NWV) void k_down(const DownParams p) {
-  constexpr int ROWS = RT * 16, SUBS = 64 / ROWS, NTHR = 64 * NWV;
-  // partial sums, column-major per wave (a lane's four accumulator rows are contiguous: one 16-byte LDS store)
-  __shared__ __attribute__((aligned(16))) float red[NWV][64][ROWS + 4];
-  const int item = blockIdx.x / SUBS, sub = blockIdx.x % SUBS;
+  constexpr int ROWS = 32, NTHR = 64 * NWV;
+  constexpr int SLAB = (ROWS + NJM * 16) * GP;                 // elements per wave: In slab, then P slab
+  constexpr int REDW = NJM * 16 * (ROWS + 4) * 2;              // the same region later holds the partial sums (floats)
+  constexpr int REGION = SLAB > REDW ? SLAB : REDW;
+  __shared__ __attribute__((aligned(16))) bf16_t lds[NWV][REGION];
+  const int item = blockIdx.x >> 1, sub = blockIdx.x & 1;
   const ItemView it = load_item(p.dtab, TS64, item);
   const int r0 = sub * ROWS;
   if (r0 >= it.nrows) return;
@@ -74,89 +79,107 @@ __global__ __launch_bounds__(64 * NWV) void k_down(const DownParams p) {
   const bf16_t* P = p.AT ? p.AT + tk.at_off : (const bf16_t*)tk.B;
   const int prow = p.AT ? NJ * 16 : rank;            // rows that exist in P
 
-  const int i = lane & 15, g = lane >> 4;
-  const int per = ((p.C + NWV - 1) / NWV + 31) & ~31;
+  const int per = ((p.C + NWV - 1) / NWV + 63) & ~63;
   const int cbeg = wave * per, cend = cbeg + per < p.C ? cbeg + per : p.C;
+  bf16_t* sX = lds[wave];
+  bf16_t* sP = lds[wave] + ROWS * GP;
 
   const rsrc_t rIn = make_rsrc(p.In + (size_t)row0 * p.C, (uint32_t)nr * (uint32_t)p.C * 2u);
   const rsrc_t rP = make_rsrc(P, (uint32_t)prow * (uint32_t)p.C * 2u);
-  uint32_t in_off[RT];
+  // one wave instruction: 8 rows x 128 B; lane -> row lane/8 (+ 8 q), 16-byte piece lane%8
+  const int b_row = lane >> 3, b_pc = (lane & 7) * 8;
+  uint32_t x_off[4], p_off[2 * NJM];
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    const int m = rt * 16 + i;
-    in_off[rt] = (m < nr && row_is_valid(p.dtab, row0 + m)) ? ((uint32_t)m * (uint32_t)p.C + 8u * g) * 2u : OOB;
+  for (int q = 0; q < 4; ++q) {
+    const int m = b_row + 8 * q;
+    x_off[q] = (m < nr && row_is_valid(p.dtab, row0 + m)) ? ((uint32_t)m * (uint32_t)p.C + (uint32_t)b_pc) * 2u : OOB;
   }
-  uint32_t p_off[4];
 #pragma unroll
-  for (int jt = 0; jt < 4; ++jt)
-    p_off[jt] = (jt < NJ && jt * 16 + i < prow) ? ((uint32_t)(jt * 16 + i) * (uint32_t)p.C + 8u * g) * 2u : OOB;
+  for (int q = 0; q < 2 * NJM; ++q) {
+    const int j = b_row + 8 * q;
+    p_off[q] = (q < 2 * NJ && j < prow) ? ((uint32_t)j * (uint32_t)p.C + (uint32_t)b_pc) * 2u : OOB;
+  }
 
-  f32x4 acc[RT][4];
+  f32x4 acc[2][NJM];
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt)
+  for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-    for (int jt = 0; jt < 4; ++jt) acc[rt][jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int jt = 0; jt < NJM; ++jt) acc[rt][jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  // U steps of 32 per group; with more than two rank tiles the group is halved to stay within registers
-  auto run = [&](auto UC, auto JC) {
-    constexpr int U = decltype(UC)::value, NJM = decltype(JC)::value;
-    u32x4 a[2][U][RT], b[2][U][NJM];
-    auto load = [&](int c, int buf) {
+  u32x4 gx[DEPTH][4], gp[DEPTH][2 * NJM];
+  auto load = [&](int c, int buf) {          // a slab that starts past the end of this wave's share reads as zeros
+    const uint32_t k = (c + b_pc < cend) ? (uint32_t)c * 2u : OOB;     // OOB + OOB wraps into range: mask on k only
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int cc = c + 32 * u;
-        const uint32_t k = (cc + 8 * g < cend) ? (uint32_t)cc * 2u : OOB;     // OOB + OOB wraps into range: mask on k only
+    for (int q = 0; q < 4; ++q) gx[buf][q] = buf_load16(rIn, (x_off[q] == OOB || k == OOB) ? OOB : x_off[q] + k);
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) a[buf][u][rt] = buf_load16(rIn, (in_off[rt] == OOB || k == OOB) ? OOB : in_off[rt] + k);
+    for (int q = 0; q < 2 * NJM; ++q)
+      if (q < 2 * NJ) gp[buf][q] = buf_load16(rP, (p_off[q] == OOB || k == OOB) ? OOB : p_off[q] + k);
+  };
+  const int i = lane & 15, g = lane >> 4;
+  // DEPTH slabs in flight while one is multiplied
 #pragma unroll
-        for (int jt = 0; jt < NJM; ++jt)
-          if (jt < NJ) b[buf][u][jt] = buf_load16(rP, (p_off[jt] == OOB || k == OOB) ? OOB : p_off[jt] + k);
-      }
-    };
-    auto mul = [&](int buf) {
+  for (int d = 0; d < DEPTH; ++d) load(cbeg + 64 * d, d);
+  for (int c = cbeg; c < cend; c += 64 * DEPTH) {
 #pragma unroll
-      for (int u = 0; u < U; ++u)
+    for (int buf = 0; buf < DEPTH; ++buf) {
+      if (c + 64 * buf < cend) {
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
+        for (int q = 0; q < 4; ++q) *(u32x4*)(sX + (b_row + 8 * q) * GP + b_pc) = gx[buf][q];
+#pragma unroll
+        for (int q = 0; q < 2 * NJM; ++q)
+          if (q < 2 * NJ) *(u32x4*)(sP + (b_row + 8 * q) * GP + b_pc) = gp[buf][q];
+        load(c + 64 * buf + 64 * DEPTH, buf);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        bf16x8 a[2][2], b[NJM][2];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+#pragma unroll
+          for (int rt = 0; rt < 2; ++rt) a[rt][s] = *(const bf16x8*)(sX + (rt * 16 + i) * GP + s * 32 + 8 * g);
 #pragma unroll
           for (int jt = 0; jt < NJM; ++jt)
-            if (jt < NJ)
-              acc[rt][jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a[buf][u][rt]), as_bf16x8(b[buf][u][jt]), acc[rt][jt], 0, 0, 0);
-    };
-    load(cbeg, 0);
-    for (int c = cbeg; c < cend; c += 64 * U) {
-      load(c + 32 * U, 1);      // past cend every piece is masked
-      mul(0);
-      load(c + 64 * U, 0);
-      mul(1);
+            if (jt < NJ) b[jt][s] = *(const bf16x8*)(sP + (jt * 16 + i) * GP + s * 32 + 8 * g);
+        }
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+          for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int jt = 0; jt < NJM; ++jt)
+              if (jt < NJ) acc[rt][jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rt][s], b[jt][s], acc[rt][jt], 0, 0, 0);
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+      }
     }
-  };
-  if (NJ <= 2) run(std::integral_constant<int, 4>{}, std::integral_constant<int, 2>{});
-  else run(std::integral_constant<int, 2>{}, std::integral_constant<int, 4>{});
+  }
 
-  // acc[rt][jt][v] = partial of Out[row0 + rt*16 + 4g + v][jt*16 + i]
+  // acc[rt][jt][v] = partial of Out[row0 + rt*16 + 4g + v][jt*16 + i]; staged column-major, one 16-byte store each
+  float* red = (float*)lds[wave];
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt)
+  for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-    for (int jt = 0; jt < 4; ++jt)
-      *(f32x4*)&red[wave][jt * 16 + i][rt * 16 + 4 * g] = acc[rt][jt];
+    for (int jt = 0; jt < NJM; ++jt)
+      if (jt < NJ) *(f32x4*)&red[(jt * 16 + i) * (ROWS + 4) + rt * 16 + 4 * g] = acc[rt][jt];
   __syncthreads();
   for (int e = tid; e < ROWS * p.RP; e += NTHR) {
     const int orow = e / p.RP, j = e % p.RP;
     if (orow >= nr) continue;
     float s = 0.f;
+    if (j < NJ * 16) {
 #pragma unroll
-    for (int w = 0; w < NWV; ++w) s += red[w][j][orow];
+      for (int w = 0; w < NWV; ++w) s += ((const float*)lds[w])[j * (ROWS + 4) + orow];
+    }
     const bool ok = row_is_valid(p.dtab, row0 + orow);
     p.Out[(size_t)(row0 + orow) * p.RP + j] = f32_to_bf16(ok && j < rank ? tk.scale * s : 0.f);
   }
 }
 
-// 32 rows per workgroup, four waves splitting the contraction: the fastest of the shapes tried (16/32/64 rows,
-// 4 or 8 waves) on both the 5k-row and the 20k-row workloads.
 void launch_down(const CallCtx& c, const char* name, const DownParams& p) {
   const unsigned items = (unsigned)c.st->items[TS64].size();
-  MUX_LAUNCH(name, (k_down<2, 4>), dim3(items * 2), dim3(256), 0, c.stream, p);
+  // eight waves split the contraction (four for ranks above 32, whose LDS regions are larger); two slabs in flight
+  if (c.st->r_max <= 16) MUX_LAUNCH(name, (k_down<1, 8, 2>), dim3(items * 2), dim3(512), 0, c.stream, p);
+  else if (c.st->r_max <= 32) MUX_LAUNCH(name, (k_down<2, 8, 2>), dim3(items * 2), dim3(512), 0, c.stream, p);
+  else MUX_LAUNCH(name, (k_down<4, 4, 2>), dim3(items * 2), dim3(256), 0, c.stream, p);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -173,8 +196,6 @@ struct GradParams {     // blockIdx.z picks the problem: 0 = dB (Small = Hs, Big
   int C[2];
   int RP, ts;
 };
-
-constexpr int GP = 72;   // LDS row pitch in elements (144 B)
 
 template <int NJM>
 __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
