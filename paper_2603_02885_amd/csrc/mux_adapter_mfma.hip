@@ -309,16 +309,17 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
 
 // ------------------------------------------------------------------------------------------------
 // IA3_OUT: part[item][n] = sum_{rows} g[i][n] * z[i][n], and dYs[i][n] = g[i][n] * l_t[n] (the operand of the
-// backbone backward for these rows).  grid = (64-row items, ceil(N/2048)); 8 columns per thread, 4 rows in flight.
-__global__ __launch_bounds__(256) void k_dl(const int32_t* __restrict__ dtab, const DevTask* __restrict__ tasks,
+// backbone backward for these rows).  grid = (64-row items, ceil(N/1024)); 8 columns per thread, 8 rows in flight.
+__global__ __launch_bounds__(128) void k_dl(const int32_t* __restrict__ dtab, const DevTask* __restrict__ tasks,
                                            const bf16_t* __restrict__ dY, const bf16_t* __restrict__ Z, float* __restrict__ part,
                                            bf16_t* __restrict__ dYs, int N) {
   const ItemView it = load_item(dtab, TS64, blockIdx.x);
   if (it.task < 0 || it.nvalid == 0) return;
   const DevTask tk = tasks[it.task];
   if (tk.kind != MUX_ADAPTER_IA3_OUT) return;
-  const int n0 = (blockIdx.y * 256 + threadIdx.x) * 8;
+  const int n0 = (blockIdx.y * 128 + threadIdx.x) * 8;
   if (n0 >= N) return;
+  constexpr int RF = 8;     // rows in flight
   float s[8], lv[8];
   {
     const uint4 l4 = *(const uint4*)((const bf16_t*)tk.L + n0);
@@ -328,12 +329,12 @@ __global__ __launch_bounds__(256) void k_dl(const int32_t* __restrict__ dtab, co
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) s[e] = 0.f;
-  for (int m0 = 0; m0 < it.nrows; m0 += 4) {
-    uint4 gv[4], zv[4];
-    bool ok[4];
-    size_t zoff[4];
+  for (int m0 = 0; m0 < it.nrows; m0 += RF) {
+    uint4 gv[RF], zv[RF];
+    bool ok[RF];
+    size_t zoff[RF];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < RF; ++u) {
       const int row = it.row0 + m0 + u;
       ok[u] = m0 + u < it.nrows && row_is_valid(dtab, row);
       zoff[u] = (size_t)(tk.zrow0 + row - tk.row_begin) * N + n0;
@@ -341,7 +342,7 @@ __global__ __launch_bounds__(256) void k_dl(const int32_t* __restrict__ dtab, co
       zv[u] = ok[u] ? *(const uint4*)(Z + zoff[u]) : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < RF; ++u) {
       if (!ok[u]) continue;
       const uint32_t* pg = (const uint32_t*)&gv[u];
       const uint32_t* pz = (const uint32_t*)&zv[u];
@@ -452,7 +453,7 @@ mux_status adapter_grads(const CallCtx& c, const void* X, const void* dY, const 
                (const float*)part0, (const float*)part1, c.N, c.K, c.RP, ts, 0, accumulate);
   }
   if (c.st->n_ia3 > 0) {
-    MUX_LAUNCH("grad_dl", k_dl, dim3((unsigned)c.st->items[TS64].size(), (c.N + 2047) / 2048), dim3(256), 0, c.stream,
+    MUX_LAUNCH("grad_dl", k_dl, dim3((unsigned)c.st->items[TS64].size(), (c.N + 1023) / 1024), dim3(128), 0, c.stream,
                c.dtab, c.dtasks, (const bf16_t*)dY, (const bf16_t*)Z, (float*)part, (bf16_t*)c.dYs, c.N);
     MUX_LAUNCH("reduce_dl", k_reduce, dim3(M, (c.N + 255) / 256), dim3(256), 0, c.stream, c.dtab, c.dtasks,
                (const float*)part, (const float*)nullptr, c.N, c.K, 1, TS64, 1, accumulate);
