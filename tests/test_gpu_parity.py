@@ -86,6 +86,18 @@ def test_long_contraction_mixed_ranks(env):
         assert torch.equal(g.Y, y1) and torch.equal(g.dX, dx1)
 
 
+def test_kernel_choice_by_shape(env):
+    """Shapes that select the other kernels: contraction lengths that are multiples of 32 but not of 64 (the 32-deep
+    pipelined GEMM, forward and backward), and rows that are not 16-byte aligned (the plain kernels)."""
+    tasks = [wlm.Task(wlm.KIND_LORA, 8, 2.0, [90, 40]), wlm.Task(wlm.KIND_IA3, 0, 1.0, [130]),
+             wlm.Task(wlm.KIND_LORA, 40, 0.5, [300]), wlm.Task(wlm.KIND_NONE, 0, 1.0, [33]),
+             wlm.Task(wlm.KIND_LORA, 16, 1.0, [257])]
+    wl = wlm.Workload(name="bk32", layers=[("w", 416, 352)], tasks=tasks, chunk=32, sigma_w=0.05, sigma_ab=0.05)
+    run_case(env, wl, seed=3)
+    wl = wlm.Workload(name="unaligned", layers=[("w", 100, 52)], tasks=tasks, chunk=16, sigma_w=0.05, sigma_ab=0.05)
+    run_case(env, wl, seed=4)
+
+
 def test_accumulate_and_determinism(env):
     mx, torch = env
     wl = mixed_workload()
