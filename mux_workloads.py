@@ -26,6 +26,7 @@ import numpy as np
 KIND_NONE = 0
 KIND_LORA = 1
 KIND_IA3 = 2
+KIND_ADAPTER = 3   # additive bottleneck after the BaseOp (Adapter-Tuning): D [N, r] in the A slot, U [r, N] in the B slot
 
 
 @dataclass
@@ -202,6 +203,10 @@ def layer_tensors(wl: Workload, layer: int, T: int, seed: int = 0, bf16: bool = 
         if task.kind == KIND_LORA:
             A.append(normal(seed, f"{tag}.A{t}", (K, task.rank), wl.sigma_ab, bf16=bf16))
             B.append(normal(seed, f"{tag}.B{t}", (task.rank, N), wl.sigma_ab, bf16=bf16))
+            L.append(None)
+        elif task.kind == KIND_ADAPTER:
+            A.append(normal(seed, f"{tag}.D{t}", (N, task.rank), wl.sigma_ab, bf16=bf16))
+            B.append(normal(seed, f"{tag}.U{t}", (task.rank, N), wl.sigma_ab, bf16=bf16))
             L.append(None)
         elif task.kind == KIND_IA3:
             A.append(None)

@@ -93,7 +93,7 @@ def forward(X, W, row_task, kinds, ranks, scales, A, B, L, cols=None, want_z=Fal
     assert row_task.shape == (T,)
     k, r, s = _task_arrays(kinds, ranks, scales)
     M = len(k)
-    r_max = int(max([int(r[t]) for t in range(M) if k[t] == 1] + [1]))
+    r_max = int(max([int(r[t]) for t in range(M) if k[t] in (1, 3)] + [1]))
     n_cols, cptr, _ckeep = _cols(cols, N)
     Ap, _ka = _ptrs_f(A); Bp, _kb = _ptrs_f(B); Lp, _kl = _ptrs_f(L)
     Y = np.zeros((T, n_cols), dtype=np.float64)
@@ -120,7 +120,7 @@ def backward(X, dY, W, row_task, kinds, ranks, scales, A, B, L, kcols=None, cols
     row_task = np.ascontiguousarray(row_task, dtype=np.int32)
     k, r, s = _task_arrays(kinds, ranks, scales)
     M = len(k)
-    r_max = int(max([int(r[t]) for t in range(M) if k[t] == 1] + [1]))
+    r_max = int(max([int(r[t]) for t in range(M) if k[t] in (1, 3)] + [1]))
     n_kcols, kptr, _kk = _cols(kcols, K)
     n_cols, cptr, _ck = _cols(cols, N)
     Ap, _ka = _ptrs_f(A); Bp, _kb = _ptrs_f(B); Lp, _kl = _ptrs_f(L)
@@ -132,6 +132,10 @@ def backward(X, dY, W, row_task, kinds, ranks, scales, A, B, L, kcols=None, cols
     for t in range(M):
         if k[t] == 1:
             dA.append(np.zeros((K, int(r[t])), dtype=np.float64))
+            dB.append(np.zeros((int(r[t]), N), dtype=np.float64))
+            dL.append(None)
+        elif k[t] == 3:     # additive kind: D [N, r] in the A slot, U [r, N] in the B slot
+            dA.append(np.zeros((N, int(r[t])), dtype=np.float64))
             dB.append(np.zeros((int(r[t]), N), dtype=np.float64))
             dL.append(None)
         elif k[t] == 2:

@@ -9,7 +9,7 @@ LIB_PATH = os.path.join(HERE, "libmux_oracle.so")
 def build_oracle() -> str:
     src = os.path.join(HERE, "mux_oracle.c")
     tmp = LIB_PATH + f".tmp{os.getpid()}"
-    subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", tmp, src])
+    subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", tmp, src, "-lm"])
     os.replace(tmp, LIB_PATH)
     return LIB_PATH
 

@@ -17,6 +17,10 @@
  *   - Aggregate = add (section 3.4.3 names the Add operator); for the IA3-style task
  *     kind of the benchmark configs the aggregate is an elementwise product with a
  *     per-task vector l:  y = (x W) * l.
+ *   - The additive kind (section 2.1 names Adapter-Tuning as the additive PEFT type and section 5
+ *     lists it among the implemented ones, without a formula) is read as the usual bottleneck
+ *     inserted after the BaseOp:  z = x W,  u = z D,  y = z + s gelu(u) U,  with D [N,r] passed
+ *     in the A slot and U [r,N] in the B slot; gelu(u) = u/2 (1 + erf(u / sqrt 2)).
  *   - Chunk alignment pads with zero tokens (section 3.5): a padding row's buffer
  *     content is ignored (selected away, never multiplied, so NaN there cannot leak),
  *     its outputs are zero, and it adds nothing to any gradient.
@@ -31,6 +35,7 @@
  * merged-weight closed form, exact finite differences, hand-worked goldens, isolation
  * invariants).
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -38,12 +43,31 @@
 #define KIND_NONE 0
 #define KIND_LORA 1
 #define KIND_IA3 2
+#define KIND_ADAPTER 3
 #define MAX_RANK 1024
+
+static inline int has_rank(int kind) { return kind == KIND_LORA || kind == KIND_ADAPTER; }
+static inline double gelu(double u) { return 0.5 * u * (1.0 + erf(u * 0.70710678118654752440)); }
+static inline double gelu_prime(double u)
+{
+    return 0.5 * (1.0 + erf(u * 0.70710678118654752440)) + u * exp(-0.5 * u * u) * 0.39894228040143267794;
+}
+
+/* z[0..N) = x W, every column, summed in ascending k */
+static void full_row_times_w(const float* x, const float* W, int K, int N, double* z)
+{
+    for (int n = 0; n < N; ++n) z[n] = 0.0;
+    for (int k = 0; k < K; ++k) {
+        const double xk = (double)x[k];
+        const float* wrow = W + (size_t)k * N;
+        for (int n = 0; n < N; ++n) z[n] += xk * (double)wrow[n];
+    }
+}
 
 static inline int col_of(const int32_t* cols, int c) { return cols ? cols[c] : c; }
 
-/* Forward.  Y[T,n_cols], H[T,r_max] (x A_t, unscaled; zero beyond rank and on pad rows),
- * Z[T,n_cols] (x W before the aggregate; may be NULL). */
+/* Forward.  Y[T,n_cols], H[T,r_max] (LoRA: x A_t, unscaled; additive kind: the pre-activation u = z D_t;
+ * zero beyond rank and on pad rows), Z[T,n_cols] (x W before the aggregate; may be NULL). */
 int mux_oracle_forward(int T, int K, int N,
                        const float* X, const float* W, const int32_t* row_task,
                        int n_tasks, const int32_t* kind, const int32_t* rank, const double* scale,
@@ -55,9 +79,10 @@ int mux_oracle_forward(int T, int K, int N,
     for (int i = 0; i < T; ++i) {
         int t = row_task[i];
         if (t >= n_tasks) return 2;
-        if (t >= 0 && kind[t] == KIND_LORA && (rank[t] > r_max || rank[t] < 0 || rank[t] > MAX_RANK))
+        if (t >= 0 && has_rank(kind[t]) && (rank[t] > r_max || rank[t] < 0 || rank[t] > MAX_RANK))
             return 3;
     }
+    int failed = 0;
 #pragma omp parallel for schedule(dynamic, 4)
     for (int i = 0; i < T; ++i) {
         const int t = row_task[i];
@@ -97,9 +122,29 @@ int mux_oracle_forward(int T, int K, int N,
         } else if (kind[t] == KIND_IA3) {          /* y = z * l_t  (aggregate: multiply) */
             const float* l = L[t];
             for (int c = 0; c < n_cols; ++c) y[c] *= (double)l[col_of(cols, c)];
+        } else if (kind[t] == KIND_ADAPTER) {      /* y = z + s_t gelu(z D_t) U_t */
+            const int r = rank[t];
+            const float* Dt = A[t];                /* [N, r] */
+            const float* Ut = B[t];                /* [r, N] */
+            double* zf = (double*)malloc(sizeof(double) * (size_t)N);
+            if (!zf) { failed = 1; continue; }
+            full_row_times_w(x, W, K, N, zf);      /* the bottleneck contracts over every output column */
+            double uu[MAX_RANK], aa[MAX_RANK];
+            for (int j = 0; j < r; ++j) uu[j] = 0.0;
+            for (int n = 0; n < N; ++n)
+                for (int j = 0; j < r; ++j) uu[j] += zf[n] * (double)Dt[(size_t)n * r + j];
+            for (int j = 0; j < r; ++j) aa[j] = gelu(uu[j]);
+            if (h) for (int j = 0; j < r; ++j) h[j] = uu[j];
+            for (int c = 0; c < n_cols; ++c) {
+                const int n = col_of(cols, c);
+                double v = 0.0;
+                for (int j = 0; j < r; ++j) v += aa[j] * (double)Ut[(size_t)j * N + n];
+                y[c] += scale[t] * v;
+            }
+            free(zf);
         }
     }
-    return 0;
+    return failed ? 4 : 0;
 }
 
 /* Backward.
@@ -108,6 +153,8 @@ int mux_oracle_forward(int T, int K, int N,
  *   dA[t] : [K, rank_t]     s_t * sum_i x_i^T q_i
  *   dB[t] : [rank_t, N]     s_t * sum_i h_i^T g_i
  *   dL[t] : [n_cols]        sum_i g_i * z_i   on the sampled output columns `cols`
+ * Additive kind (D in the A slot, U in the B slot), per row: a = gelu(u), p = s_t (g U_t^T) * gelu'(u),
+ *   dX = (g + p D_t^T) W^T,   G = p,   dA[t] : [N, rank_t] = sum_i z_i^T p_i,   dB[t] : [rank_t, N] = s_t sum_i a_i^T g_i
  * Gradient outputs are overwritten.  Entries of dA/dB/dL may be NULL to skip a task. */
 int mux_oracle_backward(int T, int K, int N,
                         const float* X, const float* dY, const float* W, const int32_t* row_task,
@@ -122,13 +169,19 @@ int mux_oracle_backward(int T, int K, int N,
     for (int i = 0; i < T; ++i) {
         int t = row_task[i];
         if (t >= n_tasks) return 2;
-        if (t >= 0 && kind[t] == KIND_LORA && (rank[t] > r_max || rank[t] < 0 || rank[t] > MAX_RANK))
+        if (t >= 0 && has_rank(kind[t]) && (rank[t] > r_max || rank[t] < 0 || rank[t] > MAX_RANK))
             return 3;
     }
-    /* per-row quantities h = x A_t and q = g B_t^T, kept in full */
+    /* per-row quantities h = x A_t and q = g B_t^T (additive kind: a and p), kept in full */
     double* Hf = (double*)calloc((size_t)(T > 0 ? T : 1) * (r_max > 0 ? r_max : 1), sizeof(double));
     double* Qf = (double*)calloc((size_t)(T > 0 ? T : 1) * (r_max > 0 ? r_max : 1), sizeof(double));
     if (!Hf || !Qf) { free(Hf); free(Qf); return 4; }
+    /* z = x W of the additive kind's rows, every column (its D gradient contracts z with p) */
+    int any_adapter = 0;
+    for (int t = 0; t < n_tasks; ++t) any_adapter |= kind[t] == KIND_ADAPTER;
+    double* Zf = any_adapter ? (double*)calloc((size_t)(T > 0 ? T : 1) * N, sizeof(double)) : NULL;
+    if (any_adapter && !Zf) { free(Hf); free(Qf); return 4; }
+    int failed = 0;
 
 #pragma omp parallel for schedule(dynamic, 4)
     for (int i = 0; i < T; ++i) {
@@ -161,6 +214,36 @@ int mux_oracle_backward(int T, int K, int N,
                 for (int j = 0; j < r; ++j) u += q[j] * (double)At[(size_t)k * r + j];
                 dx[c] = s + scale[t] * u;
             }
+        } else if (kind[t] == KIND_ADAPTER) {
+            const int r = rank[t];
+            const float* Dt = A[t];
+            const float* Ut = B[t];
+            double* zf = Zf + (size_t)i * N;
+            double* a = Hf + (size_t)i * r_max;
+            double* pp = Qf + (size_t)i * r_max;
+            double* dz = (double*)malloc(sizeof(double) * (size_t)N);
+            if (!dz) { failed = 1; continue; }
+            full_row_times_w(x, W, K, N, zf);
+            for (int j = 0; j < r; ++j) {
+                double u = 0.0;                              /* u = z D_t */
+                for (int n = 0; n < N; ++n) u += zf[n] * (double)Dt[(size_t)n * r + j];
+                double da = 0.0;                             /* g U_t^T */
+                for (int n = 0; n < N; ++n) da += (double)g[n] * (double)Ut[(size_t)j * N + n];
+                a[j] = gelu(u);
+                pp[j] = scale[t] * da * gelu_prime(u);
+            }
+            for (int n = 0; n < N; ++n) {                    /* dz = g + p D_t^T */
+                double v = 0.0;
+                for (int j = 0; j < r; ++j) v += pp[j] * (double)Dt[(size_t)n * r + j];
+                dz[n] = (double)g[n] + v;
+            }
+            if (dx) for (int c = 0; c < n_kcols; ++c) {     /* dx = dz W^T */
+                const int k = col_of(kcols, c);
+                double s = 0.0;
+                for (int n = 0; n < N; ++n) s += dz[n] * (double)W[(size_t)k * N + n];
+                dx[c] = s;
+            }
+            free(dz);
         } else if (kind[t] == KIND_IA3) {                   /* dx = (g * l_t) W^T */
             const float* l = L[t];
             if (dx) for (int c = 0; c < n_kcols; ++c) {
@@ -222,6 +305,42 @@ int mux_oracle_backward(int T, int K, int N,
                         for (int n = n0; n < n1; ++n) db[(size_t)j * N + n] *= scale[t];
                 }
             }
+        } else if (kind[t] == KIND_ADAPTER) {
+            const int r = rank[t];
+            if (dA && dA[t]) {                              /* dD_t = sum_i z_i^T p_i   [N, r] */
+                double* dd = dA[t];
+#pragma omp parallel for schedule(static)
+                for (int n0 = 0; n0 < N; n0 += 64) {
+                    const int n1 = n0 + 64 < N ? n0 + 64 : N;
+                    for (int n = n0; n < n1; ++n)
+                        for (int j = 0; j < r; ++j) dd[(size_t)n * r + j] = 0.0;
+                    for (int i = 0; i < T; ++i) {
+                        if (row_task[i] != t) continue;
+                        const double* zf = Zf + (size_t)i * N;
+                        const double* pp = Qf + (size_t)i * r_max;
+                        for (int n = n0; n < n1; ++n)
+                            for (int j = 0; j < r; ++j) dd[(size_t)n * r + j] += zf[n] * pp[j];
+                    }
+                }
+            }
+            if (dB && dB[t]) {                              /* dU_t = s_t sum_i a_i^T g_i   [r, N] */
+                double* du = dB[t];
+#pragma omp parallel for schedule(static)
+                for (int n0 = 0; n0 < N; n0 += 256) {
+                    const int n1 = n0 + 256 < N ? n0 + 256 : N;
+                    for (int j = 0; j < r; ++j)
+                        for (int n = n0; n < n1; ++n) du[(size_t)j * N + n] = 0.0;
+                    for (int i = 0; i < T; ++i) {
+                        if (row_task[i] != t) continue;
+                        const double* a = Hf + (size_t)i * r_max;
+                        const float* g = dY + (size_t)i * N;
+                        for (int j = 0; j < r; ++j)
+                            for (int n = n0; n < n1; ++n) du[(size_t)j * N + n] += a[j] * (double)g[n];
+                    }
+                    for (int j = 0; j < r; ++j)
+                        for (int n = n0; n < n1; ++n) du[(size_t)j * N + n] *= scale[t];
+                }
+            }
         } else if (kind[t] == KIND_IA3) {
             if (dL && dL[t]) {                              /* dl_t = sum_i g_i * z_i,  z = x W */
                 double* dl = dL[t];
@@ -248,7 +367,8 @@ int mux_oracle_backward(int T, int K, int N,
     }
     free(Hf);
     free(Qf);
-    return 0;
+    free(Zf);
+    return failed ? 4 : 0;
 }
 
 int mux_oracle_max_threads(void)

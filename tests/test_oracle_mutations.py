@@ -26,6 +26,15 @@ MUTATIONS = {
                                     "                    for (int i = 0; i < T; ++i) {\n                        if (row_task[i] < 0) continue;\n                        const float* x = X + (size_t)i * K;\n                        const double* q"),
     "dl_uses_scaled_output": ("dl[c] += (double)dY[(size_t)i * N + col_of(cols, c)] * z[c - c0];",
                               "dl[c] += (double)dY[(size_t)i * N + col_of(cols, c)] * z[c - c0] * (double)L[t][col_of(cols, c)];"),
+    "additive_forward_drops_scale": ("y[c] += scale[t] * v;", "y[c] += v;"),
+    "additive_forward_without_activation": ("for (int j = 0; j < r; ++j) aa[j] = gelu(uu[j]);", "for (int j = 0; j < r; ++j) aa[j] = uu[j];"),
+    "additive_backward_drops_activation_slope": ("pp[j] = scale[t] * da * gelu_prime(u);", "pp[j] = scale[t] * da;"),
+    "additive_backward_forgets_residual": ("dz[n] = (double)g[n] + v;", "dz[n] = v;"),
+    "additive_dD_uses_activation_instead_of_z": ("for (int j = 0; j < r; ++j) dd[(size_t)n * r + j] += zf[n] * pp[j];",
+                                                 "for (int j = 0; j < r; ++j) dd[(size_t)n * r + j] += (double)dY[(size_t)i * N + n] * pp[j];"),
+    "additive_dU_without_scale": ("for (int n = n0; n < n1; ++n) du[(size_t)j * N + n] *= scale[t];", ";"),
+    "gelu_slope_misses_density_term": ("return 0.5 * (1.0 + erf(u * 0.70710678118654752440)) + u * exp(-0.5 * u * u) * 0.39894228040143267794;",
+                                       "return 0.5 * (1.0 + erf(u * 0.70710678118654752440));"),
     "q_contracts_over_wrong_operand": ("for (int n = 0; n < N; ++n) u += (double)g[n] * (double)Bt[(size_t)j * N + n];\n                q[j] = u;",
                                        "for (int n = 0; n < N; ++n) u += (double)g[n] * (double)Bt[(size_t)j * N + n];\n                q[j] = u * 0.5;"),
 }
@@ -39,7 +48,7 @@ def _build(tmp_path, name, old, new):
     c = tmp_path / f"{name}.c"
     so = tmp_path / f"{name}.so"
     c.write_text(src)
-    subprocess.check_call(["gcc", "-O1", "-fopenmp", "-shared", "-fPIC", "-o", str(so), str(c)])
+    subprocess.check_call(["gcc", "-O1", "-fopenmp", "-shared", "-fPIC", "-o", str(so), str(c), "-lm"])
     return str(so)
 
 

@@ -332,3 +332,163 @@ def test_thread_count_does_not_change_results():
         env = dict(os.environ, OMP_NUM_THREADS=n)
         outs.append(subprocess.check_output([sys.executable, "-c", code], env=env).strip())
     assert outs[0] == outs[1]
+
+
+# ----------------------------------------------------------------- additive bottleneck kind
+
+def adapter_problem(seed=0, K=12, N=10, c=4, bf16=True):
+    """One additive-bottleneck task between a LoRA task and a plain one, ragged padding."""
+    tasks = [wlm.Task(wlm.KIND_LORA, 3, 2.0, [5]),
+             wlm.Task(wlm.KIND_ADAPTER, 4, 1.5, [6, 3]),
+             wlm.Task(wlm.KIND_NONE, 0, 1.0, [2]),
+             wlm.Task(wlm.KIND_ADAPTER, 2, 0.5, [5])]
+    wl = wlm.Workload(name=f"adp{seed}", layers=[("w", K, N)], tasks=tasks, chunk=c, sigma_w=0.5, sigma_ab=0.5)
+    st = segtab.build([t.seq_lens for t in tasks], c)
+    lt = wlm.layer_tensors(wl, 0, st.T, seed=seed, bf16=bf16)
+    return wl, st, lt
+
+
+def test_adapter_hand_worked_row():
+    """One token, K = 2, N = 2, r = 1, numbers a pencil can follow: z = x W = (1, 2);
+    u = z D = 1*0.5 + 2*0.25 = 1; gelu(1) = (1 + erf(1/sqrt 2))/2 = Phi(1), the standard normal cdf at 1
+    (0.8413447460685429, a tabulated constant); y = z + s gelu(u) U = (1 + 2*Phi(1)*1, 2 + 2*Phi(1)*(-1)).
+    Backward with g = (1, 1): g U^T = 0, so p = 0, dX = g W^T = (1*1 + 1*0, 1*0 + 1*2) = (1, 2),
+    dD = 0, dU = s gelu(u) g = (2 Phi(1), 2 Phi(1)).  A wrong aggregate, a dropped scale, D and U exchanged
+    or a transposed W changes one of these."""
+    phi1 = 0.8413447460685429
+    X = np.array([[1.0, 1.0]], dtype=np.float32)
+    W = np.array([[1.0, 0.0], [0.0, 2.0]], dtype=np.float32)
+    D = np.array([[0.5], [0.25]], dtype=np.float32)
+    U = np.array([[1.0, -1.0]], dtype=np.float32)
+    dY = np.array([[1.0, 1.0]], dtype=np.float32)
+    rt = np.array([0], dtype=np.int32)
+    f = oracle.forward(X, W, rt, [wlm.KIND_ADAPTER], [1], [2.0], [D], [U], [None])
+    assert np.allclose(f["Y"], [[1 + 2 * phi1, 2 - 2 * phi1]], rtol=0, atol=1e-15)
+    assert np.allclose(f["H"], [[1.0]], rtol=0, atol=0)
+    b = oracle.backward(X, dY, W, rt, [wlm.KIND_ADAPTER], [1], [2.0], [D], [U], [None])
+    assert np.allclose(b["dX"], [[1.0, 2.0]], rtol=0, atol=1e-15)
+    assert np.allclose(b["dA"][0], [[0.0], [0.0]], rtol=0, atol=1e-15)
+    assert np.allclose(b["dB"][0], [[2 * phi1, 2 * phi1]], rtol=0, atol=1e-15)
+    # second output gradient, g = (1, 0): g U^T = 1, p = s * 1 * gelu'(1), gelu'(1) = Phi(1) + pdf(1),
+    # pdf(1) = exp(-1/2)/sqrt(2 pi) = 0.24197072451914337; dz = g + p D^T; dX = dz W^T = (dz0, 2 dz1); dD = z^T p
+    gp = phi1 + 0.24197072451914337
+    dY2 = np.array([[1.0, 0.0]], dtype=np.float32)
+    b = oracle.backward(X, dY2, W, rt, [wlm.KIND_ADAPTER], [1], [2.0], [D], [U], [None])
+    p = 2.0 * gp
+    assert np.allclose(b["G"], [[p]], rtol=1e-15, atol=0)
+    assert np.allclose(b["dX"], [[1 + p * 0.5, 2 * (p * 0.25)]], rtol=1e-15, atol=0)
+    assert np.allclose(b["dA"][0], [[1 * p], [2 * p]], rtol=1e-15, atol=0)
+    assert np.allclose(b["dB"][0], [[2 * phi1, 0.0]], rtol=1e-15, atol=0)
+
+
+def test_adapter_zero_up_projection_is_plain_gemm():
+    """U = 0: the bottleneck adds nothing, Y = X W, dX = dY W^T, dD = 0 (numpy matmul as the routine)."""
+    wl, st, lt = adapter_problem(seed=1)
+    for t, task in enumerate(wl.tasks):
+        if task.kind == wlm.KIND_ADAPTER:
+            lt.B[t][:] = 0
+    f = run_fwd(wl, st, lt); b = run_bwd(wl, st, lt)
+    X64, W64, g64 = lt.X.astype(np.float64), lt.W.astype(np.float64), lt.dY.astype(np.float64)
+    for t, task in enumerate(wl.tasks):
+        if task.kind != wlm.KIND_ADAPTER:
+            continue
+        rows = st.row_task == t
+        assert np.allclose(f["Y"][rows], X64[rows] @ W64, rtol=1e-13, atol=1e-13)
+        assert np.allclose(b["dX"][rows], g64[rows] @ W64.T, rtol=1e-13, atol=1e-13)
+        assert np.all(b["dA"][t] == 0)
+
+
+def test_adapter_zero_down_projection():
+    """D = 0: u = 0, gelu(0) = 0, so Y = X W and dU = 0; gelu'(0) = 1/2, so p = s/2 g U^T,
+    dD = (X W)^T p and dX = dY W^T (p D^T vanishes) -- all through numpy matmul."""
+    wl, st, lt = adapter_problem(seed=2)
+    for t, task in enumerate(wl.tasks):
+        if task.kind == wlm.KIND_ADAPTER:
+            lt.A[t][:] = 0
+    f = run_fwd(wl, st, lt); b = run_bwd(wl, st, lt)
+    X64, W64, g64 = lt.X.astype(np.float64), lt.W.astype(np.float64), lt.dY.astype(np.float64)
+    for t, task in enumerate(wl.tasks):
+        if task.kind != wlm.KIND_ADAPTER:
+            continue
+        rows = st.row_task == t
+        z = X64[rows] @ W64
+        assert np.allclose(f["Y"][rows], z, rtol=1e-13, atol=1e-13)
+        assert np.all(b["dB"][t] == 0)
+        p = 0.5 * task.scale * (g64[rows] @ lt.B[t].astype(np.float64).T)
+        assert np.allclose(b["dA"][t], z.T @ p, rtol=1e-12, atol=1e-12)
+        assert np.allclose(b["dX"][rows], g64[rows] @ W64.T, rtol=1e-13, atol=1e-13)
+
+
+def test_adapter_large_preactivation_is_linear():
+    """For u >> 0, gelu(u) = u to double precision: the bottleneck becomes the linear low-rank
+    update z -> z + s (z D) U, i.e. Y = X W (I + s D U) -- the merged closed form through numpy."""
+    K, N, r = 6, 5, 2
+    rng = np.random.default_rng(5)
+    X = np.abs(rng.standard_normal((7, K))).astype(np.float32) + 1
+    W = np.abs(rng.standard_normal((K, N))).astype(np.float32) + 1
+    D = (np.abs(rng.standard_normal((N, r))) * 4 + 4).astype(np.float32)      # u in the hundreds
+    U = rng.standard_normal((r, N)).astype(np.float32)
+    dY = rng.standard_normal((7, N)).astype(np.float32)
+    rt = np.zeros(7, dtype=np.int32)
+    f = oracle.forward(X, W, rt, [wlm.KIND_ADAPTER], [r], [0.75], [D], [U], [None])
+    b = oracle.backward(X, dY, W, rt, [wlm.KIND_ADAPTER], [r], [0.75], [D], [U], [None])
+    M = np.eye(N) + 0.75 * D.astype(np.float64) @ U.astype(np.float64)
+    Wm = W.astype(np.float64) @ M
+    assert np.min(f["H"]) > 40
+    assert np.allclose(f["Y"], X.astype(np.float64) @ Wm, rtol=1e-13, atol=0)
+    assert np.allclose(b["dX"], dY.astype(np.float64) @ Wm.T, rtol=1e-13, atol=0)
+    z = X.astype(np.float64) @ W.astype(np.float64)
+    assert np.allclose(b["dB"][0], 0.75 * (z @ D.astype(np.float64)).T @ dY.astype(np.float64), rtol=1e-13, atol=0)
+    assert np.allclose(b["dA"][0], 0.75 * z.T @ (dY.astype(np.float64) @ U.astype(np.float64).T), rtol=1e-13, atol=0)
+
+
+def test_adapter_finite_differences():
+    """L = sum(Y * dY) is linear in U (exact central difference) and smooth in X and D:
+    a central difference with step h has error O(h^2) and must agree to 1e-6 relative."""
+    wl, st, lt = adapter_problem(seed=3, bf16=False)
+    b = run_bwd(wl, st, lt)
+    rng = np.random.default_rng(11)
+    h = 2.0 ** -9
+
+    def fd(arr, idx, step):
+        old = arr[idx]
+        arr[idx] = np.float32(old + step); lp = _loss(wl, st, lt)
+        arr[idx] = np.float32(old - step); lm = _loss(wl, st, lt)
+        hp = float(np.float32(old + step)) - float(np.float32(old - step))
+        arr[idx] = old
+        return (lp - lm) / hp
+
+    for t, task in enumerate(wl.tasks):
+        if task.kind != wlm.KIND_ADAPTER:
+            continue
+        rows = np.nonzero(st.row_task == t)[0]
+        for _ in range(6):
+            i = int(rng.choice(rows)); k = int(rng.integers(0, lt.K))
+            g = fd(lt.X, (i, k), h)
+            assert abs(g - b["dX"][i, k]) <= 2e-5 * max(1.0, abs(g)), (g, b["dX"][i, k])
+            n = int(rng.integers(0, lt.N)); j = int(rng.integers(0, task.rank))
+            g = fd(lt.A[t], (n, j), h)
+            assert abs(g - b["dA"][t][n, j]) <= 2e-5 * max(1.0, abs(g)), (g, b["dA"][t][n, j])
+            g = fd(lt.B[t], (j, n), 2.0 ** -6)
+            assert abs(g - b["dB"][t][j, n]) <= 1e-9 * max(1.0, abs(g))
+
+
+def test_adapter_isolation_and_padding():
+    """The additive task alone gives bit-identical rows and gradients; NaN in other tasks' rows and in
+    padding rows changes nothing (section 3.2)."""
+    wl, st, lt = adapter_problem(seed=4)
+    f = run_fwd(wl, st, lt); b = run_bwd(wl, st, lt)
+    t = 1
+    rows = st.row_task == t
+    rt = np.where(rows, 0, -1).astype(np.int32)
+    f1 = oracle.forward(lt.X, lt.W, rt, [wl.tasks[t].kind], [wl.tasks[t].rank], [wl.tasks[t].scale], [lt.A[t]], [lt.B[t]], [None])
+    b1 = oracle.backward(lt.X, lt.dY, lt.W, rt, [wl.tasks[t].kind], [wl.tasks[t].rank], [wl.tasks[t].scale], [lt.A[t]], [lt.B[t]], [None])
+    assert np.array_equal(f1["Y"][rows], f["Y"][rows]) and np.array_equal(b1["dX"][rows], b["dX"][rows])
+    assert np.array_equal(b1["dA"][0], b["dA"][t]) and np.array_equal(b1["dB"][0], b["dB"][t])
+    lt2 = wlm.layer_tensors(wl, 0, st.T, seed=4)
+    lt2.X[~rows] = np.nan; lt2.dY[~rows] = np.nan
+    f2 = run_fwd(wl, st, lt2); b2 = run_bwd(wl, st, lt2)
+    assert np.array_equal(f2["Y"][rows], f["Y"][rows]) and np.array_equal(b2["dX"][rows], b["dX"][rows])
+    assert np.array_equal(b2["dA"][t], b["dA"][t]) and np.array_equal(b2["dB"][t], b["dB"][t])
+    pad = st.row_task < 0
+    assert np.all(f2["Y"][pad] == 0) and np.all(b2["dX"][pad] == 0)
