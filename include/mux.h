@@ -44,8 +44,16 @@ typedef enum {
 
 /* Adapter kinds.  LORA: y = x W + s (x A) B (sections 2.1, 2.2; aggregate = add, 3.4.3).
  * IA3_OUT: y = (x W) * l, a per-task elementwise output scale (aggregate = multiply).
+ * TUNING: the additive type of section 2.1 (Adapter-Tuning, one of the three implemented types of
+ * section 5), a bottleneck inserted after the BaseOp: z = x W, y = z + s gelu(z D) U with D [N, r],
+ * U [r, N] and gelu(u) = u/2 (1 + erf(u / sqrt 2)).  D is passed in the A slot, U in the B slot.
  * NONE: y = x W. */
-typedef enum { MUX_ADAPTER_NONE = 0, MUX_ADAPTER_LORA = 1, MUX_ADAPTER_IA3_OUT = 2 } mux_adapter_kind;
+typedef enum {
+  MUX_ADAPTER_NONE = 0,
+  MUX_ADAPTER_LORA = 1,
+  MUX_ADAPTER_IA3_OUT = 2,
+  MUX_ADAPTER_TUNING = 3
+} mux_adapter_kind;
 
 /* Storage type of activations, weights and adapters.  BF16: bfloat16 storage, fp32
  * accumulation on the matrix cores.  F32: fp32 storage and arithmetic (a correctness mode).
@@ -58,8 +66,8 @@ typedef enum { MUX_DT_BF16 = 0, MUX_DT_F32 = 1 } mux_dtype;
 /* One fine-tuning task: its adapter type and the sequence lengths of its batch (host). */
 typedef struct {
   int32_t kind;            /* mux_adapter_kind                                              */
-  int32_t rank;            /* LORA: 1..MUX_MAX_RANK; ignored otherwise                      */
-  float scale;             /* LORA: s_t; ignored otherwise                                  */
+  int32_t rank;            /* LORA, TUNING: 1..MUX_MAX_RANK; ignored otherwise              */
+  float scale;             /* LORA, TUNING: s_t; ignored otherwise                          */
   int32_t n_seqs;          /* may be 0 (a task with no tokens has no rows, zero gradients)  */
   const int32_t* seq_lens; /* host, n_seqs entries, each >= 1                               */
 } mux_task_desc;
@@ -122,21 +130,23 @@ typedef struct {
   const void* W;         /* device, [K, ldw] row-major, frozen                              */
   int64_t ldw;           /* elements between rows of W, >= N                                */
   int32_t n_tasks;       /* must equal the table's                                          */
-  const void* const* A;  /* host array of device pointers, LORA: A_t[K, r_t]                */
-  const void* const* B;  /* LORA: B_t[r_t, N]                                               */
+  const void* const* A;  /* host array of device pointers, LORA: A_t[K, r_t]; TUNING: D_t[N, r_t] */
+  const void* const* B;  /* LORA: B_t[r_t, N]; TUNING: U_t[r_t, N]                          */
   const void* const* L;  /* IA3_OUT: l_t[N]                                                 */
 } mux_layer_desc;
 
 #define MUX_LAYER_REFERENCE_KERNELS 1u /* run the plain (non matrix-core) HIP kernels       */
 
-/* Bytes of `saved` (forward -> backward: scaled adapter activations s_t (x A_t), and x W of
- * IA3_OUT rows) and of `ws` (scratch, contents undefined between calls). */
+/* Bytes of `saved` (forward -> backward: scaled adapter activations s_t (x A_t); x W of the
+ * IA3_OUT and TUNING rows; the pre-activations z D_t of the TUNING rows) and of `ws` (scratch,
+ * contents undefined between calls). */
 size_t mux_lora_saved_bytes(const mux_layer_desc* layer, const mux_segtab* st);
 size_t mux_lora_workspace_bytes(const mux_layer_desc* layer, const mux_segtab* st);
 
 /* Forward (Eq. 1 + adapters + aggregate):  for row i of task t
  *     Y_i = x_i W + s_t (x_i A_t) B_t      (LORA)
  *     Y_i = (x_i W) * l_t                  (IA3_OUT)
+ *     Y_i = z_i + s_t gelu(z_i D_t) U_t ,  z_i = x_i W        (TUNING)
  *     Y_i = x_i W                          (NONE)
  * Padding rows: their X content is ignored (never multiplied) and Y_i = 0.
  * X: device [T,K]; Y: device [T,N]; saved: device, mux_lora_saved_bytes, may be NULL only if
@@ -149,6 +159,9 @@ mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_segtab* st,
  *     dX_i = g_i W^T + s_t (g_i B_t^T) A_t^T ,  dA_t = s_t sum_i x_i^T (g_i B_t^T) ,
  *     dB_t = s_t sum_i (x_i A_t)^T g_i                                        (LORA)
  *     dX_i = (g_i * l_t) W^T ,  dl_t = sum_i g_i * (x_i W)                    (IA3_OUT)
+ *     p_i = s_t (g_i U_t^T) * gelu'(z_i D_t) ,  dX_i = (g_i + p_i D_t^T) W^T ,
+ *     dD_t = sum_i z_i^T p_i  (returned in dA[t], [N,r_t]) ,
+ *     dU_t = s_t sum_i gelu(z_i D_t)^T g_i  (returned in dB[t], [r_t,N])      (TUNING)
  *     dX_i = g_i W^T                                                          (NONE)
  * sums over the rows of task t only.  dX of padding rows = 0.  No gradient of W.
  * dA, dB, dL: host arrays of n_tasks device pointers to fp32 buffers ([K,r_t], [r_t,N], [N]);

@@ -14,7 +14,7 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 __all__ = [
-    "MUX_OK", "MUX_ADAPTER_NONE", "MUX_ADAPTER_LORA", "MUX_ADAPTER_IA3_OUT", "MUX_DT_BF16", "MUX_DT_F32",
+    "MUX_OK", "MUX_ADAPTER_NONE", "MUX_ADAPTER_LORA", "MUX_ADAPTER_IA3_OUT", "MUX_ADAPTER_TUNING", "MUX_DT_BF16", "MUX_DT_F32",
     "MUX_SEGTAB_DENSE", "MUX_LAYER_REFERENCE_KERNELS", "MUX_MAX_RANK", "MuxError", "TaskDesc", "LayerDesc", "SegTab",
     "library_path", "load_library", "mux_choose_chunk_size", "mux_segtab_build", "mux_segtab_free",
     "mux_segtab_rows", "mux_segtab_n_chunks", "mux_segtab_n_tasks", "mux_segtab_valid_tokens",
@@ -24,7 +24,7 @@ __all__ = [
 ]
 
 MUX_OK = 0
-MUX_ADAPTER_NONE, MUX_ADAPTER_LORA, MUX_ADAPTER_IA3_OUT = 0, 1, 2
+MUX_ADAPTER_NONE, MUX_ADAPTER_LORA, MUX_ADAPTER_IA3_OUT, MUX_ADAPTER_TUNING = 0, 1, 2, 3
 MUX_DT_BF16, MUX_DT_F32 = 0, 1
 MUX_SEGTAB_DENSE = 1
 MUX_LAYER_REFERENCE_KERNELS = 1

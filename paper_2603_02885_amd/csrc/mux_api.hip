@@ -62,8 +62,8 @@ __global__ __launch_bounds__(256) void k_fill_tasks(const int32_t* __restrict__ 
 __global__ __launch_bounds__(256) void k_zero_grads(const DevTask* __restrict__ tasks, int K, int N) {
   const DevTask tk = tasks[blockIdx.x];
   const size_t e = (size_t)blockIdx.y * 256 + threadIdx.x;
-  if (tk.kind == MUX_ADAPTER_LORA) {
-    if (tk.dA && e < (size_t)K * tk.rank) tk.dA[e] = 0.f;
+  if (tk.kind == MUX_ADAPTER_LORA || tk.kind == MUX_ADAPTER_TUNING) {
+    if (tk.dA && e < (size_t)(tk.kind == MUX_ADAPTER_LORA ? K : N) * tk.rank) tk.dA[e] = 0.f;
     if (tk.dB && e < (size_t)tk.rank * N) tk.dB[e] = 0.f;
   } else if (tk.kind == MUX_ADAPTER_IA3_OUT) {
     if (tk.dL && e < (size_t)N) tk.dL[e] = 0.f;
@@ -75,17 +75,18 @@ namespace {
 struct Layout {
   size_t esz;          // bytes per stored element
   int RP;              // H / G row pitch in elements
-  size_t h_bytes, z_bytes, saved_bytes;
+  size_t h_bytes, z_bytes, u2_bytes, saved_bytes;
   size_t tasks_bytes, g_bytes, at_bytes, dys_bytes, part_bytes, ws_bytes;
 };
 
 Layout make_layout(const mux_layer_desc* L, const mux_segtab* st) {
   Layout o{};
   o.esz = L->dtype == MUX_DT_F32 ? 4 : 2;
-  o.RP = st->n_lora > 0 ? round_up(st->r_max, 16) : 0;
+  o.RP = rank_pitch(st);
   o.h_bytes = align256((size_t)st->T * o.RP * o.esz);
   o.z_bytes = align256((size_t)st->z_rows * (size_t)L->N * o.esz);
-  o.saved_bytes = o.h_bytes + o.z_bytes;
+  o.u2_bytes = st->n_tuning > 0 ? o.h_bytes : 0;
+  o.saved_bytes = o.h_bytes + o.z_bytes + o.u2_bytes;
   o.tasks_bytes = align256((size_t)st->n_tasks * sizeof(DevTask));
   o.g_bytes = o.h_bytes;
   size_t at_elems = 0;
@@ -93,7 +94,7 @@ Layout make_layout(const mux_layer_desc* L, const mux_segtab* st) {
     if (ht.kind == MUX_ADAPTER_LORA) at_elems += (size_t)round_up(ht.rank, 16) * L->K;
   o.at_bytes = L->dtype == MUX_DT_BF16 ? align256(at_elems * 2) : 0;
   o.part_bytes = L->dtype == MUX_DT_BF16 ? fast_partial_bytes(L->K, L->N, st) : 0;
-  o.dys_bytes = L->dtype == MUX_DT_BF16 ? o.z_bytes : 0;
+  o.dys_bytes = (L->dtype == MUX_DT_BF16 || st->n_tuning > 0) ? o.z_bytes : 0;
   o.ws_bytes = o.tasks_bytes + o.g_bytes + o.at_bytes + o.dys_bytes + o.part_bytes;
   return o;
 }
@@ -110,8 +111,8 @@ mux_status check_layer(const char* fn, const mux_layer_desc* L, const mux_segtab
     return fail(MUX_ERR_SHAPE, std::string(fn) + ": problem too large");
   for (int t = 0; t < st->n_tasks; ++t) {
     const HostTask& ht = st->tasks[t];
-    if (ht.kind == MUX_ADAPTER_LORA && (!L->A || !L->B || !L->A[t] || !L->B[t]))
-      return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": LoRA task without A or B");
+    if ((ht.kind == MUX_ADAPTER_LORA || ht.kind == MUX_ADAPTER_TUNING) && (!L->A || !L->B || !L->A[t] || !L->B[t]))
+      return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": LoRA or Adapter-Tuning task without its two matrices");
     if (ht.kind == MUX_ADAPTER_IA3_OUT && (!L->L || !L->L[t]))
       return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": IA3 task without scale vector");
   }
@@ -134,11 +135,12 @@ void fill_tasks(const mux_layer_desc* L, const mux_segtab* st, const int32_t* dt
     for (int i = 0; i < count; ++i) {
       const int t = base + i;
       const int kind = st->tasks[t].kind;
-      p.A[i] = (kind == MUX_ADAPTER_LORA) ? L->A[t] : nullptr;
-      p.B[i] = (kind == MUX_ADAPTER_LORA) ? L->B[t] : nullptr;
+      const bool ranked = kind == MUX_ADAPTER_LORA || kind == MUX_ADAPTER_TUNING;
+      p.A[i] = ranked ? L->A[t] : nullptr;
+      p.B[i] = ranked ? L->B[t] : nullptr;
       p.L[i] = (kind == MUX_ADAPTER_IA3_OUT) ? L->L[t] : nullptr;
-      p.dA[i] = (kind == MUX_ADAPTER_LORA && dA) ? (float*)dA[t] : nullptr;
-      p.dB[i] = (kind == MUX_ADAPTER_LORA && dB) ? (float*)dB[t] : nullptr;
+      p.dA[i] = (ranked && dA) ? (float*)dA[t] : nullptr;
+      p.dB[i] = (ranked && dB) ? (float*)dB[t] : nullptr;
       p.dL[i] = (kind == MUX_ADAPTER_IA3_OUT && dL) ? (float*)dL[t] : nullptr;
       p.at_off[i] = at_off;
       if (kind == MUX_ADAPTER_LORA) at_off += (int64_t)round_up(st->tasks[t].rank, 16) * L->K;
@@ -172,7 +174,8 @@ extern "C" mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_se
   if (!dev_segtab || !X || !Y || !ws) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": null device pointer");
   const Layout lo = make_layout(layer, st);
   if (ws_bytes < lo.ws_bytes) return fail(MUX_ERR_WORKSPACE, std::string(fn) + ": workspace too small");
-  if (!saved && st->n_lora > 0) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": saved is null but a task is LoRA");
+  if (!saved && (st->n_lora > 0 || st->n_tuning > 0))
+    return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": saved is null but a task is LoRA or Adapter-Tuning");
   hipStream_t stream = (hipStream_t)hip_stream;
   DevTask* dtasks = (DevTask*)ws;
   const bool fast = layer->dtype == MUX_DT_BF16 && !(layer->flags & MUX_LAYER_REFERENCE_KERNELS);
@@ -180,7 +183,8 @@ extern "C" mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_se
   fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, nullptr, nullptr, nullptr, stream,
              (fast && st->n_lora > 0) ? at_region : nullptr);
   CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP,
-            (char*)ws + lo.tasks_bytes + lo.g_bytes, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes, layer->W, stream};
+            (char*)ws + lo.tasks_bytes + lo.g_bytes, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes, layer->W, stream,
+            (saved && lo.u2_bytes) ? (char*)saved + lo.h_bytes + lo.z_bytes : nullptr};
   void* H = saved;
   void* Z = (saved && st->z_rows > 0) ? (char*)saved + lo.h_bytes : nullptr;
   mux_status s;
@@ -202,7 +206,7 @@ extern "C" mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_s
   if (st->T == 0 && st->n_tasks == 0) return MUX_OK;
   if (!dev_segtab || !ws) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": null device pointer");
   if (st->T > 0 && (!X || !dY)) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": null device pointer");
-  if (!saved && st->T > 0 && (st->n_lora > 0 || st->n_ia3 > 0))
+  if (!saved && st->T > 0 && (st->n_lora > 0 || st->n_ia3 > 0 || st->n_tuning > 0))
     return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": saved is null but a task has an adapter");
   const Layout lo = make_layout(layer, st);
   if (ws_bytes < lo.ws_bytes) return fail(MUX_ERR_WORKSPACE, std::string(fn) + ": workspace too small");
@@ -210,7 +214,8 @@ extern "C" mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_s
   DevTask* dtasks = (DevTask*)ws;
   fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, dA, dB, dL, stream, nullptr);
   CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP,
-            (char*)ws + lo.tasks_bytes + lo.g_bytes, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes, layer->W, stream};
+            (char*)ws + lo.tasks_bytes + lo.g_bytes, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes, layer->W, stream,
+            (saved && lo.u2_bytes) ? (char*)saved + lo.h_bytes + lo.z_bytes : nullptr};
   if (st->T == 0) {                 // no rows at all: zero gradients (or leave the accumulators as they are)
     if (!accumulate) {
       const size_t big = (size_t)(st->r_max > 0 ? st->r_max : 1) * (size_t)(layer->K > layer->N ? layer->K : layer->N);

@@ -50,7 +50,7 @@ struct GemmParams {
   int Kc, Nc, RP;
   int n_m, n_n, per_xcd;   // tile grid in units of 256 x TILE_N tiles; workgroups per XCD over the whole grid
   int n_full;              // workgroups that compute full-width tiles (a multiple of 8); the rest compute halves
-  const bf16_t* AinScaled;  // backward: dY * l_t of the IA3_OUT rows, [z_rows, Kc], indexed like the saved x W
+  const bf16_t* AinScaled;  // backward: prepared input rows (IA3_OUT: dY * l_t; TUNING: dY + p D_t^T), [z_rows, Kc], indexed like the saved x W
 };
 
 // Raw buffer descriptor (stride 0) over `bytes` bytes starting at p, as four dwords.
@@ -159,6 +159,7 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   const DevTask tk = p.tasks[it.task];
   const bool lora = tk.kind == MUX_ADAPTER_LORA;
   const bool ia3 = tk.kind == MUX_ADAPTER_IA3_OUT;
+  const bool tuning = tk.kind == MUX_ADAPTER_TUNING;   // forward: only x W is produced here (saved); backward: prepared rows
   const int rank = tk.rank;
   const bf16_t* adapterB = NT ? (const bf16_t*)tk.A : (const bf16_t*)tk.B;
   const bf16_t* Lvec = (const bf16_t*)tk.L;
@@ -172,7 +173,7 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   // (lane -> k-row lane/PPRB, physical piece lane%PPRB).  Loading wave w owns chunks w*ACH .. of A and w*BCH .. of B.
   const int r_in = lane / LPR;                                  // row inside the chunk
   const uint32_t a_rows_bytes = (uint32_t)it.nrows * (uint32_t)p.Kc * 2u;
-  const bf16_t* a_base = (NT && ia3) ? p.AinScaled + (size_t)(tk.zrow0 + it.row0 - tk.row_begin) * p.Kc
+  const bf16_t* a_base = (NT && (ia3 || tuning)) ? p.AinScaled + (size_t)(tk.zrow0 + it.row0 - tk.row_begin) * p.Kc
                                      : p.Ain + (size_t)it.row0 * p.Kc;
   const rsrc_t rA = make_rsrc(a_base, a_rows_bytes);
   const rsrc_t rW = make_rsrc(p.W, (uint32_t)((size_t)(NT ? p.Nc : p.Kc) * p.ldw * 2));
@@ -453,8 +454,9 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   const int e_row = lane / PPR, e_pc = (lane % PPR) * 8;
   const bool scale_out = !NT && ia3;             // IA3 forward: Z = x W is saved first, then Y = Z * l_t
   const int passes = (scale_out && p.Zsave) ? 2 : 1;
+  const bool z_only = !NT && tuning && p.Zsave;  // TUNING forward: x W goes to the saved region, Y is written by the bottleneck kernels
   for (int pass = 0; pass < passes; ++pass) {
-    const bool to_z = pass + 1 < passes;
+    const bool to_z = z_only || pass + 1 < passes;
     bf16_t* dst = to_z ? p.Zsave + (size_t)(tk.zrow0 - tk.row_begin) * p.Nc : p.Out;
     if (scale_out && !to_z) {
 #pragma unroll

@@ -44,6 +44,7 @@ struct GemmParams {
   int Kc, Nc, RP;
   int n_m, n_n, per_xcd;
   int only_ia3;        // process IA3_OUT items only (the pipelined kernel took the rest)
+  const bf16_t* Prep;  // backward: prepared input rows of the TUNING tasks (dY + p D_t^T), [z_rows, Kc], indexed like the saved x W
 };
 
 __device__ __forceinline__ uint4 zero4() { return make_uint4(0, 0, 0, 0); }
@@ -124,6 +125,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm(const GemmParams p) {
   const DevTask tk = p.tasks[it.task];
   const bool lora = tk.kind == MUX_ADAPTER_LORA;
   const bool ia3 = tk.kind == MUX_ADAPTER_IA3_OUT;
+  const bool tuning = tk.kind == MUX_ADAPTER_TUNING;   // forward: only x W is produced here (saved); backward: rows from Prep
   const int rank = tk.rank;
   const bf16_t* adapterB = NT ? (const bf16_t*)tk.A : (const bf16_t*)tk.B;  // the operand paired with Ext
   const bf16_t* Lvec = (const bf16_t*)tk.L;
@@ -151,7 +153,8 @@ __global__ __launch_bounds__(256, 1) void k_gemm(const GemmParams p) {
   const int KT_total = KT + (lora ? 1 : 0);
 
   // buffer resources (byte offsets must stay below 2^31: checked on the host)
-  const rsrc_t rA = make_rsrc(p.Ain + (size_t)it.row0 * p.Kc, (uint32_t)it.nrows * (uint32_t)p.Kc * 2u);
+  const rsrc_t rA = make_rsrc((NT && tuning) ? p.Prep + (size_t)(tk.zrow0 + it.row0 - tk.row_begin) * p.Kc : p.Ain + (size_t)it.row0 * p.Kc,
+                              (uint32_t)it.nrows * (uint32_t)p.Kc * 2u);
   const rsrc_t rW = NT ? make_rsrc(p.W + (size_t)c0 * p.ldw, (uint32_t)((size_t)(p.Nc - c0 < BN ? p.Nc - c0 : BN) * p.ldw * 2))
                        : make_rsrc(p.W + c0, (uint32_t)(((size_t)(p.Kc - 1) * p.ldw + (p.Nc - c0)) * 2));
   const rsrc_t rE = make_rsrc(lora ? p.Ext + (size_t)it.row0 * p.RP : p.Ain, lora ? (uint32_t)it.nrows * (uint32_t)p.RP * 2u : 0u);
@@ -306,8 +309,9 @@ __global__ __launch_bounds__(256, 1) void k_gemm(const GemmParams p) {
     lcol[ni] = (!NT && ia3 && c < p.Nc) ? bf16_to_f32(Lvec[c]) : 1.f;
   }
   const int passes = (!NT && ia3 && p.Zsave) ? 2 : 1;     // IA3 forward also saves x W before the scale
+  const bool z_only = !NT && tuning && p.Zsave;           // TUNING forward: x W goes to the saved region, Y is written later
   for (int pass = 0; pass < passes; ++pass) {
-    const bool to_z = passes == 2 && pass == 0;
+    const bool to_z = z_only || (passes == 2 && pass == 0);
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
@@ -353,6 +357,7 @@ mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t
   if (total == 0) return MUX_OK;
   p.per_xcd = (total + 7) / 8;
   p.only_ia3 = only_ia3;
+  p.Prep = (const bf16_t*)c.dYs;
   MUX_LAUNCH(NT ? (only_ia3 ? "gemm_nt_ia3" : "gemm_nt_regstaged") : "gemm_nn_regstaged", k_gemm<NT>, dim3(p.per_xcd * 8), dim3(256), SMEM_BYTES, c.stream, p);
   return MUX_OK;
 }

@@ -38,7 +38,7 @@ struct DevTask {
   int32_t rank;
   int32_t row_begin;
   int32_t row_count;
-  int32_t zrow0;      // first row of this task inside the saved x W region (IA3_OUT), else -1
+  int32_t zrow0;      // first row of this task inside the saved x W region (IA3_OUT, TUNING), else -1
   int64_t at_off;     // element offset of this task's transposed A_t inside the workspace region
 };
 static_assert(sizeof(DevTask) == 80, "DevTask layout");
@@ -57,7 +57,7 @@ struct mux_segtab {
   int32_t n_tasks = 0, chunk = 0, log2c = 0, n_chunks = 0, T = 0, valid_total = 0;
   int32_t max_pack_len = 0;
   uint32_t flags = 0;
-  int32_t r_max = 0, z_rows = 0, n_lora = 0, n_ia3 = 0;
+  int32_t r_max = 0, z_rows = 0, n_lora = 0, n_ia3 = 0, n_tuning = 0;   // r_max over the LORA and TUNING tasks
   std::vector<int32_t> image;       // canonical serialisation
   std::vector<int32_t> dev_image;   // device image (host copy, source of the upload)
   std::vector<int32_t> row_task;    // T entries
@@ -98,10 +98,15 @@ struct CallCtx {
   int64_t ldw;
   int RP;                  // row pitch (elements) of the H / G buffers
   void* AT;                // workspace: per-task A_t^T [round_up(r_t,16)][K] bf16 (forward, fast path)
-  void* dYs;               // workspace: dY * l_t of the IA3_OUT rows [z_rows][N] bf16 (backward, fast path)
+  void* dYs;               // workspace [z_rows][N]: the backbone backward's input rows of the kinds that change it
+                           // (IA3_OUT: dY * l_t, fast path only; TUNING: dY + p D_t^T)
   const void* W;
   hipStream_t stream;
+  void* U2;                // saved: pre-activations z D_t of the TUNING rows, [T][RP] (null without such tasks)
 };
+
+// H / G row pitch in elements
+inline int rank_pitch(const mux_segtab* st) { return (st->n_lora + st->n_tuning) > 0 ? round_up(st->r_max, 16) : 0; }
 
 // plain (non matrix-core) kernels, both storage types
 mux_status ref_forward(const CallCtx& c, int dtype, const void* X, void* Y, void* H, void* Z);
@@ -110,7 +115,13 @@ mux_status ref_backward(const CallCtx& c, int dtype, const void* X, const void* 
 
 
 // the same plain kernels, step by step (bit mask)
-enum : unsigned { REF_DOWN = 1, REF_FWD = 2, REF_G = 4, REF_DB = 8, REF_DA = 16, REF_DL = 32, REF_DX = 64 };
+enum : unsigned {
+  REF_DOWN = 1, REF_FWD = 2, REF_G = 4, REF_DB = 8, REF_DA = 16, REF_DL = 32, REF_DX = 64,
+  REF_TUNE_DOWN = 128,   // TUNING forward, after z is saved: u = z D_t, Hs = s_t gelu(u)
+  REF_TUNE_UP = 256,     // TUNING forward: Y = z + Hs U_t
+  REF_TUNE_DZ = 512,     // TUNING backward, after Gs: dYs = dY + Gs D_t^T
+  REF_ONLY_TUNING = 1024 // REF_G, REF_DB, REF_DA touch the TUNING tasks only (the LORA ones ran on the matrix cores)
+};
 void ref_steps(const CallCtx& c, int dtype, unsigned which, const void* X, const void* dY, void* Y, void* dX, void* H,
                void* Z, void* G, int accumulate);
 

@@ -53,10 +53,10 @@ extern "C" mux_status mux_segtab_build(const mux_task_desc* tasks, int32_t n_tas
   int64_t total = 0;
   for (int32_t t = 0; t < n_tasks; ++t) {
     const mux_task_desc& d = tasks[t];
-    if (d.kind != MUX_ADAPTER_NONE && d.kind != MUX_ADAPTER_LORA && d.kind != MUX_ADAPTER_IA3_OUT)
+    if (d.kind != MUX_ADAPTER_NONE && d.kind != MUX_ADAPTER_LORA && d.kind != MUX_ADAPTER_IA3_OUT && d.kind != MUX_ADAPTER_TUNING)
       return fail(MUX_ERR_INVALID_ARG, "mux_segtab_build: unknown adapter kind");
-    if (d.kind == MUX_ADAPTER_LORA && (d.rank < 1 || d.rank > MUX_MAX_RANK))
-      return fail(MUX_ERR_INVALID_ARG, "mux_segtab_build: LoRA rank outside 1..MUX_MAX_RANK");
+    if ((d.kind == MUX_ADAPTER_LORA || d.kind == MUX_ADAPTER_TUNING) && (d.rank < 1 || d.rank > MUX_MAX_RANK))
+      return fail(MUX_ERR_INVALID_ARG, "mux_segtab_build: adapter rank outside 1..MUX_MAX_RANK");
     if (d.n_seqs < 0 || (d.n_seqs > 0 && !d.seq_lens)) return fail(MUX_ERR_INVALID_ARG, "mux_segtab_build: bad seq_lens");
     for (int32_t s = 0; s < d.n_seqs; ++s) {
       if (d.seq_lens[s] < 1) return fail(MUX_ERR_INVALID_ARG, "mux_segtab_build: sequence length < 1");
@@ -121,14 +121,19 @@ extern "C" mux_status mux_segtab_build(const mux_task_desc* tasks, int32_t n_tas
       timg.insert(timg.end(), words, words + 8);
       HostTask& ht = st->tasks[t];
       ht.kind = d.kind;
-      ht.rank = d.kind == MUX_ADAPTER_LORA ? d.rank : 0;
-      ht.scale = d.kind == MUX_ADAPTER_LORA ? d.scale : 1.0f;
+      const bool ranked = d.kind == MUX_ADAPTER_LORA || d.kind == MUX_ADAPTER_TUNING;
+      ht.rank = ranked ? d.rank : 0;
+      ht.scale = ranked ? d.scale : 1.0f;
       ht.row_begin = (int32_t)task_row_begin;
       ht.row_count = (int32_t)(cur - task_row_begin);
       ht.valid = (int32_t)valid;
       ht.zrow0 = -1;
-      if (d.kind == MUX_ADAPTER_IA3_OUT) { ht.zrow0 = zrows; zrows += ht.row_count; st->n_ia3++; }
-      if (d.kind == MUX_ADAPTER_LORA) { st->n_lora++; if (d.rank > st->r_max) st->r_max = d.rank; }
+      // x W is kept for the backward pass of the kinds that need it: its rows are numbered task by task
+      if (d.kind == MUX_ADAPTER_IA3_OUT || d.kind == MUX_ADAPTER_TUNING) { ht.zrow0 = zrows; zrows += ht.row_count; }
+      if (d.kind == MUX_ADAPTER_IA3_OUT) st->n_ia3++;
+      if (d.kind == MUX_ADAPTER_TUNING) st->n_tuning++;
+      if (d.kind == MUX_ADAPTER_LORA) st->n_lora++;
+      if (ranked && d.rank > st->r_max) st->r_max = d.rank;
     }
     const int64_t T = (cur + c - 1) / c * c;
     if (T > ((int64_t)1 << 30)) { delete st; return fail(MUX_ERR_SHAPE, "mux_segtab_build: too many rows"); }

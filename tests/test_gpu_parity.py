@@ -98,9 +98,31 @@ def test_kernel_choice_by_shape(env):
     run_case(env, wl, seed=4)
 
 
-def test_accumulate_and_determinism(env):
+def tuning_workload(K=192, N=160, chunk=32):
+    """The additive bottleneck kind between the others: ragged ranks and token counts, padding, an empty task."""
+    tasks = [wlm.Task(wlm.KIND_LORA, 16, 2.0, [100]), wlm.Task(wlm.KIND_ADAPTER, 8, 1.5, [70, 45]),
+             wlm.Task(wlm.KIND_IA3, 0, 1.0, [33]), wlm.Task(wlm.KIND_ADAPTER, 24, 0.5, [150, 21]),
+             wlm.Task(wlm.KIND_NONE, 0, 1.0, [64]), wlm.Task(wlm.KIND_ADAPTER, 64, 1.0, [5]),
+             wlm.Task(wlm.KIND_ADAPTER, 16, 2.0, [])]
+    return wlm.Workload(name="tuning", layers=[("w", K, N)], tasks=tasks, chunk=chunk, sigma_w=0.08, sigma_ab=0.08)
+
+
+@pytest.mark.parametrize("seg_flags", [0, 1])
+@pytest.mark.parametrize("mode", ["bf16", "bf16_ref", "f32"])
+def test_adapter_tuning_kind(env, mode, seg_flags):
+    """Adapter-Tuning tasks (additive bottleneck after the BaseOp) beside LoRA, IA3 and plain tasks, in the three
+    modes; a second shape whose contraction lengths select the other GEMM kernels."""
+    mx, _ = env
+    dtype = mx.MUX_DT_F32 if mode == "f32" else mx.MUX_DT_BF16
+    lf = mx.MUX_LAYER_REFERENCE_KERNELS if mode == "bf16_ref" else 0
+    run_case(env, tuning_workload(), dtype=dtype, seg_flags=seg_flags, layer_flags=lf, seed=5)
+    run_case(env, tuning_workload(K=104, N=232, chunk=16), dtype=dtype, seg_flags=seg_flags, layer_flags=lf, seed=6)
+
+
+@pytest.mark.parametrize("which", ["mixed", "tuning"])
+def test_accumulate_and_determinism(env, which):
     mx, torch = env
-    wl = mixed_workload()
+    wl = mixed_workload() if which == "mixed" else tuning_workload()
     g, got, ref, _ = run_case(env, wl)
     first = {k: [None if t is None else t.clone() for t in getattr(g, k)] for k in ("dA", "dB", "dL")}
     y1, dx1 = g.Y.clone(), g.dX.clone()
@@ -117,14 +139,15 @@ def test_accumulate_and_determinism(env):
             assert a is None or torch.allclose(b, 2 * a, rtol=1e-6, atol=0)
 
 
-def test_nan_isolation(env):
+@pytest.mark.parametrize("which", ["mixed", "tuning"])
+def test_nan_isolation(env, which):
     """Poisoning one task's rows, adapters and every padding row with NaN/Inf leaves the other
     tasks' outputs and gradients bit-identical (section 3.2)."""
     mx, torch = env
-    wl = mixed_workload()
+    wl = mixed_workload() if which == "mixed" else tuning_workload()
     g, got, _, _ = run_case(env, wl)
     ot = oracle_table(wl)
-    j = 2
+    j = 2 if which == "mixed" else 3          # a LoRA task / an Adapter-Tuning task
     rows = torch.from_numpy(ot.task_rows[j]).to("cuda:0")
     pad = torch.from_numpy(np.nonzero(ot.row_task < 0)[0]).to("cuda:0")
     g.X[rows] = float("nan"); g.dY[rows] = float("inf")
