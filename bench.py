@@ -27,7 +27,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", type=int, default=1, help="index into BASELINE.json configs (default 1: LLaMA-7B shapes)")
+    ap.add_argument("--workload", type=int, default=1,
+                    help="index into BASELINE.json configs (default 1: LLaMA-7B shapes); 5 = those shapes with two Adapter-Tuning tasks")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -60,8 +61,9 @@ def setup(mx, torch, wl, seed):
         L = LayerState()
         L.name, L.K, L.N = name, K, N
         L.W = randn((K, N), 0.02)
-        L.A = [randn((K, t.rank), 0.02) if t.kind == 1 else None for t in wl.tasks]
-        L.B = [randn((t.rank, N), 0.02) if t.kind == 1 else None for t in wl.tasks]
+        # LoRA: A [K, r], B [r, N]; Adapter-Tuning: D [N, r] in the A slot, U [r, N] in the B slot
+        L.A = [randn((K if t.kind == 1 else N, t.rank), 0.02) if t.kind in (1, 3) else None for t in wl.tasks]
+        L.B = [randn((t.rank, N), 0.02) if t.kind in (1, 3) else None for t in wl.tasks]
         L.L = [randn((N,), 0.02, 1.0) if t.kind == 2 else None for t in wl.tasks]
         L.X = randn((T, K))
         L.dY = randn((T, N))
@@ -169,8 +171,10 @@ def main():
     task_rows = [int(img[16 + 8 * t + 1]) for t in range(M)]           # aligned rows per task
     sum_tr = sum(task_rows[t] * wl.tasks[t].rank for t in range(M) if wl.tasks[t].kind == 1)
     ia3_rows = sum(task_rows[t] for t in range(M) if wl.tasks[t].kind == 2)
+    tune_rows = sum(task_rows[t] for t in range(M) if wl.tasks[t].kind == 3)
+    sum_tune = sum(task_rows[t] * wl.tasks[t].rank for t in range(M) if wl.tasks[t].kind == 3)
     flops_backbone = 4.0 * T * sumKN
-    flops_adapter = 6.0 * sum_tr * sum(K + N for _, K, N in wl.layers)
+    flops_adapter = 6.0 * sum_tr * sum(K + N for _, K, N in wl.layers) + 12.0 * sum_tune * sum(N for _, K, N in wl.layers)
     gemm_flops = {  # per step, per kernel family (all layers): 2TKN + 2 sum T_t r_t N (fwd) / K (bwd)
         "gemm_nn": 2.0 * T * sumKN + 2.0 * sum_tr * sum(N for _, K, N in wl.layers),
         "gemm_nt": 2.0 * T * sumKN + 2.0 * sum_tr * sum(K for _, K, N in wl.layers),
@@ -190,6 +194,12 @@ def main():
         "down_g": sum(2.0 * T * N + 2.0 * N * sum_r + 2.0 * T * RP for _, K, N in wl.layers),
         "grad_dbda": sum(2.0 * T * (N + K) + 4.0 * T * RP + 4.0 * (N + K) * sum_r for _, K, N in wl.layers),
         "grad_dl": sum(4.0 * ia3_rows * N for _, K, N in wl.layers),
+        # Adapter-Tuning steps: each streams the task's rows of z, dY or both once
+        "tune_down": sum(2.0 * tune_rows * N for _, K, N in wl.layers),
+        "tune_up": sum(4.0 * tune_rows * N for _, K, N in wl.layers),
+        "tune_g": sum(2.0 * tune_rows * N for _, K, N in wl.layers),
+        "tune_dz": sum(4.0 * tune_rows * N for _, K, N in wl.layers),
+        "tune_grads": sum(4.0 * tune_rows * N for _, K, N in wl.layers),
     }
     for n, b in stream_bytes.items():
         if n in kernels and kernels[n]["total_ms_per_step"] > 0:

@@ -108,7 +108,7 @@ def _llama_layers(h: int, mlp: int) -> List[Tuple[str, int, int]]:
 
 
 def config(idx: int, seed: int = 0) -> Workload:
-    """The five benchmark workloads (index 0..4)."""
+    """The five benchmark workloads (index 0..4), and an extra one for the additive kind (5)."""
     if idx == 0:
         return Workload(
             name="tiny", layers=[("w", 256, 256)], chunk=64,
@@ -155,6 +155,15 @@ def config(idx: int, seed: int = 0) -> Workload:
         return Workload(
             name="llama70b_tp8_share", layers=layers, chunk=1024, tasks=tasks,
             notes="32 LoRA r16 tasks, 32768 tokens lognormal(512), chunk 1024, 1/8 TP shard shapes")
+    if idx == 5:
+        # not one of the benchmark configs: the LLaMA-7B shapes with two of the four tasks switched to the additive
+        # bottleneck kind (bottleneck width 64, the usual size of that method), to measure that kind's kernels
+        kinds = (KIND_LORA, KIND_ADAPTER, KIND_LORA, KIND_ADAPTER)
+        tasks = [Task(k, 16 if k == KIND_LORA else 64, 2.0 if k == KIND_LORA else 1.0, [n])
+                 for k, n in zip(kinds, (2048, 1536, 1024, 512))]
+        return Workload(
+            name="llama7b_tuning", layers=_llama_layers(4096, 11008), chunk=512, tasks=tasks,
+            notes="2 LoRA r16 + 2 Adapter-Tuning r64 tasks, 5120 tokens, chunk 512")
     raise ValueError(f"no config {idx}")
 
 

@@ -44,14 +44,26 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast
 // on this memory system), two slabs ahead in registers, pass through a wave-private LDS region in their natural
 // layout and come back in the 16x16x32 MFMA operand layout.  No workgroup barrier in the loop.  The partial sums
 // of the waves are combined through LDS in a fixed order.
+//   DOWN_X     LoRA items: Out = s_t X A_t (P_t = A_t^T from the transposed region); rows of other kinds: zero
+//   DOWN_G     LoRA items: Out = s_t dY B_t^T; TUNING items: Out = s_t (dY U_t^T) * gelu'(u), u from U2;
+//              rows of other kinds: zero
+//   DOWN_TUNE  TUNING items only (other rows are left alone): u = z D_t with z from the saved compact rows and
+//              P_t = D_t^T from the transposed region; U2 = u, Out = s_t gelu(u)
+enum : int { DOWN_X = 0, DOWN_G = 1, DOWN_TUNE = 2 };
 struct DownParams {
   const int32_t* dtab;
   const DevTask* tasks;
-  const bf16_t* In;    // [T, C]
+  const bf16_t* In;    // [T, C]  (DOWN_TUNE: [z_rows, C], rows numbered like the saved x W)
   bf16_t* Out;         // [T, RP]
-  const bf16_t* AT;    // S1: base of the transposed A_t region; S4: null (use B_t)
-  int C, RP;
+  const bf16_t* AT;    // base of the transposed region (DOWN_X, DOWN_TUNE); DOWN_G: null (B_t / U_t as they are)
+  bf16_t* U2;          // [T, RP] pre-activations of the TUNING rows: written by DOWN_TUNE, read by DOWN_G
+  int C, RP, mode;
 };
+
+__device__ __forceinline__ float gelu_f(float u) { return 0.5f * u * (1.f + erff(u * 0.70710678f)); }
+__device__ __forceinline__ float gelu_slope_f(float u) {
+  return 0.5f * (1.f + erff(u * 0.70710678f)) + u * __expf(-0.5f * u * u) * 0.39894228f;
+}
 
 constexpr int GP = 72;   // LDS row pitch in elements (144 B): 16 consecutive rows of one 16-byte piece hit 64 different banks
 
@@ -69,9 +81,16 @@ __global__ __launch_bounds__(64 * NWV) void k_down(const DownParams p) {
   const int nr = it.nrows - r0 < ROWS ? it.nrows - r0 : ROWS;
   const int row0 = it.row0 + r0;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const bool lora = it.task >= 0 && p.tasks[it.task].kind == MUX_ADAPTER_LORA;
-  if (!lora || it.nvalid == 0) {
-    for (int e = tid; e < nr * p.RP; e += NTHR) p.Out[(size_t)(row0 + e / p.RP) * p.RP + e % p.RP] = 0;
+  const int kind = it.task >= 0 ? p.tasks[it.task].kind : MUX_ADAPTER_NONE;
+  const bool tuning = kind == MUX_ADAPTER_TUNING;
+  const bool mine = p.mode == DOWN_TUNE ? tuning : (kind == MUX_ADAPTER_LORA || (p.mode == DOWN_G && tuning));
+  if (!mine && p.mode == DOWN_TUNE) return;
+  if (!mine || it.nvalid == 0) {
+    for (int e = tid; e < nr * p.RP; e += NTHR) {
+      const size_t o = (size_t)(row0 + e / p.RP) * p.RP + e % p.RP;
+      p.Out[o] = 0;
+      if (p.mode == DOWN_TUNE) p.U2[o] = 0;
+    }
     return;
   }
   const DevTask tk = p.tasks[it.task];
@@ -84,7 +103,8 @@ __global__ __launch_bounds__(64 * NWV) void k_down(const DownParams p) {
   bf16_t* sX = lds[wave];
   bf16_t* sP = lds[wave] + ROWS * GP;
 
-  const rsrc_t rIn = make_rsrc(p.In + (size_t)row0 * p.C, (uint32_t)nr * (uint32_t)p.C * 2u);
+  const size_t in_row0 = p.mode == DOWN_TUNE ? (size_t)(tk.zrow0 + row0 - tk.row_begin) : (size_t)row0;
+  const rsrc_t rIn = make_rsrc(p.In + in_row0 * p.C, (uint32_t)nr * (uint32_t)p.C * 2u);
   const rsrc_t rP = make_rsrc(P, (uint32_t)prow * (uint32_t)p.C * 2u);
   // one wave instruction: 8 rows x 128 B; lane -> row lane/8 (+ 8 q), 16-byte piece lane%8
   const int b_row = lane >> 3, b_pc = (lane & 7) * 8;
@@ -169,8 +189,16 @@ __global__ __launch_bounds__(64 * NWV) void k_down(const DownParams p) {
 #pragma unroll
       for (int w = 0; w < NWV; ++w) s += ((const float*)lds[w])[j * (ROWS + 4) + orow];
     }
-    const bool ok = row_is_valid(p.dtab, row0 + orow);
-    p.Out[(size_t)(row0 + orow) * p.RP + j] = f32_to_bf16(ok && j < rank ? tk.scale * s : 0.f);
+    const bool ok = row_is_valid(p.dtab, row0 + orow) && j < rank;
+    const size_t o = (size_t)(row0 + orow) * p.RP + j;
+    float v = ok ? tk.scale * s : 0.f;
+    if (p.mode == DOWN_TUNE) {
+      p.U2[o] = f32_to_bf16(ok ? s : 0.f);
+      v = ok ? tk.scale * gelu_f(s) : 0.f;
+    } else if (tuning && ok) {
+      v *= gelu_slope_f(bf16_to_f32(p.U2[o]));
+    }
+    p.Out[o] = f32_to_bf16(v);
   }
 }
 
@@ -188,13 +216,15 @@ void launch_down(const CallCtx& c, const char* name, const DownParams& p) {
 // go through a wave-private LDS region in their natural layout and come back k-major per lane through
 // ds_read_b64_tr_b16.  No workgroup barrier: the four waves are independent streams.
 struct GradParams {     // blockIdx.z picks the problem: 0 = dB (Small = Hs, Big = dY), 1 = dA (Small = Gs, Big = X)
-  const int32_t* dtab;
+  const int32_t* dtab;   // TUNING items: 0 = dU_t (the same sum), 1 = dD_t (Small = Gs, Big = the saved z rows, C = N)
   const DevTask* tasks;
   const bf16_t* Small[2];  // [T, RP]
   const bf16_t* Big[2];    // [T, C]
-  float* part[2];          // [n_items][RP][C]
+  float* part[2];          // [n_items][slot], a slot holds [RP][C] of the item's kind
   int C[2];
   int RP, ts;
+  const bf16_t* Zc;        // saved x W, [z_rows, N]
+  size_t slot[2];          // elements per item in part[z]
 };
 
 template <int NJM>
@@ -203,17 +233,19 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
   const ItemView it = load_item(p.dtab, p.ts, blockIdx.x);
   if (it.task < 0 || it.nvalid == 0) return;
   const DevTask tk = p.tasks[it.task];
-  if (tk.kind != MUX_ADAPTER_LORA) return;
+  if (tk.kind != MUX_ADAPTER_LORA && tk.kind != MUX_ADAPTER_TUNING) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int z = blockIdx.z;
-  const int C = p.C[z];
+  const bool from_z = z == 1 && tk.kind == MUX_ADAPTER_TUNING;
+  const int C = from_z ? p.C[0] : p.C[z];
   const int cw0 = blockIdx.y * 256 + wave * 64;
   if (cw0 >= C) return;
   const int rank = tk.rank, NJ = (rank + 15) >> 4;
   bf16_t* sBig = lds[wave][0];
   bf16_t* sSm = lds[wave][1];
 
-  const rsrc_t rB = make_rsrc(p.Big[z] + (size_t)it.row0 * C, (uint32_t)it.nrows * (uint32_t)C * 2u);
+  const bf16_t* big = from_z ? p.Zc + (size_t)(tk.zrow0 + it.row0 - tk.row_begin) * C : p.Big[z] + (size_t)it.row0 * C;
+  const rsrc_t rB = make_rsrc(big, (uint32_t)it.nrows * (uint32_t)C * 2u);
   const rsrc_t rS = make_rsrc(p.Small[z] + (size_t)it.row0 * p.RP, (uint32_t)it.nrows * (uint32_t)p.RP * 2u);
   // Big slab: 4 loads per lane, row = 8q + lane/8, 16-byte piece = lane%8
   const int b_row = lane >> 3, b_pc = (lane & 7) * 8;
@@ -291,7 +323,7 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
     __builtin_amdgcn_wave_barrier();
   }
   // acc[jt][ct][v] = part[j = jt*16 + 4g + v][c = cw0 + ct*16 + l16]
-  float* dst = p.part[z] + (size_t)blockIdx.x * p.RP * C;
+  float* dst = p.part[z] + (size_t)blockIdx.x * p.slot[z];
 #pragma unroll
   for (int jt = 0; jt < NJM; ++jt)
     if (jt < NJ)
@@ -305,6 +337,113 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
             if (c < C) dst[(size_t)j * C + c] = acc[jt][ct][v];
           }
       }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Adapter-Tuning: Out = In + Small P for the rows of TUNING items, P = [r][N] as stored (forward: U_t, Y = z + Hs U_t,
+// In = the saved compact z rows, Out = Y; backward: D_t^T from the transposed region, dYs = dY + Gs D_t^T, In = dY,
+// Out = the compact dYs rows).  grid = (64-row items, ceil(N/256)); each wave owns 64 columns: its [r][64] slab of P
+// goes through a wave-private LDS region in natural layout and comes back k-major with ds_read_b64_tr_b16; the
+// products are staged 16 rows at a time in fp32 so that In is read and Out is written in whole 128-byte lines.
+struct TuneAddParams {
+  const int32_t* dtab;
+  const DevTask* tasks;
+  const bf16_t* In;
+  const bf16_t* Small;   // [T, RP]
+  bf16_t* Out;
+  const bf16_t* AT;      // backward: base of the transposed region (D_t^T); forward: null (U_t = tk.B)
+  int N, RP, backward;
+};
+
+template <int NKS>      // k-steps of 32 over the rank pitch (1 or 2)
+__global__ __launch_bounds__(256) void k_tune_add(const TuneAddParams p) {
+  constexpr int SP = 68;                                       // fp32 staging pitch
+  __shared__ __attribute__((aligned(16))) bf16_t sP[4][NKS * 32 * GP];
+  __shared__ __attribute__((aligned(16))) float sC[4][16 * SP];
+  const ItemView it = load_item(p.dtab, TS64, blockIdx.x);
+  if (it.task < 0 || p.tasks[it.task].kind != MUX_ADAPTER_TUNING) return;
+  const DevTask tk = p.tasks[it.task];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int cw0 = blockIdx.y * 256 + wave * 64;
+  if (cw0 >= p.N) return;
+  const int rank = tk.rank;
+  const bf16_t* P = p.backward ? p.AT + tk.at_off : (const bf16_t*)tk.B;
+  const int prow = p.backward ? ((rank + 15) & ~15) : rank;
+  bf16_t* sp = sP[wave];
+  float* sc = sC[wave];
+
+  // P slab [NKS*32][64] -> LDS, natural layout; rows beyond the rank read as zero
+  const rsrc_t rP = make_rsrc(P, (uint32_t)prow * (uint32_t)p.N * 2u);
+  const int b_row = lane >> 3, b_pc = (lane & 7) * 8;
+#pragma unroll
+  for (int q = 0; q < NKS * 4; ++q) {
+    const int j = b_row + 8 * q;
+    const bool ok = j < prow && cw0 + b_pc < p.N;
+    const u32x4 v = buf_load16(rP, ok ? (uint32_t)(((size_t)j * p.N + cw0 + b_pc) * 2) : OOB);
+    *(u32x4*)(sp + j * GP + b_pc) = v;
+  }
+  // Small rows in the A-operand layout straight from global memory: row = 16 rt + lane%16, k = 32 ks + 8 (lane/16)
+  const int i = lane & 15, g = lane >> 4;
+  const rsrc_t rS = make_rsrc(p.Small + (size_t)it.row0 * p.RP, (uint32_t)it.nrows * (uint32_t)p.RP * 2u);
+  bf16x8 a[4][NKS];
+#pragma unroll
+  for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      const int m = rt * 16 + i, k = ks * 32 + 8 * g;
+      a[rt][ks] = as_bf16x8(buf_load16(rS, (m < it.nrows && k < p.RP) ? (uint32_t)((m * p.RP + k) * 2) : OOB));
+    }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  const int tr_off = (8 * g + (i >> 2)) * GP + 4 * (i & 3);
+  bf16x8 b[4][NKS];
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      const bf16x4 lo = lds_read_tr(sp + ks * 32 * GP + tr_off + ct * 16), hi = lds_read_tr(sp + ks * 32 * GP + tr_off + 4 * GP + ct * 16);
+      b[ct][ks] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+
+  const uint32_t vbits_lo = row_valid_bits32(p.dtab, it.row0);
+  const uint32_t vbits_hi = it.nrows > 32 ? row_valid_bits32(p.dtab, it.row0 + 32) : 0u;
+  const size_t zrow0 = (size_t)(tk.zrow0 + it.row0 - tk.row_begin);
+  const bf16_t* in = p.In + (p.backward ? (size_t)it.row0 : zrow0) * p.N;
+  bf16_t* out = p.Out + (p.backward ? zrow0 : (size_t)it.row0) * p.N;
+#pragma unroll
+  for (int rt = 0; rt < 4; ++rt) {
+    if (rt * 16 >= it.nrows) break;
+    // operands exchanged: acc[ct][v] = product[row 16 rt + i][column 16 ct + 4 g + v]
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[ct][ks], a[rt][ks], acc, 0, 0, 0);
+      *(f32x4*)(sc + i * SP + ct * 16 + 4 * g) = acc;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int ps = 0; ps < 2; ++ps) {
+      const int ml = b_row + 8 * ps, m = rt * 16 + ml, c = cw0 + b_pc;
+      if (m < it.nrows && c < p.N) {
+        const bool ok = ((m < 32 ? vbits_lo >> m : vbits_hi >> (m - 32)) & 1u) != 0;
+        uint4 o = make_uint4(0, 0, 0, 0);
+        if (ok) {
+          const uint4 x = *(const uint4*)(in + (size_t)m * p.N + c);
+          const f32x4 p0 = *(const f32x4*)(sc + ml * SP + b_pc), p1 = *(const f32x4*)(sc + ml * SP + b_pc + 4);
+          const uint32_t* px = (const uint32_t*)&x;
+          o.x = pack_bf16x2(__uint_as_float(px[0] << 16) + p0[0], __uint_as_float(px[0] & 0xffff0000u) + p0[1]);
+          o.y = pack_bf16x2(__uint_as_float(px[1] << 16) + p0[2], __uint_as_float(px[1] & 0xffff0000u) + p0[3]);
+          o.z = pack_bf16x2(__uint_as_float(px[2] << 16) + p1[0], __uint_as_float(px[2] & 0xffff0000u) + p1[1]);
+          o.w = pack_bf16x2(__uint_as_float(px[3] << 16) + p1[2], __uint_as_float(px[3] & 0xffff0000u) + p1[3]);
+        }
+        *(uint4*)(out + (size_t)m * p.N + c) = o;
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -369,19 +508,22 @@ __global__ __launch_bounds__(128) void k_dl(const int32_t* __restrict__ dtab, co
 // transposed as [K][r].  mode 1: IA3_OUT, dl_t [N] from part0 (one row per item).
 __global__ __launch_bounds__(256) void k_reduce(const int32_t* __restrict__ dtab, const DevTask* __restrict__ tasks,
                                                const float* __restrict__ part0, const float* __restrict__ part1, int N, int K,
-                                               int RP, int ts, int mode, int accumulate) {
+                                               int RP, int ts, int mode, int accumulate, size_t slot0, size_t slot1) {
   const int t = blockIdx.x;
   const DevTask tk = tasks[t];
-  if (tk.kind != (mode == 1 ? MUX_ADAPTER_IA3_OUT : MUX_ADAPTER_LORA)) return;
+  const bool ranked = tk.kind == MUX_ADAPTER_LORA || tk.kind == MUX_ADAPTER_TUNING;
+  if (mode == 1 ? tk.kind != MUX_ADAPTER_IA3_OUT : !ranked) return;
+  if (tk.kind == MUX_ADAPTER_TUNING) K = N;    // its first gradient is dD_t [N][r]
   const int rows = mode == 1 ? 1 : tk.rank;
   size_t e = (size_t)blockIdx.y * 256 + threadIdx.x;
   const float* part = part0;
   int C = N;
   float* out = mode == 1 ? tk.dL : tk.dB;
   bool transposed = false;
+  size_t slot = slot0;
   if (mode == 0 && e >= (size_t)rows * N) {
     e -= (size_t)rows * N;
-    part = part1; C = K; out = tk.dA; transposed = true;
+    part = part1; C = K; out = tk.dA; transposed = true; slot = slot1;
   }
   if (!out || e >= (size_t)rows * C) return;
   const int j = (int)(e / C), c = (int)(e % C);
@@ -391,7 +533,7 @@ __global__ __launch_bounds__(256) void k_reduce(const int32_t* __restrict__ dtab
   float s = 0.f;
   for (int q = 0; q < ic; ++q) {
     if (items[(ib + q) * DI_WORDS + DI_NVALID] == 0) continue;
-    s += part[((size_t)(ib + q) * RP + j) * C + c];
+    s += part[(size_t)(ib + q) * slot + (size_t)j * C + c];
   }
   float* dst = transposed ? out + (size_t)c * rows + j : out + e;
   *dst = accumulate ? *dst + s : s;
@@ -413,8 +555,9 @@ int choose_group(const mux_segtab* st, int K, int N) {
 
 size_t adapter_partial_bytes(int K, int N, const mux_segtab* st) {
   const int C = K > N ? K : N;
-  const int RP = st->n_lora > 0 ? round_up(st->r_max, 16) : 0;
-  size_t lora = align256((size_t)st->items[TS256].size() * RP * N * 4) + align256((size_t)st->items[TS256].size() * RP * K * 4);
+  const int RP = rank_pitch(st);
+  const int K1 = (st->n_tuning > 0 && N > K) ? N : K;       // a TUNING item's second partial is [RP][N]
+  size_t lora = align256((size_t)st->items[TS256].size() * RP * N * 4) + align256((size_t)st->items[TS256].size() * RP * K1 * 4);
   (void)C;
   size_t ia3 = st->n_ia3 > 0 ? (size_t)st->items[TS64].size() * N * 4 : 0;
   return align256(lora > ia3 ? lora : ia3);
@@ -423,40 +566,61 @@ size_t adapter_partial_bytes(int K, int N, const mux_segtab* st) {
 mux_status adapter_down_x(const CallCtx& c, const void* X, void* Hs) {
   if (c.st->n_lora == 0) return MUX_OK;
   // A_t^T was written into c.AT by the task-table kernel of this call
-  DownParams p{c.dtab, c.dtasks, (const bf16_t*)X, (bf16_t*)Hs, (const bf16_t*)c.AT, c.K, c.RP};
+  DownParams p{c.dtab, c.dtasks, (const bf16_t*)X, (bf16_t*)Hs, (const bf16_t*)c.AT, nullptr, c.K, c.RP, DOWN_X};
   launch_down(c, "down_x", p);
   return MUX_OK;
 }
 
 mux_status adapter_down_g(const CallCtx& c, const void* dY, void* Gs) {
-  if (c.st->n_lora == 0) return MUX_OK;
-  DownParams p{c.dtab, c.dtasks, (const bf16_t*)dY, (bf16_t*)Gs, nullptr, c.N, c.RP};
+  if (c.st->n_lora + c.st->n_tuning == 0) return MUX_OK;
+  DownParams p{c.dtab, c.dtasks, (const bf16_t*)dY, (bf16_t*)Gs, nullptr, (bf16_t*)c.U2, c.N, c.RP, DOWN_G};
   launch_down(c, "down_g", p);
+  return MUX_OK;
+}
+
+// Adapter-Tuning: Y = z + Hs U_t (forward) or dYs = dY + Gs D_t^T (backward, D_t^T from the transposed region)
+mux_status adapter_tune_add(const CallCtx& c, const void* In, const void* Small, void* Out, int backward) {
+  if (c.st->n_tuning == 0) return MUX_OK;
+  TuneAddParams p{c.dtab, c.dtasks, (const bf16_t*)In, (const bf16_t*)Small, (bf16_t*)Out, (const bf16_t*)c.AT, c.N, c.RP, backward};
+  const dim3 grid((unsigned)c.st->items[TS64].size(), (c.N + 255) / 256);
+  if (c.RP <= 32) MUX_LAUNCH(backward ? "tune_dz" : "tune_up", (k_tune_add<1>), grid, dim3(256), 0, c.stream, p);
+  else MUX_LAUNCH(backward ? "tune_dz" : "tune_up", (k_tune_add<2>), grid, dim3(256), 0, c.stream, p);
+  return MUX_OK;
+}
+
+// Adapter-Tuning forward, after the backbone GEMM saved z = x W: u = z D_t, Hs = s_t gelu(u).  D_t^T was written into
+// c.AT by the task-table kernel of this call.
+mux_status adapter_down_tune(const CallCtx& c, const void* Z, void* Hs) {
+  if (c.st->n_tuning == 0) return MUX_OK;
+  DownParams p{c.dtab, c.dtasks, (const bf16_t*)Z, (bf16_t*)Hs, (const bf16_t*)c.AT, (bf16_t*)c.U2, c.N, c.RP, DOWN_TUNE};
+  launch_down(c, "tune_down", p);
   return MUX_OK;
 }
 
 mux_status adapter_grads(const CallCtx& c, const void* X, const void* dY, const void* Hs, const void* Gs, const void* Z,
                          void* part, int accumulate) {
   const int M = c.st->n_tasks;
-  if (c.st->n_lora > 0) {
-    // dB_t = Hs^T dY and dA_t = X^T Gs: one launch for the partials of both, one for the two reductions
+  if (c.st->n_lora + c.st->n_tuning > 0) {
+    // dB_t = Hs^T dY and dA_t = X^T Gs (Adapter-Tuning: dU_t = Hs^T dY and dD_t = z^T Gs): one launch for the partials
+    // of both, one for the two reductions
     const int ts = choose_group(c.st, c.K, c.N);
     const size_t n_items = c.st->items[ts].size();
+    const int K1 = (c.st->n_tuning > 0 && c.N > c.K) ? c.N : c.K;
     float* part0 = (float*)part;
     float* part1 = (float*)((char*)part + align256(c.st->items[TS256].size() * (size_t)c.RP * c.N * 4));
     GradParams p{c.dtab, c.dtasks, {(const bf16_t*)Hs, (const bf16_t*)Gs}, {(const bf16_t*)dY, (const bf16_t*)X}, {part0, part1},
-                 {c.N, c.K}, c.RP, ts};
+                 {c.N, c.K}, c.RP, ts, (const bf16_t*)Z, {(size_t)c.RP * c.N, (size_t)c.RP * K1}};
     const int cmax = c.N > c.K ? c.N : c.K;
     launch_grad(c, "grad_dbda", p, dim3((unsigned)n_items, (cmax + 255) / 256, 2));
-    const size_t elems = (size_t)c.st->r_max * ((size_t)c.N + c.K);
+    const size_t elems = (size_t)c.st->r_max * ((size_t)c.N + K1);
     MUX_LAUNCH("reduce_dbda", k_reduce, dim3(M, (unsigned)((elems + 255) / 256)), dim3(256), 0, c.stream, c.dtab, c.dtasks,
-               (const float*)part0, (const float*)part1, c.N, c.K, c.RP, ts, 0, accumulate);
+               (const float*)part0, (const float*)part1, c.N, c.K, c.RP, ts, 0, accumulate, p.slot[0], p.slot[1]);
   }
   if (c.st->n_ia3 > 0) {
     MUX_LAUNCH("grad_dl", k_dl, dim3((unsigned)c.st->items[TS64].size(), (c.N + 1023) / 1024), dim3(128), 0, c.stream,
                c.dtab, c.dtasks, (const bf16_t*)dY, (const bf16_t*)Z, (float*)part, (bf16_t*)c.dYs, c.N);
     MUX_LAUNCH("reduce_dl", k_reduce, dim3(M, (c.N + 255) / 256), dim3(256), 0, c.stream, c.dtab, c.dtasks,
-               (const float*)part, (const float*)nullptr, c.N, c.K, 1, TS64, 1, accumulate);
+               (const float*)part, (const float*)nullptr, c.N, c.K, 1, TS64, 1, accumulate, (size_t)c.N, (size_t)0);
   }
   return MUX_OK;
 }

@@ -20,7 +20,8 @@ struct TaskPtrArgs {
 // beyond r) for the forward's down-projection: block b handles 64 k-values of task base + (b-1)/ceil(K/64), reading
 // the pointers from the launch arguments (not from the table block 0 is writing).
 __global__ __launch_bounds__(256) void k_fill_tasks(const int32_t* __restrict__ dtab, DevTask* __restrict__ out, TaskPtrArgs p,
-                                                     int base, int count, uint16_t* __restrict__ pack_at, int K) {
+                                                     int base, int count, uint16_t* __restrict__ pack_at, int Kin, int Nout,
+                                                     int only_tuning) {
   if (blockIdx.x == 0) {
     const int i = threadIdx.x;
     if (i >= count) return;
@@ -39,11 +40,15 @@ __global__ __launch_bounds__(256) void k_fill_tasks(const int32_t* __restrict__ 
     return;
   }
   __shared__ uint16_t t[64][66];
-  const int nkb = (K + 63) / 64;
+  const int nkb = ((Kin > Nout ? Kin : Nout) + 63) / 64;
   const int i = (blockIdx.x - 1) / nkb, k0 = ((blockIdx.x - 1) % nkb) * 64;
   if (i >= count) return;
   const int32_t* te = dtab + dtab[DH_OFF_TASKS] + (base + i) * DT_WORDS;
-  if (te[DT_KIND] != MUX_ADAPTER_LORA) return;
+  // LORA: A_t [K, r]; TUNING: D_t [N, r] (in the same slot); both go out as [round_up(r,16)][rows]
+  if (te[DT_KIND] != MUX_ADAPTER_LORA && te[DT_KIND] != MUX_ADAPTER_TUNING) return;
+  if (only_tuning && te[DT_KIND] != MUX_ADAPTER_TUNING) return;     // the backward pass needs D_t^T only
+  const int K = te[DT_KIND] == MUX_ADAPTER_LORA ? Kin : Nout;
+  if (k0 >= K) return;
   const int r = te[DT_RANK], rp = (r + 15) & ~15;
   const uint16_t* A = (const uint16_t*)p.A[i];
   for (int e = threadIdx.x; e < 64 * rp; e += 256) {
@@ -92,6 +97,7 @@ Layout make_layout(const mux_layer_desc* L, const mux_segtab* st) {
   size_t at_elems = 0;
   for (const HostTask& ht : st->tasks)
     if (ht.kind == MUX_ADAPTER_LORA) at_elems += (size_t)round_up(ht.rank, 16) * L->K;
+    else if (ht.kind == MUX_ADAPTER_TUNING) at_elems += (size_t)round_up(ht.rank, 16) * L->N;
   o.at_bytes = L->dtype == MUX_DT_BF16 ? align256(at_elems * 2) : 0;
   o.part_bytes = L->dtype == MUX_DT_BF16 ? fast_partial_bytes(L->K, L->N, st) : 0;
   o.dys_bytes = (L->dtype == MUX_DT_BF16 || st->n_tuning > 0) ? o.z_bytes : 0;
@@ -126,7 +132,7 @@ mux_status check_hip(const char* fn) {
 }
 
 void fill_tasks(const mux_layer_desc* L, const mux_segtab* st, const int32_t* dtab, DevTask* dtasks, void* const* dA,
-                void* const* dB, void* const* dL, hipStream_t stream, void* pack_at) {
+                void* const* dB, void* const* dL, hipStream_t stream, void* pack_at, int only_tuning) {
   int64_t at_off = 0;
   for (int base = 0; base < st->n_tasks; base += 16) {
     TaskPtrArgs p;
@@ -144,10 +150,12 @@ void fill_tasks(const mux_layer_desc* L, const mux_segtab* st, const int32_t* dt
       p.dL[i] = (kind == MUX_ADAPTER_IA3_OUT && dL) ? (float*)dL[t] : nullptr;
       p.at_off[i] = at_off;
       if (kind == MUX_ADAPTER_LORA) at_off += (int64_t)round_up(st->tasks[t].rank, 16) * L->K;
+      else if (kind == MUX_ADAPTER_TUNING) at_off += (int64_t)round_up(st->tasks[t].rank, 16) * L->N;
     }
-    const unsigned pack_blocks = pack_at ? (unsigned)count * (unsigned)((L->K + 63) / 64) : 0u;
+    const int rows_max = L->K > L->N ? L->K : L->N;
+    const unsigned pack_blocks = pack_at ? (unsigned)count * (unsigned)((rows_max + 63) / 64) : 0u;
     MUX_LAUNCH("fill_tasks", k_fill_tasks, dim3(1 + pack_blocks), dim3(256), 0, stream, dtab, dtasks, p, base, count,
-               (uint16_t*)pack_at, L->K);
+               (uint16_t*)pack_at, L->K, L->N, only_tuning);
   }
 }
 
@@ -181,7 +189,7 @@ extern "C" mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_se
   const bool fast = layer->dtype == MUX_DT_BF16 && !(layer->flags & MUX_LAYER_REFERENCE_KERNELS);
   void* at_region = (char*)ws + lo.tasks_bytes + lo.g_bytes;
   fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, nullptr, nullptr, nullptr, stream,
-             (fast && st->n_lora > 0) ? at_region : nullptr);
+             (fast && st->n_lora + st->n_tuning > 0) ? at_region : nullptr, 0);
   CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP,
             (char*)ws + lo.tasks_bytes + lo.g_bytes, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes, layer->W, stream,
             (saved && lo.u2_bytes) ? (char*)saved + lo.h_bytes + lo.z_bytes : nullptr};
@@ -212,7 +220,9 @@ extern "C" mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_s
   if (ws_bytes < lo.ws_bytes) return fail(MUX_ERR_WORKSPACE, std::string(fn) + ": workspace too small");
   hipStream_t stream = (hipStream_t)hip_stream;
   DevTask* dtasks = (DevTask*)ws;
-  fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, dA, dB, dL, stream, nullptr);
+  const bool fast = layer->dtype == MUX_DT_BF16 && !(layer->flags & MUX_LAYER_REFERENCE_KERNELS);
+  fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, dA, dB, dL, stream,
+             (fast && st->n_tuning > 0) ? (char*)ws + lo.tasks_bytes + lo.g_bytes : nullptr, 1);
   CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP,
             (char*)ws + lo.tasks_bytes + lo.g_bytes, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes, layer->W, stream,
             (saved && lo.u2_bytes) ? (char*)saved + lo.h_bytes + lo.z_bytes : nullptr};

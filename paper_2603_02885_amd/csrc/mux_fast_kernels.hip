@@ -21,7 +21,10 @@ mux_status fast_forward(const CallCtx& c, const void* X, void* Y, void* H, void*
   else s = gemm_mfma_forward(c, X, H, Y, Z);
   if (s != MUX_OK) return s;
   // Adapter-Tuning rows: the GEMM saved x W; the bottleneck follows (u = z D_t, Y = z + s_t gelu(u) U_t)
-  if (c.st->n_tuning > 0) ref_steps(c, MUX_DT_BF16, REF_TUNE_DOWN | REF_TUNE_UP, X, nullptr, Y, nullptr, H, Z, nullptr, 0);
+  if (c.st->n_tuning > 0) {
+    if (mux_status st = adapter_down_tune(c, Z, H)) return st;
+    if (mux_status st = adapter_tune_add(c, Z, H, Y, 0)) return st;
+  }
   return MUX_OK;
 }
 
@@ -30,10 +33,8 @@ mux_status fast_backward(const CallCtx& c, const void* X, const void* dY, const 
   if (!fast_ok(c) || !aligned16(X) || !aligned16(dY) || !aligned16(dX) || !aligned16(G) || !aligned16(H) || !aligned16(Z))
     return ref_backward(c, MUX_DT_BF16, X, dY, H, Z, G, dX, accumulate);
   if (mux_status s = adapter_down_g(c, dY, G)) return s;
-  // Adapter-Tuning tasks: Gs rows, the prepared input rows of the backbone backward, and the two gradients
-  if (c.st->n_tuning > 0)
-    ref_steps(c, MUX_DT_BF16, REF_ONLY_TUNING | REF_G | REF_TUNE_DZ | REF_DB | REF_DA, X, dY, nullptr, nullptr, (void*)H,
-              (void*)Z, G, accumulate);
+  // Adapter-Tuning rows enter the backbone backward as dY + Gs D_t^T
+  if (mux_status s = adapter_tune_add(c, dY, G, c.dYs, 1)) return s;
   if (mux_status s = adapter_grads(c, X, dY, H, G, Z, part, accumulate)) return s;
   if (!dX) return MUX_OK;
   if (gemm_dma_supported(c, true) && !getenv("MUX_GEMM_REGSTAGED")) {

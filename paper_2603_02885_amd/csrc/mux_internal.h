@@ -137,6 +137,8 @@ mux_status gemm_dma_backward(const CallCtx& c, const void* dY, const void* Gs, v
 // matrix-core adapter kernels (bf16): down-projections and per-task gradient reductions
 mux_status adapter_down_x(const CallCtx& c, const void* X, void* Hs);                       // S1
 mux_status adapter_down_g(const CallCtx& c, const void* dY, void* Gs);                      // S4a
+mux_status adapter_down_tune(const CallCtx& c, const void* Z, void* Hs);                    // Adapter-Tuning forward
+mux_status adapter_tune_add(const CallCtx& c, const void* In, const void* Small, void* Out, int backward);
 mux_status adapter_grads(const CallCtx& c, const void* X, const void* dY, const void* Hs, const void* Gs, const void* Z,
                          void* part, int accumulate);                                       // S4b, S6
 size_t adapter_partial_bytes(int K, int N, const mux_segtab* st);
