@@ -10,7 +10,8 @@ from tests import mux_harness as hz
 
 pytestmark = pytest.mark.gpu
 
-CASES = [(1, 0), (1, 4), (1, 6), (2, 0), (2, 6), (3, 0), (3, 4), (3, 6), (4, 0), (4, 3), (4, 4), (4, 6)]
+CASES = [(1, 0), (1, 4), (1, 6), (2, 0), (2, 6), (3, 0), (3, 4), (3, 6), (4, 0), (4, 3), (4, 4), (4, 6),
+         (5, 0)]     # 5: the extra workload with two Adapter-Tuning tasks (their rows need x W in full: one projection)
 
 
 @pytest.fixture(scope="module")
