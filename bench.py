@@ -32,6 +32,9 @@ def parse():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--compare-unmultiplexed", action="store_true",
+                    help="also time the same tasks one at a time (one table and one set of calls per task, same shared "
+                         "W, same rows), on one stream and alternating over two streams: what multiplexing buys")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 512 MiB device copy (known traffic) for scaling rocprofv3 byte counters")
     return ap.parse_args()
@@ -86,6 +89,60 @@ def step(mx, st, dtab, layers, ws, ws_bytes, stream):
         mx.mux_lora_forward(L.desc, st, dtab, L.X, L.Y, L.saved, ws, ws_bytes, stream)
     for L in reversed(layers):
         mx.mux_lora_backward(L.desc, st, dtab, L.X, L.dY, L.saved, L.dX, L.dA, L.dB, L.dL, 0, ws, ws_bytes, stream)
+
+
+def unmultiplexed(mx, torch, wl, st, layers, steps, warmup):
+    """The same tasks, rows and shared weights without backbone multiplexing (the paper's spatial batching, section
+    3.2, switched off): every task gets its own table and its own forward/backward calls per projection.  Rows of a
+    task are a contiguous block of the aligned batch, so its X, dY, Y, dX are views of the multiplexed buffers."""
+    import numpy as np
+    dev = "cuda:0"
+    img = mx.mux_segtab_serialize(st)
+    M = len(wl.tasks)
+    per_task = []
+    for t, task in enumerate(wl.tasks):
+        r0, rc = int(img[16 + 8 * t + 0]), int(img[16 + 8 * t + 1])
+        if rc == 0:
+            continue
+        st1 = mx.mux_segtab_build([mx.TaskDesc(task.kind, task.rank, task.scale, task.seq_lens)], wl.chunk, wl.max_pack_len, 0)
+        assert mx.mux_segtab_rows(st1) == rc
+        nb = mx.mux_segtab_device_bytes(st1)
+        dtab1 = torch.zeros(nb, dtype=torch.uint8, device=dev)
+        mx.mux_segtab_upload(st1, dtab1, nb)
+        calls = []
+        for L in layers:
+            desc = mx.LayerDesc(L.K, L.N, mx.MUX_DT_BF16, L.W, 1, [L.A[t]], [L.B[t]], [L.L[t]])
+            sb = mx.mux_lora_saved_bytes(desc, st1)
+            calls.append((desc, L.X[r0:r0 + rc], L.dY[r0:r0 + rc], L.Y[r0:r0 + rc], L.dX[r0:r0 + rc],
+                          torch.zeros(max(sb, 256), dtype=torch.uint8, device=dev), [L.dA[t]], [L.dB[t]], [L.dL[t]],
+                          mx.mux_lora_workspace_bytes(desc, st1)))
+        per_task.append((st1, dtab1, calls))
+    wsb = max(c[9] for _, _, calls in per_task for c in calls)
+    wss = [torch.zeros(max(wsb, 256), dtype=torch.uint8, device=dev) for _ in range(2)]
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream()        # default priority
+
+    def one_step(streams):
+        for i, (st1, dtab1, calls) in enumerate(per_task):
+            sidx = i % len(streams)
+            stream, ws = streams[sidx], wss[sidx]
+            for (desc, X, dY, Y, dX, saved, dA, dB, dL, _) in calls:
+                mx.mux_lora_forward(desc, st1, dtab1, X, Y, saved, ws, wsb, stream)
+            for (desc, X, dY, Y, dX, saved, dA, dB, dL, _) in reversed(calls):
+                mx.mux_lora_backward(desc, st1, dtab1, X, dY, saved, dX, dA, dB, dL, 0, ws, wsb, stream)
+
+    res = {}
+    for name, streams in (("one_stream", [main]), ("two_streams", [main, side])):
+        side.wait_stream(main)
+        for _ in range(warmup):
+            one_step(streams)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            one_step(streams)
+        torch.cuda.synchronize()
+        res[name] = {"ms_per_step": (time.perf_counter() - t0) * 1e3 / steps}
+    return res
 
 
 def cpu_baseline(wl, seconds, seed):
@@ -239,6 +296,14 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    if args.compare_unmultiplexed:
+        mx.mux_profile_enable(0)
+        mx.mux_profile_collect()
+        um = unmultiplexed(mx, torch, wl, st, layers, args.steps, args.warmup)
+        for v in um.values():
+            v["tokens_per_s"] = valid / (v["ms_per_step"] * 1e-3)
+            v["multiplexed_speedup"] = v["ms_per_step"] / ms_per_step
+        out["unmultiplexed"] = um
     if args.calibrate_copy:
         src = torch.zeros(512 << 20, dtype=torch.uint8, device="cuda:0")
         dst = torch.empty_like(src)
