@@ -258,3 +258,31 @@ def test_leading_dimension_packs_and_skipped_outputs(env):
     mx.mux_lora_backward(l0, st0, dt0, keep, keep, ws0, keep, dA, dB, [None], 0, ws0, ws0.numel())
     torch.cuda.synchronize()
     assert torch.all(dA[0] == 0) and torch.all(dB[0] == 0)      # a task without tokens has zero gradients
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_sweep(env, block):
+    """Seeded random layer calls: every adapter kind at random ranks (1..64), random shapes (multiples of 64, 32, 8
+    and odd sizes, so every GEMM kernel is met), chunk sizes, pack lengths, both table modes, empty tasks."""
+    mx, _ = env
+    rng = np.random.default_rng(9000 + block)
+    kinds = [wlm.KIND_LORA, wlm.KIND_LORA, wlm.KIND_IA3, wlm.KIND_ADAPTER, wlm.KIND_NONE]
+    for case in range(6):
+        gran = int(rng.choice([64, 64, 32, 8, 1]))
+        K = gran * int(rng.integers(1, max(2, 520 // gran)))
+        N = gran * int(rng.integers(1, max(2, 520 // gran)))
+        chunk = int(rng.choice([16, 32, 64, 128]))
+        tasks = []
+        for _t in range(int(rng.integers(1, 7))):
+            kind = int(rng.choice(kinds))
+            rank = int(rng.integers(1, 65)) if kind in (wlm.KIND_LORA, wlm.KIND_ADAPTER) else 0
+            nseq = int(rng.integers(0, 4))
+            lens = [int(v) for v in rng.integers(1, 200, size=nseq)]
+            tasks.append(wlm.Task(kind, rank, float(rng.choice([0.5, 1.0, 2.0])), lens))
+        if sum(t.tokens for t in tasks) == 0:
+            tasks.append(wlm.Task(wlm.KIND_LORA, 8, 1.0, [17]))
+        wl = wlm.Workload(name=f"rnd{block}_{case}", layers=[("w", K, N)], tasks=tasks, chunk=chunk,
+                          max_pack_len=int(rng.choice([0, 0, 150])), sigma_w=0.05, sigma_ab=0.05)
+        dtype = mx.MUX_DT_F32 if case % 3 == 2 else mx.MUX_DT_BF16
+        print(f"case {block}.{case}: K={K} N={N} chunk={chunk} tasks={[(t.kind, t.rank, t.seq_lens) for t in tasks]}", flush=True)
+        run_case(env, wl, dtype=dtype, seg_flags=int(rng.integers(0, 2)), seed=100 * block + case)
