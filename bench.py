@@ -91,31 +91,40 @@ def step(mx, st, dtab, layers, ws, ws_bytes, stream):
         mx.mux_lora_backward(L.desc, st, dtab, L.X, L.dY, L.saved, L.dX, L.dA, L.dB, L.dL, 0, ws, ws_bytes, stream)
 
 
-def unmultiplexed(mx, torch, wl, st, layers, steps, warmup):
-    """The same tasks, rows and shared weights without backbone multiplexing (the paper's spatial batching, section
-    3.2, switched off): every task gets its own table and its own forward/backward calls per projection.  Rows of a
-    task are a contiguous block of the aligned batch, so its X, dY, Y, dX are views of the multiplexed buffers."""
-    import numpy as np
+def unmultiplexed(mx, torch, wl, st, layers, steps, warmup, n_groups=None):
+    """The same tasks, rows and shared weights with less (or no) backbone multiplexing: the tasks are cut into
+    `n_groups` groups of consecutive tasks (default: one task per group, the paper's spatial batching of section 3.2
+    switched off); every group gets its own table and its own forward/backward calls per projection, i.e. the groups
+    are multiplexed in time (section 3.3) and the tasks inside a group in space.  Rows of consecutive tasks are a
+    contiguous block of the aligned batch, so a group's X, dY, Y, dX are views of the multiplexed buffers."""
     dev = "cuda:0"
     img = mx.mux_segtab_serialize(st)
     M = len(wl.tasks)
+    G = M if n_groups is None else max(1, min(n_groups, M))
+    bounds = [round(i * M / G) for i in range(G + 1)]
     per_task = []
-    for t, task in enumerate(wl.tasks):
-        r0, rc = int(img[16 + 8 * t + 0]), int(img[16 + 8 * t + 1])
+    for gi in range(G):
+        ts = list(range(bounds[gi], bounds[gi + 1]))
+        if not ts:
+            continue
+        r0 = int(img[16 + 8 * ts[0] + 0])
+        rc = sum(int(img[16 + 8 * t + 1]) for t in ts)
         if rc == 0:
             continue
-        st1 = mx.mux_segtab_build([mx.TaskDesc(task.kind, task.rank, task.scale, task.seq_lens)], wl.chunk, wl.max_pack_len, 0)
+        st1 = mx.mux_segtab_build([mx.TaskDesc(wl.tasks[t].kind, wl.tasks[t].rank, wl.tasks[t].scale, wl.tasks[t].seq_lens)
+                                   for t in ts], wl.chunk, wl.max_pack_len, 0)
         assert mx.mux_segtab_rows(st1) == rc
         nb = mx.mux_segtab_device_bytes(st1)
         dtab1 = torch.zeros(nb, dtype=torch.uint8, device=dev)
         mx.mux_segtab_upload(st1, dtab1, nb)
         calls = []
         for L in layers:
-            desc = mx.LayerDesc(L.K, L.N, mx.MUX_DT_BF16, L.W, 1, [L.A[t]], [L.B[t]], [L.L[t]])
+            desc = mx.LayerDesc(L.K, L.N, mx.MUX_DT_BF16, L.W, len(ts), [L.A[t] for t in ts], [L.B[t] for t in ts],
+                                [L.L[t] for t in ts])
             sb = mx.mux_lora_saved_bytes(desc, st1)
             calls.append((desc, L.X[r0:r0 + rc], L.dY[r0:r0 + rc], L.Y[r0:r0 + rc], L.dX[r0:r0 + rc],
-                          torch.zeros(max(sb, 256), dtype=torch.uint8, device=dev), [L.dA[t]], [L.dB[t]], [L.dL[t]],
-                          mx.mux_lora_workspace_bytes(desc, st1)))
+                          torch.zeros(max(sb, 256), dtype=torch.uint8, device=dev), [L.dA[t] for t in ts],
+                          [L.dB[t] for t in ts], [L.dL[t] for t in ts], mx.mux_lora_workspace_bytes(desc, st1)))
         per_task.append((st1, dtab1, calls))
     wsb = max(c[9] for _, _, calls in per_task for c in calls)
     wss = [torch.zeros(max(wsb, 256), dtype=torch.uint8, device=dev) for _ in range(2)]
@@ -296,13 +305,43 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    mx.mux_profile_enable(0)
+    mx.mux_profile_collect()
+    # fully multiplexed, but the (independent) projections issued alternately on two streams, each with its own
+    # workspace: the second stream's kernels fill the compute units the first one's GEMM leaves idle in its last round
+    side = torch.cuda.Stream()
+    ws2 = torch.zeros_like(ws)
+    main = torch.cuda.current_stream()
+
+    def step2():
+        for i, L in enumerate(layers):
+            sx, wx = (main, ws) if i % 2 == 0 else (side, ws2)
+            mx.mux_lora_forward(L.desc, st, dtab, L.X, L.Y, L.saved, wx, ws_bytes, sx)
+        for i, L in reversed(list(enumerate(layers))):
+            sx, wx = (main, ws) if i % 2 == 0 else (side, ws2)
+            mx.mux_lora_backward(L.desc, st, dtab, L.X, L.dY, L.saved, L.dX, L.dA, L.dB, L.dL, 0, wx, ws_bytes, sx)
+
+    side.wait_stream(main)
+    for _ in range(args.warmup):
+        step2()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        step2()
+    torch.cuda.synchronize()
+    ms2 = (time.perf_counter() - t2) * 1e3 / args.steps
+    out["multiplexed_projections_on_two_streams"] = {"ms_per_step": ms2, "tokens_per_s": valid / (ms2 * 1e-3)}
     if args.compare_unmultiplexed:
         mx.mux_profile_enable(0)
         mx.mux_profile_collect()
-        um = unmultiplexed(mx, torch, wl, st, layers, args.steps, args.warmup)
-        for v in um.values():
-            v["tokens_per_s"] = valid / (v["ms_per_step"] * 1e-3)
-            v["multiplexed_speedup"] = v["ms_per_step"] / ms_per_step
+        um = {}
+        groups = sorted({g for g in (2, 4, M) if 1 < g <= M})
+        for g in groups:          # g groups of tasks multiplexed in time, the tasks of a group in space
+            r = unmultiplexed(mx, torch, wl, st, layers, args.steps, args.warmup, g)
+            for v in r.values():
+                v["tokens_per_s"] = valid / (v["ms_per_step"] * 1e-3)
+                v["multiplexed_speedup"] = v["ms_per_step"] / ms_per_step
+            um[f"groups_{g}" if g < M else "one_task_per_call"] = r
         out["unmultiplexed"] = um
     if args.calibrate_copy:
         src = torch.zeros(512 << 20, dtype=torch.uint8, device="cuda:0")
