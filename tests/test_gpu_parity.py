@@ -286,3 +286,39 @@ def test_random_sweep(env, block):
         dtype = mx.MUX_DT_F32 if case % 3 == 2 else mx.MUX_DT_BF16
         print(f"case {block}.{case}: K={K} N={N} chunk={chunk} tasks={[(t.kind, t.rank, t.seq_lens) for t in tasks]}", flush=True)
         run_case(env, wl, dtype=dtype, seg_flags=int(rng.integers(0, 2)), seed=100 * block + case)
+
+
+@pytest.mark.parametrize("which", ["mixed", "tuning"])
+def test_graph_capture_and_replay(env, which):
+    """The calls allocate nothing and never synchronise, so a forward + backward pair can be captured into a HIP
+    graph; every replay (with eager work and synchronisations in between) must give the eager results bit for bit."""
+    mx, torch = env
+    wl = mixed_workload() if which == "mixed" else tuning_workload()
+    g, got, ref, _ = run_case(env, wl)                 # eager, also warms up every kernel
+    torch.cuda.synchronize()
+    keep = {"Y": g.Y.clone(), "dX": g.dX.clone()}
+    for k in ("dA", "dB", "dL"):
+        keep[k] = [None if t is None else t.clone() for t in getattr(g, k)]
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            g.forward()
+            g.backward()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        g.Y.fill_(float("nan")); g.dX.fill_(float("nan"))
+        for k in ("dA", "dB", "dL"):
+            for t in getattr(g, k):
+                if t is not None:
+                    t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(g.Y, keep["Y"]) and torch.equal(g.dX, keep["dX"]), f"replay {rep}"
+        for k in ("dA", "dB", "dL"):
+            for a, b in zip(keep[k], getattr(g, k)):
+                assert a is None or torch.equal(a, b), f"replay {rep} {k}"
+        g.forward(); g.backward()                      # eager work between the replays
+        torch.cuda.synchronize()
