@@ -26,6 +26,7 @@ import numpy as np
 KIND_NONE = 0
 KIND_LORA = 1
 KIND_IA3 = 2
+KIND_DIFF = 4      # selective kind (Diff-Pruning): trainable values on a fixed sparse mask over W; values in the A slot
 KIND_ADAPTER = 3   # additive bottleneck after the BaseOp (Adapter-Tuning): D [N, r] in the A slot, U [r, N] in the B slot
 
 
@@ -35,6 +36,7 @@ class Task:
     rank: int
     scale: float
     seq_lens: List[int]
+    density: float = 0.0       # KIND_DIFF: fraction of the entries of W that are trainable
 
     @property
     def tokens(self) -> int:
@@ -193,6 +195,7 @@ class LayerTensors:
     X: np.ndarray
     dY: np.ndarray
     extra: Dict[str, np.ndarray] = field(default_factory=dict)
+    masks: List[Optional[Tuple[np.ndarray, np.ndarray]]] = field(default_factory=list)   # KIND_DIFF: (k[nnz], n[nnz]) by (k, n)
 
 
 def layer_tensors(wl: Workload, layer: int, T: int, seed: int = 0, bf16: bool = True,
@@ -208,6 +211,7 @@ def layer_tensors(wl: Workload, layer: int, T: int, seed: int = 0, bf16: bool = 
     A: List[Optional[np.ndarray]] = []
     B: List[Optional[np.ndarray]] = []
     L: List[Optional[np.ndarray]] = []
+    masks: List[Optional[Tuple[np.ndarray, np.ndarray]]] = [None] * len(wl.tasks)
     for t, task in enumerate(wl.tasks):
         if task.kind == KIND_LORA:
             A.append(normal(seed, f"{tag}.A{t}", (K, task.rank), wl.sigma_ab, bf16=bf16))
@@ -216,6 +220,14 @@ def layer_tensors(wl: Workload, layer: int, T: int, seed: int = 0, bf16: bool = 
         elif task.kind == KIND_ADAPTER:
             A.append(normal(seed, f"{tag}.D{t}", (N, task.rank), wl.sigma_ab, bf16=bf16))
             B.append(normal(seed, f"{tag}.U{t}", (task.rank, N), wl.sigma_ab, bf16=bf16))
+            L.append(None)
+        elif task.kind == KIND_DIFF:
+            # unstructured mask: every entry of W independently with probability `density`, listed by (k, n)
+            rng = np.random.Generator(np.random.Philox(key=_key(seed, f"{tag}.M{t}")))
+            flat = np.flatnonzero(rng.random(K * N) < task.density).astype(np.int64)
+            masks[t] = ((flat // N).astype(np.int32), (flat % N).astype(np.int32))
+            A.append(normal(seed, f"{tag}.V{t}", (flat.size,), wl.sigma_ab, bf16=bf16))
+            B.append(None)
             L.append(None)
         elif task.kind == KIND_IA3:
             A.append(None)
@@ -228,4 +240,4 @@ def layer_tensors(wl: Workload, layer: int, T: int, seed: int = 0, bf16: bool = 
     if pad_rows is not None and pad_fill is not None:
         X[pad_rows] = np.float32(pad_fill)
         dY[pad_rows] = np.float32(pad_fill)
-    return LayerTensors(K=K, N=N, W=W, A=A, B=B, L=L, X=X, dY=dY)
+    return LayerTensors(K=K, N=N, W=W, A=A, B=B, L=L, X=X, dY=dY, masks=masks)

@@ -76,6 +76,24 @@ def _cols(cols, n_full):
     return int(c.size), c.ctypes.data_as(_I), c
 
 
+def _sparse_args(S, M):
+    """S: per task None or (k[nnz], n[nnz]) int arrays sorted by (k, n).  Returns the three C arguments and keep-alives."""
+    S = S if S is not None else [None] * M
+    nnz = np.zeros(M, dtype=np.int32)
+    IP = ctypes.POINTER(ctypes.c_int32)
+    kp = (IP * M)(); npp = (IP * M)()
+    keep = []
+    for t in range(M):
+        if S[t] is None:
+            continue
+        k = np.ascontiguousarray(S[t][0], dtype=np.int32); n = np.ascontiguousarray(S[t][1], dtype=np.int32)
+        assert k.shape == n.shape and k.ndim == 1
+        nnz[t] = k.size
+        kp[t] = k.ctypes.data_as(IP); npp[t] = n.ctypes.data_as(IP)
+        keep += [k, n]
+    return nnz.ctypes.data_as(_I), kp, npp, (nnz, keep)
+
+
 def _task_arrays(kinds, ranks, scales):
     k = np.ascontiguousarray(kinds, dtype=np.int32)
     r = np.ascontiguousarray(ranks, dtype=np.int32)
@@ -83,7 +101,7 @@ def _task_arrays(kinds, ranks, scales):
     return k, r, s
 
 
-def forward(X, W, row_task, kinds, ranks, scales, A, B, L, cols=None, want_z=False):
+def forward(X, W, row_task, kinds, ranks, scales, A, B, L, cols=None, want_z=False, S=None):
     """Returns dict(Y[T,n_cols], H[T,r_max], Z or None), all float64."""
     X = _f32(X); W = _f32(W)
     T, K = X.shape
@@ -96,6 +114,7 @@ def forward(X, W, row_task, kinds, ranks, scales, A, B, L, cols=None, want_z=Fal
     r_max = int(max([int(r[t]) for t in range(M) if k[t] in (1, 3)] + [1]))
     n_cols, cptr, _ckeep = _cols(cols, N)
     Ap, _ka = _ptrs_f(A); Bp, _kb = _ptrs_f(B); Lp, _kl = _ptrs_f(L)
+    sp = _sparse_args(S, M)
     Y = np.zeros((T, n_cols), dtype=np.float64)
     H = np.zeros((T, r_max), dtype=np.float64)
     Z = np.zeros((T, n_cols), dtype=np.float64) if want_z else None
@@ -104,14 +123,14 @@ def forward(X, W, row_task, kinds, ranks, scales, A, B, L, cols=None, want_z=Fal
         M, k.ctypes.data_as(_I), r.ctypes.data_as(_I), s.ctypes.data_as(_D),
         Ap, Bp, Lp, n_cols, cptr, r_max,
         Y.ctypes.data_as(_D), H.ctypes.data_as(_D),
-        Z.ctypes.data_as(_D) if Z is not None else None)
+        Z.ctypes.data_as(_D) if Z is not None else None, *sp[:3])
     if rc != 0:
         raise RuntimeError(f"mux_oracle_forward failed: {rc}")
     return {"Y": Y, "H": H, "Z": Z}
 
 
 def backward(X, dY, W, row_task, kinds, ranks, scales, A, B, L, kcols=None, cols=None,
-             want_dx=True):
+             want_dx=True, S=None):
     """Returns dict(dX[T,n_kcols], G[T,r_max], dA[list], dB[list], dL[list]), float64."""
     X = _f32(X); W = _f32(W); dY = _f32(dY)
     T, K = X.shape
@@ -124,6 +143,7 @@ def backward(X, dY, W, row_task, kinds, ranks, scales, A, B, L, kcols=None, cols
     n_kcols, kptr, _kk = _cols(kcols, K)
     n_cols, cptr, _ck = _cols(cols, N)
     Ap, _ka = _ptrs_f(A); Bp, _kb = _ptrs_f(B); Lp, _kl = _ptrs_f(L)
+    sp = _sparse_args(S, M)
     dX = np.zeros((T, n_kcols), dtype=np.float64) if want_dx else None
     G = np.zeros((T, r_max), dtype=np.float64)
     dA: List[Optional[np.ndarray]] = []
@@ -134,6 +154,9 @@ def backward(X, dY, W, row_task, kinds, ranks, scales, A, B, L, kcols=None, cols
             dA.append(np.zeros((K, int(r[t])), dtype=np.float64))
             dB.append(np.zeros((int(r[t]), N), dtype=np.float64))
             dL.append(None)
+        elif k[t] == 4:     # selective kind: one gradient value per masked entry
+            dA.append(np.zeros((int(np.asarray(S[t][0]).size),), dtype=np.float64))
+            dB.append(None); dL.append(None)
         elif k[t] == 3:     # additive kind: D [N, r] in the A slot, U [r, N] in the B slot
             dA.append(np.zeros((N, int(r[t])), dtype=np.float64))
             dB.append(np.zeros((int(r[t]), N), dtype=np.float64))
@@ -148,7 +171,7 @@ def backward(X, dY, W, row_task, kinds, ranks, scales, A, B, L, kcols=None, cols
         row_task.ctypes.data_as(_I), M, k.ctypes.data_as(_I), r.ctypes.data_as(_I),
         s.ctypes.data_as(_D), Ap, Bp, Lp, n_kcols, kptr, n_cols, cptr, r_max,
         dX.ctypes.data_as(_D) if dX is not None else None, G.ctypes.data_as(_D),
-        _ptrs_d(dA), _ptrs_d(dB), _ptrs_d(dL))
+        _ptrs_d(dA), _ptrs_d(dB), _ptrs_d(dL), *sp[:3])
     if rc != 0:
         raise RuntimeError(f"mux_oracle_backward failed: {rc}")
     return {"dX": dX, "G": G, "dA": dA, "dB": dB, "dL": dL}

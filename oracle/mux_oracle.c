@@ -21,6 +21,11 @@
  *     lists it among the implemented ones, without a formula) is read as the usual bottleneck
  *     inserted after the BaseOp:  z = x W,  u = z D,  y = z + s gelu(u) U,  with D [N,r] passed
  *     in the A slot and U [r,N] in the B slot; gelu(u) = u/2 (1 + erf(u / sqrt 2)).
+ *   - The selective kind (section 2.1 names Diff-Pruning: a subset of the parameters is fine-tuned through a
+ *     binary mask; also among the implemented types of section 5, without a formula) is read as
+ *     y = x (W + M * delta) with a fixed 0/1 mask M over the entries of W and trainable values delta on
+ *     the masked entries only, given as a list of (k, n, value) sorted by (k, n); its gradient is the masked
+ *     slice of the dense x^T g, the one place where entries of a weight gradient are formed.
  *   - Chunk alignment pads with zero tokens (section 3.5): a padding row's buffer
  *     content is ignored (selected away, never multiplied, so NaN there cannot leak),
  *     its outputs are zero, and it adds nothing to any gradient.
@@ -44,6 +49,7 @@
 #define KIND_LORA 1
 #define KIND_IA3 2
 #define KIND_ADAPTER 3
+#define KIND_DIFF 4
 #define MAX_RANK 1024
 
 static inline int has_rank(int kind) { return kind == KIND_LORA || kind == KIND_ADAPTER; }
@@ -73,8 +79,9 @@ int mux_oracle_forward(int T, int K, int N,
                        int n_tasks, const int32_t* kind, const int32_t* rank, const double* scale,
                        const float* const* A, const float* const* B, const float* const* L,
                        int n_cols, const int32_t* cols, int r_max,
-                       double* Y, double* H, double* Z)
-{
+                       double* Y, double* H, double* Z,
+                       const int32_t* s_nnz, const int32_t* const* s_k, const int32_t* const* s_n)
+{   /* selective kind: task t has s_nnz[t] masked entries (s_k[t][e], s_n[t][e]) with values A[t][e] */
     if (T < 0 || K <= 0 || N <= 0 || n_cols < 0 || r_max < 0) return 1;
     for (int i = 0; i < T; ++i) {
         int t = row_task[i];
@@ -122,6 +129,15 @@ int mux_oracle_forward(int T, int K, int N,
         } else if (kind[t] == KIND_IA3) {          /* y = z * l_t  (aggregate: multiply) */
             const float* l = L[t];
             for (int c = 0; c < n_cols; ++c) y[c] *= (double)l[col_of(cols, c)];
+        } else if (kind[t] == KIND_DIFF) {         /* y = x (W + M_t * delta_t) = z + sum over masked (k, n) of x_k delta_kn */
+            const float* dv = A[t];
+            for (int c = 0; c < n_cols; ++c) {
+                const int n = col_of(cols, c);
+                double v = 0.0;
+                for (int e = 0; e < s_nnz[t]; ++e)     /* entries are sorted by (k, n): ascending k inside a column */
+                    if (s_n[t][e] == n) v += (double)x[s_k[t][e]] * (double)dv[e];
+                y[c] += v;
+            }
         } else if (kind[t] == KIND_ADAPTER) {      /* y = z + s_t gelu(z D_t) U_t */
             const int r = rank[t];
             const float* Dt = A[t];                /* [N, r] */
@@ -163,8 +179,9 @@ int mux_oracle_backward(int T, int K, int N,
                         int n_kcols, const int32_t* kcols,
                         int n_cols, const int32_t* cols, int r_max,
                         double* dX, double* G, double* const* dA, double* const* dB,
-                        double* const* dL)
-{
+                        double* const* dL,
+                        const int32_t* s_nnz, const int32_t* const* s_k, const int32_t* const* s_n)
+{   /* selective kind: dX = g (W + M_t * delta_t)^T, dA[t][e] = sum_i x_i[k_e] g_i[n_e] */
     if (T < 0 || K <= 0 || N <= 0 || r_max < 0) return 1;
     for (int i = 0; i < T; ++i) {
         int t = row_task[i];
@@ -244,6 +261,17 @@ int mux_oracle_backward(int T, int K, int N,
                 dx[c] = s;
             }
             free(dz);
+        } else if (kind[t] == KIND_DIFF) {                  /* dx = g W^T + g (M_t * delta_t)^T */
+            const float* dv = A[t];
+            if (dx) for (int c = 0; c < n_kcols; ++c) {
+                const int k = col_of(kcols, c);
+                double s = 0.0;
+                for (int n = 0; n < N; ++n) s += (double)g[n] * (double)W[(size_t)k * N + n];
+                double v = 0.0;
+                for (int e = 0; e < s_nnz[t]; ++e)
+                    if (s_k[t][e] == k) v += (double)g[s_n[t][e]] * (double)dv[e];
+                dx[c] = s + v;
+            }
         } else if (kind[t] == KIND_IA3) {                   /* dx = (g * l_t) W^T */
             const float* l = L[t];
             if (dx) for (int c = 0; c < n_kcols; ++c) {
@@ -303,6 +331,19 @@ int mux_oracle_backward(int T, int K, int N,
                     }
                     for (int j = 0; j < r; ++j)
                         for (int n = n0; n < n1; ++n) db[(size_t)j * N + n] *= scale[t];
+                }
+            }
+        } else if (kind[t] == KIND_DIFF) {
+            if (dA && dA[t]) {                              /* d delta_e = sum_i x_i[k_e] g_i[n_e]: masked entries of x^T g */
+                double* dd = dA[t];
+#pragma omp parallel for schedule(static)
+                for (int e = 0; e < s_nnz[t]; ++e) {
+                    double v = 0.0;
+                    for (int i = 0; i < T; ++i) {
+                        if (row_task[i] != t) continue;
+                        v += (double)X[(size_t)i * K + s_k[t][e]] * (double)dY[(size_t)i * N + s_n[t][e]];
+                    }
+                    dd[e] = v;
                 }
             }
         } else if (kind[t] == KIND_ADAPTER) {

@@ -35,6 +35,11 @@ MUTATIONS = {
     "additive_dU_without_scale": ("for (int n = n0; n < n1; ++n) du[(size_t)j * N + n] *= scale[t];", ";"),
     "gelu_slope_misses_density_term": ("return 0.5 * (1.0 + erf(u * 0.70710678118654752440)) + u * exp(-0.5 * u * u) * 0.39894228040143267794;",
                                        "return 0.5 * (1.0 + erf(u * 0.70710678118654752440));"),
+    "selective_forward_swaps_mask_indices": ("if (s_n[t][e] == n) v += (double)x[s_k[t][e]] * (double)dv[e];",
+                                             "if (s_k[t][e] == n) v += (double)x[s_n[t][e]] * (double)dv[e];"),
+    "selective_backward_forgets_sparse_part": ("dx[c] = s + v;", "dx[c] = s;"),
+    "selective_gradient_sums_all_rows": ("                    for (int i = 0; i < T; ++i) {\n                        if (row_task[i] != t) continue;\n                        v += (double)X[(size_t)i * K + s_k[t][e]]",
+                                         "                    for (int i = 0; i < T; ++i) {\n                        if (row_task[i] < 0) continue;\n                        v += (double)X[(size_t)i * K + s_k[t][e]]"),
     "q_contracts_over_wrong_operand": ("for (int n = 0; n < N; ++n) u += (double)g[n] * (double)Bt[(size_t)j * N + n];\n                q[j] = u;",
                                        "for (int n = 0; n < N; ++n) u += (double)g[n] * (double)Bt[(size_t)j * N + n];\n                q[j] = u * 0.5;"),
 }

@@ -492,3 +492,111 @@ def test_adapter_isolation_and_padding():
     assert np.array_equal(b2["dA"][t], b["dA"][t]) and np.array_equal(b2["dB"][t], b["dB"][t])
     pad = st.row_task < 0
     assert np.all(f2["Y"][pad] == 0) and np.all(b2["dX"][pad] == 0)
+
+
+# ----------------------------------------------------------------- selective kind (masked sparse update of W)
+
+def diff_problem(seed=0, K=14, N=11, c=4, bf16=True, density=0.2):
+    tasks = [wlm.Task(wlm.KIND_LORA, 3, 2.0, [5]),
+             wlm.Task(wlm.KIND_DIFF, 0, 1.0, [6, 3], density=density),
+             wlm.Task(wlm.KIND_NONE, 0, 1.0, [2]),
+             wlm.Task(wlm.KIND_DIFF, 0, 1.0, [5], density=density / 2)]
+    wl = wlm.Workload(name=f"diff{seed}", layers=[("w", K, N)], tasks=tasks, chunk=c, sigma_w=0.5, sigma_ab=0.5)
+    st = segtab.build([t.seq_lens for t in tasks], c)
+    lt = wlm.layer_tensors(wl, 0, st.T, seed=seed, bf16=bf16)
+    return wl, st, lt
+
+
+def _kw(lt):
+    return {"S": lt.masks}
+
+
+def test_diff_hand_worked_row():
+    """x = (1, 2, 3), W = [[1,0],[0,1],[1,1]], mask entries (0,1) and (2,0) with values 10 and -1:
+    W' = [[1,10],[0,1],[0,1]], y = x W' = (1, 10 + 2 + 3) = (1, 15).  With g = (1, 2): dX = g W'^T = (21, 2, 2);
+    d delta = (x_0 g_1, x_2 g_0) = (2, 3).  A transposed mask index or an unmasked gradient entry changes these."""
+    X = np.array([[1.0, 2.0, 3.0]], dtype=np.float32)
+    W = np.array([[1.0, 0.0], [0.0, 1.0], [1.0, 1.0]], dtype=np.float32)
+    k = np.array([0, 2], dtype=np.int32); n = np.array([1, 0], dtype=np.int32)
+    v = np.array([10.0, -1.0], dtype=np.float32)
+    dY = np.array([[1.0, 2.0]], dtype=np.float32)
+    rt = np.array([0], dtype=np.int32)
+    f = oracle.forward(X, W, rt, [wlm.KIND_DIFF], [0], [1.0], [v], [None], [None], S=[(k, n)])
+    assert np.array_equal(f["Y"], [[1.0, 15.0]])
+    b = oracle.backward(X, dY, W, rt, [wlm.KIND_DIFF], [0], [1.0], [v], [None], [None], S=[(k, n)])
+    assert np.array_equal(b["dX"], [[21.0, 2.0, 2.0]])
+    assert np.array_equal(b["dA"][0], [2.0, 3.0])
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_diff_against_dense_weights(seed):
+    """The definition through dense matrices and numpy: W_t = W + scatter(mask, delta), Y = X W_t, dX = dY W_t^T,
+    and the gradient is the masked slice of the dense X^T dY -- the weight gradient the rest of the method never forms."""
+    wl, st, lt = diff_problem(seed=seed)
+    f = run_fwd(wl, st, lt, **_kw(lt)); b = run_bwd(wl, st, lt, **_kw(lt))
+    X64, W64, g64 = lt.X.astype(np.float64), lt.W.astype(np.float64), lt.dY.astype(np.float64)
+    for t, task in enumerate(wl.tasks):
+        if task.kind != wlm.KIND_DIFF:
+            continue
+        rows = st.row_task == t
+        k, n = lt.masks[t]
+        assert k.size > 0 and np.all(np.diff(k.astype(np.int64) * lt.N + n) > 0)      # sorted by (k, n), no duplicates
+        Wt = W64.copy(); Wt[k, n] += lt.A[t].astype(np.float64)
+        assert np.allclose(f["Y"][rows], X64[rows] @ Wt, rtol=1e-13, atol=1e-13)
+        assert np.allclose(b["dX"][rows], g64[rows] @ Wt.T, rtol=1e-13, atol=1e-13)
+        dense = X64[rows].T @ g64[rows]
+        assert np.allclose(b["dA"][t], dense[k, n], rtol=1e-13, atol=1e-13)
+
+
+def test_diff_empty_mask_is_plain_gemm():
+    wl, st, lt = diff_problem(seed=2, density=0.0)
+    f = run_fwd(wl, st, lt, **_kw(lt)); b = run_bwd(wl, st, lt, **_kw(lt))
+    rows = st.row_task == 1
+    assert lt.masks[1][0].size == 0
+    assert np.allclose(f["Y"][rows], lt.X[rows].astype(np.float64) @ lt.W.astype(np.float64), rtol=1e-13, atol=1e-13)
+    assert b["dA"][1].shape == (0,)
+
+
+def test_diff_finite_differences_are_exact():
+    """L = sum(Y * dY) is linear in the masked values and in X: central differences have no truncation error."""
+    wl, st, lt = diff_problem(seed=3)
+    b = run_bwd(wl, st, lt, **_kw(lt))
+    eps = 2.0 ** -6
+    rng = np.random.default_rng(3)
+
+    def loss():
+        return float(np.sum(run_fwd(wl, st, lt, **_kw(lt))["Y"] * masked(lt.dY, st.row_task)))
+
+    def fd(arr, idx):
+        old = arr[idx]
+        arr[idx] = np.float32(old + eps); lp = loss()
+        arr[idx] = np.float32(old - eps); lm = loss()
+        arr[idx] = old
+        return (lp - lm) / (2 * eps)
+
+    for t, task in enumerate(wl.tasks):
+        if task.kind != wlm.KIND_DIFF:
+            continue
+        rows = np.nonzero(st.row_task == t)[0]
+        for e in range(0, lt.A[t].size, max(1, lt.A[t].size // 6)):
+            g = fd(lt.A[t], (e,))
+            assert abs(g - b["dA"][t][e]) <= 1e-9 * max(1.0, abs(g))
+        for _ in range(6):
+            i = int(rng.choice(rows)); k = int(rng.integers(0, lt.K))
+            g = fd(lt.X, (i, k))
+            assert abs(g - b["dX"][i, k]) <= 1e-9 * max(1.0, abs(g))
+
+
+def test_diff_isolation_and_column_sampling():
+    """NaN in the other tasks' rows and in the padding rows changes nothing; sampled columns equal the full run."""
+    wl, st, lt = diff_problem(seed=4)
+    f = run_fwd(wl, st, lt, **_kw(lt)); b = run_bwd(wl, st, lt, **_kw(lt))
+    rows = st.row_task == 1
+    lt2 = wlm.layer_tensors(wl, 0, st.T, seed=4)
+    lt2.X[~rows] = np.nan; lt2.dY[~rows] = np.nan
+    f2 = run_fwd(wl, st, lt2, **_kw(lt2)); b2 = run_bwd(wl, st, lt2, **_kw(lt2))
+    assert np.array_equal(f2["Y"][rows], f["Y"][rows]) and np.array_equal(b2["dX"][rows], b["dX"][rows])
+    assert np.array_equal(b2["dA"][1], b["dA"][1])
+    cols = np.array([1, 4, 9], dtype=np.int32); kcols = np.array([0, 5, 13], dtype=np.int32)
+    fs = run_fwd(wl, st, lt, cols=cols, **_kw(lt)); bs = run_bwd(wl, st, lt, cols=cols, kcols=kcols, **_kw(lt))
+    assert np.array_equal(fs["Y"], f["Y"][:, cols]) and np.array_equal(bs["dX"], b["dX"][:, kcols])
