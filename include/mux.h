@@ -47,12 +47,17 @@ typedef enum {
  * TUNING: the additive type of section 2.1 (Adapter-Tuning, one of the three implemented types of
  * section 5), a bottleneck inserted after the BaseOp: z = x W, y = z + s gelu(z D) U with D [N, r],
  * U [r, N] and gelu(u) = u/2 (1 + erf(u / sqrt 2)).  D is passed in the A slot, U in the B slot.
+ * DIFF: the selective type of section 2.1 (Diff-Pruning, also among the implemented types of section 5):
+ * y = x (W + M * delta) with a fixed 0/1 mask M over the entries of W and trainable values delta on the
+ * masked entries only.  The values are passed in the A slot (one per masked entry, in the row-major order
+ * of the mask), the mask itself as a mux_sparse_mask in mux_layer_desc.masks.
  * NONE: y = x W. */
 typedef enum {
   MUX_ADAPTER_NONE = 0,
   MUX_ADAPTER_LORA = 1,
   MUX_ADAPTER_IA3_OUT = 2,
-  MUX_ADAPTER_TUNING = 3
+  MUX_ADAPTER_TUNING = 3,
+  MUX_ADAPTER_DIFF = 4
 } mux_adapter_kind;
 
 /* Storage type of activations, weights and adapters.  BF16: bfloat16 storage, fp32
@@ -120,6 +125,19 @@ mux_status mux_segtab_row_task(const mux_segtab* st, int32_t* host_dst, size_t c
 size_t mux_segtab_device_bytes(const mux_segtab* st);
 mux_status mux_segtab_upload(const mux_segtab* st, void* dev_dst, size_t cap, void* hip_stream);
 
+/* Fixed sparse mask of one DIFF task over W[K,N] (host struct, device arrays of int32).  The masked entries
+ * are numbered in row-major order (by k, then n, no duplicates): entry e of row k has column col_idx[e],
+ * row_ptr[k] <= e < row_ptr[k+1].  The same entries are listed a second time column by column:
+ * col_ent[2*i] = row k and col_ent[2*i+1] = number e of the i-th listed entry, col_ptr[n] <= i < col_ptr[n+1],
+ * k ascending inside a column.  The mask is fixed during training, so both listings are built once. */
+typedef struct mux_sparse_mask {
+  int32_t nnz;
+  const int32_t* row_ptr;  /* device, K+1 */
+  const int32_t* col_idx;  /* device, nnz */
+  const int32_t* col_ptr;  /* device, N+1 */
+  const int32_t* col_ent;  /* device, 2*nnz */
+} mux_sparse_mask;
+
 /* One multiplexed layer call.  All pointers inside are device pointers, except the three
  * arrays A, B, L themselves, which are host arrays of n_tasks device pointers (entry NULL
  * where the task's kind does not use it).  Ranks, scales and kinds come from the table. */
@@ -133,6 +151,8 @@ typedef struct {
   const void* const* A;  /* host array of device pointers, LORA: A_t[K, r_t]; TUNING: D_t[N, r_t] */
   const void* const* B;  /* LORA: B_t[r_t, N]; TUNING: U_t[r_t, N]                          */
   const void* const* L;  /* IA3_OUT: l_t[N]                                                 */
+  const struct mux_sparse_mask* const* masks; /* host array of n_tasks host pointers, DIFF: the task's mask
+                            (NULL entries for the other kinds; the array may be NULL without DIFF tasks)   */
 } mux_layer_desc;
 
 #define MUX_LAYER_REFERENCE_KERNELS 1u /* run the plain (non matrix-core) HIP kernels       */
@@ -147,6 +167,7 @@ size_t mux_lora_workspace_bytes(const mux_layer_desc* layer, const mux_segtab* s
  *     Y_i = x_i W + s_t (x_i A_t) B_t      (LORA)
  *     Y_i = (x_i W) * l_t                  (IA3_OUT)
  *     Y_i = z_i + s_t gelu(z_i D_t) U_t ,  z_i = x_i W        (TUNING)
+ *     Y_i = x_i (W + M_t * delta_t)        (DIFF)
  *     Y_i = x_i W                          (NONE)
  * Padding rows: their X content is ignored (never multiplied) and Y_i = 0.
  * X: device [T,K]; Y: device [T,N]; saved: device, mux_lora_saved_bytes, may be NULL only if
@@ -162,6 +183,8 @@ mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_segtab* st,
  *     p_i = s_t (g_i U_t^T) * gelu'(z_i D_t) ,  dX_i = (g_i + p_i D_t^T) W^T ,
  *     dD_t = sum_i z_i^T p_i  (returned in dA[t], [N,r_t]) ,
  *     dU_t = s_t sum_i gelu(z_i D_t)^T g_i  (returned in dB[t], [r_t,N])      (TUNING)
+ *     dX_i = g_i (W + M_t * delta_t)^T ,  d delta_t[e] = sum_i x_i[k_e] g_i[n_e]  (returned in dA[t], [nnz],
+ *     the masked entries of x^T g: the one place where entries of a weight gradient are formed)   (DIFF)
  *     dX_i = g_i W^T                                                          (NONE)
  * sums over the rows of task t only.  dX of padding rows = 0.  No gradient of W.
  * dA, dB, dL: host arrays of n_tasks device pointers to fp32 buffers ([K,r_t], [r_t,N], [N]);

@@ -14,7 +14,7 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 __all__ = [
-    "MUX_OK", "MUX_ADAPTER_NONE", "MUX_ADAPTER_LORA", "MUX_ADAPTER_IA3_OUT", "MUX_ADAPTER_TUNING", "MUX_DT_BF16", "MUX_DT_F32",
+    "MUX_OK", "MUX_ADAPTER_NONE", "MUX_ADAPTER_LORA", "MUX_ADAPTER_IA3_OUT", "MUX_ADAPTER_TUNING", "MUX_ADAPTER_DIFF", "SparseMask", "MUX_DT_BF16", "MUX_DT_F32",
     "MUX_SEGTAB_DENSE", "MUX_LAYER_REFERENCE_KERNELS", "MUX_MAX_RANK", "MuxError", "TaskDesc", "LayerDesc", "SegTab",
     "library_path", "load_library", "mux_choose_chunk_size", "mux_segtab_build", "mux_segtab_free",
     "mux_segtab_rows", "mux_segtab_n_chunks", "mux_segtab_n_tasks", "mux_segtab_valid_tokens",
@@ -24,7 +24,7 @@ __all__ = [
 ]
 
 MUX_OK = 0
-MUX_ADAPTER_NONE, MUX_ADAPTER_LORA, MUX_ADAPTER_IA3_OUT, MUX_ADAPTER_TUNING = 0, 1, 2, 3
+MUX_ADAPTER_NONE, MUX_ADAPTER_LORA, MUX_ADAPTER_IA3_OUT, MUX_ADAPTER_TUNING, MUX_ADAPTER_DIFF = 0, 1, 2, 3, 4
 MUX_DT_BF16, MUX_DT_F32 = 0, 1
 MUX_SEGTAB_DENSE = 1
 MUX_LAYER_REFERENCE_KERNELS = 1
@@ -45,10 +45,15 @@ class _TaskDescC(ctypes.Structure):
                 ("seq_lens", POINTER(c_int32))]
 
 
+class _SparseMaskC(ctypes.Structure):
+    _fields_ = [("nnz", c_int32), ("row_ptr", c_void_p), ("col_idx", c_void_p), ("col_ptr", c_void_p),
+                ("col_ent", c_void_p)]
+
+
 class _LayerDescC(ctypes.Structure):
     _fields_ = [("K", c_int32), ("N", c_int32), ("dtype", c_int32), ("flags", c_uint32), ("W", c_void_p),
                 ("ldw", c_int64), ("n_tasks", c_int32), ("A", POINTER(c_void_p)), ("B", POINTER(c_void_p)),
-                ("L", POINTER(c_void_p))]
+                ("L", POINTER(c_void_p)), ("masks", POINTER(POINTER(_SparseMaskC)))]
 
 
 class _ProfileEntryC(ctypes.Structure):
@@ -160,19 +165,51 @@ class SegTab:
             _lib.mux_segtab_free(h)
 
 
+class SparseMask:
+    """Mirror of mux_sparse_mask.  Built from the masked entries (k[nnz], n[nnz]) sorted by (k, n): the row-major
+    listing (row_ptr, col_idx) and the column-by-column listing (col_ptr, col_ent) are laid out on the host (index
+    bookkeeping only) and handed to `to_device`, a callable that turns an int32 numpy array into an object with a
+    device pointer (for instance lambda a: torch.from_numpy(a).cuda())."""
+
+    def __init__(self, k, n, K: int, N: int, to_device):
+        import numpy as np
+        k = np.ascontiguousarray(k, dtype=np.int64); n = np.ascontiguousarray(n, dtype=np.int64)
+        assert k.shape == n.shape and k.ndim == 1
+        flat = k * N + n
+        assert np.all(np.diff(flat) > 0), "mask entries must be sorted by (k, n) without duplicates"
+        assert k.size == 0 or (k.min() >= 0 and k.max() < K and n.min() >= 0 and n.max() < N)
+        nnz = int(k.size)
+        row_ptr = np.zeros(K + 1, dtype=np.int32); row_ptr[1:] = np.cumsum(np.bincount(k, minlength=K))
+        col_ptr = np.zeros(N + 1, dtype=np.int32); col_ptr[1:] = np.cumsum(np.bincount(n, minlength=N))
+        order = np.lexsort((k, n))                       # by column, then row: positions in the row-major numbering
+        col_ent = np.empty(2 * nnz, dtype=np.int32)
+        col_ent[0::2] = k[order]; col_ent[1::2] = order
+        self.nnz = nnz
+        self._bufs = [to_device(row_ptr), to_device(n.astype(np.int32)), to_device(col_ptr),
+                      to_device(col_ent if nnz else np.zeros(2, dtype=np.int32))]
+        self.c = _SparseMaskC(nnz=nnz, row_ptr=_ptr(self._bufs[0]), col_idx=_ptr(self._bufs[1]),
+                              col_ptr=_ptr(self._bufs[2]), col_ent=_ptr(self._bufs[3]))
+
+
 class LayerDesc:
     """Mirror of mux_layer_desc; keeps the pointer arrays alive."""
 
     def __init__(self, K: int, N: int, dtype: int, W, n_tasks: int, A=None, B=None, L=None, ldw: Optional[int] = None,
-                 flags: int = 0):
+                 flags: int = 0, masks=None):
         self._A = _ptr_array(A, n_tasks)
         self._B = _ptr_array(B, n_tasks)
         self._L = _ptr_array(L, n_tasks)
-        self._keep = (W, A, B, L)
+        self._keep = (W, A, B, L, masks)
+        self._masks = (POINTER(_SparseMaskC) * max(n_tasks, 1))()
+        if masks is not None:
+            for t in range(n_tasks):
+                if masks[t] is not None:
+                    self._masks[t] = ctypes.pointer(masks[t].c)
         self.c = _LayerDescC(K=int(K), N=int(N), dtype=int(dtype), flags=int(flags), W=_ptr(W),
                              ldw=int(N if ldw is None else ldw), n_tasks=int(n_tasks),
                              A=ctypes.cast(self._A, POINTER(c_void_p)), B=ctypes.cast(self._B, POINTER(c_void_p)),
-                             L=ctypes.cast(self._L, POINTER(c_void_p)))
+                             L=ctypes.cast(self._L, POINTER(c_void_p)),
+                             masks=ctypes.cast(self._masks, POINTER(POINTER(_SparseMaskC))) if masks is not None else None)
         self.n_tasks = int(n_tasks)
 
 

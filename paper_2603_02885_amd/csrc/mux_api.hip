@@ -72,6 +72,8 @@ __global__ __launch_bounds__(256) void k_zero_grads(const DevTask* __restrict__ 
     if (tk.dB && e < (size_t)tk.rank * N) tk.dB[e] = 0.f;
   } else if (tk.kind == MUX_ADAPTER_IA3_OUT) {
     if (tk.dL && e < (size_t)N) tk.dL[e] = 0.f;
+  } else if (tk.kind == MUX_ADAPTER_DIFF) {
+    if (tk.dA && e < (size_t)tk.at_off) tk.dA[e] = 0.f;
   }
 }
 
@@ -121,8 +123,23 @@ mux_status check_layer(const char* fn, const mux_layer_desc* L, const mux_segtab
       return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": LoRA or Adapter-Tuning task without its two matrices");
     if (ht.kind == MUX_ADAPTER_IA3_OUT && (!L->L || !L->L[t]))
       return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": IA3 task without scale vector");
+    if (ht.kind == MUX_ADAPTER_DIFF) {
+      if (!L->masks || !L->masks[t]) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": Diff-Pruning task without a mask");
+      const mux_sparse_mask* m = L->masks[t];
+      if (m->nnz < 0 || !m->row_ptr || !m->col_ptr) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": bad mask");
+      if (m->nnz > 0 && (!m->col_idx || !m->col_ent || !L->A || !L->A[t]))
+        return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": Diff-Pruning task without entries or values");
+    }
   }
   return MUX_OK;
+}
+
+int diff_max_nnz(const mux_layer_desc* L, const mux_segtab* st) {
+  int m = 0;
+  if (st->n_diff > 0 && L->masks)
+    for (int t = 0; t < st->n_tasks; ++t)
+      if (st->tasks[t].kind == MUX_ADAPTER_DIFF && L->masks[t] && L->masks[t]->nnz > m) m = L->masks[t]->nnz;
+  return m;
 }
 
 mux_status check_hip(const char* fn) {
@@ -149,6 +166,14 @@ void fill_tasks(const mux_layer_desc* L, const mux_segtab* st, const int32_t* dt
       p.dB[i] = (ranked && dB) ? (float*)dB[t] : nullptr;
       p.dL[i] = (kind == MUX_ADAPTER_IA3_OUT && dL) ? (float*)dL[t] : nullptr;
       p.at_off[i] = at_off;
+      if (kind == MUX_ADAPTER_DIFF) {
+        const mux_sparse_mask* m = L->masks[t];
+        p.A[i] = m->nnz > 0 ? L->A[t] : nullptr;
+        p.dA[i] = (m->nnz > 0 && dA) ? (float*)dA[t] : nullptr;
+        p.B[i] = m->row_ptr; p.L[i] = m->col_idx;
+        p.dB[i] = (float*)m->col_ptr; p.dL[i] = (float*)m->col_ent;
+        p.at_off[i] = m->nnz;
+      }
       if (kind == MUX_ADAPTER_LORA) at_off += (int64_t)round_up(st->tasks[t].rank, 16) * L->K;
       else if (kind == MUX_ADAPTER_TUNING) at_off += (int64_t)round_up(st->tasks[t].rank, 16) * L->N;
     }
@@ -192,7 +217,7 @@ extern "C" mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_se
              (fast && st->n_lora + st->n_tuning > 0) ? at_region : nullptr, 0);
   CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP,
             (char*)ws + lo.tasks_bytes + lo.g_bytes, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes, layer->W, stream,
-            (saved && lo.u2_bytes) ? (char*)saved + lo.h_bytes + lo.z_bytes : nullptr};
+            (saved && lo.u2_bytes) ? (char*)saved + lo.h_bytes + lo.z_bytes : nullptr, diff_max_nnz(layer, st)};
   void* H = saved;
   void* Z = (saved && st->z_rows > 0) ? (char*)saved + lo.h_bytes : nullptr;
   mux_status s;
@@ -201,6 +226,8 @@ extern "C" mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_se
   else
     s = fast_forward(c, X, Y, H, Z, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes + lo.dys_bytes);
   if (s) return s;
+  // Diff-Pruning rows: the backbone wrote x W; the masked sparse update follows
+  if (st->n_diff > 0) ref_steps(c, layer->dtype, REF_DIFF_FWD, X, nullptr, Y, nullptr, nullptr, nullptr, nullptr, 0);
   return check_hip(fn);
 }
 
@@ -225,10 +252,11 @@ extern "C" mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_s
              (fast && st->n_tuning > 0) ? (char*)ws + lo.tasks_bytes + lo.g_bytes : nullptr, 1);
   CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP,
             (char*)ws + lo.tasks_bytes + lo.g_bytes, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes, layer->W, stream,
-            (saved && lo.u2_bytes) ? (char*)saved + lo.h_bytes + lo.z_bytes : nullptr};
+            (saved && lo.u2_bytes) ? (char*)saved + lo.h_bytes + lo.z_bytes : nullptr, diff_max_nnz(layer, st)};
   if (st->T == 0) {                 // no rows at all: zero gradients (or leave the accumulators as they are)
     if (!accumulate) {
-      const size_t big = (size_t)(st->r_max > 0 ? st->r_max : 1) * (size_t)(layer->K > layer->N ? layer->K : layer->N);
+      size_t big = (size_t)(st->r_max > 0 ? st->r_max : 1) * (size_t)(layer->K > layer->N ? layer->K : layer->N);
+      if ((size_t)c.diff_max_nnz > big) big = (size_t)c.diff_max_nnz;
       MUX_LAUNCH("zero_grads", k_zero_grads, dim3(st->n_tasks, (unsigned)((big + 255) / 256)), dim3(256), 0, stream, dtasks,
                  layer->K, layer->N);
     }
@@ -243,5 +271,7 @@ extern "C" mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_s
   else
     s = fast_backward(c, X, dY, H, Z, G, dX, accumulate, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes + lo.dys_bytes);
   if (s) return s;
+  if (st->n_diff > 0)
+    ref_steps(c, layer->dtype, REF_DIFF_BWD | REF_DIFF_GRAD, X, dY, nullptr, dX, nullptr, nullptr, nullptr, accumulate);
   return check_hip(fn);
 }

@@ -40,6 +40,8 @@ struct DevTask {
   int32_t row_count;
   int32_t zrow0;      // first row of this task inside the saved x W region (IA3_OUT, TUNING), else -1
   int64_t at_off;     // element offset of this task's transposed A_t inside the workspace region
+                      // DIFF tasks: A = values, dA = their gradient, B = row_ptr, L = col_idx, dB = col_ptr, dL = col_ent
+                      // (all int32 arrays), at_off = number of masked entries
 };
 static_assert(sizeof(DevTask) == 80, "DevTask layout");
 
@@ -57,7 +59,7 @@ struct mux_segtab {
   int32_t n_tasks = 0, chunk = 0, log2c = 0, n_chunks = 0, T = 0, valid_total = 0;
   int32_t max_pack_len = 0;
   uint32_t flags = 0;
-  int32_t r_max = 0, z_rows = 0, n_lora = 0, n_ia3 = 0, n_tuning = 0;   // r_max over the LORA and TUNING tasks
+  int32_t r_max = 0, z_rows = 0, n_lora = 0, n_ia3 = 0, n_tuning = 0, n_diff = 0;   // r_max over the LORA and TUNING tasks
   std::vector<int32_t> image;       // canonical serialisation
   std::vector<int32_t> dev_image;   // device image (host copy, source of the upload)
   std::vector<int32_t> row_task;    // T entries
@@ -103,6 +105,7 @@ struct CallCtx {
   const void* W;
   hipStream_t stream;
   void* U2;                // saved: pre-activations z D_t of the TUNING rows, [T][RP] (null without such tasks)
+  int diff_max_nnz;        // largest mask of the DIFF tasks of this call
 };
 
 // H / G row pitch in elements
@@ -120,7 +123,10 @@ enum : unsigned {
   REF_TUNE_DOWN = 128,   // TUNING forward, after z is saved: u = z D_t, Hs = s_t gelu(u)
   REF_TUNE_UP = 256,     // TUNING forward: Y = z + Hs U_t
   REF_TUNE_DZ = 512,     // TUNING backward, after Gs: dYs = dY + Gs D_t^T
-  REF_ONLY_TUNING = 1024 // REF_G, REF_DB, REF_DA touch the TUNING tasks only (the LORA ones ran on the matrix cores)
+  REF_ONLY_TUNING = 1024, // REF_G, REF_DB, REF_DA touch the TUNING tasks only (the LORA ones ran on the matrix cores)
+  REF_DIFF_FWD = 2048,    // DIFF forward, after the backbone GEMM: Y += x (M_t * delta_t)
+  REF_DIFF_BWD = 4096,    // DIFF backward, after the backbone GEMM: dX += g (M_t * delta_t)^T
+  REF_DIFF_GRAD = 8192    // DIFF backward: d delta_t = masked entries of x^T g
 };
 void ref_steps(const CallCtx& c, int dtype, unsigned which, const void* X, const void* dY, void* Y, void* dX, void* H,
                void* Z, void* G, int accumulate);

@@ -53,7 +53,8 @@ extern "C" mux_status mux_segtab_build(const mux_task_desc* tasks, int32_t n_tas
   int64_t total = 0;
   for (int32_t t = 0; t < n_tasks; ++t) {
     const mux_task_desc& d = tasks[t];
-    if (d.kind != MUX_ADAPTER_NONE && d.kind != MUX_ADAPTER_LORA && d.kind != MUX_ADAPTER_IA3_OUT && d.kind != MUX_ADAPTER_TUNING)
+    if (d.kind != MUX_ADAPTER_NONE && d.kind != MUX_ADAPTER_LORA && d.kind != MUX_ADAPTER_IA3_OUT && d.kind != MUX_ADAPTER_TUNING &&
+        d.kind != MUX_ADAPTER_DIFF)
       return fail(MUX_ERR_INVALID_ARG, "mux_segtab_build: unknown adapter kind");
     if ((d.kind == MUX_ADAPTER_LORA || d.kind == MUX_ADAPTER_TUNING) && (d.rank < 1 || d.rank > MUX_MAX_RANK))
       return fail(MUX_ERR_INVALID_ARG, "mux_segtab_build: adapter rank outside 1..MUX_MAX_RANK");
@@ -132,6 +133,7 @@ extern "C" mux_status mux_segtab_build(const mux_task_desc* tasks, int32_t n_tas
       if (d.kind == MUX_ADAPTER_IA3_OUT || d.kind == MUX_ADAPTER_TUNING) { ht.zrow0 = zrows; zrows += ht.row_count; }
       if (d.kind == MUX_ADAPTER_IA3_OUT) st->n_ia3++;
       if (d.kind == MUX_ADAPTER_TUNING) st->n_tuning++;
+      if (d.kind == MUX_ADAPTER_DIFF) st->n_diff++;
       if (d.kind == MUX_ADAPTER_LORA) st->n_lora++;
       if (ranked && d.rank > st->r_max) st->r_max = d.rank;
     }

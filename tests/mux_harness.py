@@ -50,7 +50,11 @@ class GpuLayer:
         self.B = [up(b) for b in lt.B]
         self.L = [up(l) for l in lt.L]
         M = len(wl.tasks)
-        self.layer = mx.LayerDesc(lt.K, lt.N, dtype, self.W, M, self.A, self.B, self.L, flags=layer_flags)
+        todev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        self.masks = [None if (not lt.masks or lt.masks[t] is None) else mx.SparseMask(lt.masks[t][0], lt.masks[t][1], lt.K, lt.N, todev)
+                      for t in range(M)]
+        self.layer = mx.LayerDesc(lt.K, lt.N, dtype, self.W, M, self.A, self.B, self.L, flags=layer_flags,
+                                  masks=self.masks if any(m is not None for m in self.masks) else None)
         nb = mx.mux_segtab_device_bytes(self.st)
         self.dtab = torch.zeros(nb, dtype=torch.uint8, device=dev)
         mx.mux_segtab_upload(self.st, self.dtab, nb)
@@ -93,8 +97,9 @@ def oracle_results(wl: wlm.Workload, lt: wlm.LayerTensors, row_task: np.ndarray,
     kinds = [t.kind for t in wl.tasks]
     ranks = [t.rank for t in wl.tasks]
     scales = [t.scale for t in wl.tasks]
-    f = oracle.forward(lt.X, lt.W, row_task, kinds, ranks, scales, lt.A, lt.B, lt.L, cols=cols)
-    b = oracle.backward(lt.X, lt.dY, lt.W, row_task, kinds, ranks, scales, lt.A, lt.B, lt.L, kcols=kcols, cols=cols)
+    S = lt.masks if lt.masks else None
+    f = oracle.forward(lt.X, lt.W, row_task, kinds, ranks, scales, lt.A, lt.B, lt.L, cols=cols, S=S)
+    b = oracle.backward(lt.X, lt.dY, lt.W, row_task, kinds, ranks, scales, lt.A, lt.B, lt.L, kcols=kcols, cols=cols, S=S)
     return {"Y": f["Y"], "dX": b["dX"], "dA": b["dA"], "dB": b["dB"], "dL": b["dL"]}
 
 

@@ -119,10 +119,31 @@ def test_adapter_tuning_kind(env, mode, seg_flags):
     run_case(env, tuning_workload(K=104, N=232, chunk=16), dtype=dtype, seg_flags=seg_flags, layer_flags=lf, seed=6)
 
 
-@pytest.mark.parametrize("which", ["mixed", "tuning"])
+def diff_workload(K=192, N=160, chunk=32, density=0.02):
+    """The selective kind (masked sparse update of W) beside the others; one task with an empty mask."""
+    tasks = [wlm.Task(wlm.KIND_LORA, 16, 2.0, [100]), wlm.Task(wlm.KIND_DIFF, 0, 1.0, [70, 45], density=density),
+             wlm.Task(wlm.KIND_IA3, 0, 1.0, [33]), wlm.Task(wlm.KIND_DIFF, 0, 1.0, [150, 21], density=density * 4),
+             wlm.Task(wlm.KIND_ADAPTER, 8, 1.0, [64]), wlm.Task(wlm.KIND_DIFF, 0, 1.0, [5], density=0.0),
+             wlm.Task(wlm.KIND_DIFF, 0, 1.0, [], density=density)]
+    return wlm.Workload(name="diff", layers=[("w", K, N)], tasks=tasks, chunk=chunk, sigma_w=0.08, sigma_ab=0.08)
+
+
+@pytest.mark.parametrize("seg_flags", [0, 1])
+@pytest.mark.parametrize("mode", ["bf16", "bf16_ref", "f32"])
+def test_diff_pruning_kind(env, mode, seg_flags):
+    """Diff-Pruning tasks (trainable values on a fixed sparse mask over W) beside every other kind, in the three modes,
+    on two shapes."""
+    mx, _ = env
+    dtype = mx.MUX_DT_F32 if mode == "f32" else mx.MUX_DT_BF16
+    lf = mx.MUX_LAYER_REFERENCE_KERNELS if mode == "bf16_ref" else 0
+    run_case(env, diff_workload(), dtype=dtype, seg_flags=seg_flags, layer_flags=lf, seed=7)
+    run_case(env, diff_workload(K=104, N=328, chunk=16, density=0.05), dtype=dtype, seg_flags=seg_flags, layer_flags=lf, seed=8)
+
+
+@pytest.mark.parametrize("which", ["mixed", "tuning", "diff"])
 def test_accumulate_and_determinism(env, which):
     mx, torch = env
-    wl = mixed_workload() if which == "mixed" else tuning_workload()
+    wl = {"mixed": mixed_workload, "tuning": tuning_workload, "diff": diff_workload}[which]()
     g, got, ref, _ = run_case(env, wl)
     first = {k: [None if t is None else t.clone() for t in getattr(g, k)] for k in ("dA", "dB", "dL")}
     y1, dx1 = g.Y.clone(), g.dX.clone()
@@ -139,20 +160,22 @@ def test_accumulate_and_determinism(env, which):
             assert a is None or torch.allclose(b, 2 * a, rtol=1e-6, atol=0)
 
 
-@pytest.mark.parametrize("which", ["mixed", "tuning"])
+@pytest.mark.parametrize("which", ["mixed", "tuning", "diff"])
 def test_nan_isolation(env, which):
     """Poisoning one task's rows, adapters and every padding row with NaN/Inf leaves the other
     tasks' outputs and gradients bit-identical (section 3.2)."""
     mx, torch = env
-    wl = mixed_workload() if which == "mixed" else tuning_workload()
+    wl = {"mixed": mixed_workload, "tuning": tuning_workload, "diff": diff_workload}[which]()
     g, got, _, _ = run_case(env, wl)
     ot = oracle_table(wl)
-    j = 2 if which == "mixed" else 3          # a LoRA task / an Adapter-Tuning task
+    j = 2 if which == "mixed" else 3          # a LoRA task / an Adapter-Tuning task / a Diff-Pruning task
     rows = torch.from_numpy(ot.task_rows[j]).to("cuda:0")
     pad = torch.from_numpy(np.nonzero(ot.row_task < 0)[0]).to("cuda:0")
     g.X[rows] = float("nan"); g.dY[rows] = float("inf")
     g.X[pad] = float("nan"); g.dY[pad] = float("nan")
-    g.A[j].fill_(float("nan")); g.B[j].fill_(float("nan"))
+    g.A[j].fill_(float("nan"))
+    if g.B[j] is not None:
+        g.B[j].fill_(float("nan"))
     g.forward(); g.backward()
     got2 = g.results()
     for t in range(len(wl.tasks)):
@@ -266,7 +289,7 @@ def test_random_sweep(env, block):
     and odd sizes, so every GEMM kernel is met), chunk sizes, pack lengths, both table modes, empty tasks."""
     mx, _ = env
     rng = np.random.default_rng(9000 + block)
-    kinds = [wlm.KIND_LORA, wlm.KIND_LORA, wlm.KIND_IA3, wlm.KIND_ADAPTER, wlm.KIND_NONE]
+    kinds = [wlm.KIND_LORA, wlm.KIND_LORA, wlm.KIND_IA3, wlm.KIND_ADAPTER, wlm.KIND_NONE, wlm.KIND_DIFF]
     for case in range(6):
         gran = int(rng.choice([64, 64, 32, 8, 1]))
         K = gran * int(rng.integers(1, max(2, 520 // gran)))
@@ -278,7 +301,8 @@ def test_random_sweep(env, block):
             rank = int(rng.integers(1, 65)) if kind in (wlm.KIND_LORA, wlm.KIND_ADAPTER) else 0
             nseq = int(rng.integers(0, 4))
             lens = [int(v) for v in rng.integers(1, 200, size=nseq)]
-            tasks.append(wlm.Task(kind, rank, float(rng.choice([0.5, 1.0, 2.0])), lens))
+            tasks.append(wlm.Task(kind, rank, float(rng.choice([0.5, 1.0, 2.0])), lens,
+                                  density=float(rng.choice([0.0, 0.01, 0.1])) if kind == wlm.KIND_DIFF else 0.0))
         if sum(t.tokens for t in tasks) == 0:
             tasks.append(wlm.Task(wlm.KIND_LORA, 8, 1.0, [17]))
         wl = wlm.Workload(name=f"rnd{block}_{case}", layers=[("w", K, N)], tasks=tasks, chunk=chunk,
@@ -288,12 +312,12 @@ def test_random_sweep(env, block):
         run_case(env, wl, dtype=dtype, seg_flags=int(rng.integers(0, 2)), seed=100 * block + case)
 
 
-@pytest.mark.parametrize("which", ["mixed", "tuning"])
+@pytest.mark.parametrize("which", ["mixed", "tuning", "diff"])
 def test_graph_capture_and_replay(env, which):
     """The calls allocate nothing and never synchronise, so a forward + backward pair can be captured into a HIP
     graph; every replay (with eager work and synchronisations in between) must give the eager results bit for bit."""
     mx, torch = env
-    wl = mixed_workload() if which == "mixed" else tuning_workload()
+    wl = {"mixed": mixed_workload, "tuning": tuning_workload, "diff": diff_workload}[which]()
     g, got, ref, _ = run_case(env, wl)                 # eager, also warms up every kernel
     torch.cuda.synchronize()
     keep = {"Y": g.Y.clone(), "dX": g.dX.clone()}
