@@ -28,7 +28,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=1,
-                    help="index into BASELINE.json configs (default 1: LLaMA-7B shapes); 5 = those shapes with two Adapter-Tuning tasks")
+                    help="index into BASELINE.json configs (default 1: LLaMA-7B shapes); 5 / 6 = those shapes with two "
+                         "Adapter-Tuning / Diff-Pruning tasks")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -68,6 +69,13 @@ def setup(mx, torch, wl, seed):
         L.A = [randn((K if t.kind == 1 else N, t.rank), 0.02) if t.kind in (1, 3) else None for t in wl.tasks]
         L.B = [randn((t.rank, N), 0.02) if t.kind in (1, 3) else None for t in wl.tasks]
         L.L = [randn((N,), 0.02, 1.0) if t.kind == 2 else None for t in wl.tasks]
+        # Diff-Pruning: a random mask of the stated density over W, values in the A slot
+        L.masks = [None] * len(wl.tasks)
+        for ti, t in enumerate(wl.tasks):
+            if t.kind == 4:
+                kn = torch.nonzero(torch.rand((K, N), device=dev, generator=gen) < t.density).cpu().numpy()
+                L.masks[ti] = mx.SparseMask(kn[:, 0], kn[:, 1], K, N, lambda a: torch.from_numpy(a).to(dev))
+                L.A[ti] = randn((L.masks[ti].nnz,), 0.02)
         L.X = randn((T, K))
         L.dY = randn((T, N))
         L.Y = torch.empty((T, N), device=dev, dtype=bf)
@@ -75,7 +83,8 @@ def setup(mx, torch, wl, seed):
         L.dA = [None if a is None else torch.zeros(a.shape, device=dev, dtype=torch.float32) for a in L.A]
         L.dB = [None if b is None else torch.zeros(b.shape, device=dev, dtype=torch.float32) for b in L.B]
         L.dL = [None if l is None else torch.zeros(l.shape, device=dev, dtype=torch.float32) for l in L.L]
-        L.desc = mx.LayerDesc(K, N, mx.MUX_DT_BF16, L.W, len(wl.tasks), L.A, L.B, L.L)
+        L.desc = mx.LayerDesc(K, N, mx.MUX_DT_BF16, L.W, len(wl.tasks), L.A, L.B, L.L,
+                              masks=L.masks if any(m is not None for m in L.masks) else None)
         L.saved_bytes = mx.mux_lora_saved_bytes(L.desc, st)
         L.saved = torch.zeros(max(L.saved_bytes, 256), dtype=torch.uint8, device=dev)
         ws_bytes = max(ws_bytes, mx.mux_lora_workspace_bytes(L.desc, st))
@@ -119,8 +128,9 @@ def unmultiplexed(mx, torch, wl, st, layers, steps, warmup, n_groups=None):
         mx.mux_segtab_upload(st1, dtab1, nb)
         calls = []
         for L in layers:
+            mk = [L.masks[t] for t in ts]
             desc = mx.LayerDesc(L.K, L.N, mx.MUX_DT_BF16, L.W, len(ts), [L.A[t] for t in ts], [L.B[t] for t in ts],
-                                [L.L[t] for t in ts])
+                                [L.L[t] for t in ts], masks=mk if any(m is not None for m in mk) else None)
             sb = mx.mux_lora_saved_bytes(desc, st1)
             calls.append((desc, L.X[r0:r0 + rc], L.dY[r0:r0 + rc], L.Y[r0:r0 + rc], L.dX[r0:r0 + rc],
                           torch.zeros(max(sb, 256), dtype=torch.uint8, device=dev), [L.dA[t] for t in ts],

@@ -166,6 +166,14 @@ def config(idx: int, seed: int = 0) -> Workload:
         return Workload(
             name="llama7b_tuning", layers=_llama_layers(4096, 11008), chunk=512, tasks=tasks,
             notes="2 LoRA r16 + 2 Adapter-Tuning r64 tasks, 5120 tokens, chunk 512")
+    if idx == 6:
+        # not one of the benchmark configs either: two of the four tasks switched to the selective kind, 0.5 % of the
+        # entries of every W trainable (the sparsity that method reports), to measure that kind's kernels
+        tasks = [Task(KIND_LORA, 16, 2.0, [2048]), Task(KIND_DIFF, 0, 1.0, [1536], density=0.005),
+                 Task(KIND_LORA, 16, 2.0, [1024]), Task(KIND_DIFF, 0, 1.0, [512], density=0.005)]
+        return Workload(
+            name="llama7b_diff", layers=_llama_layers(4096, 11008), chunk=512, tasks=tasks,
+            notes="2 LoRA r16 + 2 Diff-Pruning (0.5 % of W) tasks, 5120 tokens, chunk 512")
     raise ValueError(f"no config {idx}")
 
 

@@ -83,7 +83,7 @@ struct Layout {
   size_t esz;          // bytes per stored element
   int RP;              // H / G row pitch in elements
   size_t h_bytes, z_bytes, u2_bytes, saved_bytes;
-  size_t tasks_bytes, g_bytes, at_bytes, dys_bytes, part_bytes, ws_bytes;
+  size_t tasks_bytes, g_bytes, at_bytes, dys_bytes, part_bytes, dt_bytes, ws_bytes;
 };
 
 Layout make_layout(const mux_layer_desc* L, const mux_segtab* st) {
@@ -103,7 +103,8 @@ Layout make_layout(const mux_layer_desc* L, const mux_segtab* st) {
   o.at_bytes = L->dtype == MUX_DT_BF16 ? align256(at_elems * 2) : 0;
   o.part_bytes = L->dtype == MUX_DT_BF16 ? fast_partial_bytes(L->K, L->N, st) : 0;
   o.dys_bytes = (L->dtype == MUX_DT_BF16 || st->n_tuning > 0) ? o.z_bytes : 0;
-  o.ws_bytes = o.tasks_bytes + o.g_bytes + o.at_bytes + o.dys_bytes + o.part_bytes;
+  o.dt_bytes = diff_transposed_bytes(L->K, L->N, st, o.esz);
+  o.ws_bytes = o.tasks_bytes + o.g_bytes + o.at_bytes + o.dys_bytes + o.part_bytes + 2 * o.dt_bytes;
   return o;
 }
 
@@ -217,7 +218,8 @@ extern "C" mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_se
              (fast && st->n_lora + st->n_tuning > 0) ? at_region : nullptr, 0);
   CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP,
             (char*)ws + lo.tasks_bytes + lo.g_bytes, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes, layer->W, stream,
-            (saved && lo.u2_bytes) ? (char*)saved + lo.h_bytes + lo.z_bytes : nullptr, diff_max_nnz(layer, st)};
+            (saved && lo.u2_bytes) ? (char*)saved + lo.h_bytes + lo.z_bytes : nullptr, diff_max_nnz(layer, st),
+            {(char*)ws + lo.ws_bytes - 2 * lo.dt_bytes, (char*)ws + lo.ws_bytes - lo.dt_bytes}};
   void* H = saved;
   void* Z = (saved && st->z_rows > 0) ? (char*)saved + lo.h_bytes : nullptr;
   mux_status s;
@@ -227,7 +229,7 @@ extern "C" mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_se
     s = fast_forward(c, X, Y, H, Z, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes + lo.dys_bytes);
   if (s) return s;
   // Diff-Pruning rows: the backbone wrote x W; the masked sparse update follows
-  if (st->n_diff > 0) ref_steps(c, layer->dtype, REF_DIFF_FWD, X, nullptr, Y, nullptr, nullptr, nullptr, nullptr, 0);
+  diff_forward(c, layer->dtype, X, Y);
   return check_hip(fn);
 }
 
@@ -252,7 +254,8 @@ extern "C" mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_s
              (fast && st->n_tuning > 0) ? (char*)ws + lo.tasks_bytes + lo.g_bytes : nullptr, 1);
   CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP,
             (char*)ws + lo.tasks_bytes + lo.g_bytes, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes, layer->W, stream,
-            (saved && lo.u2_bytes) ? (char*)saved + lo.h_bytes + lo.z_bytes : nullptr, diff_max_nnz(layer, st)};
+            (saved && lo.u2_bytes) ? (char*)saved + lo.h_bytes + lo.z_bytes : nullptr, diff_max_nnz(layer, st),
+            {(char*)ws + lo.ws_bytes - 2 * lo.dt_bytes, (char*)ws + lo.ws_bytes - lo.dt_bytes}};
   if (st->T == 0) {                 // no rows at all: zero gradients (or leave the accumulators as they are)
     if (!accumulate) {
       size_t big = (size_t)(st->r_max > 0 ? st->r_max : 1) * (size_t)(layer->K > layer->N ? layer->K : layer->N);
@@ -271,7 +274,6 @@ extern "C" mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_s
   else
     s = fast_backward(c, X, dY, H, Z, G, dX, accumulate, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes + lo.dys_bytes);
   if (s) return s;
-  if (st->n_diff > 0)
-    ref_steps(c, layer->dtype, REF_DIFF_BWD | REF_DIFF_GRAD, X, dY, nullptr, dX, nullptr, nullptr, nullptr, accumulate);
+  diff_backward(c, layer->dtype, X, dY, dX, accumulate);
   return check_hip(fn);
 }

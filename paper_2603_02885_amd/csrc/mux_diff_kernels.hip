@@ -1,0 +1,239 @@
+// Diff-Pruning kind (section 2.1, section 5: trainable values delta_t on a fixed sparse mask M_t over W):
+//   forward   Y  = x (W + M_t * delta_t)      -> after the backbone GEMM wrote x W:      Y  += x (M_t * delta_t)
+//   backward  dX = g (W + M_t * delta_t)^T    -> after the backbone GEMM wrote g W^T:    dX += g (M_t * delta_t)^T
+//             d delta_t[e] = sum over the task's rows of x[i][k_e] * g[i][n_e]
+//
+// All three are sums over (entry, row) pairs with a handful of FMAs each, so what they cost is how x and g are
+// fetched.  An entry needs one COLUMN of the task's rows of x (or g).  The rows of the Diff-Pruning tasks are
+// therefore first copied in blocks of 64 rows with the block transposed -- T[block][column][64 rows], one aligned
+// 128-byte (bf16) or 256-byte (fp32) line per (block, column) -- with the padding rows selected to zero.  After that
+// every (entry, block) pair reads whole lines:
+//   sparse update   a few lanes per output column and block with the 64 row sums between them, a plain loop over the
+//                   entries of that column (column listing of the mask forward, row listing backward)
+//   masked gradient a few lanes per entry, a plain loop over the task's blocks, two lines per block
+// No barriers, no atomics; every sum has one owner and a fixed order.
+#include "mux_device_utils.h"
+
+namespace mux {
+namespace {
+
+constexpr int TS64 = 0;  // index of the 64-row work list
+
+// A line of a transposed block (64 rows of one column) is read by LPL neighbouring lanes, 16 bytes each, so that one
+// load instruction of a wave covers 64 / LPL whole lines and no byte is fetched twice.
+template <class S> struct Piece;
+template <> struct Piece<float> {
+  static constexpr int LPL = 16, RPL = 4;      // lanes per line, rows per lane
+  static __device__ __forceinline__ void ld(const float* __restrict__ line, int sub, float (&x)[4]) {
+    const float4 v = ((const float4*)line)[sub];
+    x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+  }
+};
+template <> struct Piece<bf16_t> {
+  static constexpr int LPL = 8, RPL = 8;
+  static __device__ __forceinline__ void ld(const bf16_t* __restrict__ line, int sub, float (&x)[8]) {
+    const uint4 v = ((const uint4*)line)[sub];
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      x[2 * h] = __uint_as_float(w[h] << 16);
+      x[2 * h + 1] = __uint_as_float(w[h] & 0xffff0000u);
+    }
+  }
+};
+
+// Block-transposed copy of the Diff-Pruning rows of In [T, C]:  Out[(block * C + c) * 64 + r] = In[row0 + r][c], zero
+// for padding rows and for r beyond the item.  grid = (64-row items, ceil(C / 64)).  VEC: the rows of In can be read
+// 16 bytes at a time (C a multiple of 16 bytes' worth of elements, In 16-byte aligned).
+template <class S, bool VEC>
+__global__ __launch_bounds__(256) void k_diff_transpose(const int32_t* __restrict__ dtab, const DevTask* __restrict__ tasks,
+                                                        const S* __restrict__ In, S* __restrict__ Out, int C) {
+  constexpr int VE = 16 / (int)sizeof(S);          // elements per 16-byte vector
+  __shared__ __align__(16) S tile[64][64 + VE];
+  const ItemView it = load_item(dtab, TS64, blockIdx.x);
+  if (it.task < 0 || tasks[it.task].kind != MUX_ADAPTER_DIFF) return;
+  const DevTask tk = tasks[it.task];
+  if (tk.at_off == 0) return;
+  const int c0 = blockIdx.y * 64;
+  {
+    const int r = threadIdx.x >> 2, cq = (threadIdx.x & 3) * 16;
+    const bool v = r < it.nrows && row_is_valid(dtab, it.row0 + r);
+    __align__(16) S tmp[16];
+    const S* src = In + (size_t)(it.row0 + r) * C + c0 + cq;
+    if (VEC) {
+#pragma unroll
+      for (int i = 0; i < 16 / VE; ++i)
+        ((uint4*)tmp)[i] = (v && c0 + cq + i * VE < C) ? ((const uint4*)src)[i] : uint4{0u, 0u, 0u, 0u};
+    } else {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) tmp[i] = (v && c0 + cq + i < C) ? src[i] : S(0);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) tile[cq + i][r] = tmp[i];
+  }
+  __syncthreads();
+  const int cc = threadIdx.x >> 2, rq = (threadIdx.x & 3) * 16;
+  if (c0 + cc < C) {
+    const size_t block = (size_t)(tk.zrow0 + it.row0 - tk.row_begin) >> 6;
+    uint4* o = (uint4*)(Out + (block * (size_t)C + c0 + cc) * 64 + rq);
+    const uint4* t = (const uint4*)&tile[cc][rq];
+#pragma unroll
+    for (int i = 0; i < 16 / VE; ++i) o[i] = t[i];
+  }
+}
+
+// Sparse update of one 64-row item: Out[row][c] += sum over the entries (j, v) of output column c of Tin[block][j][row] * v.
+// LPL lanes share one output column, each with RPL of the 64 row sums; grid = items x ceil(Cout / (256 / LPL))
+// workgroups, the column blocks of one item next to each other so that they find the item's block in the L2 caches.
+template <class S>
+__global__ __launch_bounds__(256) void k_diff_apply(const int32_t* __restrict__ dtab, const DevTask* __restrict__ tasks,
+                                                    const S* __restrict__ Tin, S* __restrict__ Out, int Cin, int Cout,
+                                                    int backward) {
+  constexpr int LPL = Piece<S>::LPL, RPL = Piece<S>::RPL, CPW = 256 / LPL;
+  const int ncb = (Cout + CPW - 1) / CPW;
+  const ItemView it = load_item(dtab, TS64, blockIdx.x / ncb);
+  if (it.task < 0 || it.nvalid == 0 || tasks[it.task].kind != MUX_ADAPTER_DIFF) return;
+  const DevTask tk = tasks[it.task];
+  const int sub = threadIdx.x % LPL;
+  const int c = (blockIdx.x % ncb) * CPW + threadIdx.x / LPL;
+  if (tk.at_off == 0 || c >= Cout) return;
+  const S* val = (const S*)tk.A;
+  const int32_t* ptr = backward ? (const int32_t*)tk.B : (const int32_t*)tk.dB;       // row_ptr / col_ptr
+  const int32_t* ent = backward ? (const int32_t*)tk.L : (const int32_t*)tk.dL;       // col_idx / (k, e) pairs
+  const int e0 = ptr[c], e1 = ptr[c + 1];
+  if (e0 >= e1) return;
+  const size_t block = (size_t)(tk.zrow0 + it.row0 - tk.row_begin) >> 6;
+  const S* base = Tin + block * (size_t)Cin * 64;
+  float acc[RPL];
+#pragma unroll
+  for (int r = 0; r < RPL; ++r) acc[r] = 0.f;
+#pragma unroll 4
+  for (int e = e0; e < e1; ++e) {
+    const int j = backward ? ent[e] : ent[2 * e];
+    const float v = Store<S>::ld(val, (size_t)(backward ? e : ent[2 * e + 1]));
+    float x[RPL];
+    Piece<S>::ld(base + (size_t)j * 64, sub, x);
+#pragma unroll
+    for (int r = 0; r < RPL; ++r) acc[r] = fmaf(x[r], v, acc[r]);
+  }
+#pragma unroll
+  for (int r = 0; r < RPL; ++r) {
+    const int m = sub * RPL + r;
+    if (m < it.nrows && row_is_valid(dtab, it.row0 + m)) {
+      const size_t o = (size_t)(it.row0 + m) * Cout + c;
+      Store<S>::st(Out, o, Store<S>::ld(Out, o) + acc[r]);
+    }
+  }
+}
+
+// d delta[e] = sum over the task's 64-row blocks of <Xt[block][k_e][.], Gt[block][n_e][.]>.  A wave owns 64 consecutive
+// entries; LPL lanes share one entry at a time (a wave's load covers 64 / LPL whole lines), each lane summing its RPL
+// rows over the blocks in ascending order; the LPL partial sums are then added in a fixed tree.
+// grid = (tasks, ceil(max nnz / 256)).
+template <class S>
+__global__ __launch_bounds__(256) void k_diff_grad(const DevTask* __restrict__ tasks, const S* __restrict__ Xt,
+                                                   const S* __restrict__ Gt, int K, int N, int accumulate) {
+  constexpr int LPL = Piece<S>::LPL, RPL = Piece<S>::RPL, EPI = 64 / LPL;    // EPI: entries per load instruction
+  const DevTask tk = tasks[blockIdx.x];
+  if (tk.kind != MUX_ADAPTER_DIFF || tk.dA == nullptr) return;
+  const int lane = threadIdx.x & 63;
+  const int wave_e0 = blockIdx.y * 256 + (threadIdx.x & ~63);
+  if (wave_e0 >= tk.at_off) return;                       // whole wave
+  const int e_own = wave_e0 + lane;
+  int k_own = 0, n_own = 0;                               // lanes past the last entry work on entry (0, 0), unused
+  if (e_own < tk.at_off) {
+    const int32_t* row_ptr = (const int32_t*)tk.B;
+    int lo = 0, hi = K;                                   // the row k with row_ptr[k] <= e < row_ptr[k+1]
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (row_ptr[mid] <= e_own) lo = mid; else hi = mid;
+    }
+    k_own = lo;
+    n_own = ((const int32_t*)tk.L)[e_own];
+  }
+  const int sub = lane % LPL, grp = lane / LPL;
+  int ks[LPL], ns[LPL];
+#pragma unroll
+  for (int i = 0; i < LPL; ++i) {                         // pass i works on entry wave_e0 + i * EPI + grp
+    ks[i] = __shfl(k_own, i * EPI + grp);
+    ns[i] = __shfl(n_own, i * EPI + grp);
+  }
+  float acc[LPL];
+#pragma unroll
+  for (int i = 0; i < LPL; ++i) acc[i] = 0.f;
+  const int nb = (tk.row_count + 63) >> 6;
+  const size_t b0 = (size_t)tk.zrow0 >> 6;
+  for (int b = 0; b < nb; ++b) {
+    const S* xb = Xt + (b0 + b) * (size_t)K * 64;
+    const S* gb = Gt + (b0 + b) * (size_t)N * 64;
+#pragma unroll
+    for (int i = 0; i < LPL; ++i) {
+      float x[RPL], g[RPL];
+      Piece<S>::ld(xb + (size_t)ks[i] * 64, sub, x);
+      Piece<S>::ld(gb + (size_t)ns[i] * 64, sub, g);
+#pragma unroll
+      for (int r = 0; r < RPL; ++r) acc[i] = fmaf(x[r], g[r], acc[i]);
+    }
+  }
+  float mine = 0.f;
+#pragma unroll
+  for (int i = 0; i < LPL; ++i) {
+    float v = acc[i];
+#pragma unroll
+    for (int m = 1; m < LPL; m <<= 1) v += __shfl_xor(v, m);
+    if (sub == i) mine = v;
+  }
+  const int e_w = wave_e0 + sub * EPI + grp;              // the lane with sub == i writes the entry of pass i
+  if (e_w < tk.at_off) tk.dA[e_w] = accumulate ? tk.dA[e_w] + mine : mine;
+}
+
+template <class S>
+void transpose(const CallCtx& c, const void* In, void* Out, int C, const char* name) {
+  const int n_items = (int)c.st->items[TS64].size();
+  const bool vec = C % (16 / (int)sizeof(S)) == 0 && ((uintptr_t)In & 15) == 0;
+  if (vec)
+    MUX_LAUNCH(name, (k_diff_transpose<S, true>), dim3(n_items, (C + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks,
+               (const S*)In, (S*)Out, C);
+  else
+    MUX_LAUNCH(name, (k_diff_transpose<S, false>), dim3(n_items, (C + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks,
+               (const S*)In, (S*)Out, C);
+}
+
+template <class S>
+void forward(const CallCtx& c, const void* X, void* Y) {
+  const int n_items = (int)c.st->items[TS64].size();
+  transpose<S>(c, X, c.diffT[0], c.K, "diff_xt");
+  constexpr int CPW = 256 / Piece<S>::LPL;
+  MUX_LAUNCH("diff_fwd", k_diff_apply<S>, dim3((unsigned)n_items * (unsigned)((c.N + CPW - 1) / CPW)), dim3(256), 0, c.stream, c.dtab, c.dtasks,
+             (const S*)c.diffT[0], (S*)Y, c.K, c.N, 0);
+}
+
+template <class S>
+void backward(const CallCtx& c, const void* X, const void* dY, void* dX, int accumulate) {
+  const int n_items = (int)c.st->items[TS64].size();
+  transpose<S>(c, dY, c.diffT[1], c.N, "diff_gt");
+  if (dX)
+    MUX_LAUNCH("diff_bwd", k_diff_apply<S>, dim3((unsigned)n_items * (unsigned)((c.K + (256 / Piece<S>::LPL) - 1) / (256 / Piece<S>::LPL))), dim3(256), 0, c.stream, c.dtab, c.dtasks,
+               (const S*)c.diffT[1], (S*)dX, c.N, c.K, 1);
+  transpose<S>(c, X, c.diffT[0], c.K, "diff_xt");
+  MUX_LAUNCH("diff_grad", k_diff_grad<S>, dim3(c.st->n_tasks, (c.diff_max_nnz + 255) / 256), dim3(256), 0, c.stream,
+             c.dtasks, (const S*)c.diffT[0], (const S*)c.diffT[1], c.K, c.N, accumulate);
+}
+
+}  // namespace
+
+size_t diff_transposed_bytes(int K, int N, const mux_segtab* st, size_t esz) {
+  return st->n_diff > 0 ? align256((size_t)st->d_rows * (size_t)(K > N ? K : N) * esz) : 0;
+}
+
+void diff_forward(const CallCtx& c, int dtype, const void* X, void* Y) {
+  if (c.st->n_diff == 0 || c.diff_max_nnz == 0 || c.st->items[TS64].empty()) return;
+  if (dtype == MUX_DT_F32) forward<float>(c, X, Y); else forward<bf16_t>(c, X, Y);
+}
+
+void diff_backward(const CallCtx& c, int dtype, const void* X, const void* dY, void* dX, int accumulate) {
+  if (c.st->n_diff == 0 || c.diff_max_nnz == 0 || c.st->items[TS64].empty()) return;
+  if (dtype == MUX_DT_F32) backward<float>(c, X, dY, dX, accumulate); else backward<bf16_t>(c, X, dY, dX, accumulate);
+}
+
+}  // namespace mux

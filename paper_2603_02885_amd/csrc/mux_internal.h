@@ -38,7 +38,8 @@ struct DevTask {
   int32_t rank;
   int32_t row_begin;
   int32_t row_count;
-  int32_t zrow0;      // first row of this task inside the saved x W region (IA3_OUT, TUNING), else -1
+  int32_t zrow0;      // first row of this task inside the saved x W region (IA3_OUT, TUNING) or inside the
+                      // block-transposed copies (DIFF, a multiple of 64), else -1
   int64_t at_off;     // element offset of this task's transposed A_t inside the workspace region
                       // DIFF tasks: A = values, dA = their gradient, B = row_ptr, L = col_idx, dB = col_ptr, dL = col_ent
                       // (all int32 arrays), at_off = number of masked entries
@@ -59,6 +60,7 @@ struct mux_segtab {
   int32_t n_tasks = 0, chunk = 0, log2c = 0, n_chunks = 0, T = 0, valid_total = 0;
   int32_t max_pack_len = 0;
   uint32_t flags = 0;
+  int32_t d_rows = 0;               // rows of the block-transposed copies of the DIFF tasks (each task rounded up to 64)
   int32_t r_max = 0, z_rows = 0, n_lora = 0, n_ia3 = 0, n_tuning = 0, n_diff = 0;   // r_max over the LORA and TUNING tasks
   std::vector<int32_t> image;       // canonical serialisation
   std::vector<int32_t> dev_image;   // device image (host copy, source of the upload)
@@ -106,6 +108,7 @@ struct CallCtx {
   hipStream_t stream;
   void* U2;                // saved: pre-activations z D_t of the TUNING rows, [T][RP] (null without such tasks)
   int diff_max_nnz;        // largest mask of the DIFF tasks of this call
+  void* diffT[2];          // workspace: block-transposed copies of the DIFF rows of X ([0]) and of dY ([1])
 };
 
 // H / G row pitch in elements
@@ -123,13 +126,15 @@ enum : unsigned {
   REF_TUNE_DOWN = 128,   // TUNING forward, after z is saved: u = z D_t, Hs = s_t gelu(u)
   REF_TUNE_UP = 256,     // TUNING forward: Y = z + Hs U_t
   REF_TUNE_DZ = 512,     // TUNING backward, after Gs: dYs = dY + Gs D_t^T
-  REF_ONLY_TUNING = 1024, // REF_G, REF_DB, REF_DA touch the TUNING tasks only (the LORA ones ran on the matrix cores)
-  REF_DIFF_FWD = 2048,    // DIFF forward, after the backbone GEMM: Y += x (M_t * delta_t)
-  REF_DIFF_BWD = 4096,    // DIFF backward, after the backbone GEMM: dX += g (M_t * delta_t)^T
-  REF_DIFF_GRAD = 8192    // DIFF backward: d delta_t = masked entries of x^T g
+  REF_ONLY_TUNING = 1024  // REF_G, REF_DB, REF_DA touch the TUNING tasks only (the LORA ones ran on the matrix cores)
 };
 void ref_steps(const CallCtx& c, int dtype, unsigned which, const void* X, const void* dY, void* Y, void* dX, void* H,
                void* Z, void* G, int accumulate);
+
+// Diff-Pruning tasks, both storage types: the masked sparse update after the backbone GEMM, and the masked gradient
+size_t diff_transposed_bytes(int K, int N, const mux_segtab* st, size_t esz);
+void diff_forward(const CallCtx& c, int dtype, const void* X, void* Y);                                       // Y += x (M_t * delta_t)
+void diff_backward(const CallCtx& c, int dtype, const void* X, const void* dY, void* dX, int accumulate);     // dX, d delta_t
 
 // matrix-core backbone GEMM (bf16)
 bool gemm_mfma_supported(const CallCtx& c);

@@ -382,71 +382,6 @@ __global__ __launch_bounds__(256) void k_tune_add(const int32_t* __restrict__ dt
   }
 }
 
-// DIFF (masked sparse update of W), after the backbone GEMM wrote Out = In W (or In W^T):
-//   forward   Out = Y [T,N],  In = X [T,K]:   Y[i][n]  += sum over the entries of column n of x[i][k] * delta[e]
-//   backward  Out = dX [T,K], In = dY [T,N]:  dX[i][k] += sum over the entries of row k    of g[i][n] * delta[e]
-// One thread per output column, eight rows at a time; the entries of a column (row) are walked in ascending
-// order, so the sum order is fixed.  grid = (items, ceil(Cout/256)).
-template <class S>
-__global__ __launch_bounds__(256) void k_diff_apply(const int32_t* __restrict__ dtab, const DevTask* __restrict__ tasks,
-                                                    const S* __restrict__ In, S* __restrict__ Out, int Cin, int Cout,
-                                                    int backward) {
-  const ItemView it = load_item(dtab, TS64, blockIdx.x);
-  if (it.task < 0 || it.nvalid == 0 || tasks[it.task].kind != MUX_ADAPTER_DIFF) return;
-  const DevTask tk = tasks[it.task];
-  const int c = blockIdx.y * 256 + threadIdx.x;
-  if (c >= Cout || tk.at_off == 0) return;
-  const S* val = (const S*)tk.A;
-  const int32_t* ptr = backward ? (const int32_t*)tk.B : (const int32_t*)tk.dB;       // row_ptr / col_ptr
-  const int32_t* ent = backward ? (const int32_t*)tk.L : (const int32_t*)tk.dL;       // col_idx / (k, e) pairs
-  const int e0 = ptr[c], e1 = ptr[c + 1];
-  if (e0 == e1) return;
-  for (int m0 = 0; m0 < it.nrows; m0 += 8) {
-    float acc[8];
-    bool ok[8];
-#pragma unroll
-    for (int r = 0; r < 8; ++r) { acc[r] = 0.f; ok[r] = m0 + r < it.nrows && row_is_valid(dtab, it.row0 + m0 + r); }
-    for (int i = e0; i < e1; ++i) {
-      const int j = backward ? ent[i] : ent[2 * i];                 // contraction index: n (backward) or k (forward)
-      const float v = Store<S>::ld(val, (size_t)(backward ? i : ent[2 * i + 1]));
-#pragma unroll
-      for (int r = 0; r < 8; ++r)
-        if (ok[r]) acc[r] = fmaf(Store<S>::ld(In, (size_t)(it.row0 + m0 + r) * Cin + j), v, acc[r]);
-    }
-#pragma unroll
-    for (int r = 0; r < 8; ++r)
-      if (ok[r]) {
-        const size_t o = (size_t)(it.row0 + m0 + r) * Cout + c;
-        Store<S>::st(Out, o, Store<S>::ld(Out, o) + acc[r]);
-      }
-  }
-}
-
-// DIFF: d delta[e] = sum over the task's rows of x[i][k_e] * g[i][n_e], rows ascending.  grid = (tasks, ceil(max nnz/256)).
-template <class S>
-__global__ __launch_bounds__(256) void k_diff_grad(const int32_t* __restrict__ dtab, const DevTask* __restrict__ tasks,
-                                                   const S* __restrict__ X, const S* __restrict__ dY, int K, int N,
-                                                   int accumulate) {
-  const DevTask tk = tasks[blockIdx.x];
-  if (tk.kind != MUX_ADAPTER_DIFF || tk.dA == nullptr) return;
-  const int e = blockIdx.y * 256 + threadIdx.x;
-  if (e >= tk.at_off) return;
-  const int32_t* row_ptr = (const int32_t*)tk.B;
-  int lo = 0, hi = K;                      // the row k with row_ptr[k] <= e < row_ptr[k+1]
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (row_ptr[mid] <= e) lo = mid; else hi = mid;
-  }
-  const int k = lo, n = ((const int32_t*)tk.L)[e];
-  float s = 0.f;
-  for (int i = 0; i < tk.row_count; ++i) {
-    const int row = tk.row_begin + i;
-    if (!row_is_valid(dtab, row)) continue;
-    s = fmaf(Store<S>::ld(X, (size_t)row * K + k), Store<S>::ld(dY, (size_t)row * N + n), s);
-  }
-  tk.dA[e] = accumulate ? tk.dA[e] + s : s;
-}
-
 template <class S>
 void steps(const CallCtx& c, unsigned which, const void* X, const void* dY, void* Y, void* dX, void* H, void* Z, void* G,
            int accumulate) {
@@ -485,15 +420,6 @@ void steps(const CallCtx& c, unsigned which, const void* X, const void* dY, void
   if ((which & REF_DL) && ia3)
     MUX_LAUNCH("ref_dl", k_ref_dl<S>, dim3(M, (c.N + 255) / 256), dim3(256), 0, c.stream, c.dtab, c.dtasks, (const S*)dY,
                        (const S*)Z, c.N, accumulate);
-  if ((which & REF_DIFF_FWD) && c.st->n_diff > 0)
-    MUX_LAUNCH("diff_fwd", k_diff_apply<S>, dim3(n_items, (c.N + 255) / 256), dim3(256), 0, c.stream, c.dtab, c.dtasks,
-                       (const S*)X, (S*)Y, c.K, c.N, 0);
-  if ((which & REF_DIFF_BWD) && c.st->n_diff > 0 && dX)
-    MUX_LAUNCH("diff_bwd", k_diff_apply<S>, dim3(n_items, (c.K + 255) / 256), dim3(256), 0, c.stream, c.dtab, c.dtasks,
-                       (const S*)dY, (S*)dX, c.N, c.K, 1);
-  if ((which & REF_DIFF_GRAD) && c.st->n_diff > 0 && c.diff_max_nnz > 0)
-    MUX_LAUNCH("diff_grad", k_diff_grad<S>, dim3(M, (c.diff_max_nnz + 255) / 256), dim3(256), 0, c.stream, c.dtab, c.dtasks,
-                       (const S*)X, (const S*)dY, c.K, c.N, accumulate);
   if ((which & REF_DX) && dX)
     MUX_LAUNCH("ref_dx", k_ref_dx<S>, dim3(n_items, (c.K + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks,
                        (const S*)dY, (const S*)c.W, c.ldw, (const S*)G, (const S*)c.dYs, (S*)dX, c.K, c.N, c.RP);

@@ -79,7 +79,7 @@ extern "C" mux_status mux_segtab_build(const mux_task_desc* tasks, int32_t n_tas
     std::vector<int32_t> timg;  // per-task words of the canonical image
     st->tasks.resize(n_tasks);
     int64_t cur = 0;            // next free row
-    int32_t zrows = 0;
+    int32_t zrows = 0, drows = 0;
     for (int32_t t = 0; t < n_tasks; ++t) {
       const mux_task_desc& d = tasks[t];
       const int64_t task_row_begin = cur;
@@ -131,6 +131,9 @@ extern "C" mux_status mux_segtab_build(const mux_task_desc* tasks, int32_t n_tas
       ht.zrow0 = -1;
       // x W is kept for the backward pass of the kinds that need it: its rows are numbered task by task
       if (d.kind == MUX_ADAPTER_IA3_OUT || d.kind == MUX_ADAPTER_TUNING) { ht.zrow0 = zrows; zrows += ht.row_count; }
+      // the rows of the Diff-Pruning tasks are copied in transposed blocks of 64 rows: numbered task by task, a block
+      // never holds rows of two tasks
+      if (d.kind == MUX_ADAPTER_DIFF) { ht.zrow0 = drows; drows += (ht.row_count + 63) / 64 * 64; }
       if (d.kind == MUX_ADAPTER_IA3_OUT) st->n_ia3++;
       if (d.kind == MUX_ADAPTER_TUNING) st->n_tuning++;
       if (d.kind == MUX_ADAPTER_DIFF) st->n_diff++;
@@ -148,6 +151,7 @@ extern "C" mux_status mux_segtab_build(const mux_task_desc* tasks, int32_t n_tas
     st->max_pack_len = max_pack_len;
     st->flags = flags;
     st->z_rows = zrows;
+    st->d_rows = drows;
 
     std::vector<Chunk> chunks(st->n_chunks);
     for (size_t k = 0; k < segs.size(); ++k) {

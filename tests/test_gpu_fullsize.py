@@ -1,7 +1,7 @@
 """Full-size GPU parity: the benchmark workloads at their real shapes, in the launch configuration
 bench.py times, compared with the fp64 oracle on sampled output columns (all rows x 48 seeded
-columns of Y and of dX; Hs/Gs enter through them; every task's dA_t, dB_t in full, dl_t on the
-sampled columns)."""
+columns of Y and of dX; Hs/Gs enter through them; every task's dA_t, dB_t, d delta_t in full, dl_t on
+the sampled columns)."""
 import numpy as np
 import pytest
 
@@ -11,7 +11,8 @@ from tests import mux_harness as hz
 pytestmark = pytest.mark.gpu
 
 CASES = [(1, 0), (1, 4), (1, 6), (2, 0), (2, 6), (3, 0), (3, 4), (3, 6), (4, 0), (4, 3), (4, 4), (4, 6),
-         (5, 0)]     # 5: the extra workload with two Adapter-Tuning tasks (their rows need x W in full: one projection)
+         (5, 0),     # 5: the extra workload with two Adapter-Tuning tasks (their rows need x W in full: one projection)
+         (6, 0), (6, 6)]   # 6: the extra workload with two Diff-Pruning tasks (d delta_t in full)
 
 
 @pytest.fixture(scope="module")
