@@ -277,6 +277,20 @@ def main():
         "tune_dz": sum(4.0 * tune_rows * N for _, K, N in wl.layers),
         "tune_grads": sum(4.0 * tune_rows * N for _, K, N in wl.layers),
     }
+    # Diff-Pruning steps: the block-transposed copies move the task rows of X (or dY) once each way; the sparse update
+    # reads the rows once, reads and writes the output rows and reads the lists of the mask (8 B an entry forward,
+    # 4 B backward, 2 B a value); the masked gradient reads both row sets and the row listing, and writes 4 B an entry.
+    diff_rows = sum(task_rows[t] for t in range(M) if wl.tasks[t].kind == 4)
+    if diff_rows:
+        nnz = [sum(m.nnz for m in L.masks if m is not None) for L in layers]
+        dims = [(K, N) for _, K, N in wl.layers]
+        stream_bytes.update({
+            "diff_xt": sum(8.0 * diff_rows * K for K, N in dims),      # launched forward and backward
+            "diff_gt": sum(4.0 * diff_rows * N for K, N in dims),
+            "diff_fwd": sum(2.0 * diff_rows * K + 4.0 * diff_rows * N + 10.0 * z for (K, N), z in zip(dims, nnz)),
+            "diff_bwd": sum(2.0 * diff_rows * N + 4.0 * diff_rows * K + 6.0 * z for (K, N), z in zip(dims, nnz)),
+            "diff_grad": sum(2.0 * diff_rows * (K + N) + 8.0 * z for (K, N), z in zip(dims, nnz)),
+        })
     for n, b in stream_bytes.items():
         if n in kernels and kernels[n]["total_ms_per_step"] > 0:
             kernels[n]["gbps"] = b / (kernels[n]["total_ms_per_step"] * 1e-3) / 1e9
