@@ -36,6 +36,10 @@ def parse():
     ap.add_argument("--compare-unmultiplexed", action="store_true",
                     help="also time the same tasks one at a time (one table and one set of calls per task, same shared "
                          "W, same rows), on one stream and alternating over two streams: what multiplexing buys")
+    ap.add_argument("--tradeoff", action="store_true",
+                    help="instead of the benchmark line: spatial against temporal multiplexing of m equal LoRA tasks "
+                         "(micro-batch 8, sequence length 128 each) on the LLaMA-7B projections, m = 1..16, and "
+                         "gradient accumulation over 4 micro-batches")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 512 MiB device copy (known traffic) for scaling rocprofv3 byte counters")
     return ap.parse_args()
@@ -164,6 +168,61 @@ def unmultiplexed(mx, torch, wl, st, layers, steps, warmup, n_groups=None):
     return res
 
 
+def tradeoff(mx, torch, args):
+    """Section 3.3, the spatial-temporal tradeoff on one GPU: m equal tasks (8 sequences of 128 tokens, LoRA rank 16)
+    over the seven LLaMA-7B projections, (a) batched in space: one call per projection and pass; (b) interleaved in
+    time: one call per task, projection and pass, on one stream and alternating over two; (c) batched in space with
+    the batch cut into 4 micro-batches of 2 sequences per task whose adapter gradients accumulate."""
+    import mux_workloads as wlm
+    base = wlm.config(1)
+    rows = []
+    stream = torch.cuda.current_stream()
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    for m in (1, 2, 4, 8, 16):
+        mk = lambda seqs: wlm.Workload(name=f"tradeoff_{m}", layers=base.layers,
+                                       tasks=[wlm.Task(wlm.KIND_LORA, 16, 2.0, [128] * seqs) for _ in range(m)], chunk=128)
+        wl = mk(8)
+        st, dtab, T, layers, ws, ws_bytes = setup(mx, torch, wl, args.seed)
+        tokens = mx.mux_segtab_valid_tokens(st)
+        ms_space = timed(lambda: step(mx, st, dtab, layers, ws, ws_bytes, stream))
+        row = {"tasks": m, "tokens": tokens, "spatial_ms": ms_space, "spatial_tokens_per_s": tokens / (ms_space * 1e-3)}
+        if m > 1:
+            r = unmultiplexed(mx, torch, wl, st, layers, args.steps, args.warmup, None)
+            row["temporal_one_stream_ms"] = r["one_stream"]["ms_per_step"]
+            row["temporal_two_streams_ms"] = r["two_streams"]["ms_per_step"]
+        # 4 micro-batches: the same table for each (2 sequences per task), gradients accumulate from the second on
+        wl4 = mk(2)
+        st4, dtab4, T4, layers4, ws4, ws_bytes4 = setup(mx, torch, wl4, args.seed)
+
+        def step_mb():
+            for c in range(4):
+                for L in layers4:
+                    mx.mux_lora_forward(L.desc, st4, dtab4, L.X, L.Y, L.saved, ws4, ws_bytes4, stream)
+                for L in reversed(layers4):
+                    mx.mux_lora_backward(L.desc, st4, dtab4, L.X, L.dY, L.saved, L.dX, L.dA, L.dB, L.dL, 1 if c else 0,
+                                         ws4, ws_bytes4, stream)
+        row["spatial_4_microbatches_ms"] = timed(step_mb)
+        rows.append(row)
+        print(f"tradeoff: {m} tasks done", file=sys.stderr, flush=True)
+        del layers, layers4, ws, ws4
+        torch.cuda.empty_cache()
+    one = rows[0]["spatial_tokens_per_s"]
+    for r in rows:
+        r["spatial_gain_over_one_task"] = r["spatial_tokens_per_s"] / one
+    return {"metric": "spatial against temporal multiplexing, fwd+bwd of 7 LLaMA-7B projections", "unit": "ms per step",
+            "steps": args.steps, "warmup": args.warmup, "dtype": "bf16", "data": "synthetic", "rows": rows}
+
+
 def cpu_baseline(wl, seconds, seed):
     """The fp64 oracle, as it stands, on a bounded sample: the first m tokens of every task through
     every projection (fwd+bwd), m sized from a short calibration so that the run takes about `seconds`."""
@@ -208,6 +267,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     mx.load_library()
+    if args.tradeoff:
+        print(json.dumps(tradeoff(mx, torch, args)))
+        return
     wl = wlm.config(args.workload, seed=args.seed)
     st, dtab, T, layers, ws, ws_bytes = setup(mx, torch, wl, args.seed)
     stream = torch.cuda.current_stream()
