@@ -21,6 +21,7 @@ __all__ = [
     "mux_segtab_serialized_bytes", "mux_segtab_serialize", "mux_segtab_row_task", "mux_segtab_device_bytes",
     "mux_segtab_upload", "mux_lora_saved_bytes", "mux_lora_workspace_bytes", "mux_lora_forward",
     "mux_lora_backward", "mux_last_error", "mux_version", "mux_profile_enable", "mux_profile_collect",
+    "CostModel", "mux_plan_stage_latency", "mux_plan_htask_latency", "mux_plan_fusion",
 ]
 
 MUX_OK = 0
@@ -58,6 +59,47 @@ class _LayerDescC(ctypes.Structure):
 
 class _ProfileEntryC(ctypes.Structure):
     _fields_ = [("name", c_char_p), ("launches", c_int32), ("total_ms", ctypes.c_double)]
+
+
+class _CurveC(ctypes.Structure):
+    _fields_ = [("n_points", c_int32), ("tokens", POINTER(c_int64)), ("value", POINTER(ctypes.c_double))]
+
+
+class _StageModelC(ctypes.Structure):
+    _fields_ = [("n_gpus", c_int32), ("n_baseops", c_int32), ("baseop_latency", POINTER(_CurveC)),
+                ("n_adapters", c_int32), ("adapter_latency", POINTER(_CurveC)), ("adapter_util", POINTER(_CurveC))]
+
+
+class _CostModelC(ctypes.Structure):
+    _fields_ = [("n_stages", c_int32), ("stages", POINTER(_StageModelC)), ("n_microbatches", c_int32)]
+
+
+class CostModel:
+    """mux_cost_model (include/mux_plan.h) laid out from plain Python data:
+    stages = [{"n_gpus": N_g, "baseops": [(tokens, values), ...], "adapters": [((tokens, t_a), (tokens, u_a)), ...]}, ...],
+    C = number of micro-batches.  Marshalling only; the arrays stay alive with the object."""
+
+    def __init__(self, stages, C: int):
+        self._keep = []
+
+        def curves(items):
+            arr = (_CurveC * max(len(items), 1))()
+            for i, (xs, ys) in enumerate(items):
+                tx = (c_int64 * max(len(xs), 1))(*[int(v) for v in xs])
+                ty = (ctypes.c_double * max(len(ys), 1))(*[float(v) for v in ys])
+                self._keep += [tx, ty]
+                arr[i] = _CurveC(min(len(xs), len(ys)), ctypes.cast(tx, POINTER(c_int64)),
+                                 ctypes.cast(ty, POINTER(ctypes.c_double)))
+            self._keep.append(arr)
+            return ctypes.cast(arr, POINTER(_CurveC))
+
+        sarr = (_StageModelC * max(len(stages), 1))()
+        for i, st in enumerate(stages):
+            sarr[i] = _StageModelC(int(st["n_gpus"]), len(st["baseops"]), curves(list(st["baseops"])),
+                                   len(st["adapters"]), curves([a[0] for a in st["adapters"]]),
+                                   curves([a[1] for a in st["adapters"]]))
+        self._keep.append(sarr)
+        self.c = _CostModelC(len(stages), ctypes.cast(sarr, POINTER(_StageModelC)), int(C))
 
 
 class TaskDesc:
@@ -108,6 +150,10 @@ def load_library() -> ctypes.CDLL:
         "mux_profile_collect": (c_int, [POINTER(_ProfileEntryC), c_int32, POINTER(c_int32)]),
         "mux_last_error": (c_char_p, []),
         "mux_version": (c_char_p, []),
+        "mux_plan_stage_latency": (c_int, [POINTER(_CostModelC), c_int32, c_int32, POINTER(c_int64), POINTER(ctypes.c_double)]),
+        "mux_plan_htask_latency": (c_int, [POINTER(_CostModelC), c_int32, POINTER(c_int64), POINTER(ctypes.c_double)]),
+        "mux_plan_fusion": (c_int, [POINTER(_CostModelC), c_int32, POINTER(c_int64), c_int32, POINTER(c_int32),
+                                    POINTER(c_int32), POINTER(c_int32), POINTER(ctypes.c_double)]),
     }
     for name, (res, args) in sig.items():
         f = getattr(lib, name)
@@ -326,3 +372,32 @@ def mux_profile_collect(cap: int = 64) -> List[dict]:
     _check(load_library().mux_profile_collect(arr, cap, ctypes.byref(n)))
     return [{"name": arr[i].name.decode(), "launches": int(arr[i].launches), "total_ms": float(arr[i].total_ms)}
             for i in range(min(n.value, cap))]
+
+
+def _tokens_c(tokens: Sequence[int]):
+    return (c_int64 * max(len(tokens), 1))(*[int(v) for v in tokens])
+
+
+def mux_plan_stage_latency(model: CostModel, stage: int, tokens: Sequence[int]) -> float:
+    out = ctypes.c_double(0.0)
+    _check(load_library().mux_plan_stage_latency(ctypes.byref(model.c), int(stage), len(tokens), _tokens_c(tokens),
+                                                 ctypes.byref(out)))
+    return float(out.value)
+
+
+def mux_plan_htask_latency(model: CostModel, tokens: Sequence[int]) -> float:
+    out = ctypes.c_double(0.0)
+    _check(load_library().mux_plan_htask_latency(ctypes.byref(model.c), len(tokens), _tokens_c(tokens), ctypes.byref(out)))
+    return float(out.value)
+
+
+def mux_plan_fusion(model: CostModel, tokens: Sequence[int], max_htasks: int = 0):
+    """Returns (latency, order, htask_begin): hybrid task h holds the tasks order[htask_begin[h]:htask_begin[h+1]]."""
+    n = len(tokens)
+    order = (c_int32 * max(n, 1))()
+    begins = (c_int32 * (n + 1))()
+    nh = c_int32(0)
+    lat = ctypes.c_double(0.0)
+    _check(load_library().mux_plan_fusion(ctypes.byref(model.c), n, _tokens_c(tokens), int(max_htasks), order, begins,
+                                          ctypes.byref(nh), ctypes.byref(lat)))
+    return float(lat.value), [int(order[i]) for i in range(n)], [int(begins[i]) for i in range(nh.value + 1)]

@@ -24,10 +24,11 @@ def mx():
 
 
 def test_exports_every_declared_symbol(mx):
-    hdr = open(os.path.join(ROOT, "include", "mux.h")).read()
+    hdr = "".join(open(os.path.join(ROOT, "include", f)).read() for f in sorted(os.listdir(os.path.join(ROOT, "include")))
+                  if f.endswith(".h"))
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)          # declarations only, not prose
     names = set(re.findall(r"\b(mux_[a-z0-9_]+)\s*\(", hdr))
-    assert {"mux_lora_forward", "mux_lora_backward", "mux_segtab_build", "mux_segtab_upload"} <= names
+    assert {"mux_lora_forward", "mux_lora_backward", "mux_segtab_build", "mux_segtab_upload", "mux_plan_fusion"} <= names
     lib = ctypes.CDLL(mx.library_path())
     for n in sorted(names):
         assert hasattr(lib, n), n
