@@ -40,6 +40,10 @@ def parse():
                     help="instead of the benchmark line: spatial against temporal multiplexing of m equal LoRA tasks "
                          "(micro-batch 8, sequence length 128 each) on the LLaMA-7B projections, m = 1..16, and "
                          "gradient accumulation over 4 micro-batches")
+    ap.add_argument("--plan", action="store_true",
+                    help="instead of the benchmark line: profile t_o(x), t_a(x), u_a(x) of the seven projections over "
+                         "the token count, plan the fusion of 8 unequal LoRA tasks with the library's planner and compare "
+                         "the cost model's predictions with measured steps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 512 MiB device copy (known traffic) for scaling rocprofv3 byte counters")
     return ap.parse_args()
@@ -223,6 +227,109 @@ def tradeoff(mx, torch, args):
             "steps": args.steps, "warmup": args.warmup, "dtype": "bf16", "data": "synthetic", "rows": rows}
 
 
+def plan(mx, torch, args):
+    """Section 3.3 with S = 1, N_g = 1 on this GPU.  Offline profiling (section 5): for x tokens and each projection,
+    the wall time of a forward + backward call pair with one task of x tokens, once without an adapter and once with a
+    LoRA r16 adapter; t_o(x) = half the first (Eq. 3 counts one pass, Eq. 4 doubles it), t_a(x) = half the difference,
+    u_a(x) = the adapter's token rate at x over its best token rate.  Then the planner cuts 8 unequal tasks into
+    hybrid tasks, and three executions are timed against the model's prediction: the plan, everything in one hybrid
+    task, and every task alone (hybrid tasks one after the other on one stream)."""
+    import mux_workloads as wlm
+    base = wlm.config(1)
+    stream = torch.cuda.current_stream()
+    xs = [128, 256, 512, 1024, 2048, 4096, 8192, 16384]
+    reps = max(args.steps, 5)
+    t_pair = {kind: [[0.0] * len(xs) for _ in base.layers] for kind in (wlm.KIND_NONE, wlm.KIND_LORA)}
+    for xi, x in enumerate(xs):
+        for kind in (wlm.KIND_NONE, wlm.KIND_LORA):
+            wl = wlm.Workload(name="profile", layers=base.layers, tasks=[wlm.Task(kind, 16, 2.0, [x])], chunk=128)
+            st, dtab, T, layers, ws, ws_bytes = setup(mx, torch, wl, args.seed)
+            for li, L in enumerate(layers):
+                def pair():
+                    mx.mux_lora_forward(L.desc, st, dtab, L.X, L.Y, L.saved, ws, ws_bytes, stream)
+                    mx.mux_lora_backward(L.desc, st, dtab, L.X, L.dY, L.saved, L.dX, L.dA, L.dB, L.dL, 0, ws, ws_bytes, stream)
+                for _ in range(3):
+                    pair()
+                best = float("inf")
+                for _ in range(4):              # the fastest of four batches: a profile, not a sample of the noise
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    for _ in range(reps):
+                        pair()
+                    torch.cuda.synchronize()
+                    best = min(best, (time.perf_counter() - t0) * 1e3 / reps)
+                t_pair[kind][li][xi] = best
+            del layers, ws
+            torch.cuda.empty_cache()
+        print(f"plan: profiled {x} tokens", file=sys.stderr, flush=True)
+    baseops, adapters = [], []
+    for li in range(len(base.layers)):
+        t_o = [v / 2.0 for v in t_pair[wlm.KIND_NONE][li]]
+        t_a = [max((a - b) / 2.0, 1e-4) for a, b in zip(t_pair[wlm.KIND_LORA][li], t_pair[wlm.KIND_NONE][li])]
+        rate = [x / t for x, t in zip(xs, t_a)]
+        u_a = [min(1.0, r / max(rate)) for r in rate]
+        baseops.append((xs, t_o))
+        adapters.append(((xs, t_a), (xs, u_a)))
+    stages = [{"n_gpus": 1, "baseops": baseops, "adapters": adapters}]
+    model = mx.CostModel(stages, 1)
+    tokens = [256, 8192, 512, 1024, 4096, 1024, 2048, 256]
+    t0 = time.perf_counter()
+    f_star, order, begins = mx.mux_plan_fusion(model, tokens)
+    plan_seconds = time.perf_counter() - t0
+
+    def groups_of(begins_):
+        return [[order[i] for i in range(begins_[h], begins_[h + 1])] for h in range(len(begins_) - 1)]
+
+    def measure(groups):
+        runs = []
+        for g in groups:
+            wl = wlm.Workload(name="planned", layers=base.layers,
+                              tasks=[wlm.Task(wlm.KIND_LORA, 16, 2.0, [tokens[t]]) for t in g], chunk=128)
+            runs.append(setup(mx, torch, wl, args.seed))
+
+        def one():
+            for st, dtab, T, layers, ws, ws_bytes in runs:
+                step(mx, st, dtab, layers, ws, ws_bytes, stream)
+        for _ in range(args.warmup):
+            one()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            one()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        del runs
+        torch.cuda.empty_cache()
+        return ms
+
+    def predict(groups):
+        return sum(mx.mux_plan_htask_latency(model, [tokens[t] for t in g]) for g in groups)
+
+    M = len(tokens)
+    candidates = {"planned": groups_of(begins), "one_hybrid_task": groups_of([0, M]),
+                  "every_task_alone": groups_of(list(range(M + 1))),
+                  "two_halves": groups_of([0, M // 2, M])}
+    results = {}
+    for name, groups in candidates.items():
+        results[name] = {"hybrid_tasks": [[tokens[t] for t in g] for g in groups], "predicted_ms": predict(groups),
+                         "measured_ms": measure(groups)}
+        results[name]["predicted_over_measured"] = results[name]["predicted_ms"] / results[name]["measured_ms"]
+        print(f"plan: measured {name}", file=sys.stderr, flush=True)
+    # the same profiles as four equal pipeline stages with four micro-batches: what the planner would choose there
+    # (prediction only: this build runs on one GPU)
+    model4 = mx.CostModel([{"n_gpus": 1, "baseops": baseops, "adapters": adapters}] * 4, 4)
+    f4, order4, begins4 = mx.mux_plan_fusion(model4, tokens)
+    return {"metric": "task-fusion plan: cost model against measurement, fwd+bwd of 7 LLaMA-7B projections",
+            "unit": "ms per step", "steps": args.steps, "warmup": args.warmup, "dtype": "bf16", "data": "synthetic",
+            "profile": {"tokens": xs, "t_o_ms": {n: baseops[i][1] for i, (n, _, _) in enumerate(base.layers)},
+                        "t_a_ms": {n: adapters[i][0][1] for i, (n, _, _) in enumerate(base.layers)},
+                        "u_a": {n: adapters[i][1][1] for i, (n, _, _) in enumerate(base.layers)}},
+            "tasks_tokens": tokens, "plan_seconds": plan_seconds, "F_star_ms": f_star, "executions": results,
+            "four_stage_pipeline_prediction": {"C": 4, "F_star_ms": f4,
+                                               "hybrid_tasks": [[tokens[order4[i]] for i in range(begins4[h], begins4[h + 1])]
+                                                                for h in range(len(begins4) - 1)]}}
+
+
 def cpu_baseline(wl, seconds, seed):
     """The fp64 oracle, as it stands, on a bounded sample: the first m tokens of every task through
     every projection (fwd+bwd), m sized from a short calibration so that the run takes about `seconds`."""
@@ -269,6 +376,9 @@ def main():
     mx.load_library()
     if args.tradeoff:
         print(json.dumps(tradeoff(mx, torch, args)))
+        return
+    if args.plan:
+        print(json.dumps(plan(mx, torch, args)))
         return
     wl = wlm.config(args.workload, seed=args.seed)
     st, dtab, T, layers, ws, ws_bytes = setup(mx, torch, wl, args.seed)
