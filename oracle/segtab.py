@@ -158,3 +158,11 @@ def build(task_seq_lens: Sequence[Sequence[int]], chunk: int, max_pack_len: int 
     task_rows = [np.nonzero(row_task == t)[0].astype(np.int64) for t in range(M)]
     return SegTab(image=np.asarray(img, dtype="<i4"), T=T, chunk=c, n_chunks=n_chunks,
                   valid_total=valid_total, row_task=row_task, task_rows=task_rows)
+
+
+def sequences(st: SegTab) -> List[List[int]]:
+    """The sequences of the aligned batch as [task, pack, first_row, len], read back from the canonical image."""
+    img = [int(v) for v in st.image]
+    M, n_chunks, n_packs, n_segs, n_seqs = img[3], img[6], img[9], img[10], img[11]
+    off = HEADER_INTS + M * TASK_INTS + n_packs * PACK_INTS + n_chunks * CHUNK_INTS + n_segs * SEG_INTS
+    return [img[off + SEQ_INTS * i: off + SEQ_INTS * (i + 1)] for i in range(n_seqs)]
