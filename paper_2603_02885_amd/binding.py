@@ -22,6 +22,7 @@ __all__ = [
     "mux_segtab_upload", "mux_lora_saved_bytes", "mux_lora_workspace_bytes", "mux_lora_forward",
     "mux_lora_backward", "mux_last_error", "mux_version", "mux_profile_enable", "mux_profile_collect",
     "CostModel", "mux_plan_stage_latency", "mux_plan_htask_latency", "mux_plan_fusion",
+    "AttnDesc", "mux_attn_saved_bytes", "mux_attn_workspace_bytes", "mux_attn_forward", "mux_attn_backward",
 ]
 
 MUX_OK = 0
@@ -59,6 +60,20 @@ class _LayerDescC(ctypes.Structure):
 
 class _ProfileEntryC(ctypes.Structure):
     _fields_ = [("name", c_char_p), ("launches", c_int32), ("total_ms", ctypes.c_double)]
+
+
+class _AttnDescC(ctypes.Structure):
+    _fields_ = [("n_heads", c_int32), ("n_kv_heads", c_int32), ("head_dim", c_int32), ("dtype", c_int32),
+                ("scale", c_float), ("ldq", c_int64), ("ldk", c_int64), ("ldv", c_int64), ("ldo", c_int64)]
+
+
+class AttnDesc:
+    """mux_attn_desc (include/mux_attn.h)."""
+
+    def __init__(self, n_heads: int, head_dim: int, ldq: int, ldk: int, ldv: int, ldo: int, scale: float = 0.0,
+                 n_kv_heads: Optional[int] = None, dtype: int = MUX_DT_BF16):
+        self.c = _AttnDescC(int(n_heads), int(n_heads if n_kv_heads is None else n_kv_heads), int(head_dim), int(dtype),
+                            float(scale), int(ldq), int(ldk), int(ldv), int(ldo))
 
 
 class _CurveC(ctypes.Structure):
@@ -150,6 +165,10 @@ def load_library() -> ctypes.CDLL:
         "mux_profile_collect": (c_int, [POINTER(_ProfileEntryC), c_int32, POINTER(c_int32)]),
         "mux_last_error": (c_char_p, []),
         "mux_version": (c_char_p, []),
+        "mux_attn_saved_bytes": (c_size_t, [POINTER(_AttnDescC), vp]),
+        "mux_attn_workspace_bytes": (c_size_t, [POINTER(_AttnDescC), vp]),
+        "mux_attn_forward": (c_int, [POINTER(_AttnDescC), vp, vp, vp, vp, vp, vp, vp, vp]),
+        "mux_attn_backward": (c_int, [POINTER(_AttnDescC), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, c_size_t, vp]),
         "mux_plan_stage_latency": (c_int, [POINTER(_CostModelC), c_int32, c_int32, POINTER(c_int64), POINTER(ctypes.c_double)]),
         "mux_plan_htask_latency": (c_int, [POINTER(_CostModelC), c_int32, POINTER(c_int64), POINTER(ctypes.c_double)]),
         "mux_plan_fusion": (c_int, [POINTER(_CostModelC), c_int32, POINTER(c_int64), c_int32, POINTER(c_int32),
@@ -401,3 +420,23 @@ def mux_plan_fusion(model: CostModel, tokens: Sequence[int], max_htasks: int = 0
     _check(load_library().mux_plan_fusion(ctypes.byref(model.c), n, _tokens_c(tokens), int(max_htasks), order, begins,
                                           ctypes.byref(nh), ctypes.byref(lat)))
     return float(lat.value), [int(order[i]) for i in range(n)], [int(begins[i]) for i in range(nh.value + 1)]
+
+
+def mux_attn_saved_bytes(desc: AttnDesc, st: SegTab) -> int:
+    return int(load_library().mux_attn_saved_bytes(ctypes.byref(desc.c), st.handle))
+
+
+def mux_attn_workspace_bytes(desc: AttnDesc, st: SegTab) -> int:
+    return int(load_library().mux_attn_workspace_bytes(ctypes.byref(desc.c), st.handle))
+
+
+def mux_attn_forward(desc: AttnDesc, st: SegTab, dev_segtab, Q, K, V, O, saved, stream=None) -> None:
+    _check(load_library().mux_attn_forward(ctypes.byref(desc.c), st.handle, _ptr(dev_segtab), _ptr(Q), _ptr(K), _ptr(V),
+                                           _ptr(O), _ptr(saved), _stream(stream)))
+
+
+def mux_attn_backward(desc: AttnDesc, st: SegTab, dev_segtab, Q, K, V, O, dO, saved, dQ, dK, dV, ws, ws_bytes: int,
+                      stream=None) -> None:
+    _check(load_library().mux_attn_backward(ctypes.byref(desc.c), st.handle, _ptr(dev_segtab), _ptr(Q), _ptr(K), _ptr(V),
+                                            _ptr(O), _ptr(dO), _ptr(saved), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ws),
+                                            int(ws_bytes), _stream(stream)))

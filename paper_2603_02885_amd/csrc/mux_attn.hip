@@ -1,0 +1,516 @@
+// Attention step of a chunk-aligned batch (section 3.5): causal softmax attention of every sequence on its own,
+// forward and backward, bf16 storage, fp32 accumulation on the matrix cores (v_mfma_f32_32x32x16_bf16).
+//
+// Work item = a block of 128 tokens of one sequence x one head; four waves, 32 tokens each.  All three kernels keep
+// the wave's own tokens on the N side of every product (lane l owns token l % 32; its two half-waves split the
+// other index), so that softmax statistics, log-sum-exp and the dO.O term are per-lane scalars and a probability
+// tile leaves the accumulators already in the layout of the next product's B operand:
+//   forward   S^T = K Q^T (keys x queries)      -> P^T -> O^T  += V^T P^T          online softmax over key tiles
+//   dQ        S^T, dP^T = V dO^T                -> dS^T -> dQ^T += K^T dS^T
+//   dK, dV    S = Q K^T, dP = dO V^T (queries x keys, the wave owns keys) -> dV^T += dO^T P, dK^T += Q^T dS
+// The operand that has to be read across rows (V^T, K^T, dO^T, Q^T) comes from a row-major LDS tile through
+// ds_read_b64_tr_b16.  A sum over 16 tokens may take them in any order as long as both operands agree; the order
+// used is the one the accumulator layout gives: slot i of half-wave h <-> token 8 (i / 4) + 4 h + i % 4.
+// Every output element has one owner; nothing is accumulated across workgroups, results repeat bit for bit.
+#include "mux_attn.h"
+#include "mux_device_utils.h"
+
+namespace mux {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int D = 128;          // head dimension
+constexpr int BLK = kAttnBlockRows;
+constexpr int TILE = 64;        // tokens of the other side staged per step
+constexpr int KP = 136;         // LDS row pitch (elements) of a tile that is only read along rows
+constexpr int TP = 144;         // ... of a tile that is also read across rows
+constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
+
+struct AttnParams {
+  const int32_t* dtab;
+  const bf16_t *Q, *K, *V, *O, *dO;
+  bf16_t *Out, *dQ, *dK, *dV;
+  float* lse;         // [H][T], natural log
+  float* delta;       // [H][T]
+  int64_t ldq, ldk, ldv, ldo;
+  int T, H;
+  float scale;
+};
+
+__device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)p);
+}
+__device__ __forceinline__ f32x16 mma(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ bf16x8 zero8() { return __builtin_bit_cast(bf16x8, uint4{0u, 0u, 0u, 0u}); }
+// accumulator elements 8u .. 8u+7 as a B operand
+__device__ __forceinline__ bf16x8 pack8(const f32x16& v, int u) {
+  uint4 r;
+  r.x = pack_bf16x2(v[8 * u + 0], v[8 * u + 1]);
+  r.y = pack_bf16x2(v[8 * u + 2], v[8 * u + 3]);
+  r.z = pack_bf16x2(v[8 * u + 4], v[8 * u + 5]);
+  r.w = pack_bf16x2(v[8 * u + 6], v[8 * u + 7]);
+  return __builtin_bit_cast(bf16x8, r);
+}
+// A operand read across the rows of a row-major tile: column c0 + lane % 32, the 8 rows 4h + {0..3}, 8 + 4h + {0..3} from row0
+__device__ __forceinline__ bf16x8 read_across(const bf16_t* tile, int row0, int c0, int lane) {
+  const int j = lane & 15, grp = lane >> 4;
+  const bf16_t* p = tile + (row0 + 4 * (grp >> 1) + (j >> 2)) * TP + c0 + 16 * (grp & 1) + 4 * (j & 3);
+  const bf16x4 lo = lds_read_tr(p), hi = lds_read_tr(p + 8 * TP);
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+// token of accumulator element j for half-wave h inside a 32-token tile
+__device__ __forceinline__ int tok(int j, int half) { return 8 * (j >> 2) + 4 * half + (j & 3); }
+
+// 64 rows x 128 columns of one head from global memory (rows past `limit` read as zero) into registers, then LDS
+struct TileLoad {
+  uint4 r[4];
+  __device__ __forceinline__ void load(const bf16_t* base, int64_t ld, int first, int row0, int limit, int hc, int tid) {
+    const int row = row0 + (tid >> 2);
+    const uint4* src = (const uint4*)(base + (size_t)(first + row) * ld + hc + (tid & 3) * 32);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = row < limit ? src[i] : uint4{0u, 0u, 0u, 0u};
+  }
+  __device__ __forceinline__ void store(bf16_t* tile, int pitch, int tid) const {
+    uint4* dst = (uint4*)(tile + (tid >> 2) * pitch + (tid & 3) * 32);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dst[i] = r[i];
+  }
+};
+
+// ------------------------------------------------------------------------------------------------ forward
+__global__ __launch_bounds__(256) void k_attn_fwd(AttnParams p) {
+  __shared__ __align__(16) bf16_t sK[TILE * KP];
+  __shared__ __align__(16) bf16_t sV[TILE * TP];
+  const int32_t* blk = p.dtab + p.dtab[DH_ATT_OFF_FWD] + blockIdx.x * DA_WORDS;
+  const int first = blk[DA_FIRST_ROW], len = blk[DA_LEN], q0 = blk[DA_BLOCK0];
+  const int hc = blockIdx.y * D;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, half = lane >> 5;
+  const int ql = q0 + 32 * wave + li;          // this lane's query inside the sequence
+  const bool qok = ql < len;
+  bf16x8 qf[8];
+  {
+    const bf16_t* qrow = p.Q + (size_t)(first + ql) * p.ldq + hc + 8 * half;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) qf[s] = qok ? *(const bf16x8*)(qrow + 16 * s) : zero8();
+  }
+  f32x16 o[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) o[dt][j] = 0.f;
+  float m = -INFINITY, l = 0.f;
+  const float c = p.scale * LOG2E;
+  const int kend = min(len, q0 + BLK);          // keys [0, kend) are visible to some query of the block
+  const int wq_first = q0 + 32 * wave, wq_last = wq_first + 31;
+  TileLoad tk, tv;
+  tk.load(p.K, p.ldk, first, 0, len, hc, tid);
+  tv.load(p.V, p.ldv, first, 0, len, hc, tid);
+  for (int kb = 0; kb < kend; kb += TILE) {
+    __syncthreads();
+    tk.store(sK, KP, tid);
+    tv.store(sV, TP, tid);
+    __syncthreads();
+    if (kb + TILE < kend) {
+      tk.load(p.K, p.ldk, first, kb + TILE, len, hc, tid);
+      tv.load(p.V, p.ldv, first, kb + TILE, len, hc, tid);
+    }
+    if (kb > wq_last) continue;                 // no key of this tile is visible to this wave's queries
+    f32x16 s[2];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) s[kt][j] = 0.f;
+#pragma unroll
+      for (int st = 0; st < 8; ++st)
+        s[kt] = mma(*(const bf16x8*)(sK + (32 * kt + li) * KP + 16 * st + 8 * half), qf[st], s[kt]);
+    }
+    const bool diag = kb + TILE - 1 > wq_first;
+    float mx = m;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        float t = s[kt][j] * c;
+        if (diag && kb + 32 * kt + tok(j, half) > ql) t = -INFINITY;
+        s[kt][j] = t;
+        mx = fmaxf(mx, t);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float ms = mx == -INFINITY ? 0.f : mx;
+    const float alpha = exp2f(m - ms);
+    m = mx;
+    float rs = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const float e = exp2f(s[kt][j] - ms);
+        s[kt][j] = e;
+        rs += e;
+      }
+    l = l * alpha + rs;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) o[dt][j] *= alpha;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const bf16x8 pb = pack8(s[kt], u);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) o[dt] = mma(read_across(sV, 32 * kt + 16 * u, 32 * dt, lane), pb, o[dt]);
+      }
+  }
+  l += __shfl_xor(l, 32);
+  if (qok) {
+    const float inv = 1.f / l;
+    bf16_t* orow = p.Out + (size_t)(first + ql) * p.ldo + hc;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int jg = 0; jg < 4; ++jg) {
+        uint2 v;
+        v.x = pack_bf16x2(o[dt][4 * jg + 0] * inv, o[dt][4 * jg + 1] * inv);
+        v.y = pack_bf16x2(o[dt][4 * jg + 2] * inv, o[dt][4 * jg + 3] * inv);
+        *(uint2*)(orow + 32 * dt + 8 * jg + 4 * half) = v;
+      }
+    if (p.lse && half == 0) p.lse[(size_t)blockIdx.y * p.T + first + ql] = (m + log2f(l)) * LN2;
+  }
+}
+
+// Rows that belong to no sequence: zero in `n_out` outputs.  grid = 64-row items.
+struct ZeroParams {
+  const int32_t* dtab;
+  bf16_t* out[3];
+  int64_t ld[3];
+  int n_out, width;
+};
+__global__ __launch_bounds__(256) void k_attn_zero_pad(ZeroParams p) {
+  const ItemView it = load_item(p.dtab, 0, blockIdx.x);
+  if (it.task >= 0 && it.nvalid == it.nrows) return;
+  for (int r = 0; r < it.nrows; ++r) {
+    if (it.task >= 0 && row_is_valid(p.dtab, it.row0 + r)) continue;
+    for (int o = 0; o < p.n_out; ++o) {
+      uint4* dst = (uint4*)(p.out[o] + (size_t)(it.row0 + r) * p.ld[o]);
+      for (int c = threadIdx.x; c < p.width / 8; c += 256) dst[c] = uint4{0u, 0u, 0u, 0u};
+    }
+  }
+}
+
+// delta[h][row] = sum_d dO[row][h, d] * O[row][h, d] for the rows of sequences.  One thread per (row, head).
+__global__ __launch_bounds__(256) void k_attn_delta(AttnParams p) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (size_t)p.T * p.H) return;
+  const int row = (int)(idx / p.H), h = (int)(idx % p.H);
+  float s = 0.f;
+  if (row_is_valid(p.dtab, row)) {
+    const uint4* a = (const uint4*)(p.dO + (size_t)row * p.ldo + h * D);
+    const uint4* b = (const uint4*)(p.O + (size_t)row * p.ldo + h * D);
+#pragma unroll 4
+    for (int i = 0; i < D / 8; ++i) {
+      const uint4 x = a[i], y = b[i];
+      const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        s = fmaf(__uint_as_float(xs[q] << 16), __uint_as_float(ys[q] << 16), s);
+        s = fmaf(__uint_as_float(xs[q] & 0xffff0000u), __uint_as_float(ys[q] & 0xffff0000u), s);
+      }
+    }
+  }
+  p.delta[(size_t)h * p.T + row] = s;
+}
+
+// ------------------------------------------------------------------------------------------------ dQ
+__global__ __launch_bounds__(256) void k_attn_bwd_q(AttnParams p) {
+  __shared__ __align__(16) bf16_t sK[TILE * TP];
+  __shared__ __align__(16) bf16_t sV[TILE * KP];
+  const int32_t* blk = p.dtab + p.dtab[DH_ATT_OFF_FWD] + blockIdx.x * DA_WORDS;
+  const int first = blk[DA_FIRST_ROW], len = blk[DA_LEN], q0 = blk[DA_BLOCK0];
+  const int hc = blockIdx.y * D;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, half = lane >> 5;
+  const int ql = q0 + 32 * wave + li;
+  const bool qok = ql < len;
+  bf16x8 qf[8], df[8];
+  {
+    const bf16_t* qrow = p.Q + (size_t)(first + ql) * p.ldq + hc + 8 * half;
+    const bf16_t* drow = p.dO + (size_t)(first + ql) * p.ldo + hc + 8 * half;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      qf[s] = qok ? *(const bf16x8*)(qrow + 16 * s) : zero8();
+      df[s] = qok ? *(const bf16x8*)(drow + 16 * s) : zero8();
+    }
+  }
+  const float c = p.scale * LOG2E;
+  const float lse2 = qok ? p.lse[(size_t)blockIdx.y * p.T + first + ql] * LOG2E : 0.f;
+  const float dl = qok ? p.delta[(size_t)blockIdx.y * p.T + first + ql] : 0.f;
+  f32x16 dq[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) dq[dt][j] = 0.f;
+  const int kend = min(len, q0 + BLK);
+  const int wq_first = q0 + 32 * wave, wq_last = wq_first + 31;
+  TileLoad tk, tv;
+  tk.load(p.K, p.ldk, first, 0, len, hc, tid);
+  tv.load(p.V, p.ldv, first, 0, len, hc, tid);
+  for (int kb = 0; kb < kend; kb += TILE) {
+    __syncthreads();
+    tk.store(sK, TP, tid);
+    tv.store(sV, KP, tid);
+    __syncthreads();
+    if (kb + TILE < kend) {
+      tk.load(p.K, p.ldk, first, kb + TILE, len, hc, tid);
+      tv.load(p.V, p.ldv, first, kb + TILE, len, hc, tid);
+    }
+    if (kb > wq_last) continue;
+    f32x16 s[2], dp[2];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) { s[kt][j] = 0.f; dp[kt][j] = 0.f; }
+#pragma unroll
+      for (int st = 0; st < 8; ++st) {
+        s[kt] = mma(*(const bf16x8*)(sK + (32 * kt + li) * TP + 16 * st + 8 * half), qf[st], s[kt]);
+        dp[kt] = mma(*(const bf16x8*)(sV + (32 * kt + li) * KP + 16 * st + 8 * half), df[st], dp[kt]);
+      }
+    }
+    const bool diag = kb + TILE - 1 > wq_first;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        float pr = exp2f(s[kt][j] * c - lse2);
+        if (!qok || (diag && kb + 32 * kt + tok(j, half) > ql)) pr = 0.f;
+        s[kt][j] = pr * (dp[kt][j] - dl);          // dS^T
+      }
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const bf16x8 ds = pack8(s[kt], u);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) dq[dt] = mma(read_across(sK, 32 * kt + 16 * u, 32 * dt, lane), ds, dq[dt]);
+      }
+  }
+  if (qok) {
+    bf16_t* orow = p.dQ + (size_t)(first + ql) * p.ldq + hc;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int jg = 0; jg < 4; ++jg) {
+        uint2 v;
+        v.x = pack_bf16x2(dq[dt][4 * jg + 0] * p.scale, dq[dt][4 * jg + 1] * p.scale);
+        v.y = pack_bf16x2(dq[dt][4 * jg + 2] * p.scale, dq[dt][4 * jg + 3] * p.scale);
+        *(uint2*)(orow + 32 * dt + 8 * jg + 4 * half) = v;
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ dK, dV
+__global__ __launch_bounds__(256) void k_attn_bwd_kv(AttnParams p) {
+  __shared__ __align__(16) bf16_t sQ[TILE * TP];
+  __shared__ __align__(16) bf16_t sD[TILE * TP];
+  __shared__ float sLse[TILE], sDelta[TILE];
+  const int32_t* blk = p.dtab + p.dtab[DH_ATT_OFF_BWD] + blockIdx.x * DA_WORDS;
+  const int first = blk[DA_FIRST_ROW], len = blk[DA_LEN], k0 = blk[DA_BLOCK0];
+  const int hc = blockIdx.y * D;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, half = lane >> 5;
+  const int kl = k0 + 32 * wave + li;          // this lane's key inside the sequence
+  const bool kok = kl < len;
+  bf16x8 kf[8], vf[8];
+  {
+    const bf16_t* krow = p.K + (size_t)(first + kl) * p.ldk + hc + 8 * half;
+    const bf16_t* vrow = p.V + (size_t)(first + kl) * p.ldv + hc + 8 * half;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      kf[s] = kok ? *(const bf16x8*)(krow + 16 * s) : zero8();
+      vf[s] = kok ? *(const bf16x8*)(vrow + 16 * s) : zero8();
+    }
+  }
+  const float c = p.scale * LOG2E;
+  f32x16 dk[4], dv[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) { dk[dt][j] = 0.f; dv[dt][j] = 0.f; }
+  const int wk_first = k0 + 32 * wave;
+  TileLoad tq, td;
+  float r_lse = 0.f, r_delta = 0.f;
+  auto load_stats = [&](int qb) {
+    if (tid < TILE) {
+      const bool ok = qb + tid < len;
+      r_lse = ok ? p.lse[(size_t)blockIdx.y * p.T + first + qb + tid] * LOG2E : INFINITY;   // exp2(x - inf) = 0
+      r_delta = ok ? p.delta[(size_t)blockIdx.y * p.T + first + qb + tid] : 0.f;
+    }
+  };
+  tq.load(p.Q, p.ldq, first, k0, len, hc, tid);
+  td.load(p.dO, p.ldo, first, k0, len, hc, tid);
+  load_stats(k0);
+  for (int qb = k0; qb < len; qb += TILE) {     // queries before the block see none of its keys
+    __syncthreads();
+    tq.store(sQ, TP, tid);
+    td.store(sD, TP, tid);
+    if (tid < TILE) { sLse[tid] = r_lse; sDelta[tid] = r_delta; }
+    __syncthreads();
+    if (qb + TILE < len) {
+      tq.load(p.Q, p.ldq, first, qb + TILE, len, hc, tid);
+      td.load(p.dO, p.ldo, first, qb + TILE, len, hc, tid);
+      load_stats(qb + TILE);
+    }
+    if (qb + TILE - 1 < wk_first) continue;     // every query of the tile lies before this wave's keys
+    f32x16 s[2], dp[2];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) { s[qt][j] = 0.f; dp[qt][j] = 0.f; }
+#pragma unroll
+      for (int st = 0; st < 8; ++st) {
+        s[qt] = mma(*(const bf16x8*)(sQ + (32 * qt + li) * TP + 16 * st + 8 * half), kf[st], s[qt]);
+        dp[qt] = mma(*(const bf16x8*)(sD + (32 * qt + li) * TP + 16 * st + 8 * half), vf[st], dp[qt]);
+      }
+    }
+    const bool diag = qb < wk_first + 32;        // some query of the tile lies before some key of the wave
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int qi = 32 * qt + tok(j, half);
+        float pr = exp2f(s[qt][j] * c - sLse[qi]);
+        if (!kok || (diag && qb + qi < kl)) pr = 0.f;
+        s[qt][j] = pr;                               // P
+        dp[qt][j] = pr * (dp[qt][j] - sDelta[qi]);   // dS
+      }
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const bf16x8 pb = pack8(s[qt], u), ds = pack8(dp[qt], u);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+          dv[dt] = mma(read_across(sD, 32 * qt + 16 * u, 32 * dt, lane), pb, dv[dt]);
+          dk[dt] = mma(read_across(sQ, 32 * qt + 16 * u, 32 * dt, lane), ds, dk[dt]);
+        }
+      }
+  }
+  if (kok) {
+    bf16_t* krow = p.dK + (size_t)(first + kl) * p.ldk + hc;
+    bf16_t* vrow = p.dV + (size_t)(first + kl) * p.ldv + hc;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int jg = 0; jg < 4; ++jg) {
+        uint2 a, b;
+        a.x = pack_bf16x2(dk[dt][4 * jg + 0] * p.scale, dk[dt][4 * jg + 1] * p.scale);
+        a.y = pack_bf16x2(dk[dt][4 * jg + 2] * p.scale, dk[dt][4 * jg + 3] * p.scale);
+        b.x = pack_bf16x2(dv[dt][4 * jg + 0], dv[dt][4 * jg + 1]);
+        b.y = pack_bf16x2(dv[dt][4 * jg + 2], dv[dt][4 * jg + 3]);
+        *(uint2*)(krow + 32 * dt + 8 * jg + 4 * half) = a;
+        *(uint2*)(vrow + 32 * dt + 8 * jg + 4 * half) = b;
+      }
+  }
+}
+
+mux_status check(const char* fn, const mux_attn_desc* d, const mux_segtab* st) {
+  if (!d || !st) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": null descriptor or table");
+  if (d->n_heads < 1 || d->n_kv_heads < 1 || d->head_dim < 1) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": bad head counts");
+  if (d->dtype != MUX_DT_BF16 || d->head_dim != D || d->n_kv_heads != d->n_heads)
+    return fail(MUX_ERR_UNSUPPORTED, std::string(fn) + ": only bf16, head_dim 128 and n_kv_heads == n_heads are built");
+  const int64_t w = (int64_t)d->n_heads * D;
+  const int64_t lds[4] = {d->ldq, d->ldk, d->ldv, d->ldo};
+  for (int64_t ld : lds) {
+    if (ld < w) return fail(MUX_ERR_SHAPE, std::string(fn) + ": a leading dimension is smaller than n_heads * head_dim");
+    if (ld % 8) return fail(MUX_ERR_UNSUPPORTED, std::string(fn) + ": leading dimensions must be multiples of 8");
+    if ((int64_t)st->T * ld >= ((int64_t)1 << 40)) return fail(MUX_ERR_SHAPE, std::string(fn) + ": problem too large");
+  }
+  if (d->n_heads > 65535) return fail(MUX_ERR_SHAPE, std::string(fn) + ": too many heads");
+  if (!(d->scale >= 0.f)) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": negative scale");
+  return MUX_OK;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+mux_status last_hip(const char* fn) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(MUX_ERR_DEVICE, std::string(fn) + ": " + hipGetErrorString(e));
+  return MUX_OK;
+}
+
+}  // namespace
+}  // namespace mux
+
+using namespace mux;
+
+extern "C" size_t mux_attn_saved_bytes(const mux_attn_desc* desc, const mux_segtab* st) {
+  if (!desc || !st || desc->n_heads < 1) return 0;
+  return align256((size_t)st->T * (size_t)desc->n_heads * sizeof(float));
+}
+
+extern "C" size_t mux_attn_workspace_bytes(const mux_attn_desc* desc, const mux_segtab* st) {
+  return mux_attn_saved_bytes(desc, st);
+}
+
+extern "C" mux_status mux_attn_forward(const mux_attn_desc* desc, const mux_segtab* st, const void* dev_segtab,
+                                       const void* Q, const void* K, const void* V, void* O, void* saved,
+                                       void* hip_stream) {
+  static const char* fn = "mux_attn_forward";
+  if (mux_status s = check(fn, desc, st)) return s;
+  if (st->T == 0) return MUX_OK;
+  if (!dev_segtab || !Q || !K || !V || !O) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": null device pointer");
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O))
+    return fail(MUX_ERR_UNSUPPORTED, std::string(fn) + ": pointers must be 16-byte aligned");
+  hipStream_t stream = (hipStream_t)hip_stream;
+  AttnParams p{};
+  p.dtab = (const int32_t*)dev_segtab;
+  p.Q = (const bf16_t*)Q; p.K = (const bf16_t*)K; p.V = (const bf16_t*)V; p.Out = (bf16_t*)O;
+  p.lse = (float*)saved;
+  p.ldq = desc->ldq; p.ldk = desc->ldk; p.ldv = desc->ldv; p.ldo = desc->ldo;
+  p.T = st->T; p.H = desc->n_heads;
+  p.scale = desc->scale > 0.f ? desc->scale : 1.f / sqrtf((float)D);
+  ZeroParams z{};
+  z.dtab = p.dtab; z.out[0] = (bf16_t*)O; z.ld[0] = desc->ldo; z.n_out = 1; z.width = desc->n_heads * D;
+  MUX_LAUNCH("attn_zero_pad", k_attn_zero_pad, dim3((unsigned)st->items[0].size()), dim3(256), 0, stream, z);
+  if (st->n_attn_blocks > 0)
+    MUX_LAUNCH("attn_fwd", k_attn_fwd, dim3((unsigned)st->n_attn_blocks, (unsigned)desc->n_heads), dim3(256), 0, stream, p);
+  return last_hip(fn);
+}
+
+extern "C" mux_status mux_attn_backward(const mux_attn_desc* desc, const mux_segtab* st, const void* dev_segtab,
+                                        const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                                        const void* saved, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes,
+                                        void* hip_stream) {
+  static const char* fn = "mux_attn_backward";
+  if (mux_status s = check(fn, desc, st)) return s;
+  if (st->T == 0) return MUX_OK;
+  if (!dev_segtab || !Q || !K || !V || !O || !dO || !saved || !dQ || !dK || !dV || !ws)
+    return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": null device pointer");
+  const void* ptrs[8] = {Q, K, V, O, dO, dQ, dK, dV};
+  for (const void* q : ptrs)
+    if (!aligned16(q)) return fail(MUX_ERR_UNSUPPORTED, std::string(fn) + ": pointers must be 16-byte aligned");
+  if (ws_bytes < mux_attn_workspace_bytes(desc, st)) return fail(MUX_ERR_WORKSPACE, std::string(fn) + ": workspace too small");
+  hipStream_t stream = (hipStream_t)hip_stream;
+  AttnParams p{};
+  p.dtab = (const int32_t*)dev_segtab;
+  p.Q = (const bf16_t*)Q; p.K = (const bf16_t*)K; p.V = (const bf16_t*)V; p.O = (const bf16_t*)O; p.dO = (const bf16_t*)dO;
+  p.dQ = (bf16_t*)dQ; p.dK = (bf16_t*)dK; p.dV = (bf16_t*)dV;
+  p.lse = (float*)saved; p.delta = (float*)ws;
+  p.ldq = desc->ldq; p.ldk = desc->ldk; p.ldv = desc->ldv; p.ldo = desc->ldo;
+  p.T = st->T; p.H = desc->n_heads;
+  p.scale = desc->scale > 0.f ? desc->scale : 1.f / sqrtf((float)D);
+  ZeroParams z{};
+  z.dtab = p.dtab; z.n_out = 3; z.width = desc->n_heads * D;
+  z.out[0] = p.dQ; z.ld[0] = desc->ldq; z.out[1] = p.dK; z.ld[1] = desc->ldk; z.out[2] = p.dV; z.ld[2] = desc->ldv;
+  MUX_LAUNCH("attn_zero_pad", k_attn_zero_pad, dim3((unsigned)st->items[0].size()), dim3(256), 0, stream, z);
+  const size_t n = (size_t)st->T * desc->n_heads;
+  MUX_LAUNCH("attn_delta", k_attn_delta, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p);
+  if (st->n_attn_blocks > 0) {
+    MUX_LAUNCH("attn_bwd_kv", k_attn_bwd_kv, dim3((unsigned)st->n_attn_blocks, (unsigned)desc->n_heads), dim3(256), 0, stream, p);
+    MUX_LAUNCH("attn_bwd_q", k_attn_bwd_q, dim3((unsigned)st->n_attn_blocks, (unsigned)desc->n_heads), dim3(256), 0, stream, p);
+  }
+  return last_hip(fn);
+}

@@ -14,7 +14,11 @@ namespace mux {
 enum : int {
   DH_MAGIC = 0, DH_T, DH_CHUNK, DH_LOG2C, DH_NTASKS, DH_NCHUNKS, DH_OFF_TASKS, DH_OFF_CHUNK_VALID,
   DH_NITEMS0,            // + 3*i : n_items, off_items, off_task_items for tile size kTileRows[i]
-  DH_ZROWS = DH_NITEMS0 + 12, DH_RMAX, DH_WORDS, DH_OFF_ROWBITS, DH_HDR_WORDS = 32
+  DH_ZROWS = DH_NITEMS0 + 12, DH_RMAX, DH_WORDS, DH_OFF_ROWBITS,
+  DH_ATT_NBLK,           // attention work lists: number of 128-row blocks of sequences, then the word offsets of the
+  DH_ATT_OFF_FWD,        // list ordered for the passes that walk the keys before a block (longest walk first) and of the
+  DH_ATT_OFF_BWD,        // list ordered for the pass that walks the queries after a block; 4 words an entry (DA_*)
+  DH_HDR_WORDS = 32
 };
 constexpr int kNumTileSizes = 4;
 constexpr int kTileRows[kNumTileSizes] = {64, 128, 256, 1024};
@@ -22,6 +26,9 @@ constexpr uint32_t kDevMagic = 0x4458554Du;  // "MUXD"
 
 // per task, 8 words
 enum : int { DT_ROW_BEGIN = 0, DT_ROW_COUNT, DT_VALID, DT_KIND, DT_RANK, DT_SCALE_BITS, DT_ZROW0, DT_ITEM_PAD, DT_WORDS };
+// per attention block, 4 words: the sequence's first row and length, the block's first token inside the sequence
+enum : int { DA_FIRST_ROW = 0, DA_LEN, DA_BLOCK0, DA_PAD, DA_WORDS };
+constexpr int kAttnBlockRows = 128;
 // per work item, 4 words: rows [row0, row0+nrows) all belong to `task` (-1: rows of no task)
 enum : int { DI_TASK = 0, DI_ROW0, DI_NROWS, DI_NVALID, DI_WORDS };
 
@@ -66,6 +73,7 @@ struct mux_segtab {
   std::vector<int32_t> dev_image;   // device image (host copy, source of the upload)
   std::vector<int32_t> row_task;    // T entries
   std::vector<mux::HostTask> tasks;
+  int32_t n_attn_blocks = 0;        // 128-row blocks of sequences (attention work items)
   std::vector<mux::Item> items[mux::kNumTileSizes];
   std::vector<int32_t> task_item_begin[mux::kNumTileSizes], task_item_count[mux::kNumTileSizes];
 };

@@ -2,6 +2,7 @@
 // the canonical serialisation, and the device image with the tile work lists.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstring>
 #include <new>
 
@@ -235,6 +236,22 @@ extern "C" mux_status mux_segtab_build(const mux_task_desc* tasks, int32_t n_tas
       dv.resize(base + words, 0);
       for (int32_t i = 0; i < st->T; ++i)
         if (st->row_task[i] >= 0) dv[base + (i >> 5)] |= (int32_t)(1u << (i & 31));
+    }
+    // attention work lists: every sequence cut into blocks of 128 tokens.  A block of queries walks the keys of its
+    // sequence up to its own end, a block of keys the queries from its own start on: longest walk first in each list
+    {
+      struct Blk { int32_t first_row, len, b0; };
+      std::vector<Blk> blks;
+      for (const Seq& sq : seqs)
+        for (int32_t b0 = 0; b0 < sq.len; b0 += kAttnBlockRows) blks.push_back({sq.first_row, sq.len, b0});
+      st->n_attn_blocks = (int32_t)blks.size();
+      dv[DH_ATT_NBLK] = st->n_attn_blocks;
+      std::stable_sort(blks.begin(), blks.end(), [](const Blk& a, const Blk& b) { return a.b0 > b.b0; });
+      dv[DH_ATT_OFF_FWD] = (int32_t)dv.size();
+      for (const Blk& b : blks) { const int32_t w[DA_WORDS] = {b.first_row, b.len, b.b0, 0}; dv.insert(dv.end(), w, w + DA_WORDS); }
+      std::stable_sort(blks.begin(), blks.end(), [](const Blk& a, const Blk& b) { return a.len - a.b0 > b.len - b.b0; });
+      dv[DH_ATT_OFF_BWD] = (int32_t)dv.size();
+      for (const Blk& b : blks) { const int32_t w[DA_WORDS] = {b.first_row, b.len, b.b0, 0}; dv.insert(dv.end(), w, w + DA_WORDS); }
     }
     while (dv.size() % 64) dv.push_back(0);
     dv[DH_WORDS] = (int32_t)dv.size();

@@ -1,0 +1,140 @@
+"""GPU parity of the attention step (include/mux_attn.h) against the fp64 attention oracle, same seeded inputs,
+through the C ABI: forward and backward, sequences of every length relation to the 128-token blocks and 64-token
+tiles, packed and chunk-cut, padding rows poisoned."""
+import numpy as np
+import pytest
+
+from oracle import attention as oatt
+from oracle import segtab
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2     # bf16 storage, fp32 accumulation: max |gpu - ref| / max |ref| per tensor
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2603_02885_amd as mx
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    mx.load_library()
+    return mx, torch
+
+
+def bf16_round(a):
+    """Round fp32 values to bfloat16 (nearest even) so that both sides start from the same numbers."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    r = ((u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000).astype(np.uint32)
+    return r.view(np.float32)
+
+
+def run(env, task_lens, chunk, H, seed, max_pack_len=0, flags=0, fused=False, sigma=1.0, check_repeat=False):
+    mx, torch = env
+    d = 128
+    ot = segtab.build(task_lens, chunk, max_pack_len, flags)
+    seqs = [(s[2], s[3]) for s in segtab.sequences(ot)]
+    T = ot.T
+    rng = np.random.default_rng(seed)
+    Q, K, V, dO = (bf16_round(rng.standard_normal((T, H * d)) * sigma) for _ in range(4))
+    pad = ot.row_task < 0
+    for a in (Q, K, V, dO):
+        a[pad] = np.nan if seed % 2 else 1e30            # padding rows must not leak anywhere
+    print(f"attention case: T={T} H={H} chunk={chunk} seqs={len(seqs)} longest={max([n for _, n in seqs] + [0])}", flush=True)
+    st = mx.mux_segtab_build([mx.TaskDesc(mx.MUX_ADAPTER_NONE, 0, 1.0, l) for l in task_lens], chunk, max_pack_len, flags)
+    assert np.array_equal(mx.mux_segtab_serialize(st), ot.image)
+    dev = "cuda:0"
+    nb = mx.mux_segtab_device_bytes(st)
+    dtab = torch.zeros(nb, dtype=torch.uint8, device=dev)
+    mx.mux_segtab_upload(st, dtab, nb)
+    up = lambda a: torch.from_numpy(a).to(dev).to(torch.bfloat16)
+    if fused:        # the three slices of one [T, 3 H d] buffer
+        qkv = torch.cat([up(Q), up(K), up(V)], dim=1).contiguous()
+        tq, tk, tv = qkv[:, :H * d], qkv[:, H * d:2 * H * d], qkv[:, 2 * H * d:]
+        ld = 3 * H * d
+    else:
+        tq, tk, tv = up(Q), up(K), up(V)
+        ld = H * d
+    tdo = up(dO)
+    desc = mx.AttnDesc(H, d, ld, ld, ld, H * d)
+    nan = float("nan")
+    O = torch.full((T, H * d), nan, dtype=torch.bfloat16, device=dev)
+    dQ, dK, dV = (torch.full((T, H * d), nan, dtype=torch.bfloat16, device=dev) for _ in range(3))
+    gdesc = mx.AttnDesc(H, d, H * d, H * d, H * d, H * d)
+    saved = torch.full((max(mx.mux_attn_saved_bytes(desc, st), 256),), 0xFF, dtype=torch.uint8, device=dev)
+    wsb = mx.mux_attn_workspace_bytes(desc, st)
+    ws = torch.full((max(wsb, 256),), 0xFF, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+    mx.mux_attn_forward(desc, st, dtab, tq, tk, tv, O, saved, stream)
+    torch.cuda.synchronize()
+    if fused:        # backward writes dQ, dK, dV with the leading dimensions of Q, K, V: give it a fused buffer too
+        dqkv = torch.full((T, 3 * H * d), nan, dtype=torch.bfloat16, device=dev)
+        dQ, dK, dV = dqkv[:, :H * d], dqkv[:, H * d:2 * H * d], dqkv[:, 2 * H * d:]
+    mx.mux_attn_backward(desc, st, dtab, tq, tk, tv, O, tdo, saved, dQ, dK, dV, ws, wsb, stream)
+    torch.cuda.synchronize()
+    got = {k: v.float().cpu().numpy().astype(np.float64) for k, v in (("O", O), ("dQ", dQ), ("dK", dK), ("dV", dV))}
+    ref = oatt.forward(Q, K, V, seqs, H)
+    # the backward consumes the O the forward stored (bf16); the oracle's dO.O term uses its own O: same to rounding
+    ref.update(oatt.backward(Q, K, V, dO, seqs, H))
+    errs = {}
+    for k in ("O", "dQ", "dK", "dV"):
+        assert np.isfinite(got[k]).all(), k
+        assert np.all(got[k][pad] == 0), f"{k}: padding rows must be zero"
+        scale = np.max(np.abs(ref[k])) or 1.0
+        errs[k] = float(np.max(np.abs(got[k] - ref[k])) / scale)
+    print({k: float(f"{v:.2e}") for k, v in errs.items()}, flush=True)
+    assert all(v <= TOL for v in errs.values()), errs
+    lse = saved[: T * H * 4].view(torch.float32).view(H, T).cpu().numpy().astype(np.float64)
+    valid = ~pad
+    assert np.allclose(lse[:, valid], ref["lse"][:, valid], rtol=0, atol=2e-2)
+    if check_repeat:
+        keep = [t.clone() for t in (O, dQ, dK, dV)]
+        for _ in range(3):
+            mx.mux_attn_forward(desc, st, dtab, tq, tk, tv, O, saved, stream)
+            mx.mux_attn_backward(desc, st, dtab, tq, tk, tv, O, tdo, saved, dQ, dK, dV, ws, wsb, stream)
+            torch.cuda.synchronize()
+            for a, b in zip(keep, (O, dQ, dK, dV)):
+                assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    return errs
+
+
+def test_short_and_ragged_sequences(env):
+    """Lengths around every boundary: 1 token, below / at / above a 32-token wave, a 64-token tile, a 128-token block."""
+    lens = [[1, 2, 31, 32, 33], [63, 64, 65], [127, 128, 129], [200, 5], []]
+    run(env, lens, chunk=64, H=2, seed=0, check_repeat=True)
+    run(env, lens, chunk=16, H=1, seed=1)
+    run(env, lens, chunk=64, H=2, seed=2, flags=1)                   # dense table: sequences back to back
+
+
+def test_long_sequences_span_chunks(env):
+    """Packs longer than a chunk: later chunks reuse the keys and values of the earlier ones (several blocks a sequence)."""
+    run(env, [[700], [300, 260], [513]], chunk=128, H=3, seed=3)
+    run(env, [[1000, 24]], chunk=256, H=2, seed=4, max_pack_len=1024)
+
+
+def test_fused_qkv_buffer_and_large_scores(env):
+    """Q, K, V as slices of one buffer (leading dimension 3 H d), and scores far from zero (softmax close to one-hot)."""
+    run(env, [[150, 90], [257]], chunk=64, H=2, seed=5, fused=True)
+    run(env, [[150, 90], [257]], chunk=64, H=2, seed=6, sigma=3.0)
+
+
+def test_llama_heads_one_block(env):
+    """32 heads of 128 (the q/k/v width of the 4096-wide projections), ragged lengths."""
+    run(env, [[384, 100], [77]], chunk=128, H=32, seed=7)
+
+
+def test_argument_checks(env):
+    mx, torch = env
+    st = mx.mux_segtab_build([mx.TaskDesc(mx.MUX_ADAPTER_NONE, 0, 1.0, [64])], 64, 0, 0)
+    dev = "cuda:0"
+    nb = mx.mux_segtab_device_bytes(st)
+    dtab = torch.zeros(nb, dtype=torch.uint8, device=dev)
+    mx.mux_segtab_upload(st, dtab, nb)
+    x = torch.zeros((64, 256), dtype=torch.bfloat16, device=dev)
+    with pytest.raises(mx.MuxError):
+        mx.mux_attn_forward(mx.AttnDesc(2, 64, 128, 128, 128, 128), st, dtab, x, x, x, x, None)       # head_dim 64
+    with pytest.raises(mx.MuxError):
+        mx.mux_attn_forward(mx.AttnDesc(2, 128, 128, 256, 256, 256), st, dtab, x, x, x, x, None)      # ldq too small
+    with pytest.raises(mx.MuxError):
+        mx.mux_attn_forward(mx.AttnDesc(2, 128, 256, 256, 256, 256, n_kv_heads=1), st, dtab, x, x, x, x, None)
+    with pytest.raises(mx.MuxError):
+        mx.mux_attn_forward(mx.AttnDesc(2, 128, 256, 256, 256, 256), st, dtab, x, None, x, x, None)   # null K
