@@ -44,6 +44,9 @@ def parse():
                     help="instead of the benchmark line: profile t_o(x), t_a(x), u_a(x) of the seven projections over "
                          "the token count, plan the fusion of 8 unequal LoRA tasks with the library's planner and compare "
                          "the cost model's predictions with measured steps")
+    ap.add_argument("--attention", action="store_true",
+                    help="instead of the benchmark line: the attention step between the q/k/v and o projections on the "
+                         "sequences of the chosen workload (heads of 128, as many as the q projection is wide)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 512 MiB device copy (known traffic) for scaling rocprofv3 byte counters")
     return ap.parse_args()
@@ -330,6 +333,75 @@ def plan(mx, torch, args):
                                                                 for h in range(len(begins4) - 1)]}}
 
 
+def attention(mx, torch, args):
+    """Causal attention of every sequence of the workload's chunk-aligned batch (section 3.5), forward + backward, on
+    the same table as the linear layers.  FLOPs counted on the visible (query, key) pairs only, n (n + 1) / 2 per
+    sequence of n tokens and head: 2 products forward (4 d FLOP a pair), 5 backward (10 d FLOP a pair; the kernels
+    recompute the scores and dO.V^T in both backward passes, which is not counted)."""
+    import mux_workloads as wlm
+    import numpy as np
+    wl = wlm.config(args.workload, seed=args.seed)
+    dev = "cuda:0"
+    d = 128
+    H = wl.layers[0][2] // d
+    st = mx.mux_segtab_build([mx.TaskDesc(t.kind, t.rank, t.scale, t.seq_lens) for t in wl.tasks], wl.chunk,
+                             wl.max_pack_len, 0)
+    T = mx.mux_segtab_rows(st)
+    nb = mx.mux_segtab_device_bytes(st)
+    dtab = torch.zeros(nb, dtype=torch.uint8, device=dev)
+    mx.mux_segtab_upload(st, dtab, nb)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed)
+    rnd = lambda: torch.randn((T, H * d), device=dev, dtype=torch.float32, generator=gen).to(torch.bfloat16)
+    qkv = torch.cat([rnd(), rnd(), rnd()], dim=1).contiguous()         # the fused output of the q/k/v projections
+    Q, K, V = qkv[:, :H * d], qkv[:, H * d:2 * H * d], qkv[:, 2 * H * d:]
+    dqkv = torch.empty_like(qkv)
+    dQ, dK, dV = dqkv[:, :H * d], dqkv[:, H * d:2 * H * d], dqkv[:, 2 * H * d:]
+    O, dO = torch.empty((T, H * d), device=dev, dtype=torch.bfloat16), rnd()
+    desc = mx.AttnDesc(H, d, 3 * H * d, 3 * H * d, 3 * H * d, H * d)
+    saved = torch.zeros(max(mx.mux_attn_saved_bytes(desc, st), 256), dtype=torch.uint8, device=dev)
+    wsb = mx.mux_attn_workspace_bytes(desc, st)
+    ws = torch.zeros(max(wsb, 256), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def one():
+        mx.mux_attn_forward(desc, st, dtab, Q, K, V, O, saved, stream)
+        mx.mux_attn_backward(desc, st, dtab, Q, K, V, O, dO, saved, dQ, dK, dV, ws, wsb, stream)
+    for _ in range(args.warmup):
+        one()
+    torch.cuda.synchronize()
+    mx.mux_profile_enable(1)
+    mx.mux_profile_collect()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    prof = mx.mux_profile_collect()
+    mx.mux_profile_enable(0)
+    lens = [n for t in wl.tasks for n in t.seq_lens]
+    pairs = float(sum(n * (n + 1) // 2 for n in lens)) * H
+    flops = {"attn_fwd": 4.0 * d * pairs, "attn_bwd_kv": 6.0 * d * pairs, "attn_bwd_q": 4.0 * d * pairs}
+    kernels = {}
+    for e in prof:
+        k = {"launches": e["launches"], "avg_us": e["total_ms"] * 1e3 / max(e["launches"], 1)}
+        if e["name"] in flops:
+            k["tflops"] = flops[e["name"]] / (k["avg_us"] * 1e-6) / 1e12
+            k["frac_of_bf16_mfma_peak"] = k["tflops"] / PEAK_BF16_MFMA
+        kernels[e["name"]] = k
+    valid = mx.mux_segtab_valid_tokens(st)
+    dom = max((n for n in kernels if n in flops), key=lambda n: kernels[n]["avg_us"])
+    return {"metric": "chunk-aligned causal attention fwd+bwd tokens/s", "value": valid / (ms * 1e-3), "unit": "tokens/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+            "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"configs[{args.workload}] {wl.name}: sequences of {wl.notes}; {H} heads of {d}",
+                       "rows": T, "valid_tokens": valid, "sequences": len(lens), "longest": max(lens)},
+            "tflops": 14.0 * d * pairs / (ms * 1e-3) / 1e12,
+            "roofline": {"kernel": dom, "bound": "mfma", "achieved": kernels[dom]["tflops"], "peak": PEAK_BF16_MFMA,
+                         "unit": "TFLOP/s", "frac": kernels[dom]["frac_of_bf16_mfma_peak"], "traffic": None},
+            "kernels": kernels}
+
+
 def cpu_baseline(wl, seconds, seed):
     """The fp64 oracle, as it stands, on a bounded sample: the first m tokens of every task through
     every projection (fwd+bwd), m sized from a short calibration so that the run takes about `seconds`."""
@@ -379,6 +451,9 @@ def main():
         return
     if args.plan:
         print(json.dumps(plan(mx, torch, args)))
+        return
+    if args.attention:
+        print(json.dumps(attention(mx, torch, args)))
         return
     wl = wlm.config(args.workload, seed=args.seed)
     st, dtab, T, layers, ws, ws_bytes = setup(mx, torch, wl, args.seed)

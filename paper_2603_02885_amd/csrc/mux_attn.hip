@@ -46,6 +46,8 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t* p) {
 __device__ __forceinline__ f32x16 mma(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
+// 2^x by the hardware instruction (arguments here are <= 0 or masked afterwards; denormal results may flush to zero)
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ bf16x8 zero8() { return __builtin_bit_cast(bf16x8, uint4{0u, 0u, 0u, 0u}); }
 // accumulator elements 8u .. 8u+7 as a B operand
 __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int u) {
@@ -83,7 +85,7 @@ struct TileLoad {
 };
 
 // ------------------------------------------------------------------------------------------------ forward
-__global__ __launch_bounds__(256) void k_attn_fwd(AttnParams p) {
+__global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
   __shared__ __align__(16) bf16_t sK[TILE * KP];
   __shared__ __align__(16) bf16_t sV[TILE * TP];
   const int32_t* blk = p.dtab + p.dtab[DH_ATT_OFF_FWD] + blockIdx.x * DA_WORDS;
@@ -142,22 +144,24 @@ __global__ __launch_bounds__(256) void k_attn_fwd(AttnParams p) {
       }
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     const float ms = mx == -INFINITY ? 0.f : mx;
-    const float alpha = exp2f(m - ms);
+    const float alpha = fast_exp2(m - ms);
     m = mx;
     float rs = 0.f;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        const float e = exp2f(s[kt][j] - ms);
+        const float e = fast_exp2(s[kt][j] - ms);
         s[kt][j] = e;
         rs += e;
       }
     l = l * alpha + rs;
+    if (__any(alpha != 1.f)) {                  // the running maximum of some query moved
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+      for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int j = 0; j < 16; ++j) o[dt][j] *= alpha;
+        for (int j = 0; j < 16; ++j) o[dt][j] *= alpha;
+    }
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -227,7 +231,7 @@ __global__ __launch_bounds__(256) void k_attn_delta(AttnParams p) {
 }
 
 // ------------------------------------------------------------------------------------------------ dQ
-__global__ __launch_bounds__(256) void k_attn_bwd_q(AttnParams p) {
+__global__ __launch_bounds__(256, 2) void k_attn_bwd_q(AttnParams p) {
   __shared__ __align__(16) bf16_t sK[TILE * TP];
   __shared__ __align__(16) bf16_t sV[TILE * KP];
   const int32_t* blk = p.dtab + p.dtab[DH_ATT_OFF_FWD] + blockIdx.x * DA_WORDS;
@@ -269,34 +273,30 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(AttnParams p) {
       tv.load(p.V, p.ldv, first, kb + TILE, len, hc, tid);
     }
     if (kb > wq_last) continue;
-    f32x16 s[2], dp[2];
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-      for (int j = 0; j < 16; ++j) { s[kt][j] = 0.f; dp[kt][j] = 0.f; }
-#pragma unroll
-      for (int st = 0; st < 8; ++st) {
-        s[kt] = mma(*(const bf16x8*)(sK + (32 * kt + li) * TP + 16 * st + 8 * half), qf[st], s[kt]);
-        dp[kt] = mma(*(const bf16x8*)(sV + (32 * kt + li) * KP + 16 * st + 8 * half), df[st], dp[kt]);
-      }
-    }
     const bool diag = kb + TILE - 1 > wq_first;
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
+    for (int kt = 0; kt < 2; ++kt) {            // one half of the tile at a time keeps the live registers down
+      f32x16 s, dp;
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        float pr = exp2f(s[kt][j] * c - lse2);
-        if (!qok || (diag && kb + 32 * kt + tok(j, half) > ql)) pr = 0.f;
-        s[kt][j] = pr * (dp[kt][j] - dl);          // dS^T
+      for (int j = 0; j < 16; ++j) { s[j] = 0.f; dp[j] = 0.f; }
+#pragma unroll
+      for (int st = 0; st < 8; ++st) {
+        s = mma(*(const bf16x8*)(sK + (32 * kt + li) * TP + 16 * st + 8 * half), qf[st], s);
+        dp = mma(*(const bf16x8*)(sV + (32 * kt + li) * KP + 16 * st + 8 * half), df[st], dp);
       }
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
+      for (int j = 0; j < 16; ++j) {
+        float pr = fast_exp2(s[j] * c - lse2);
+        if (!qok || (diag && kb + 32 * kt + tok(j, half) > ql)) pr = 0.f;
+        s[j] = pr * (dp[j] - dl);          // dS^T
+      }
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        const bf16x8 ds = pack8(s[kt], u);
+        const bf16x8 ds = pack8(s, u);
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) dq[dt] = mma(read_across(sK, 32 * kt + 16 * u, 32 * dt, lane), ds, dq[dt]);
       }
+    }
   }
   if (qok) {
     bf16_t* orow = p.dQ + (size_t)(first + ql) * p.ldq + hc;
@@ -313,9 +313,10 @@ __global__ __launch_bounds__(256) void k_attn_bwd_q(AttnParams p) {
 }
 
 // ------------------------------------------------------------------------------------------------ dK, dV
-__global__ __launch_bounds__(256) void k_attn_bwd_kv(AttnParams p) {
+__global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
   __shared__ __align__(16) bf16_t sQ[TILE * TP];
   __shared__ __align__(16) bf16_t sD[TILE * TP];
+  __shared__ __align__(16) bf16_t sVf[BLK * KP];   // the block's own V rows (B operand of dO V^T), kept here to save registers
   __shared__ float sLse[TILE], sDelta[TILE];
   const int32_t* blk = p.dtab + p.dtab[DH_ATT_OFF_BWD] + blockIdx.x * DA_WORDS;
   const int first = blk[DA_FIRST_ROW], len = blk[DA_LEN], k0 = blk[DA_BLOCK0];
@@ -323,16 +324,18 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(AttnParams p) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, half = lane >> 5;
   const int kl = k0 + 32 * wave + li;          // this lane's key inside the sequence
   const bool kok = kl < len;
-  bf16x8 kf[8], vf[8];
+  bf16x8 kf[8];
   {
     const bf16_t* krow = p.K + (size_t)(first + kl) * p.ldk + hc + 8 * half;
-    const bf16_t* vrow = p.V + (size_t)(first + kl) * p.ldv + hc + 8 * half;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      kf[s] = kok ? *(const bf16x8*)(krow + 16 * s) : zero8();
-      vf[s] = kok ? *(const bf16x8*)(vrow + 16 * s) : zero8();
-    }
+    for (int s = 0; s < 8; ++s) kf[s] = kok ? *(const bf16x8*)(krow + 16 * s) : zero8();
+    TileLoad t;
+    t.load(p.V, p.ldv, first, k0, len, hc, tid);
+    t.store(sVf, KP, tid);
+    t.load(p.V, p.ldv, first, k0 + TILE, len, hc, tid);
+    t.store(sVf + TILE * KP, KP, tid);
   }
+  const bf16_t* vfrag = sVf + (32 * wave + li) * KP + 8 * half;
   const float c = p.scale * LOG2E;
   f32x16 dk[4], dv[4];
 #pragma unroll
@@ -364,39 +367,37 @@ __global__ __launch_bounds__(256) void k_attn_bwd_kv(AttnParams p) {
       load_stats(qb + TILE);
     }
     if (qb + TILE - 1 < wk_first) continue;     // every query of the tile lies before this wave's keys
-    f32x16 s[2], dp[2];
-#pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-#pragma unroll
-      for (int j = 0; j < 16; ++j) { s[qt][j] = 0.f; dp[qt][j] = 0.f; }
-#pragma unroll
-      for (int st = 0; st < 8; ++st) {
-        s[qt] = mma(*(const bf16x8*)(sQ + (32 * qt + li) * TP + 16 * st + 8 * half), kf[st], s[qt]);
-        dp[qt] = mma(*(const bf16x8*)(sD + (32 * qt + li) * TP + 16 * st + 8 * half), vf[st], dp[qt]);
-      }
-    }
     const bool diag = qb < wk_first + 32;        // some query of the tile lies before some key of the wave
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt)
+    for (int qt = 0; qt < 2; ++qt) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) { s[j] = 0.f; dp[j] = 0.f; }
+#pragma unroll
+      for (int st = 0; st < 8; ++st) {
+        s = mma(*(const bf16x8*)(sQ + (32 * qt + li) * TP + 16 * st + 8 * half), kf[st], s);
+        dp = mma(*(const bf16x8*)(sD + (32 * qt + li) * TP + 16 * st + 8 * half), *(const bf16x8*)(vfrag + 16 * st), dp);
+        if (st % 2 == 1) __builtin_amdgcn_sched_barrier(0);
+      }
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
         const int qi = 32 * qt + tok(j, half);
-        float pr = exp2f(s[qt][j] * c - sLse[qi]);
+        float pr = fast_exp2(s[j] * c - sLse[qi]);
         if (!kok || (diag && qb + qi < kl)) pr = 0.f;
-        s[qt][j] = pr;                               // P
-        dp[qt][j] = pr * (dp[qt][j] - sDelta[qi]);   // dS
+        s[j] = pr;                            // P
+        dp[j] = pr * (dp[j] - sDelta[qi]);    // dS
       }
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
       for (int u = 0; u < 2; ++u) {
-        const bf16x8 pb = pack8(s[qt], u), ds = pack8(dp[qt], u);
+        const bf16x8 pb = pack8(s, u), ds = pack8(dp, u);
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
           dv[dt] = mma(read_across(sD, 32 * qt + 16 * u, 32 * dt, lane), pb, dv[dt]);
           dk[dt] = mma(read_across(sQ, 32 * qt + 16 * u, 32 * dt, lane), ds, dk[dt]);
         }
+        __builtin_amdgcn_sched_barrier(0);      // keeps the operand reads of the next group from piling up in registers
       }
+    }
   }
   if (kok) {
     bf16_t* krow = p.dK + (size_t)(first + kl) * p.ldk + hc;
