@@ -132,26 +132,27 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
         s[kt] = mma(*(const bf16x8*)(sK + (32 * kt + li) * KP + 16 * st + 8 * half), qf[st], s[kt]);
     }
     const bool diag = kb + TILE - 1 > wq_first;
+    // running maximum on the raw scores (the scale is positive), then one fused multiply-add per element: m is kept in
+    // units of the raw score, exp2 arguments are s c - m c
     float mx = m;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        float t = s[kt][j] * c;
-        if (diag && kb + 32 * kt + tok(j, half) > ql) t = -INFINITY;
-        s[kt][j] = t;
-        mx = fmaxf(mx, t);
+        if (diag && kb + 32 * kt + tok(j, half) > ql) s[kt][j] = -INFINITY;
+        mx = fmaxf(mx, s[kt][j]);
       }
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     const float ms = mx == -INFINITY ? 0.f : mx;
-    const float alpha = fast_exp2(m - ms);
+    const float alpha = fast_exp2((m - ms) * c);
     m = mx;
+    const float msc = ms * c;
     float rs = 0.f;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        const float e = fast_exp2(s[kt][j] - ms);
+        const float e = fast_exp2(fmaf(s[kt][j], c, -msc));
         s[kt][j] = e;
         rs += e;
       }
@@ -184,7 +185,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
         v.y = pack_bf16x2(o[dt][4 * jg + 2] * inv, o[dt][4 * jg + 3] * inv);
         *(uint2*)(orow + 32 * dt + 8 * jg + 4 * half) = v;
       }
-    if (p.lse && half == 0) p.lse[(size_t)blockIdx.y * p.T + first + ql] = (m + log2f(l)) * LN2;
+    if (p.lse && half == 0) p.lse[(size_t)blockIdx.y * p.T + first + ql] = (m * c + log2f(l)) * LN2;
   }
 }
 
