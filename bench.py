@@ -36,6 +36,10 @@ def parse():
     ap.add_argument("--compare-unmultiplexed", action="store_true",
                     help="also time the same tasks one at a time (one table and one set of calls per task, same shared "
                          "W, same rows), on one stream and alternating over two streams: what multiplexing buys")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="also time the fully multiplexed step with its independent projections issued alternately on two "
+                         "streams (kernels of the two streams overlap, so per-kernel times of a profiler run then differ "
+                         "from the single-stream ones)")
     ap.add_argument("--tradeoff", action="store_true",
                     help="instead of the benchmark line: spatial against temporal multiplexing of m equal LoRA tasks "
                          "(micro-batch 8, sequence length 128 each) on the LLaMA-7B projections, m = 1..16, and "
@@ -578,30 +582,31 @@ def main():
     }
     mx.mux_profile_enable(0)
     mx.mux_profile_collect()
-    # fully multiplexed, but the (independent) projections issued alternately on two streams, each with its own
-    # workspace: the second stream's kernels fill the compute units the first one's GEMM leaves idle in its last round
-    side = torch.cuda.Stream()
-    ws2 = torch.zeros_like(ws)
-    main = torch.cuda.current_stream()
+    if args.two_streams or args.compare_unmultiplexed:
+        # fully multiplexed, but the (independent) projections issued alternately on two streams, each with its own
+        # workspace: the second stream's kernels fill the compute units the first one's GEMM leaves idle in its last round
+        side = torch.cuda.Stream()
+        ws2 = torch.zeros_like(ws)
+        main = torch.cuda.current_stream()
 
-    def step2():
-        for i, L in enumerate(layers):
-            sx, wx = (main, ws) if i % 2 == 0 else (side, ws2)
-            mx.mux_lora_forward(L.desc, st, dtab, L.X, L.Y, L.saved, wx, ws_bytes, sx)
-        for i, L in reversed(list(enumerate(layers))):
-            sx, wx = (main, ws) if i % 2 == 0 else (side, ws2)
-            mx.mux_lora_backward(L.desc, st, dtab, L.X, L.dY, L.saved, L.dX, L.dA, L.dB, L.dL, 0, wx, ws_bytes, sx)
+        def step2():
+            for i, L in enumerate(layers):
+                sx, wx = (main, ws) if i % 2 == 0 else (side, ws2)
+                mx.mux_lora_forward(L.desc, st, dtab, L.X, L.Y, L.saved, wx, ws_bytes, sx)
+            for i, L in reversed(list(enumerate(layers))):
+                sx, wx = (main, ws) if i % 2 == 0 else (side, ws2)
+                mx.mux_lora_backward(L.desc, st, dtab, L.X, L.dY, L.saved, L.dX, L.dA, L.dB, L.dL, 0, wx, ws_bytes, sx)
 
-    side.wait_stream(main)
-    for _ in range(args.warmup):
-        step2()
-    torch.cuda.synchronize()
-    t2 = time.perf_counter()
-    for _ in range(args.steps):
-        step2()
-    torch.cuda.synchronize()
-    ms2 = (time.perf_counter() - t2) * 1e3 / args.steps
-    out["multiplexed_projections_on_two_streams"] = {"ms_per_step": ms2, "tokens_per_s": valid / (ms2 * 1e-3)}
+        side.wait_stream(main)
+        for _ in range(args.warmup):
+            step2()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(args.steps):
+            step2()
+        torch.cuda.synchronize()
+        ms2 = (time.perf_counter() - t2) * 1e3 / args.steps
+        out["multiplexed_projections_on_two_streams"] = {"ms_per_step": ms2, "tokens_per_s": valid / (ms2 * 1e-3)}
     if args.compare_unmultiplexed:
         mx.mux_profile_enable(0)
         mx.mux_profile_collect()
