@@ -120,3 +120,34 @@ def test_rejects_bad_arguments():
         segtab.build([[3]], 12)
     with pytest.raises(ValueError):
         segtab.build([[0]], 16)
+
+
+def test_dispatch_oracle_hand_example_and_round_trip():
+    """Dispatch places a task's packed tokens on its valid rows in order (pinned on the hand-laid table of the paper's
+    alignment example: Task1's 8 tokens on rows 0-5, 8, 9, Task2's 3 tokens on rows 12-14, zeros elsewhere) and
+    scatter is its inverse on the valid rows."""
+    import json
+    import os
+    from oracle import dispatch
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "segtab_hand_example.json")))
+    st = segtab.build(g["tasks"], g["chunk"], g["max_pack_len"], 0)
+    a = np.arange(1, 9, dtype=np.float64)[:, None] * np.array([[1.0, 10.0]])        # task 1: tokens 1..8
+    b = -np.arange(1, 4, dtype=np.float64)[:, None] * np.array([[1.0, 10.0]])       # task 2: tokens -1..-3
+    X = dispatch.gather([a, b], st.row_task, 2)
+    want = np.zeros((16, 2))
+    for tok, row in enumerate([0, 1, 2, 3, 4, 5, 8, 9]):
+        want[row] = a[tok]
+    for tok, row in enumerate([12, 13, 14]):
+        want[row] = b[tok]
+    assert np.array_equal(X, want)
+    back = dispatch.scatter(X, st.row_task, 2)
+    assert np.array_equal(back[0], a) and np.array_equal(back[1], b)
+    # the dense table of the same example: same tokens, other rows
+    sd = segtab.build(g["tasks"], g["chunk"], g["max_pack_len"], 1)
+    Xd = dispatch.gather([a, b], sd.row_task, 2)
+    assert np.array_equal(Xd[:8], a) and np.array_equal(Xd[8:11], b) and np.all(Xd[11] == 0)
+    # a token keeps its place inside its sequence: the rows of a sequence are consecutive and in order
+    for t, p, first, n in segtab.sequences(st):
+        src = a if t == 0 else b
+        off = sum(s[3] for s in segtab.sequences(st) if s[0] == t and s[2] < first)
+        assert np.array_equal(X[first:first + n], src[off:off + n])
