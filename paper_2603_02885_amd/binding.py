@@ -22,6 +22,7 @@ __all__ = [
     "mux_segtab_upload", "mux_lora_saved_bytes", "mux_lora_workspace_bytes", "mux_lora_forward",
     "mux_lora_backward", "mux_last_error", "mux_version", "mux_profile_enable", "mux_profile_collect",
     "CostModel", "mux_plan_stage_latency", "mux_plan_htask_latency", "mux_plan_fusion",
+    "mux_dispatch_gather", "mux_dispatch_scatter",
     "AttnDesc", "mux_attn_saved_bytes", "mux_attn_workspace_bytes", "mux_attn_forward", "mux_attn_backward",
 ]
 
@@ -165,6 +166,8 @@ def load_library() -> ctypes.CDLL:
         "mux_profile_collect": (c_int, [POINTER(_ProfileEntryC), c_int32, POINTER(c_int32)]),
         "mux_last_error": (c_char_p, []),
         "mux_version": (c_char_p, []),
+        "mux_dispatch_gather": (c_int, [vp, vp, POINTER(vp), c_int64, vp, c_int64, c_int32, c_int32, vp]),
+        "mux_dispatch_scatter": (c_int, [vp, vp, vp, c_int64, POINTER(vp), c_int64, c_int32, c_int32, vp]),
         "mux_attn_saved_bytes": (c_size_t, [POINTER(_AttnDescC), vp]),
         "mux_attn_workspace_bytes": (c_size_t, [POINTER(_AttnDescC), vp]),
         "mux_attn_forward": (c_int, [POINTER(_AttnDescC), vp, vp, vp, vp, vp, vp, vp, vp]),
@@ -440,3 +443,18 @@ def mux_attn_backward(desc: AttnDesc, st: SegTab, dev_segtab, Q, K, V, O, dO, sa
     _check(load_library().mux_attn_backward(ctypes.byref(desc.c), st.handle, _ptr(dev_segtab), _ptr(Q), _ptr(K), _ptr(V),
                                             _ptr(O), _ptr(dO), _ptr(saved), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ws),
                                             int(ws_bytes), _stream(stream)))
+
+
+def mux_dispatch_gather(st: SegTab, dev_segtab, task_ptrs: Sequence, ld_task: int, aligned, ld_aligned: int, width: int,
+                        elem_bytes: int, stream=None) -> None:
+    arr = _ptr_array(task_ptrs, len(task_ptrs))
+    _check(load_library().mux_dispatch_gather(st.handle, _ptr(dev_segtab), ctypes.cast(arr, POINTER(c_void_p)), int(ld_task),
+                                              _ptr(aligned), int(ld_aligned), int(width), int(elem_bytes), _stream(stream)))
+
+
+def mux_dispatch_scatter(st: SegTab, dev_segtab, aligned, ld_aligned: int, task_ptrs: Sequence, ld_task: int, width: int,
+                         elem_bytes: int, stream=None) -> None:
+    arr = _ptr_array(task_ptrs, len(task_ptrs))
+    _check(load_library().mux_dispatch_scatter(st.handle, _ptr(dev_segtab), _ptr(aligned), int(ld_aligned),
+                                               ctypes.cast(arr, POINTER(c_void_p)), int(ld_task), int(width),
+                                               int(elem_bytes), _stream(stream)))

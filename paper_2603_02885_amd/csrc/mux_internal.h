@@ -18,6 +18,7 @@ enum : int {
   DH_ATT_NBLK,           // attention work lists: number of 128-row blocks of sequences, then the word offsets of the
   DH_ATT_OFF_FWD,        // list ordered for the passes that walk the keys before a block (longest walk first) and of the
   DH_ATT_OFF_BWD,        // list ordered for the pass that walks the queries after a block; 4 words an entry (DA_*)
+  DH_OFF_ITEM_TOK0,      // per 64-row work item: how many tokens of its task lie on the rows before it
   DH_HDR_WORDS = 32
 };
 constexpr int kNumTileSizes = 4;

@@ -237,6 +237,15 @@ extern "C" mux_status mux_segtab_build(const mux_task_desc* tasks, int32_t n_tas
       for (int32_t i = 0; i < st->T; ++i)
         if (st->row_task[i] >= 0) dv[base + (i >> 5)] |= (int32_t)(1u << (i & 31));
     }
+    // Dispatch: the packed position of a task's token = the number of the task's tokens on the rows before it
+    {
+      dv[DH_OFF_ITEM_TOK0] = (int32_t)dv.size();
+      std::vector<int32_t> seen(n_tasks, 0);
+      for (const Item& it : st->items[0]) {
+        dv.push_back(it.task >= 0 ? seen[it.task] : 0);
+        if (it.task >= 0) seen[it.task] += it.nvalid;
+      }
+    }
     // attention work lists: every sequence cut into blocks of 128 tokens.  A block of queries walks the keys of its
     // sequence up to its own end, a block of keys the queries from its own start on: longest walk first in each list
     {
