@@ -38,6 +38,7 @@ struct AttnParams {
   int64_t ldq, ldk, ldv, ldo;
   int T, H;
   float scale;
+  int probe;
 };
 
 __device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t* p) {
@@ -68,6 +69,21 @@ __device__ __forceinline__ bf16x8 read_across(const bf16_t* tile, int row0, int 
 // token of accumulator element j for half-wave h inside a 32-token tile
 __device__ __forceinline__ int tok(int j, int half) { return 8 * (j >> 2) + 4 * half + (j & 3); }
 
+// Work item of a workgroup: (block of the list, head).  Workgroups go to the eight XCDs round-robin; with a multiple of
+// eight heads every XCD takes its own heads and walks the list in order, so that the blocks running on an XCD at one
+// time belong to two or three sequences of one head and find their keys and values in that XCD's L2.
+__device__ __forceinline__ void work_item(int n_blocks, int n_heads, int& block, int& head) {
+  const unsigned id = blockIdx.x;
+  if ((n_heads & 7) == 0) {
+    const unsigned j = id >> 3;
+    head = (int)(id & 7) + 8 * (int)(j / (unsigned)n_blocks);
+    block = (int)(j % (unsigned)n_blocks);
+  } else {
+    head = (int)(id / (unsigned)n_blocks);
+    block = (int)(id % (unsigned)n_blocks);
+  }
+}
+
 // 64 rows x 128 columns of one head from global memory (rows past `limit` read as zero) into registers, then LDS
 struct TileLoad {
   uint4 r[4];
@@ -88,9 +104,11 @@ struct TileLoad {
 __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
   __shared__ __align__(16) bf16_t sK[TILE * KP];
   __shared__ __align__(16) bf16_t sV[TILE * TP];
-  const int32_t* blk = p.dtab + p.dtab[DH_ATT_OFF_FWD] + blockIdx.x * DA_WORDS;
+  int wi_block, wi_head;
+  work_item(p.dtab[DH_ATT_NBLK], p.H, wi_block, wi_head);
+  const int32_t* blk = p.dtab + p.dtab[DH_ATT_OFF_FWD] + wi_block * DA_WORDS;
   const int first = blk[DA_FIRST_ROW], len = blk[DA_LEN], q0 = blk[DA_BLOCK0];
-  const int hc = blockIdx.y * D;
+  const int hc = wi_head * D;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, half = lane >> 5;
   const int ql = q0 + 32 * wave + li;          // this lane's query inside the sequence
   const bool qok = ql < len;
@@ -117,31 +135,49 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
     tk.store(sK, KP, tid);
     tv.store(sV, TP, tid);
     __syncthreads();
-    if (kb + TILE < kend) {
+    if (kb + TILE < kend && !(p.probe & 1)) {
       tk.load(p.K, p.ldk, first, kb + TILE, len, hc, tid);
       tv.load(p.V, p.ldv, first, kb + TILE, len, hc, tid);
     }
     if (kb > wq_last) continue;                 // no key of this tile is visible to this wave's queries
     f32x16 s[2];
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+    for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int j = 0; j < 16; ++j) s[kt][j] = 0.f;
+    {
+      // the eight K fragments of the first 32 keys are fetched up front; each is refilled for the second 32 keys as
+      // soon as its product is issued, so that an LDS read has seven products to land behind
+      const bf16_t* kp = sK + li * KP + 8 * half;
+      bf16x8 kf[8];
 #pragma unroll
-      for (int st = 0; st < 8; ++st)
-        s[kt] = mma(*(const bf16x8*)(sK + (32 * kt + li) * KP + 16 * st + 8 * half), qf[st], s[kt]);
+      for (int st = 0; st < 8; ++st) kf[st] = *(const bf16x8*)(kp + 16 * st);
+      __builtin_amdgcn_sched_barrier(0);        // (the scheduler would otherwise sink every read next to its use)
+#pragma unroll
+      for (int st = 0; st < 8; ++st) {
+        s[0] = mma(kf[st], qf[st], s[0]);
+        kf[st] = *(const bf16x8*)(kp + 32 * KP + 16 * st);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int st = 0; st < 8; ++st) s[1] = mma(kf[st], qf[st], s[1]);
     }
     const bool diag = kb + TILE - 1 > wq_first;
     // running maximum on the raw scores (the scale is positive), then one fused multiply-add per element: m is kept in
     // units of the raw score, exp2 arguments are s c - m c
     float mx = m;
+    if (diag) {                                 // only the tiles on the diagonal pay for the mask
+      const int rel = ql - kb - 4 * half;       // key 32 kt + 8 (j / 4) + j % 4 is hidden iff it exceeds rel
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+          if (32 * kt + 8 * (j >> 2) + (j & 3) > rel) s[kt][j] = -INFINITY;
+    }
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        if (diag && kb + 32 * kt + tok(j, half) > ql) s[kt][j] = -INFINITY;
-        mx = fmaxf(mx, s[kt][j]);
-      }
+      for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[kt][j]);
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     const float ms = mx == -INFINITY ? 0.f : mx;
     const float alpha = fast_exp2((m - ms) * c);
@@ -152,7 +188,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        const float e = fast_exp2(fmaf(s[kt][j], c, -msc));
+        const float e = (p.probe & 2) ? fmaf(s[kt][j], c, -msc) : fast_exp2(fmaf(s[kt][j], c, -msc));
         s[kt][j] = e;
         rs += e;
       }
@@ -185,7 +221,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
         v.y = pack_bf16x2(o[dt][4 * jg + 2] * inv, o[dt][4 * jg + 3] * inv);
         *(uint2*)(orow + 32 * dt + 8 * jg + 4 * half) = v;
       }
-    if (p.lse && half == 0) p.lse[(size_t)blockIdx.y * p.T + first + ql] = (m * c + log2f(l)) * LN2;
+    if (p.lse && half == 0) p.lse[(size_t)wi_head * p.T + first + ql] = (m * c + log2f(l)) * LN2;
   }
 }
 
@@ -235,9 +271,11 @@ __global__ __launch_bounds__(256) void k_attn_delta(AttnParams p) {
 __global__ __launch_bounds__(256, 2) void k_attn_bwd_q(AttnParams p) {
   __shared__ __align__(16) bf16_t sK[TILE * TP];
   __shared__ __align__(16) bf16_t sV[TILE * KP];
-  const int32_t* blk = p.dtab + p.dtab[DH_ATT_OFF_FWD] + blockIdx.x * DA_WORDS;
+  int wi_block, wi_head;
+  work_item(p.dtab[DH_ATT_NBLK], p.H, wi_block, wi_head);
+  const int32_t* blk = p.dtab + p.dtab[DH_ATT_OFF_FWD] + wi_block * DA_WORDS;
   const int first = blk[DA_FIRST_ROW], len = blk[DA_LEN], q0 = blk[DA_BLOCK0];
-  const int hc = blockIdx.y * D;
+  const int hc = wi_head * D;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, half = lane >> 5;
   const int ql = q0 + 32 * wave + li;
   const bool qok = ql < len;
@@ -252,8 +290,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_q(AttnParams p) {
     }
   }
   const float c = p.scale * LOG2E;
-  const float lse2 = qok ? p.lse[(size_t)blockIdx.y * p.T + first + ql] * LOG2E : 0.f;
-  const float dl = qok ? p.delta[(size_t)blockIdx.y * p.T + first + ql] : 0.f;
+  const float lse2 = qok ? p.lse[(size_t)wi_head * p.T + first + ql] * LOG2E : 0.f;
+  const float dl = qok ? p.delta[(size_t)wi_head * p.T + first + ql] : 0.f;
   f32x16 dq[4];
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
@@ -319,9 +357,11 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
   __shared__ __align__(16) bf16_t sD[TILE * TP];
   __shared__ __align__(16) bf16_t sVf[BLK * KP];   // the block's own V rows (B operand of dO V^T), kept here to save registers
   __shared__ float sLse[TILE], sDelta[TILE];
-  const int32_t* blk = p.dtab + p.dtab[DH_ATT_OFF_BWD] + blockIdx.x * DA_WORDS;
+  int wi_block, wi_head;
+  work_item(p.dtab[DH_ATT_NBLK], p.H, wi_block, wi_head);
+  const int32_t* blk = p.dtab + p.dtab[DH_ATT_OFF_BWD] + wi_block * DA_WORDS;
   const int first = blk[DA_FIRST_ROW], len = blk[DA_LEN], k0 = blk[DA_BLOCK0];
-  const int hc = blockIdx.y * D;
+  const int hc = wi_head * D;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, half = lane >> 5;
   const int kl = k0 + 32 * wave + li;          // this lane's key inside the sequence
   const bool kok = kl < len;
@@ -349,8 +389,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
   auto load_stats = [&](int qb) {
     if (tid < TILE) {
       const bool ok = qb + tid < len;
-      r_lse = ok ? p.lse[(size_t)blockIdx.y * p.T + first + qb + tid] * LOG2E : INFINITY;   // exp2(x - inf) = 0
-      r_delta = ok ? p.delta[(size_t)blockIdx.y * p.T + first + qb + tid] : 0.f;
+      r_lse = ok ? p.lse[(size_t)wi_head * p.T + first + qb + tid] * LOG2E : INFINITY;   // exp2(x - inf) = 0
+      r_delta = ok ? p.delta[(size_t)wi_head * p.T + first + qb + tid] : 0.f;
     }
   };
   tq.load(p.Q, p.ldq, first, k0, len, hc, tid);
@@ -430,7 +470,7 @@ mux_status check(const char* fn, const mux_attn_desc* d, const mux_segtab* st) {
     if (ld % 8) return fail(MUX_ERR_UNSUPPORTED, std::string(fn) + ": leading dimensions must be multiples of 8");
     if ((int64_t)st->T * ld >= ((int64_t)1 << 40)) return fail(MUX_ERR_SHAPE, std::string(fn) + ": problem too large");
   }
-  if (d->n_heads > 65535) return fail(MUX_ERR_SHAPE, std::string(fn) + ": too many heads");
+  if ((int64_t)st->n_attn_blocks * d->n_heads >= ((int64_t)1 << 31)) return fail(MUX_ERR_SHAPE, std::string(fn) + ": too many work items");
   if (!(d->scale >= 0.f)) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": negative scale");
   return MUX_OK;
 }
@@ -474,11 +514,12 @@ extern "C" mux_status mux_attn_forward(const mux_attn_desc* desc, const mux_segt
   p.ldq = desc->ldq; p.ldk = desc->ldk; p.ldv = desc->ldv; p.ldo = desc->ldo;
   p.T = st->T; p.H = desc->n_heads;
   p.scale = desc->scale > 0.f ? desc->scale : 1.f / sqrtf((float)D);
+  { const char* e = getenv("MUX_ATTN_PROBE"); p.probe = e ? atoi(e) : 0; }
   ZeroParams z{};
   z.dtab = p.dtab; z.out[0] = (bf16_t*)O; z.ld[0] = desc->ldo; z.n_out = 1; z.width = desc->n_heads * D;
   MUX_LAUNCH("attn_zero_pad", k_attn_zero_pad, dim3((unsigned)st->items[0].size()), dim3(256), 0, stream, z);
   if (st->n_attn_blocks > 0)
-    MUX_LAUNCH("attn_fwd", k_attn_fwd, dim3((unsigned)st->n_attn_blocks, (unsigned)desc->n_heads), dim3(256), 0, stream, p);
+    MUX_LAUNCH("attn_fwd", k_attn_fwd, dim3((unsigned)st->n_attn_blocks * (unsigned)desc->n_heads), dim3(256), 0, stream, p);
   return last_hip(fn);
 }
 
@@ -511,8 +552,8 @@ extern "C" mux_status mux_attn_backward(const mux_attn_desc* desc, const mux_seg
   const size_t n = (size_t)st->T * desc->n_heads;
   MUX_LAUNCH("attn_delta", k_attn_delta, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p);
   if (st->n_attn_blocks > 0) {
-    MUX_LAUNCH("attn_bwd_kv", k_attn_bwd_kv, dim3((unsigned)st->n_attn_blocks, (unsigned)desc->n_heads), dim3(256), 0, stream, p);
-    MUX_LAUNCH("attn_bwd_q", k_attn_bwd_q, dim3((unsigned)st->n_attn_blocks, (unsigned)desc->n_heads), dim3(256), 0, stream, p);
+    MUX_LAUNCH("attn_bwd_kv", k_attn_bwd_kv, dim3((unsigned)st->n_attn_blocks * (unsigned)desc->n_heads), dim3(256), 0, stream, p);
+    MUX_LAUNCH("attn_bwd_q", k_attn_bwd_q, dim3((unsigned)st->n_attn_blocks * (unsigned)desc->n_heads), dim3(256), 0, stream, p);
   }
   return last_hip(fn);
 }

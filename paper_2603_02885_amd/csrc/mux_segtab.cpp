@@ -247,20 +247,25 @@ extern "C" mux_status mux_segtab_build(const mux_task_desc* tasks, int32_t n_tas
       }
     }
     // attention work lists: every sequence cut into blocks of 128 tokens.  A block of queries walks the keys of its
-    // sequence up to its own end, a block of keys the queries from its own start on: longest walk first in each list
+    // sequence up to its own end, a block of keys the queries from its own start on.  Both lists keep the blocks of
+    // a sequence together (they share its keys and values in the L2), longest sequence first and inside a sequence
+    // the longest walk first, so that the last items of a launch are the short ones.
     {
       struct Blk { int32_t first_row, len, b0; };
-      std::vector<Blk> blks;
-      for (const Seq& sq : seqs)
-        for (int32_t b0 = 0; b0 < sq.len; b0 += kAttnBlockRows) blks.push_back({sq.first_row, sq.len, b0});
-      st->n_attn_blocks = (int32_t)blks.size();
+      std::vector<Seq> order(seqs.begin(), seqs.end());
+      std::stable_sort(order.begin(), order.end(), [](const Seq& a, const Seq& b) { return a.len > b.len; });
+      std::vector<Blk> fwd, bwd;
+      for (const Seq& sq : order) {
+        const int32_t nb = (sq.len + kAttnBlockRows - 1) / kAttnBlockRows;
+        for (int32_t b = nb - 1; b >= 0; --b) fwd.push_back({sq.first_row, sq.len, b * kAttnBlockRows});
+        for (int32_t b = 0; b < nb; ++b) bwd.push_back({sq.first_row, sq.len, b * kAttnBlockRows});
+      }
+      st->n_attn_blocks = (int32_t)fwd.size();
       dv[DH_ATT_NBLK] = st->n_attn_blocks;
-      std::stable_sort(blks.begin(), blks.end(), [](const Blk& a, const Blk& b) { return a.b0 > b.b0; });
       dv[DH_ATT_OFF_FWD] = (int32_t)dv.size();
-      for (const Blk& b : blks) { const int32_t w[DA_WORDS] = {b.first_row, b.len, b.b0, 0}; dv.insert(dv.end(), w, w + DA_WORDS); }
-      std::stable_sort(blks.begin(), blks.end(), [](const Blk& a, const Blk& b) { return a.len - a.b0 > b.len - b.b0; });
+      for (const Blk& b : fwd) { const int32_t w[DA_WORDS] = {b.first_row, b.len, b.b0, 0}; dv.insert(dv.end(), w, w + DA_WORDS); }
       dv[DH_ATT_OFF_BWD] = (int32_t)dv.size();
-      for (const Blk& b : blks) { const int32_t w[DA_WORDS] = {b.first_row, b.len, b.b0, 0}; dv.insert(dv.end(), w, w + DA_WORDS); }
+      for (const Blk& b : bwd) { const int32_t w[DA_WORDS] = {b.first_row, b.len, b.b0, 0}; dv.insert(dv.end(), w, w + DA_WORDS); }
     }
     while (dv.size() % 64) dv.push_back(0);
     dv[DH_WORDS] = (int32_t)dv.size();
