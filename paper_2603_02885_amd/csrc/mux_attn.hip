@@ -290,7 +290,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_q(AttnParams p) {
     }
   }
   const float c = p.scale * LOG2E;
-  const float lse2 = qok ? p.lse[(size_t)wi_head * p.T + first + ql] * LOG2E : 0.f;
+  const float lse2 = qok ? p.lse[(size_t)wi_head * p.T + first + ql] * LOG2E : INFINITY;    // exp2(x - inf) = 0
   const float dl = qok ? p.delta[(size_t)wi_head * p.T + first + ql] : 0.f;
   f32x16 dq[4];
 #pragma unroll
@@ -324,11 +324,15 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_q(AttnParams p) {
         dp = mma(*(const bf16x8*)(sV + (32 * kt + li) * KP + 16 * st + 8 * half), df[st], dp);
       }
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        float pr = fast_exp2(s[j] * c - lse2);
-        if (!qok || (diag && kb + 32 * kt + tok(j, half) > ql)) pr = 0.f;
-        s[j] = pr * (dp[j] - dl);          // dS^T
+      for (int j = 0; j < 16; ++j) s[j] = fast_exp2(fmaf(s[j], c, -lse2));        // P^T (zero for a lane without query)
+      if (diag) {                               // only the tiles on the diagonal pay for the mask
+        const int rel = ql - kb - 32 * kt - 4 * half;
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+          if (8 * (j >> 2) + (j & 3) > rel) s[j] = 0.f;
       }
+#pragma unroll
+      for (int j = 0; j < 16; ++j) s[j] *= dp[j] - dl;                           // dS^T
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const bf16x8 ds = pack8(s, u);
@@ -420,14 +424,17 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
         dp = mma(*(const bf16x8*)(sD + (32 * qt + li) * TP + 16 * st + 8 * half), *(const bf16x8*)(vfrag + 16 * st), dp);
         if (st % 2 == 1) __builtin_amdgcn_sched_barrier(0);
       }
+      // P (a lane without key computes on zeros and is not stored)
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const int qi = 32 * qt + tok(j, half);
-        float pr = fast_exp2(s[j] * c - sLse[qi]);
-        if (!kok || (diag && qb + qi < kl)) pr = 0.f;
-        s[j] = pr;                            // P
-        dp[j] = pr * (dp[j] - sDelta[qi]);    // dS
+      for (int j = 0; j < 16; ++j) s[j] = fast_exp2(fmaf(s[j], c, -sLse[32 * qt + tok(j, half)]));
+      if (diag) {                               // only the tiles on the diagonal pay for the mask
+        const int rel = kl - qb - 32 * qt - 4 * half;      // query 8 (j / 4) + j % 4 sees the key iff it is >= rel
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+          if (8 * (j >> 2) + (j & 3) < rel) s[j] = 0.f;
       }
+#pragma unroll
+      for (int j = 0; j < 16; ++j) dp[j] = s[j] * (dp[j] - sDelta[32 * qt + tok(j, half)]);   // dS
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const bf16x8 pb = pack8(s, u), ds = pack8(dp, u);
