@@ -38,7 +38,6 @@ struct AttnParams {
   int64_t ldq, ldk, ldv, ldo;
   int T, H;
   float scale;
-  int probe;
 };
 
 __device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t* p) {
@@ -123,8 +122,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
     for (int j = 0; j < 16; ++j) o[dt][j] = 0.f;
-  float m = -INFINITY, l = 0.f;
+  float m = -INFINITY, m_prev = -INFINITY, l = 0.f;
   const float c = p.scale * LOG2E;
+  const float lazy = 8.f / c;                   // 8 in the exponent, in units of the raw score
   const int kend = min(len, q0 + BLK);          // keys [0, kend) are visible to some query of the block
   const int wq_first = q0 + 32 * wave, wq_last = wq_first + 31;
   TileLoad tk, tv;
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
     tk.store(sK, KP, tid);
     tv.store(sV, TP, tid);
     __syncthreads();
-    if (kb + TILE < kend && !(p.probe & 1)) {
+    if (kb + TILE < kend) {
       tk.load(p.K, p.ldk, first, kb + TILE, len, hc, tid);
       tv.load(p.V, p.ldv, first, kb + TILE, len, hc, tid);
     }
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
     const bool diag = kb + TILE - 1 > wq_first;
     // running maximum on the raw scores (the scale is positive), then one fused multiply-add per element: m is kept in
     // units of the raw score, exp2 arguments are s c - m c
-    float mx = m;
+    float mx = -INFINITY;
     if (diag) {                                 // only the tiles on the diagonal pay for the mask
       const int rel = ql - kb - 4 * half;       // key 32 kt + 8 (j / 4) + j % 4 is hidden iff it exceeds rel
 #pragma unroll
@@ -179,16 +179,20 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
 #pragma unroll
       for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[kt][j]);
     mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float ms = mx == -INFINITY ? 0.f : mx;
-    const float alpha = fast_exp2((m - ms) * c);
-    m = mx;
+    // The reference point of the exponentials follows the running maximum lazily: it moves only when the maximum
+    // has grown by more than 8 in the exponent (probabilities then stay below 2^8, harmless in fp32 and bf16, and
+    // the final division by the row sum cancels the choice), so the rescaling of the output is rare.
+    if (!(mx <= m + lazy)) m = mx;              // also the first tile (m = -inf) and never for mx = -inf
+    const float ms = m == -INFINITY ? 0.f : m;
+    const float alpha = fast_exp2((m_prev - ms) * c);
+    m_prev = m;
     const float msc = ms * c;
     float rs = 0.f;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        const float e = (p.probe & 2) ? fmaf(s[kt][j], c, -msc) : fast_exp2(fmaf(s[kt][j], c, -msc));
+        const float e = fast_exp2(fmaf(s[kt][j], c, -msc));
         s[kt][j] = e;
         rs += e;
       }
@@ -521,7 +525,6 @@ extern "C" mux_status mux_attn_forward(const mux_attn_desc* desc, const mux_segt
   p.ldq = desc->ldq; p.ldk = desc->ldk; p.ldv = desc->ldv; p.ldo = desc->ldo;
   p.T = st->T; p.H = desc->n_heads;
   p.scale = desc->scale > 0.f ? desc->scale : 1.f / sqrtf((float)D);
-  { const char* e = getenv("MUX_ATTN_PROBE"); p.probe = e ? atoi(e) : 0; }
   ZeroParams z{};
   z.dtab = p.dtab; z.out[0] = (bf16_t*)O; z.ld[0] = desc->ldo; z.n_out = 1; z.width = desc->n_heads * D;
   MUX_LAUNCH("attn_zero_pad", k_attn_zero_pad, dim3((unsigned)st->items[0].size()), dim3(256), 0, stream, z);
