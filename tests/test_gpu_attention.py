@@ -111,6 +111,13 @@ def test_long_sequences_span_chunks(env):
     run(env, [[1000, 24]], chunk=256, H=2, seed=4, max_pack_len=1024)
 
 
+def test_long_sequence_many_blocks(env):
+    """Sequences of 2048 tokens and more (16 and more blocks, 32 and more key tiles) beside short ones, ragged ends
+    included."""
+    run(env, [[2100], [300, 260], [1]], chunk=128, H=2, seed=8, check_repeat=True)
+    run(env, [[2048, 255, 257]], chunk=256, H=1, seed=9)
+
+
 def test_fused_qkv_buffer_and_large_scores(env):
     """Q, K, V as slices of one buffer (leading dimension 3 H d), and scores far from zero (softmax close to one-hot)."""
     run(env, [[150, 90], [257]], chunk=64, H=2, seed=5, fused=True)
