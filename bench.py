@@ -3,8 +3,10 @@
 synthetic multi-tenant workload, on ONE MI355X.
 
 One "step" = forward + backward of all layer calls of the workload (7 projections of a
-LLaMA-shaped block), inputs resident in HBM.  Prints one JSON line (see the design doc for the
-definition of every field).  `--gpus N` with N > 1 is refused: this build is single-GPU.
+LLaMA-shaped block), inputs resident in HBM.  Prints one JSON line: value = valid tokens per second of the whole
+step; roofline = the slower backbone GEMM kernel against the bf16 matrix-core peak, its duration from HIP events on
+the launch stream; kernels = every kernel of the step; cpu_baseline = the fp64 oracle on a bounded sample.
+`--gpus N` with N > 1 is refused: this build is single-GPU.
 """
 from __future__ import annotations
 
@@ -442,7 +444,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print(f"bench.py: this build runs on exactly one GPU (got --gpus {args.gpus}); "
-              "the layer has no multi-GPU path, see DESIGN.md", file=sys.stderr)
+              "the layer has no multi-GPU path", file=sys.stderr)
         sys.exit(2)
     import torch
     import mux_workloads as wlm
