@@ -53,6 +53,9 @@ def parse():
     ap.add_argument("--attention", action="store_true",
                     help="instead of the benchmark line: the attention step between the q/k/v and o projections on the "
                          "sequences of the chosen workload (heads of 128, as many as the q projection is wide)")
+    ap.add_argument("--dispatch", action="store_true",
+                    help="instead of the benchmark line: Dispatch of the chosen workload's tokens (packed per task <-> "
+                         "aligned batch) at the width of the first projection's input, in GB/s")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 512 MiB device copy (known traffic) for scaling rocprofv3 byte counters")
     return ap.parse_args()
@@ -408,6 +411,50 @@ def attention(mx, torch, args):
             "kernels": kernels}
 
 
+def dispatch(mx, torch, args):
+    """Gather of every task's packed tokens onto the aligned batch and scatter back (section 3.2, Dispatch), bf16 rows
+    of the first projection's input width.  Algorithmic bytes of one pass: every valid token read once and written once
+    (plus the zero rows of the padding for the gather)."""
+    import mux_workloads as wlm
+    wl = wlm.config(args.workload, seed=args.seed)
+    dev = "cuda:0"
+    width = wl.layers[0][1]
+    st = mx.mux_segtab_build([mx.TaskDesc(t.kind, t.rank, t.scale, t.seq_lens) for t in wl.tasks], wl.chunk,
+                             wl.max_pack_len, 0)
+    T = mx.mux_segtab_rows(st)
+    valid = mx.mux_segtab_valid_tokens(st)
+    nb = mx.mux_segtab_device_bytes(st)
+    dtab = torch.zeros(nb, dtype=torch.uint8, device=dev)
+    mx.mux_segtab_upload(st, dtab, nb)
+    packed = [torch.randn((max(t.tokens, 1), width), device=dev, dtype=torch.float32).to(torch.bfloat16) for t in wl.tasks]
+    ptrs = [p if t.tokens else None for p, t in zip(packed, wl.tasks)]
+    back = [torch.empty_like(p) for p in packed]
+    bptrs = [p if t.tokens else None for p, t in zip(back, wl.tasks)]
+    aligned = torch.empty((T, width), device=dev, dtype=torch.bfloat16)
+    stream = torch.cuda.current_stream()
+    res = {}
+    for name, fn in (("dispatch_gather", lambda: mx.mux_dispatch_gather(st, dtab, ptrs, width, aligned, width, width, 2, stream)),
+                     ("dispatch_scatter", lambda: mx.mux_dispatch_scatter(st, dtab, aligned, width, bptrs, width, width, 2, stream))):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        mx.mux_profile_enable(1)
+        mx.mux_profile_collect()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        prof = mx.mux_profile_collect()
+        mx.mux_profile_enable(0)
+        us = sum(e["total_ms"] for e in prof) * 1e3 / args.steps
+        nbytes = 2.0 * valid * width * 2 + (2.0 * (T - valid) * width if name == "dispatch_gather" else 0.0)
+        res[name] = {"avg_us": us, "gbps": nbytes / (us * 1e-6) / 1e9, "frac_of_hbm_peak": nbytes / (us * 1e-6) / 1e9 / PEAK_HBM}
+    ok = all(torch.equal(a[:t.tokens], b[:t.tokens]) for a, b, t in zip(packed, back, wl.tasks))
+    return {"metric": "Dispatch packed <-> aligned", "unit": "GB/s", "steps": args.steps, "warmup": args.warmup,
+            "dtype": "bf16", "data": "synthetic", "round_trip_bit_exact": bool(ok),
+            "config": {"workload": f"configs[{args.workload}] {wl.name}", "rows": T, "valid_tokens": valid, "width": width},
+            "kernels": res}
+
+
 def cpu_baseline(wl, seconds, seed):
     """The fp64 oracle, as it stands, on a bounded sample: the first m tokens of every task through
     every projection (fwd+bwd), m sized from a short calibration so that the run takes about `seconds`."""
@@ -460,6 +507,9 @@ def main():
         return
     if args.attention:
         print(json.dumps(attention(mx, torch, args)))
+        return
+    if args.dispatch:
+        print(json.dumps(dispatch(mx, torch, args)))
         return
     wl = wlm.config(args.workload, seed=args.seed)
     st, dtab, T, layers, ws, ws_bytes = setup(mx, torch, wl, args.seed)

@@ -20,7 +20,7 @@ struct DispatchParams {
   int to_aligned;                                // 1: gather (packed -> aligned, padding zeroed), 0: scatter
 };
 
-// grid = 64-row items, four waves: wave w moves the rows w, w + 4, ..; a lane moves every 64th vector of a row.
+// grid = (64-row items, slabs of 256 vectors across the width), four waves: wave w moves the rows w, w + 4, ...
 // `first` launch of a gather also zeroes the rows of no task and the padding rows of every task.
 template <class V>
 __global__ __launch_bounds__(256) void k_dispatch(DispatchParams p, int first) {
@@ -35,7 +35,9 @@ __global__ __launch_bounds__(256) void k_dispatch(DispatchParams p, int first) {
     if (it.nrows < 64) valid &= ((uint64_t)1 << it.nrows) - 1;
   }
   char* packed = mine ? p.task[it.task - p.task_base] : nullptr;
+  // a workgroup moves a slab of 4 x 64 vectors of every row of its item; four vectors per lane are in flight
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int slab = (int)blockIdx.y * 256 * (int)sizeof(V) + lane * (int)sizeof(V);
   for (int r = wave; r < it.nrows; r += 4) {
     char* arow = p.aligned + (size_t)(it.row0 + r) * p.row_bytes_aligned;
     if ((valid >> r) & 1) {
@@ -44,10 +46,24 @@ __global__ __launch_bounds__(256) void k_dispatch(DispatchParams p, int first) {
       char* prow = packed + (size_t)tok * p.row_bytes_task;
       char* dst = p.to_aligned ? arow : prow;
       const char* src = p.to_aligned ? prow : arow;
-      for (int o = lane * (int)sizeof(V); o < p.width_bytes; o += 64 * (int)sizeof(V)) *(V*)(dst + o) = *(const V*)(src + o);
+      V v[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int o = slab + k * 64 * (int)sizeof(V);
+        if (o < p.width_bytes) v[k] = *(const V*)(src + o);
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int o = slab + k * 64 * (int)sizeof(V);
+        if (o < p.width_bytes) *(V*)(dst + o) = v[k];
+      }
     } else if (p.to_aligned && first) {
       V z{};
-      for (int o = lane * (int)sizeof(V); o < p.width_bytes; o += 64 * (int)sizeof(V)) *(V*)(arow + o) = z;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int o = slab + k * 64 * (int)sizeof(V);
+        if (o < p.width_bytes) *(V*)(arow + o) = z;
+      }
     }
   }
 }
@@ -81,9 +97,10 @@ mux_status run(const char* fn, const mux_segtab* st, const void* dev_segtab, voi
     p.width_bytes = width * elem_bytes;
     p.to_aligned = to_aligned;
     const char* name = to_aligned ? "dispatch_gather" : "dispatch_scatter";
-    if (vec) MUX_LAUNCH(name, k_dispatch<uint4>, dim3(n_items), dim3(256), 0, stream, p, first ? 1 : 0);
-    else if (elem_bytes == 4) MUX_LAUNCH(name, k_dispatch<uint32_t>, dim3(n_items), dim3(256), 0, stream, p, first ? 1 : 0);
-    else MUX_LAUNCH(name, k_dispatch<uint16_t>, dim3(n_items), dim3(256), 0, stream, p, first ? 1 : 0);
+    const unsigned wb = (unsigned)p.width_bytes;
+    if (vec) MUX_LAUNCH(name, k_dispatch<uint4>, dim3(n_items, (wb + 4095) / 4096), dim3(256), 0, stream, p, first ? 1 : 0);
+    else if (elem_bytes == 4) MUX_LAUNCH(name, k_dispatch<uint32_t>, dim3(n_items, (wb + 1023) / 1024), dim3(256), 0, stream, p, first ? 1 : 0);
+    else MUX_LAUNCH(name, k_dispatch<uint16_t>, dim3(n_items, (wb + 511) / 512), dim3(256), 0, stream, p, first ? 1 : 0);
     first = false;
   }
   hipError_t e = hipGetLastError();
