@@ -229,7 +229,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
   }
 }
 
-// Rows that belong to no sequence: zero in `n_out` outputs.  grid = 64-row items.
+// Rows that belong to no sequence: zero in `n_out` outputs.  grid = (64-row items, slabs of 2048 elements).
 struct ZeroParams {
   const int32_t* dtab;
   bf16_t* out[3];
@@ -239,11 +239,16 @@ struct ZeroParams {
 __global__ __launch_bounds__(256) void k_attn_zero_pad(ZeroParams p) {
   const ItemView it = load_item(p.dtab, 0, blockIdx.x);
   if (it.task >= 0 && it.nvalid == it.nrows) return;
-  for (int r = 0; r < it.nrows; ++r) {
+  // wave w takes the rows w, w + 4, ..; the workgroup covers a slab of 256 vectors (4 KB) of the row width
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int slab = (int)blockIdx.y * 256 + lane;
+  for (int r = wave; r < it.nrows; r += 4) {
     if (it.task >= 0 && row_is_valid(p.dtab, it.row0 + r)) continue;
     for (int o = 0; o < p.n_out; ++o) {
       uint4* dst = (uint4*)(p.out[o] + (size_t)(it.row0 + r) * p.ld[o]);
-      for (int c = threadIdx.x; c < p.width / 8; c += 256) dst[c] = uint4{0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        if (slab + 64 * k < p.width / 8) dst[slab + 64 * k] = uint4{0u, 0u, 0u, 0u};
     }
   }
 }
@@ -527,7 +532,7 @@ extern "C" mux_status mux_attn_forward(const mux_attn_desc* desc, const mux_segt
   p.scale = desc->scale > 0.f ? desc->scale : 1.f / sqrtf((float)D);
   ZeroParams z{};
   z.dtab = p.dtab; z.out[0] = (bf16_t*)O; z.ld[0] = desc->ldo; z.n_out = 1; z.width = desc->n_heads * D;
-  MUX_LAUNCH("attn_zero_pad", k_attn_zero_pad, dim3((unsigned)st->items[0].size()), dim3(256), 0, stream, z);
+  MUX_LAUNCH("attn_zero_pad", k_attn_zero_pad, dim3((unsigned)st->items[0].size(), (unsigned)((z.width + 2047) / 2048)), dim3(256), 0, stream, z);
   if (st->n_attn_blocks > 0)
     MUX_LAUNCH("attn_fwd", k_attn_fwd, dim3((unsigned)st->n_attn_blocks * (unsigned)desc->n_heads), dim3(256), 0, stream, p);
   return last_hip(fn);
@@ -558,7 +563,7 @@ extern "C" mux_status mux_attn_backward(const mux_attn_desc* desc, const mux_seg
   ZeroParams z{};
   z.dtab = p.dtab; z.n_out = 3; z.width = desc->n_heads * D;
   z.out[0] = p.dQ; z.ld[0] = desc->ldq; z.out[1] = p.dK; z.ld[1] = desc->ldk; z.out[2] = p.dV; z.ld[2] = desc->ldv;
-  MUX_LAUNCH("attn_zero_pad", k_attn_zero_pad, dim3((unsigned)st->items[0].size()), dim3(256), 0, stream, z);
+  MUX_LAUNCH("attn_zero_pad", k_attn_zero_pad, dim3((unsigned)st->items[0].size(), (unsigned)((z.width + 2047) / 2048)), dim3(256), 0, stream, z);
   const size_t n = (size_t)st->T * desc->n_heads;
   MUX_LAUNCH("attn_delta", k_attn_delta, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p);
   if (st->n_attn_blocks > 0) {
