@@ -145,3 +145,59 @@ def test_argument_checks(env):
         mx.mux_attn_forward(mx.AttnDesc(2, 128, 256, 256, 256, 256, n_kv_heads=1), st, dtab, x, x, x, x, None)
     with pytest.raises(mx.MuxError):
         mx.mux_attn_forward(mx.AttnDesc(2, 128, 256, 256, 256, 256), st, dtab, x, None, x, x, None)   # null K
+
+
+def test_graph_capture_of_dispatch_and_attention(env):
+    """Dispatch and the attention step allocate nothing and never synchronise: gather -> attention forward -> backward ->
+    scatter captured into one HIP graph replays bit for bit, with eager work and synchronisations between the replays."""
+    mx, torch = env
+    d, H = 128, 2
+    lens = [[150, 90], [257], [33]]
+    st = mx.mux_segtab_build([mx.TaskDesc(mx.MUX_ADAPTER_NONE, 0, 1.0, l) for l in lens], 64, 0, 0)
+    T = mx.mux_segtab_rows(st)
+    dev = "cuda:0"
+    nb = mx.mux_segtab_device_bytes(st)
+    dtab = torch.zeros(nb, dtype=torch.uint8, device=dev)
+    mx.mux_segtab_upload(st, dtab, nb)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    W = 3 * H * d
+    packed = [torch.randn((sum(l), W), device=dev, generator=gen).to(torch.bfloat16) for l in lens]     # packed q|k|v rows
+    qkv = torch.empty((T, W), dtype=torch.bfloat16, device=dev)
+    dqkv = torch.empty_like(qkv)
+    O = torch.empty((T, H * d), dtype=torch.bfloat16, device=dev)
+    dO = torch.randn((T, H * d), device=dev, generator=gen).to(torch.bfloat16)
+    outs = [torch.empty((sum(l), W), dtype=torch.bfloat16, device=dev) for l in lens]
+    desc = mx.AttnDesc(H, d, W, W, W, H * d)
+    saved = torch.zeros(max(mx.mux_attn_saved_bytes(desc, st), 256), dtype=torch.uint8, device=dev)
+    wsb = mx.mux_attn_workspace_bytes(desc, st)
+    ws = torch.zeros(max(wsb, 256), dtype=torch.uint8, device=dev)
+    Q, K, V = qkv[:, :H * d], qkv[:, H * d:2 * H * d], qkv[:, 2 * H * d:]
+    dQ, dK, dV = dqkv[:, :H * d], dqkv[:, H * d:2 * H * d], dqkv[:, 2 * H * d:]
+
+    def chain(stream):
+        mx.mux_dispatch_gather(st, dtab, packed, W, qkv, W, W, 2, stream)
+        mx.mux_attn_forward(desc, st, dtab, Q, K, V, O, saved, stream)
+        mx.mux_attn_backward(desc, st, dtab, Q, K, V, O, dO, saved, dQ, dK, dV, ws, wsb, stream)
+        mx.mux_dispatch_scatter(st, dtab, dqkv, W, outs, W, W, 2, stream)
+
+    chain(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    keep = [t.clone() for t in outs] + [O.clone()]
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            chain(stream)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in outs + [O, qkv, dqkv]:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(keep, outs + [O]):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"replay {rep}"
+        chain(torch.cuda.current_stream())               # eager work between the replays
+        torch.cuda.synchronize()
