@@ -1,7 +1,7 @@
 """Full-size GPU parity: the benchmark workloads at their real shapes, in the launch configuration
 bench.py times, compared with the fp64 oracle on sampled output columns (all rows x 48 seeded
 columns of Y and of dX; Hs/Gs enter through them; every task's dA_t, dB_t, d delta_t in full, dl_t on
-the sampled columns)."""
+the sampled columns).  Likewise the attention step on the benchmark sequences with all heads, three heads compared."""
 import numpy as np
 import pytest
 
@@ -48,3 +48,58 @@ def test_benchmark_config_layer(env, cfg, layer):
     print({k: float(f"{v:.2e}") for k, v in list(errs.items())[:6]}, flush=True)
     del g
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("cfg", [1, 3])
+def test_attention_benchmark_sequences(env, cfg):
+    """The attention step on the sequences of a benchmark workload with all its heads, as `bench.py --attention` runs
+    it (fused QKV buffer), compared with the attention oracle on three sampled heads."""
+    mx, torch = env
+    from oracle import attention as oatt
+    from oracle import segtab
+    wl = wlm.config(cfg)
+    d = 128
+    H = wl.layers[0][2] // d
+    ot = segtab.build([t.seq_lens for t in wl.tasks], wl.chunk)
+    seqs = [(s[2], s[3]) for s in segtab.sequences(ot)]
+    T = ot.T
+    print(f"attention config {cfg}: T={T} H={H} longest={max(n for _, n in seqs)}", flush=True)
+    dev = "cuda:0"
+    st = mx.mux_segtab_build([mx.TaskDesc(t.kind, t.rank, t.scale, t.seq_lens) for t in wl.tasks], wl.chunk, 0, 0)
+    nb = mx.mux_segtab_device_bytes(st)
+    dtab = torch.zeros(nb, dtype=torch.uint8, device=dev)
+    mx.mux_segtab_upload(st, dtab, nb)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(100 + cfg)
+    W = 3 * H * d
+    qkv = torch.randn((T, W), device=dev, generator=gen).to(torch.bfloat16)
+    dO = torch.randn((T, H * d), device=dev, generator=gen).to(torch.bfloat16)
+    pad = torch.from_numpy(ot.row_task < 0).to(dev)
+    qkv[pad] = float("nan")
+    dO[pad] = float("nan")
+    dqkv = torch.full_like(qkv, float("nan"))
+    O = torch.full((T, H * d), float("nan"), dtype=torch.bfloat16, device=dev)
+    desc = mx.AttnDesc(H, d, W, W, W, H * d)
+    saved = torch.zeros(max(mx.mux_attn_saved_bytes(desc, st), 256), dtype=torch.uint8, device=dev)
+    wsb = mx.mux_attn_workspace_bytes(desc, st)
+    ws = torch.zeros(max(wsb, 256), dtype=torch.uint8, device=dev)
+    Q, K, V = qkv[:, :H * d], qkv[:, H * d:2 * H * d], qkv[:, 2 * H * d:]
+    dQ, dK, dV = dqkv[:, :H * d], dqkv[:, H * d:2 * H * d], dqkv[:, 2 * H * d:]
+    stream = torch.cuda.current_stream()
+    mx.mux_attn_forward(desc, st, dtab, Q, K, V, O, saved, stream)
+    mx.mux_attn_backward(desc, st, dtab, Q, K, V, O, dO, saved, dQ, dK, dV, ws, wsb, stream)
+    torch.cuda.synchronize()
+    f = lambda t: t.float().cpu().numpy().astype(np.float64)
+    padn = ot.row_task < 0
+    for h in (0, H // 2 - 1, H - 1):
+        c = slice(h * d, (h + 1) * d)
+        q, k, v, do = f(Q[:, c]), f(K[:, c]), f(V[:, c]), f(dO[:, c])
+        ref = oatt.forward(q, k, v, seqs, 1)
+        ref.update(oatt.backward(q, k, v, do, seqs, 1))
+        got = {"O": f(O[:, c]), "dQ": f(dQ[:, c]), "dK": f(dK[:, c]), "dV": f(dV[:, c])}
+        errs = {}
+        for name in got:
+            assert np.all(got[name][padn] == 0), name
+            errs[name] = hz.norm_err(got[name], ref[name])
+        print(f"head {h}:", {k_: float(f"{v_:.2e}") for k_, v_ in errs.items()}, flush=True)
+        assert all(v_ <= hz.TOL_BF16 for v_ in errs.values()), errs
