@@ -31,7 +31,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=1,
                     help="index into BASELINE.json configs (default 1: LLaMA-7B shapes); 5 / 6 = those shapes with two "
-                         "Adapter-Tuning / Diff-Pruning tasks")
+                         "Adapter-Tuning / Diff-Pruning tasks; 7 / 8 = the paper's Table 2 mixes A / B")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -629,6 +629,7 @@ def main():
         "tflops": (flops_backbone + flops_adapter) / (ms_per_step * 1e-3) / 1e12,
         "frac_of_bf16_mfma_peak": (flops_backbone + flops_adapter) / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA,
         "padded_rows_per_s": T / (ms_per_step * 1e-3),
+        "valid_row_fraction": valid / max(T, 1),          # FLOP figures count every row of the aligned batch
         "roofline": roofline,
         "kernels": kernels,
     }

@@ -174,6 +174,12 @@ def config(idx: int, seed: int = 0) -> Workload:
         return Workload(
             name="llama7b_diff", layers=_llama_layers(4096, 11008), chunk=512, tasks=tasks,
             notes="2 LoRA r16 + 2 Diff-Pruning (0.5 % of W) tasks, 5120 tokens, chunk 512")
+    if idx in (7, 8):
+        # not benchmark configs: the small-batch regime of the paper's own workload mixes (Table 2: eight tasks of 2-8
+        # sequences padded to 64, 128 or 256 tokens), all seven LLaMA-7B projections, LoRA rank 16
+        w = table2_workload("A" if idx == 7 else "B", 64 if idx == 7 else 128)
+        return Workload(name=w.name, layers=_llama_layers(4096, 11008), chunk=w.chunk, tasks=w.tasks,
+                        notes=f"Table 2 mix {'A' if idx == 7 else 'B'}: 8 LoRA r16 tasks, {sum(t.tokens for t in w.tasks)} tokens, chunk {w.chunk}")
     raise ValueError(f"no config {idx}")
 
 
