@@ -96,6 +96,33 @@ def check_pins(att):
             ref[si] = out[first:first + n]
 
 
+def check_gqa(att):
+    """Grouped-query heads: the same as ordinary heads on keys and values repeated for every query head of a group,
+    with the key/value gradients of the copies added up."""
+    rng = np.random.default_rng(21)
+    H, Hkv, d = 4, 2, 3
+    seqs = [(0, 5), (6, 3)]
+    T = 10
+    Q, dO = rng.standard_normal((T, H * d)), rng.standard_normal((T, H * d))
+    K, V = rng.standard_normal((T, Hkv * d)), rng.standard_normal((T, Hkv * d))
+    rep = lambda a: np.concatenate([a[:, (h // 2) * d:(h // 2 + 1) * d] for h in range(H)], axis=1)
+    f = att.forward(Q, K, V, seqs, H, n_kv_heads=Hkv)
+    fr = att.forward(Q, rep(K), rep(V), seqs, H)
+    assert np.array_equal(f["O"], fr["O"]) and np.array_equal(f["lse"], fr["lse"])
+    b = att.backward(Q, K, V, dO, seqs, H, n_kv_heads=Hkv)
+    br = att.backward(Q, rep(K), rep(V), dO, seqs, H)
+    assert np.array_equal(b["dQ"], br["dQ"])
+    fold = lambda a: np.concatenate([a[:, (2 * g) * d:(2 * g + 1) * d] + a[:, (2 * g + 1) * d:(2 * g + 2) * d] for g in range(Hkv)], axis=1)
+    assert np.allclose(b["dK"], fold(br["dK"]), rtol=1e-13, atol=1e-13) and np.allclose(b["dV"], fold(br["dV"]), rtol=1e-13, atol=1e-13)
+    assert not np.allclose(b["dK"][:, :d], br["dK"][:, :d])          # really a sum over the group
+    bm = att.backward(Q, rep(K), rep(V), dO, seqs, H, n_kv_heads=H)
+    assert all(np.array_equal(bm[k], br[k]) for k in br)             # Hkv = H is the ordinary case
+
+
+def test_attention_oracle_gqa():
+    check_gqa(attention)
+
+
 def test_attention_oracle_pins():
     check_pins(attention)
 
@@ -106,11 +133,13 @@ MUTATIONS = [
     ("np.tril(np.ones((n, n), dtype=bool))", "np.ones((n, n), dtype=bool)"),                 # not causal
     ("lse[h, r] = l", "lse[h, r] = l - np.log(n)"),
     ("ds = p * (dp - (dp * p).sum(axis=1, keepdims=True))", "ds = p * dp"),                  # softmax slope without its sum term
-    ("dQ[r, c] = scale * (ds @ K[r, c])", "dQ[r, c] = (ds @ K[r, c])"),
-    ("dK[r, c] = scale * (ds.T @ Q[r, c])", "dK[r, c] = scale * (ds @ Q[r, c])"),            # transposed operand
-    ("dV[r, c] = p.T @ dO[r, c]", "dV[r, c] = p @ dO[r, c]"),
-    ("dp = dO[r, c] @ V[r, c].T", "dp = dO[r, c] @ K[r, c].T"),
-    ("O[r, c] = p @ V[r, c]", "O[r, c] = p @ K[r, c]"),
+    ("dQ[r, c] = scale * (ds @ K[r, ck])", "dQ[r, c] = (ds @ K[r, ck])"),
+    ("dK[r, ck] += scale * (ds.T @ Q[r, c])", "dK[r, ck] += scale * (ds @ Q[r, c])"),            # transposed operand
+    ("dV[r, ck] += p.T @ dO[r, c]", "dV[r, ck] += p @ dO[r, c]"),
+    ("dp = dO[r, c] @ V[r, ck].T", "dp = dO[r, c] @ K[r, ck].T"),
+    ("O[r, c] = p @ V[r, ck]", "O[r, c] = p @ K[r, ck]"),
+    ("dV[r, ck] += p.T @ dO[r, c]", "dV[r, ck] = p.T @ dO[r, c]"),                             # last head of a group wins
+    ("ck = slice((h // group) * d, (h // group + 1) * d)\n            p, l =", "ck = slice((h % (n_heads // group)) * d, (h % (n_heads // group) + 1) * d)\n            p, l ="),
 ]
 
 
@@ -125,3 +154,4 @@ def test_attention_pins_catch_planted_mistakes(idx):
     with pytest.raises((AssertionError, ValueError, FloatingPointError)):
         with np.errstate(all="ignore"):
             check_pins(mod)
+            check_gqa(mod)
