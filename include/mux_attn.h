@@ -9,11 +9,13 @@
  *     O_i = sum_{j <= i} softmax_j(scale * q_i . k_j) v_j          per head
  * The sequences come from the same table (mux_segtab) as the linear layers; rows follow its layout.
  *
- * Conventions as in mux.h.  Q, K, V, O, dO, dQ, dK, dV are device, bf16, [T, n_heads * head_dim] row-major with the
- * given leading dimensions (elements between rows; head h in columns h*head_dim ..), so the three slices of a
- * fused QKV buffer can be passed as they are.  Rows of padding are written as zero in every output.
- * Supported now: MUX_DT_BF16, head_dim 128, n_kv_heads == n_heads, leading dimensions that are multiples of 8
- * and 16-byte aligned pointers; anything else returns MUX_ERR_UNSUPPORTED and launches nothing.
+ * Conventions as in mux.h.  Q, O, dO, dQ are device, bf16, [T, n_heads * head_dim] row-major, K, V, dK, dV
+ * [T, n_kv_heads * head_dim], with the given leading dimensions (elements between rows; head h in columns
+ * h*head_dim ..), so the three slices of a fused QKV buffer can be passed as they are.  n_kv_heads divides n_heads
+ * (grouped-query attention: query head h reads key/value head h / (n_heads / n_kv_heads); dK, dV collect the
+ * contributions of every query head of the group).  Rows of padding are written as zero in every output.
+ * Supported now: MUX_DT_BF16, head_dim 128, leading dimensions that are multiples of 8 and 16-byte aligned
+ * pointers; anything else returns MUX_ERR_UNSUPPORTED and launches nothing.
  */
 #ifndef MUX_ATTN_H_
 #define MUX_ATTN_H_
@@ -29,7 +31,7 @@ extern "C" {
 
 typedef struct {
   int32_t n_heads;
-  int32_t n_kv_heads; /* must equal n_heads for now */
+  int32_t n_kv_heads; /* divides n_heads */
   int32_t head_dim;   /* 128 */
   int32_t dtype;      /* MUX_DT_BF16 */
   float scale;        /* 0: 1 / sqrt(head_dim) */

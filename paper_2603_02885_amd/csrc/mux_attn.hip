@@ -36,7 +36,7 @@ struct AttnParams {
   float* lse;         // [H][T], natural log
   float* delta;       // [H][T]
   int64_t ldq, ldk, ldv, ldo;
-  int T, H;
+  int T, H, Hkv;      // query heads, key/value heads (H = group * Hkv: query head h reads key/value head h / group)
   float scale;
 };
 
@@ -128,16 +128,17 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
   const int kend = min(len, q0 + BLK);          // keys [0, kend) are visible to some query of the block
   const int wq_first = q0 + 32 * wave, wq_last = wq_first + 31;
   TileLoad tk, tv;
-  tk.load(p.K, p.ldk, first, 0, len, hc, tid);
-  tv.load(p.V, p.ldv, first, 0, len, hc, tid);
+  const int hck = wi_head / (p.H / p.Hkv) * D;  // this head's key/value columns
+  tk.load(p.K, p.ldk, first, 0, len, hck, tid);
+  tv.load(p.V, p.ldv, first, 0, len, hck, tid);
   for (int kb = 0; kb < kend; kb += TILE) {
     __syncthreads();
     tk.store(sK, KP, tid);
     tv.store(sV, TP, tid);
     __syncthreads();
     if (kb + TILE < kend) {
-      tk.load(p.K, p.ldk, first, kb + TILE, len, hc, tid);
-      tv.load(p.V, p.ldv, first, kb + TILE, len, hc, tid);
+      tk.load(p.K, p.ldk, first, kb + TILE, len, hck, tid);
+      tv.load(p.V, p.ldv, first, kb + TILE, len, hck, tid);
     }
     if (kb > wq_last) continue;                 // no key of this tile is visible to this wave's queries
     f32x16 s[2];
@@ -234,7 +235,8 @@ struct ZeroParams {
   const int32_t* dtab;
   bf16_t* out[3];
   int64_t ld[3];
-  int n_out, width;
+  int n_out;
+  int width[3];
 };
 __global__ __launch_bounds__(256) void k_attn_zero_pad(ZeroParams p) {
   const ItemView it = load_item(p.dtab, 0, blockIdx.x);
@@ -248,7 +250,7 @@ __global__ __launch_bounds__(256) void k_attn_zero_pad(ZeroParams p) {
       uint4* dst = (uint4*)(p.out[o] + (size_t)(it.row0 + r) * p.ld[o]);
 #pragma unroll
       for (int k = 0; k < 4; ++k)
-        if (slab + 64 * k < p.width / 8) dst[slab + 64 * k] = uint4{0u, 0u, 0u, 0u};
+        if (slab + 64 * k < p.width[o] / 8) dst[slab + 64 * k] = uint4{0u, 0u, 0u, 0u};
     }
   }
 }
@@ -309,16 +311,17 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_q(AttnParams p) {
   const int kend = min(len, q0 + BLK);
   const int wq_first = q0 + 32 * wave, wq_last = wq_first + 31;
   TileLoad tk, tv;
-  tk.load(p.K, p.ldk, first, 0, len, hc, tid);
-  tv.load(p.V, p.ldv, first, 0, len, hc, tid);
+  const int hck = wi_head / (p.H / p.Hkv) * D;  // this head's key/value columns
+  tk.load(p.K, p.ldk, first, 0, len, hck, tid);
+  tv.load(p.V, p.ldv, first, 0, len, hck, tid);
   for (int kb = 0; kb < kend; kb += TILE) {
     __syncthreads();
     tk.store(sK, TP, tid);
     tv.store(sV, KP, tid);
     __syncthreads();
     if (kb + TILE < kend) {
-      tk.load(p.K, p.ldk, first, kb + TILE, len, hc, tid);
-      tv.load(p.V, p.ldv, first, kb + TILE, len, hc, tid);
+      tk.load(p.K, p.ldk, first, kb + TILE, len, hck, tid);
+      tv.load(p.V, p.ldv, first, kb + TILE, len, hck, tid);
     }
     if (kb > wq_last) continue;
     const bool diag = kb + TILE - 1 > wq_first;
@@ -370,11 +373,12 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
   __shared__ __align__(16) bf16_t sD[TILE * TP];
   __shared__ __align__(16) bf16_t sVf[BLK * KP];   // the block's own V rows (B operand of dO V^T), kept here to save registers
   __shared__ float sLse[TILE], sDelta[TILE];
-  int wi_block, wi_head;
-  work_item(p.dtab[DH_ATT_NBLK], p.H, wi_block, wi_head);
+  int wi_block, wi_head;                       // wi_head: a key/value head
+  work_item(p.dtab[DH_ATT_NBLK], p.Hkv, wi_block, wi_head);
   const int32_t* blk = p.dtab + p.dtab[DH_ATT_OFF_BWD] + wi_block * DA_WORDS;
   const int first = blk[DA_FIRST_ROW], len = blk[DA_LEN], k0 = blk[DA_BLOCK0];
   const int hc = wi_head * D;
+  const int group = p.H / p.Hkv;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, half = lane >> 5;
   const int kl = k0 + 32 * wave + li;          // this lane's key inside the sequence
   const bool kok = kl < len;
@@ -399,15 +403,17 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
   const int wk_first = k0 + 32 * wave;
   TileLoad tq, td;
   float r_lse = 0.f, r_delta = 0.f;
+  for (int g = 0; g < group; ++g) {             // every query head that reads this key/value head
+  const int hq = wi_head * group + g, hcq = hq * D;
   auto load_stats = [&](int qb) {
     if (tid < TILE) {
       const bool ok = qb + tid < len;
-      r_lse = ok ? p.lse[(size_t)wi_head * p.T + first + qb + tid] * LOG2E : INFINITY;   // exp2(x - inf) = 0
-      r_delta = ok ? p.delta[(size_t)wi_head * p.T + first + qb + tid] : 0.f;
+      r_lse = ok ? p.lse[(size_t)hq * p.T + first + qb + tid] * LOG2E : INFINITY;   // exp2(x - inf) = 0
+      r_delta = ok ? p.delta[(size_t)hq * p.T + first + qb + tid] : 0.f;
     }
   };
-  tq.load(p.Q, p.ldq, first, k0, len, hc, tid);
-  td.load(p.dO, p.ldo, first, k0, len, hc, tid);
+  tq.load(p.Q, p.ldq, first, k0, len, hcq, tid);
+  td.load(p.dO, p.ldo, first, k0, len, hcq, tid);
   load_stats(k0);
   for (int qb = k0; qb < len; qb += TILE) {     // queries before the block see none of its keys
     __syncthreads();
@@ -416,8 +422,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
     if (tid < TILE) { sLse[tid] = r_lse; sDelta[tid] = r_delta; }
     __syncthreads();
     if (qb + TILE < len) {
-      tq.load(p.Q, p.ldq, first, qb + TILE, len, hc, tid);
-      td.load(p.dO, p.ldo, first, qb + TILE, len, hc, tid);
+      tq.load(p.Q, p.ldq, first, qb + TILE, len, hcq, tid);
+      td.load(p.dO, p.ldo, first, qb + TILE, len, hcq, tid);
       load_stats(qb + TILE);
     }
     if (qb + TILE - 1 < wk_first) continue;     // every query of the tile lies before this wave's keys
@@ -456,6 +462,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
       }
     }
   }
+  }                                             // next query head of the group
   if (kok) {
     bf16_t* krow = p.dK + (size_t)(first + kl) * p.ldk + hc;
     bf16_t* vrow = p.dV + (size_t)(first + kl) * p.ldv + hc;
@@ -477,12 +484,14 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
 mux_status check(const char* fn, const mux_attn_desc* d, const mux_segtab* st) {
   if (!d || !st) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": null descriptor or table");
   if (d->n_heads < 1 || d->n_kv_heads < 1 || d->head_dim < 1) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": bad head counts");
-  if (d->dtype != MUX_DT_BF16 || d->head_dim != D || d->n_kv_heads != d->n_heads)
-    return fail(MUX_ERR_UNSUPPORTED, std::string(fn) + ": only bf16, head_dim 128 and n_kv_heads == n_heads are built");
-  const int64_t w = (int64_t)d->n_heads * D;
+  if (d->n_heads % d->n_kv_heads) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": n_kv_heads must divide n_heads");
+  if (d->dtype != MUX_DT_BF16 || d->head_dim != D)
+    return fail(MUX_ERR_UNSUPPORTED, std::string(fn) + ": only bf16 and head_dim 128 are built");
+  const int64_t w = (int64_t)d->n_heads * D, wkv = (int64_t)d->n_kv_heads * D;
   const int64_t lds[4] = {d->ldq, d->ldk, d->ldv, d->ldo};
-  for (int64_t ld : lds) {
-    if (ld < w) return fail(MUX_ERR_SHAPE, std::string(fn) + ": a leading dimension is smaller than n_heads * head_dim");
+  for (int i = 0; i < 4; ++i) {
+    const int64_t ld = lds[i];
+    if (ld < (i == 1 || i == 2 ? wkv : w)) return fail(MUX_ERR_SHAPE, std::string(fn) + ": a leading dimension is smaller than its heads * head_dim");
     if (ld % 8) return fail(MUX_ERR_UNSUPPORTED, std::string(fn) + ": leading dimensions must be multiples of 8");
     if ((int64_t)st->T * ld >= ((int64_t)1 << 40)) return fail(MUX_ERR_SHAPE, std::string(fn) + ": problem too large");
   }
@@ -528,11 +537,11 @@ extern "C" mux_status mux_attn_forward(const mux_attn_desc* desc, const mux_segt
   p.Q = (const bf16_t*)Q; p.K = (const bf16_t*)K; p.V = (const bf16_t*)V; p.Out = (bf16_t*)O;
   p.lse = (float*)saved;
   p.ldq = desc->ldq; p.ldk = desc->ldk; p.ldv = desc->ldv; p.ldo = desc->ldo;
-  p.T = st->T; p.H = desc->n_heads;
+  p.T = st->T; p.H = desc->n_heads; p.Hkv = desc->n_kv_heads;
   p.scale = desc->scale > 0.f ? desc->scale : 1.f / sqrtf((float)D);
   ZeroParams z{};
-  z.dtab = p.dtab; z.out[0] = (bf16_t*)O; z.ld[0] = desc->ldo; z.n_out = 1; z.width = desc->n_heads * D;
-  MUX_LAUNCH("attn_zero_pad", k_attn_zero_pad, dim3((unsigned)st->items[0].size(), (unsigned)((z.width + 2047) / 2048)), dim3(256), 0, stream, z);
+  z.dtab = p.dtab; z.out[0] = (bf16_t*)O; z.ld[0] = desc->ldo; z.n_out = 1; z.width[0] = desc->n_heads * D;
+  MUX_LAUNCH("attn_zero_pad", k_attn_zero_pad, dim3((unsigned)st->items[0].size(), (unsigned)((z.width[0] + 2047) / 2048)), dim3(256), 0, stream, z);
   if (st->n_attn_blocks > 0)
     MUX_LAUNCH("attn_fwd", k_attn_fwd, dim3((unsigned)st->n_attn_blocks * (unsigned)desc->n_heads), dim3(256), 0, stream, p);
   return last_hip(fn);
@@ -558,16 +567,17 @@ extern "C" mux_status mux_attn_backward(const mux_attn_desc* desc, const mux_seg
   p.dQ = (bf16_t*)dQ; p.dK = (bf16_t*)dK; p.dV = (bf16_t*)dV;
   p.lse = (float*)saved; p.delta = (float*)ws;
   p.ldq = desc->ldq; p.ldk = desc->ldk; p.ldv = desc->ldv; p.ldo = desc->ldo;
-  p.T = st->T; p.H = desc->n_heads;
+  p.T = st->T; p.H = desc->n_heads; p.Hkv = desc->n_kv_heads;
   p.scale = desc->scale > 0.f ? desc->scale : 1.f / sqrtf((float)D);
   ZeroParams z{};
-  z.dtab = p.dtab; z.n_out = 3; z.width = desc->n_heads * D;
+  z.dtab = p.dtab; z.n_out = 3;
+  z.width[0] = desc->n_heads * D; z.width[1] = z.width[2] = desc->n_kv_heads * D;
   z.out[0] = p.dQ; z.ld[0] = desc->ldq; z.out[1] = p.dK; z.ld[1] = desc->ldk; z.out[2] = p.dV; z.ld[2] = desc->ldv;
-  MUX_LAUNCH("attn_zero_pad", k_attn_zero_pad, dim3((unsigned)st->items[0].size(), (unsigned)((z.width + 2047) / 2048)), dim3(256), 0, stream, z);
+  MUX_LAUNCH("attn_zero_pad", k_attn_zero_pad, dim3((unsigned)st->items[0].size(), (unsigned)((z.width[0] + 2047) / 2048)), dim3(256), 0, stream, z);
   const size_t n = (size_t)st->T * desc->n_heads;
   MUX_LAUNCH("attn_delta", k_attn_delta, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p);
   if (st->n_attn_blocks > 0) {
-    MUX_LAUNCH("attn_bwd_kv", k_attn_bwd_kv, dim3((unsigned)st->n_attn_blocks * (unsigned)desc->n_heads), dim3(256), 0, stream, p);
+    MUX_LAUNCH("attn_bwd_kv", k_attn_bwd_kv, dim3((unsigned)st->n_attn_blocks * (unsigned)desc->n_kv_heads), dim3(256), 0, stream, p);
     MUX_LAUNCH("attn_bwd_q", k_attn_bwd_q, dim3((unsigned)st->n_attn_blocks * (unsigned)desc->n_heads), dim3(256), 0, stream, p);
   }
   return last_hip(fn);

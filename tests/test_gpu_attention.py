@@ -28,14 +28,16 @@ def bf16_round(a):
     return r.view(np.float32)
 
 
-def run(env, task_lens, chunk, H, seed, max_pack_len=0, flags=0, fused=False, sigma=1.0, check_repeat=False):
+def run(env, task_lens, chunk, H, seed, max_pack_len=0, flags=0, fused=False, sigma=1.0, check_repeat=False, Hkv=None):
     mx, torch = env
     d = 128
     ot = segtab.build(task_lens, chunk, max_pack_len, flags)
     seqs = [(s[2], s[3]) for s in segtab.sequences(ot)]
     T = ot.T
     rng = np.random.default_rng(seed)
-    Q, K, V, dO = (bf16_round(rng.standard_normal((T, H * d)) * sigma) for _ in range(4))
+    Hkv = H if Hkv is None else Hkv
+    Q, dO = (bf16_round(rng.standard_normal((T, H * d)) * sigma) for _ in range(2))
+    K, V = (bf16_round(rng.standard_normal((T, Hkv * d)) * sigma) for _ in range(2))
     pad = ot.row_task < 0
     for a in (Q, K, V, dO):
         a[pad] = np.nan if seed % 2 else 1e30            # padding rows must not leak anywhere
@@ -49,17 +51,17 @@ def run(env, task_lens, chunk, H, seed, max_pack_len=0, flags=0, fused=False, si
     up = lambda a: torch.from_numpy(a).to(dev).to(torch.bfloat16)
     if fused:        # the three slices of one [T, 3 H d] buffer
         qkv = torch.cat([up(Q), up(K), up(V)], dim=1).contiguous()
-        tq, tk, tv = qkv[:, :H * d], qkv[:, H * d:2 * H * d], qkv[:, 2 * H * d:]
-        ld = 3 * H * d
+        tq, tk, tv = qkv[:, :H * d], qkv[:, H * d:(H + Hkv) * d], qkv[:, (H + Hkv) * d:]
+        ldq = ldk = (H + 2 * Hkv) * d
     else:
         tq, tk, tv = up(Q), up(K), up(V)
-        ld = H * d
+        ldq, ldk = H * d, Hkv * d
     tdo = up(dO)
-    desc = mx.AttnDesc(H, d, ld, ld, ld, H * d)
+    desc = mx.AttnDesc(H, d, ldq, ldk, ldk, H * d, n_kv_heads=Hkv)
     nan = float("nan")
     O = torch.full((T, H * d), nan, dtype=torch.bfloat16, device=dev)
-    dQ, dK, dV = (torch.full((T, H * d), nan, dtype=torch.bfloat16, device=dev) for _ in range(3))
-    gdesc = mx.AttnDesc(H, d, H * d, H * d, H * d, H * d)
+    dQ = torch.full((T, H * d), nan, dtype=torch.bfloat16, device=dev)
+    dK, dV = (torch.full((T, Hkv * d), nan, dtype=torch.bfloat16, device=dev) for _ in range(2))
     saved = torch.full((max(mx.mux_attn_saved_bytes(desc, st), 256),), 0xFF, dtype=torch.uint8, device=dev)
     wsb = mx.mux_attn_workspace_bytes(desc, st)
     ws = torch.full((max(wsb, 256),), 0xFF, dtype=torch.uint8, device=dev)
@@ -67,14 +69,14 @@ def run(env, task_lens, chunk, H, seed, max_pack_len=0, flags=0, fused=False, si
     mx.mux_attn_forward(desc, st, dtab, tq, tk, tv, O, saved, stream)
     torch.cuda.synchronize()
     if fused:        # backward writes dQ, dK, dV with the leading dimensions of Q, K, V: give it a fused buffer too
-        dqkv = torch.full((T, 3 * H * d), nan, dtype=torch.bfloat16, device=dev)
-        dQ, dK, dV = dqkv[:, :H * d], dqkv[:, H * d:2 * H * d], dqkv[:, 2 * H * d:]
+        dqkv = torch.full((T, (H + 2 * Hkv) * d), nan, dtype=torch.bfloat16, device=dev)
+        dQ, dK, dV = dqkv[:, :H * d], dqkv[:, H * d:(H + Hkv) * d], dqkv[:, (H + Hkv) * d:]
     mx.mux_attn_backward(desc, st, dtab, tq, tk, tv, O, tdo, saved, dQ, dK, dV, ws, wsb, stream)
     torch.cuda.synchronize()
     got = {k: v.float().cpu().numpy().astype(np.float64) for k, v in (("O", O), ("dQ", dQ), ("dK", dK), ("dV", dV))}
-    ref = oatt.forward(Q, K, V, seqs, H)
+    ref = oatt.forward(Q, K, V, seqs, H, n_kv_heads=Hkv)
     # the backward consumes the O the forward stored (bf16); the oracle's dO.O term uses its own O: same to rounding
-    ref.update(oatt.backward(Q, K, V, dO, seqs, H))
+    ref.update(oatt.backward(Q, K, V, dO, seqs, H, n_kv_heads=Hkv))
     errs = {}
     for k in ("O", "dQ", "dK", "dV"):
         assert np.isfinite(got[k]).all(), k
@@ -124,6 +126,14 @@ def test_fused_qkv_buffer_and_large_scores(env):
     run(env, [[150, 90], [257]], chunk=64, H=2, seed=6, sigma=3.0)
 
 
+def test_grouped_query_heads(env):
+    """Fewer key/value heads than query heads: groups of 2 and of 4 (one key/value head for all), separate and fused
+    buffers; dK and dV add up the query heads of a group."""
+    run(env, [[300, 70], [129]], chunk=64, H=4, Hkv=2, seed=10, check_repeat=True)
+    run(env, [[300, 70], [129]], chunk=64, H=4, Hkv=1, seed=11, fused=True)
+    run(env, [[1000]], chunk=128, H=8, Hkv=8, seed=12)                    # eight heads: the XCD-wise work mapping
+
+
 def test_llama_heads_one_block(env):
     """32 heads of 128 (the q/k/v width of the 4096-wide projections), ragged lengths."""
     run(env, [[384, 100], [77]], chunk=128, H=32, seed=7)
@@ -141,8 +151,9 @@ def test_argument_checks(env):
         mx.mux_attn_forward(mx.AttnDesc(2, 64, 128, 128, 128, 128), st, dtab, x, x, x, x, None)       # head_dim 64
     with pytest.raises(mx.MuxError):
         mx.mux_attn_forward(mx.AttnDesc(2, 128, 128, 256, 256, 256), st, dtab, x, x, x, x, None)      # ldq too small
+    x3 = torch.zeros((64, 384), dtype=torch.bfloat16, device=dev)
     with pytest.raises(mx.MuxError):
-        mx.mux_attn_forward(mx.AttnDesc(2, 128, 256, 256, 256, 256, n_kv_heads=1), st, dtab, x, x, x, x, None)
+        mx.mux_attn_forward(mx.AttnDesc(3, 128, 384, 384, 384, 384, n_kv_heads=2), st, dtab, x3, x3, x3, x3, None)   # 2 does not divide 3
     with pytest.raises(mx.MuxError):
         mx.mux_attn_forward(mx.AttnDesc(2, 128, 256, 256, 256, 256), st, dtab, x, None, x, x, None)   # null K
 
