@@ -368,11 +368,27 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_q(AttnParams p) {
 }
 
 // ------------------------------------------------------------------------------------------------ dK, dV
+// 32 rows x 128 columns of one head: thread t carries 32 bytes of row t / 8
+struct TileLoad32 {
+  uint4 r[2];
+  __device__ __forceinline__ void load(const bf16_t* base, int64_t ld, int first, int row0, int limit, int hc, int tid) {
+    const int row = row0 + (tid >> 3);
+    const uint4* src = (const uint4*)(base + (size_t)(first + row) * ld + hc + (tid & 7) * 16);
+    r[0] = row < limit ? src[0] : uint4{0u, 0u, 0u, 0u};
+    r[1] = row < limit ? src[1] : uint4{0u, 0u, 0u, 0u};
+  }
+  __device__ __forceinline__ void store(bf16_t* tile, int pitch, int tid) const {
+    uint4* dst = (uint4*)(tile + (tid >> 3) * pitch + (tid & 7) * 16);
+    dst[0] = r[0]; dst[1] = r[1];
+  }
+};
+
 __global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
-  __shared__ __align__(16) bf16_t sQ[TILE * TP];
-  __shared__ __align__(16) bf16_t sD[TILE * TP];
+  constexpr int QT = 32;                       // queries staged per step
+  __shared__ __align__(16) bf16_t sQ[QT * TP];
+  __shared__ __align__(16) bf16_t sD[QT * TP];
   __shared__ __align__(16) bf16_t sVf[BLK * KP];   // the block's own V rows (B operand of dO V^T), kept here to save registers
-  __shared__ float sLse[TILE], sDelta[TILE];
+  __shared__ float sLse[QT], sDelta[QT];
   int wi_block, wi_head;                       // wi_head: a key/value head
   work_item(p.dtab[DH_ATT_NBLK], p.Hkv, wi_block, wi_head);
   const int32_t* blk = p.dtab + p.dtab[DH_ATT_OFF_BWD] + wi_block * DA_WORDS;
@@ -401,12 +417,12 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
 #pragma unroll
     for (int j = 0; j < 16; ++j) { dk[dt][j] = 0.f; dv[dt][j] = 0.f; }
   const int wk_first = k0 + 32 * wave;
-  TileLoad tq, td;
+  TileLoad32 tq, td;
   float r_lse = 0.f, r_delta = 0.f;
   for (int g = 0; g < group; ++g) {             // every query head that reads this key/value head
   const int hq = wi_head * group + g, hcq = hq * D;
   auto load_stats = [&](int qb) {
-    if (tid < TILE) {
+    if (tid < QT) {
       const bool ok = qb + tid < len;
       r_lse = ok ? p.lse[(size_t)hq * p.T + first + qb + tid] * LOG2E : INFINITY;   // exp2(x - inf) = 0
       r_delta = ok ? p.delta[(size_t)hq * p.T + first + qb + tid] : 0.f;
@@ -415,21 +431,21 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
   tq.load(p.Q, p.ldq, first, k0, len, hcq, tid);
   td.load(p.dO, p.ldo, first, k0, len, hcq, tid);
   load_stats(k0);
-  for (int qb = k0; qb < len; qb += TILE) {     // queries before the block see none of its keys
+  for (int qb = k0; qb < len; qb += QT) {       // queries before the block see none of its keys
     __syncthreads();
     tq.store(sQ, TP, tid);
     td.store(sD, TP, tid);
-    if (tid < TILE) { sLse[tid] = r_lse; sDelta[tid] = r_delta; }
+    if (tid < QT) { sLse[tid] = r_lse; sDelta[tid] = r_delta; }
     __syncthreads();
-    if (qb + TILE < len) {
-      tq.load(p.Q, p.ldq, first, qb + TILE, len, hcq, tid);
-      td.load(p.dO, p.ldo, first, qb + TILE, len, hcq, tid);
-      load_stats(qb + TILE);
+    if (qb + QT < len) {
+      tq.load(p.Q, p.ldq, first, qb + QT, len, hcq, tid);
+      td.load(p.dO, p.ldo, first, qb + QT, len, hcq, tid);
+      load_stats(qb + QT);
     }
-    if (qb + TILE - 1 < wk_first) continue;     // every query of the tile lies before this wave's keys
+    if (qb + QT - 1 < wk_first) continue;     // every query of the tile lies before this wave's keys
     const bool diag = qb < wk_first + 32;        // some query of the tile lies before some key of the wave
-#pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
+    {
+      constexpr int qt = 0;
       f32x16 s, dp;
 #pragma unroll
       for (int j = 0; j < 16; ++j) { s[j] = 0.f; dp[j] = 0.f; }
