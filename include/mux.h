@@ -23,8 +23,9 @@
  *     A_t[K,r_t], B_t[r_t,N], l_t[N].  T = mux_segtab_rows().
  *   - Environment variables, for measurement and testing only (none is needed in normal use):
  *     MUX_GEMM_REGSTAGED (read at every call) runs the backbone product through the register-staged kernel also
- *     on the shapes the pipelined kernel takes; MUX_GEMM_BK32 and MUX_GEMM_NO_HALF_TILES (read once per process)
- *     make the pipelined kernel use 32-deep stages everywhere and keep the tiles of the last round at full width.
+ *     on the shapes the pipelined kernel takes; MUX_GEMM_BK32, MUX_GEMM_NO_HALF_TILES and MUX_GEMM_NO_QUARTER_TILES
+ *     (read once per process) make the pipelined kernel use 32-deep stages everywhere, keep the tiles of the last
+ *     round whole, and split them into halves where it would take quarters.
  */
 #ifndef MUX_H_
 #define MUX_H_

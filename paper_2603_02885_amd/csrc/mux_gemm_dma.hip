@@ -49,7 +49,8 @@ struct GemmParams {
   bf16_t* Zsave;       // forward: x W of IA3_OUT rows (may be null)
   int Kc, Nc, RP;
   int n_m, n_n, per_xcd;   // tile grid in units of 256 x TILE_N tiles; workgroups per XCD over the whole grid
-  int n_full;              // workgroups that compute full-width tiles (a multiple of 8); the rest compute halves
+  int n_full;              // workgroups that compute full tiles (a multiple of 8); the rest compute pieces of tiles
+  int tail_split;          // pieces per tile after the full ones: 2 (halves) or 4 (quarters)
   const bf16_t* AinScaled;  // backward: prepared input rows (IA3_OUT: dY * l_t; TUNING: dY + p D_t^T), [z_rows, Kc], indexed like the saved x W
 };
 
@@ -95,25 +96,34 @@ struct Smem {
   int* row;
 };
 
-// One output tile.  WNW = waves along N, NI = 32-column MFMA tiles per wave; eight waves (two per SIMD) on a
-// 256 x BN tile with BN = WNW*NI*32:
-//   <4,2> 128x64 per wave, the full 256x256 tile;
-//   <4,1> 128x32 per wave, a 256x128 half of a tile: for what is left after the last full round of workgroups.
+// One output tile.  WNW = waves along N, MI x NI = 32x32 MFMA tiles per wave; 2*WNW waves on a
+// BMT x BN tile with BMT = 2*MI*32 and BN = WNW*NI*32:
+//   <4,4,2> eight waves (two per SIMD), 128x64 per wave, the full 256x256 tile;
+//   <4,4,1> eight waves, 128x32 per wave, a 256x128 half of a tile,
+//   <2,2,2> four waves (one per SIMD), 64x64 per wave, a 128x128 quarter: for what is left after the last full
+//           round of workgroups.
 // BK = 64 with two stages, or BK = 32 with four.
-// `xcd_slot` = (per-XCD tile slot) * 8 + XCD; `half` selects the 128 columns of a half-width tile.
-template <bool NT, int WNW, int NI, int BK>
-__device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slot, const int half, const Smem sm) {
+// `xcd_slot` = (per-XCD tile slot) * 8 + XCD; `half` selects the 128 columns of a half-width tile, `mhalf` the
+// 128 rows of a quarter.
+template <bool NT, int WNW, int MI, int NI, int BK>
+__device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slot, const int half, const int mhalf,
+                                          const Smem sm) {
   constexpr int BN = WNW * NI * 32;
+  constexpr int BMT = 2 * MI * 32;
   static_assert(BN == 256 || BN == 128, "tile width");
+  static_assert(BMT == 256 || BMT == 128, "tile height");
   static_assert(BK == 32 || BK == 64, "K-tile depth");
-  constexpr int NST = BK == 64 ? 2 : 4;           // LDS stages
+  // LDS stages.  A 64-deep stage of a full or half tile takes 64 or 48 KB: two fit.  A quarter's takes 32 KB and
+  // half the MFMA time, which is less than the latency of the loads: four stages, three tiles in flight.
+  constexpr int NST = (BK == 64 && MI == 4) ? 2 : 4;
+  constexpr bool SPLIT = BK == 64 && NST == 4;    // four stages in the two arrays per operand that 64-deep stages have
   constexpr int NW = 2 * WNW, NTHR = 64 * NW;
-  constexpr int A_ELEMS = BM * BK;                // elements of one A stage
+  constexpr int A_ELEMS = BMT * BK;               // elements of one A stage
   // The loads are issued by the first half of the waves only.  Each SIMD hosts waves w and w + NW/2 and serves the
   // older one first, so wave w runs ahead and then idles at the barrier; a wave that cannot issue a load (the
   // vector memory pipeline takes 16 cycles per instruction, 1 KB) cannot issue the MFMA behind it either.
   // Giving wave w all the loads uses its slack and leaves wave w + NW/2 a pure MFMA / LDS-read stream.
-  constexpr int LW = NW / 2;
+  constexpr int LW = NW == 8 ? NW / 2 : NW;       // four waves: one per SIMD, all of them load
   constexpr int ACH = (A_ELEMS / 512) / LW, BCH = (BN * BK / 512) / LW;   // 1 KB chunks a loading wave fetches per K-tile
   static_assert(ACH >= 1 && BCH >= 1, "every loading wave fetches at least one chunk of each tile");
   constexpr int LPR = BK / 8;                     // [rows][BK] tiles: lanes (16-byte pieces) per row
@@ -139,19 +149,24 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   const int tn = (L % width) / gsize;
 
   const ItemView it = load_item(p.dtab, TS256, tm);
+  const int mrow0 = mhalf * BMT;                  // first row of the item this tile covers
+  const int nrows = it.nrows - mrow0 < BMT ? it.nrows - mrow0 : BMT;   // rows of the item inside this tile
+  if (nrows <= 0) return;
+  const int row0 = it.row0 + mrow0;
   const int c0 = tn * TILE_N + half * BN;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  if (wave >= NW) return;                         // a tile of four waves: the others end here, before any barrier
   const int wm = wave / WNW, wn = wave % WNW;
   const bool loader = wave < LW;
   const int lw = wave % LW;                       // chunk owner index (meaningful for loading waves)
 
-  if (tid < 256) sRow[tid] = (it.task >= 0 && tid < it.nrows && row_is_valid(p.dtab, it.row0 + tid)) ? 1 : 0;
+  if (tid < BMT) sRow[tid] = (it.task >= 0 && tid < nrows && row_is_valid(p.dtab, row0 + tid)) ? 1 : 0;
 
   if (it.task < 0 || it.nvalid == 0) {             // rows of no task, or padding only: zeros out
-    for (int e = tid; e < it.nrows * (BN / 8); e += NTHR) {
+    for (int e = tid; e < nrows * (BN / 8); e += NTHR) {
       const int m = e / (BN / 8), c = c0 + (e % (BN / 8)) * 8;
-      if (c < p.Nc) *(uint4*)(p.Out + (size_t)(it.row0 + m) * p.Nc + c) = make_uint4(0, 0, 0, 0);
+      if (c < p.Nc) *(uint4*)(p.Out + (size_t)(row0 + m) * p.Nc + c) = make_uint4(0, 0, 0, 0);
     }
     return;
   }
@@ -172,12 +187,12 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   // (lane -> row lane/LPR, physical piece lane%LPR), or RPCB k-rows of the forward's [BK][BN] tile of W
   // (lane -> k-row lane/PPRB, physical piece lane%PPRB).  Loading wave w owns chunks w*ACH .. of A and w*BCH .. of B.
   const int r_in = lane / LPR;                                  // row inside the chunk
-  const uint32_t a_rows_bytes = (uint32_t)it.nrows * (uint32_t)p.Kc * 2u;
-  const bf16_t* a_base = (NT && (ia3 || tuning)) ? p.AinScaled + (size_t)(tk.zrow0 + it.row0 - tk.row_begin) * p.Kc
-                                     : p.Ain + (size_t)it.row0 * p.Kc;
+  const uint32_t a_rows_bytes = (uint32_t)nrows * (uint32_t)p.Kc * 2u;
+  const bf16_t* a_base = (NT && (ia3 || tuning)) ? p.AinScaled + (size_t)(tk.zrow0 + row0 - tk.row_begin) * p.Kc
+                                     : p.Ain + (size_t)row0 * p.Kc;
   const rsrc_t rA = make_rsrc(a_base, a_rows_bytes);
   const rsrc_t rW = make_rsrc(p.W, (uint32_t)((size_t)(NT ? p.Nc : p.Kc) * p.ldw * 2));
-  const rsrc_t rE = make_rsrc(lora ? p.Ext + (size_t)it.row0 * p.RP : p.Ain, lora ? (uint32_t)it.nrows * (uint32_t)p.RP * 2u : 0u);
+  const rsrc_t rE = make_rsrc(lora ? p.Ext + (size_t)row0 * p.RP : p.Ain, lora ? (uint32_t)nrows * (uint32_t)p.RP * 2u : 0u);
   const rsrc_t rP = make_rsrc(lora ? adapterB : p.Ain, lora ? (uint32_t)(NT ? (size_t)p.Nc * rank : (size_t)rank * p.Nc) * 2u : 0u);
 
   // row of the [rows][BK] tile chunk q of this wave puts this lane on, and the logical k-piece it fetches there
@@ -259,16 +274,16 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   const int l16 = lane & 15, lhalf = (lane >> 4) & 1;
   // [rows][BK] tiles: row = (wm|wn)*128 + t*32 + li; logical piece 2*ks + lg (the swizzle depends on li only)
   const int swz = swz_row<BK>(li);
-  const int a_rd = (wm * 128 + li) * BK;        // elements; + t*32*BK + ((2ks+lg)^swz)*8
+  const int a_rd = (wm * (32 * MI) + li) * BK;  // elements; + t*32*BK + ((2ks+lg)^swz)*8
   const int bt_rd = (wn * WCOLS + li) * BK;
   // forward W tile: k = ks*16 + 8 lg + 4 h + l16/4 ; logical seg = wn*8 + 2 t + lhalf ; + 4*(l16%4) elements
   const int kq = l16 >> 2;                      // k & 3 of the rows this lane addresses
   const int bn_col = 4 * (l16 & 3);
 
-  auto read_ops = [&](const bf16_t* cA, const bf16_t* cB, int ks, bf16x8 (&a)[4], bf16x8 (&b)[NI]) {
+  auto read_ops = [&](const bf16_t* cA, const bf16_t* cB, int ks, bf16x8 (&a)[MI], bf16x8 (&b)[NI]) {
     const int pa = ((2 * ks + lg) ^ swz) * 8;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) a[t] = *(const bf16x8*)(cA + a_rd + t * 32 * BK + pa);
+    for (int t = 0; t < MI; ++t) a[t] = *(const bf16x8*)(cA + a_rd + t * 32 * BK + pa);
     if (NT) {
 #pragma unroll
       for (int t = 0; t < NI; ++t) b[t] = *(const bf16x8*)(cB + bt_rd + t * 32 * BK + pa);
@@ -287,41 +302,42 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   // Accumulators.  The MFMAs are issued with the operands exchanged, so acc[mi][ni] holds the transposed 32x32
   // block: this lane has row 32 mi + li and the four consecutive columns 32 ni + 8 j + 4 lg .. + 3 in registers
   // 4j .. 4j+3, which the epilogue packs into one 8-byte LDS store.
-  f32x16 acc[4][NI];
+  f32x16 acc[MI][NI];
 #pragma unroll
-  for (int mi = 0; mi < 4; ++mi)
+  for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-  auto mma = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[NI]) {
+  auto mma = [&](const bf16x8 (&a)[MI], const bf16x8 (&b)[NI]) {
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
         acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ni], a[mi], acc[mi][ni], 0, 0, 0);
   };
 
-  auto mma_one = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[NI], int m) {
+  auto mma_one = [&](const bf16x8 (&a)[MI], const bf16x8 (&b)[NI], int m) {
     const int mi = m / NI, ni = m % NI;
     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ni], a[mi], acc[mi][ni], 0, 0, 0);
   };
   // one MFMA step with the loads of one tile (all ACH+BCH of them) spread between its MFMA pairs
-  auto mma_with_loads = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[NI], bf16_t* dA, bf16_t* dB) {
+  auto mma_with_loads = [&](const bf16x8 (&a)[MI], const bf16x8 (&b)[NI], bf16_t* dA, bf16_t* dB) {
+    constexpr int PAIRS = MI * NI / 2;
 #pragma unroll
-    for (int i = 0; i < 2 * NI; ++i) {
+    for (int i = 0; i < PAIRS; ++i) {
       mma_one(a, b, 2 * i);
       mma_one(a, b, 2 * i + 1);
 #pragma unroll
-      for (int d = (i * (ACH + BCH)) / (2 * NI); d < ((i + 1) * (ACH + BCH)) / (2 * NI); ++d) issue_one(dA, dB, d);
+      for (int d = (i * (ACH + BCH)) / PAIRS; d < ((i + 1) * (ACH + BCH)) / PAIRS; ++d) issue_one(dA, dB, d);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
 
   // One operand fragment of step ks: r = 0, 1 .. in the order the next step's MFMAs first need them
-  // (A0, B0 .. B(NI-1), A1, A2, A3).
-  auto read_one = [&](const bf16_t* cA, const bf16_t* cB, int ks, int r, bf16x8 (&a)[4], bf16x8 (&b)[NI]) {
+  // (A0, B0 .. B(NI-1), A1 .. A(MI-1)).
+  auto read_one = [&](const bf16_t* cA, const bf16_t* cB, int ks, int r, bf16x8 (&a)[MI], bf16x8 (&b)[NI]) {
     const int pa = ((2 * ks + lg) ^ swz) * 8;
     if (r == 0 || r > NI) {
       const int t = r == 0 ? 0 : r - NI;
@@ -342,16 +358,16 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   // One MFMA step from (a, b) with the operand reads of step ks_next of (cA, cB) into (an, bn) issued one per
   // MFMA in its shadow (skipped when rd is false), and, when LOADS, the loads of one tile into (dA, dB) spread
   // over the MFMAs after them.
-  auto fused_step = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[NI], const bf16_t* cA, const bf16_t* cB, int ks_next,
-                        bf16x8 (&an)[4], bf16x8 (&bn)[NI], bool rd, auto LOADS, bf16_t* dA, bf16_t* dB) {
+  auto fused_step = [&](const bf16x8 (&a)[MI], const bf16x8 (&b)[NI], const bf16_t* cA, const bf16_t* cB, int ks_next,
+                        bf16x8 (&an)[MI], bf16x8 (&bn)[NI], bool rd, auto LOADS, bf16_t* dA, bf16_t* dB) {
     constexpr bool loads = decltype(LOADS)::value;
-    constexpr int NM = 4 * NI, NR = 4 + NI, NL = ACH + BCH;
+    constexpr int NM = MI * NI, NR = MI + NI, NL = ACH + BCH;
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
       mma_one(a, b, m);
       if (rd) {
         if (m < NR) read_one(cA, cB, ks_next, m, an, bn);
-        if (m == NM - 1) {                                   // a half-width tile has more fragments than MFMAs
+        if (m == NM - 1) {                                   // a narrower tile has more fragments than MFMAs
 #pragma unroll
           for (int r = NM; r < NR; ++r) read_one(cA, cB, ks_next, r, an, bn);
         }
@@ -364,32 +380,40 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
     }
   };
 
-  auto stA = [&](int s) -> bf16_t* { return s == 0 ? sA0 : (s == 1 ? sA1 : (s == 2 ? sA2 : sA3)); };
-  auto stB = [&](int s) -> bf16_t* { return s == 0 ? sB0 : (s == 1 ? sB1 : (s == 2 ? sB2 : sB3)); };
+  static_assert(!SPLIT || (2 * A_ELEMS <= BM * BK && 2 * BN * BK <= BM * BK), "two stages per array");
+  auto stA = [&](int s) -> bf16_t* {
+    if (SPLIT) return (s < 2 ? sA0 : sA1) + (s & 1) * A_ELEMS;
+    return s == 0 ? sA0 : (s == 1 ? sA1 : (s == 2 ? sA2 : sA3));
+  };
+  auto stB = [&](int s) -> bf16_t* {
+    if (SPLIT) return (s < 2 ? sB0 : sB1) + (s & 1) * (BN * BK);
+    return s == 0 ? sB0 : (s == 1 ? sB1 : (s == 2 ? sB2 : sB3));
+  };
   auto tile_barrier = [&]() {
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
   };
 
-  // ---- prologue: tiles 0 .. NST-2 in flight; tile 0 landed and visible; its first operands in registers
+  // ---- prologue: tiles 0 .. PRE-1 in flight; tile 0 landed and visible; its first operands in registers
+  constexpr int PRE = BK == 64 ? NST : NST - 1;
 #pragma unroll
-  for (int s0 = 0; s0 < (NST == 2 ? 2 : NST - 1); ++s0) { prepare(); issue(stA(s0), stB(s0)); }
-  wait_vmcnt<(NST == 2 ? 1 : NST - 2) * (ACH + BCH)>();
+  for (int s0 = 0; s0 < PRE; ++s0) { prepare(); issue(stA(s0), stB(s0)); }
+  wait_vmcnt<(PRE - 1) * (ACH + BCH)>();
   wait_lgkm0();
   tile_barrier();
 
-  bf16x8 a0[4], b0[NI], a1[4], b1[NI];
+  bf16x8 a0[MI], b0[NI], a1[MI], b1[NI];
   read_ops(sA0, sB0, 0, a0, b0);
 
   if (BK == 64) {
-    // Two stages.  Steps 0..2 run from registers read one step ahead; before the last step every wave has read
-    // all of this stage and tile kt+1 has landed (the only loads in flight): barrier; then, under the last
-    // step's MFMAs, the first operands of tile kt+1 are read and all loads of tile kt+2 are issued into the
-    // stage just freed.
-    for (int kt2 = 0; kt2 < KT_total; kt2 += 2) {
+    // Steps 0..2 run from registers read one step ahead; before the last step every wave has read all of this
+    // stage and tile kt+1 has landed (the loads of the NST-2 tiles after it may stay in flight): barrier; then,
+    // under the last step's MFMAs, the first operands of tile kt+1 are read and all loads of tile kt+NST are
+    // issued into the stage just freed.
+    for (int kt2 = 0; kt2 < KT_total; kt2 += NST) {
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
+      for (int u = 0; u < NST; ++u) {
         const int kt = kt2 + u;
         if (kt < KT_total) {
           bf16_t* cA = stA(u);
@@ -399,11 +423,11 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
           fused_step(a0, b0, cA, cB, 1, a1, b1, true, std::false_type{}, nullptr, nullptr);
           fused_step(a1, b1, cA, cB, 2, a0, b0, true, std::false_type{}, nullptr, nullptr);
           fused_step(a0, b0, cA, cB, 3, a1, b1, true, std::false_type{}, nullptr, nullptr);
-          wait_vmcnt<0>();
+          wait_vmcnt<(NST - 2) * (ACH + BCH)>();
           wait_lgkm0();
           tile_barrier();
           __builtin_amdgcn_sched_barrier(0);
-          fused_step(a1, b1, stA(u ^ 1), stB(u ^ 1), 0, a0, b0, true, std::true_type{}, cA, cB);   // past the last tile: read, unused
+          fused_step(a1, b1, stA((u + 1) % NST), stB((u + 1) % NST), 0, a0, b0, true, std::true_type{}, cA, cB);   // past the last tile: read, unused
           issue_done();
         }
       }
@@ -446,9 +470,10 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   asm volatile("" ::: "memory");
 
   // ---- epilogue: aggregate, mask, store; 32 rows of the wave tile at a time through this wave's own array.
-  constexpr int AREAS = A_ELEMS / 2560;           // 5 KB staging areas per A stage
-  static_assert(32 * EPW <= 2560 && NW <= AREAS * NST, "every wave has its own staging area");
-  bf16_t* stage = stA(wave / AREAS) + (wave % AREAS) * 2560;
+  constexpr int AREA = NI == 2 ? 2560 : 1280;     // elements of a staging area (5 KB or 2.5 KB)
+  constexpr int AREAS = A_ELEMS / AREA;           // staging areas per A stage
+  static_assert(32 * EPW <= AREA && NW <= AREAS * NST, "every wave has its own staging area");
+  bf16_t* stage = stA(wave / AREAS) + (wave % AREAS) * AREA;
   constexpr int PPR = WCOLS / 8;                 // 16-byte pieces per staged row
   constexpr int RPI = 64 / PPR;                  // rows one wave instruction moves
   const int e_row = lane / PPR, e_pc = (lane % PPR) * 8;
@@ -457,7 +482,7 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   const bool z_only = !NT && tuning && p.Zsave;  // TUNING forward: x W goes to the saved region, Y is written by the bottleneck kernels
   for (int pass = 0; pass < passes; ++pass) {
     const bool to_z = z_only || pass + 1 < passes;
-    bf16_t* dst = to_z ? p.Zsave + (size_t)(tk.zrow0 - tk.row_begin) * p.Nc : p.Out;
+    bf16_t* dst = to_z ? p.Zsave + (size_t)(tk.zrow0 - tk.row_begin) * p.Nc : p.Out;   // indexed by the row in the batch
     if (scale_out && !to_z) {
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
@@ -468,7 +493,7 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
           const float l0 = in ? bf16_to_f32(Lvec[c]) : 0.f, l1 = in ? bf16_to_f32(Lvec[c + 1]) : 0.f;
           const float l2 = in ? bf16_to_f32(Lvec[c + 2]) : 0.f, l3 = in ? bf16_to_f32(Lvec[c + 3]) : 0.f;
 #pragma unroll
-          for (int mi = 0; mi < 4; ++mi) {
+          for (int mi = 0; mi < MI; ++mi) {
             acc[mi][ni][4 * j + 0] *= l0;
             acc[mi][ni][4 * j + 1] *= l1;
             acc[mi][ni][4 * j + 2] *= l2;
@@ -477,7 +502,7 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
         }
     }
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
+    for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
@@ -492,12 +517,12 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
 #pragma unroll
       for (int rr = 0; rr < 32 / RPI; ++rr) {
         const int ml = rr * RPI + e_row;
-        const int m = wm * 128 + mi * 32 + ml;
+        const int m = wm * (32 * MI) + mi * 32 + ml;
         const int c = c0 + wn * WCOLS + e_pc;
-        if (m < it.nrows && c < p.Nc) {
+        if (m < nrows && c < p.Nc) {
           uint4 v = *(const uint4*)(stage + ml * EPW + e_pc);
           if (sRow[m] == 0) v = make_uint4(0, 0, 0, 0);
-          *(uint4*)(dst + (size_t)(it.row0 + m) * p.Nc + c) = v;
+          *(uint4*)(dst + (size_t)(row0 + m) * p.Nc + c) = v;
         }
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -508,9 +533,9 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
 
 // Workgroups 0 .. n_full-1 compute full tiles, slot by slot with the XCD in the low three bits of the index (the
 // hardware deals consecutive workgroups round-robin to the eight XCDs, so one XCD's L2 sees neighbouring tiles).
-// The workgroups after them compute the remaining tiles as two half-width tiles each; both halves of a tile
-// run on the same XCD.  The dispatcher hands out workgroups in index order, so the halves start as the compute
-// units finish their last full tile.
+// The workgroups after them compute the remaining tiles in pieces (tail_split = 2: two half-width tiles each;
+// 4: four 128 x 128 quarters each); all pieces of a tile run on the same XCD.  The dispatcher hands out workgroups
+// in index order, so the pieces start as the compute units finish their last full tile.
 template <bool NT, int BK>
 __global__ __launch_bounds__(512, 1) void k_gemm_dma(const GemmParams p) {
   constexpr int STAGE_ELEMS = BM * BK;            // 16 KB (BK = 32, four stages) or 32 KB (BK = 64, two) per operand
@@ -526,10 +551,13 @@ __global__ __launch_bounds__(512, 1) void k_gemm_dma(const GemmParams p) {
   const Smem sm = {sA0, sA1, sA2, sA3, sB0, sB1, sB2, sB3, sRow};
   const int b = blockIdx.x;
   if (b < p.n_full) {
-    gemm_tile<NT, 4, 2, BK>(p, b, 0, sm);
-  } else {
+    gemm_tile<NT, 4, 4, 2, BK>(p, b, 0, 0, sm);
+  } else if (p.tail_split == 2) {
     const int t = b - p.n_full;                                       // n_full is a multiple of 8
-    gemm_tile<NT, 4, 1, BK>(p, p.n_full + (((t >> 4) << 3) | (t & 7)), (t >> 3) & 1, sm);
+    gemm_tile<NT, 4, 4, 1, BK>(p, p.n_full + (((t >> 4) << 3) | (t & 7)), (t >> 3) & 1, 0, sm);
+  } else {
+    const int t = b - p.n_full;
+    gemm_tile<NT, 2, 2, 2, BK>(p, p.n_full + (((t >> 5) << 3) | (t & 7)), (t >> 3) & 1, (t >> 4) & 1, sm);
   }
 }
 
@@ -556,16 +584,19 @@ mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t
   if (total == 0) return MUX_OK;
   p.per_xcd = (total + 7) / 8;
   // One workgroup per compute unit at a time: the tiles left after the last full round would keep a fraction of
-  // the units busy for a whole tile time.  When they fit twice, they run as half-width tiles.
+  // the units busy for a whole tile time.  When they fit four times, they run as quarters, when twice, as
+  // half-width tiles.
   static const bool no_halves = getenv("MUX_GEMM_NO_HALF_TILES") != nullptr;
+  static const bool no_quarters = getenv("MUX_GEMM_NO_QUARTER_TILES") != nullptr;
   static const bool narrow = getenv("MUX_GEMM_BK32") != nullptr;
   const int ncu = compute_units();
   const int full_slots = (total / ncu) * (ncu / 8);          // per-XCD slots covered by whole rounds
   const int rem = total - full_slots * 8;
   int tail_slots = 0;
   if (!no_halves && ncu % 8 == 0 && rem > 0 && 2 * rem <= ncu) tail_slots = p.per_xcd - full_slots;
+  p.tail_split = (!no_quarters && 4 * rem <= ncu) ? 4 : 2;
   p.n_full = 8 * (p.per_xcd - tail_slots);
-  const int grid = p.n_full + 16 * tail_slots;
+  const int grid = p.n_full + 8 * p.tail_split * tail_slots;
   if (Kc % 64 == 0 && !narrow) {
     MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", (k_gemm_dma<NT, 64>), dim3(grid), dim3(512), 0, c.stream, p);
   } else {

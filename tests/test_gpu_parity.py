@@ -358,10 +358,11 @@ def test_register_staged_gemm_on_shapes_of_the_pipelined_one(env, monkeypatch):
     run_case(env, mixed_workload(K=320, N=256), seed=21)
 
 
-@pytest.mark.parametrize("var", ["MUX_GEMM_BK32", "MUX_GEMM_NO_HALF_TILES"])
+@pytest.mark.parametrize("var", ["MUX_GEMM_BK32", "MUX_GEMM_NO_HALF_TILES", "MUX_GEMM_NO_QUARTER_TILES"])
 def test_gemm_variants_in_a_fresh_process(env, var):
-    """The two switches that are read once per process (32-deep stages where 64-deep ones would be taken; no
-    half-width tiles for the last round): a parity case in a child process with the switch set."""
+    """The switches that are read once per process (32-deep stages where 64-deep ones would be taken; full tiles
+    only; half-width tiles where quarters would be taken for the last round): a parity case in a child process with
+    the switch set."""
     import os
     import subprocess
     import sys
