@@ -98,6 +98,32 @@ def test_kernel_choice_by_shape(env):
     run_case(env, wl, seed=4)
 
 
+@pytest.mark.parametrize("n_items", [16, 20, 23, 28])
+def test_gemm_last_round_pieces(env, n_items):
+    """The backbone GEMM cuts the tiles left after the last full round of workgroups (one per compute unit) into
+    quarters or halves, or leaves them whole, by how many there are.  With 256 compute units and 16 column tiles the
+    four row counts leave 0, 64, 112 and 192 tiles, forward and backward: nothing to cut, quarters, halves, whole
+    tiles.  Ragged row items, padding rows and every adapter kind lie in the cut tiles; compared on all rows and a
+    sample of the columns of Y and dX."""
+    mx, torch = env
+    K, N, chunk = 4096, 4096, 256
+    kinds = [(wlm.KIND_LORA, 16, 2.0), (wlm.KIND_IA3, 0, 1.0), (wlm.KIND_LORA, 40, 0.5), (wlm.KIND_NONE, 0, 1.0),
+             (wlm.KIND_ADAPTER, 24, 1.0)]
+    # one 256-row item per chunk; the last chunk of every task is partly padding (some with fewer than 128 rows)
+    per = [n_items // len(kinds) + (1 if i < n_items % len(kinds) else 0) for i in range(len(kinds))]
+    tails = [100, 256, 129, 7, 200]
+    tasks = [wlm.Task(k, r, sc, [chunk * (c - 1) + tails[i]]) for i, ((k, r, sc), c) in enumerate(zip(kinds, per))]
+    wl = wlm.Workload(name=f"pieces{n_items}", layers=[("w", K, N)], tasks=tasks, chunk=chunk, sigma_w=0.05, sigma_ab=0.05)
+    ot = oracle_table(wl)
+    assert ot.T == n_items * chunk
+    rng = np.random.default_rng(n_items)
+    cols = np.sort(rng.choice(N, 160, replace=False))
+    cols[:4] = [0, 127, 128, N - 1]
+    kcols = np.sort(rng.choice(K, 160, replace=False))
+    kcols[:4] = [0, 127, 128, K - 1]
+    run_case(env, wl, seed=n_items, cols=np.unique(cols), kcols=np.unique(kcols))
+
+
 def tuning_workload(K=192, N=160, chunk=32):
     """The additive bottleneck kind between the others: ragged ranks and token counts, padding, an empty task."""
     tasks = [wlm.Task(wlm.KIND_LORA, 16, 2.0, [100]), wlm.Task(wlm.KIND_ADAPTER, 8, 1.5, [70, 45]),
