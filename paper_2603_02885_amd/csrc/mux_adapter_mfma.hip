@@ -515,7 +515,7 @@ __global__ __launch_bounds__(256) void k_reduce(const int32_t* __restrict__ dtab
   if (mode == 1 ? tk.kind != MUX_ADAPTER_IA3_OUT : !ranked) return;
   if (tk.kind == MUX_ADAPTER_TUNING) K = N;    // its first gradient is dD_t [N][r]
   const int rows = mode == 1 ? 1 : tk.rank;
-  size_t e = (size_t)blockIdx.y * 256 + threadIdx.x;
+  size_t e = ((size_t)blockIdx.y * 256 + threadIdx.x) * 4;     // four consecutive elements of one row (N, K multiples of 4)
   const float* part = part0;
   int C = N;
   float* out = mode == 1 ? tk.dL : tk.dB;
@@ -530,13 +530,37 @@ __global__ __launch_bounds__(256) void k_reduce(const int32_t* __restrict__ dtab
   const int32_t* ti = dtab + dtab[DH_NITEMS0 + 3 * ts + 2] + 2 * t;
   const int ib = ti[0], ic = ti[1];
   const int32_t* items = dtab + dtab[DH_NITEMS0 + 3 * ts + 1];
-  float s = 0.f;
-  for (int q = 0; q < ic; ++q) {
-    if (items[(ib + q) * DI_WORDS + DI_NVALID] == 0) continue;
-    s += part[(size_t)(ib + q) * slot + (size_t)j * C + c];
+  // four items in flight (a thread that fetched them one by one would wait a memory latency per item); an item
+  // without valid rows holds no partial and adds an exact zero; the sum runs in ascending item order
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int q = 0; q < ic; q += 4) {
+    float4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const bool has = q + u < ic && items[(ib + q + u) * DI_WORDS + DI_NVALID] != 0;
+      v[u] = has ? *(const float4*)(part + (size_t)(ib + q + u) * slot + (size_t)j * C + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
   }
-  float* dst = transposed ? out + (size_t)c * rows + j : out + e;
-  *dst = accumulate ? *dst + s : s;
+  if (transposed) {
+    float* dst = out + (size_t)c * rows + j;
+    dst[0] = accumulate ? dst[0] + s.x : s.x;
+    dst[rows] = accumulate ? dst[rows] + s.y : s.y;
+    dst[2 * (size_t)rows] = accumulate ? dst[2 * (size_t)rows] + s.z : s.z;
+    dst[3 * (size_t)rows] = accumulate ? dst[3 * (size_t)rows] + s.w : s.w;
+  } else if (((uintptr_t)out & 15) == 0) {
+    float4* dst = (float4*)(out + e);
+    float4 o = s;
+    if (accumulate) { const float4 d = *dst; o.x += d.x; o.y += d.y; o.z += d.z; o.w += d.w; }
+    *dst = o;
+  } else {                                     // a gradient buffer of the caller that is only 4-byte aligned
+    float* dst = out + e;
+    dst[0] = accumulate ? dst[0] + s.x : s.x;
+    dst[1] = accumulate ? dst[1] + s.y : s.y;
+    dst[2] = accumulate ? dst[2] + s.z : s.z;
+    dst[3] = accumulate ? dst[3] + s.w : s.w;
+  }
 }
 
 void launch_grad(const CallCtx& c, const char* name, const GradParams& p, dim3 grid) {
@@ -613,13 +637,13 @@ mux_status adapter_grads(const CallCtx& c, const void* X, const void* dY, const 
     const int cmax = c.N > c.K ? c.N : c.K;
     launch_grad(c, "grad_dbda", p, dim3((unsigned)n_items, (cmax + 255) / 256, 2));
     const size_t elems = (size_t)c.st->r_max * ((size_t)c.N + K1);
-    MUX_LAUNCH("reduce_dbda", k_reduce, dim3(M, (unsigned)((elems + 255) / 256)), dim3(256), 0, c.stream, c.dtab, c.dtasks,
+    MUX_LAUNCH("reduce_dbda", k_reduce, dim3(M, (unsigned)((elems + 1023) / 1024)), dim3(256), 0, c.stream, c.dtab, c.dtasks,
                (const float*)part0, (const float*)part1, c.N, c.K, c.RP, ts, 0, accumulate, p.slot[0], p.slot[1]);
   }
   if (c.st->n_ia3 > 0) {
     MUX_LAUNCH("grad_dl", k_dl, dim3((unsigned)c.st->items[TS64].size(), (c.N + 1023) / 1024), dim3(128), 0, c.stream,
                c.dtab, c.dtasks, (const bf16_t*)dY, (const bf16_t*)Z, (float*)part, (bf16_t*)c.dYs, c.N);
-    MUX_LAUNCH("reduce_dl", k_reduce, dim3(M, (c.N + 255) / 256), dim3(256), 0, c.stream, c.dtab, c.dtasks,
+    MUX_LAUNCH("reduce_dl", k_reduce, dim3(M, (c.N + 1023) / 1024), dim3(256), 0, c.stream, c.dtab, c.dtasks,
                (const float*)part, (const float*)nullptr, c.N, c.K, 1, TS64, 1, accumulate, (size_t)c.N, (size_t)0);
   }
   return MUX_OK;
