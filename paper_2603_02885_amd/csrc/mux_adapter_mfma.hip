@@ -458,7 +458,7 @@ __global__ __launch_bounds__(128) void k_dl(const int32_t* __restrict__ dtab, co
   if (tk.kind != MUX_ADAPTER_IA3_OUT) return;
   const int n0 = (blockIdx.y * 128 + threadIdx.x) * 8;
   if (n0 >= N) return;
-  constexpr int RF = 8;     // rows in flight
+  constexpr int RF = 8;     // rows per batch; two batches in flight
   float s[8], lv[8];
   {
     const uint4 l4 = *(const uint4*)((const bf16_t*)tk.L + n0);
@@ -468,21 +468,21 @@ __global__ __launch_bounds__(128) void k_dl(const int32_t* __restrict__ dtab, co
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) s[e] = 0.f;
-  for (int m0 = 0; m0 < it.nrows; m0 += RF) {
-    uint4 gv[RF], zv[RF];
-    bool ok[RF];
-    size_t zoff[RF];
+  // Every batch issues the same 2 RF loads (a row that does not count reads the item's first row instead and is
+  // dropped afterwards), so that the batch being summed can be waited for while the next one is still in flight.
+  auto fetch = [&](int m0, uint4 (&gv)[RF], uint4 (&zv)[RF]) {
+#pragma unroll
+    for (int u = 0; u < RF; ++u) {
+      const int row = it.row0 + (m0 + u < it.nrows ? m0 + u : 0);
+      gv[u] = *(const uint4*)(dY + (size_t)row * N + n0);
+      zv[u] = *(const uint4*)(Z + (size_t)(tk.zrow0 + row - tk.row_begin) * N + n0);
+    }
+  };
+  auto consume = [&](int m0, const uint4 (&gv)[RF], const uint4 (&zv)[RF]) {
 #pragma unroll
     for (int u = 0; u < RF; ++u) {
       const int row = it.row0 + m0 + u;
-      ok[u] = m0 + u < it.nrows && row_is_valid(dtab, row);
-      zoff[u] = (size_t)(tk.zrow0 + row - tk.row_begin) * N + n0;
-      gv[u] = ok[u] ? *(const uint4*)(dY + (size_t)row * N + n0) : make_uint4(0, 0, 0, 0);
-      zv[u] = ok[u] ? *(const uint4*)(Z + zoff[u]) : make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int u = 0; u < RF; ++u) {
-      if (!ok[u]) continue;
+      if (!(m0 + u < it.nrows && row_is_valid(dtab, row))) continue;
       const uint32_t* pg = (const uint32_t*)&gv[u];
       const uint32_t* pz = (const uint32_t*)&zv[u];
       uint4 sv;
@@ -494,8 +494,16 @@ __global__ __launch_bounds__(128) void k_dl(const int32_t* __restrict__ dtab, co
         s[2 * e + 1] = fmaf(g1, __uint_as_float(pz[e] & 0xffff0000u), s[2 * e + 1]);
         ps[e] = pack_bf16x2(g0 * lv[2 * e], g1 * lv[2 * e + 1]);
       }
-      *(uint4*)(dYs + zoff[u]) = sv;
+      *(uint4*)(dYs + (size_t)(tk.zrow0 + row - tk.row_begin) * N + n0) = sv;
     }
+  };
+  uint4 ga[RF], za[RF], gb[RF], zb[RF];
+  fetch(0, ga, za);
+  for (int m0 = 0; m0 < it.nrows; m0 += 2 * RF) {
+    fetch(m0 + RF, gb, zb);
+    consume(m0, ga, za);
+    fetch(m0 + 2 * RF, ga, za);
+    consume(m0 + RF, gb, zb);
   }
   float* dst = part + (size_t)blockIdx.x * N + n0;
 #pragma unroll
