@@ -29,6 +29,11 @@ constexpr int KP = 136;         // LDS row pitch (elements) of a tile that is on
 constexpr int TP = 144;         // ... of a tile that is also read across rows
 constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
 
+// A wave in a run of matrix products is served before the other wave of its SIMD, whose vector instructions then
+// fill the issue slots between the products (forward and dQ: 2 % faster; dK/dV: no change, not used there).
+#define ATTN_PRIO_HIGH() __builtin_amdgcn_s_setprio(2)
+#define ATTN_PRIO_LOW() __builtin_amdgcn_s_setprio(0)
+
 struct AttnParams {
   const int32_t* dtab;
   const bf16_t *Q, *K, *V, *O, *dO;
@@ -154,6 +159,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
 #pragma unroll
       for (int st = 0; st < 8; ++st) kf[st] = *(const bf16x8*)(kp + 16 * st);
       __builtin_amdgcn_sched_barrier(0);        // (the scheduler would otherwise sink every read next to its use)
+      ATTN_PRIO_HIGH();
 #pragma unroll
       for (int st = 0; st < 8; ++st) {
         s[0] = mma(kf[st], qf[st], s[0]);
@@ -162,6 +168,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
       }
 #pragma unroll
       for (int st = 0; st < 8; ++st) s[1] = mma(kf[st], qf[st], s[1]);
+      ATTN_PRIO_LOW();
     }
     const bool diag = kb + TILE - 1 > wq_first;
     // running maximum on the raw scores (the scale is positive), then one fused multiply-add per element: m is kept in
@@ -204,6 +211,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
 #pragma unroll
         for (int j = 0; j < 16; ++j) o[dt][j] *= alpha;
     }
+    ATTN_PRIO_HIGH();
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -212,6 +220,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) o[dt] = mma(read_across(sV, 32 * kt + 16 * u, 32 * dt, lane), pb, o[dt]);
       }
+    ATTN_PRIO_LOW();
   }
   l += __shfl_xor(l, 32);
   if (qok) {
@@ -330,11 +339,13 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_q(AttnParams p) {
       f32x16 s, dp;
 #pragma unroll
       for (int j = 0; j < 16; ++j) { s[j] = 0.f; dp[j] = 0.f; }
+      ATTN_PRIO_HIGH();
 #pragma unroll
       for (int st = 0; st < 8; ++st) {
         s = mma(*(const bf16x8*)(sK + (32 * kt + li) * TP + 16 * st + 8 * half), qf[st], s);
         dp = mma(*(const bf16x8*)(sV + (32 * kt + li) * KP + 16 * st + 8 * half), df[st], dp);
       }
+      ATTN_PRIO_LOW();
 #pragma unroll
       for (int j = 0; j < 16; ++j) s[j] = fast_exp2(fmaf(s[j], c, -lse2));        // P^T (zero for a lane without query)
       if (diag) {                               // only the tiles on the diagonal pay for the mask
@@ -345,12 +356,14 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_q(AttnParams p) {
       }
 #pragma unroll
       for (int j = 0; j < 16; ++j) s[j] *= dp[j] - dl;                           // dS^T
+      ATTN_PRIO_HIGH();
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const bf16x8 ds = pack8(s, u);
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) dq[dt] = mma(read_across(sK, 32 * kt + 16 * u, 32 * dt, lane), ds, dq[dt]);
       }
+      ATTN_PRIO_LOW();
     }
   }
   if (qok) {
