@@ -18,6 +18,10 @@
 //     [rows][BK] tiles by row bits, the forward's [BK][256] tile of W by k bits.
 //   * one workgroup barrier per K-tile, placed before the last MFMA step: by then every read of
 //     the current stage is done (it may be refilled) and the next tile has landed (it may be read).
+//   * one workgroup per compute unit at a time; the tiles left over after the last full round of workgroups are
+//     cut into two 256x128 halves or four 128x128 quarters (four waves, four 32 KB stages) at the end of the
+//     same launch, so that they occupy the compute units once more instead of a fraction of them for a whole
+//     tile time.
 // Every stage is its own __shared__ array so that the compiler's wait-count insertion can tell
 // the stage being filled from the stage being read.
 #include <cstdlib>
