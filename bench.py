@@ -52,7 +52,9 @@ def parse():
                          "the cost model's predictions with measured steps")
     ap.add_argument("--attention", action="store_true",
                     help="instead of the benchmark line: the attention step between the q/k/v and o projections on the "
-                         "sequences of the chosen workload (heads of 128, as many as the q projection is wide)")
+                         "sequences of the chosen workload (heads of --head-dim, as many as the q projection is wide)")
+    ap.add_argument("--head-dim", type=int, default=128,
+                    help="with --attention: head dimension (64, 80, 96 or 128); heads = projection width / head dimension")
     ap.add_argument("--dispatch", action="store_true",
                     help="instead of the benchmark line: Dispatch of the chosen workload's tokens (packed per task <-> "
                          "aligned batch) at the width of the first projection's input, in GB/s")
@@ -351,8 +353,11 @@ def attention(mx, torch, args):
     import numpy as np
     wl = wlm.config(args.workload, seed=args.seed)
     dev = "cuda:0"
-    d = 128
-    H = wl.layers[0][2] // d
+    d = args.head_dim
+    width = wl.layers[0][2]
+    if d not in (64, 80, 96, 128) or width % d:
+        raise SystemExit(f"--head-dim {d}: must be 64, 80, 96 or 128 and divide the projection width {width}")
+    H = width // d
     st = mx.mux_segtab_build([mx.TaskDesc(t.kind, t.rank, t.scale, t.seq_lens) for t in wl.tasks], wl.chunk,
                              wl.max_pack_len, 0)
     T = mx.mux_segtab_rows(st)

@@ -14,7 +14,7 @@
  * h*head_dim ..), so the three slices of a fused QKV buffer can be passed as they are.  n_kv_heads divides n_heads
  * (grouped-query attention: query head h reads key/value head h / (n_heads / n_kv_heads); dK, dV collect the
  * contributions of every query head of the group).  Rows of padding are written as zero in every output.
- * Supported now: MUX_DT_BF16, head_dim 128, leading dimensions that are multiples of 8 and 16-byte aligned
+ * Supported now: MUX_DT_BF16, head_dim 64, 80, 96 or 128, leading dimensions that are multiples of 8 and 16-byte aligned
  * pointers; anything else returns MUX_ERR_UNSUPPORTED and launches nothing.
  */
 #ifndef MUX_ATTN_H_
@@ -32,7 +32,7 @@ extern "C" {
 typedef struct {
   int32_t n_heads;
   int32_t n_kv_heads; /* divides n_heads */
-  int32_t head_dim;   /* 128 */
+  int32_t head_dim;   /* 64, 80, 96 or 128 */
   int32_t dtype;      /* MUX_DT_BF16 */
   float scale;        /* 0: 1 / sqrt(head_dim) */
   int64_t ldq, ldk, ldv, ldo; /* elements between rows of Q (and dQ), K (and dK), V (and dV), O (and dO) */

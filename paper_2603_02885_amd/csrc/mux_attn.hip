@@ -22,11 +22,18 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int D = 128;          // head dimension
 constexpr int BLK = kAttnBlockRows;
 constexpr int TILE = 64;        // tokens of the other side staged per step
-constexpr int KP = 136;         // LDS row pitch (elements) of a tile that is only read along rows
-constexpr int TP = 144;         // ... of a tile that is also read across rows
+// What follows from the head dimension D (a multiple of 16 up to 128; built for 64, 80, 96 and 128).
+template <int D>
+struct Dim {
+  static_assert(D % 16 == 0 && D >= 32 && D <= 128, "head dimension");
+  static constexpr int KS = D / 16;          // contraction steps of 16 over the head dimension
+  static constexpr int DT = (D + 31) / 32;   // 32-column tiles of an output row (the last may be half used)
+  static constexpr int DP = 32 * DT;         // columns of a staged tile; those from D on stay zero
+  static constexpr int KP = DP + 8;          // LDS row pitch (elements) of a tile that is only read along rows
+  static constexpr int TP = DP + 16;         // ... of a tile that is also read across rows
+};
 constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
 
 // A wave in a run of matrix products is served before the other wave of its SIMD, whose vector instructions then
@@ -64,6 +71,7 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int u) {
   return __builtin_bit_cast(bf16x8, r);
 }
 // A operand read across the rows of a row-major tile: column c0 + lane % 32, the 8 rows 4h + {0..3}, 8 + 4h + {0..3} from row0
+template <int TP>
 __device__ __forceinline__ bf16x8 read_across(const bf16_t* tile, int row0, int c0, int lane) {
   const int j = lane & 15, grp = lane >> 4;
   const bf16_t* p = tile + (row0 + 4 * (grp >> 1) + (j >> 2)) * TP + c0 + 16 * (grp & 1) + 4 * (j & 3);
@@ -88,24 +96,57 @@ __device__ __forceinline__ void work_item(int n_blocks, int n_heads, int& block,
   }
 }
 
-// 64 rows x 128 columns of one head from global memory (rows past `limit` read as zero) into registers, then LDS
-struct TileLoad {
-  uint4 r[4];
+// ROWS rows x D columns of one head from global memory (rows past `limit` read as zero) into registers, then LDS.
+// The tile is cut into 16-byte pieces, D / 8 a row.  Where the pieces of a row divide evenly among the 256 / ROWS
+// threads that a row can have, a thread takes consecutive pieces of one row (one address, constant offsets);
+// otherwise the 256 threads take the pieces of the tile in order, 256 at a time.
+template <int ROWS, int D>
+struct TileLoadT {
+  static constexpr int PPR = D / 8, NP = ROWS * PPR, TPR = 256 / ROWS;
+  static constexpr bool RUNS = PPR % TPR == 0;
+  static constexpr int N = RUNS ? PPR / TPR : (NP + 255) / 256;
+  uint4 r[N];
   __device__ __forceinline__ void load(const bf16_t* base, int64_t ld, int first, int row0, int limit, int hc, int tid) {
-    const int row = row0 + (tid >> 2);
-    const uint4* src = (const uint4*)(base + (size_t)(first + row) * ld + hc + (tid & 3) * 32);
+    if (RUNS) {
+      const int row = row0 + tid / TPR;
+      const uint4* src = (const uint4*)(base + (size_t)(first + row) * ld + hc + (tid % TPR) * (8 * N));
 #pragma unroll
-    for (int i = 0; i < 4; ++i) r[i] = row < limit ? src[i] : uint4{0u, 0u, 0u, 0u};
+      for (int i = 0; i < N; ++i) r[i] = row < limit ? src[i] : uint4{0u, 0u, 0u, 0u};
+    } else {
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        const int e = tid + 256 * i, row = row0 + e / PPR, pc = e % PPR;
+        const bool ok = (NP % 256 == 0 || e < NP) && row < limit;
+        r[i] = ok ? *(const uint4*)(base + (size_t)(first + row) * ld + hc + pc * 8) : uint4{0u, 0u, 0u, 0u};
+      }
+    }
   }
   __device__ __forceinline__ void store(bf16_t* tile, int pitch, int tid) const {
-    uint4* dst = (uint4*)(tile + (tid >> 2) * pitch + (tid & 3) * 32);
+    if (RUNS) {
+      uint4* dst = (uint4*)(tile + (tid / TPR) * pitch + (tid % TPR) * (8 * N));
 #pragma unroll
-    for (int i = 0; i < 4; ++i) dst[i] = r[i];
+      for (int i = 0; i < N; ++i) dst[i] = r[i];
+    } else {
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        const int e = tid + 256 * i;
+        if (NP % 256 == 0 || e < NP) *(uint4*)(tile + (e / PPR) * pitch + (e % PPR) * 8) = r[i];
+      }
+    }
   }
 };
+// Zero in the columns D .. DP-1 of a staged tile of `rows` rows (nothing is ever stored there afterwards).
+template <int D, int DP>
+__device__ __forceinline__ void zero_pad_columns(bf16_t* tile, int rows, int pitch, int tid) {
+  if (DP > D)
+    for (int e = tid; e < rows * ((DP - D) / 8); e += 256)
+      *(uint4*)(tile + (e / ((DP - D) / 8)) * pitch + D + (e % ((DP - D) / 8)) * 8) = uint4{0u, 0u, 0u, 0u};
+}
 
 // ------------------------------------------------------------------------------------------------ forward
+template <int D>
 __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
+  constexpr int KS = Dim<D>::KS, DT = Dim<D>::DT, DP = Dim<D>::DP, KP = Dim<D>::KP, TP = Dim<D>::TP;
   __shared__ __align__(16) bf16_t sK[TILE * KP];
   __shared__ __align__(16) bf16_t sV[TILE * TP];
   int wi_block, wi_head;
@@ -116,15 +157,16 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, half = lane >> 5;
   const int ql = q0 + 32 * wave + li;          // this lane's query inside the sequence
   const bool qok = ql < len;
-  bf16x8 qf[8];
+  zero_pad_columns<D, DP>(sV, TILE, TP, tid);
+  bf16x8 qf[KS];
   {
     const bf16_t* qrow = p.Q + (size_t)(first + ql) * p.ldq + hc + 8 * half;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) qf[s] = qok ? *(const bf16x8*)(qrow + 16 * s) : zero8();
+    for (int s = 0; s < KS; ++s) qf[s] = qok ? *(const bf16x8*)(qrow + 16 * s) : zero8();
   }
-  f32x16 o[4];
+  f32x16 o[DT];
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+  for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
     for (int j = 0; j < 16; ++j) o[dt][j] = 0.f;
   float m = -INFINITY, m_prev = -INFINITY, l = 0.f;
@@ -132,7 +174,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
   const float lazy = 8.f / c;                   // 8 in the exponent, in units of the raw score
   const int kend = min(len, q0 + BLK);          // keys [0, kend) are visible to some query of the block
   const int wq_first = q0 + 32 * wave, wq_last = wq_first + 31;
-  TileLoad tk, tv;
+  TileLoadT<TILE, D> tk, tv;
   const int hck = wi_head / (p.H / p.Hkv) * D;  // this head's key/value columns
   tk.load(p.K, p.ldk, first, 0, len, hck, tid);
   tv.load(p.V, p.ldv, first, 0, len, hck, tid);
@@ -152,22 +194,22 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
 #pragma unroll
       for (int j = 0; j < 16; ++j) s[kt][j] = 0.f;
     {
-      // the eight K fragments of the first 32 keys are fetched up front; each is refilled for the second 32 keys as
-      // soon as its product is issued, so that an LDS read has seven products to land behind
+      // the K fragments of the first 32 keys are fetched up front; each is refilled for the second 32 keys as
+      // soon as its product is issued, so that an LDS read has the other products to land behind
       const bf16_t* kp = sK + li * KP + 8 * half;
-      bf16x8 kf[8];
+      bf16x8 kf[KS];
 #pragma unroll
-      for (int st = 0; st < 8; ++st) kf[st] = *(const bf16x8*)(kp + 16 * st);
+      for (int st = 0; st < KS; ++st) kf[st] = *(const bf16x8*)(kp + 16 * st);
       __builtin_amdgcn_sched_barrier(0);        // (the scheduler would otherwise sink every read next to its use)
       ATTN_PRIO_HIGH();
 #pragma unroll
-      for (int st = 0; st < 8; ++st) {
+      for (int st = 0; st < KS; ++st) {
         s[0] = mma(kf[st], qf[st], s[0]);
         kf[st] = *(const bf16x8*)(kp + 32 * KP + 16 * st);
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
-      for (int st = 0; st < 8; ++st) s[1] = mma(kf[st], qf[st], s[1]);
+      for (int st = 0; st < KS; ++st) s[1] = mma(kf[st], qf[st], s[1]);
       ATTN_PRIO_LOW();
     }
     const bool diag = kb + TILE - 1 > wq_first;
@@ -207,7 +249,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
     l = l * alpha + rs;
     if (__any(alpha != 1.f)) {                  // the running maximum of some query moved
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
+      for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int j = 0; j < 16; ++j) o[dt][j] *= alpha;
     }
@@ -218,7 +260,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
       for (int u = 0; u < 2; ++u) {
         const bf16x8 pb = pack8(s[kt], u);
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) o[dt] = mma(read_across(sV, 32 * kt + 16 * u, 32 * dt, lane), pb, o[dt]);
+        for (int dt = 0; dt < DT; ++dt) o[dt] = mma(read_across<TP>(sV, 32 * kt + 16 * u, 32 * dt, lane), pb, o[dt]);
       }
     ATTN_PRIO_LOW();
   }
@@ -227,9 +269,10 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd(AttnParams p) {
     const float inv = 1.f / l;
     bf16_t* orow = p.Out + (size_t)(first + ql) * p.ldo + hc;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int jg = 0; jg < 4; ++jg) {
+        if (32 * dt + 8 * jg >= D) continue;      // the unused half of the last 32 columns
         uint2 v;
         v.x = pack_bf16x2(o[dt][4 * jg + 0] * inv, o[dt][4 * jg + 1] * inv);
         v.y = pack_bf16x2(o[dt][4 * jg + 2] * inv, o[dt][4 * jg + 3] * inv);
@@ -265,6 +308,7 @@ __global__ __launch_bounds__(256) void k_attn_zero_pad(ZeroParams p) {
 }
 
 // delta[h][row] = sum_d dO[row][h, d] * O[row][h, d] for the rows of sequences.  One thread per (row, head).
+template <int D>
 __global__ __launch_bounds__(256) void k_attn_delta(AttnParams p) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= (size_t)p.T * p.H) return;
@@ -288,7 +332,9 @@ __global__ __launch_bounds__(256) void k_attn_delta(AttnParams p) {
 }
 
 // ------------------------------------------------------------------------------------------------ dQ
+template <int D>
 __global__ __launch_bounds__(256, 2) void k_attn_bwd_q(AttnParams p) {
+  constexpr int KS = Dim<D>::KS, DT = Dim<D>::DT, DP = Dim<D>::DP, KP = Dim<D>::KP, TP = Dim<D>::TP;
   __shared__ __align__(16) bf16_t sK[TILE * TP];
   __shared__ __align__(16) bf16_t sV[TILE * KP];
   int wi_block, wi_head;
@@ -299,12 +345,13 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_q(AttnParams p) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, half = lane >> 5;
   const int ql = q0 + 32 * wave + li;
   const bool qok = ql < len;
-  bf16x8 qf[8], df[8];
+  zero_pad_columns<D, DP>(sK, TILE, TP, tid);
+  bf16x8 qf[KS], df[KS];
   {
     const bf16_t* qrow = p.Q + (size_t)(first + ql) * p.ldq + hc + 8 * half;
     const bf16_t* drow = p.dO + (size_t)(first + ql) * p.ldo + hc + 8 * half;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
+    for (int s = 0; s < KS; ++s) {
       qf[s] = qok ? *(const bf16x8*)(qrow + 16 * s) : zero8();
       df[s] = qok ? *(const bf16x8*)(drow + 16 * s) : zero8();
     }
@@ -312,14 +359,14 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_q(AttnParams p) {
   const float c = p.scale * LOG2E;
   const float lse2 = qok ? p.lse[(size_t)wi_head * p.T + first + ql] * LOG2E : INFINITY;    // exp2(x - inf) = 0
   const float dl = qok ? p.delta[(size_t)wi_head * p.T + first + ql] : 0.f;
-  f32x16 dq[4];
+  f32x16 dq[DT];
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+  for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
     for (int j = 0; j < 16; ++j) dq[dt][j] = 0.f;
   const int kend = min(len, q0 + BLK);
   const int wq_first = q0 + 32 * wave, wq_last = wq_first + 31;
-  TileLoad tk, tv;
+  TileLoadT<TILE, D> tk, tv;
   const int hck = wi_head / (p.H / p.Hkv) * D;  // this head's key/value columns
   tk.load(p.K, p.ldk, first, 0, len, hck, tid);
   tv.load(p.V, p.ldv, first, 0, len, hck, tid);
@@ -341,7 +388,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_q(AttnParams p) {
       for (int j = 0; j < 16; ++j) { s[j] = 0.f; dp[j] = 0.f; }
       ATTN_PRIO_HIGH();
 #pragma unroll
-      for (int st = 0; st < 8; ++st) {
+      for (int st = 0; st < KS; ++st) {
         s = mma(*(const bf16x8*)(sK + (32 * kt + li) * TP + 16 * st + 8 * half), qf[st], s);
         dp = mma(*(const bf16x8*)(sV + (32 * kt + li) * KP + 16 * st + 8 * half), df[st], dp);
       }
@@ -361,7 +408,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_q(AttnParams p) {
       for (int u = 0; u < 2; ++u) {
         const bf16x8 ds = pack8(s, u);
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) dq[dt] = mma(read_across(sK, 32 * kt + 16 * u, 32 * dt, lane), ds, dq[dt]);
+        for (int dt = 0; dt < DT; ++dt) dq[dt] = mma(read_across<TP>(sK, 32 * kt + 16 * u, 32 * dt, lane), ds, dq[dt]);
       }
       ATTN_PRIO_LOW();
     }
@@ -369,9 +416,10 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_q(AttnParams p) {
   if (qok) {
     bf16_t* orow = p.dQ + (size_t)(first + ql) * p.ldq + hc;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int jg = 0; jg < 4; ++jg) {
+        if (32 * dt + 8 * jg >= D) continue;      // the unused half of the last 32 columns
         uint2 v;
         v.x = pack_bf16x2(dq[dt][4 * jg + 0] * p.scale, dq[dt][4 * jg + 1] * p.scale);
         v.y = pack_bf16x2(dq[dt][4 * jg + 2] * p.scale, dq[dt][4 * jg + 3] * p.scale);
@@ -381,22 +429,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_q(AttnParams p) {
 }
 
 // ------------------------------------------------------------------------------------------------ dK, dV
-// 32 rows x 128 columns of one head: thread t carries 32 bytes of row t / 8
-struct TileLoad32 {
-  uint4 r[2];
-  __device__ __forceinline__ void load(const bf16_t* base, int64_t ld, int first, int row0, int limit, int hc, int tid) {
-    const int row = row0 + (tid >> 3);
-    const uint4* src = (const uint4*)(base + (size_t)(first + row) * ld + hc + (tid & 7) * 16);
-    r[0] = row < limit ? src[0] : uint4{0u, 0u, 0u, 0u};
-    r[1] = row < limit ? src[1] : uint4{0u, 0u, 0u, 0u};
-  }
-  __device__ __forceinline__ void store(bf16_t* tile, int pitch, int tid) const {
-    uint4* dst = (uint4*)(tile + (tid >> 3) * pitch + (tid & 7) * 16);
-    dst[0] = r[0]; dst[1] = r[1];
-  }
-};
-
+template <int D>
 __global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
+  constexpr int KS = Dim<D>::KS, DT = Dim<D>::DT, DP = Dim<D>::DP, KP = Dim<D>::KP, TP = Dim<D>::TP;
   constexpr int QT = 32;                       // queries staged per step
   __shared__ __align__(16) bf16_t sQ[QT * TP];
   __shared__ __align__(16) bf16_t sD[QT * TP];
@@ -411,12 +446,14 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, half = lane >> 5;
   const int kl = k0 + 32 * wave + li;          // this lane's key inside the sequence
   const bool kok = kl < len;
-  bf16x8 kf[8];
+  zero_pad_columns<D, DP>(sQ, QT, TP, tid);
+  zero_pad_columns<D, DP>(sD, QT, TP, tid);
+  bf16x8 kf[KS];
   {
     const bf16_t* krow = p.K + (size_t)(first + kl) * p.ldk + hc + 8 * half;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) kf[s] = kok ? *(const bf16x8*)(krow + 16 * s) : zero8();
-    TileLoad t;
+    for (int s = 0; s < KS; ++s) kf[s] = kok ? *(const bf16x8*)(krow + 16 * s) : zero8();
+    TileLoadT<TILE, D> t;
     t.load(p.V, p.ldv, first, k0, len, hc, tid);
     t.store(sVf, KP, tid);
     t.load(p.V, p.ldv, first, k0 + TILE, len, hc, tid);
@@ -424,13 +461,13 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
   }
   const bf16_t* vfrag = sVf + (32 * wave + li) * KP + 8 * half;
   const float c = p.scale * LOG2E;
-  f32x16 dk[4], dv[4];
+  f32x16 dk[DT], dv[DT];
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+  for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
     for (int j = 0; j < 16; ++j) { dk[dt][j] = 0.f; dv[dt][j] = 0.f; }
   const int wk_first = k0 + 32 * wave;
-  TileLoad32 tq, td;
+  TileLoadT<QT, D> tq, td;
   float r_lse = 0.f, r_delta = 0.f;
   for (int g = 0; g < group; ++g) {             // every query head that reads this key/value head
   const int hq = wi_head * group + g, hcq = hq * D;
@@ -463,7 +500,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
 #pragma unroll
       for (int j = 0; j < 16; ++j) { s[j] = 0.f; dp[j] = 0.f; }
 #pragma unroll
-      for (int st = 0; st < 8; ++st) {
+      for (int st = 0; st < KS; ++st) {
         s = mma(*(const bf16x8*)(sQ + (32 * qt + li) * TP + 16 * st + 8 * half), kf[st], s);
         dp = mma(*(const bf16x8*)(sD + (32 * qt + li) * TP + 16 * st + 8 * half), *(const bf16x8*)(vfrag + 16 * st), dp);
         if (st % 2 == 1) __builtin_amdgcn_sched_barrier(0);
@@ -483,9 +520,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
       for (int u = 0; u < 2; ++u) {
         const bf16x8 pb = pack8(s, u), ds = pack8(dp, u);
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-          dv[dt] = mma(read_across(sD, 32 * qt + 16 * u, 32 * dt, lane), pb, dv[dt]);
-          dk[dt] = mma(read_across(sQ, 32 * qt + 16 * u, 32 * dt, lane), ds, dk[dt]);
+        for (int dt = 0; dt < DT; ++dt) {
+          dv[dt] = mma(read_across<TP>(sD, 32 * qt + 16 * u, 32 * dt, lane), pb, dv[dt]);
+          dk[dt] = mma(read_across<TP>(sQ, 32 * qt + 16 * u, 32 * dt, lane), ds, dk[dt]);
         }
         __builtin_amdgcn_sched_barrier(0);      // keeps the operand reads of the next group from piling up in registers
       }
@@ -496,9 +533,10 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_kv(AttnParams p) {
     bf16_t* krow = p.dK + (size_t)(first + kl) * p.ldk + hc;
     bf16_t* vrow = p.dV + (size_t)(first + kl) * p.ldv + hc;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int jg = 0; jg < 4; ++jg) {
+        if (32 * dt + 8 * jg >= D) continue;      // the unused half of the last 32 columns
         uint2 a, b;
         a.x = pack_bf16x2(dk[dt][4 * jg + 0] * p.scale, dk[dt][4 * jg + 1] * p.scale);
         a.y = pack_bf16x2(dk[dt][4 * jg + 2] * p.scale, dk[dt][4 * jg + 3] * p.scale);
@@ -514,8 +552,9 @@ mux_status check(const char* fn, const mux_attn_desc* d, const mux_segtab* st) {
   if (!d || !st) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": null descriptor or table");
   if (d->n_heads < 1 || d->n_kv_heads < 1 || d->head_dim < 1) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": bad head counts");
   if (d->n_heads % d->n_kv_heads) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": n_kv_heads must divide n_heads");
-  if (d->dtype != MUX_DT_BF16 || d->head_dim != D)
-    return fail(MUX_ERR_UNSUPPORTED, std::string(fn) + ": only bf16 and head_dim 128 are built");
+  const int D = d->head_dim;
+  if (d->dtype != MUX_DT_BF16 || (D != 64 && D != 80 && D != 96 && D != 128))
+    return fail(MUX_ERR_UNSUPPORTED, std::string(fn) + ": only bf16 and head_dim 64, 80, 96 and 128 are built");
   const int64_t w = (int64_t)d->n_heads * D, wkv = (int64_t)d->n_kv_heads * D;
   const int64_t lds[4] = {d->ldq, d->ldk, d->ldv, d->ldo};
   for (int i = 0; i < 4; ++i) {
@@ -530,6 +569,15 @@ mux_status check(const char* fn, const mux_attn_desc* d, const mux_segtab* st) {
 }
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+// One launch of kernel template K<D> for the head dimension of the call.
+#define ATTN_LAUNCH(name, K, D, grid, stream, p)                                           \
+  do {                                                                                     \
+    if ((D) == 128) MUX_LAUNCH(name, K<128>, grid, dim3(256), 0, stream, p);               \
+    else if ((D) == 96) MUX_LAUNCH(name, K<96>, grid, dim3(256), 0, stream, p);            \
+    else if ((D) == 80) MUX_LAUNCH(name, K<80>, grid, dim3(256), 0, stream, p);            \
+    else MUX_LAUNCH(name, K<64>, grid, dim3(256), 0, stream, p);                           \
+  } while (0)
 
 mux_status last_hip(const char* fn) {
   hipError_t e = hipGetLastError();
@@ -561,6 +609,7 @@ extern "C" mux_status mux_attn_forward(const mux_attn_desc* desc, const mux_segt
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O))
     return fail(MUX_ERR_UNSUPPORTED, std::string(fn) + ": pointers must be 16-byte aligned");
   hipStream_t stream = (hipStream_t)hip_stream;
+  const int D = desc->head_dim;
   AttnParams p{};
   p.dtab = (const int32_t*)dev_segtab;
   p.Q = (const bf16_t*)Q; p.K = (const bf16_t*)K; p.V = (const bf16_t*)V; p.Out = (bf16_t*)O;
@@ -572,7 +621,7 @@ extern "C" mux_status mux_attn_forward(const mux_attn_desc* desc, const mux_segt
   z.dtab = p.dtab; z.out[0] = (bf16_t*)O; z.ld[0] = desc->ldo; z.n_out = 1; z.width[0] = desc->n_heads * D;
   MUX_LAUNCH("attn_zero_pad", k_attn_zero_pad, dim3((unsigned)st->items[0].size(), (unsigned)((z.width[0] + 2047) / 2048)), dim3(256), 0, stream, z);
   if (st->n_attn_blocks > 0)
-    MUX_LAUNCH("attn_fwd", k_attn_fwd, dim3((unsigned)st->n_attn_blocks * (unsigned)desc->n_heads), dim3(256), 0, stream, p);
+    ATTN_LAUNCH("attn_fwd", k_attn_fwd, D, dim3((unsigned)st->n_attn_blocks * (unsigned)desc->n_heads), stream, p);
   return last_hip(fn);
 }
 
@@ -590,6 +639,7 @@ extern "C" mux_status mux_attn_backward(const mux_attn_desc* desc, const mux_seg
     if (!aligned16(q)) return fail(MUX_ERR_UNSUPPORTED, std::string(fn) + ": pointers must be 16-byte aligned");
   if (ws_bytes < mux_attn_workspace_bytes(desc, st)) return fail(MUX_ERR_WORKSPACE, std::string(fn) + ": workspace too small");
   hipStream_t stream = (hipStream_t)hip_stream;
+  const int D = desc->head_dim;
   AttnParams p{};
   p.dtab = (const int32_t*)dev_segtab;
   p.Q = (const bf16_t*)Q; p.K = (const bf16_t*)K; p.V = (const bf16_t*)V; p.O = (const bf16_t*)O; p.dO = (const bf16_t*)dO;
@@ -604,10 +654,10 @@ extern "C" mux_status mux_attn_backward(const mux_attn_desc* desc, const mux_seg
   z.out[0] = p.dQ; z.ld[0] = desc->ldq; z.out[1] = p.dK; z.ld[1] = desc->ldk; z.out[2] = p.dV; z.ld[2] = desc->ldv;
   MUX_LAUNCH("attn_zero_pad", k_attn_zero_pad, dim3((unsigned)st->items[0].size(), (unsigned)((z.width[0] + 2047) / 2048)), dim3(256), 0, stream, z);
   const size_t n = (size_t)st->T * desc->n_heads;
-  MUX_LAUNCH("attn_delta", k_attn_delta, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p);
+  ATTN_LAUNCH("attn_delta", k_attn_delta, D, dim3((unsigned)((n + 255) / 256)), stream, p);
   if (st->n_attn_blocks > 0) {
-    MUX_LAUNCH("attn_bwd_kv", k_attn_bwd_kv, dim3((unsigned)st->n_attn_blocks * (unsigned)desc->n_kv_heads), dim3(256), 0, stream, p);
-    MUX_LAUNCH("attn_bwd_q", k_attn_bwd_q, dim3((unsigned)st->n_attn_blocks * (unsigned)desc->n_heads), dim3(256), 0, stream, p);
+    ATTN_LAUNCH("attn_bwd_kv", k_attn_bwd_kv, D, dim3((unsigned)st->n_attn_blocks * (unsigned)desc->n_kv_heads), stream, p);
+    ATTN_LAUNCH("attn_bwd_q", k_attn_bwd_q, D, dim3((unsigned)st->n_attn_blocks * (unsigned)desc->n_heads), stream, p);
   }
   return last_hip(fn);
 }

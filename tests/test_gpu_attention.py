@@ -28,9 +28,9 @@ def bf16_round(a):
     return r.view(np.float32)
 
 
-def run(env, task_lens, chunk, H, seed, max_pack_len=0, flags=0, fused=False, sigma=1.0, check_repeat=False, Hkv=None):
+def run(env, task_lens, chunk, H, seed, max_pack_len=0, flags=0, fused=False, sigma=1.0, check_repeat=False, Hkv=None,
+        d=128):
     mx, torch = env
-    d = 128
     ot = segtab.build(task_lens, chunk, max_pack_len, flags)
     seqs = [(s[2], s[3]) for s in segtab.sequences(ot)]
     T = ot.T
@@ -41,7 +41,7 @@ def run(env, task_lens, chunk, H, seed, max_pack_len=0, flags=0, fused=False, si
     pad = ot.row_task < 0
     for a in (Q, K, V, dO):
         a[pad] = np.nan if seed % 2 else 1e30            # padding rows must not leak anywhere
-    print(f"attention case: T={T} H={H} chunk={chunk} seqs={len(seqs)} longest={max([n for _, n in seqs] + [0])}", flush=True)
+    print(f"attention case: T={T} H={H} d={d} chunk={chunk} seqs={len(seqs)} longest={max([n for _, n in seqs] + [0])}", flush=True)
     st = mx.mux_segtab_build([mx.TaskDesc(mx.MUX_ADAPTER_NONE, 0, 1.0, l) for l in task_lens], chunk, max_pack_len, flags)
     assert np.array_equal(mx.mux_segtab_serialize(st), ot.image)
     dev = "cuda:0"
@@ -139,6 +139,18 @@ def test_llama_heads_one_block(env):
     run(env, [[384, 100], [77]], chunk=128, H=32, seed=7)
 
 
+@pytest.mark.parametrize("d", [64, 80, 96])
+def test_other_head_dimensions(env, d):
+    """Head dimensions below 128: 64 and 96 (two and three 32-column tiles of an output row) and 80 (GPT3-2.7B: 2560 / 32
+    heads; the third tile half used).  Ragged lengths around every boundary, long sequences, grouped heads, a fused
+    buffer, eight heads (the XCD-wise work mapping)."""
+    lens = [[1, 2, 31, 32, 33], [63, 64, 65], [127, 128, 129], [200, 5], []]
+    run(env, lens, chunk=64, H=2, seed=20 + d, d=d, check_repeat=True)
+    run(env, [[700], [300, 260], [513]], chunk=128, H=3, seed=21 + d, d=d)
+    run(env, [[300, 70], [129]], chunk=64, H=4, Hkv=2, seed=22 + d, d=d, fused=True)
+    run(env, [[1000, 24]], chunk=256, H=8, seed=23 + d, d=d, max_pack_len=1024)
+
+
 def test_argument_checks(env):
     mx, torch = env
     st = mx.mux_segtab_build([mx.TaskDesc(mx.MUX_ADAPTER_NONE, 0, 1.0, [64])], 64, 0, 0)
@@ -148,7 +160,7 @@ def test_argument_checks(env):
     mx.mux_segtab_upload(st, dtab, nb)
     x = torch.zeros((64, 256), dtype=torch.bfloat16, device=dev)
     with pytest.raises(mx.MuxError):
-        mx.mux_attn_forward(mx.AttnDesc(2, 64, 128, 128, 128, 128), st, dtab, x, x, x, x, None)       # head_dim 64
+        mx.mux_attn_forward(mx.AttnDesc(2, 48, 96, 96, 96, 96), st, dtab, x, x, x, x, None)           # head_dim 48
     with pytest.raises(mx.MuxError):
         mx.mux_attn_forward(mx.AttnDesc(2, 128, 128, 256, 256, 256), st, dtab, x, x, x, x, None)      # ldq too small
     x3 = torch.zeros((64, 384), dtype=torch.bfloat16, device=dev)

@@ -50,20 +50,20 @@ def test_benchmark_config_layer(env, cfg, layer):
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("cfg", [1, 3])
-def test_attention_benchmark_sequences(env, cfg):
+@pytest.mark.parametrize("cfg,d", [(1, 128), (3, 128), (3, 80), (1, 64)])
+def test_attention_benchmark_sequences(env, cfg, d):
     """The attention step on the sequences of a benchmark workload with all its heads, as `bench.py --attention` runs
-    it (fused QKV buffer), compared with the attention oracle on three sampled heads."""
+    it (fused QKV buffer; heads of 128, and of 80 and 64 as `--head-dim` runs them), compared with the attention oracle
+    on three sampled heads."""
     mx, torch = env
     from oracle import attention as oatt
     from oracle import segtab
     wl = wlm.config(cfg)
-    d = 128
     H = wl.layers[0][2] // d
     ot = segtab.build([t.seq_lens for t in wl.tasks], wl.chunk)
     seqs = [(s[2], s[3]) for s in segtab.sequences(ot)]
     T = ot.T
-    print(f"attention config {cfg}: T={T} H={H} longest={max(n for _, n in seqs)}", flush=True)
+    print(f"attention config {cfg}: T={T} H={H} d={d} longest={max(n for _, n in seqs)}", flush=True)
     dev = "cuda:0"
     st = mx.mux_segtab_build([mx.TaskDesc(t.kind, t.rank, t.scale, t.seq_lens) for t in wl.tasks], wl.chunk, 0, 0)
     nb = mx.mux_segtab_device_bytes(st)
