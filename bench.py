@@ -31,7 +31,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=1,
                     help="index into BASELINE.json configs (default 1: LLaMA-7B shapes); 5 / 6 = those shapes with two "
-                         "Adapter-Tuning / Diff-Pruning tasks; 7 / 8 = the paper's Table 2 mixes A / B")
+                         "Adapter-Tuning / Diff-Pruning tasks; 7 / 8 = the paper's Table 2 mixes A / B; 9 = mix A on GPT3-2.7B "
+                         "shapes")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")

@@ -180,6 +180,14 @@ def config(idx: int, seed: int = 0) -> Workload:
         w = table2_workload("A" if idx == 7 else "B", 64 if idx == 7 else 128)
         return Workload(name=w.name, layers=_llama_layers(4096, 11008), chunk=w.chunk, tasks=w.tasks,
                         notes=f"Table 2 mix {'A' if idx == 7 else 'B'}: 8 LoRA r16 tasks, {sum(t.tokens for t in w.tasks)} tokens, chunk {w.chunk}")
+    if idx == 9:
+        # Table 2's mix A on the backbone the paper runs it on (GPT3-2.7B, Table 3: hidden 2560, 32 heads): the four
+        # attention projections and the two matrices of its MLP (4 x hidden)
+        w = table2_workload("A", 64)
+        layers = [("q", 2560, 2560), ("k", 2560, 2560), ("v", 2560, 2560), ("o", 2560, 2560),
+                  ("fc1", 2560, 10240), ("fc2", 10240, 2560)]
+        return Workload(name="gpt2p7b_mixA", layers=layers, chunk=w.chunk, tasks=w.tasks,
+                        notes=f"Table 2 mix A on GPT3-2.7B shapes: 8 LoRA r16 tasks, {sum(t.tokens for t in w.tasks)} tokens, chunk {w.chunk}")
     raise ValueError(f"no config {idx}")
 
 

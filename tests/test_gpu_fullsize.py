@@ -12,7 +12,8 @@ pytestmark = pytest.mark.gpu
 
 CASES = [(1, 0), (1, 4), (1, 6), (2, 0), (2, 6), (3, 0), (3, 4), (3, 6), (4, 0), (4, 3), (4, 4), (4, 6),
          (5, 0),     # 5: the extra workload with two Adapter-Tuning tasks (their rows need x W in full: one projection)
-         (6, 0), (6, 6)]   # 6: the extra workload with two Diff-Pruning tasks (d delta_t in full)
+         (6, 0), (6, 6),   # 6: the extra workload with two Diff-Pruning tasks (d delta_t in full)
+         (9, 0), (9, 4), (9, 5)]   # 9: Table 2's mix A (eight small tasks) on GPT3-2.7B shapes
 
 
 @pytest.fixture(scope="module")
