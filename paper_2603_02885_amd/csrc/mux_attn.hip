@@ -138,9 +138,11 @@ struct TileLoadT {
 // Zero in the columns D .. DP-1 of a staged tile of `rows` rows (nothing is ever stored there afterwards).
 template <int D, int DP>
 __device__ __forceinline__ void zero_pad_columns(bf16_t* tile, int rows, int pitch, int tid) {
-  if (DP > D)
-    for (int e = tid; e < rows * ((DP - D) / 8); e += 256)
-      *(uint4*)(tile + (e / ((DP - D) / 8)) * pitch + D + (e % ((DP - D) / 8)) * 8) = uint4{0u, 0u, 0u, 0u};
+  if constexpr (DP > D) {
+    constexpr int PIECES = (DP - D) / 8;       // 16-byte pieces a row
+    for (int e = tid; e < rows * PIECES; e += 256)
+      *(uint4*)(tile + (e / PIECES) * pitch + D + (e % PIECES) * 8) = uint4{0u, 0u, 0u, 0u};
+  }
 }
 
 // ------------------------------------------------------------------------------------------------ forward

@@ -35,34 +35,46 @@ __global__ __launch_bounds__(256) void k_dispatch(DispatchParams p, int first) {
     if (it.nrows < 64) valid &= ((uint64_t)1 << it.nrows) - 1;
   }
   char* packed = mine ? p.task[it.task - p.task_base] : nullptr;
-  // a workgroup moves a slab of 4 x 64 vectors of every row of its item; four vectors per lane are in flight
+  // a workgroup moves a slab of 4 x 64 vectors of every row of its item; a wave has four of its rows in flight at
+  // a time, four vectors per lane each (one row at a time cost a memory latency per row)
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int slab = (int)blockIdx.y * 256 * (int)sizeof(V) + lane * (int)sizeof(V);
-  for (int r = wave; r < it.nrows; r += 4) {
-    char* arow = p.aligned + (size_t)(it.row0 + r) * p.row_bytes_aligned;
-    if ((valid >> r) & 1) {
-      if (!mine) continue;
-      const int tok = tok0 + __popcll(valid & (((uint64_t)1 << r) - 1));
-      char* prow = packed + (size_t)tok * p.row_bytes_task;
-      char* dst = p.to_aligned ? arow : prow;
-      const char* src = p.to_aligned ? prow : arow;
-      V v[4];
+  constexpr int RU = 4;
+  for (int r0 = wave; r0 < it.nrows; r0 += 4 * RU) {
+    V v[RU][4];
+    char* dst[RU];
+    int what[RU];                                  // 0: nothing, 1: copy, 2: zero
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int o = slab + k * 64 * (int)sizeof(V);
-        if (o < p.width_bytes) v[k] = *(const V*)(src + o);
+    for (int u = 0; u < RU; ++u) {
+      const int r = r0 + 4 * u;
+      what[u] = 0;
+      dst[u] = nullptr;
+      if (r >= it.nrows) continue;
+      char* arow = p.aligned + (size_t)(it.row0 + r) * p.row_bytes_aligned;
+      if ((valid >> r) & 1) {
+        if (!mine) continue;
+        const int tok = tok0 + __popcll(valid & (((uint64_t)1 << r) - 1));
+        char* prow = packed + (size_t)tok * p.row_bytes_task;
+        const char* src = p.to_aligned ? prow : arow;
+        dst[u] = p.to_aligned ? arow : prow;
+        what[u] = 1;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int o = slab + k * 64 * (int)sizeof(V);
+          if (o < p.width_bytes) v[u][k] = *(const V*)(src + o);
+        }
+      } else if (p.to_aligned && first) {
+        dst[u] = arow;
+        what[u] = 2;
       }
+    }
+#pragma unroll
+    for (int u = 0; u < RU; ++u) {
+      if (what[u] == 0) continue;
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         const int o = slab + k * 64 * (int)sizeof(V);
-        if (o < p.width_bytes) *(V*)(dst + o) = v[k];
-      }
-    } else if (p.to_aligned && first) {
-      V z{};
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int o = slab + k * 64 * (int)sizeof(V);
-        if (o < p.width_bytes) *(V*)(arow + o) = z;
+        if (o < p.width_bytes) *(V*)(dst[u] + o) = what[u] == 1 ? v[u][k] : V{};
       }
     }
   }
