@@ -309,28 +309,44 @@ __global__ __launch_bounds__(256) void k_attn_zero_pad(ZeroParams p) {
   }
 }
 
-// delta[h][row] = sum_d dO[row][h, d] * O[row][h, d] for the rows of sequences.  One thread per (row, head).
+// delta[h][row] = sum_d dO[row][h, d] * O[row][h, d] for the rows of sequences.  Sixteen lanes per (row, head), a
+// 16-byte piece each (a wave instruction then reads whole runs of the row); a group of sixteen takes four
+// consecutive heads, all loads issued before the sums.
 template <int D>
 __global__ __launch_bounds__(256) void k_attn_delta(AttnParams p) {
-  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= (size_t)p.T * p.H) return;
-  const int row = (int)(idx / p.H), h = (int)(idx % p.H);
-  float s = 0.f;
-  if (row_is_valid(p.dtab, row)) {
-    const uint4* a = (const uint4*)(p.dO + (size_t)row * p.ldo + h * D);
-    const uint4* b = (const uint4*)(p.O + (size_t)row * p.ldo + h * D);
-#pragma unroll 4
-    for (int i = 0; i < D / 8; ++i) {
-      const uint4 x = a[i], y = b[i];
-      const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+  constexpr int PPR = D / 8, U = 4;
+  const int l16 = threadIdx.x & 15;
+  const size_t group = ((size_t)blockIdx.x * 256 + threadIdx.x) >> 4;
+  const size_t n = (size_t)p.T * p.H;
+  uint4 x[U], y[U];
+  bool ok[U];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        s = fmaf(__uint_as_float(xs[q] << 16), __uint_as_float(ys[q] << 16), s);
-        s = fmaf(__uint_as_float(xs[q] & 0xffff0000u), __uint_as_float(ys[q] & 0xffff0000u), s);
-      }
+  for (int u = 0; u < U; ++u) {
+    const size_t idx = group * U + u;
+    const int row = idx < n ? (int)(idx / p.H) : 0, h = (int)(idx % p.H);
+    ok[u] = idx < n && l16 < PPR && row_is_valid(p.dtab, row);
+    x[u] = y[u] = uint4{0u, 0u, 0u, 0u};
+    if (ok[u]) {
+      x[u] = *(const uint4*)(p.dO + (size_t)row * p.ldo + h * D + 8 * l16);
+      y[u] = *(const uint4*)(p.O + (size_t)row * p.ldo + h * D + 8 * l16);
     }
   }
-  p.delta[(size_t)h * p.T + row] = s;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint32_t xs[4] = {x[u].x, x[u].y, x[u].z, x[u].w}, ys[4] = {y[u].x, y[u].y, y[u].z, y[u].w};
+    float s = 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      s = fmaf(__uint_as_float(xs[q] << 16), __uint_as_float(ys[q] << 16), s);
+      s = fmaf(__uint_as_float(xs[q] & 0xffff0000u), __uint_as_float(ys[q] & 0xffff0000u), s);
+    }
+    s += __shfl_xor(s, 8);
+    s += __shfl_xor(s, 4);
+    s += __shfl_xor(s, 2);
+    s += __shfl_xor(s, 1);
+    const size_t idx = group * U + u;
+    if (idx < n && l16 == 0) p.delta[(size_t)(idx % p.H) * p.T + idx / p.H] = s;
+  }
 }
 
 // ------------------------------------------------------------------------------------------------ dQ
@@ -656,7 +672,7 @@ extern "C" mux_status mux_attn_backward(const mux_attn_desc* desc, const mux_seg
   z.out[0] = p.dQ; z.ld[0] = desc->ldq; z.out[1] = p.dK; z.ld[1] = desc->ldk; z.out[2] = p.dV; z.ld[2] = desc->ldv;
   MUX_LAUNCH("attn_zero_pad", k_attn_zero_pad, dim3((unsigned)st->items[0].size(), (unsigned)((z.width[0] + 2047) / 2048)), dim3(256), 0, stream, z);
   const size_t n = (size_t)st->T * desc->n_heads;
-  ATTN_LAUNCH("attn_delta", k_attn_delta, D, dim3((unsigned)((n + 255) / 256)), stream, p);
+  ATTN_LAUNCH("attn_delta", k_attn_delta, D, dim3((unsigned)(((n + 3) / 4 * 16 + 255) / 256)), stream, p);
   if (st->n_attn_blocks > 0) {
     ATTN_LAUNCH("attn_bwd_kv", k_attn_bwd_kv, D, dim3((unsigned)st->n_attn_blocks * (unsigned)desc->n_kv_heads), stream, p);
     ATTN_LAUNCH("attn_bwd_q", k_attn_bwd_q, D, dim3((unsigned)st->n_attn_blocks * (unsigned)desc->n_heads), stream, p);
