@@ -410,6 +410,18 @@ __global__ __launch_bounds__(256) void k_tune_add(const TuneAddParams p) {
   const size_t zrow0 = (size_t)(tk.zrow0 + it.row0 - tk.row_begin);
   const bf16_t* in = p.In + (p.backward ? (size_t)it.row0 : zrow0) * p.N;
   bf16_t* out = p.Out + (p.backward ? zrow0 : (size_t)it.row0) * p.N;
+  // the eight pieces of `In` this lane adds to are fetched up front (fetched where they are used, each cost the wave
+  // a memory latency)
+  uint4 xin[4][2];
+  bool xok[4][2];
+#pragma unroll
+  for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+    for (int ps = 0; ps < 2; ++ps) {
+      const int m = rt * 16 + b_row + 8 * ps, c = cw0 + b_pc;
+      xok[rt][ps] = m < it.nrows && c < p.N && ((m < 32 ? vbits_lo >> m : vbits_hi >> (m - 32)) & 1u) != 0;
+      xin[rt][ps] = xok[rt][ps] ? *(const uint4*)(in + (size_t)m * p.N + c) : make_uint4(0, 0, 0, 0);
+    }
 #pragma unroll
   for (int rt = 0; rt < 4; ++rt) {
     if (rt * 16 >= it.nrows) break;
@@ -427,10 +439,9 @@ __global__ __launch_bounds__(256) void k_tune_add(const TuneAddParams p) {
     for (int ps = 0; ps < 2; ++ps) {
       const int ml = b_row + 8 * ps, m = rt * 16 + ml, c = cw0 + b_pc;
       if (m < it.nrows && c < p.N) {
-        const bool ok = ((m < 32 ? vbits_lo >> m : vbits_hi >> (m - 32)) & 1u) != 0;
         uint4 o = make_uint4(0, 0, 0, 0);
-        if (ok) {
-          const uint4 x = *(const uint4*)(in + (size_t)m * p.N + c);
+        if (xok[rt][ps]) {
+          const uint4 x = xin[rt][ps];
           const f32x4 p0 = *(const f32x4*)(sc + ml * SP + b_pc), p1 = *(const f32x4*)(sc + ml * SP + b_pc + 4);
           const uint32_t* px = (const uint32_t*)&x;
           o.x = pack_bf16x2(__uint_as_float(px[0] << 16) + p0[0], __uint_as_float(px[0] & 0xffff0000u) + p0[1]);
