@@ -127,22 +127,27 @@ __global__ __launch_bounds__(64 * NWV) void k_down(const DownParams p) {
     for (int jt = 0; jt < NJM; ++jt) acc[rt][jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   u32x4 gx[DEPTH][4], gp[DEPTH][2 * NJM];
+  // Every slab issues the same number of loads, whatever the rank and wherever the share ends (a piece that does not
+  // exist gets an out-of-range offset, costs no memory access and reads as zeros): the compiler can then count the
+  // loads still in flight when it waits for a slab, instead of waiting for all of them.
   auto load = [&](int c, int buf) {          // a slab that starts past the end of this wave's share reads as zeros
     const uint32_t k = (c + b_pc < cend) ? (uint32_t)c * 2u : OOB;     // OOB + OOB wraps into range: mask on k only
 #pragma unroll
     for (int q = 0; q < 4; ++q) gx[buf][q] = buf_load16(rIn, (x_off[q] == OOB || k == OOB) ? OOB : x_off[q] + k);
 #pragma unroll
-    for (int q = 0; q < 2 * NJM; ++q)
-      if (q < 2 * NJ) gp[buf][q] = buf_load16(rP, (p_off[q] == OOB || k == OOB) ? OOB : p_off[q] + k);
+    for (int q = 0; q < 2 * NJM; ++q) gp[buf][q] = buf_load16(rP, (p_off[q] == OOB || k == OOB) ? OOB : p_off[q] + k);
   };
   const int i = lane & 15, g = lane >> 4;
   // DEPTH slabs in flight while one is multiplied
 #pragma unroll
-  for (int d = 0; d < DEPTH; ++d) load(cbeg + 64 * d, d);
+  for (int d = 0; d < DEPTH; ++d) {
+    load(cbeg + 64 * d, d);
+    __builtin_amdgcn_sched_barrier(0);       // in the order in which the loop uses them
+  }
   for (int c = cbeg; c < cend; c += 64 * DEPTH) {
 #pragma unroll
     for (int buf = 0; buf < DEPTH; ++buf) {
-      if (c + 64 * buf < cend) {
+      {                                      // also for a slab past the end (zeros): no branch around the loads
 #pragma unroll
         for (int q = 0; q < 4; ++q) *(u32x4*)(sX + (b_row + 8 * q) * GP + b_pc) = gx[buf][q];
 #pragma unroll
