@@ -35,6 +35,8 @@ def parse():
                          "shapes")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mfma-probe", action="store_true",
+                    help="leave out the register-only MFMA rate of this box (zeros and N(0,1) operands)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--compare-unmultiplexed", action="store_true",
                     help="also time the same tasks one at a time (one table and one set of calls per task, same shared "
@@ -66,6 +68,38 @@ def parse():
 
 class LayerState:
     pass
+
+
+def mfma_probe(mx, torch, seed):
+    """Context for the roofline fraction: the rate the matrix cores sustain on this machine with bf16 operands that stay in
+    registers (two waves per SIMD, independent MFMAs back to back), for operands that are all zero, N(0,1), and
+    distributed like the benchmark's (activations N(0,1), weights N(0,0.02)).  The clock under dense MFMA load is set
+    by power, hence by the data."""
+    dev = "cuda:0"
+    n = mx.mux_probe_mfma_operand_bytes() // 2
+    sink = torch.empty(mx.mux_probe_mfma_sink_bytes(), dtype=torch.uint8, device=dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    rnd = torch.randn(n, device=dev, dtype=torch.float32, generator=gen)
+    like = rnd.clone()
+    like[n // 2:] *= 0.02                                # second half: the B operands, distributed like W
+    kinds = {"zeros": torch.zeros(n, dtype=torch.bfloat16, device=dev),
+             "normal": rnd.to(torch.bfloat16),            # both operands N(0,1)
+             "like_benchmark": like.to(torch.bfloat16)}  # A ~ N(0,1) like X and dY, B ~ N(0,0.02) like W
+    stream = torch.cuda.current_stream()
+    out = {"unit": "TFLOP/s", "waves_per_simd": 2, "instruction": "v_mfma_f32_32x32x16_bf16"}
+    iters = 4000                                         # about 10 ms a launch
+    for name, ops in kinds.items():
+        mx.mux_probe_mfma(ops, sink, iters, stream)      # warm-up, and the clock settles
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flop = 0.0
+        for _ in range(3):
+            flop += mx.mux_probe_mfma(ops, sink, iters, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    return out
 
 
 def setup(mx, torch, wl, seed):
@@ -685,6 +719,11 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         out["calibration_copy_bytes"] = int(src.numel())
+    if not args.no_mfma_probe:
+        out["mfma_probe"] = mfma_probe(mx, torch, args.seed)
+        if out["roofline"].get("achieved"):
+            # the same kernel against what the matrix cores of this machine sustain on such operands from registers
+            out["roofline"]["achieved_over_mfma_probe"] = out["roofline"]["achieved"] / out["mfma_probe"]["like_benchmark"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds, args.seed)
     print(json.dumps(out))

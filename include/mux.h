@@ -218,6 +218,17 @@ typedef struct {
 mux_status mux_profile_enable(int on);
 mux_status mux_profile_collect(mux_profile_entry* host_out, int32_t cap, int32_t* n);
 
+/* Diagnostic for the roofline of the backbone GEMM: what the matrix cores sustain on bf16 operands that stay in
+ * registers (two waves per SIMD on every compute unit, independent v_mfma_f32_32x32x16_bf16 back to back).  The
+ * clock under such load is set by power, hence by the operand values, so the caller supplies them: `dev_operands`
+ * holds mux_probe_mfma_operand_bytes() bytes of bf16 values (device, 16-byte aligned; every wave reads the same),
+ * `dev_sink` receives mux_probe_mfma_sink_bytes() bytes of results nobody needs (device).  One launch of `iters`
+ * loop turns on `hip_stream`, no synchronisation; *flop (host, may be null) is set to the floating-point
+ * operations of the launch, so that the caller's timing gives FLOP/s. */
+size_t mux_probe_mfma_operand_bytes(void);
+size_t mux_probe_mfma_sink_bytes(void);
+mux_status mux_probe_mfma(const void* dev_operands, void* dev_sink, int32_t iters, void* hip_stream, double* flop);
+
 const char* mux_last_error(void);
 const char* mux_version(void);
 

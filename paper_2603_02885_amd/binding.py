@@ -24,6 +24,7 @@ __all__ = [
     "CostModel", "mux_plan_stage_latency", "mux_plan_htask_latency", "mux_plan_fusion",
     "mux_dispatch_gather", "mux_dispatch_scatter",
     "AttnDesc", "mux_attn_saved_bytes", "mux_attn_workspace_bytes", "mux_attn_forward", "mux_attn_backward",
+    "mux_probe_mfma_operand_bytes", "mux_probe_mfma_sink_bytes", "mux_probe_mfma",
 ]
 
 MUX_OK = 0
@@ -166,6 +167,9 @@ def load_library() -> ctypes.CDLL:
         "mux_profile_collect": (c_int, [POINTER(_ProfileEntryC), c_int32, POINTER(c_int32)]),
         "mux_last_error": (c_char_p, []),
         "mux_version": (c_char_p, []),
+        "mux_probe_mfma_operand_bytes": (c_size_t, []),
+        "mux_probe_mfma_sink_bytes": (c_size_t, []),
+        "mux_probe_mfma": (c_int, [vp, vp, c_int32, vp, POINTER(ctypes.c_double)]),
         "mux_dispatch_gather": (c_int, [vp, vp, POINTER(vp), c_int64, vp, c_int64, c_int32, c_int32, vp]),
         "mux_dispatch_scatter": (c_int, [vp, vp, vp, c_int64, POINTER(vp), c_int64, c_int32, c_int32, vp]),
         "mux_attn_saved_bytes": (c_size_t, [POINTER(_AttnDescC), vp]),
@@ -289,6 +293,21 @@ def mux_last_error() -> str:
 
 def mux_version() -> str:
     return load_library().mux_version().decode()
+
+
+def mux_probe_mfma_operand_bytes() -> int:
+    return int(load_library().mux_probe_mfma_operand_bytes())
+
+
+def mux_probe_mfma_sink_bytes() -> int:
+    return int(load_library().mux_probe_mfma_sink_bytes())
+
+
+def mux_probe_mfma(dev_operands, dev_sink, iters: int, stream=None) -> float:
+    """Launches the register-only MFMA loop; returns the floating-point operations of the launch."""
+    flop = ctypes.c_double(0.0)
+    _check(load_library().mux_probe_mfma(_ptr(dev_operands), _ptr(dev_sink), int(iters), _stream(stream), ctypes.byref(flop)))
+    return float(flop.value)
 
 
 def mux_choose_chunk_size(lens: Sequence[int], floor_: int = 64) -> int:

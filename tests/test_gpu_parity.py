@@ -124,6 +124,25 @@ def test_gemm_last_round_pieces(env, n_items):
     run_case(env, wl, seed=n_items, cols=np.unique(cols), kcols=np.unique(kcols))
 
 
+def test_mfma_probe_runs(env):
+    """The diagnostic MFMA loop: launches, reports its FLOP count, leaves finite sums (operands 1 and 0.5: every
+    accumulator element of a loop turn grows by 8 products of 16 terms of 0.5), rejects bad arguments."""
+    mx, torch = env
+    n = mx.mux_probe_mfma_operand_bytes() // 2
+    ops = torch.ones(n, dtype=torch.bfloat16, device="cuda:0")
+    ops[n // 2:] = 0.5                                   # the B operands
+    sink = torch.zeros(mx.mux_probe_mfma_sink_bytes() // 4, dtype=torch.float32, device="cuda:0")
+    flop = mx.mux_probe_mfma(ops, sink, 3, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    assert flop == 512 * 4 * 3 * 64 * 2 * 32 * 32 * 16
+    # a lane sums its 8 x 16 accumulator elements, each 3 turns x 8 products x 16 terms x (1 x 0.5)
+    assert torch.all(sink == 8 * 16 * 3 * 8 * 16 * 0.5)
+    with pytest.raises(mx.MuxError):
+        mx.mux_probe_mfma(ops, sink, 0, None)
+    with pytest.raises(mx.MuxError):
+        mx.mux_probe_mfma(None, sink, 1, None)
+
+
 def tuning_workload(K=192, N=160, chunk=32):
     """The additive bottleneck kind between the others: ragged ranks and token counts, padding, an empty task."""
     tasks = [wlm.Task(wlm.KIND_LORA, 16, 2.0, [100]), wlm.Task(wlm.KIND_ADAPTER, 8, 1.5, [70, 45]),
