@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mfma-probe", action="store_true",
-                    help="leave out the register-only MFMA rate of this box (zeros and N(0,1) operands)")
+                    help="leave out the two context probes of this box (register-only MFMA rate, plain HBM read stream)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--compare-unmultiplexed", action="store_true",
                     help="also time the same tasks one at a time (one table and one set of calls per task, same shared "
@@ -68,6 +68,27 @@ def parse():
 
 class LayerState:
     pass
+
+
+def hbm_read_probe(mx, torch):
+    """Context for the HBM fractions of the adapter kernels: what one plain read stream draws on this machine.  Four
+    buffers of 512 MiB read in turn, so that the 256 MB last-level cache cannot serve any of it."""
+    dev = "cuda:0"
+    nbytes = 512 << 20
+    bufs = [torch.zeros(nbytes, dtype=torch.uint8, device=dev) for _ in range(4)]
+    sink = torch.empty(mx.mux_probe_read_sink_bytes(), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+    for b in bufs:
+        mx.mux_probe_read(b, nbytes, sink, stream)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(3):
+        for b in bufs:
+            mx.mux_probe_read(b, nbytes, sink, stream)
+    e1.record()
+    torch.cuda.synchronize()
+    gbps = 12 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    return {"unit": "GB/s", "read_stream": gbps, "frac_of_hbm_peak": gbps / PEAK_HBM, "bytes_per_launch": nbytes}
 
 
 def mfma_probe(mx, torch, seed):
@@ -720,6 +741,7 @@ def main():
         torch.cuda.synchronize()
         out["calibration_copy_bytes"] = int(src.numel())
     if not args.no_mfma_probe:
+        out["hbm_read_probe"] = hbm_read_probe(mx, torch)
         out["mfma_probe"] = mfma_probe(mx, torch, args.seed)
         if out["roofline"].get("achieved"):
             # the same kernel against what the matrix cores of this machine sustain on such operands from registers

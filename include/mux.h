@@ -229,6 +229,13 @@ size_t mux_probe_mfma_operand_bytes(void);
 size_t mux_probe_mfma_sink_bytes(void);
 mux_status mux_probe_mfma(const void* dev_operands, void* dev_sink, int32_t iters, void* hip_stream, double* flop);
 
+/* Diagnostic for the roofline of the adapter kernels: one plain read stream over `bytes` bytes at `dev_buf` (device,
+ * 16-byte aligned; the last bytes % 16 bytes are not read), every 16-byte piece read once, each workgroup walking a
+ * contiguous share with eight loads a thread in flight.  `dev_sink` receives mux_probe_read_sink_bytes() bytes nobody needs (device).  One launch on `hip_stream`,
+ * no synchronisation; the caller's timing over `bytes` gives the GB/s a read stream reaches on the box. */
+size_t mux_probe_read_sink_bytes(void);
+mux_status mux_probe_read(const void* dev_buf, size_t bytes, void* dev_sink, void* hip_stream);
+
 const char* mux_last_error(void);
 const char* mux_version(void);
 

@@ -143,6 +143,26 @@ def test_mfma_probe_runs(env):
         mx.mux_probe_mfma(None, sink, 1, None)
 
 
+def test_read_probe_runs(env):
+    """The diagnostic read stream: reads every 16-byte piece once (the sink holds the sum of the words' XOR, here of
+    a buffer of ones), with a ragged size, and rejects bad arguments."""
+    mx, torch = env
+    n_vec = 2048 * 256 * 8 * 2 + 12345                  # two full turns of the eight-deep loop and a ragged rest
+    buf = torch.ones(n_vec * 4 + 3, dtype=torch.int32, device="cuda:0")
+    sink = torch.zeros(mx.mux_probe_read_sink_bytes() // 4, dtype=torch.int32, device="cuda:0")
+    mx.mux_probe_read(buf, n_vec * 16 + 12, sink, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    assert int(sink.sum().item()) == 0                  # 1 ^ 1 ^ 1 ^ 1 = 0 for every piece
+    buf[::4] = 3                                        # 3 ^ 1 ^ 1 ^ 1 = 2 for every piece
+    mx.mux_probe_read(buf, n_vec * 16 + 12, sink, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    assert int(sink.to(torch.int64).sum().item()) == 2 * n_vec
+    with pytest.raises(mx.MuxError):
+        mx.mux_probe_read(buf, 8, sink, None)
+    with pytest.raises(mx.MuxError):
+        mx.mux_probe_read(None, 1024, sink, None)
+
+
 def tuning_workload(K=192, N=160, chunk=32):
     """The additive bottleneck kind between the others: ragged ranks and token counts, padding, an empty task."""
     tasks = [wlm.Task(wlm.KIND_LORA, 16, 2.0, [100]), wlm.Task(wlm.KIND_ADAPTER, 8, 1.5, [70, 45]),
