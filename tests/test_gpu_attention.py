@@ -151,6 +151,24 @@ def test_other_head_dimensions(env, d):
     run(env, [[1000, 24]], chunk=256, H=8, seed=23 + d, d=d, max_pack_len=1024)
 
 
+def test_random_sweep(env):
+    """Seeded random calls: head dimensions 64 / 80 / 96 / 128, 1 to 8 key/value heads with groups of 1, 2 or 4 query
+    heads, chunk sizes 16 to 256, up to four tasks of up to three sequences of up to 700 tokens, padded and dense
+    tables, packs, separate and fused buffers."""
+    rng = np.random.default_rng(777)
+    for case in range(16):
+        d = int(rng.choice([64, 80, 96, 128]))
+        Hkv = int(rng.choice([1, 2, 3, 4, 8]))
+        H = Hkv * int(rng.choice([1, 1, 2, 4]))
+        chunk = int(rng.choice([16, 32, 64, 128, 256]))
+        lens = [[int(v) for v in rng.integers(1, int(rng.choice([40, 200, 700])), size=int(rng.integers(0, 4)))]
+                for _ in range(int(rng.integers(1, 5)))]
+        if sum(len(l) for l in lens) == 0:
+            lens[0] = [33]
+        run(env, lens, chunk=chunk, H=H, Hkv=Hkv, seed=1000 + case, d=d, flags=int(rng.integers(0, 2)),
+            fused=bool(rng.integers(0, 2)), max_pack_len=int(rng.choice([0, 0, 300])))
+
+
 def test_argument_checks(env):
     mx, torch = env
     st = mx.mux_segtab_build([mx.TaskDesc(mx.MUX_ADAPTER_NONE, 0, 1.0, [64])], 64, 0, 0)
