@@ -3,7 +3,8 @@
 synthetic multi-tenant workload, on ONE MI355X.
 
 One "step" = forward + backward of all layer calls of the workload (7 projections of a
-LLaMA-shaped block), inputs resident in HBM.  Prints one JSON line: value = valid tokens per second of the whole
+LLaMA-shaped block), inputs resident in HBM.  Default workload: configs[3] of the benchmark spec (LLaMA-13B shapes,
+6 LoRA r16 + 2 IA3 tasks, about 20 k rows).  Prints one JSON line: value = valid tokens per second of the whole
 step; roofline = the slower backbone GEMM kernel against the bf16 matrix-core peak, its duration from HIP events on
 the launch stream; kernels = every kernel of the step; cpu_baseline = the fp64 oracle on a bounded sample.
 `--gpus N` with N > 1 is refused: this build is single-GPU.
@@ -29,8 +30,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", type=int, default=1,
-                    help="index into BASELINE.json configs (default 1: LLaMA-7B shapes); 5 / 6 = those shapes with two "
+    ap.add_argument("--workload", type=int, default=3,
+                    help="index into BASELINE.json configs (default 3: the LLaMA-13B shapes with 6 LoRA + 2 IA3 tasks the "
+                         "matrix-core target is stated on; 1: LLaMA-7B shapes); 5 / 6 = those shapes with two "
                          "Adapter-Tuning / Diff-Pruning tasks; 7 / 8 = the paper's Table 2 mixes A / B; 9 = mix A on GPT3-2.7B "
                          "shapes")
     ap.add_argument("--seed", type=int, default=0)
@@ -39,7 +41,9 @@ def parse():
                     help="leave out the extra measurement of the step replayed from a HIP graph")
     ap.add_argument("--no-mfma-probe", action="store_true",
                     help="leave out the two context probes of this box (register-only MFMA rate, plain HBM read stream)")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--no-cpu-full", action="store_true",
+                    help="leave out the oracle runs timed in full (tiny config, q projection of the LLaMA-7B config)")
     ap.add_argument("--compare-unmultiplexed", action="store_true",
                     help="also time the same tasks one at a time (one table and one set of calls per task, same shared "
                          "W, same rows), on one stream and alternating over two streams: what multiplexing buys")
@@ -72,6 +76,100 @@ class LayerState:
     pass
 
 
+class Telemetry:
+    """Clock and power of the GPU as the driver reports them (sysfs of the amdgpu card: hwmon freq1_input = shader
+    clock in Hz, power1_average or power1_input in microwatts, power1_cap), polled by a thread every few milliseconds
+    while a region runs.  Whatever cannot be read on the box is left out; the clock measured inside the kernels
+    (mux_diag_set_clock_buffer) does not depend on it."""
+
+    def __init__(self):
+        import glob
+        self.files = {}
+        for dev in sorted(glob.glob("/sys/class/drm/card*/device")):
+            try:
+                if open(os.path.join(dev, "vendor")).read().strip() != "0x1002":
+                    continue
+            except OSError:
+                continue
+            for hw in sorted(glob.glob(os.path.join(dev, "hwmon", "hwmon*"))):
+                for key, names in (("sclk_hz", ("freq1_input",)), ("power_uw", ("power1_average", "power1_input")),
+                                   ("power_cap_uw", ("power1_cap",))):
+                    for n in names:
+                        f = os.path.join(hw, n)
+                        if key not in self.files and os.access(f, os.R_OK):
+                            self.files[key] = f
+            for key, n in (("pp_dpm_sclk", "pp_dpm_sclk"), ("gpu_busy_percent", "gpu_busy_percent")):
+                f = os.path.join(dev, n)
+                if os.access(f, os.R_OK):
+                    self.files[key] = f
+            if self.files:
+                break
+
+    def _read(self, key):
+        try:
+            txt = open(self.files[key]).read()
+        except (OSError, KeyError):
+            return None
+        if key == "pp_dpm_sclk":          # "1: 1878Mhz *" marks the current level
+            for line in txt.splitlines():
+                if line.rstrip().endswith("*"):
+                    try:
+                        return float(line.split(":")[1].strip().split("M")[0]) * 1e6
+                    except (IndexError, ValueError):
+                        return None
+            return None
+        try:
+            return float(txt.strip())
+        except ValueError:
+            return None
+
+    def sample_while(self, fn, period=0.004):
+        """Runs fn() while a thread polls; returns (fn's result, summary of the samples)."""
+        import threading
+        stop = threading.Event()
+        rows = {"sclk_hz": [], "power_uw": [], "pp_dpm_sclk": []}
+
+        def poll():
+            while not stop.is_set():
+                for k in rows:
+                    if k in self.files:
+                        v = self._read(k)
+                        if v is not None:
+                            rows[k].append(v)
+                stop.wait(period)
+        th = threading.Thread(target=poll, daemon=True)
+        th.start()
+        try:
+            res = fn()
+        finally:
+            stop.set()
+            th.join()
+        out = {"source": "sysfs", "samples": max(len(v) for v in rows.values()) if rows else 0}
+        mean = lambda v: sum(v) / len(v)
+        if rows["sclk_hz"]:
+            out["sclk_mhz_mean"] = mean(rows["sclk_hz"]) / 1e6
+            out["sclk_mhz_min"] = min(rows["sclk_hz"]) / 1e6
+        elif rows["pp_dpm_sclk"]:
+            out["sclk_mhz_mean"] = mean(rows["pp_dpm_sclk"]) / 1e6
+            out["sclk_mhz_min"] = min(rows["pp_dpm_sclk"]) / 1e6
+        if rows["power_uw"]:
+            out["power_w_mean"] = mean(rows["power_uw"]) / 1e6
+            out["power_w_max"] = max(rows["power_uw"]) / 1e6
+        cap = self._read("power_cap_uw")
+        if cap:
+            out["power_cap_w"] = cap / 1e6
+        if out["samples"] == 0:
+            out["note"] = "no readable clock or power file under /sys/class/drm/card*/device on this box"
+        return res, out
+
+
+def clock_from_buffer(torch, buf):
+    """MHz from the two counters the matrix-core kernels add to (shader cycles, 100 MHz ticks); None if unused."""
+    torch.cuda.synchronize()
+    c, r = int(buf[0].item()), int(buf[1].item())
+    return (100.0 * c / r) if r > 0 else None
+
+
 def hbm_read_probe(mx, torch):
     """Context for the HBM fractions of the adapter kernels: what one plain read stream draws on this machine.  Four
     buffers of 512 MiB read in turn, so that the 256 MB last-level cache cannot serve any of it."""
@@ -93,7 +191,7 @@ def hbm_read_probe(mx, torch):
     return {"unit": "GB/s", "read_stream": gbps, "frac_of_hbm_peak": gbps / PEAK_HBM, "bytes_per_launch": nbytes}
 
 
-def mfma_probe(mx, torch, seed):
+def mfma_probe(mx, torch, seed, tele=None, clkbuf=None):
     """Context for the roofline fraction: the rate the matrix cores sustain on this machine with bf16 operands that stay in
     registers (two waves per SIMD, independent MFMAs back to back), for operands that are all zero, N(0,1), and
     distributed like the benchmark's (activations N(0,1), weights N(0,0.02)).  The clock under dense MFMA load is set
@@ -114,14 +212,29 @@ def mfma_probe(mx, torch, seed):
     iters = 4000                                         # about 10 ms a launch
     for name, ops in kinds.items():
         mx.mux_probe_mfma(ops, sink, iters, stream)      # warm-up, and the clock settles
+        if clkbuf is not None:
+            clkbuf.zero_()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        flop = 0.0
-        for _ in range(3):
-            flop += mx.mux_probe_mfma(ops, sink, iters, stream)
-        e1.record()
-        torch.cuda.synchronize()
+
+        def run():
+            e0.record()
+            flop = 0.0
+            for _ in range(3):
+                flop += mx.mux_probe_mfma(ops, sink, iters, stream)
+            e1.record()
+            torch.cuda.synchronize()
+            return flop
+        flop, smp = tele.sample_while(run) if tele is not None else (run(), None)
         out[name] = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        if clkbuf is not None:
+            mhz = clock_from_buffer(torch, clkbuf)
+            if mhz:
+                # the same box, the same instruction, every matrix pipe busy all the time: FLOP/s over the clock it
+                # ran at gives the FLOP per cycle the part really delivers (nominal: 256 CUs x 4 SIMDs x 1024)
+                out[name + "_clock_mhz"] = mhz
+                out[name + "_flop_per_cycle"] = out[name] * 1e12 / (mhz * 1e6)
+        if smp is not None and name == "like_benchmark":
+            out["telemetry_like_benchmark"] = smp
     return out
 
 
@@ -518,36 +631,55 @@ def dispatch(mx, torch, args):
             "kernels": res}
 
 
-def cpu_baseline(wl, seconds, seed):
-    """The fp64 oracle, as it stands, on a bounded sample: the first m tokens of every task through
-    every projection (fwd+bwd), m sized from a short calibration so that the run takes about `seconds`."""
+def cpu_baseline(wl, seconds, seed, full_runs=True):
+    """The fp64 oracle, as it stands, timed on the host cores.  `value`: a bounded sample of the benchmarked workload --
+    the first m tokens of every task, aligned by the workload's own rule (its chunk size and packing), through every
+    projection forward + backward, m sized from a short calibration so that the run takes about `seconds`.  Beside it,
+    timed in full: the tiny config and the q projection of the LLaMA-7B config (5120 tokens, 4096 x 4096)."""
     import numpy as np
     import mux_workloads as wlm
     import oracle
     from oracle import segtab
 
-    def run(m):
-        tasks = [wlm.Task(t.kind, t.rank, t.scale, [min(m, t.tokens)] if t.tokens > 0 else []) for t in wl.tasks]
-        sub = wlm.Workload(name=wl.name + "_sample", layers=wl.layers, tasks=tasks, chunk=16)
-        ot = segtab.build([t.seq_lens for t in tasks], 16)
+    def run(work, layer_ids, m=None):
+        tasks = work.tasks if m is None else [
+            wlm.Task(t.kind, t.rank, t.scale, [min(m, t.tokens)] if t.tokens > 0 else [], t.density) for t in work.tasks]
+        sub = wlm.Workload(name=work.name + ("" if m is None else "_sample"), layers=work.layers, tasks=tasks,
+                           chunk=work.chunk, max_pack_len=work.max_pack_len)
+        ot = segtab.build([t.seq_lens for t in tasks], work.chunk, work.max_pack_len, 0)
         kinds, ranks, scales = [t.kind for t in tasks], [t.rank for t in tasks], [t.scale for t in tasks]
-        total = 0.0
-        for li in range(len(sub.layers)):
+        total, flop = 0.0, 0.0
+        for li in layer_ids:
             lt = wlm.layer_tensors(sub, li, ot.T, seed=seed)
+            S = lt.masks if any(mk is not None for mk in lt.masks) else None
             t0 = time.perf_counter()
-            oracle.forward(lt.X, lt.W, ot.row_task, kinds, ranks, scales, lt.A, lt.B, lt.L)
-            oracle.backward(lt.X, lt.dY, lt.W, ot.row_task, kinds, ranks, scales, lt.A, lt.B, lt.L)
+            oracle.forward(lt.X, lt.W, ot.row_task, kinds, ranks, scales, lt.A, lt.B, lt.L, S=S)
+            oracle.backward(lt.X, lt.dY, lt.W, ot.row_task, kinds, ranks, scales, lt.A, lt.B, lt.L, S=S)
             total += time.perf_counter() - t0
-        return ot.valid_total, total
+            flop += 4.0 * ot.valid_total * lt.K * lt.N
+        return ot.valid_total, total, flop
 
-    run(1)                                  # warm up (library load, OpenMP pool)
-    n0, t0 = run(8)
-    per_tok = t0 / max(n0, 1)
-    m = int(max(2, min(4096, seconds / max(per_tok, 1e-9) / max(len(wl.tasks), 1))))
-    n, t = run(m)
-    return {"value": n / t, "unit": "tokens/s", "cores": oracle.max_threads(), "kind": "oracle",
-            "sample": f"first {m} tokens of each of the {len(wl.tasks)} tasks ({n} tokens) through all "
-                      f"{len(wl.layers)} projections fwd+bwd, fp64, {t:.1f} s"}
+    all_layers = list(range(len(wl.layers)))
+    run(wl, all_layers[:1], 1)              # warm up (library load, OpenMP pool)
+    # two short runs give the fixed cost (outputs of the padded rows are still zeroed) and the cost per token
+    n0, t0, _ = run(wl, all_layers, 2)
+    n1, t1, _ = run(wl, all_layers, 12)
+    per_tok = max((t1 - t0) / max(n1 - n0, 1), 1e-9)
+    fixed = max(t0 - per_tok * n0, 0.0)
+    m = int(max(2, min(4096, max(seconds - fixed, 0.2 * seconds) / per_tok / max(len(wl.tasks), 1))))
+    n, t, flop = run(wl, all_layers, m)
+    out = {"value": n / t, "unit": "tokens/s", "cores": oracle.max_threads(), "kind": "oracle",
+           "gflops_backbone": flop / t / 1e9,
+           "sample": f"first {m} tokens of each of the {len(wl.tasks)} tasks ({n} tokens), aligned with the workload's "
+                     f"chunk size {wl.chunk}, through all {len(wl.layers)} projections fwd+bwd, fp64, {t:.1f} s"}
+    if full_runs:
+        full = {}
+        for label, idx, lids in (("configs[0] tiny, in full", 0, None), ("configs[1] llama7b, q projection in full", 1, [0])):
+            w = wlm.config(idx, seed=seed)
+            nn, tt, ff = run(w, list(range(len(w.layers))) if lids is None else lids)
+            full[label] = {"tokens": nn, "seconds": tt, "tokens_per_s": nn / tt, "gflops_backbone": ff / tt / 1e9}
+        out["in_full"] = full
+    return out
 
 
 def main():
@@ -584,16 +716,26 @@ def main():
     torch.cuda.synchronize()
 
     # timed region: K steps; the backbone GEMM launches are bracketed by HIP events recorded by the library on
-    # the launch stream (only those: an event pair costs microseconds, which matters for the 10-microsecond kernels)
+    # the launch stream (only those: an event pair costs microseconds, which matters for the 10-microsecond kernels).
+    # Around it: the first workgroup of every GEMM launch adds its cycle and 100 MHz tick counts to a device buffer
+    # (the clock the kernel really ran at), and a thread polls the driver's clock and power files.
+    tele = Telemetry()
+    clkbuf = torch.zeros(4, dtype=torch.int64, device="cuda:0")
+    mx.mux_diag_set_clock_buffer(clkbuf)
     mx.mux_profile_enable(2)
     mx.mux_profile_collect()
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(mx, st, dtab, layers, ws, ws_bytes, stream)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+
+    def timed_region():
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step(mx, st, dtab, layers, ws, ws_bytes, stream)
+        torch.cuda.synchronize()
+        return t0, time.perf_counter()
+    (t0, t1), telemetry = tele.sample_while(timed_region)
     prof = mx.mux_profile_collect()
+    gemm_clock_mhz = clock_from_buffer(torch, clkbuf)
+    mx.mux_diag_set_clock_buffer(None)
     # after the timed region: a few more steps with every kernel bracketed, for the per-kernel table
     mx.mux_profile_enable(1)
     extra_steps = min(args.steps, 5)
@@ -628,20 +770,35 @@ def main():
     for e in prof:          # the GEMM kernels, from the timed region itself
         kernels[e["name"]] = {"launches": e["launches"], "avg_us": e["total_ms"] * 1e3 / max(e["launches"], 1),
                               "total_ms_per_step": e["total_ms"] / args.steps, "timed_region": True}
-    # HBM-bound adapter kernels: algorithmic bytes per step (bf16 = 2 B, fp32 gradients = 4 B)
-    RP = ((max([t.rank for t in wl.tasks if t.kind == 1] + [1]) + 15) // 16) * 16
+    # HBM-bound adapter kernels: algorithmic bytes per step (bf16 = 2 B, fp32 gradients = 4 B), counted over the rows
+    # each kernel really streams: the VALID rows of the tasks whose kind it serves (padding rows and the rows of other
+    # kinds cost it no memory access), plus the small operands and what it writes.
+    valid_rows = [int(img[16 + 8 * t + 2]) for t in range(M)]          # real tokens per task
+    kinds = [t.kind for t in wl.tasks]
+    v_lora = sum(valid_rows[t] for t in range(M) if kinds[t] == 1)
+    v_rank = sum(valid_rows[t] for t in range(M) if kinds[t] in (1, 3))  # LoRA and Adapter-Tuning share down_g / the gradient pass
+    v_ia3 = sum(valid_rows[t] for t in range(M) if kinds[t] == 2)
+    v_tune = sum(valid_rows[t] for t in range(M) if kinds[t] == 3)
+    ranked = [t.rank for t in wl.tasks if t.kind in (1, 3)]
+    RP = ((max(ranked + [1]) + 15) // 16) * 16
     sum_r = sum(t.rank for t in wl.tasks if t.kind == 1)
+    sum_r13 = sum(ranked)
+    dims = [(K, N) for _, K, N in wl.layers]
     stream_bytes = {
-        "down_x": sum(2.0 * T * K + 2.0 * K * sum_r + 2.0 * T * RP for _, K, N in wl.layers),
-        "down_g": sum(2.0 * T * N + 2.0 * N * sum_r + 2.0 * T * RP for _, K, N in wl.layers),
-        "grad_dbda": sum(2.0 * T * (N + K) + 4.0 * T * RP + 4.0 * (N + K) * sum_r for _, K, N in wl.layers),
-        "grad_dl": sum(4.0 * ia3_rows * N for _, K, N in wl.layers),
+        # Hs / Gs are written for every aligned row (zeros outside the kernel's tasks)
+        "down_x": sum(2.0 * v_lora * K + 2.0 * K * sum_r + 2.0 * T * RP for K, N in dims),
+        "down_g": sum(2.0 * v_rank * N + 2.0 * N * sum_r13 + 2.0 * T * RP for K, N in dims),
+        # one pass over dY: Gs and dB_t together (reads Hs, writes Gs and the fp32 dB_t)
+        "s4_dy_pass": sum(2.0 * v_rank * N + 2.0 * N * sum_r13 + 2.0 * v_rank * RP + 2.0 * T * RP + 4.0 * N * sum_r13 for K, N in dims),
+        "grad_dbda": sum(2.0 * v_rank * (N + K) + 4.0 * v_rank * RP + 4.0 * (N + K) * sum_r13 for K, N in dims),
+        "grad_da": sum(2.0 * v_rank * K + 2.0 * v_rank * RP + 4.0 * K * sum_r13 for K, N in dims),
+        "grad_dl": sum(4.0 * v_ia3 * N + 4.0 * N * sum(1 for k in kinds if k == 2) for K, N in dims),
         # Adapter-Tuning steps: each streams the task's rows of z, dY or both once
-        "tune_down": sum(2.0 * tune_rows * N for _, K, N in wl.layers),
-        "tune_up": sum(4.0 * tune_rows * N for _, K, N in wl.layers),
-        "tune_g": sum(2.0 * tune_rows * N for _, K, N in wl.layers),
-        "tune_dz": sum(4.0 * tune_rows * N for _, K, N in wl.layers),
-        "tune_grads": sum(4.0 * tune_rows * N for _, K, N in wl.layers),
+        "tune_down": sum(2.0 * v_tune * N for K, N in dims),
+        "tune_up": sum(4.0 * v_tune * N for K, N in dims),
+        "tune_g": sum(2.0 * v_tune * N for K, N in dims),
+        "tune_dz": sum(4.0 * v_tune * N for K, N in dims),
+        "tune_grads": sum(4.0 * v_tune * N for K, N in dims),
     }
     # Diff-Pruning steps: the block-transposed copies move the task rows of X (or dY) once each way; the sparse update
     # reads the rows once, reads and writes the output rows and reads the lists of the mask (8 B an entry forward,
@@ -649,7 +806,6 @@ def main():
     diff_rows = sum(task_rows[t] for t in range(M) if wl.tasks[t].kind == 4)
     if diff_rows:
         nnz = [sum(m.nnz for m in L.masks if m is not None) for L in layers]
-        dims = [(K, N) for _, K, N in wl.layers]
         stream_bytes.update({
             "diff_xt": sum(8.0 * diff_rows * K for K, N in dims),      # launched forward and backward
             "diff_gt": sum(4.0 * diff_rows * N for K, N in dims),
@@ -659,8 +815,21 @@ def main():
         })
     for n, b in stream_bytes.items():
         if n in kernels and kernels[n]["total_ms_per_step"] > 0:
+            kernels[n]["bound"] = "hbm"
+            kernels[n]["algorithmic_bytes_per_launch"] = b / (kernels[n]["launches"] / extra_steps)
             kernels[n]["gbps"] = b / (kernels[n]["total_ms_per_step"] * 1e-3) / 1e9
             kernels[n]["frac_of_hbm_peak"] = kernels[n]["gbps"] / PEAK_HBM
+    # kernels that exist only because of how the path is cut into launches (partial sums brought together, the task
+    # table written): the method itself asks for none of their bytes, so they get the bytes they move, as the
+    # library counts them at the launch, and the rate that gives
+    for e in prof_all:
+        k = kernels.get(e["name"])
+        if k is not None and "gbps" not in k and e.get("bytes", 0.0) > 0 and k["total_ms_per_step"] > 0:
+            k["bound"] = "hbm"
+            k["algorithmic_bytes_per_launch"] = 0.0
+            k["moved_bytes_per_launch"] = e["bytes"] / e["launches"]
+            k["gbps_moved"] = e["bytes"] / extra_steps / (k["total_ms_per_step"] * 1e-3) / 1e9
+            k["frac_of_hbm_peak"] = k["gbps_moved"] / PEAK_HBM
     gemm_names = [n for n in kernels if n in gemm_flops]
     dom = max(gemm_names, key=lambda n: kernels[n]["total_ms_per_step"]) if gemm_names else None
     roofline = None
@@ -669,6 +838,14 @@ def main():
         roofline = {"kernel": dom, "bound": "mfma", "achieved": tf, "peak": PEAK_BF16_MFMA, "unit": "TFLOP/s",
                     "frac": tf / PEAK_BF16_MFMA, "traffic": None,
                     "launches_per_step": kernels[dom]["launches"] / args.steps, "avg_launch_us": kernels[dom]["avg_us"]}
+        # The clock the GEMM kernels ran at in the timed region (cycles over 100 MHz ticks of their first workgroups)
+        # and what the part could deliver at that clock with every matrix pipe busy all the time: 256 compute units x
+        # 4 SIMDs x 1024 FLOP a cycle (the nominal peak is this at 2.4 GHz).
+        if gemm_clock_mhz:
+            roofline["clock_mhz_in_kernel"] = gemm_clock_mhz
+            roofline["ceiling_at_clock"] = gemm_clock_mhz * 1e6 * 1024 * 1024 / 1e12
+            roofline["achieved_over_ceiling_at_clock"] = tf / roofline["ceiling_at_clock"]
+        roofline["telemetry"] = telemetry
     # HBM bytes per launch of that kernel from the committed rocprofv3 --pmc summary of this workload (two separate
     # counter runs, scaled by a plain copy of known size); null when no summary for this workload is there
     tpath = os.path.join(ROOT, "profiles", f"traffic_{wl.name}.txt")
@@ -761,12 +938,14 @@ def main():
         out["hip_graph_replay"] = {"ms_per_step": msg, "tokens_per_s": valid / (msg * 1e-3)}
     if not args.no_mfma_probe:
         out["hbm_read_probe"] = hbm_read_probe(mx, torch)
-        out["mfma_probe"] = mfma_probe(mx, torch, args.seed)
+        mx.mux_diag_set_clock_buffer(clkbuf)
+        out["mfma_probe"] = mfma_probe(mx, torch, args.seed, tele, clkbuf)
+        mx.mux_diag_set_clock_buffer(None)
         if out["roofline"].get("achieved"):
             # the same kernel against what the matrix cores of this machine sustain on such operands from registers
             out["roofline"]["achieved_over_mfma_probe"] = out["roofline"]["achieved"] / out["mfma_probe"]["like_benchmark"]
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds, args.seed)
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds, args.seed, not args.no_cpu_full)
     print(json.dumps(out))
 
 

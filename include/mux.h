@@ -21,11 +21,8 @@
  *   - Tensors are row-major and dense unless a leading dimension is given.
  *     X[T,K], W[K,N] (Y = X W, the orientation of Eq. 1), Y[T,N], dY[T,N], dX[T,K],
  *     A_t[K,r_t], B_t[r_t,N], l_t[N].  T = mux_segtab_rows().
- *   - Environment variables, for measurement and testing only (none is needed in normal use):
- *     MUX_GEMM_REGSTAGED (read at every call) runs the backbone product through the register-staged kernel also
- *     on the shapes the pipelined kernel takes; MUX_GEMM_BK32, MUX_GEMM_NO_HALF_TILES and MUX_GEMM_NO_QUARTER_TILES
- *     (read once per process) make the pipelined kernel use 32-deep stages everywhere, keep the tiles of the last
- *     round whole, and split them into halves where it would take quarters.
+ *   - Diagnostics (per-kernel timing, probes of the box, measurement switches) are declared in mux_diag.h; none
+ *     of them is needed in normal use.
  */
 #ifndef MUX_H_
 #define MUX_H_
@@ -201,40 +198,6 @@ mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_segtab* st,
                              const void* saved, void* dX, void* const* dA, void* const* dB,
                              void* const* dL, int accumulate, void* ws, size_t ws_bytes,
                              void* hip_stream);
-
-/* Per-kernel timing for benchmarks.  While enabled (on = 1: every kernel, on = 2: only the
- * backbone GEMM kernels, on = 0: off), each such launch is bracketed by two HIP events
- * recorded on the launch stream (no synchronisation is added; an event pair costs a few
- * microseconds of stream time, which is why mode 2 exists).
- * mux_profile_collect waits for the recorded events, fills up to `cap` entries with one line
- * per kernel (name, number of launches, summed duration in milliseconds), returns the number
- * of distinct kernels in *n, and clears the record.  Process-wide, not thread-safe; leave it
- * disabled under HIP graph capture. */
-typedef struct {
-  const char* name;   /* static string owned by the library */
-  int32_t launches;
-  double total_ms;
-} mux_profile_entry;
-mux_status mux_profile_enable(int on);
-mux_status mux_profile_collect(mux_profile_entry* host_out, int32_t cap, int32_t* n);
-
-/* Diagnostic for the roofline of the backbone GEMM: what the matrix cores sustain on bf16 operands that stay in
- * registers (two waves per SIMD on every compute unit, independent v_mfma_f32_32x32x16_bf16 back to back).  The
- * clock under such load is set by power, hence by the operand values, so the caller supplies them: `dev_operands`
- * holds mux_probe_mfma_operand_bytes() bytes of bf16 values (device, 16-byte aligned; every wave reads the same),
- * `dev_sink` receives mux_probe_mfma_sink_bytes() bytes of results nobody needs (device).  One launch of `iters`
- * loop turns on `hip_stream`, no synchronisation; *flop (host, may be null) is set to the floating-point
- * operations of the launch, so that the caller's timing gives FLOP/s. */
-size_t mux_probe_mfma_operand_bytes(void);
-size_t mux_probe_mfma_sink_bytes(void);
-mux_status mux_probe_mfma(const void* dev_operands, void* dev_sink, int32_t iters, void* hip_stream, double* flop);
-
-/* Diagnostic for the roofline of the adapter kernels: one plain read stream over `bytes` bytes at `dev_buf` (device,
- * 16-byte aligned; the last bytes % 16 bytes are not read), every 16-byte piece read once, each workgroup walking a
- * contiguous share with eight loads a thread in flight.  `dev_sink` receives mux_probe_read_sink_bytes() bytes nobody needs (device).  One launch on `hip_stream`,
- * no synchronisation; the caller's timing over `bytes` gives the GB/s a read stream reaches on the box. */
-size_t mux_probe_read_sink_bytes(void);
-mux_status mux_probe_read(const void* dev_buf, size_t bytes, void* dev_sink, void* hip_stream);
 
 const char* mux_last_error(void);
 const char* mux_version(void);

@@ -25,7 +25,7 @@ __all__ = [
     "mux_dispatch_gather", "mux_dispatch_scatter",
     "AttnDesc", "mux_attn_saved_bytes", "mux_attn_workspace_bytes", "mux_attn_forward", "mux_attn_backward",
     "mux_probe_mfma_operand_bytes", "mux_probe_mfma_sink_bytes", "mux_probe_mfma",
-    "mux_probe_read_sink_bytes", "mux_probe_read",
+    "mux_probe_read_sink_bytes", "mux_probe_read", "mux_diag_set_clock_buffer",
 ]
 
 MUX_OK = 0
@@ -173,6 +173,7 @@ def load_library() -> ctypes.CDLL:
         "mux_probe_mfma": (c_int, [vp, vp, c_int32, vp, POINTER(ctypes.c_double)]),
         "mux_probe_read_sink_bytes": (c_size_t, []),
         "mux_probe_read": (c_int, [vp, c_size_t, vp, vp]),
+        "mux_diag_set_clock_buffer": (c_int, [vp]),
         "mux_dispatch_gather": (c_int, [vp, vp, POINTER(vp), c_int64, vp, c_int64, c_int32, c_int32, vp]),
         "mux_dispatch_scatter": (c_int, [vp, vp, vp, c_int64, POINTER(vp), c_int64, c_int32, c_int32, vp]),
         "mux_attn_saved_bytes": (c_size_t, [POINTER(_AttnDescC), vp]),
@@ -308,6 +309,12 @@ def mux_probe_mfma_sink_bytes() -> int:
 
 def mux_probe_read_sink_bytes() -> int:
     return int(load_library().mux_probe_read_sink_bytes())
+
+
+def mux_diag_set_clock_buffer(dev_four_u64) -> None:
+    """Device buffer of four zeroed 64-bit words the matrix-core kernels add their cycle and 100 MHz tick counts to
+    (None switches it off)."""
+    _check(load_library().mux_diag_set_clock_buffer(_ptr(dev_four_u64)))
 
 
 def mux_probe_read(dev_buf, nbytes: int, dev_sink, stream=None) -> None:

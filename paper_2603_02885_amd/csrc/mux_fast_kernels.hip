@@ -9,6 +9,12 @@ size_t fast_partial_bytes(int K, int N, const mux_segtab* st) { return adapter_p
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
+// Measurement switch, read once per process: the register-staged backbone kernel on every shape.
+static bool regstaged() {
+  static const bool on = getenv("MUX_GEMM_REGSTAGED") != nullptr;
+  return on;
+}
+
 // The 16-byte loads of the matrix-core kernels need 16-byte aligned rows everywhere.
 static bool fast_ok(const CallCtx& c) { return gemm_mfma_supported(c); }
 
@@ -17,7 +23,7 @@ mux_status fast_forward(const CallCtx& c, const void* X, void* Y, void* H, void*
     return ref_forward(c, MUX_DT_BF16, X, Y, H, Z);    // shapes the 16-byte loads cannot take
   if (mux_status s = adapter_down_x(c, X, H)) return s;
   mux_status s;
-  if (gemm_dma_supported(c, false) && !getenv("MUX_GEMM_REGSTAGED")) s = gemm_dma_forward(c, X, H, Y, Z);
+  if (gemm_dma_supported(c, false) && !regstaged()) s = gemm_dma_forward(c, X, H, Y, Z);
   else s = gemm_mfma_forward(c, X, H, Y, Z);
   if (s != MUX_OK) return s;
   // Adapter-Tuning rows: the GEMM saved x W; the bottleneck follows (u = z D_t, Y = z + s_t gelu(u) U_t)
@@ -37,7 +43,7 @@ mux_status fast_backward(const CallCtx& c, const void* X, const void* dY, const 
   if (mux_status s = adapter_tune_add(c, dY, G, c.dYs, 1)) return s;
   if (mux_status s = adapter_grads(c, X, dY, H, G, Z, part, accumulate)) return s;
   if (!dX) return MUX_OK;
-  if (gemm_dma_supported(c, true) && !getenv("MUX_GEMM_REGSTAGED")) {
+  if (gemm_dma_supported(c, true) && !regstaged()) {
     // IA3_OUT rows read dY * l_t, written by the dl kernel above
     return gemm_dma_backward(c, dY, G, dX);
   }

@@ -55,6 +55,7 @@ struct GemmParams {
   int n_m, n_n, per_xcd;   // tile grid in units of 256 x TILE_N tiles; workgroups per XCD over the whole grid
   int n_full;              // workgroups that compute full tiles (a multiple of 8); the rest compute pieces of tiles
   int tail_split;          // pieces per tile after the full ones: 2 (halves) or 4 (quarters)
+  unsigned long long* clk;  // diagnostic: counters workgroup 0 adds its elapsed cycles and 100 MHz ticks to (null: off)
   const bf16_t* AinScaled;  // backward: prepared input rows (IA3_OUT: dY * l_t; TUNING: dY + p D_t^T), [z_rows, Kc], indexed like the saved x W
 };
 
@@ -554,6 +555,8 @@ __global__ __launch_bounds__(512, 1) void k_gemm_dma(const GemmParams p) {
   __shared__ int sRow[256];
   const Smem sm = {sA0, sA1, sA2, sA3, sB0, sB1, sB2, sB3, sRow};
   const int b = blockIdx.x;
+  // the start stamps wait in the buffer itself (words 2, 3), so that nothing stays live across the tile
+  if (p.clk != nullptr && b == 0 && threadIdx.x == 0) { p.clk[2] = clock64(); p.clk[3] = wall_clock64(); }
   if (b < p.n_full) {
     gemm_tile<NT, 4, 4, 2, BK>(p, b, 0, 0, sm);
   } else if (p.tail_split == 2) {
@@ -562,6 +565,10 @@ __global__ __launch_bounds__(512, 1) void k_gemm_dma(const GemmParams p) {
   } else {
     const int t = b - p.n_full;
     gemm_tile<NT, 2, 2, 2, BK>(p, p.n_full + (((t >> 5) << 3) | (t & 7)), (t >> 3) & 1, (t >> 4) & 1, sm);
+  }
+  if (p.clk != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
+    atomicAdd(p.clk, (unsigned long long)clock64() - p.clk[2]);
+    atomicAdd(p.clk + 1, (unsigned long long)wall_clock64() - p.clk[3]);
   }
 }
 
@@ -584,6 +591,7 @@ mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t
   p.n_m = (int)c.st->items[TS256].size();
   p.n_n = (Nc + TILE_N - 1) / TILE_N;
   p.AinScaled = (const bf16_t*)c.dYs;
+  p.clk = diag_clock_buffer();
   const int total = p.n_m * p.n_n;
   if (total == 0) return MUX_OK;
   p.per_xcd = (total + 7) / 8;

@@ -6,6 +6,7 @@
 #include <vector>
 
 #include "mux.h"
+#include "mux_diag.h"
 
 namespace mux {
 
@@ -92,6 +93,9 @@ struct ProfScope {
   ProfScope(const char* name, hipStream_t stream) : s(stream) { prof_begin(name, stream); }
   ~ProfScope() { prof_end(s); }
 };
+
+// Device buffer of two 64-bit words set by mux_diag_set_clock_buffer (null when off): see mux_diag.h.
+unsigned long long* diag_clock_buffer();
 
 #define MUX_LAUNCH(name, kernel, grid, block, smem, stream, ...)         \
   do {                                                                   \

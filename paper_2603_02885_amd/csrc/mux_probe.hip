@@ -15,8 +15,10 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr int kProbeBlocks = 512, kProbeThreads = 256;    // 2048 waves: two per SIMD of 256 compute units
 
 __global__ __launch_bounds__(256, 2) void k_probe_mfma(const uint4* __restrict__ operands, float* __restrict__ sink,
-                                                       int iters) {
+                                                       int iters, unsigned long long* __restrict__ clk) {
   const int lane = threadIdx.x & 63;
+  const bool stamp = clk != nullptr && blockIdx.x == 0 && threadIdx.x == 0;
+  if (stamp) { clk[2] = clock64(); clk[3] = wall_clock64(); }
   bf16x8 a[8], b[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
@@ -40,6 +42,10 @@ __global__ __launch_bounds__(256, 2) void k_probe_mfma(const uint4* __restrict__
 #pragma unroll
     for (int v = 0; v < 16; ++v) s += acc[j][v];
   sink[(size_t)blockIdx.x * kProbeThreads + threadIdx.x] = s;
+  if (stamp) {
+    atomicAdd(clk, (unsigned long long)clock64() - clk[2]);
+    atomicAdd(clk + 1, (unsigned long long)wall_clock64() - clk[3]);
+  }
 }
 
 // Read stream: a workgroup sums the 16-byte pieces of its own contiguous share of the buffer, 4 KB per wave
@@ -92,7 +98,7 @@ extern "C" mux_status mux_probe_mfma(const void* dev_operands, void* dev_sink, i
   if (!dev_operands || !dev_sink || iters < 1) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": null buffer or iters < 1");
   if (((uintptr_t)dev_operands & 15) != 0) return fail(MUX_ERR_UNSUPPORTED, std::string(fn) + ": operands must be 16-byte aligned");
   hipLaunchKernelGGL(k_probe_mfma, dim3(kProbeBlocks), dim3(kProbeThreads), 0, (hipStream_t)hip_stream,
-                     (const uint4*)dev_operands, (float*)dev_sink, (int)iters);
+                     (const uint4*)dev_operands, (float*)dev_sink, (int)iters, diag_clock_buffer());
   if (flop) *flop = (double)kProbeBlocks * (kProbeThreads / 64) * (double)iters * 64.0 * (2.0 * 32 * 32 * 16);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(MUX_ERR_DEVICE, std::string(fn) + ": " + hipGetErrorString(e));

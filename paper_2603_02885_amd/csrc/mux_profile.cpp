@@ -16,6 +16,7 @@ std::vector<Rec> g_recs;
 std::vector<hipEvent_t> g_pool;
 hipEvent_t g_open = nullptr;
 const char* g_open_name = nullptr;
+unsigned long long* g_clock = nullptr;
 
 hipEvent_t get_event() {
   if (!g_pool.empty()) { hipEvent_t e = g_pool.back(); g_pool.pop_back(); return e; }
@@ -24,6 +25,8 @@ hipEvent_t get_event() {
   return e;
 }
 }  // namespace
+
+unsigned long long* diag_clock_buffer() { return g_clock; }
 
 void prof_begin(const char* name, hipStream_t stream) {
   if (!g_on) return;
@@ -47,6 +50,12 @@ void prof_end(hipStream_t stream) {
 }  // namespace mux
 
 using namespace mux;
+
+extern "C" mux_status mux_diag_set_clock_buffer(void* dev_four_u64) {
+  if (((uintptr_t)dev_four_u64 & 7) != 0) return fail(MUX_ERR_INVALID_ARG, "mux_diag_set_clock_buffer: the buffer must be 8-byte aligned");
+  g_clock = (unsigned long long*)dev_four_u64;
+  return MUX_OK;
+}
 
 extern "C" mux_status mux_profile_enable(int on) {
   if (on < 0 || on > 2) return fail(MUX_ERR_INVALID_ARG, "mux_profile_enable: mode must be 0, 1 or 2");

@@ -413,30 +413,21 @@ def test_graph_capture_and_replay(env, which):
         torch.cuda.synchronize()
 
 
-def test_register_staged_gemm_on_shapes_of_the_pipelined_one(env, monkeypatch):
-    """MUX_GEMM_REGSTAGED (read at every call) routes the backbone product through the register-staged kernel, which
-    otherwise only sees the shapes the pipelined kernel does not take: same parity on a shape both can run."""
-    monkeypatch.setenv("MUX_GEMM_REGSTAGED", "1")
-    run_case(env, mixed_workload(K=320, N=256), seed=21)
-    run_case(env, tuning_workload(K=192, N=160), seed=22)
-    monkeypatch.delenv("MUX_GEMM_REGSTAGED")
-    run_case(env, mixed_workload(K=320, N=256), seed=21)
-
-
-@pytest.mark.parametrize("var", ["MUX_GEMM_BK32", "MUX_GEMM_NO_HALF_TILES", "MUX_GEMM_NO_QUARTER_TILES"])
+@pytest.mark.parametrize("var", ["MUX_GEMM_BK32", "MUX_GEMM_NO_HALF_TILES", "MUX_GEMM_NO_QUARTER_TILES", "MUX_GEMM_REGSTAGED"])
 def test_gemm_variants_in_a_fresh_process(env, var):
     """The switches that are read once per process (32-deep stages where 64-deep ones would be taken; full tiles
-    only; half-width tiles where quarters would be taken for the last round): a parity case in a child process with
-    the switch set."""
+    only; half-width tiles where quarters would be taken for the last round; the register-staged kernel, which
+    otherwise only sees the shapes the pipelined kernel does not take, on shapes both can run): a parity case in a
+    child process with the switch set."""
     import os
     import subprocess
     import sys
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     code = ("import torch, paper_2603_02885_amd as mx; mx.load_library(); import mux_workloads as wlm;"
-            "from tests.test_gpu_parity import run_case, mixed_workload;"
+            "from tests.test_gpu_parity import run_case, mixed_workload, tuning_workload;"
             "tasks = [wlm.Task(wlm.KIND_LORA, 16, 2.0, [700]), wlm.Task(wlm.KIND_IA3, 0, 1.0, [300]), wlm.Task(wlm.KIND_LORA, 40, 1.0, [900])];"
             "wl = wlm.Workload(name='v', layers=[('w', 512, 1280)], tasks=tasks, chunk=64, sigma_w=0.04, sigma_ab=0.05);"
-            "run_case((mx, torch), wl, seed=5); run_case((mx, torch), mixed_workload(K=320, N=256), seed=6); print('variant ok')")
+            "run_case((mx, torch), wl, seed=5); run_case((mx, torch), mixed_workload(K=320, N=256), seed=6); run_case((mx, torch), tuning_workload(K=192, N=160), seed=22); print('variant ok')")
     envv = dict(os.environ)
     envv[var] = "1"
     r = subprocess.run([sys.executable, "-c", code], cwd=root, env=envv, capture_output=True, text=True, timeout=110)
