@@ -199,6 +199,21 @@ mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_segtab* st,
                              void* const* dL, int accumulate, void* ws, size_t ws_bytes,
                              void* hip_stream);
 
+/* mux_lora_backward for callers that cannot allocate device memory or hand over a workspace: code running under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results (bit for bit)
+ * as mux_lora_backward without `ws` / `ws_bytes`: the workspace is a device array of MUX_STATIC_WS_BYTES bytes inside
+ * the library, one copy per GPU, held from the loading of the library until the process ends.  The call allocates
+ * nothing and frees nothing; its first call on a device looks the array's address up once (make that call outside a
+ * capture).  A call whose mux_lora_workspace_bytes() exceeds MUX_STATIC_WS_BYTES returns MUX_ERR_WORKSPACE and
+ * launches nothing.  All calls on one GPU share that GPU's array: the array keeps the last call's contents (every
+ * call writes what it reads, nothing has to start at zero), and two such calls that overlap in time on one GPU (two
+ * streams, two threads) race on it; order them on one stream or with events. */
+#define MUX_STATIC_WS_BYTES ((size_t)32 << 20)
+mux_status mux_lora_backward_static_ws(const mux_layer_desc* layer, const mux_segtab* st,
+                                       const void* dev_segtab, const void* X, const void* dY,
+                                       const void* saved, void* dX, void* const* dA, void* const* dB,
+                                       void* const* dL, int accumulate, void* hip_stream);
+
 const char* mux_last_error(void);
 const char* mux_version(void);
 

@@ -20,7 +20,7 @@ __all__ = [
     "mux_segtab_rows", "mux_segtab_n_chunks", "mux_segtab_n_tasks", "mux_segtab_valid_tokens",
     "mux_segtab_serialized_bytes", "mux_segtab_serialize", "mux_segtab_row_task", "mux_segtab_device_bytes",
     "mux_segtab_upload", "mux_lora_saved_bytes", "mux_lora_workspace_bytes", "mux_lora_forward",
-    "mux_lora_backward", "mux_last_error", "mux_version", "mux_profile_enable", "mux_profile_collect",
+    "mux_lora_backward", "mux_lora_backward_static_ws", "MUX_STATIC_WS_BYTES", "mux_last_error", "mux_version", "mux_profile_enable", "mux_profile_collect",
     "CostModel", "mux_plan_stage_latency", "mux_plan_htask_latency", "mux_plan_fusion",
     "mux_dispatch_gather", "mux_dispatch_scatter",
     "AttnDesc", "mux_attn_saved_bytes", "mux_attn_workspace_bytes", "mux_attn_forward", "mux_attn_backward",
@@ -34,6 +34,7 @@ MUX_DT_BF16, MUX_DT_F32 = 0, 1
 MUX_SEGTAB_DENSE = 1
 MUX_LAYER_REFERENCE_KERNELS = 1
 MUX_MAX_RANK = 64
+MUX_STATIC_WS_BYTES = 32 << 20
 
 _STATUS_NAMES = {1: "MUX_ERR_INVALID_ARG", 2: "MUX_ERR_SHAPE", 3: "MUX_ERR_UNSUPPORTED", 4: "MUX_ERR_WORKSPACE",
                  5: "MUX_ERR_HOST_NOMEM", 6: "MUX_ERR_DEVICE"}
@@ -164,6 +165,8 @@ def load_library() -> ctypes.CDLL:
         "mux_lora_forward": (c_int, [POINTER(_LayerDescC), vp, vp, vp, vp, vp, vp, c_size_t, vp]),
         "mux_lora_backward": (c_int, [POINTER(_LayerDescC), vp, vp, vp, vp, vp, vp, POINTER(vp), POINTER(vp),
                                       POINTER(vp), c_int, vp, c_size_t, vp]),
+        "mux_lora_backward_static_ws": (c_int, [POINTER(_LayerDescC), vp, vp, vp, vp, vp, vp, POINTER(vp), POINTER(vp),
+                                                POINTER(vp), c_int, vp]),
         "mux_profile_enable": (c_int, [c_int]),
         "mux_profile_collect": (c_int, [POINTER(_ProfileEntryC), c_int32, POINTER(c_int32)]),
         "mux_last_error": (c_char_p, []),
@@ -418,6 +421,16 @@ def mux_lora_backward(layer: LayerDesc, st: SegTab, dev_segtab, X, dY, saved, dX
         ctypes.byref(layer.c), st.handle, _ptr(dev_segtab), _ptr(X), _ptr(dY), _ptr(saved), _ptr(dX),
         ctypes.cast(pa, POINTER(c_void_p)), ctypes.cast(pb, POINTER(c_void_p)), ctypes.cast(pl, POINTER(c_void_p)),
         int(accumulate), _ptr(ws), int(ws_bytes), _stream(stream)))
+
+
+def mux_lora_backward_static_ws(layer: LayerDesc, st: SegTab, dev_segtab, X, dY, saved, dX, dA, dB, dL, accumulate: int,
+                                stream=None) -> None:
+    n = layer.n_tasks
+    pa, pb, pl = _ptr_array(dA, n), _ptr_array(dB, n), _ptr_array(dL, n)
+    _check(load_library().mux_lora_backward_static_ws(
+        ctypes.byref(layer.c), st.handle, _ptr(dev_segtab), _ptr(X), _ptr(dY), _ptr(saved), _ptr(dX),
+        ctypes.cast(pa, POINTER(c_void_p)), ctypes.cast(pb, POINTER(c_void_p)), ctypes.cast(pl, POINTER(c_void_p)),
+        int(accumulate), _stream(stream)))
 
 
 def mux_profile_enable(on) -> None:

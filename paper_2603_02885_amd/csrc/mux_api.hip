@@ -1,5 +1,7 @@
 // Entry points of the layer: argument checks, buffer carving, kernel sequencing.
 #include <cstring>
+#include <mutex>
+#include <string>
 
 #include "mux_device_utils.h"
 
@@ -233,11 +235,11 @@ extern "C" mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_se
   return check_hip(fn);
 }
 
-extern "C" mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_segtab* st, const void* dev_segtab,
-                                        const void* X, const void* dY, const void* saved, void* dX, void* const* dA,
-                                        void* const* dB, void* const* dL, int accumulate, void* ws, size_t ws_bytes,
-                                        void* hip_stream) {
-  static const char* fn = "mux_lora_backward";
+// The backward pass behind both entry points; `ws` is the caller's workspace or the library's static one.
+static mux_status backward_impl(const char* fn, const mux_layer_desc* layer, const mux_segtab* st, const void* dev_segtab,
+                                const void* X, const void* dY, const void* saved, void* dX, void* const* dA,
+                                void* const* dB, void* const* dL, int accumulate, void* ws, size_t ws_bytes,
+                                void* hip_stream) {
   if (mux_status s = check_layer(fn, layer, st)) return s;
   if (accumulate != 0 && accumulate != 1) return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": accumulate must be 0 or 1");
   if (st->T == 0 && st->n_tasks == 0) return MUX_OK;
@@ -276,4 +278,56 @@ extern "C" mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_s
   if (s) return s;
   diff_backward(c, layer->dtype, X, dY, dX, accumulate);
   return check_hip(fn);
+}
+
+extern "C" mux_status mux_lora_backward(const mux_layer_desc* layer, const mux_segtab* st, const void* dev_segtab,
+                                        const void* X, const void* dY, const void* saved, void* dX, void* const* dA,
+                                        void* const* dB, void* const* dL, int accumulate, void* ws, size_t ws_bytes,
+                                        void* hip_stream) {
+  return backward_impl("mux_lora_backward", layer, st, dev_segtab, X, dY, saved, dX, dA, dB, dL, accumulate, ws, ws_bytes,
+                       hip_stream);
+}
+
+// ---- the backward pass for callers that cannot allocate: its workspace is a file-scope device array -------------------
+namespace {
+
+constexpr size_t kStaticWsBytes = MUX_STATIC_WS_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticWsBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];      // per device: the address of that device's copy of `scratch`
+
+// Address of the current device's copy of the array (looked up once per device, with that device current).
+mux_status static_workspace(const char* fn, void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+    return fail(MUX_ERR_DEVICE, std::string(fn) + ": no current device");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p)
+      return fail(MUX_ERR_DEVICE, std::string(fn) + ": hipGetSymbolAddress: " + hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MUX_OK;
+}
+
+}  // namespace
+
+extern "C" mux_status mux_lora_backward_static_ws(const mux_layer_desc* layer, const mux_segtab* st, const void* dev_segtab,
+                                                  const void* X, const void* dY, const void* saved, void* dX,
+                                                  void* const* dA, void* const* dB, void* const* dL, int accumulate,
+                                                  void* hip_stream) {
+  static const char* fn = "mux_lora_backward_static_ws";
+  if (mux_status s = check_layer(fn, layer, st)) return s;
+  const size_t need = make_layout(layer, st).ws_bytes;
+  if (need > kStaticWsBytes)
+    return fail(MUX_ERR_WORKSPACE, std::string(fn) + ": this call needs " + std::to_string(need) +
+                                       " bytes of workspace, the static one holds " + std::to_string(kStaticWsBytes));
+  void* ws = nullptr;
+  if (mux_status s = static_workspace(fn, &ws)) return s;
+  return backward_impl(fn, layer, st, dev_segtab, X, dY, saved, dX, dA, dB, dL, accumulate, ws, kStaticWsBytes, hip_stream);
 }
