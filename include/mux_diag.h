@@ -24,13 +24,16 @@ extern "C" {
  * recorded on the launch stream (no synchronisation is added; an event pair costs a few
  * microseconds of stream time, which is why mode 2 exists).
  * mux_profile_collect waits for the recorded events, fills up to `cap` entries with one line
- * per kernel (name, number of launches, summed duration in milliseconds), returns the number
+ * per kernel (name, number of launches, summed duration in milliseconds; for the kernels that only bring partial
+ * sums together or write the task table -- the method itself asks for none of their bytes -- the bytes they moved
+ * as the library counts them at the launch, else 0), returns the number
  * of distinct kernels in *n, and clears the record.  Process-wide, not thread-safe; leave it
  * disabled under HIP graph capture. */
 typedef struct {
   const char* name;   /* static string owned by the library */
   int32_t launches;
   double total_ms;
+  double bytes;       /* summed over the launches; 0 where the caller counts the algorithmic bytes itself */
 } mux_profile_entry;
 mux_status mux_profile_enable(int on);
 mux_status mux_profile_collect(mux_profile_entry* host_out, int32_t cap, int32_t* n);

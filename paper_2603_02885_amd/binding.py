@@ -63,7 +63,7 @@ class _LayerDescC(ctypes.Structure):
 
 
 class _ProfileEntryC(ctypes.Structure):
-    _fields_ = [("name", c_char_p), ("launches", c_int32), ("total_ms", ctypes.c_double)]
+    _fields_ = [("name", c_char_p), ("launches", c_int32), ("total_ms", ctypes.c_double), ("bytes", ctypes.c_double)]
 
 
 class _AttnDescC(ctypes.Structure):
@@ -443,7 +443,8 @@ def mux_profile_collect(cap: int = 64) -> List[dict]:
     arr = (_ProfileEntryC * cap)()
     n = c_int32(0)
     _check(load_library().mux_profile_collect(arr, cap, ctypes.byref(n)))
-    return [{"name": arr[i].name.decode(), "launches": int(arr[i].launches), "total_ms": float(arr[i].total_ms)}
+    return [{"name": arr[i].name.decode(), "launches": int(arr[i].launches), "total_ms": float(arr[i].total_ms),
+             "bytes": float(arr[i].bytes)}
             for i in range(min(n.value, cap))]
 
 

@@ -2,10 +2,12 @@
 // activation matrix once from HBM and are bound by that stream; the MFMA only keeps the
 // arithmetic (r FLOP per byte) off the vector ALUs.
 //
-//   down:  Out[T,RP] = s_t * In[T,C] P_t^T      S1: In = X,  P_t = A_t^T (pre-transposed, [r][K])
-//                                               S4: In = dY, P_t = B_t            ([r][N])
+//   down:  Out[T,RP] = s_t * In[T,C] P_t^T      S1: In = X,  P_t^T = A_t as it is ([K][r], ranks that are multiples
+//                                               of 8) or P_t = A_t^T from the transposed region ([r][K])
+//   s4:    one pass over dY for both of its products (the adapter's backward is computed "in a fused manner",
+//          section 3.2): per (row group, 512-column slab) the slab's share of dY B_t^T (summed over the slabs and scaled
+//          by gs_reduce -> Gs[T,RP]) and the row group's share of Hs^T dY (summed over the row groups by reduce -> dB_t)
 //   grad:  part[item][r][C] = sum_{rows of item} Small[i][:]^T Big[i][:]
-//                                               S4: Small = Hs, Big = dY  -> dB_t[r][N]
 //                                               S6: Small = Gs, Big = X   -> dA_t[K][r] (transposed on reduce)
 //   dl:    part[item][N] = sum_{rows of item} dY[i][:] * Z[i][:]          (IA3_OUT)
 //   reduce: per task, partials summed in ascending item order (deterministic), optional accumulate.
@@ -44,20 +46,24 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast
 // on this memory system), two slabs ahead in registers, pass through a wave-private LDS region in their natural
 // layout and come back in the 16x16x32 MFMA operand layout.  No workgroup barrier in the loop.  The partial sums
 // of the waves are combined through LDS in a fixed order.
-//   DOWN_X     LoRA items: Out = s_t X A_t (P_t = A_t^T from the transposed region); rows of other kinds: zero
-//   DOWN_G     LoRA items: Out = s_t dY B_t^T; TUNING items: Out = s_t (dY U_t^T) * gelu'(u), u from U2;
-//              rows of other kinds: zero
+//   DOWN_X     LoRA items: Out = s_t X A_t; rows of other kinds: zero.  NAT: A_t is read as it is, [K][r] with r a
+//              multiple of 8 -- the 64 rows of a slab are one contiguous run of 128 r bytes, laid into LDS row by row
+//              and read back with the contraction index contiguous through ds_read_b64_tr_b16; else P_t = A_t^T from
+//              the transposed region.
 //   DOWN_TUNE  TUNING items only (other rows are left alone): u = z D_t with z from the saved compact rows and
 //              P_t = D_t^T from the transposed region; U2 = u, Out = s_t gelu(u)
-enum : int { DOWN_X = 0, DOWN_G = 1, DOWN_TUNE = 2 };
+// The work item and the validity bits of its rows come from two lists whose offsets are launch arguments, so the
+// first loads of X wait for one memory latency, not for a chain of them.
+enum : int { DOWN_X = 0, DOWN_TUNE = 2 };
 struct DownParams {
   const int32_t* dtab;
-  const DevTask* tasks;
   const bf16_t* In;    // [T, C]  (DOWN_TUNE: [z_rows, C], rows numbered like the saved x W)
   bf16_t* Out;         // [T, RP]
-  const bf16_t* AT;    // base of the transposed region (DOWN_X, DOWN_TUNE); DOWN_G: null (B_t / U_t as they are)
-  bf16_t* U2;          // [T, RP] pre-activations of the TUNING rows: written by DOWN_TUNE, read by DOWN_G
+  const bf16_t* AT;    // base of the transposed region (null with NAT)
+  bf16_t* U2;          // [T, RP] pre-activations of the TUNING rows: written by DOWN_TUNE
   int C, RP, mode;
+  int items_off, bits_off;   // word offsets in dtab: 64-row items, and two words of row-validity bits per item
+  TaskRef tasks;
 };
 
 __device__ __forceinline__ float gelu_f(float u) { return 0.5f * u * (1.f + erff(u * 0.70710678f)); }
@@ -67,25 +73,28 @@ __device__ __forceinline__ float gelu_slope_f(float u) {
 
 constexpr int GP = 72;   // LDS row pitch in elements (144 B): 16 consecutive rows of one 16-byte piece hit 64 different banks
 
-template <int NJM, int NWV, int DEPTH>
+template <int NJM, int NWV, int DEPTH, bool NAT>
 __global__ __launch_bounds__(64 * NWV) void k_down(const DownParams p) {
   constexpr int ROWS = 32, NTHR = 64 * NWV;
-  constexpr int SLAB = (ROWS + NJM * 16) * GP;                 // elements per wave: In slab, then P slab
+  constexpr int PP = NJM * 16 + 8;                              // NAT: LDS pitch of the [64][r] slab of A_t (elements)
+  constexpr int PSLAB = NAT ? 64 * PP : NJM * 16 * GP;
+  constexpr int SLAB = ROWS * GP + PSLAB;                      // elements per wave: In slab, then P slab
   constexpr int REDW = NJM * 16 * (ROWS + 4) * 2;              // the same region later holds the partial sums (floats)
   constexpr int REGION = SLAB > REDW ? SLAB : REDW;
   __shared__ __attribute__((aligned(16))) bf16_t lds[NWV][REGION];
   const int item = blockIdx.x >> 1, sub = blockIdx.x & 1;
-  const ItemView it = load_item(p.dtab, TS64, item);
+  const int4 iw = *(const int4*)(p.dtab + p.items_off + item * DI_WORDS);
+  const uint32_t vbits = ((const uint32_t*)(p.dtab + p.bits_off))[2 * item + sub];
+  const ItemView it = {iw.x, iw.y, iw.z, iw.w};
   const int r0 = sub * ROWS;
   if (r0 >= it.nrows) return;
   const int nr = it.nrows - r0 < ROWS ? it.nrows - r0 : ROWS;
   const int row0 = it.row0 + r0;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int kind = it.task >= 0 ? p.tasks[it.task].kind : MUX_ADAPTER_NONE;
-  const bool tuning = kind == MUX_ADAPTER_TUNING;
-  const bool mine = p.mode == DOWN_TUNE ? tuning : (kind == MUX_ADAPTER_LORA || (p.mode == DOWN_G && tuning));
+  const int kind = it.task >= 0 ? get_task_kind(p.tasks, it.task) : MUX_ADAPTER_NONE;
+  const bool mine = p.mode == DOWN_TUNE ? kind == MUX_ADAPTER_TUNING : kind == MUX_ADAPTER_LORA;
   if (!mine && p.mode == DOWN_TUNE) return;
-  if (!mine || it.nvalid == 0) {
+  if (!mine || vbits == 0u) {
     for (int e = tid; e < nr * p.RP; e += NTHR) {
       const size_t o = (size_t)(row0 + e / p.RP) * p.RP + e % p.RP;
       p.Out[o] = 0;
@@ -93,10 +102,10 @@ __global__ __launch_bounds__(64 * NWV) void k_down(const DownParams p) {
     }
     return;
   }
-  const DevTask tk = p.tasks[it.task];
+  const DevTask tk = get_task(p.tasks, it.task);
   const int rank = tk.rank, NJ = (rank + 15) >> 4;
-  const bf16_t* P = p.AT ? p.AT + tk.at_off : (const bf16_t*)tk.B;
-  const int prow = p.AT ? NJ * 16 : rank;            // rows that exist in P
+  const bf16_t* P = NAT ? (const bf16_t*)tk.A : p.AT + tk.at_off;
+  const int prow = NJ * 16;                          // rows that exist in a transposed P
 
   const int per = ((p.C + NWV - 1) / NWV + 63) & ~63;
   const int cbeg = wave * per, cend = cbeg + per < p.C ? cbeg + per : p.C;
@@ -105,19 +114,34 @@ __global__ __launch_bounds__(64 * NWV) void k_down(const DownParams p) {
 
   const size_t in_row0 = p.mode == DOWN_TUNE ? (size_t)(tk.zrow0 + row0 - tk.row_begin) : (size_t)row0;
   const rsrc_t rIn = make_rsrc(p.In + in_row0 * p.C, (uint32_t)nr * (uint32_t)p.C * 2u);
-  const rsrc_t rP = make_rsrc(P, (uint32_t)prow * (uint32_t)p.C * 2u);
+  const rsrc_t rP = make_rsrc(P, (NAT ? (uint32_t)p.C * (uint32_t)rank : (uint32_t)prow * (uint32_t)p.C) * 2u);
   // one wave instruction: 8 rows x 128 B; lane -> row lane/8 (+ 8 q), 16-byte piece lane%8
   const int b_row = lane >> 3, b_pc = (lane & 7) * 8;
   uint32_t x_off[4], p_off[2 * NJM];
+  int p_lds[2 * NJM];
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int m = b_row + 8 * q;
-    x_off[q] = (m < nr && row_is_valid(p.dtab, row0 + m)) ? ((uint32_t)m * (uint32_t)p.C + (uint32_t)b_pc) * 2u : OOB;
+    x_off[q] = (m < nr && ((vbits >> m) & 1u)) ? ((uint32_t)m * (uint32_t)p.C + (uint32_t)b_pc) * 2u : OOB;
   }
+  if (NAT) {
+    // the [64][rank] slab is 8 rank 16-byte pieces in a row; piece -> (row, piece of the row)
+    const int ppr = rank >> 3;
 #pragma unroll
-  for (int q = 0; q < 2 * NJM; ++q) {
-    const int j = b_row + 8 * q;
-    p_off[q] = (q < 2 * NJ && j < prow) ? ((uint32_t)j * (uint32_t)p.C + (uint32_t)b_pc) * 2u : OOB;
+    for (int q = 0; q < 2 * NJM; ++q) {
+      const int piece = q * 64 + lane;
+      p_off[q] = q < ppr ? (uint32_t)piece * 16u : OOB;
+      p_lds[q] = (piece / ppr) * PP + (piece % ppr) * 8;
+    }
+    // columns of the LDS slab beyond the rank are never written: they read as zero
+    for (int e = lane; e < 64 * (PP / 8); e += 64) *(u32x4*)(sP + (e / (PP / 8)) * PP + (e % (PP / 8)) * 8) = (u32x4){0u, 0u, 0u, 0u};
+  } else {
+#pragma unroll
+    for (int q = 0; q < 2 * NJM; ++q) {
+      const int j = b_row + 8 * q;
+      p_off[q] = (q < 2 * NJ && j < prow) ? ((uint32_t)j * (uint32_t)p.C + (uint32_t)b_pc) * 2u : OOB;
+      p_lds[q] = j * GP + b_pc;
+    }
   }
 
   f32x4 acc[2][NJM];
@@ -131,13 +155,19 @@ __global__ __launch_bounds__(64 * NWV) void k_down(const DownParams p) {
   // exist gets an out-of-range offset, costs no memory access and reads as zeros): the compiler can then count the
   // loads still in flight when it waits for a slab, instead of waiting for all of them.
   auto load = [&](int c, int buf) {          // a slab that starts past the end of this wave's share reads as zeros
-    const uint32_t k = (c + b_pc < cend) ? (uint32_t)c * 2u : OOB;     // OOB + OOB wraps into range: mask on k only
+    const bool in = c < cend;                 // the share ends on a multiple of 64 or at C, where the buffer ends
+    const uint32_t kx = (c + b_pc < cend) ? (uint32_t)c * 2u : OOB;     // OOB + OOB wraps into range: mask on k only
+    const uint32_t kp = in ? (NAT ? (uint32_t)c * (uint32_t)rank * 2u : (uint32_t)c * 2u) : OOB;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) gx[buf][q] = buf_load16(rIn, (x_off[q] == OOB || k == OOB) ? OOB : x_off[q] + k);
+    for (int q = 0; q < 4; ++q) gx[buf][q] = buf_load16(rIn, (x_off[q] == OOB || kx == OOB) ? OOB : x_off[q] + kx);
 #pragma unroll
-    for (int q = 0; q < 2 * NJM; ++q) gp[buf][q] = buf_load16(rP, (p_off[q] == OOB || k == OOB) ? OOB : p_off[q] + k);
+    for (int q = 0; q < 2 * NJM; ++q) {
+      const bool ok = p_off[q] != OOB && kp != OOB && (NAT || c + b_pc < cend);
+      gp[buf][q] = buf_load16(rP, ok ? p_off[q] + kp : OOB);
+    }
   };
   const int i = lane & 15, g = lane >> 4;
+  const int tr_off = (8 * g + (i >> 2)) * PP + 4 * (i & 3);     // NAT: transposed reads of the [k][j] slab
   // DEPTH slabs in flight while one is multiplied
 #pragma unroll
   for (int d = 0; d < DEPTH; ++d) {
@@ -152,7 +182,7 @@ __global__ __launch_bounds__(64 * NWV) void k_down(const DownParams p) {
         for (int q = 0; q < 4; ++q) *(u32x4*)(sX + (b_row + 8 * q) * GP + b_pc) = gx[buf][q];
 #pragma unroll
         for (int q = 0; q < 2 * NJM; ++q)
-          if (q < 2 * NJ) *(u32x4*)(sP + (b_row + 8 * q) * GP + b_pc) = gp[buf][q];
+          if (NAT ? (q * 8 < rank) : (q < 2 * NJ)) *(u32x4*)(sP + p_lds[q]) = gp[buf][q];
         load(c + 64 * buf + 64 * DEPTH, buf);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -163,7 +193,15 @@ __global__ __launch_bounds__(64 * NWV) void k_down(const DownParams p) {
           for (int rt = 0; rt < 2; ++rt) a[rt][s] = *(const bf16x8*)(sX + (rt * 16 + i) * GP + s * 32 + 8 * g);
 #pragma unroll
           for (int jt = 0; jt < NJM; ++jt)
-            if (jt < NJ) b[jt][s] = *(const bf16x8*)(sP + (jt * 16 + i) * GP + s * 32 + 8 * g);
+            if (jt < NJ) {
+              if (NAT) {
+                const bf16x4 lo = lds_read_tr(sP + s * 32 * PP + tr_off + jt * 16);
+                const bf16x4 hi = lds_read_tr(sP + s * 32 * PP + tr_off + 4 * PP + jt * 16);
+                b[jt][s] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+              } else {
+                b[jt][s] = *(const bf16x8*)(sP + (jt * 16 + i) * GP + s * 32 + 8 * g);
+              }
+            }
         }
 #pragma unroll
         for (int s = 0; s < 2; ++s)
@@ -194,25 +232,253 @@ __global__ __launch_bounds__(64 * NWV) void k_down(const DownParams p) {
 #pragma unroll
       for (int w = 0; w < NWV; ++w) s += ((const float*)lds[w])[j * (ROWS + 4) + orow];
     }
-    const bool ok = row_is_valid(p.dtab, row0 + orow) && j < rank;
+    const bool ok = ((vbits >> orow) & 1u) && j < rank;
     const size_t o = (size_t)(row0 + orow) * p.RP + j;
     float v = ok ? tk.scale * s : 0.f;
     if (p.mode == DOWN_TUNE) {
       p.U2[o] = f32_to_bf16(ok ? s : 0.f);
       v = ok ? tk.scale * gelu_f(s) : 0.f;
-    } else if (tuning && ok) {
-      v *= gelu_slope_f(bf16_to_f32(p.U2[o]));
     }
     p.Out[o] = f32_to_bf16(v);
   }
 }
 
-void launch_down(const CallCtx& c, const char* name, const DownParams& p) {
+template <bool NAT>
+void launch_down_t(const CallCtx& c, const char* name, const DownParams& p) {
   const unsigned items = (unsigned)c.st->items[TS64].size();
   // eight waves split the contraction (four for ranks above 32, whose LDS regions are larger); two slabs in flight
-  if (c.st->r_max <= 16) MUX_LAUNCH(name, (k_down<1, 8, 2>), dim3(items * 2), dim3(512), 0, c.stream, p);
-  else if (c.st->r_max <= 32) MUX_LAUNCH(name, (k_down<2, 8, 2>), dim3(items * 2), dim3(512), 0, c.stream, p);
-  else MUX_LAUNCH(name, (k_down<4, 4, 2>), dim3(items * 2), dim3(256), 0, c.stream, p);
+  if (c.st->r_max <= 16) MUX_LAUNCH(name, (k_down<1, 8, 2, NAT>), dim3(items * 2), dim3(512), 0, c.stream, p);
+  else if (c.st->r_max <= 32) MUX_LAUNCH(name, (k_down<2, 8, 2, NAT>), dim3(items * 2), dim3(512), 0, c.stream, p);
+  else MUX_LAUNCH(name, (k_down<4, 4, 2, NAT>), dim3(items * 2), dim3(256), 0, c.stream, p);
+}
+void launch_down(const CallCtx& c, const char* name, DownParams p, bool natural) {
+  p.items_off = c.st->dev_image[DH_NITEMS0 + 3 * TS64 + 1];
+  p.bits_off = c.st->dev_image[DH_OFF_ITEM_BITS];
+  p.tasks = *c.tref;
+  if (natural) launch_down_t<true>(c, name, p);
+  else launch_down_t<false>(c, name, p);
+}
+
+// ------------------------------------------------------------------------------------------------
+// The pass over dY of the backward (LoRA: Gs = s_t dY B_t^T and dB_t = Hs^T dY; Adapter-Tuning: the same two products
+// with U_t in the place of B_t).  grid = (row groups of the chosen size, ceil(N / 512)); each of the eight waves owns
+// 64 columns and walks the group's rows 32 at a time: the 32x64 slab of dY and the 32xRP slab of Hs go through a
+// wave-private LDS region; dY is read from it twice, row-major as the A operand of the slab's share of dY B_t^T
+// (B_t's [r][64] piece stays in registers for the whole group), and with the rows contiguous, through
+// ds_read_b64_tr_b16, as the B operand of Hs^T dY, whose sums stay in the accumulators until the group ends.
+// The shares of dY B_t^T of the eight waves are added up through LDS (two barriers a step) and go out as one fp32
+// partial per (column slab, row); k_gs_reduce adds the slabs.
+struct S4Params {
+  const int32_t* dtab;
+  const bf16_t* dY;     // [T, N]
+  const bf16_t* Hs;     // [T, RP]
+  float* gpart;         // [n_slabs][T][RP]: dY B_t^T over the columns of one slab, unscaled
+  float* bpart;         // [n_items][RP][N]: Hs^T dY over the rows of one group
+  int N, RP, ts, T;
+  TaskRef tasks;
+};
+
+template <int NJM>
+__global__ __launch_bounds__(512) void k_s4(const S4Params p) {
+  constexpr int NWV = 8, NTHR = 512, RPITCH = 36;               // RPITCH: floats between two columns of a staged share
+  static_assert(NJM * 16 * RPITCH * 4 <= 2 * 32 * GP * 2, "a wave's share of dY B_t^T fits its own LDS region");
+  __shared__ __attribute__((aligned(16))) bf16_t lds[NWV][2][32 * GP];
+  const ItemView it = load_item(p.dtab, p.ts, blockIdx.x);
+  if (it.task < 0 || it.nvalid == 0) return;
+  const DevTask tk = get_task(p.tasks, it.task);
+  if (tk.kind != MUX_ADAPTER_LORA && tk.kind != MUX_ADAPTER_TUNING) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int cw0 = blockIdx.y * (64 * NWV) + wave * 64;           // may lie beyond N: such a wave adds zeros
+  const int rank = tk.rank, NJ = (rank + 15) >> 4;
+  bf16_t* sBig = lds[wave][0];
+  bf16_t* sSm = lds[wave][1];
+
+  const rsrc_t rB = make_rsrc(p.dY + (size_t)it.row0 * p.N, (uint32_t)it.nrows * (uint32_t)p.N * 2u);
+  const rsrc_t rS = make_rsrc(p.Hs + (size_t)it.row0 * p.RP, (uint32_t)it.nrows * (uint32_t)p.RP * 2u);
+  const rsrc_t rP = make_rsrc(tk.B, (uint32_t)rank * (uint32_t)p.N * 2u);
+  const int b_row = lane >> 3, b_pc = (lane & 7) * 8;
+  const bool b_col_ok = cw0 + b_pc < p.N;
+  const int ppr = p.RP >> 3;
+  const int n_small = (32 * ppr + 63) >> 6;    // loads per lane (1..4)
+  const int l16 = lane & 15, g = lane >> 4;
+
+  // B_t[j][columns of this wave], as the B operand of dY B_t^T: lane (j = l16, g) holds 8 consecutive columns
+  bf16x8 bt[NJM][2];
+#pragma unroll
+  for (int jt = 0; jt < NJM; ++jt)
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const int j = jt * 16 + l16, col = cw0 + s * 32 + 8 * g;
+      bt[jt][s] = as_bf16x8(buf_load16(rP, (j < rank && col < p.N) ? (uint32_t)(((size_t)j * p.N + col) * 2) : OOB));
+    }
+
+  u32x4 gb[4], gs[4];
+  auto load_step = [&](int s) {
+    const int base = s * 32;
+    const uint32_t vbits = it.row0 + base < p.T ? row_valid_bits32(p.dtab, it.row0 + base) : 0u;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int m = base + b_row + 8 * q;
+      const bool ok = b_col_ok && m < it.nrows && ((vbits >> (b_row + 8 * q)) & 1u);
+      gb[q] = buf_load16(rB, ok ? (uint32_t)(((size_t)m * p.N + cw0 + b_pc) * 2) : OOB);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (q < n_small) {
+        const int idx = lane + 64 * q, m = base + idx / ppr, pc = (idx % ppr) * 8;
+        const bool ok = idx < 32 * ppr && m < it.nrows;
+        gs[q] = buf_load16(rS, ok ? (uint32_t)((m * p.RP + pc) * 2) : OOB);
+      }
+    }
+  };
+  auto store_step = [&]() {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) *(u32x4*)(sBig + (b_row + 8 * q) * GP + b_pc) = gb[q];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (q < n_small) {
+        const int idx = lane + 64 * q;
+        if (idx < 32 * ppr) *(u32x4*)(sSm + (idx / ppr) * GP + (idx % ppr) * 8) = gs[q];
+      }
+    }
+  };
+
+  f32x4 accb[NJM][4];
+#pragma unroll
+  for (int jt = 0; jt < NJM; ++jt)
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) accb[jt][ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  const int tr_off = (8 * g + (l16 >> 2)) * GP + 4 * (l16 & 3);
+  const int steps = (it.nrows + 31) >> 5;
+  const int slab = blockIdx.y;
+  float* red = (float*)lds[wave];
+  load_step(0);
+  for (int s = 0; s < steps; ++s) {
+    store_step();
+    if (s + 1 < steps) load_step(s + 1);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    f32x4 accg[2][NJM];
+    {
+      bf16x8 a[NJM], b[4], ay[2][2];
+#pragma unroll
+      for (int jt = 0; jt < NJM; ++jt)
+        if (jt < NJ) {
+          const bf16x4 lo = lds_read_tr(sSm + tr_off + jt * 16), hi = lds_read_tr(sSm + tr_off + 4 * GP + jt * 16);
+          a[jt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        const bf16x4 lo = lds_read_tr(sBig + tr_off + ct * 16), hi = lds_read_tr(sBig + tr_off + 4 * GP + ct * 16);
+        b[ct] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) ay[rt][ks] = *(const bf16x8*)(sBig + (rt * 16 + l16) * GP + ks * 32 + 8 * g);
+#pragma unroll
+      for (int jt = 0; jt < NJM; ++jt)
+        if (jt < NJ)
+#pragma unroll
+          for (int ct = 0; ct < 4; ++ct) accb[jt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[jt], b[ct], accb[jt][ct], 0, 0, 0);
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int jt = 0; jt < NJM; ++jt) {
+          accg[rt][jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+          if (jt < NJ)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) accg[rt][jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ay[rt][ks], bt[jt][ks], accg[rt][jt], 0, 0, 0);
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    // accg[rt][jt][v] = share of (dY B_t^T)[row base + rt*16 + 4g + v][jt*16 + l16]: staged over the slabs just read
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+      for (int jt = 0; jt < NJM; ++jt)
+        if (jt < NJ) *(f32x4*)&red[(jt * 16 + l16) * RPITCH + rt * 16 + 4 * g] = accg[rt][jt];
+    __syncthreads();
+    {
+      const int base = s * 32;
+      for (int e = tid; e < 32 * p.RP; e += NTHR) {
+        const int m = e / p.RP, j = e % p.RP;
+        if (base + m >= it.nrows) continue;
+        float v = 0.f;
+        if (j < NJ * 16) {
+#pragma unroll
+          for (int w = 0; w < NWV; ++w) v += ((const float*)lds[w])[j * RPITCH + m];
+        }
+        p.gpart[((size_t)slab * p.T + it.row0 + base + m) * p.RP + j] = v;
+      }
+    }
+    __syncthreads();
+  }
+  if (cw0 >= p.N) return;
+  // accb[jt][ct][v] = bpart[j = jt*16 + 4g + v][c = cw0 + ct*16 + l16]
+  float* dst = p.bpart + (size_t)blockIdx.x * ((size_t)p.RP * p.N);
+#pragma unroll
+  for (int jt = 0; jt < NJM; ++jt)
+    if (jt < NJ)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int j = jt * 16 + 4 * g + v;
+        if (j < rank)
+#pragma unroll
+          for (int ct = 0; ct < 4; ++ct) {
+            const int c = cw0 + ct * 16 + l16;
+            if (c < p.N) dst[(size_t)j * p.N + c] = accb[jt][ct][v];
+          }
+      }
+}
+
+// Gs[T,RP] = s_t * (sum over the column slabs of the shares k_s4 left, ascending), times gelu'(u) for the TUNING rows;
+// zero on padding rows, beyond the rank and on the rows of the other kinds.  One workgroup per 64-row item.
+__global__ __launch_bounds__(256) void k_gs_reduce(const int32_t* __restrict__ dtab, const TaskRef tasks,
+                                                  const float* __restrict__ gpart, int n_slabs, int T, int RP,
+                                                  const bf16_t* __restrict__ U2, bf16_t* __restrict__ Gs, int items_off,
+                                                  int bits_off) {
+  const int item = blockIdx.x;
+  const int4 iw = *(const int4*)(dtab + items_off + item * DI_WORDS);
+  const uint32_t* bw = (const uint32_t*)(dtab + bits_off) + 2 * item;
+  const uint32_t bits0 = bw[0], bits1 = bw[1];
+  const int task = iw.x, row0 = iw.y, nrows = iw.z;
+  const int kind = task >= 0 ? get_task_kind(tasks, task) : MUX_ADAPTER_NONE;
+  const bool mine = (kind == MUX_ADAPTER_LORA || kind == MUX_ADAPTER_TUNING) && (bits0 | bits1) != 0u;
+  float scale = 0.f;
+  int rank = 0;
+  if (mine) { const DevTask tk = get_task(tasks, task); scale = tk.scale; rank = tk.rank; }
+  const int q4 = RP >> 2;                        // groups of four columns a row
+  for (int e = threadIdx.x; e < nrows * q4; e += 256) {
+    const int m = e / q4, j = (e % q4) * 4;
+    const size_t o = (size_t)(row0 + m) * RP + j;
+    const bool valid = mine && (((m < 32 ? bits0 >> m : bits1 >> (m - 32)) & 1u) != 0u) && j < rank;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (valid) {
+      for (int q = 0; q < n_slabs; q += 4) {     // four slabs in flight; the sum runs in ascending slab order
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          v[u] = q + u < n_slabs ? *(const float4*)(gpart + ((size_t)(q + u) * T + row0 + m) * RP + j) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+      }
+      s.x *= scale; s.y *= scale; s.z *= scale; s.w *= scale;
+      if (kind == MUX_ADAPTER_TUNING) {
+        s.x *= gelu_slope_f(bf16_to_f32(U2[o])); s.y *= gelu_slope_f(bf16_to_f32(U2[o + 1]));
+        s.z *= gelu_slope_f(bf16_to_f32(U2[o + 2])); s.w *= gelu_slope_f(bf16_to_f32(U2[o + 3]));
+      }
+      if (j + 1 >= rank) s.y = 0.f;
+      if (j + 2 >= rank) s.z = 0.f;
+      if (j + 3 >= rank) s.w = 0.f;
+    }
+    uint2 out;
+    out.x = pack_bf16x2(s.x, s.y);
+    out.y = pack_bf16x2(s.z, s.w);
+    *(uint2*)(Gs + o) = out;
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -220,9 +486,8 @@ void launch_down(const CallCtx& c, const char* name, const DownParams& p) {
 // 64 columns and walks the item's rows 32 at a time: the 32x64 slab of Big and the 32xRP slab of Small
 // go through a wave-private LDS region in their natural layout and come back k-major per lane through
 // ds_read_b64_tr_b16.  No workgroup barrier: the four waves are independent streams.
-struct GradParams {     // blockIdx.z picks the problem: 0 = dB (Small = Hs, Big = dY), 1 = dA (Small = Gs, Big = X)
+struct GradParams {     // z0 + blockIdx.z picks the problem: 0 = dB (Small = Hs, Big = dY), 1 = dA (Small = Gs, Big = X)
   const int32_t* dtab;   // TUNING items: 0 = dU_t (the same sum), 1 = dD_t (Small = Gs, Big = the saved z rows, C = N)
-  const DevTask* tasks;
   const bf16_t* Small[2];  // [T, RP]
   const bf16_t* Big[2];    // [T, C]
   float* part[2];          // [n_items][slot], a slot holds [RP][C] of the item's kind
@@ -230,6 +495,8 @@ struct GradParams {     // blockIdx.z picks the problem: 0 = dB (Small = Hs, Big
   int RP, ts;
   const bf16_t* Zc;        // saved x W, [z_rows, N]
   size_t slot[2];          // elements per item in part[z]
+  int z0;                  // 1: the launch computes the second problem only (the pass over dY has done the first)
+  TaskRef tasks;
 };
 
 template <int NJM>
@@ -237,10 +504,10 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
   __shared__ __attribute__((aligned(16))) bf16_t lds[4][2][32 * GP];
   const ItemView it = load_item(p.dtab, p.ts, blockIdx.x);
   if (it.task < 0 || it.nvalid == 0) return;
-  const DevTask tk = p.tasks[it.task];
+  const DevTask tk = get_task(p.tasks, it.task);
   if (tk.kind != MUX_ADAPTER_LORA && tk.kind != MUX_ADAPTER_TUNING) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int z = blockIdx.z;
+  const int z = blockIdx.z + p.z0;
   const bool from_z = z == 1 && tk.kind == MUX_ADAPTER_TUNING;
   const int C = from_z ? p.C[0] : p.C[z];
   const int cw0 = blockIdx.y * 256 + wave * 64;
@@ -352,12 +619,12 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
 // products are staged 16 rows at a time in fp32 so that In is read and Out is written in whole 128-byte lines.
 struct TuneAddParams {
   const int32_t* dtab;
-  const DevTask* tasks;
   const bf16_t* In;
   const bf16_t* Small;   // [T, RP]
   bf16_t* Out;
   const bf16_t* AT;      // backward: base of the transposed region (D_t^T); forward: null (U_t = tk.B)
   int N, RP, backward;
+  TaskRef tasks;
 };
 
 template <int NKS>      // k-steps of 32 over the rank pitch (1 or 2)
@@ -366,8 +633,8 @@ __global__ __launch_bounds__(256) void k_tune_add(const TuneAddParams p) {
   __shared__ __attribute__((aligned(16))) bf16_t sP[4][NKS * 32 * GP];
   __shared__ __attribute__((aligned(16))) float sC[4][16 * SP];
   const ItemView it = load_item(p.dtab, TS64, blockIdx.x);
-  if (it.task < 0 || p.tasks[it.task].kind != MUX_ADAPTER_TUNING) return;
-  const DevTask tk = p.tasks[it.task];
+  if (it.task < 0 || get_task_kind(p.tasks, it.task) != MUX_ADAPTER_TUNING) return;
+  const DevTask tk = get_task(p.tasks, it.task);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int cw0 = blockIdx.y * 256 + wave * 64;
   if (cw0 >= p.N) return;
@@ -465,12 +732,12 @@ __global__ __launch_bounds__(256) void k_tune_add(const TuneAddParams p) {
 // ------------------------------------------------------------------------------------------------
 // IA3_OUT: part[item][n] = sum_{rows} g[i][n] * z[i][n], and dYs[i][n] = g[i][n] * l_t[n] (the operand of the
 // backbone backward for these rows).  grid = (64-row items, ceil(N/1024)); 8 columns per thread, 8 rows in flight.
-__global__ __launch_bounds__(128) void k_dl(const int32_t* __restrict__ dtab, const DevTask* __restrict__ tasks,
+__global__ __launch_bounds__(128) void k_dl(const int32_t* __restrict__ dtab, const TaskRef tasks,
                                            const bf16_t* __restrict__ dY, const bf16_t* __restrict__ Z, float* __restrict__ part,
                                            bf16_t* __restrict__ dYs, int N) {
   const ItemView it = load_item(dtab, TS64, blockIdx.x);
   if (it.task < 0 || it.nvalid == 0) return;
-  const DevTask tk = tasks[it.task];
+  const DevTask tk = get_task(tasks, it.task);
   if (tk.kind != MUX_ADAPTER_IA3_OUT) return;
   const int n0 = (blockIdx.y * 128 + threadIdx.x) * 8;
   if (n0 >= N) return;
@@ -530,11 +797,11 @@ __global__ __launch_bounds__(128) void k_dl(const int32_t* __restrict__ dtab, co
 // out_t = (accumulate ? out_t : 0) + sum over the task's items, ascending.  grid = (tasks, blocks over the elements).
 // mode 0: LoRA, elements [0, r*N) are dB_t [r][N] from part0, elements [r*N, r*(N+K)) are dA_t from part1, stored
 // transposed as [K][r].  mode 1: IA3_OUT, dl_t [N] from part0 (one row per item).
-__global__ __launch_bounds__(256) void k_reduce(const int32_t* __restrict__ dtab, const DevTask* __restrict__ tasks,
+__global__ __launch_bounds__(256) void k_reduce(const int32_t* __restrict__ dtab, const TaskRef tasks,
                                                const float* __restrict__ part0, const float* __restrict__ part1, int N, int K,
-                                               int RP, int ts, int mode, int accumulate, size_t slot0, size_t slot1) {
+                                               int RP, int ts0, int ts1, int mode, int accumulate, size_t slot0, size_t slot1) {
   const int t = blockIdx.x;
-  const DevTask tk = tasks[t];
+  const DevTask tk = get_task(tasks, t);
   const bool ranked = tk.kind == MUX_ADAPTER_LORA || tk.kind == MUX_ADAPTER_TUNING;
   if (mode == 1 ? tk.kind != MUX_ADAPTER_IA3_OUT : !ranked) return;
   if (tk.kind == MUX_ADAPTER_TUNING) K = N;    // its first gradient is dD_t [N][r]
@@ -545,9 +812,10 @@ __global__ __launch_bounds__(256) void k_reduce(const int32_t* __restrict__ dtab
   float* out = mode == 1 ? tk.dL : tk.dB;
   bool transposed = false;
   size_t slot = slot0;
+  int ts = ts0;                                // row-group size of the partials: the two passes choose their own
   if (mode == 0 && e >= (size_t)rows * N) {
     e -= (size_t)rows * N;
-    part = part1; C = K; out = tk.dA; transposed = true; slot = slot1;
+    part = part1; C = K; out = tk.dA; transposed = true; slot = slot1; ts = ts1;
   }
   if (!out || e >= (size_t)rows * C) return;
   const int j = (int)(e / C), c = (int)(e % C);
@@ -593,82 +861,124 @@ void launch_grad(const CallCtx& c, const char* name, const GradParams& p, dim3 g
   else MUX_LAUNCH(name, (k_grad<4>), grid, dim3(256), 0, c.stream, p);
 }
 
-int choose_group(const mux_segtab* st, int K, int N) {
-  // bigger row groups mean fewer partial bytes; keep at least ~1024 workgroups in flight
-  const size_t wg1024 = st->items[TS1024].size() * (size_t)((K + 255) / 256 + (N + 255) / 256);
-  return wg1024 >= 1024 ? TS1024 : TS256;
+// Row groups of 1024 mean 1/4 of the partial bytes of groups of 256; they are taken when the launch still has
+// `enough` workgroups to occupy the chip.
+int choose_group(const mux_segtab* st, int col_blocks, int enough) {
+  return st->items[TS1024].size() * (size_t)col_blocks >= (size_t)enough ? TS1024 : TS256;
+}
+constexpr int kS4Cols = 512;                          // columns of one workgroup of the dY pass
+int s4_slabs(int N) { return (N + kS4Cols - 1) / kS4Cols; }
+int s4_group(const mux_segtab* st, int N) { return choose_group(st, s4_slabs(N), 192); }
+int da_group(const mux_segtab* st, int C) { return choose_group(st, (C + 255) / 256, 384); }
+
+struct PartLayout { size_t gpart, part0, part1, ia3, total; };
+PartLayout part_layout(int K, int N, const mux_segtab* st) {
+  PartLayout o{};
+  const int RP = rank_pitch(st);
+  const int K1 = (st->n_tuning > 0 && N > K) ? N : K;       // a TUNING item's second partial is [RP][N]
+  if (RP > 0) {
+    o.gpart = align256((size_t)s4_slabs(N) * st->T * RP * 4);
+    o.part0 = align256((size_t)st->items[TS256].size() * RP * N * 4);      // sized for the smaller row groups
+    o.part1 = align256((size_t)st->items[TS256].size() * RP * K1 * 4);
+  }
+  o.ia3 = st->n_ia3 > 0 ? align256((size_t)st->items[TS64].size() * N * 4) : 0;
+  const size_t lora = o.gpart + o.part0 + o.part1;
+  o.total = lora > o.ia3 ? lora : o.ia3;
+  return o;
 }
 
 }  // namespace
 
-size_t adapter_partial_bytes(int K, int N, const mux_segtab* st) {
-  const int C = K > N ? K : N;
-  const int RP = rank_pitch(st);
-  const int K1 = (st->n_tuning > 0 && N > K) ? N : K;       // a TUNING item's second partial is [RP][N]
-  size_t lora = align256((size_t)st->items[TS256].size() * RP * N * 4) + align256((size_t)st->items[TS256].size() * RP * K1 * 4);
-  (void)C;
-  size_t ia3 = st->n_ia3 > 0 ? (size_t)st->items[TS64].size() * N * 4 : 0;
-  return align256(lora > ia3 ? lora : ia3);
-}
+size_t adapter_partial_bytes(int K, int N, const mux_segtab* st) { return part_layout(K, N, st).total; }
 
 mux_status adapter_down_x(const CallCtx& c, const void* X, void* Hs) {
   if (c.st->n_lora == 0) return MUX_OK;
-  // A_t^T was written into c.AT by the task-table kernel of this call
-  DownParams p{c.dtab, c.dtasks, (const bf16_t*)X, (bf16_t*)Hs, (const bf16_t*)c.AT, nullptr, c.K, c.RP, DOWN_X};
-  launch_down(c, "down_x", p);
+  // A_t is read as it is when every LoRA rank allows it; else A_t^T was laid into c.AT by the packing kernel of this call
+  DownParams p{c.dtab, (const bf16_t*)X, (bf16_t*)Hs, c.lora_natural ? nullptr : (const bf16_t*)c.AT, nullptr, c.K, c.RP, DOWN_X};
+  launch_down(c, "down_x", p, c.lora_natural);
   return MUX_OK;
 }
 
-mux_status adapter_down_g(const CallCtx& c, const void* dY, void* Gs) {
+// The pass over dY: Gs (LoRA: s_t dY B_t^T; Adapter-Tuning: s_t (dY U_t^T) * gelu'(u)) and the partial sums of
+// dB_t = Hs^T dY (dU_t), which adapter_grads brings together.
+mux_status adapter_dy_pass(const CallCtx& c, const void* dY, const void* Hs, void* Gs, void* part) {
   if (c.st->n_lora + c.st->n_tuning == 0) return MUX_OK;
-  DownParams p{c.dtab, c.dtasks, (const bf16_t*)dY, (bf16_t*)Gs, nullptr, (bf16_t*)c.U2, c.N, c.RP, DOWN_G};
-  launch_down(c, "down_g", p);
+  const PartLayout pl = part_layout(c.K, c.N, c.st);
+  float* gpart = (float*)part;
+  float* part0 = (float*)((char*)part + pl.gpart);
+  const int ts = s4_group(c.st, c.N), slabs = s4_slabs(c.N);
+  S4Params p{c.dtab, (const bf16_t*)dY, (const bf16_t*)Hs, gpart, part0, c.N, c.RP, ts, c.st->T};
+  p.tasks = *c.tref;
+  const dim3 grid((unsigned)c.st->items[ts].size(), (unsigned)slabs);
+  if (c.st->r_max <= 16) MUX_LAUNCH("s4_dy_pass", (k_s4<1>), grid, dim3(512), 0, c.stream, p);
+  else if (c.st->r_max <= 32) MUX_LAUNCH("s4_dy_pass", (k_s4<2>), grid, dim3(512), 0, c.stream, p);
+  else MUX_LAUNCH("s4_dy_pass", (k_s4<4>), grid, dim3(512), 0, c.stream, p);
+  // moved: the partials of every slab once in, Gs once out
+  prof_note_bytes((double)slabs * c.st->T * c.RP * 4 + (double)c.st->T * c.RP * 2);
+  MUX_LAUNCH("gs_reduce", k_gs_reduce, dim3((unsigned)c.st->items[TS64].size()), dim3(256), 0, c.stream, c.dtab, *c.tref,
+             (const float*)gpart, slabs, c.st->T, c.RP, (const bf16_t*)c.U2, (bf16_t*)Gs,
+             c.st->dev_image[DH_NITEMS0 + 3 * TS64 + 1], c.st->dev_image[DH_OFF_ITEM_BITS]);
   return MUX_OK;
 }
 
 // Adapter-Tuning: Y = z + Hs U_t (forward) or dYs = dY + Gs D_t^T (backward, D_t^T from the transposed region)
 mux_status adapter_tune_add(const CallCtx& c, const void* In, const void* Small, void* Out, int backward) {
   if (c.st->n_tuning == 0) return MUX_OK;
-  TuneAddParams p{c.dtab, c.dtasks, (const bf16_t*)In, (const bf16_t*)Small, (bf16_t*)Out, (const bf16_t*)c.AT, c.N, c.RP, backward};
+  TuneAddParams p{c.dtab, (const bf16_t*)In, (const bf16_t*)Small, (bf16_t*)Out, (const bf16_t*)c.AT, c.N, c.RP, backward};
+  p.tasks = *c.tref;
   const dim3 grid((unsigned)c.st->items[TS64].size(), (c.N + 255) / 256);
   if (c.RP <= 32) MUX_LAUNCH(backward ? "tune_dz" : "tune_up", (k_tune_add<1>), grid, dim3(256), 0, c.stream, p);
   else MUX_LAUNCH(backward ? "tune_dz" : "tune_up", (k_tune_add<2>), grid, dim3(256), 0, c.stream, p);
   return MUX_OK;
 }
 
-// Adapter-Tuning forward, after the backbone GEMM saved z = x W: u = z D_t, Hs = s_t gelu(u).  D_t^T was written into
-// c.AT by the task-table kernel of this call.
+// Adapter-Tuning forward, after the backbone GEMM saved z = x W: u = z D_t, Hs = s_t gelu(u).  D_t^T was laid into
+// c.AT by the packing kernel of this call.
 mux_status adapter_down_tune(const CallCtx& c, const void* Z, void* Hs) {
   if (c.st->n_tuning == 0) return MUX_OK;
-  DownParams p{c.dtab, c.dtasks, (const bf16_t*)Z, (bf16_t*)Hs, (const bf16_t*)c.AT, (bf16_t*)c.U2, c.N, c.RP, DOWN_TUNE};
-  launch_down(c, "tune_down", p);
+  DownParams p{c.dtab, (const bf16_t*)Z, (bf16_t*)Hs, (const bf16_t*)c.AT, (bf16_t*)c.U2, c.N, c.RP, DOWN_TUNE};
+  launch_down(c, "tune_down", p, false);
   return MUX_OK;
 }
 
+// After adapter_dy_pass: dA_t = X^T Gs (Adapter-Tuning: dD_t = z^T Gs) in partial sums per row group, then both
+// gradients of every task brought together; IA3_OUT: dl_t and the scaled rows the backbone backward reads.
 mux_status adapter_grads(const CallCtx& c, const void* X, const void* dY, const void* Hs, const void* Gs, const void* Z,
                          void* part, int accumulate) {
   const int M = c.st->n_tasks;
+  const PartLayout pl = part_layout(c.K, c.N, c.st);
   if (c.st->n_lora + c.st->n_tuning > 0) {
-    // dB_t = Hs^T dY and dA_t = X^T Gs (Adapter-Tuning: dU_t = Hs^T dY and dD_t = z^T Gs): one launch for the partials
-    // of both, one for the two reductions
-    const int ts = choose_group(c.st, c.K, c.N);
-    const size_t n_items = c.st->items[ts].size();
     const int K1 = (c.st->n_tuning > 0 && c.N > c.K) ? c.N : c.K;
-    float* part0 = (float*)part;
-    float* part1 = (float*)((char*)part + align256(c.st->items[TS256].size() * (size_t)c.RP * c.N * 4));
-    GradParams p{c.dtab, c.dtasks, {(const bf16_t*)Hs, (const bf16_t*)Gs}, {(const bf16_t*)dY, (const bf16_t*)X}, {part0, part1},
-                 {c.N, c.K}, c.RP, ts, (const bf16_t*)Z, {(size_t)c.RP * c.N, (size_t)c.RP * K1}};
-    const int cmax = c.N > c.K ? c.N : c.K;
-    launch_grad(c, "grad_dbda", p, dim3((unsigned)n_items, (cmax + 255) / 256, 2));
+    const int ts_b = s4_group(c.st, c.N), ts_a = da_group(c.st, K1);
+    float* part0 = (float*)((char*)part + pl.gpart);
+    float* part1 = (float*)((char*)part + pl.gpart + pl.part0);
+    GradParams p{c.dtab, {(const bf16_t*)Hs, (const bf16_t*)Gs}, {(const bf16_t*)dY, (const bf16_t*)X}, {part0, part1},
+                 {c.N, c.K}, c.RP, ts_a, (const bf16_t*)Z, {(size_t)c.RP * c.N, (size_t)c.RP * K1}, 1};
+    p.tasks = *c.tref;
+    launch_grad(c, "grad_da", p, dim3((unsigned)c.st->items[ts_a].size(), (K1 + 255) / 256, 1));
     const size_t elems = (size_t)c.st->r_max * ((size_t)c.N + K1);
-    MUX_LAUNCH("reduce_dbda", k_reduce, dim3(M, (unsigned)((elems + 1023) / 1024)), dim3(256), 0, c.stream, c.dtab, c.dtasks,
-               (const float*)part0, (const float*)part1, c.N, c.K, c.RP, ts, 0, accumulate, p.slot[0], p.slot[1]);
+    // moved: every row group's partials once in (rows of the ranked tasks only), both gradients once out
+    double moved = 0.0;
+    for (const HostTask& ht : c.st->tasks)
+      if (ht.kind == MUX_ADAPTER_LORA || ht.kind == MUX_ADAPTER_TUNING) {
+        const double kk = ht.kind == MUX_ADAPTER_TUNING ? c.N : c.K;
+        const double gb = (ht.row_count + kTileRows[ts_b] - 1) / kTileRows[ts_b], ga = (ht.row_count + kTileRows[ts_a] - 1) / kTileRows[ts_a];
+        moved += 4.0 * ht.rank * (gb * c.N + ga * kk) + 4.0 * ht.rank * (c.N + kk) * (accumulate ? 2 : 1);
+      }
+    prof_note_bytes(moved);
+    MUX_LAUNCH("reduce_dbda", k_reduce, dim3(M, (unsigned)((elems + 1023) / 1024)), dim3(256), 0, c.stream, c.dtab, *c.tref,
+               (const float*)part0, (const float*)part1, c.N, c.K, c.RP, ts_b, ts_a, 0, accumulate, p.slot[0], p.slot[1]);
   }
   if (c.st->n_ia3 > 0) {
+    // the IA3_OUT partials share the region with the (finished) LoRA ones only in time: the launches are in stream order
     MUX_LAUNCH("grad_dl", k_dl, dim3((unsigned)c.st->items[TS64].size(), (c.N + 1023) / 1024), dim3(128), 0, c.stream,
-               c.dtab, c.dtasks, (const bf16_t*)dY, (const bf16_t*)Z, (float*)part, (bf16_t*)c.dYs, c.N);
-    MUX_LAUNCH("reduce_dl", k_reduce, dim3(M, (c.N + 1023) / 1024), dim3(256), 0, c.stream, c.dtab, c.dtasks,
-               (const float*)part, (const float*)nullptr, c.N, c.K, 1, TS64, 1, accumulate, (size_t)c.N, (size_t)0);
+               c.dtab, *c.tref, (const bf16_t*)dY, (const bf16_t*)Z, (float*)part, (bf16_t*)c.dYs, c.N);
+    double moved = 0.0;
+    for (const HostTask& ht : c.st->tasks)
+      if (ht.kind == MUX_ADAPTER_IA3_OUT) moved += 4.0 * c.N * ((ht.row_count + 63) / 64) + 4.0 * c.N * (accumulate ? 2 : 1);
+    prof_note_bytes(moved);
+    MUX_LAUNCH("reduce_dl", k_reduce, dim3(M, (c.N + 1023) / 1024), dim3(256), 0, c.stream, c.dtab, *c.tref,
+               (const float*)part, (const float*)nullptr, c.N, c.K, 1, TS64, TS64, 1, accumulate, (size_t)c.N, (size_t)0);
   }
   return MUX_OK;
 }

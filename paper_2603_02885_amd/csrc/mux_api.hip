@@ -2,63 +2,41 @@
 #include <cstring>
 #include <mutex>
 #include <string>
+#include <vector>
 
 #include "mux_device_utils.h"
 
 namespace mux {
 
-// Launch-argument block for k_fill_tasks: adapter pointers of up to 16 tasks.
-struct TaskPtrArgs {
-  const void* A[16];
-  const void* B[16];
-  const void* L[16];
-  float* dA[16];
-  float* dB[16];
-  float* dL[16];
-  int64_t at_off[16];
-};
+// Writes `count` entries of the per-call task table, handed over in the launch arguments, into the workspace.
+__global__ __launch_bounds__(64) void k_write_tasks(DevTask* __restrict__ out, const TaskTable tb, int base, int count) {
+  const int i = threadIdx.x;
+  if (i < count) out[base + i] = tb.t[i];
+}
 
-// Block 0 writes the per-call task table.  With pack_at, blocks 1.. also write A_t^T [round_up(r,16)][K] (zero rows
-// beyond r) for the forward's down-projection: block b handles 64 k-values of task base + (b-1)/ceil(K/64), reading
-// the pointers from the launch arguments (not from the table block 0 is writing).
-__global__ __launch_bounds__(256) void k_fill_tasks(const int32_t* __restrict__ dtab, DevTask* __restrict__ out, TaskPtrArgs p,
-                                                     int base, int count, uint16_t* __restrict__ pack_at, int Kin, int Nout,
-                                                     int only_tuning) {
-  if (blockIdx.x == 0) {
-    const int i = threadIdx.x;
-    if (i >= count) return;
-    const int32_t* te = dtab + dtab[DH_OFF_TASKS] + (base + i) * DT_WORDS;
-    DevTask d;
-    d.A = p.A[i]; d.B = p.B[i]; d.L = p.L[i];
-    d.dA = p.dA[i]; d.dB = p.dB[i]; d.dL = p.dL[i];
-    d.scale = __int_as_float(te[DT_SCALE_BITS]);
-    d.kind = te[DT_KIND];
-    d.rank = te[DT_RANK];
-    d.row_begin = te[DT_ROW_BEGIN];
-    d.row_count = te[DT_ROW_COUNT];
-    d.zrow0 = te[DT_ZROW0];
-    d.at_off = p.at_off[i];
-    out[base + i] = d;
-    return;
-  }
+// A_t^T [round_up(r,16)][K] (zero rows beyond r) of the LoRA tasks whose rank is not a multiple of 8, and D_t^T
+// [round_up(r,16)][N] of the Adapter-Tuning tasks, into the transposed region of the workspace: the down-projection
+// reads these operands with the contraction index contiguous.  Block b handles 64 rows of task b / nkb.
+__global__ __launch_bounds__(256) void k_pack_at(const TaskRef tasks, uint16_t* __restrict__ pack_at, int Kin, int Nout,
+                                                  int only_tuning) {
   __shared__ uint16_t t[64][66];
   const int nkb = ((Kin > Nout ? Kin : Nout) + 63) / 64;
-  const int i = (blockIdx.x - 1) / nkb, k0 = ((blockIdx.x - 1) % nkb) * 64;
-  if (i >= count) return;
-  const int32_t* te = dtab + dtab[DH_OFF_TASKS] + (base + i) * DT_WORDS;
+  const int i = blockIdx.x / nkb, k0 = (blockIdx.x % nkb) * 64;
+  const DevTask tk = get_task(tasks, i);
   // LORA: A_t [K, r]; TUNING: D_t [N, r] (in the same slot); both go out as [round_up(r,16)][rows]
-  if (te[DT_KIND] != MUX_ADAPTER_LORA && te[DT_KIND] != MUX_ADAPTER_TUNING) return;
-  if (only_tuning && te[DT_KIND] != MUX_ADAPTER_TUNING) return;     // the backward pass needs D_t^T only
-  const int K = te[DT_KIND] == MUX_ADAPTER_LORA ? Kin : Nout;
+  if (tk.kind != MUX_ADAPTER_LORA && tk.kind != MUX_ADAPTER_TUNING) return;
+  if (only_tuning && tk.kind != MUX_ADAPTER_TUNING) return;     // the backward pass needs D_t^T only
+  if (tk.at_off < 0) return;                                     // a LoRA task whose A_t is read as it is
+  const int K = tk.kind == MUX_ADAPTER_LORA ? Kin : Nout;
   if (k0 >= K) return;
-  const int r = te[DT_RANK], rp = (r + 15) & ~15;
-  const uint16_t* A = (const uint16_t*)p.A[i];
+  const int r = tk.rank, rp = (r + 15) & ~15;
+  const uint16_t* A = (const uint16_t*)tk.A;
   for (int e = threadIdx.x; e < 64 * rp; e += 256) {
     const int kk = e / rp, j = e % rp;
     t[j][kk] = (j < r && k0 + kk < K) ? A[(size_t)(k0 + kk) * r + j] : (uint16_t)0;
   }
   __syncthreads();
-  uint16_t* dst = pack_at + p.at_off[i];
+  uint16_t* dst = pack_at + tk.at_off;
   for (int e = threadIdx.x; e < 64 * rp; e += 256) {
     const int j = e >> 6, kk = e & 63;
     if (k0 + kk < K) dst[(size_t)j * K + k0 + kk] = t[j][kk];
@@ -66,8 +44,8 @@ __global__ __launch_bounds__(256) void k_fill_tasks(const int32_t* __restrict__ 
 }
 
 // A table without rows: every task's gradient is zero.  grid = (tasks, blocks over the largest gradient).
-__global__ __launch_bounds__(256) void k_zero_grads(const DevTask* __restrict__ tasks, int K, int N) {
-  const DevTask tk = tasks[blockIdx.x];
+__global__ __launch_bounds__(256) void k_zero_grads(const TaskRef tasks, int K, int N) {
+  const DevTask tk = get_task(tasks, blockIdx.x);
   const size_t e = (size_t)blockIdx.y * 256 + threadIdx.x;
   if (tk.kind == MUX_ADAPTER_LORA || tk.kind == MUX_ADAPTER_TUNING) {
     if (tk.dA && e < (size_t)(tk.kind == MUX_ADAPTER_LORA ? K : N) * tk.rank) tk.dA[e] = 0.f;
@@ -151,40 +129,75 @@ mux_status check_hip(const char* fn) {
   return MUX_OK;
 }
 
-void fill_tasks(const mux_layer_desc* L, const mux_segtab* st, const int32_t* dtab, DevTask* dtasks, void* const* dA,
-                void* const* dB, void* const* dL, hipStream_t stream, void* pack_at, int only_tuning) {
+// Does the down-projection read this LoRA task's A_t [K, r] as it is (rows of 16-byte pieces), or a transposed copy?
+inline bool lora_a_natural(const HostTask& ht) { return (ht.rank & 7) == 0; }
+
+// The per-call task parameters, laid out on the host.  at_off: element offset of the task's transposed operand in the
+// workspace region, -1 for a LoRA task whose A_t is read as it is.
+void build_tasks(const mux_layer_desc* L, const mux_segtab* st, void* const* dA, void* const* dB, void* const* dL,
+                 bool fast, std::vector<DevTask>& out) {
+  out.assign((size_t)st->n_tasks, DevTask{});
   int64_t at_off = 0;
-  for (int base = 0; base < st->n_tasks; base += 16) {
-    TaskPtrArgs p;
-    std::memset(&p, 0, sizeof(p));
-    const int count = st->n_tasks - base < 16 ? st->n_tasks - base : 16;
-    for (int i = 0; i < count; ++i) {
-      const int t = base + i;
-      const int kind = st->tasks[t].kind;
-      const bool ranked = kind == MUX_ADAPTER_LORA || kind == MUX_ADAPTER_TUNING;
-      p.A[i] = ranked ? L->A[t] : nullptr;
-      p.B[i] = ranked ? L->B[t] : nullptr;
-      p.L[i] = (kind == MUX_ADAPTER_IA3_OUT) ? L->L[t] : nullptr;
-      p.dA[i] = (ranked && dA) ? (float*)dA[t] : nullptr;
-      p.dB[i] = (ranked && dB) ? (float*)dB[t] : nullptr;
-      p.dL[i] = (kind == MUX_ADAPTER_IA3_OUT && dL) ? (float*)dL[t] : nullptr;
-      p.at_off[i] = at_off;
-      if (kind == MUX_ADAPTER_DIFF) {
-        const mux_sparse_mask* m = L->masks[t];
-        p.A[i] = m->nnz > 0 ? L->A[t] : nullptr;
-        p.dA[i] = (m->nnz > 0 && dA) ? (float*)dA[t] : nullptr;
-        p.B[i] = m->row_ptr; p.L[i] = m->col_idx;
-        p.dB[i] = (float*)m->col_ptr; p.dL[i] = (float*)m->col_ent;
-        p.at_off[i] = m->nnz;
-      }
-      if (kind == MUX_ADAPTER_LORA) at_off += (int64_t)round_up(st->tasks[t].rank, 16) * L->K;
-      else if (kind == MUX_ADAPTER_TUNING) at_off += (int64_t)round_up(st->tasks[t].rank, 16) * L->N;
+  for (int t = 0; t < st->n_tasks; ++t) {
+    const HostTask& ht = st->tasks[t];
+    const int kind = ht.kind;
+    const bool ranked = kind == MUX_ADAPTER_LORA || kind == MUX_ADAPTER_TUNING;
+    DevTask& d = out[t];
+    d.A = ranked ? L->A[t] : nullptr;
+    d.B = ranked ? L->B[t] : nullptr;
+    d.L = (kind == MUX_ADAPTER_IA3_OUT) ? L->L[t] : nullptr;
+    d.dA = (ranked && dA) ? (float*)dA[t] : nullptr;
+    d.dB = (ranked && dB) ? (float*)dB[t] : nullptr;
+    d.dL = (kind == MUX_ADAPTER_IA3_OUT && dL) ? (float*)dL[t] : nullptr;
+    d.scale = ht.scale; d.kind = kind; d.rank = ht.rank;
+    d.row_begin = ht.row_begin; d.row_count = ht.row_count; d.zrow0 = ht.zrow0;
+    d.at_off = at_off;
+    if (kind == MUX_ADAPTER_DIFF) {
+      const mux_sparse_mask* m = L->masks[t];
+      d.A = m->nnz > 0 ? L->A[t] : nullptr;
+      d.dA = (m->nnz > 0 && dA) ? (float*)dA[t] : nullptr;
+      d.B = m->row_ptr; d.L = m->col_idx;
+      d.dB = (float*)m->col_ptr; d.dL = (float*)m->col_ent;
+      d.at_off = m->nnz;
     }
-    const int rows_max = L->K > L->N ? L->K : L->N;
-    const unsigned pack_blocks = pack_at ? (unsigned)count * (unsigned)((rows_max + 63) / 64) : 0u;
-    MUX_LAUNCH("fill_tasks", k_fill_tasks, dim3(1 + pack_blocks), dim3(256), 0, stream, dtab, dtasks, p, base, count,
-               (uint16_t*)pack_at, L->K, L->N, only_tuning);
+    if (kind == MUX_ADAPTER_LORA) {
+      if (fast && lora_a_natural(ht)) d.at_off = -1;
+      at_off += (int64_t)round_up(ht.rank, 16) * L->K;
+    } else if (kind == MUX_ADAPTER_TUNING) {
+      at_off += (int64_t)round_up(ht.rank, 16) * L->N;
+    }
   }
+}
+
+// Makes the tasks visible to the kernels of the call: by value in `ref` when they fit and no kernel of the call needs
+// the table in memory, else written into the workspace by a small kernel; and lays out the transposed operands when
+// a kernel of the call reads them (pack: 0 no, 1 all of them, 2 only those of the Adapter-Tuning tasks).
+void publish_tasks(const mux_layer_desc* L, const mux_segtab* st, const std::vector<DevTask>& tasks, bool need_table,
+                   DevTask* dtasks, TaskRef& ref, int pack, void* pack_at, hipStream_t stream) {
+  std::memset(&ref, 0, sizeof(ref));
+  if (!need_table && st->n_tasks <= kArgTasks) {
+    for (int t = 0; t < st->n_tasks; ++t) ref.arg.t[t] = tasks[t];
+  } else {
+    for (int base = 0; base < st->n_tasks; base += kArgTasks) {
+      TaskTable tb;
+      std::memset(&tb, 0, sizeof(tb));
+      const int count = st->n_tasks - base < kArgTasks ? st->n_tasks - base : kArgTasks;
+      for (int i = 0; i < count; ++i) tb.t[i] = tasks[base + i];
+      MUX_LAUNCH("fill_tasks", k_write_tasks, dim3(1), dim3(64), 0, stream, dtasks, tb, base, count);
+    }
+    ref.mem = dtasks;
+  }
+  if (pack && pack_at) {
+    const int rows_max = L->K > L->N ? L->K : L->N;
+    MUX_LAUNCH("pack_at", k_pack_at, dim3((unsigned)st->n_tasks * (unsigned)((rows_max + 63) / 64)), dim3(256), 0, stream,
+               ref, (uint16_t*)pack_at, L->K, L->N, pack == 2 ? 1 : 0);
+  }
+}
+
+bool any_packed_lora(const mux_segtab* st) {
+  for (const HostTask& ht : st->tasks)
+    if (ht.kind == MUX_ADAPTER_LORA && !lora_a_natural(ht)) return true;
+  return false;
 }
 
 }  // namespace
@@ -202,6 +215,28 @@ extern "C" size_t mux_lora_workspace_bytes(const mux_layer_desc* layer, const mu
   return make_layout(layer, st).ws_bytes;
 }
 
+namespace {
+
+// Everything a call's kernels share, from the layer, the table and the carved workspace.
+CallCtx make_ctx(const mux_layer_desc* layer, const mux_segtab* st, const void* dev_segtab, const Layout& lo, void* ws,
+                 const void* saved, hipStream_t stream) {
+  CallCtx c{};
+  c.st = st;
+  c.dtab = (const int32_t*)dev_segtab;
+  c.K = layer->K; c.N = layer->N; c.ldw = layer->ldw; c.RP = lo.RP;
+  c.AT = (char*)ws + lo.tasks_bytes + lo.g_bytes;
+  c.dYs = (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes;
+  c.W = layer->W;
+  c.stream = stream;
+  c.U2 = (saved && lo.u2_bytes) ? (char*)saved + lo.h_bytes + lo.z_bytes : nullptr;
+  c.diff_max_nnz = diff_max_nnz(layer, st);
+  c.diffT[0] = (char*)ws + lo.ws_bytes - 2 * lo.dt_bytes;
+  c.diffT[1] = (char*)ws + lo.ws_bytes - lo.dt_bytes;
+  return c;
+}
+
+}  // namespace
+
 extern "C" mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_segtab* st, const void* dev_segtab,
                                        const void* X, void* Y, void* saved, void* ws, size_t ws_bytes, void* hip_stream) {
   static const char* fn = "mux_lora_forward";
@@ -213,22 +248,23 @@ extern "C" mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_se
   if (!saved && (st->n_lora > 0 || st->n_tuning > 0))
     return fail(MUX_ERR_INVALID_ARG, std::string(fn) + ": saved is null but a task is LoRA or Adapter-Tuning");
   hipStream_t stream = (hipStream_t)hip_stream;
-  DevTask* dtasks = (DevTask*)ws;
-  const bool fast = layer->dtype == MUX_DT_BF16 && !(layer->flags & MUX_LAYER_REFERENCE_KERNELS);
-  void* at_region = (char*)ws + lo.tasks_bytes + lo.g_bytes;
-  fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, nullptr, nullptr, nullptr, stream,
-             (fast && st->n_lora + st->n_tuning > 0) ? at_region : nullptr, 0);
-  CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP,
-            (char*)ws + lo.tasks_bytes + lo.g_bytes, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes, layer->W, stream,
-            (saved && lo.u2_bytes) ? (char*)saved + lo.h_bytes + lo.z_bytes : nullptr, diff_max_nnz(layer, st),
-            {(char*)ws + lo.ws_bytes - 2 * lo.dt_bytes, (char*)ws + lo.ws_bytes - lo.dt_bytes}};
+  CallCtx c = make_ctx(layer, st, dev_segtab, lo, ws, saved, stream);
   void* H = saved;
   void* Z = (saved && st->z_rows > 0) ? (char*)saved + lo.h_bytes : nullptr;
+  // the matrix-core kernels, unless the storage type, the flag, a shape or a pointer rules them out: then the plain ones
+  const bool fast = layer->dtype == MUX_DT_BF16 && !(layer->flags & MUX_LAYER_REFERENCE_KERNELS) &&
+                    fast_supported(c, X, Y, H, Z, nullptr, nullptr);
+  c.lora_natural = fast && !any_packed_lora(st);
+  std::vector<DevTask> tasks;
+  build_tasks(layer, st, nullptr, nullptr, nullptr, c.lora_natural, tasks);
+  TaskRef tref;
+  const int pack = !fast ? 0 : ((st->n_lora > 0 && !c.lora_natural) ? 1 : (st->n_tuning > 0 ? 2 : 0));
+  publish_tasks(layer, st, tasks, !fast || st->n_diff > 0, (DevTask*)ws, tref, pack, c.AT, stream);
+  c.tref = &tref;
+  c.dtasks = tref.mem;
   mux_status s;
-  if (layer->dtype == MUX_DT_F32 || (layer->flags & MUX_LAYER_REFERENCE_KERNELS))
-    s = ref_forward(c, layer->dtype, X, Y, H, Z);
-  else
-    s = fast_forward(c, X, Y, H, Z, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes + lo.dys_bytes);
+  if (!fast) s = ref_forward(c, layer->dtype, X, Y, H, Z);
+  else s = fast_forward(c, X, Y, H, Z, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes + lo.dys_bytes);
   if (s) return s;
   // Diff-Pruning rows: the backbone wrote x W; the masked sparse update follows
   diff_forward(c, layer->dtype, X, Y);
@@ -250,31 +286,31 @@ static mux_status backward_impl(const char* fn, const mux_layer_desc* layer, con
   const Layout lo = make_layout(layer, st);
   if (ws_bytes < lo.ws_bytes) return fail(MUX_ERR_WORKSPACE, std::string(fn) + ": workspace too small");
   hipStream_t stream = (hipStream_t)hip_stream;
-  DevTask* dtasks = (DevTask*)ws;
-  const bool fast = layer->dtype == MUX_DT_BF16 && !(layer->flags & MUX_LAYER_REFERENCE_KERNELS);
-  fill_tasks(layer, st, (const int32_t*)dev_segtab, dtasks, dA, dB, dL, stream,
-             (fast && st->n_tuning > 0) ? (char*)ws + lo.tasks_bytes + lo.g_bytes : nullptr, 1);
-  CallCtx c{st, (const int32_t*)dev_segtab, dtasks, layer->K, layer->N, layer->ldw, lo.RP,
-            (char*)ws + lo.tasks_bytes + lo.g_bytes, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes, layer->W, stream,
-            (saved && lo.u2_bytes) ? (char*)saved + lo.h_bytes + lo.z_bytes : nullptr, diff_max_nnz(layer, st),
-            {(char*)ws + lo.ws_bytes - 2 * lo.dt_bytes, (char*)ws + lo.ws_bytes - lo.dt_bytes}};
+  CallCtx c = make_ctx(layer, st, dev_segtab, lo, ws, saved, stream);
+  const void* H = saved;
+  const void* Z = (saved && st->z_rows > 0) ? (const char*)saved + lo.h_bytes : nullptr;
+  void* G = (char*)ws + lo.tasks_bytes;
+  const bool fast = layer->dtype == MUX_DT_BF16 && !(layer->flags & MUX_LAYER_REFERENCE_KERNELS) &&
+                    fast_supported(c, X, dY, dX, G, H, Z);
+  c.lora_natural = fast && !any_packed_lora(st);
+  std::vector<DevTask> tasks;
+  build_tasks(layer, st, dA, dB, dL, c.lora_natural, tasks);
+  TaskRef tref;
+  publish_tasks(layer, st, tasks, !fast || st->n_diff > 0, (DevTask*)ws, tref, (fast && st->n_tuning > 0) ? 2 : 0, c.AT, stream);
+  c.tref = &tref;
+  c.dtasks = tref.mem;
   if (st->T == 0) {                 // no rows at all: zero gradients (or leave the accumulators as they are)
     if (!accumulate) {
       size_t big = (size_t)(st->r_max > 0 ? st->r_max : 1) * (size_t)(layer->K > layer->N ? layer->K : layer->N);
       if ((size_t)c.diff_max_nnz > big) big = (size_t)c.diff_max_nnz;
-      MUX_LAUNCH("zero_grads", k_zero_grads, dim3(st->n_tasks, (unsigned)((big + 255) / 256)), dim3(256), 0, stream, dtasks,
+      MUX_LAUNCH("zero_grads", k_zero_grads, dim3(st->n_tasks, (unsigned)((big + 255) / 256)), dim3(256), 0, stream, tref,
                  layer->K, layer->N);
     }
     return check_hip(fn);
   }
-  const void* H = saved;
-  const void* Z = (saved && st->z_rows > 0) ? (const char*)saved + lo.h_bytes : nullptr;
-  void* G = (char*)ws + lo.tasks_bytes;
   mux_status s;
-  if (layer->dtype == MUX_DT_F32 || (layer->flags & MUX_LAYER_REFERENCE_KERNELS))
-    s = ref_backward(c, layer->dtype, X, dY, H, Z, G, dX, accumulate);
-  else
-    s = fast_backward(c, X, dY, H, Z, G, dX, accumulate, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes + lo.dys_bytes);
+  if (!fast) s = ref_backward(c, layer->dtype, X, dY, H, Z, G, dX, accumulate);
+  else s = fast_backward(c, X, dY, H, Z, G, dX, accumulate, (char*)ws + lo.tasks_bytes + lo.g_bytes + lo.at_bytes + lo.dys_bytes);
   if (s) return s;
   diff_backward(c, layer->dtype, X, dY, dX, accumulate);
   return check_hip(fn);

@@ -47,6 +47,26 @@ __device__ __forceinline__ uint32_t row_valid_bits32(const int32_t* __restrict__
   return (uint32_t)(two >> sh);
 }
 
+// Task t of the call.  t is the same for every lane of the wave (an item, a tile or a block belongs to one task), and
+// so is every word of the result: saying so word by word keeps what is derived from it (buffer descriptors, loop
+// bounds) in scalar registers whichever of the two sources the words came from.
+__device__ __forceinline__ DevTask get_task(const TaskRef& r, int t) {
+  t = __builtin_amdgcn_readfirstlane(t);
+  const DevTask d = r.mem ? r.mem[t] : r.arg.t[t];
+  constexpr int W = sizeof(DevTask) / 4;
+  uint32_t w[W];
+  __builtin_memcpy(w, &d, sizeof(DevTask));
+#pragma unroll
+  for (int i = 0; i < W; ++i) w[i] = (uint32_t)__builtin_amdgcn_readfirstlane((int)w[i]);
+  DevTask o;
+  __builtin_memcpy(&o, w, sizeof(DevTask));
+  return o;
+}
+__device__ __forceinline__ int get_task_kind(const TaskRef& r, int t) {
+  t = __builtin_amdgcn_readfirstlane(t);
+  return __builtin_amdgcn_readfirstlane(r.mem ? r.mem[t].kind : r.arg.t[t].kind);
+}
+
 struct ItemView { int task, row0, nrows, nvalid; };
 __device__ __forceinline__ ItemView load_item(const int32_t* __restrict__ dtab, int tile_size_index, int item) {
   const int32_t* p = dtab + dtab[DH_NITEMS0 + 3 * tile_size_index + 1] + item * DI_WORDS;

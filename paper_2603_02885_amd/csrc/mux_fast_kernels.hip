@@ -16,11 +16,14 @@ static bool regstaged() {
 }
 
 // The 16-byte loads of the matrix-core kernels need 16-byte aligned rows everywhere.
-static bool fast_ok(const CallCtx& c) { return gemm_mfma_supported(c); }
+bool fast_supported(const CallCtx& c, const void* p0, const void* p1, const void* p2, const void* p3, const void* p4,
+                    const void* p5) {
+  return gemm_mfma_supported(c) && aligned16(p0) && aligned16(p1) && aligned16(p2) && aligned16(p3) && aligned16(p4) &&
+         aligned16(p5);
+}
 
+// The caller has checked fast_supported for the shapes and pointers of this call.
 mux_status fast_forward(const CallCtx& c, const void* X, void* Y, void* H, void* Z, void*) {
-  if (!fast_ok(c) || !aligned16(X) || !aligned16(Y) || !aligned16(H) || !aligned16(Z))
-    return ref_forward(c, MUX_DT_BF16, X, Y, H, Z);    // shapes the 16-byte loads cannot take
   if (mux_status s = adapter_down_x(c, X, H)) return s;
   mux_status s;
   if (gemm_dma_supported(c, false) && !regstaged()) s = gemm_dma_forward(c, X, H, Y, Z);
@@ -36,9 +39,8 @@ mux_status fast_forward(const CallCtx& c, const void* X, void* Y, void* H, void*
 
 mux_status fast_backward(const CallCtx& c, const void* X, const void* dY, const void* H, const void* Z, void* G, void* dX,
                          int accumulate, void* part) {
-  if (!fast_ok(c) || !aligned16(X) || !aligned16(dY) || !aligned16(dX) || !aligned16(G) || !aligned16(H) || !aligned16(Z))
-    return ref_backward(c, MUX_DT_BF16, X, dY, H, Z, G, dX, accumulate);
-  if (mux_status s = adapter_down_g(c, dY, G)) return s;
+  // one pass over dY: Gs and the partial sums of dB_t
+  if (mux_status s = adapter_dy_pass(c, dY, H, G, part)) return s;
   // Adapter-Tuning rows enter the backbone backward as dY + Gs D_t^T
   if (mux_status s = adapter_tune_add(c, dY, G, c.dYs, 1)) return s;
   if (mux_status s = adapter_grads(c, X, dY, H, G, Z, part, accumulate)) return s;

@@ -44,7 +44,6 @@ constexpr uint32_t OOB = 0x80000000u;
 
 struct GemmParams {
   const int32_t* dtab;
-  const DevTask* tasks;
   const bf16_t* Ain;   // [T, Kc]  activations (X or dY)
   const bf16_t* W;     // [K, ldw]
   int64_t ldw;
@@ -57,6 +56,7 @@ struct GemmParams {
   int tail_split;          // pieces per tile after the full ones: 2 (halves) or 4 (quarters)
   unsigned long long* clk;  // diagnostic: counters workgroup 0 adds its elapsed cycles and 100 MHz ticks to (null: off)
   const bf16_t* AinScaled;  // backward: prepared input rows (IA3_OUT: dY * l_t; TUNING: dY + p D_t^T), [z_rows, Kc], indexed like the saved x W
+  TaskRef tasks;
 };
 
 // Raw buffer descriptor (stride 0) over `bytes` bytes starting at p, as four dwords.
@@ -176,7 +176,7 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
     return;
   }
 
-  const DevTask tk = p.tasks[it.task];
+  const DevTask tk = get_task(p.tasks, it.task);
   const bool lora = tk.kind == MUX_ADAPTER_LORA;
   const bool ia3 = tk.kind == MUX_ADAPTER_IA3_OUT;
   const bool tuning = tk.kind == MUX_ADAPTER_TUNING;   // forward: only x W is produced here (saved); backward: prepared rows
@@ -586,7 +586,7 @@ int compute_units() {
 template <bool NT>
 mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t* Out, bf16_t* Zsave, int Kc, int Nc) {
   GemmParams p;
-  p.dtab = c.dtab; p.tasks = c.dtasks; p.Ain = Ain; p.W = (const bf16_t*)c.W; p.ldw = c.ldw; p.Ext = Ext; p.Out = Out;
+  p.dtab = c.dtab; p.tasks = *c.tref; p.Ain = Ain; p.W = (const bf16_t*)c.W; p.ldw = c.ldw; p.Ext = Ext; p.Out = Out;
   p.Zsave = Zsave; p.Kc = Kc; p.Nc = Nc; p.RP = c.RP;
   p.n_m = (int)c.st->items[TS256].size();
   p.n_n = (Nc + TILE_N - 1) / TILE_N;

@@ -34,7 +34,6 @@ constexpr int EP_PITCH = 128 + 8;    // elements; epilogue staging rows of one w
 
 struct GemmParams {
   const int32_t* dtab;
-  const DevTask* tasks;
   const bf16_t* Ain;   // [T, Kc]  activations (X or dY)
   const bf16_t* W;     // [K, ldw]
   int64_t ldw;
@@ -45,6 +44,7 @@ struct GemmParams {
   int n_m, n_n, per_xcd;
   int only_ia3;        // process IA3_OUT items only (the pipelined kernel took the rest)
   const bf16_t* Prep;  // backward: prepared input rows of the TUNING tasks (dY + p D_t^T), [z_rows, Kc], indexed like the saved x W
+  TaskRef tasks;
 };
 
 __device__ __forceinline__ uint4 zero4() { return make_uint4(0, 0, 0, 0); }
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm(const GemmParams p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
 
-  if (p.only_ia3 && !(it.task >= 0 && it.nvalid > 0 && p.tasks[it.task].kind == MUX_ADAPTER_IA3_OUT)) return;
+  if (p.only_ia3 && !(it.task >= 0 && it.nvalid > 0 && get_task_kind(p.tasks, it.task) == MUX_ADAPTER_IA3_OUT)) return;
 
   {
     const int row = it.row0 + tid;
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm(const GemmParams p) {
     return;
   }
 
-  const DevTask tk = p.tasks[it.task];
+  const DevTask tk = get_task(p.tasks, it.task);
   const bool lora = tk.kind == MUX_ADAPTER_LORA;
   const bool ia3 = tk.kind == MUX_ADAPTER_IA3_OUT;
   const bool tuning = tk.kind == MUX_ADAPTER_TUNING;   // forward: only x W is produced here (saved); backward: rows from Prep
@@ -349,7 +349,7 @@ mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t
     attr_set = true;
   }
   GemmParams p;
-  p.dtab = c.dtab; p.tasks = c.dtasks; p.Ain = Ain; p.W = (const bf16_t*)c.W; p.ldw = c.ldw; p.Ext = Ext; p.Out = Out;
+  p.dtab = c.dtab; p.tasks = *c.tref; p.Ain = Ain; p.W = (const bf16_t*)c.W; p.ldw = c.ldw; p.Ext = Ext; p.Out = Out;
   p.Zsave = Zsave; p.Kc = Kc; p.Nc = Nc; p.RP = c.RP;
   p.n_m = (int)c.st->items[TS256].size();
   p.n_n = (Nc + BN - 1) / BN;
@@ -366,10 +366,11 @@ mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t
 
 bool gemm_mfma_supported(const CallCtx& c) {
   // 16-byte global loads need rows of X, dY, W, Hs and B_t to start 16-byte aligned
-  // and the 32-bit buffer offsets need W and one 256-row slab of activations below 2 GiB
+  // and the 32-bit buffer offsets need W and the largest row group a kernel builds one descriptor over (1024 rows of
+  // activations; rows parked at offset 2^31 must stay out of range) below 2 GiB
   const int64_t big = (int64_t)1 << 31;
   return (c.K % 8 == 0) && (c.N % 8 == 0) && (c.ldw % 8 == 0) && (((uintptr_t)c.W & 15) == 0) &&
-         ((int64_t)c.K * c.ldw * 2 < big) && ((int64_t)256 * (c.K > c.N ? c.K : c.N) * 2 < big);
+         ((int64_t)c.K * c.ldw * 2 < big) && ((int64_t)1024 * (c.K > c.N ? c.K : c.N) * 2 < big);
 }
 
 mux_status gemm_mfma_forward(const CallCtx& c, const void* X, const void* Hs, void* Y, void* Z) {

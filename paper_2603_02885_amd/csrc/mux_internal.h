@@ -20,6 +20,7 @@ enum : int {
   DH_ATT_OFF_FWD,        // list ordered for the passes that walk the keys before a block (longest walk first) and of the
   DH_ATT_OFF_BWD,        // list ordered for the pass that walks the queries after a block; 4 words an entry (DA_*)
   DH_OFF_ITEM_TOK0,      // per 64-row work item: how many tokens of its task lie on the rows before it
+  DH_OFF_ITEM_BITS,      // per 64-row work item: two words, bit r = row row0 + r of the item is a real token
   DH_HDR_WORDS = 32
 };
 constexpr int kNumTileSizes = 4;
@@ -55,6 +56,16 @@ struct DevTask {
 };
 static_assert(sizeof(DevTask) == 80, "DevTask layout");
 
+// The task parameters of a call as the kernels see them: up to kArgTasks tasks travel by value in the kernel
+// arguments (no kernel has to write a table first); more tasks than that, and the kernels that take a plain pointer,
+// read the table a small kernel wrote into the workspace.
+constexpr int kArgTasks = 32;
+struct TaskTable { DevTask t[kArgTasks]; };
+struct TaskRef {
+  const DevTask* mem;   // device table, or null: then `arg` holds the tasks
+  TaskTable arg;
+};
+
 struct HostTask {
   int32_t kind, rank;
   float scale;
@@ -86,6 +97,7 @@ mux_status fail(mux_status s, const std::string& msg);
 void clear_error();
 
 // Optional event bracketing of kernel launches (see mux_profile_enable).
+void prof_note_bytes(double bytes);   // bytes the next bracketed launch moves (kernels the method itself asks no bytes of)
 void prof_begin(const char* name, hipStream_t stream);
 void prof_end(hipStream_t stream);
 struct ProfScope {
@@ -110,7 +122,8 @@ inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 struct CallCtx {
   const mux_segtab* st;
   const int32_t* dtab;     // device image
-  const DevTask* dtasks;   // device, in workspace
+  const DevTask* dtasks;   // device table in the workspace (null when no kernel of this call reads it)
+  const TaskRef* tref;     // what the matrix-core kernels take: that table, or the tasks by value
   int K, N;
   int64_t ldw;
   int RP;                  // row pitch (elements) of the H / G buffers
@@ -120,6 +133,7 @@ struct CallCtx {
   const void* W;
   hipStream_t stream;
   void* U2;                // saved: pre-activations z D_t of the TUNING rows, [T][RP] (null without such tasks)
+  bool lora_natural;       // every LoRA rank is a multiple of 8: the down-projection reads A_t [K, r] as it is
   int diff_max_nnz;        // largest mask of the DIFF tasks of this call
   void* diffT[2];          // workspace: block-transposed copies of the DIFF rows of X ([0]) and of dY ([1])
 };
@@ -160,15 +174,17 @@ mux_status gemm_dma_backward(const CallCtx& c, const void* dY, const void* Gs, v
 
 // matrix-core adapter kernels (bf16): down-projections and per-task gradient reductions
 mux_status adapter_down_x(const CallCtx& c, const void* X, void* Hs);                       // S1
-mux_status adapter_down_g(const CallCtx& c, const void* dY, void* Gs);                      // S4a
+mux_status adapter_dy_pass(const CallCtx& c, const void* dY, const void* Hs, void* Gs, void* part);   // S4: Gs, dB partials
 mux_status adapter_down_tune(const CallCtx& c, const void* Z, void* Hs);                    // Adapter-Tuning forward
 mux_status adapter_tune_add(const CallCtx& c, const void* In, const void* Small, void* Out, int backward);
 mux_status adapter_grads(const CallCtx& c, const void* X, const void* dY, const void* Hs, const void* Gs, const void* Z,
-                         void* part, int accumulate);                                       // S4b, S6
+                         void* part, int accumulate);                                       // S6, and the sums of S4
 size_t adapter_partial_bytes(int K, int N, const mux_segtab* st);
 
 // matrix-core (MFMA) kernels, bf16 storage
 size_t fast_partial_bytes(int K, int N, const mux_segtab* st);
+bool fast_supported(const CallCtx& c, const void* p0, const void* p1, const void* p2, const void* p3, const void* p4,
+                    const void* p5);   // shapes and pointers the 16-byte loads of the matrix-core kernels can take
 mux_status fast_forward(const CallCtx& c, const void* X, void* Y, void* H, void* Z, void* part);
 mux_status fast_backward(const CallCtx& c, const void* X, const void* dY, const void* H, const void* Z, void* G, void* dX,
                          int accumulate, void* part);

@@ -237,6 +237,17 @@ extern "C" mux_status mux_segtab_build(const mux_task_desc* tasks, int32_t n_tas
       for (int32_t i = 0; i < st->T; ++i)
         if (st->row_task[i] >= 0) dv[base + (i >> 5)] |= (int32_t)(1u << (i & 31));
     }
+    // validity bits of the rows of every 64-row item, two words an item (bit r of the pair = row row0 + r is a real token)
+    {
+      dv[DH_OFF_ITEM_BITS] = (int32_t)dv.size();
+      for (const Item& it : st->items[0]) {
+        uint32_t w[2] = {0u, 0u};
+        for (int32_t r = 0; r < it.nrows; ++r)
+          if (st->row_task[it.row0 + r] >= 0) w[r >> 5] |= 1u << (r & 31);
+        dv.push_back((int32_t)w[0]);
+        dv.push_back((int32_t)w[1]);
+      }
+    }
     // Dispatch: the packed position of a task's token = the number of the task's tokens on the rows before it
     {
       dv[DH_OFF_ITEM_TOK0] = (int32_t)dv.size();

@@ -348,6 +348,42 @@ def test_leading_dimension_packs_and_skipped_outputs(env):
     assert torch.all(dA[0] == 0) and torch.all(dB[0] == 0)      # a task without tokens has zero gradients
 
 
+def test_task_table_by_value_and_in_memory(env):
+    """Up to 32 tasks travel in the kernel arguments; more than that (here 40, all kinds but the selective one, some
+    without rows) make the kernels read the table a small kernel wrote into the workspace.  Both against the oracle,
+    and bit-identical repeats."""
+    mx, torch = env
+    rng = np.random.default_rng(77)
+    kinds = [wlm.KIND_LORA, wlm.KIND_LORA, wlm.KIND_IA3, wlm.KIND_ADAPTER, wlm.KIND_NONE]
+    for n_tasks in (32, 40):
+        tasks = []
+        for t in range(n_tasks):
+            kind = kinds[t % len(kinds)]
+            rank = int(rng.choice([8, 16, 24])) if kind in (wlm.KIND_LORA, wlm.KIND_ADAPTER) else 0
+            tasks.append(wlm.Task(kind, rank, 1.5, [] if t % 11 == 7 else [int(rng.integers(5, 90))]))
+        wl = wlm.Workload(name=f"many{n_tasks}", layers=[("w", 256, 192)], tasks=tasks, chunk=32, sigma_w=0.05, sigma_ab=0.05)
+        g, got, ref, errs = run_case(env, wl, seed=n_tasks)
+        keep = [t.clone() for t in [g.Y, g.dX] + [x for x in g.dA + g.dB + g.dL if x is not None]]
+        g.forward(); g.backward()
+        torch.cuda.synchronize()
+        for a, b in zip(keep, [g.Y, g.dX] + [x for x in g.dA + g.dB + g.dL if x is not None]):
+            assert torch.equal(a, b)
+
+
+def test_dy_pass_row_groups_and_column_slabs(env):
+    """The pass over dY on shapes that give it several 512-column slabs (the last one ragged, one wave of it past the
+    end), row groups of 1024 and of 256 rows with ragged tails, ranks that fill one, two and four 16-wide pieces, and
+    A_t read in place (every rank a multiple of 8) or from the transposed copy (one rank that is not)."""
+    for ranks, K, N, toks in (((16, 8, 16), 256, 1352, (2500, 1100, 300)),     # three slabs, 1024-row groups
+                              ((32, 24, 64), 192, 1096, (700, 300, 1300)),     # NJ = 2 and 4
+                              ((16, 12, 8), 320, 520, (600, 270, 130))):       # rank 12: the transposed copy
+        tasks = [wlm.Task(wlm.KIND_LORA, r, 2.0, [n, 17]) for r, n in zip(ranks, toks)]
+        tasks.insert(1, wlm.Task(wlm.KIND_IA3, 0, 1.0, [150]))
+        wl = wlm.Workload(name=f"s4_{N}", layers=[("w", K, N)], tasks=tasks, chunk=64, sigma_w=0.05, sigma_ab=0.05)
+        run_case(env, wl, seed=N)
+        run_case(env, wl, seed=N + 1, seg_flags=1)
+
+
 @pytest.mark.parametrize("block", range(4))
 def test_random_sweep(env, block):
     """Seeded random layer calls: every adapter kind at random ranks (1..64), random shapes (multiples of 64, 32, 8
