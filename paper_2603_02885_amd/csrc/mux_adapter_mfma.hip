@@ -39,6 +39,26 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t* p) {
 }
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
+// Validity bits of the rows of a row group of up to 1024 rows, fetched once: lane l keeps the 32-bit word that holds
+// row row0 + 32 l (and the one after it); step s of the group then takes its 32 bits from lanes with two lane reads
+// instead of a memory access of its own, on which the step's loads would have to wait.
+struct GroupBits { uint32_t lo, hi; int sh; };
+__device__ __forceinline__ GroupBits load_group_bits(const int32_t* __restrict__ dtab, int rowbits_off, int row0, int nrows, int T, int lane) {
+  const uint32_t* bm = (const uint32_t*)(dtab + rowbits_off);
+  const int w0 = row0 >> 5;
+  const int last = (T + 31) >> 5;                        // the spare word after the last one exists
+  const int nw = ((nrows + 31) >> 5) + 1;
+  GroupBits g;
+  g.lo = (lane < nw && w0 + lane <= last) ? bm[w0 + lane] : 0u;
+  g.hi = (lane < nw && w0 + lane + 1 <= last) ? bm[w0 + lane + 1] : 0u;
+  g.sh = row0 & 31;
+  return g;
+}
+__device__ __forceinline__ uint32_t step_bits(const GroupBits& g, int s) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)g.lo, s), hi = (uint32_t)__builtin_amdgcn_readlane((int)g.hi, s);
+  return (uint32_t)((((uint64_t)hi << 32) | lo) >> g.sh);
+}
+
 // ------------------------------------------------------------------------------------------------
 // down-projection.  One workgroup = 32 rows of one 64-row item; its waves split the contraction.
 // A wave walks its share 64 columns at a time: the 32x64 slab of In and the rank x 64 slab of P_t are fetched with
@@ -275,15 +295,34 @@ struct S4Params {
   float* gpart;         // [n_slabs][T][RP]: dY B_t^T over the columns of one slab, unscaled
   float* bpart;         // [n_items][RP][N]: Hs^T dY over the rows of one group
   int N, RP, ts, T;
+  int items_off, rowbits_off;   // word offsets in dtab of the row-group list and of the row-validity bits
   TaskRef tasks;
 };
 
-template <int NJM>
+// BATCH: steps whose shares of dY B_t^T wait in registers before the waves meet to add them up; DEPTH: steps of loads
+// in flight.  The loop body has no branch and a fixed number of loads and stores per step (what does not exist gets an
+// out-of-range offset), so that the waits for one step's data leave the younger loads in flight.
+__device__ __forceinline__ void buf_store4(rsrc_t r, uint32_t byte_off, float v) {
+  __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, v), r, (int)byte_off, 0, 0);
+}
+__device__ __forceinline__ void lds_barrier() {     // LDS traffic of every wave done; loads from memory stay in flight
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xC07F);               // lgkmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+template <int NJM, int BATCH, int DEPTH>
 __global__ __launch_bounds__(512) void k_s4(const S4Params p) {
-  constexpr int NWV = 8, NTHR = 512, RPITCH = 36;               // RPITCH: floats between two columns of a staged share
-  static_assert(NJM * 16 * RPITCH * 4 <= 2 * 32 * GP * 2, "a wave's share of dY B_t^T fits its own LDS region");
+  constexpr int NWV = 8, NTHR = 512, BROWS = BATCH * 32, RPITCH = BROWS + 4;   // RPITCH: floats between two columns of a staged share
+  constexpr int UNR = BATCH > DEPTH ? BATCH : DEPTH;
+  constexpr int RPJ = NJM * 16;                                   // columns of a staged share
+  constexpr int NRED = BROWS * RPJ / NTHR;                        // sums a thread forms when the waves meet
+  static_assert(RPJ * RPITCH * 4 <= 2 * 32 * GP * 2, "a wave's share of dY B_t^T fits its own LDS region");
+  static_assert(UNR % BATCH == 0 && UNR % DEPTH == 0 && BROWS * RPJ % NTHR == 0, "powers of two");
   __shared__ __attribute__((aligned(16))) bf16_t lds[NWV][2][32 * GP];
-  const ItemView it = load_item(p.dtab, p.ts, blockIdx.x);
+  const int4 iw = *(const int4*)(p.dtab + p.items_off + blockIdx.x * DI_WORDS);   // the lists' offsets are launch arguments:
+  const ItemView it = {iw.x, iw.y, iw.z, iw.w};                                    // one memory latency before the first load
   if (it.task < 0 || it.nvalid == 0) return;
   const DevTask tk = get_task(p.tasks, it.task);
   if (tk.kind != MUX_ADAPTER_LORA && tk.kind != MUX_ADAPTER_TUNING) return;
@@ -296,10 +335,11 @@ __global__ __launch_bounds__(512) void k_s4(const S4Params p) {
   const rsrc_t rB = make_rsrc(p.dY + (size_t)it.row0 * p.N, (uint32_t)it.nrows * (uint32_t)p.N * 2u);
   const rsrc_t rS = make_rsrc(p.Hs + (size_t)it.row0 * p.RP, (uint32_t)it.nrows * (uint32_t)p.RP * 2u);
   const rsrc_t rP = make_rsrc(tk.B, (uint32_t)rank * (uint32_t)p.N * 2u);
+  // the partial sums of this slab for the rows of this group
+  const rsrc_t rG = make_rsrc(p.gpart + ((size_t)blockIdx.y * p.T + it.row0) * p.RP, (uint32_t)it.nrows * (uint32_t)p.RP * 4u);
   const int b_row = lane >> 3, b_pc = (lane & 7) * 8;
   const bool b_col_ok = cw0 + b_pc < p.N;
-  const int ppr = p.RP >> 3;
-  const int n_small = (32 * ppr + 63) >> 6;    // loads per lane (1..4)
+  const int ppr = p.RP >> 3;                   // 16-byte pieces in a row of Hs; RP <= 16 NJM, so a lane loads at most NJM of them
   const int l16 = lane & 15, g = lane >> 4;
 
   // B_t[j][columns of this wave], as the B operand of dY B_t^T: lane (j = l16, g) holds 8 consecutive columns
@@ -312,35 +352,35 @@ __global__ __launch_bounds__(512) void k_s4(const S4Params p) {
       bt[jt][s] = as_bf16x8(buf_load16(rP, (j < rank && col < p.N) ? (uint32_t)(((size_t)j * p.N + col) * 2) : OOB));
     }
 
-  u32x4 gb[4], gs[4];
-  auto load_step = [&](int s) {
+  u32x4 gb[DEPTH][4], gs[DEPTH][NJM];
+  const int steps = (it.nrows + 31) >> 5;
+  const GroupBits gbits = load_group_bits(p.dtab, p.rowbits_off, it.row0, it.nrows, p.T, lane);
+  // per-lane pieces of the Hs slab: idx = lane + 64 q -> row idx / ppr, piece idx % ppr
+  int s_row[NJM], s_pc[NJM];
+#pragma unroll
+  for (int q = 0; q < NJM; ++q) { const int idx = lane + 64 * q; s_row[q] = idx / ppr; s_pc[q] = (idx % ppr) * 8; }
+  auto load_step = [&](int s, int buf) {       // a step past the end loads nothing (every offset out of range)
     const int base = s * 32;
-    const uint32_t vbits = it.row0 + base < p.T ? row_valid_bits32(p.dtab, it.row0 + base) : 0u;
+    const uint32_t vbits = s < steps ? step_bits(gbits, s) : 0u;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int m = base + b_row + 8 * q;
       const bool ok = b_col_ok && m < it.nrows && ((vbits >> (b_row + 8 * q)) & 1u);
-      gb[q] = buf_load16(rB, ok ? (uint32_t)(((size_t)m * p.N + cw0 + b_pc) * 2) : OOB);
+      gb[buf][q] = buf_load16(rB, ok ? (uint32_t)(((size_t)m * p.N + cw0 + b_pc) * 2) : OOB);
     }
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      if (q < n_small) {
-        const int idx = lane + 64 * q, m = base + idx / ppr, pc = (idx % ppr) * 8;
-        const bool ok = idx < 32 * ppr && m < it.nrows;
-        gs[q] = buf_load16(rS, ok ? (uint32_t)((m * p.RP + pc) * 2) : OOB);
-      }
+    for (int q = 0; q < NJM; ++q) {
+      const int m = base + s_row[q];
+      const bool ok = s < steps && s_row[q] < 32 && m < it.nrows;
+      gs[buf][q] = buf_load16(rS, ok ? (uint32_t)((m * p.RP + s_pc[q]) * 2) : OOB);
     }
   };
-  auto store_step = [&]() {
+  auto store_step = [&](int buf) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) *(u32x4*)(sBig + (b_row + 8 * q) * GP + b_pc) = gb[q];
+    for (int q = 0; q < 4; ++q) *(u32x4*)(sBig + (b_row + 8 * q) * GP + b_pc) = gb[buf][q];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      if (q < n_small) {
-        const int idx = lane + 64 * q;
-        if (idx < 32 * ppr) *(u32x4*)(sSm + (idx / ppr) * GP + (idx % ppr) * 8) = gs[q];
-      }
-    }
+    for (int q = 0; q < NJM; ++q)
+      if (s_row[q] < 32) *(u32x4*)(sSm + s_row[q] * GP + s_pc[q]) = gs[buf][q];
   };
 
   f32x4 accb[NJM][4];
@@ -348,73 +388,77 @@ __global__ __launch_bounds__(512) void k_s4(const S4Params p) {
   for (int jt = 0; jt < NJM; ++jt)
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct) accb[jt][ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  f32x4 accg[BATCH][2][NJM];
 
   const int tr_off = (8 * g + (l16 >> 2)) * GP + 4 * (l16 & 3);
-  const int steps = (it.nrows + 31) >> 5;
-  const int slab = blockIdx.y;
   float* red = (float*)lds[wave];
-  load_step(0);
-  for (int s = 0; s < steps; ++s) {
-    store_step();
-    if (s + 1 < steps) load_step(s + 1);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    f32x4 accg[2][NJM];
-    {
-      bf16x8 a[NJM], b[4], ay[2][2];
 #pragma unroll
-      for (int jt = 0; jt < NJM; ++jt)
-        if (jt < NJ) {
+  for (int d = 0; d < DEPTH; ++d) load_step(d, d);
+  for (int s0 = 0; s0 < steps; s0 += UNR) {
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int s = s0 + u;                       // may run past the last step: zeros in, nothing out
+      store_step(u % DEPTH);
+      load_step(s + DEPTH, u % DEPTH);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      {
+        bf16x8 a[NJM], b[4], ay[2][2];
+#pragma unroll
+        for (int jt = 0; jt < NJM; ++jt) {
           const bf16x4 lo = lds_read_tr(sSm + tr_off + jt * 16), hi = lds_read_tr(sSm + tr_off + 4 * GP + jt * 16);
           a[jt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         }
 #pragma unroll
-      for (int ct = 0; ct < 4; ++ct) {
-        const bf16x4 lo = lds_read_tr(sBig + tr_off + ct * 16), hi = lds_read_tr(sBig + tr_off + 4 * GP + ct * 16);
-        b[ct] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      }
+        for (int ct = 0; ct < 4; ++ct) {
+          const bf16x4 lo = lds_read_tr(sBig + tr_off + ct * 16), hi = lds_read_tr(sBig + tr_off + 4 * GP + ct * 16);
+          b[ct] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
 #pragma unroll
-      for (int rt = 0; rt < 2; ++rt)
+        for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) ay[rt][ks] = *(const bf16x8*)(sBig + (rt * 16 + l16) * GP + ks * 32 + 8 * g);
+          for (int ks = 0; ks < 2; ++ks) ay[rt][ks] = *(const bf16x8*)(sBig + (rt * 16 + l16) * GP + ks * 32 + 8 * g);
 #pragma unroll
-      for (int jt = 0; jt < NJM; ++jt)
-        if (jt < NJ)
-#pragma unroll
-          for (int ct = 0; ct < 4; ++ct) accb[jt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[jt], b[ct], accb[jt][ct], 0, 0, 0);
-#pragma unroll
-      for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-        for (int jt = 0; jt < NJM; ++jt) {
-          accg[rt][jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int jt = 0; jt < NJM; ++jt)
           if (jt < NJ)
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks) accg[rt][jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ay[rt][ks], bt[jt][ks], accg[rt][jt], 0, 0, 0);
-        }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    // accg[rt][jt][v] = share of (dY B_t^T)[row base + rt*16 + 4g + v][jt*16 + l16]: staged over the slabs just read
+            for (int ct = 0; ct < 4; ++ct) accb[jt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[jt], b[ct], accb[jt][ct], 0, 0, 0);
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
+        for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-      for (int jt = 0; jt < NJM; ++jt)
-        if (jt < NJ) *(f32x4*)&red[(jt * 16 + l16) * RPITCH + rt * 16 + 4 * g] = accg[rt][jt];
-    __syncthreads();
-    {
-      const int base = s * 32;
-      for (int e = tid; e < 32 * p.RP; e += NTHR) {
-        const int m = e / p.RP, j = e % p.RP;
-        if (base + m >= it.nrows) continue;
-        float v = 0.f;
-        if (j < NJ * 16) {
+          for (int jt = 0; jt < NJM; ++jt) {
+            f32x4 v = (f32x4){0.f, 0.f, 0.f, 0.f};
+            if (jt < NJ)
+#pragma unroll
+              for (int ks = 0; ks < 2; ++ks) v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ay[rt][ks], bt[jt][ks], v, 0, 0, 0);
+            accg[u % BATCH][rt][jt] = v;
+          }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      if ((u % BATCH) == BATCH - 1) {
+        // The waves meet: accg[bi][rt][jt][v] = this wave's share of (dY B_t^T)[row of the batch 32 bi + 16 rt + 4 g + v]
+        // [16 jt + l16], staged over the slabs just read, added up in wave order, one fp32 partial per row and column out.
+#pragma unroll
+        for (int bi = 0; bi < BATCH; ++bi)
+#pragma unroll
+          for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int jt = 0; jt < NJM; ++jt) *(f32x4*)&red[(jt * 16 + l16) * RPITCH + bi * 32 + rt * 16 + 4 * g] = accg[bi][rt][jt];
+        lds_barrier();
+        const int base = (s - (BATCH - 1)) * 32;                // first row of the batch inside the group
+#pragma unroll
+        for (int i = 0; i < NRED; ++i) {
+          const int e = tid + NTHR * i, m = e / RPJ, j = e % RPJ;
+          float v = 0.f;
 #pragma unroll
           for (int w = 0; w < NWV; ++w) v += ((const float*)lds[w])[j * RPITCH + m];
+          const bool ok = base + m < it.nrows && j < p.RP;
+          buf_store4(rG, ok ? (uint32_t)(((base + m) * p.RP + j) * 4) : OOB, v);
         }
-        p.gpart[((size_t)slab * p.T + it.row0 + base + m) * p.RP + j] = v;
+        lds_barrier();
       }
     }
-    __syncthreads();
   }
   if (cw0 >= p.N) return;
   // accb[jt][ct][v] = bpart[j = jt*16 + 4g + v][c = cw0 + ct*16 + l16]
@@ -496,13 +540,17 @@ struct GradParams {     // z0 + blockIdx.z picks the problem: 0 = dB (Small = Hs
   const bf16_t* Zc;        // saved x W, [z_rows, N]
   size_t slot[2];          // elements per item in part[z]
   int z0;                  // 1: the launch computes the second problem only (the pass over dY has done the first)
+  int items_off, rowbits_off, T;   // word offsets in dtab of the row-group list and of the row-validity bits; rows of the batch
   TaskRef tasks;
 };
 
-template <int NJM>
+// DEPTH steps of loads in flight; the loop body has no branch and a fixed number of loads per step (what does not
+// exist gets an out-of-range offset), so that the wait for one step's data leaves the younger loads in flight.
+template <int NJM, int DEPTH>
 __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
   __shared__ __attribute__((aligned(16))) bf16_t lds[4][2][32 * GP];
-  const ItemView it = load_item(p.dtab, p.ts, blockIdx.x);
+  const int4 iw = *(const int4*)(p.dtab + p.items_off + blockIdx.x * DI_WORDS);
+  const ItemView it = {iw.x, iw.y, iw.z, iw.w};
   if (it.task < 0 || it.nvalid == 0) return;
   const DevTask tk = get_task(p.tasks, it.task);
   if (tk.kind != MUX_ADAPTER_LORA && tk.kind != MUX_ADAPTER_TUNING) return;
@@ -522,41 +570,38 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
   // Big slab: 4 loads per lane, row = 8q + lane/8, 16-byte piece = lane%8
   const int b_row = lane >> 3, b_pc = (lane & 7) * 8;
   const bool b_col_ok = cw0 + b_pc < C;
-  // Small slab: pieces per row = RP/8; idx = lane + 64 q -> row = idx / ppr, piece = idx % ppr
+  // Small slab: pieces per row = RP/8 (RP <= 16 NJM); idx = lane + 64 q -> row = idx / ppr, piece = idx % ppr
   const int ppr = p.RP >> 3;
-  const int n_small = (32 * ppr + 63) >> 6;    // loads per lane (1..4)
+  int s_row[NJM], s_pc[NJM];
+#pragma unroll
+  for (int q = 0; q < NJM; ++q) { const int idx = lane + 64 * q; s_row[q] = idx / ppr; s_pc[q] = (idx % ppr) * 8; }
 
-  u32x4 gb[4], gs[4];
-  const int total_rows = p.dtab[DH_T];
-  auto load_step = [&](int s) {
+  u32x4 gb[DEPTH][4], gs[DEPTH][NJM];
+  const int steps = (it.nrows + 31) >> 5;
+  const GroupBits gbits = load_group_bits(p.dtab, p.rowbits_off, it.row0, it.nrows, p.T, lane);
+  auto load_step = [&](int s, int buf) {       // a step past the end loads nothing (every offset out of range)
     const int base = s * 32;
-    // validity of the 32 rows of this step, wave-uniform (rows past the end of the batch are never valid)
-    const uint32_t vbits = it.row0 + base < total_rows ? row_valid_bits32(p.dtab, it.row0 + base) : 0u;
+    // validity of the 32 rows of this step, wave-uniform, from the words fetched once for the whole group
+    const uint32_t vbits = s < steps ? step_bits(gbits, s) : 0u;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int m = base + b_row + 8 * q;
       const bool ok = b_col_ok && m < it.nrows && ((vbits >> (b_row + 8 * q)) & 1u);
-      gb[q] = buf_load16(rB, ok ? (uint32_t)(((size_t)m * C + cw0 + b_pc) * 2) : OOB);
+      gb[buf][q] = buf_load16(rB, ok ? (uint32_t)(((size_t)m * C + cw0 + b_pc) * 2) : OOB);
     }
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      if (q < n_small) {
-        const int idx = lane + 64 * q, m = base + idx / ppr, pc = (idx % ppr) * 8;
-        const bool ok = idx < 32 * ppr && m < it.nrows;
-        gs[q] = buf_load16(rS, ok ? (uint32_t)((m * p.RP + pc) * 2) : OOB);
-      }
+    for (int q = 0; q < NJM; ++q) {
+      const int m = base + s_row[q];
+      const bool ok = s < steps && s_row[q] < 32 && m < it.nrows;
+      gs[buf][q] = buf_load16(rS, ok ? (uint32_t)((m * p.RP + s_pc[q]) * 2) : OOB);
     }
   };
-  auto store_step = [&]() {
+  auto store_step = [&](int buf) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) *(u32x4*)(sBig + (b_row + 8 * q) * GP + b_pc) = gb[q];
+    for (int q = 0; q < 4; ++q) *(u32x4*)(sBig + (b_row + 8 * q) * GP + b_pc) = gb[buf][q];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      if (q < n_small) {
-        const int idx = lane + 64 * q;
-        if (idx < 32 * ppr) *(u32x4*)(sSm + (idx / ppr) * GP + (idx % ppr) * 8) = gs[q];
-      }
-    }
+    for (int q = 0; q < NJM; ++q)
+      if (s_row[q] < 32) *(u32x4*)(sSm + s_row[q] * GP + s_pc[q]) = gs[buf][q];
   };
 
   f32x4 acc[NJM][4];
@@ -567,32 +612,34 @@ __global__ __launch_bounds__(256) void k_grad(const GradParams p) {
 
   const int l16 = lane & 15, g = lane >> 4;
   const int tr_off = (8 * g + (l16 >> 2)) * GP + 4 * (l16 & 3);
-  const int steps = (it.nrows + 31) >> 5;
-  load_step(0);
-  for (int s = 0; s < steps; ++s) {
-    store_step();
-    if (s + 1 < steps) load_step(s + 1);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    bf16x8 a[NJM], b[4];
 #pragma unroll
-    for (int jt = 0; jt < NJM; ++jt)
-      if (jt < NJ) {
+  for (int d = 0; d < DEPTH; ++d) load_step(d, d);
+  for (int s0 = 0; s0 < steps; s0 += DEPTH) {
+#pragma unroll
+    for (int u = 0; u < DEPTH; ++u) {          // may run past the last step: zeros in
+      store_step(u);
+      load_step(s0 + u + DEPTH, u);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      bf16x8 a[NJM], b[4];
+#pragma unroll
+      for (int jt = 0; jt < NJM; ++jt) {
         const bf16x4 lo = lds_read_tr(sSm + tr_off + jt * 16), hi = lds_read_tr(sSm + tr_off + 4 * GP + jt * 16);
         a[jt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       }
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct) {
-      const bf16x4 lo = lds_read_tr(sBig + tr_off + ct * 16), hi = lds_read_tr(sBig + tr_off + 4 * GP + ct * 16);
-      b[ct] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      for (int ct = 0; ct < 4; ++ct) {
+        const bf16x4 lo = lds_read_tr(sBig + tr_off + ct * 16), hi = lds_read_tr(sBig + tr_off + 4 * GP + ct * 16);
+        b[ct] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+#pragma unroll
+      for (int jt = 0; jt < NJM; ++jt)
+        if (jt < NJ)
+#pragma unroll
+          for (int ct = 0; ct < 4; ++ct) acc[jt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[jt], b[ct], acc[jt][ct], 0, 0, 0);
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
     }
-#pragma unroll
-    for (int jt = 0; jt < NJM; ++jt)
-      if (jt < NJ)
-#pragma unroll
-        for (int ct = 0; ct < 4; ++ct) acc[jt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[jt], b[ct], acc[jt][ct], 0, 0, 0);
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
   }
   // acc[jt][ct][v] = part[j = jt*16 + 4g + v][c = cw0 + ct*16 + l16]
   float* dst = p.part[z] + (size_t)blockIdx.x * p.slot[z];
@@ -856,9 +903,10 @@ __global__ __launch_bounds__(256) void k_reduce(const int32_t* __restrict__ dtab
 }
 
 void launch_grad(const CallCtx& c, const char* name, const GradParams& p, dim3 grid) {
-  if (c.st->r_max <= 16) MUX_LAUNCH(name, (k_grad<1>), grid, dim3(256), 0, c.stream, p);
-  else if (c.st->r_max <= 32) MUX_LAUNCH(name, (k_grad<2>), grid, dim3(256), 0, c.stream, p);
-  else MUX_LAUNCH(name, (k_grad<4>), grid, dim3(256), 0, c.stream, p);
+  // two steps of loads in flight where the registers still allow four waves a SIMD
+  if (c.st->r_max <= 16) MUX_LAUNCH(name, (k_grad<1, 2>), grid, dim3(256), 0, c.stream, p);
+  else if (c.st->r_max <= 32) MUX_LAUNCH(name, (k_grad<2, 2>), grid, dim3(256), 0, c.stream, p);
+  else MUX_LAUNCH(name, (k_grad<4, 1>), grid, dim3(256), 0, c.stream, p);
 }
 
 // Row groups of 1024 mean 1/4 of the partial bytes of groups of 256; they are taken when the launch still has
@@ -907,12 +955,14 @@ mux_status adapter_dy_pass(const CallCtx& c, const void* dY, const void* Hs, voi
   float* gpart = (float*)part;
   float* part0 = (float*)((char*)part + pl.gpart);
   const int ts = s4_group(c.st, c.N), slabs = s4_slabs(c.N);
-  S4Params p{c.dtab, (const bf16_t*)dY, (const bf16_t*)Hs, gpart, part0, c.N, c.RP, ts, c.st->T};
+  S4Params p{c.dtab, (const bf16_t*)dY, (const bf16_t*)Hs, gpart, part0, c.N, c.RP, ts, c.st->T,
+             c.st->dev_image[DH_NITEMS0 + 3 * ts + 1], c.st->dev_image[DH_OFF_ROWBITS]};
   p.tasks = *c.tref;
   const dim3 grid((unsigned)c.st->items[ts].size(), (unsigned)slabs);
-  if (c.st->r_max <= 16) MUX_LAUNCH("s4_dy_pass", (k_s4<1>), grid, dim3(512), 0, c.stream, p);
-  else if (c.st->r_max <= 32) MUX_LAUNCH("s4_dy_pass", (k_s4<2>), grid, dim3(512), 0, c.stream, p);
-  else MUX_LAUNCH("s4_dy_pass", (k_s4<4>), grid, dim3(512), 0, c.stream, p);
+  // (rank pieces, steps between two meetings of the waves, steps of loads in flight)
+  if (c.st->r_max <= 16) MUX_LAUNCH("s4_dy_pass", (k_s4<1, 2, 2>), grid, dim3(512), 0, c.stream, p);
+  else if (c.st->r_max <= 32) MUX_LAUNCH("s4_dy_pass", (k_s4<2, 2, 1>), grid, dim3(512), 0, c.stream, p);
+  else MUX_LAUNCH("s4_dy_pass", (k_s4<4, 1, 1>), grid, dim3(512), 0, c.stream, p);
   // moved: the partials of every slab once in, Gs once out
   prof_note_bytes((double)slabs * c.st->T * c.RP * 4 + (double)c.st->T * c.RP * 2);
   MUX_LAUNCH("gs_reduce", k_gs_reduce, dim3((unsigned)c.st->items[TS64].size()), dim3(256), 0, c.stream, c.dtab, *c.tref,
@@ -953,7 +1003,8 @@ mux_status adapter_grads(const CallCtx& c, const void* X, const void* dY, const 
     float* part0 = (float*)((char*)part + pl.gpart);
     float* part1 = (float*)((char*)part + pl.gpart + pl.part0);
     GradParams p{c.dtab, {(const bf16_t*)Hs, (const bf16_t*)Gs}, {(const bf16_t*)dY, (const bf16_t*)X}, {part0, part1},
-                 {c.N, c.K}, c.RP, ts_a, (const bf16_t*)Z, {(size_t)c.RP * c.N, (size_t)c.RP * K1}, 1};
+                 {c.N, c.K}, c.RP, ts_a, (const bf16_t*)Z, {(size_t)c.RP * c.N, (size_t)c.RP * K1}, 1,
+                 c.st->dev_image[DH_NITEMS0 + 3 * ts_a + 1], c.st->dev_image[DH_OFF_ROWBITS], c.st->T};
     p.tasks = *c.tref;
     launch_grad(c, "grad_da", p, dim3((unsigned)c.st->items[ts_a].size(), (K1 + 255) / 256, 1));
     const size_t elems = (size_t)c.st->r_max * ((size_t)c.N + K1);
