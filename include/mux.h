@@ -140,6 +140,13 @@ typedef struct mux_sparse_mask {
   const int32_t* col_ent;  /* device, 2*nnz */
 } mux_sparse_mask;
 
+/* Lays out both listings of a mask on the host from its entries (k[e], n[e]), e = 0 .. nnz-1, which must be sorted
+ * by (k, n) without duplicates and lie inside W[K,N]: row_ptr [K+1], col_idx [nnz], col_ptr [N+1], col_ent [2 nnz], all
+ * host arrays of the caller, who copies them to the device and points a mux_sparse_mask at the copies.  Index work
+ * only; nothing is launched. */
+mux_status mux_sparse_mask_layout(const int32_t* k, const int32_t* n, int32_t nnz, int32_t K, int32_t N,
+                                  int32_t* row_ptr, int32_t* col_idx, int32_t* col_ptr, int32_t* col_ent);
+
 /* One multiplexed layer call.  All pointers inside are device pointers, except the three
  * arrays A, B, L themselves, which are host arrays of n_tasks device pointers (entry NULL
  * where the task's kind does not use it).  Ranks, scales and kinds come from the table. */

@@ -19,7 +19,7 @@ __all__ = [
     "library_path", "load_library", "mux_choose_chunk_size", "mux_segtab_build", "mux_segtab_free",
     "mux_segtab_rows", "mux_segtab_n_chunks", "mux_segtab_n_tasks", "mux_segtab_valid_tokens",
     "mux_segtab_serialized_bytes", "mux_segtab_serialize", "mux_segtab_row_task", "mux_segtab_device_bytes",
-    "mux_segtab_upload", "mux_lora_saved_bytes", "mux_lora_workspace_bytes", "mux_lora_forward",
+    "mux_segtab_upload", "mux_sparse_mask_layout", "mux_lora_saved_bytes", "mux_lora_workspace_bytes", "mux_lora_forward",
     "mux_lora_backward", "mux_lora_backward_static_ws", "MUX_STATIC_WS_BYTES", "mux_last_error", "mux_version", "mux_profile_enable", "mux_profile_collect",
     "CostModel", "mux_plan_stage_latency", "mux_plan_htask_latency", "mux_plan_fusion",
     "mux_dispatch_gather", "mux_dispatch_scatter",
@@ -160,6 +160,8 @@ def load_library() -> ctypes.CDLL:
         "mux_segtab_row_task": (c_int, [vp, POINTER(c_int32), c_size_t]),
         "mux_segtab_device_bytes": (c_size_t, [vp]),
         "mux_segtab_upload": (c_int, [vp, vp, c_size_t, vp]),
+        "mux_sparse_mask_layout": (c_int, [POINTER(c_int32), POINTER(c_int32), c_int32, c_int32, c_int32, POINTER(c_int32),
+                                           POINTER(c_int32), POINTER(c_int32), POINTER(c_int32)]),
         "mux_lora_saved_bytes": (c_size_t, [POINTER(_LayerDescC), vp]),
         "mux_lora_workspace_bytes": (c_size_t, [POINTER(_LayerDescC), vp]),
         "mux_lora_forward": (c_int, [POINTER(_LayerDescC), vp, vp, vp, vp, vp, vp, c_size_t, vp]),
@@ -244,29 +246,35 @@ class SegTab:
             _lib.mux_segtab_free(h)
 
 
+def mux_sparse_mask_layout(k, n, K: int, N: int):
+    """The two listings of a mask as host arrays (row_ptr [K+1], col_idx [nnz], col_ptr [N+1], col_ent [2 nnz]), laid
+    out by the library from the entries (k[e], n[e]) sorted by (k, n)."""
+    k = np.ascontiguousarray(k, dtype=np.int32)
+    n = np.ascontiguousarray(n, dtype=np.int32)
+    if k.shape != n.shape or k.ndim != 1:
+        raise ValueError("k and n must be one-dimensional arrays of the same length")
+    nnz = int(k.size)
+    row_ptr = np.zeros(K + 1, dtype=np.int32)
+    col_ptr = np.zeros(N + 1, dtype=np.int32)
+    col_idx = np.zeros(max(nnz, 1), dtype=np.int32)
+    col_ent = np.zeros(max(2 * nnz, 2), dtype=np.int32)
+    ip = lambda a: a.ctypes.data_as(POINTER(c_int32))
+    _check(load_library().mux_sparse_mask_layout(ip(k), ip(n), nnz, int(K), int(N), ip(row_ptr), ip(col_idx),
+                                                 ip(col_ptr), ip(col_ent)))
+    return row_ptr, col_idx, col_ptr, col_ent
+
+
 class SparseMask:
-    """Mirror of mux_sparse_mask.  Built from the masked entries (k[nnz], n[nnz]) sorted by (k, n): the row-major
-    listing (row_ptr, col_idx) and the column-by-column listing (col_ptr, col_ent) are laid out on the host (index
-    bookkeeping only) and handed to `to_device`, a callable that turns an int32 numpy array into an object with a
-    device pointer (for instance lambda a: torch.from_numpy(a).cuda())."""
+    """Mirror of mux_sparse_mask.  Built from the masked entries (k[nnz], n[nnz]) sorted by (k, n): the library lays the
+    row-major listing (row_ptr, col_idx) and the column-by-column listing (col_ptr, col_ent) out on the host
+    (mux_sparse_mask_layout); `to_device` is a callable that turns an int32 numpy array into an object with a device
+    pointer (for instance lambda a: torch.from_numpy(a).cuda())."""
 
     def __init__(self, k, n, K: int, N: int, to_device):
-        import numpy as np
-        k = np.ascontiguousarray(k, dtype=np.int64); n = np.ascontiguousarray(n, dtype=np.int64)
-        assert k.shape == n.shape and k.ndim == 1
-        flat = k * N + n
-        assert np.all(np.diff(flat) > 0), "mask entries must be sorted by (k, n) without duplicates"
-        assert k.size == 0 or (k.min() >= 0 and k.max() < K and n.min() >= 0 and n.max() < N)
-        nnz = int(k.size)
-        row_ptr = np.zeros(K + 1, dtype=np.int32); row_ptr[1:] = np.cumsum(np.bincount(k, minlength=K))
-        col_ptr = np.zeros(N + 1, dtype=np.int32); col_ptr[1:] = np.cumsum(np.bincount(n, minlength=N))
-        order = np.lexsort((k, n))                       # by column, then row: positions in the row-major numbering
-        col_ent = np.empty(2 * nnz, dtype=np.int32)
-        col_ent[0::2] = k[order]; col_ent[1::2] = order
-        self.nnz = nnz
-        self._bufs = [to_device(row_ptr), to_device(n.astype(np.int32)), to_device(col_ptr),
-                      to_device(col_ent if nnz else np.zeros(2, dtype=np.int32))]
-        self.c = _SparseMaskC(nnz=nnz, row_ptr=_ptr(self._bufs[0]), col_idx=_ptr(self._bufs[1]),
+        row_ptr, col_idx, col_ptr, col_ent = mux_sparse_mask_layout(k, n, K, N)
+        self.nnz = int(np.asarray(k).size)
+        self._bufs = [to_device(row_ptr), to_device(col_idx), to_device(col_ptr), to_device(col_ent)]
+        self.c = _SparseMaskC(nnz=self.nnz, row_ptr=_ptr(self._bufs[0]), col_idx=_ptr(self._bufs[1]),
                               col_ptr=_ptr(self._bufs[2]), col_ent=_ptr(self._bufs[3]))
 
 

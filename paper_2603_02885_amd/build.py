@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB_PATH = os.path.join(HERE, "libmuxlora.so")
-SOURCES = ["mux_segtab.cpp", "mux_api.hip", "mux_ref_kernels.hip", "mux_fast_kernels.hip", "mux_gemm_mfma.hip", "mux_profile.cpp", "mux_adapter_mfma.hip", "mux_gemm_dma.hip", "mux_diff_kernels.hip", "mux_planner.cpp", "mux_attn.hip", "mux_dispatch.hip", "mux_probe.hip"]
+SOURCES = ["mux_segtab.cpp", "mux_api.hip", "mux_ref_kernels.hip", "mux_fast_kernels.hip", "mux_gemm_mfma.hip", "mux_profile.cpp", "mux_adapter_mfma.hip", "mux_gemm_dma.hip", "mux_diff_kernels.hip", "mux_planner.cpp", "mux_attn.hip", "mux_dispatch.hip", "mux_probe.hip", "mux_mask.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -1,7 +1,9 @@
 """Full-size GPU parity: the benchmark workloads at their real shapes, in the launch configuration
-bench.py times, compared with the fp64 oracle on sampled output columns (all rows x 48 seeded
-columns of Y and of dX; Hs/Gs enter through them; every task's dA_t, dB_t, d delta_t in full, dl_t on
-the sampled columns).  Likewise the attention step on the benchmark sequences with all heads, three heads compared."""
+bench.py times, compared with the fp64 oracle on sampled output columns: all rows x one seeded column out of every
+128-column piece of Y and of dX (the last, ragged piece included) plus the first and last column of the first and of
+the last piece, so that every 256 x 256 tile, half tile and quarter tile of a launch holds compared elements;
+Hs/Gs enter through them; every task's dA_t, dB_t, d delta_t in full, dl_t on the sampled columns.
+Likewise the attention step on the benchmark sequences with all heads, three heads compared."""
 import numpy as np
 import pytest
 
@@ -10,7 +12,18 @@ from tests import mux_harness as hz
 
 pytestmark = pytest.mark.gpu
 
-CASES = [(1, 0), (1, 4), (1, 6), (2, 0), (2, 6), (3, 0), (3, 4), (3, 6), (4, 0), (4, 3), (4, 4), (4, 6),
+
+def stratified_columns(rng, n, piece=128):
+    """One column of every `piece`-wide piece of 0..n-1, and the edges of the first and of the last piece."""
+    cols = set()
+    for c0 in range(0, n, piece):
+        cols.add(int(rng.integers(c0, min(c0 + piece, n))))
+    last0 = ((n - 1) // piece) * piece
+    cols.update({0, min(piece, n) - 1, last0, n - 1})
+    return np.array(sorted(cols), dtype=np.int32)
+
+
+CASES = [(1, 0), (1, 4), (1, 6), (2, 0), (2, 4), (2, 6), (3, 0), (3, 4), (3, 6), (4, 0), (4, 3), (4, 4), (4, 6),
          (5, 0),     # 5: the extra workload with two Adapter-Tuning tasks (their rows need x W in full: one projection)
          (6, 0), (6, 6),   # 6: the extra workload with two Diff-Pruning tasks (d delta_t in full)
          (9, 0), (9, 4), (9, 5)]   # 9: Table 2's mix A (eight small tasks) on GPT3-2.7B shapes
@@ -35,8 +48,10 @@ def test_benchmark_config_layer(env, cfg, layer):
     ot = segtab.build([t.seq_lens for t in wl.tasks], wl.chunk)
     lt = wlm.layer_tensors(wl, layer, ot.T, seed=cfg, pad_rows=ot.row_task < 0, pad_fill=1e30)
     rng = np.random.default_rng(1000 * cfg + layer)
-    cols = np.sort(rng.choice(N, size=48, replace=False)).astype(np.int32)
-    kcols = np.sort(rng.choice(K, size=48, replace=False)).astype(np.int32)
+    # the selective kind's oracle walks the whole mask for every sampled column: wider pieces there
+    piece = 512 if any(t.kind == wlm.KIND_DIFF for t in wl.tasks) else 128
+    cols = stratified_columns(rng, N, piece)
+    kcols = stratified_columns(rng, K, piece)
     g = hz.GpuLayer(mx, torch, wl, lt, mx.MUX_DT_BF16)
     assert np.array_equal(mx.mux_segtab_serialize(g.st), ot.image)
     g.forward()

@@ -114,3 +114,34 @@ def test_empty_table(mx):
     assert mx.mux_segtab_rows(st) == 0
     o = segtab.build([[]], 64)
     assert mx.mux_segtab_serialize(st).tobytes() == o.image.tobytes()
+
+
+def test_sparse_mask_layout_against_a_direct_listing(mx):
+    """mux_sparse_mask_layout against both listings written down directly from the entries (pure Python), on random
+    masks with empty rows and columns; unsorted, duplicated and out-of-range entries are refused."""
+    import ctypes
+    rng = np.random.default_rng(5)
+
+    class Keep:
+        def __init__(self, a):
+            self.a = a
+
+        def data_ptr(self):
+            return self.a.ctypes.data
+
+    for K, N, dens in ((7, 5, 0.4), (33, 64, 0.05), (16, 9, 0.0), (5, 300, 0.3)):
+        flat = np.flatnonzero(rng.random(K * N) < dens)
+        k, n = (flat // N).astype(np.int32), (flat % N).astype(np.int32)
+        held = []
+        m = mx.SparseMask(k, n, K, N, lambda a: held.append(Keep(a.copy())) or held[-1])
+        row_ptr, col_idx, col_ptr, col_ent = (h.a for h in held)
+        assert m.nnz == flat.size
+        by_row = [[int(n[e]) for e in range(flat.size) if k[e] == r] for r in range(K)]
+        assert list(row_ptr) == [sum(len(x) for x in by_row[:r]) for r in range(K + 1)]
+        assert list(col_idx[:flat.size]) == [c for x in by_row for c in x]
+        by_col = [[(int(k[e]), e) for e in range(flat.size) if n[e] == c] for c in range(N)]
+        assert list(col_ptr) == [sum(len(x) for x in by_col[:c]) for c in range(N + 1)]
+        assert list(col_ent[:2 * flat.size]) == [v for x in by_col for pair in x for v in pair]
+    for k, n in (([1, 0], [0, 0]), ([0, 0], [2, 2]), ([0], [9]), ([-1], [0])):
+        with pytest.raises(mx.MuxError):
+            mx.SparseMask(np.array(k), np.array(n), 4, 4, lambda a: Keep(a))
