@@ -403,7 +403,22 @@ __global__ __launch_bounds__(512) void k_s4(const S4Params p) {
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       {
-        bf16x8 a[NJM], b[4], ay[2][2];
+        // the slab's share of dY B_t^T first, one 16-row half at a time (its operands are dead before the next are read)
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+          bf16x8 ay[2];
+#pragma unroll
+          for (int ks = 0; ks < 2; ++ks) ay[ks] = *(const bf16x8*)(sBig + (rt * 16 + l16) * GP + ks * 32 + 8 * g);
+#pragma unroll
+          for (int jt = 0; jt < NJM; ++jt) {
+            f32x4 v = (f32x4){0.f, 0.f, 0.f, 0.f};
+            if (jt < NJ)
+#pragma unroll
+              for (int ks = 0; ks < 2; ++ks) v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ay[ks], bt[jt][ks], v, 0, 0, 0);
+            accg[u % BATCH][rt][jt] = v;
+          }
+        }
+        bf16x8 a[NJM];
 #pragma unroll
         for (int jt = 0; jt < NJM; ++jt) {
           const bf16x4 lo = lds_read_tr(sSm + tr_off + jt * 16), hi = lds_read_tr(sSm + tr_off + 4 * GP + jt * 16);
@@ -412,27 +427,11 @@ __global__ __launch_bounds__(512) void k_s4(const S4Params p) {
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct) {
           const bf16x4 lo = lds_read_tr(sBig + tr_off + ct * 16), hi = lds_read_tr(sBig + tr_off + 4 * GP + ct * 16);
-          b[ct] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          const bf16x8 b = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+          for (int jt = 0; jt < NJM; ++jt)
+            if (jt < NJ) accb[jt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[jt], b, accb[jt][ct], 0, 0, 0);
         }
-#pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-          for (int ks = 0; ks < 2; ++ks) ay[rt][ks] = *(const bf16x8*)(sBig + (rt * 16 + l16) * GP + ks * 32 + 8 * g);
-#pragma unroll
-        for (int jt = 0; jt < NJM; ++jt)
-          if (jt < NJ)
-#pragma unroll
-            for (int ct = 0; ct < 4; ++ct) accb[jt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[jt], b[ct], accb[jt][ct], 0, 0, 0);
-#pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-          for (int jt = 0; jt < NJM; ++jt) {
-            f32x4 v = (f32x4){0.f, 0.f, 0.f, 0.f};
-            if (jt < NJ)
-#pragma unroll
-              for (int ks = 0; ks < 2; ++ks) v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ay[rt][ks], bt[jt][ks], v, 0, 0, 0);
-            accg[u % BATCH][rt][jt] = v;
-          }
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       __builtin_amdgcn_wave_barrier();
