@@ -8,7 +8,10 @@
  *                              the shapes the pipelined kernel takes;
  *   MUX_GEMM_BK32              the pipelined kernel uses 32-deep stages everywhere;
  *   MUX_GEMM_NO_HALF_TILES     it keeps the tiles of the last round whole;
- *   MUX_GEMM_NO_QUARTER_TILES  it splits them into halves where it would take quarters.
+ *   MUX_GEMM_NO_QUARTER_TILES  it splits them into halves where it would take quarters;
+ *   MUX_GEMM_FUSE_DOWN=0       the forward never forms Hs = s_t X A_t inside the backbone tile loop (by default it
+ *                              does in launches of quarter tiles, LoRA ranks up to 32 that are multiples of 8, no
+ *                              Adapter-Tuning task); =2: in launches of half tiles as well.
  */
 #ifndef MUX_DIAG_H_
 #define MUX_DIAG_H_

@@ -24,9 +24,13 @@ bool fast_supported(const CallCtx& c, const void* p0, const void* p1, const void
 
 // The caller has checked fast_supported for the shapes and pointers of this call.
 mux_status fast_forward(const CallCtx& c, const void* X, void* Y, void* H, void* Z, void*) {
-  if (mux_status s = adapter_down_x(c, X, H)) return s;
+  // small launches form Hs = s_t X A_t inside the backbone tile loop; the others stream X once more for it
+  const bool pipelined = gemm_dma_supported(c, false) && !regstaged();
+  const bool fuse_down = pipelined && gemm_dma_fuses_down(c);
+  if (!fuse_down)
+    if (mux_status s = adapter_down_x(c, X, H)) return s;
   mux_status s;
-  if (gemm_dma_supported(c, false) && !regstaged()) s = gemm_dma_forward(c, X, H, Y, Z);
+  if (pipelined) s = gemm_dma_forward(c, X, H, Y, Z, fuse_down);
   else s = gemm_mfma_forward(c, X, H, Y, Z);
   if (s != MUX_OK) return s;
   // Adapter-Tuning rows: the GEMM saved x W; the bottleneck follows (u = z D_t, Y = z + s_t gelu(u) U_t)

@@ -50,6 +50,7 @@ struct GemmParams {
   const bf16_t* Ext;   // [T, RP]  Hs or Gs
   bf16_t* Out;         // [T, Nc]
   bf16_t* Zsave;       // forward: x W of IA3_OUT rows (may be null)
+  bf16_t* HsOut;       // forward with the down-projection in the tile loop: Hs [T, RP] is written here (else null)
   int Kc, Nc, RP;
   int n_m, n_n, per_xcd;   // tile grid in units of 256 x TILE_N tiles; workgroups per XCD over the whole grid
   int n_full;              // workgroups that compute full tiles (a multiple of 8); the rest compute pieces of tiles
@@ -99,6 +100,7 @@ __device__ __forceinline__ int swz_row(int r) {
 struct Smem {
   bf16_t *a0, *a1, *a2, *a3, *b0, *b1, *b2, *b3;
   int* row;
+  bf16_t *e0, *e1, *e2, *e3;     // FUSE: stages of the [64][rank] slabs of A_t
 };
 
 // One output tile.  WNW = waves along N, MI x NI = 32x32 MFMA tiles per wave; 2*WNW waves on a
@@ -110,9 +112,16 @@ struct Smem {
 // BK = 64 with two stages, or BK = 32 with four.
 // `xcd_slot` = (per-XCD tile slot) * 8 + XCD; `half` selects the 128 columns of a half-width tile, `mhalf` the
 // 128 rows of a quarter.
-template <bool NT, int WNW, int MI, int NI, int BK>
+// FUSE (forward, 64-deep stages, half and quarter tiles): the down-projection Hs = s_t X A_t of the tile's rows is
+// computed in the same K loop -- the [64][rank] slab of A_t of every K-tile is staged beside the tile of W, wave
+// (wm, wn) multiplies it with the X fragment of its row block wn (one more MFMA per step) -- and goes, scaled and
+// rounded to bf16, straight into the A side of the adapter K-tile (and, from the tiles of the first column, to
+// memory for the backward): no separate pass over X, no launch for it.  Every column tile redoes the product for
+// its rows, which is why this is for launches that do not fill the compute units anyway.
+template <bool NT, int WNW, int MI, int NI, int BK, bool FUSE = false>
 __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slot, const int half, const int mhalf,
                                           const Smem sm) {
+  static_assert(!FUSE || (!NT && BK == 64 && WNW == MI && !(MI == 4 && NI == 2)), "FUSE: forward, 64-deep, half or quarter tiles");
   constexpr int BN = WNW * NI * 32;
   constexpr int BMT = 2 * MI * 32;
   static_assert(BN == 256 || BN == 128, "tile width");
@@ -130,7 +139,10 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   // Giving wave w all the loads uses its slack and leaves wave w + NW/2 a pure MFMA / LDS-read stream.
   constexpr int LW = NW == 8 ? NW / 2 : NW;       // four waves: one per SIMD, all of them load
   constexpr int ACH = (A_ELEMS / 512) / LW, BCH = (BN * BK / 512) / LW;   // 1 KB chunks a loading wave fetches per K-tile
+  constexpr int ECH = FUSE ? 1 : 0;               // FUSE: and one of the (up to) 4 KB of the slab of A_t
+  constexpr int NLD = ACH + BCH + ECH;            // loads a loading wave issues per K-tile
   static_assert(ACH >= 1 && BCH >= 1, "every loading wave fetches at least one chunk of each tile");
+  static_assert(!FUSE || LW == 4, "FUSE: four loading waves bring the four chunks of a slab");
   constexpr int LPR = BK / 8;                     // [rows][BK] tiles: lanes (16-byte pieces) per row
   constexpr int RPC = 64 / LPR;                   //                   rows per 1 KB chunk
   constexpr int PPRB = BN / 8;                    // forward: 16-byte pieces per k-row of the [BK][BN] tile
@@ -139,6 +151,7 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   constexpr int EPW = WCOLS + 8;                  // epilogue staging pitch (elements)
   bf16_t* const sA0 = sm.a0; bf16_t* const sA1 = sm.a1; bf16_t* const sA2 = sm.a2; bf16_t* const sA3 = sm.a3;
   bf16_t* const sB0 = sm.b0; bf16_t* const sB1 = sm.b1; bf16_t* const sB2 = sm.b2; bf16_t* const sB3 = sm.b3;
+  bf16_t* const sE0 = sm.e0; bf16_t* const sE1 = sm.e1; bf16_t* const sE2 = sm.e2; bf16_t* const sE3 = sm.e3;
   int* const sRow = sm.row;
 
   const int total = p.n_m * p.n_n;
@@ -168,11 +181,18 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
 
   if (tid < BMT) sRow[tid] = (it.task >= 0 && tid < nrows && row_is_valid(p.dtab, row0 + tid)) ? 1 : 0;
 
+  // FUSE: the tiles of the first column also write Hs of their rows; zeros where no LoRA product is formed
+  auto zero_hs_rows = [&]() {
+    if (FUSE && c0 == 0 && p.HsOut != nullptr)
+      for (int e = tid; e < nrows * (p.RP / 8); e += NTHR)
+        *(uint4*)(p.HsOut + (size_t)(row0 + e / (p.RP / 8)) * p.RP + (e % (p.RP / 8)) * 8) = make_uint4(0, 0, 0, 0);
+  };
   if (it.task < 0 || it.nvalid == 0) {             // rows of no task, or padding only: zeros out
     for (int e = tid; e < nrows * (BN / 8); e += NTHR) {
       const int m = e / (BN / 8), c = c0 + (e % (BN / 8)) * 8;
       if (c < p.Nc) *(uint4*)(p.Out + (size_t)(row0 + m) * p.Nc + c) = make_uint4(0, 0, 0, 0);
     }
+    zero_hs_rows();
     return;
   }
 
@@ -187,6 +207,8 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   const int KT = p.Kc / BK;                         // the contraction length is a multiple of BK
   const int KT_ext = lora ? (rank + BK - 1) / BK : 0;
   const int KT_total = KT + KT_ext;
+  const bool fuse_h = FUSE && lora;                 // this tile forms Hs of its rows in the K loop
+  if (FUSE && !lora) zero_hs_rows();
 
   // ---- DMA geometry.  A wave instruction fills 1 KB: RPC rows x 2 BK bytes of a [rows][BK] tile
   // (lane -> row lane/LPR, physical piece lane%LPR), or RPCB k-rows of the forward's [BK][BN] tile of W
@@ -199,6 +221,13 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   const rsrc_t rW = make_rsrc(p.W, (uint32_t)((size_t)(NT ? p.Nc : p.Kc) * p.ldw * 2));
   const rsrc_t rE = make_rsrc(lora ? p.Ext + (size_t)row0 * p.RP : p.Ain, lora ? (uint32_t)nrows * (uint32_t)p.RP * 2u : 0u);
   const rsrc_t rP = make_rsrc(lora ? adapterB : p.Ain, lora ? (uint32_t)(NT ? (size_t)p.Nc * rank : (size_t)rank * p.Nc) * 2u : 0u);
+
+  // FUSE: A_t [K][rank] as it is; the slab of K-tile kt is the 128 rank bytes from byte kt * 128 rank on, loading wave
+  // w brings its w-th KB (lane l the 16 bytes at 1024 w + 16 l), so the slab lies in LDS as in memory, [64][rank]
+  const rsrc_t rAt = make_rsrc(fuse_h ? tk.A : (const void*)p.Ain, fuse_h ? (uint32_t)p.Kc * (uint32_t)rank * 2u : 0u);
+  const uint32_t offE = (fuse_h && (uint32_t)(lw * 1024 + lane * 16) < 128u * (uint32_t)rank) ? (uint32_t)(lw * 1024 + lane * 16) : OOB;
+  uint32_t kE = 0;
+  const uint32_t stepE = 128u * (uint32_t)rank;
 
   // row of the [rows][BK] tile chunk q of this wave puts this lane on, and the logical k-piece it fetches there
   auto a_row_of = [&](int q) { return lw * (RPC * ACH) + RPC * q + r_in; };
@@ -235,15 +264,21 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   // uniform, rarely taken: everything that changes at a tile-kind boundary
   auto prepare = [&]() {
     if (next_tile >= KT) {
+      if (FUSE) kE = OOB;                                     // no slab of A_t past the backbone tiles
       if (next_tile >= KT_total) {
         kA = OOB; kB = OOB;
       } else {
         const int j0 = (next_tile - KT) * BK;                 // first contraction index of this adapter tile
-        curA = rE; curB = rP; kA = 0; kB = 0; stepA = 0; stepB = 0;
+        curB = rP; kB = 0; stepA = 0; stepB = 0;
+        if (FUSE) {
+          kA = OOB;                                           // the A side of the adapter tile comes from the accumulators
+        } else {
+          curA = rE; kA = 0;
 #pragma unroll
-        for (int q = 0; q < ACH; ++q) {
-          const int j = j0 + piece_of(a_row_of(q)) * 8;
-          offA[q] = (j < p.RP) ? ((uint32_t)a_row_of(q) * (uint32_t)p.RP + (uint32_t)j) * 2u : OOB;
+          for (int q = 0; q < ACH; ++q) {
+            const int j = j0 + piece_of(a_row_of(q)) * 8;
+            offA[q] = (j < p.RP) ? ((uint32_t)a_row_of(q) * (uint32_t)p.RP + (uint32_t)j) * 2u : OOB;
+          }
         }
 #pragma unroll
         for (int q = 0; q < BCH; ++q) {
@@ -261,16 +296,17 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
       }
     }
   };
-  // one load of the tile being fetched: i = 0 .. ACH+BCH-1, the A pieces first
-  auto issue_one = [&](bf16_t* dA, bf16_t* dB, int i) {
+  // one load of the tile being fetched: i = 0 .. NLD-1, the A pieces first, then W, then (FUSE) the slab of A_t
+  auto issue_one = [&](bf16_t* dA, bf16_t* dB, bf16_t* dE, int i) {
     if (!loader) return;
     if (i < ACH) dma16(curA, dA + (lw * ACH + i) * 512, offA[i] + kA);
-    else dma16(curB, dB + (lw * BCH + (i - ACH)) * 512, offB[i - ACH] + kB);
+    else if (i < ACH + BCH) dma16(curB, dB + (lw * BCH + (i - ACH)) * 512, offB[i - ACH] + kB);
+    else dma16(rAt, dE + lw * 512, (offE == OOB || kE == OOB) ? OOB : offE + kE);
   };
-  auto issue_done = [&]() { kA += stepA; kB += stepB; ++next_tile; };
-  auto issue = [&](bf16_t* dA, bf16_t* dB) {
+  auto issue_done = [&]() { kA += stepA; kB += stepB; if (FUSE && kE != OOB) kE += stepE; ++next_tile; };
+  auto issue = [&](bf16_t* dA, bf16_t* dB, bf16_t* dE) {
 #pragma unroll
-    for (int i = 0; i < ACH + BCH; ++i) issue_one(dA, dB, i);
+    for (int i = 0; i < NLD; ++i) issue_one(dA, dB, dE, i);
     issue_done();
   };
 
@@ -335,7 +371,7 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
       mma_one(a, b, 2 * i);
       mma_one(a, b, 2 * i + 1);
 #pragma unroll
-      for (int d = (i * (ACH + BCH)) / PAIRS; d < ((i + 1) * (ACH + BCH)) / PAIRS; ++d) issue_one(dA, dB, d);
+      for (int d = (i * (ACH + BCH)) / PAIRS; d < ((i + 1) * (ACH + BCH)) / PAIRS; ++d) issue_one(dA, dB, nullptr, d);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -360,13 +396,42 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
       }
     }
   };
+  // FUSE: the accumulator of this wave's 32 x 32 block of X A_t (row block wn of the wave's rows, transposed like acc),
+  // the fragment of the slab of A_t for step ks (lane (li, lg): column li of the slab, 8 consecutive k), and the X
+  // fragment of row block wn.
+  f32x16 hacc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) hacc[v] = 0.f;
+  auto read_e = [&](const bf16_t* cE, int ks) -> bf16x8 {
+    const int krow = ks * 16 + 8 * lg + kq;
+    const bf16x4 lo = lds_read_tr(cE + krow * rank + lhalf * 16 + bn_col);
+    const bf16x4 hi = lds_read_tr(cE + (krow + 4) * rank + lhalf * 16 + bn_col);
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  };
+  // the product of this step's slab fragment with the X fragment of row block wn, picked by selects on the (uniform)
+  // wn: an index would send the fragments through scratch memory, and a branch per row block makes the compiler copy
+  // the accumulator behind each MFMA
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  auto mma_h = [&](const bf16x8& e, const bf16x8 (&a)[MI]) {
+    u32x4 x = __builtin_bit_cast(u32x4, a[0]);
+#pragma unroll
+    for (int t = 1; t < MI; ++t) {
+      const u32x4 y = __builtin_bit_cast(u32x4, a[t]);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) x[c] = wn == t ? y[c] : x[c];
+    }
+    hacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(e, __builtin_bit_cast(bf16x8, x), hacc, 0, 0, 0);
+  };
   // One MFMA step from (a, b) with the operand reads of step ks_next of (cA, cB) into (an, bn) issued one per
-  // MFMA in its shadow (skipped when rd is false), and, when LOADS, the loads of one tile into (dA, dB) spread
-  // over the MFMAs after them.
+  // MFMA in its shadow (skipped when rd is false), and, when LOADS, the loads of one tile into (dA, dB, dE) spread
+  // over the MFMAs after them.  FUSE: one more product, e with the X fragment of row block wn, and the read of the
+  // next step's fragment en of the slab cE.
   auto fused_step = [&](const bf16x8 (&a)[MI], const bf16x8 (&b)[NI], const bf16_t* cA, const bf16_t* cB, int ks_next,
-                        bf16x8 (&an)[MI], bf16x8 (&bn)[NI], bool rd, auto LOADS, bf16_t* dA, bf16_t* dB) {
+                        bf16x8 (&an)[MI], bf16x8 (&bn)[NI], bool rd, auto LOADS, bf16_t* dA, bf16_t* dB,
+                        const bf16x8& e, bf16x8& en, const bf16_t* cE, bf16_t* dE) {
     constexpr bool loads = decltype(LOADS)::value;
-    constexpr int NM = MI * NI, NR = MI + NI, NL = ACH + BCH;
+    constexpr int NM = MI * NI, NR = MI + NI, NL = NLD;
+    if (FUSE && fuse_h) en = read_e(cE, ks_next);
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
       mma_one(a, b, m);
@@ -379,8 +444,12 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
       }
       if (loads) {
 #pragma unroll
-        for (int d = (m * NL) / NM; d < ((m + 1) * NL) / NM; ++d) issue_one(dA, dB, d);
+        for (int d = (m * NL) / NM; d < ((m + 1) * NL) / NM; ++d) issue_one(dA, dB, dE, d);
       }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (FUSE && fuse_h) {
+      mma_h(e, a);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -394,6 +463,7 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
     if (SPLIT) return (s < 2 ? sB0 : sB1) + (s & 1) * (BN * BK);
     return s == 0 ? sB0 : (s == 1 ? sB1 : (s == 2 ? sB2 : sB3));
   };
+  auto stE = [&](int s) -> bf16_t* { return s == 0 ? sE0 : (s == 1 ? sE1 : (s == 2 ? sE2 : sE3)); };
   auto tile_barrier = [&]() {
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
@@ -403,36 +473,42 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   // ---- prologue: tiles 0 .. PRE-1 in flight; tile 0 landed and visible; its first operands in registers
   constexpr int PRE = BK == 64 ? NST : NST - 1;
 #pragma unroll
-  for (int s0 = 0; s0 < PRE; ++s0) { prepare(); issue(stA(s0), stB(s0)); }
-  wait_vmcnt<(PRE - 1) * (ACH + BCH)>();
+  for (int s0 = 0; s0 < PRE; ++s0) { prepare(); issue(stA(s0), stB(s0), stE(s0)); }
+  wait_vmcnt<(PRE - 1) * NLD>();
   wait_lgkm0();
   tile_barrier();
 
   bf16x8 a0[MI], b0[NI], a1[MI], b1[NI];
+  bf16x8 e0 = {}, e1 = {};
   read_ops(sA0, sB0, 0, a0, b0);
+  if (FUSE && fuse_h) e0 = read_e(sE0, 0);
+  // FUSE: the K loop ends with the backbone; the adapter tile (its B_t side is fetched like any tile) follows below
+  const int KT_loop = fuse_h ? KT : KT_total;
 
   if (BK == 64) {
     // Steps 0..2 run from registers read one step ahead; before the last step every wave has read all of this
     // stage and tile kt+1 has landed (the loads of the NST-2 tiles after it may stay in flight): barrier; then,
     // under the last step's MFMAs, the first operands of tile kt+1 are read and all loads of tile kt+NST are
     // issued into the stage just freed.
-    for (int kt2 = 0; kt2 < KT_total; kt2 += NST) {
+    for (int kt2 = 0; kt2 < KT_loop; kt2 += NST) {
 #pragma unroll
       for (int u = 0; u < NST; ++u) {
         const int kt = kt2 + u;
-        if (kt < KT_total) {
+        if (kt < KT_loop) {
           bf16_t* cA = stA(u);
           bf16_t* cB = stB(u);
+          bf16_t* cE = stE(u);
           prepare();
           __builtin_amdgcn_sched_barrier(0);
-          fused_step(a0, b0, cA, cB, 1, a1, b1, true, std::false_type{}, nullptr, nullptr);
-          fused_step(a1, b1, cA, cB, 2, a0, b0, true, std::false_type{}, nullptr, nullptr);
-          fused_step(a0, b0, cA, cB, 3, a1, b1, true, std::false_type{}, nullptr, nullptr);
-          wait_vmcnt<(NST - 2) * (ACH + BCH)>();
+          fused_step(a0, b0, cA, cB, 1, a1, b1, true, std::false_type{}, nullptr, nullptr, e0, e1, cE, nullptr);
+          fused_step(a1, b1, cA, cB, 2, a0, b0, true, std::false_type{}, nullptr, nullptr, e1, e0, cE, nullptr);
+          fused_step(a0, b0, cA, cB, 3, a1, b1, true, std::false_type{}, nullptr, nullptr, e0, e1, cE, nullptr);
+          wait_vmcnt<(NST - 2) * NLD>();
           wait_lgkm0();
           tile_barrier();
           __builtin_amdgcn_sched_barrier(0);
-          fused_step(a1, b1, stA((u + 1) % NST), stB((u + 1) % NST), 0, a0, b0, true, std::true_type{}, cA, cB);   // past the last tile: read, unused
+          fused_step(a1, b1, stA((u + 1) % NST), stB((u + 1) % NST), 0, a0, b0, true, std::true_type{}, cA, cB, e1, e0,
+                     stE((u + 1) % NST), cE);   // past the last tile: read, unused
           issue_done();
         }
       }
@@ -455,7 +531,7 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
           mma_with_loads(a0, b0, stA((u + NST - 1) % NST), stB((u + NST - 1) % NST));
           issue_done();
           // tile kt+1 must have landed (the two newer ones may stay in flight) and every read of this stage be done
-          wait_vmcnt<(NST - 2) * (ACH + BCH)>();
+          wait_vmcnt<(NST - 2) * NLD>();
           wait_lgkm0();
           tile_barrier();
           __builtin_amdgcn_sched_barrier(0);
@@ -473,6 +549,43 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
+
+  if (FUSE && fuse_h) {
+    // The adapter tile.  Its W-side operand (rows of B_t) was fetched like any K-tile into the stage after the last
+    // backbone tile's; its A side is Hs = s_t (X A_t) of the tile's rows, which the waves hold in hacc: this lane has
+    // row wn*32 + li of the wave's row half and columns 8 j + 4 lg .. + 3.  Scaled, masked beyond the rank, rounded to
+    // bf16, it goes into that stage in the layout the operand reads expect (pieces 4..7 of a row, contraction
+    // indices 32..63, are zero), and from the tiles of the first column to memory.
+    const int sK = KT % NST;
+    bf16_t* hA = stA(sK);
+    const bf16_t* hB = stB(sK);
+    const int row_l = wm * (32 * MI) + wn * 32 + li;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int col = 8 * j + 4 * lg;
+      float v[4];
+#pragma unroll
+      for (int c4 = 0; c4 < 4; ++c4) v[c4] = (col + c4 < rank) ? tk.scale * hacc[4 * j + c4] : 0.f;
+      uint2 pk;
+      pk.x = pack_bf16x2(v[0], v[1]);
+      pk.y = pack_bf16x2(v[2], v[3]);
+      *(uint2*)(hA + row_l * BK + ((j ^ swz) * 8) + 4 * lg) = pk;
+      if (c0 == 0 && p.HsOut != nullptr && row_l < nrows && col < p.RP)
+        *(uint2*)(p.HsOut + (size_t)(row0 + row_l) * p.RP + col) = pk;
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+      *(uint4*)(hA + row_l * BK + (((4 + 2 * lg + q) ^ swz) * 8)) = make_uint4(0, 0, 0, 0);
+    wait_lgkm0();
+    tile_barrier();
+    const int nks = (rank + 15) >> 4;               // steps that carry data (rank <= 32: one or two)
+    for (int ks = 0; ks < nks; ++ks) {
+      read_ops(hA, hB, ks, a0, b0);
+      mma(a0, b0);
+    }
+    wait_lgkm0();
+    tile_barrier();                                 // the stages are reused as staging below
+  }
 
   // ---- epilogue: aggregate, mask, store; 32 rows of the wave tile at a time through this wave's own array.
   constexpr int AREA = NI == 2 ? 2560 : 1280;     // elements of a staging area (5 KB or 2.5 KB)
@@ -541,7 +654,7 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
 // The workgroups after them compute the remaining tiles in pieces (tail_split = 2: two half-width tiles each;
 // 4: four 128 x 128 quarters each); all pieces of a tile run on the same XCD.  The dispatcher hands out workgroups
 // in index order, so the pieces start as the compute units finish their last full tile.
-template <bool NT, int BK>
+template <bool NT, int BK, bool FUSE>
 __global__ __launch_bounds__(512, 1) void k_gemm_dma(const GemmParams p) {
   constexpr int STAGE_ELEMS = BM * BK;            // 16 KB (BK = 32, four stages) or 32 KB (BK = 64, two) per operand
   __shared__ __attribute__((aligned(1024))) bf16_t sA0[STAGE_ELEMS];
@@ -552,19 +665,23 @@ __global__ __launch_bounds__(512, 1) void k_gemm_dma(const GemmParams p) {
   __shared__ __attribute__((aligned(1024))) bf16_t sB1[STAGE_ELEMS];
   __shared__ __attribute__((aligned(1024))) bf16_t sB2[BK == 32 ? STAGE_ELEMS : 8];
   __shared__ __attribute__((aligned(1024))) bf16_t sB3[BK == 32 ? STAGE_ELEMS : 8];
+  __shared__ __attribute__((aligned(1024))) bf16_t sE0[FUSE ? 2048 : 8];   // FUSE: [64][rank <= 32] slabs of A_t, 4 KB a stage
+  __shared__ __attribute__((aligned(1024))) bf16_t sE1[FUSE ? 2048 : 8];
+  __shared__ __attribute__((aligned(1024))) bf16_t sE2[FUSE ? 2048 : 8];
+  __shared__ __attribute__((aligned(1024))) bf16_t sE3[FUSE ? 2048 : 8];
   __shared__ int sRow[256];
-  const Smem sm = {sA0, sA1, sA2, sA3, sB0, sB1, sB2, sB3, sRow};
+  const Smem sm = {sA0, sA1, sA2, sA3, sB0, sB1, sB2, sB3, sRow, sE0, sE1, sE2, sE3};
   const int b = blockIdx.x;
   // the start stamps wait in the buffer itself (words 2, 3), so that nothing stays live across the tile
   if (p.clk != nullptr && b == 0 && threadIdx.x == 0) { p.clk[2] = clock64(); p.clk[3] = wall_clock64(); }
-  if (b < p.n_full) {
-    gemm_tile<NT, 4, 4, 2, BK>(p, b, 0, 0, sm);
+  if (!FUSE && b < p.n_full) {                    // a launch with the down-projection in the loop has pieces only
+    gemm_tile<NT, 4, 4, 2, BK, false>(p, b, 0, 0, sm);
   } else if (p.tail_split == 2) {
     const int t = b - p.n_full;                                       // n_full is a multiple of 8
-    gemm_tile<NT, 4, 4, 1, BK>(p, p.n_full + (((t >> 4) << 3) | (t & 7)), (t >> 3) & 1, 0, sm);
+    gemm_tile<NT, 4, 4, 1, BK, FUSE>(p, p.n_full + (((t >> 4) << 3) | (t & 7)), (t >> 3) & 1, 0, sm);
   } else {
     const int t = b - p.n_full;
-    gemm_tile<NT, 2, 2, 2, BK>(p, p.n_full + (((t >> 5) << 3) | (t & 7)), (t >> 3) & 1, (t >> 4) & 1, sm);
+    gemm_tile<NT, 2, 2, 2, BK, FUSE>(p, p.n_full + (((t >> 5) << 3) | (t & 7)), (t >> 3) & 1, (t >> 4) & 1, sm);
   }
   if (p.clk != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
     atomicAdd(p.clk, (unsigned long long)clock64() - p.clk[2]);
@@ -583,18 +700,14 @@ int compute_units() {
   return n;
 }
 
-template <bool NT>
-mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t* Out, bf16_t* Zsave, int Kc, int Nc) {
-  GemmParams p;
-  p.dtab = c.dtab; p.tasks = *c.tref; p.Ain = Ain; p.W = (const bf16_t*)c.W; p.ldw = c.ldw; p.Ext = Ext; p.Out = Out;
-  p.Zsave = Zsave; p.Kc = Kc; p.Nc = Nc; p.RP = c.RP;
-  p.n_m = (int)c.st->items[TS256].size();
-  p.n_n = (Nc + TILE_N - 1) / TILE_N;
-  p.AinScaled = (const bf16_t*)c.dYs;
-  p.clk = diag_clock_buffer();
-  const int total = p.n_m * p.n_n;
-  if (total == 0) return MUX_OK;
-  p.per_xcd = (total + 7) / 8;
+// The tile plan of a launch: whole tiles for the full rounds of workgroups, the rest as halves or quarters.
+struct TilePlan { int n_m, n_n, per_xcd, n_full, tail_split, grid; bool narrow; };
+TilePlan plan_tiles(const CallCtx& c, int Kc, int Nc) {
+  TilePlan t{};
+  t.n_m = (int)c.st->items[TS256].size();
+  t.n_n = (Nc + TILE_N - 1) / TILE_N;
+  const int total = t.n_m * t.n_n;
+  t.per_xcd = (total + 7) / 8;
   // One workgroup per compute unit at a time: the tiles left after the last full round would keep a fraction of
   // the units busy for a whole tile time.  When they fit four times, they run as quarters, when twice, as
   // half-width tiles.
@@ -605,14 +718,32 @@ mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t
   const int full_slots = (total / ncu) * (ncu / 8);          // per-XCD slots covered by whole rounds
   const int rem = total - full_slots * 8;
   int tail_slots = 0;
-  if (!no_halves && ncu % 8 == 0 && rem > 0 && 2 * rem <= ncu) tail_slots = p.per_xcd - full_slots;
-  p.tail_split = (!no_quarters && 4 * rem <= ncu) ? 4 : 2;
-  p.n_full = 8 * (p.per_xcd - tail_slots);
-  const int grid = p.n_full + 8 * p.tail_split * tail_slots;
-  if (Kc % 64 == 0 && !narrow) {
-    MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", (k_gemm_dma<NT, 64>), dim3(grid), dim3(512), 0, c.stream, p);
+  if (!no_halves && ncu % 8 == 0 && rem > 0 && 2 * rem <= ncu) tail_slots = t.per_xcd - full_slots;
+  t.tail_split = (!no_quarters && 4 * rem <= ncu) ? 4 : 2;
+  t.n_full = 8 * (t.per_xcd - tail_slots);
+  t.grid = t.n_full + 8 * t.tail_split * tail_slots;
+  t.narrow = narrow || Kc % 64 != 0;
+  return t;
+}
+
+template <bool NT>
+mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t* Out, bf16_t* Zsave, int Kc, int Nc,
+                  bool fuse_down) {
+  GemmParams p;
+  p.dtab = c.dtab; p.tasks = *c.tref; p.Ain = Ain; p.W = (const bf16_t*)c.W; p.ldw = c.ldw; p.Ext = Ext; p.Out = Out;
+  p.Zsave = Zsave; p.Kc = Kc; p.Nc = Nc; p.RP = c.RP;
+  p.HsOut = fuse_down ? (bf16_t*)Ext : nullptr;
+  const TilePlan t = plan_tiles(c, Kc, Nc);
+  p.n_m = t.n_m; p.n_n = t.n_n; p.per_xcd = t.per_xcd; p.n_full = t.n_full; p.tail_split = t.tail_split;
+  p.AinScaled = (const bf16_t*)c.dYs;
+  p.clk = diag_clock_buffer();
+  if (t.n_m * t.n_n == 0) return MUX_OK;
+  if (fuse_down && (NT || t.narrow || t.n_full != 0)) return fail(MUX_ERR_UNSUPPORTED, "gemm: this launch cannot carry the down-projection");
+  if (!t.narrow) {
+    if (!NT && fuse_down) MUX_LAUNCH("gemm_nn", (k_gemm_dma<false, 64, true>), dim3(t.grid), dim3(512), 0, c.stream, p);
+    else MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", (k_gemm_dma<NT, 64, false>), dim3(t.grid), dim3(512), 0, c.stream, p);
   } else {
-    MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", (k_gemm_dma<NT, 32>), dim3(grid), dim3(512), 0, c.stream, p);
+    MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", (k_gemm_dma<NT, 32, false>), dim3(t.grid), dim3(512), 0, c.stream, p);
   }
   return MUX_OK;
 }
@@ -630,12 +761,27 @@ bool gemm_dma_supported(const CallCtx& c, bool backward) {
   return true;
 }
 
-mux_status gemm_dma_forward(const CallCtx& c, const void* X, const void* Hs, void* Y, void* Z) {
-  return launch<false>(c, (const bf16_t*)X, (const bf16_t*)Hs, (bf16_t*)Y, (bf16_t*)Z, c.K, c.N);
+// Can the forward of this call form Hs = s_t X A_t inside the backbone tile loop?  The kernel can when the launch is
+// made of half or quarter tiles only, with 64-deep stages, LoRA ranks up to 32 that are multiples of 8 (A_t is read in
+// place) and no Adapter-Tuning task.  It is chosen for launches of quarter tiles (at most a quarter of the compute
+// units' worth of 256 x 256 tiles): there the loop waits on loads, the extra product per step costs about 0.13 us per
+// 64 of K, and the launch it saves costs 9 to 25 us; in launches of half tiles the extra product costs more than the
+// launch (measured 4 to 13 % slower).  MUX_GEMM_FUSE_DOWN (read once): 0 never, 2 in launches of half tiles as well.
+bool gemm_dma_fuses_down(const CallCtx& c) {
+  static const int mode = [] { const char* e = getenv("MUX_GEMM_FUSE_DOWN"); return e == nullptr ? 1 : atoi(e); }();
+  if (mode == 0 || !gemm_dma_supported(c, false)) return false;
+  if (c.st->n_lora == 0 || c.st->n_tuning > 0 || !c.lora_natural || c.st->r_max > 32) return false;
+  const TilePlan t = plan_tiles(c, c.K, c.N);
+  if (t.narrow || t.n_full != 0 || t.n_m * t.n_n == 0) return false;
+  return t.tail_split == 4 || mode == 2;
+}
+
+mux_status gemm_dma_forward(const CallCtx& c, const void* X, const void* Hs, void* Y, void* Z, bool fuse_down) {
+  return launch<false>(c, (const bf16_t*)X, (const bf16_t*)Hs, (bf16_t*)Y, (bf16_t*)Z, c.K, c.N, fuse_down);
 }
 
 mux_status gemm_dma_backward(const CallCtx& c, const void* dY, const void* Gs, void* dX) {
-  return launch<true>(c, (const bf16_t*)dY, (const bf16_t*)Gs, (bf16_t*)dX, nullptr, c.N, c.K);
+  return launch<true>(c, (const bf16_t*)dY, (const bf16_t*)Gs, (bf16_t*)dX, nullptr, c.N, c.K, false);
 }
 
 }  // namespace mux

@@ -169,7 +169,8 @@ mux_status gemm_mfma_forward(const CallCtx& c, const void* X, const void* Hs, vo
 mux_status gemm_mfma_backward(const CallCtx& c, const void* dY, const void* Gs, void* dX, int only_ia3);
 // pipelined variant (direct-to-LDS loads, 4 stages)
 bool gemm_dma_supported(const CallCtx& c, bool backward);
-mux_status gemm_dma_forward(const CallCtx& c, const void* X, const void* Hs, void* Y, void* Z);
+bool gemm_dma_fuses_down(const CallCtx& c);   // the forward launch would be half / quarter tiles only: Hs is formed in its K loop
+mux_status gemm_dma_forward(const CallCtx& c, const void* X, const void* Hs, void* Y, void* Z, bool fuse_down);
 mux_status gemm_dma_backward(const CallCtx& c, const void* dY, const void* Gs, void* dX);
 
 // matrix-core adapter kernels (bf16): down-projections and per-task gradient reductions

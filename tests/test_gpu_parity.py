@@ -370,6 +370,43 @@ def test_task_table_by_value_and_in_memory(env):
             assert torch.equal(a, b)
 
 
+def fuse_workload(K, N, toks):
+    tasks = [wlm.Task(wlm.KIND_LORA, 16, 2.0, [toks[0]]), wlm.Task(wlm.KIND_IA3, 0, 1.0, [70]),
+             wlm.Task(wlm.KIND_LORA, 32, 0.5, [toks[1], 21]), wlm.Task(wlm.KIND_NONE, 0, 1.0, [64]),
+             wlm.Task(wlm.KIND_LORA, 8, 1.5, [toks[2]]), wlm.Task(wlm.KIND_LORA, 24, 1.0, [toks[3]]),
+             wlm.Task(wlm.KIND_LORA, 16, 2.0, [])]
+    return wlm.Workload(name=f"fuse{N}", layers=[("w", K, N)], tasks=tasks, chunk=64, sigma_w=0.05, sigma_ab=0.05)
+
+
+FUSE_CASES = ((512, 384, (100, 300, 37, 150), True), (256, 2816, (700, 300, 200, 130), False),
+              (1024, 200, (33, 64, 5, 129), True))
+
+
+def check_fused_down(env, half_tiles_too):
+    """Parity of the FUSE_CASES and, from the kernel list of a forward, whether a separate down-projection ran."""
+    mx, torch = env
+    for K, N, toks, quarters in FUSE_CASES:
+        for seg_flags in (0, 1):
+            g, got, ref, errs = run_case(env, fuse_workload(K, N, toks), seed=K + seg_flags, seg_flags=seg_flags)
+            mx.mux_profile_enable(1)
+            mx.mux_profile_collect()
+            g.forward()
+            torch.cuda.synchronize()
+            names = [e["name"] for e in mx.mux_profile_collect()]
+            mx.mux_profile_enable(0)
+            assert "gemm_nn" in names, names
+            assert ("down_x" not in names) == (quarters or half_tiles_too), (K, N, names)
+
+
+def test_down_projection_in_the_tile_loop(env):
+    """Forward launches made of quarter tiles only form Hs = s_t X A_t inside the backbone tile loop (no down_x
+    launch): ranks 8, 16, 24 and 32 next to IA3 and plain tasks, ragged rows, a ragged last column tile; against the
+    oracle, forward and backward (which reads the Hs the tiles of the first column saved), and the kernel list shows
+    that no separate down-projection ran.  The launch of half tiles among the cases keeps the separate launch (the
+    variants test below runs it with the switch that fuses there too)."""
+    check_fused_down(env, False)
+
+
 def test_dy_pass_row_groups_and_column_slabs(env):
     """The pass over dY on shapes that give it several 512-column slabs (the last one ragged, one wave of it past the
     end), row groups of 1024 and of 256 rows with ragged tails, ranks that fill one, two and four 16-wide pieces, and
@@ -449,22 +486,28 @@ def test_graph_capture_and_replay(env, which):
         torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("var", ["MUX_GEMM_BK32", "MUX_GEMM_NO_HALF_TILES", "MUX_GEMM_NO_QUARTER_TILES", "MUX_GEMM_REGSTAGED"])
+@pytest.mark.parametrize("var", ["MUX_GEMM_BK32", "MUX_GEMM_NO_HALF_TILES", "MUX_GEMM_NO_QUARTER_TILES", "MUX_GEMM_REGSTAGED",
+                                 "MUX_GEMM_FUSE_DOWN=0", "MUX_GEMM_FUSE_DOWN=2"])
 def test_gemm_variants_in_a_fresh_process(env, var):
     """The switches that are read once per process (32-deep stages where 64-deep ones would be taken; full tiles
     only; half-width tiles where quarters would be taken for the last round; the register-staged kernel, which
-    otherwise only sees the shapes the pipelined kernel does not take, on shapes both can run): a parity case in a
-    child process with the switch set."""
+    otherwise only sees the shapes the pipelined kernel does not take, on shapes both can run; the down-projection
+    never inside the tile loop, or in launches of half tiles as well): a parity case in a child process with the
+    switch set."""
     import os
     import subprocess
     import sys
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     code = ("import torch, paper_2603_02885_amd as mx; mx.load_library(); import mux_workloads as wlm;"
-            "from tests.test_gpu_parity import run_case, mixed_workload, tuning_workload;"
+            "from tests.test_gpu_parity import run_case, mixed_workload, tuning_workload, check_fused_down;"
             "tasks = [wlm.Task(wlm.KIND_LORA, 16, 2.0, [700]), wlm.Task(wlm.KIND_IA3, 0, 1.0, [300]), wlm.Task(wlm.KIND_LORA, 40, 1.0, [900])];"
             "wl = wlm.Workload(name='v', layers=[('w', 512, 1280)], tasks=tasks, chunk=64, sigma_w=0.04, sigma_ab=0.05);"
-            "run_case((mx, torch), wl, seed=5); run_case((mx, torch), mixed_workload(K=320, N=256), seed=6); run_case((mx, torch), tuning_workload(K=192, N=160), seed=22); print('variant ok')")
+            "run_case((mx, torch), wl, seed=5); run_case((mx, torch), mixed_workload(K=320, N=256), seed=6); run_case((mx, torch), tuning_workload(K=192, N=160), seed=22);")
+    if var == "MUX_GEMM_FUSE_DOWN=2":
+        code += "check_fused_down((mx, torch), True);"
+    code += "print('variant ok')"
     envv = dict(os.environ)
-    envv[var] = "1"
+    name, _, value = var.partition("=")
+    envv[name] = value or "1"
     r = subprocess.run([sys.executable, "-c", code], cwd=root, env=envv, capture_output=True, text=True, timeout=110)
     assert r.returncode == 0 and "variant ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
