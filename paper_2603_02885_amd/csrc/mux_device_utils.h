@@ -67,6 +67,13 @@ __device__ __forceinline__ int get_task_kind(const TaskRef& r, int t) {
   return __builtin_amdgcn_readfirstlane(r.mem ? r.mem[t].kind : r.arg.t[t].kind);
 }
 
+// The weight the rows of a task meet in the backbone product: W, or for a Diff-Pruning task whose merged weight the call
+// has built, W + M_t * delta_t in the workspace.
+template <class T>
+__device__ __forceinline__ const T* task_weight(const DevTask& tk, const T* W, const T* Wdiff, int64_t stride) {
+  return (tk.kind == MUX_ADAPTER_DIFF && Wdiff != nullptr && tk.rank >= 0) ? Wdiff + (size_t)tk.rank * (size_t)stride : W;
+}
+
 struct ItemView { int task, row0, nrows, nvalid; };
 __device__ __forceinline__ ItemView load_item(const int32_t* __restrict__ dtab, int tile_size_index, int item) {
   const int32_t* p = dtab + dtab[DH_NITEMS0 + 3 * tile_size_index + 1] + item * DI_WORDS;

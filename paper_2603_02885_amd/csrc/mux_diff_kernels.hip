@@ -12,6 +12,8 @@
 //                   entries of that column (column listing of the mask forward, row listing backward)
 //   masked gradient a few lanes per entry, a plain loop over the task's blocks, two lines per block
 // No barriers, no atomics; every sum has one owner and a fixed order.
+#include <type_traits>
+
 #include "mux_device_utils.h"
 
 namespace mux {
@@ -187,6 +189,179 @@ __global__ __launch_bounds__(256) void k_diff_grad(const DevTask* __restrict__ t
   if (e_w < tk.at_off) tk.dA[e_w] = accumulate ? tk.dA[e_w] + mine : mine;
 }
 
+// The masked gradient by blocks of the mask (bf16).  A workgroup owns the entries of one GB x GB block of one task's mask
+// and walks the task's 64-row blocks: the GB lines of Xt and the GB lines of Gt of a row block (two contiguous
+// stretches of the transposed copies) are staged in LDS once and serve all entries of the mask block, so a line is
+// fetched once per mask block instead of once per entry; the loads of the next row block are in flight (in registers)
+// while the entries are summed.  The entries of the block come from the row listing: thread i looks up, by two binary
+// searches in row k0 + i, the stretch of its entries whose column lies in the block; a prefix sum over the rows numbers
+// them, and a thread holds G_EPT of them per pass (more entries: more passes over the row blocks).  Every entry has one
+// owner and a fixed order of summation (row blocks ascending, rows ascending).  grid = (mask blocks, tasks).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+constexpr int GB = 512;                 // edge of a mask block
+constexpr int GP = 72;                  // LDS pitch (elements) of a line of 64 rows: 144 bytes
+constexpr int G_EPT = 4;                // entries per thread and pass
+constexpr int G_THREADS = 512;
+constexpr int G_SMEM = 2 * GB * GP * 2 + (GB + 1) * 4 + GB * 4;
+__global__ __launch_bounds__(G_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_diff_grad_tiled(const DevTask* __restrict__ tasks, const bf16_t* __restrict__ Xt,
+                                                               const bf16_t* __restrict__ Gt, int K, int N, int accumulate) {
+  extern __shared__ __align__(16) unsigned char g_smem[];
+  bf16_t* Xs = (bf16_t*)g_smem;
+  bf16_t* Gs = Xs + GB * GP;
+  int* offs = (int*)(Gs + GB * GP);     // GB + 1: entries of the block before row i
+  int* start = offs + GB + 1;           // GB: index (in the row listing) of row i's first entry inside the block
+  const DevTask tk = tasks[blockIdx.y];
+  if (tk.kind != MUX_ADAPTER_DIFF || tk.dA == nullptr || tk.at_off == 0) return;
+  const int n_nb = (N + GB - 1) / GB;
+  const int k0 = (int)(blockIdx.x / n_nb) * GB, n0 = (int)(blockIdx.x % n_nb) * GB;
+  const int tid = threadIdx.x;
+  const int32_t* row_ptr = (const int32_t*)tk.B;
+  const int32_t* col_idx = (const int32_t*)tk.L;
+  int my_start = 0, my_cnt = 0;
+  if (k0 + tid < K) {
+    int a = row_ptr[k0 + tid], b = row_ptr[k0 + tid + 1];
+    const int hi = b;
+    while (a < b) { const int m = (a + b) >> 1; if (col_idx[m] < n0) a = m + 1; else b = m; }
+    my_start = a;
+    b = hi;
+    while (a < b) { const int m = (a + b) >> 1; if (col_idx[m] < n0 + GB) a = m + 1; else b = m; }
+    my_cnt = a - my_start;
+  }
+  start[tid] = my_start;
+  offs[tid + 1] = my_cnt;               // inclusive prefix sums in offs[1 .. GB]
+  if (tid == 0) offs[0] = 0;
+  __syncthreads();
+  for (int d = 1; d < GB; d <<= 1) {
+    const int v = tid >= d ? offs[tid + 1 - d] : 0;
+    __syncthreads();
+    offs[tid + 1] += v;
+    __syncthreads();
+  }
+  const int total = offs[GB];
+  if (total == 0) return;               // whole workgroup
+  const int lx = K - k0 < GB ? K - k0 : GB, lg = N - n0 < GB ? N - n0 : GB;   // lines of this block that exist
+  const int nbk = (tk.row_count + 63) >> 6;
+  const size_t b0 = (size_t)tk.zrow0 >> 6;
+  constexpr int PPT = GB * 8 / G_THREADS;            // 16-byte pieces per thread and operand
+  // piece q of this thread: index tid + q * G_THREADS of the stretch (a line that does not exist reads line 0 instead
+  // and is never staged)
+  int px[PPT], pg[PPT];
+#pragma unroll
+  for (int q = 0; q < PPT; ++q) {
+    const int p = tid + q * G_THREADS;
+    px[q] = p < lx * 8 ? p : -1;
+    pg[q] = p < lg * 8 ? p : -1;
+  }
+  for (int f0 = 0; f0 < total; f0 += G_THREADS * G_EPT) {
+    int kl[G_EPT], nl[G_EPT], ee[G_EPT];
+    float acc[G_EPT];
+#pragma unroll
+    for (int i = 0; i < G_EPT; ++i) {
+      const int f = f0 + i * G_THREADS + tid;
+      acc[i] = 0.f;
+      kl[i] = 0; nl[i] = 0; ee[i] = -1;
+      if (f < total) {
+        int lo = 0, hi = GB;                        // the row r with offs[r] <= f < offs[r + 1]
+        while (hi - lo > 1) { const int m = (lo + hi) >> 1; if (offs[m] <= f) lo = m; else hi = m; }
+        kl[i] = lo;
+        ee[i] = start[lo] + (f - offs[lo]);
+        nl[i] = col_idx[ee[i]] - n0;
+      }
+    }
+    u32x4 rx[PPT], rg[PPT];
+    {
+      const u32x4* xs = (const u32x4*)(Xt + (b0 * (size_t)K + k0) * 64);
+      const u32x4* gs = (const u32x4*)(Gt + (b0 * (size_t)N + n0) * 64);
+#pragma unroll
+      for (int q = 0; q < PPT; ++q) { rx[q] = xs[px[q] < 0 ? 0 : px[q]]; rg[q] = gs[pg[q] < 0 ? 0 : pg[q]]; }
+    }
+    for (int b = 0; b < nbk; ++b) {
+      __syncthreads();                               // every read of the previous row block is done
+#pragma unroll
+      for (int q = 0; q < PPT; ++q) {
+        if (px[q] >= 0) *(u32x4*)(Xs + (px[q] >> 3) * GP + (px[q] & 7) * 8) = rx[q];
+        if (pg[q] >= 0) *(u32x4*)(Gs + (pg[q] >> 3) * GP + (pg[q] & 7) * 8) = rg[q];
+      }
+      __syncthreads();
+      if (b + 1 < nbk) {                             // the next row block's lines, in flight while this one is summed
+        const u32x4* xs = (const u32x4*)(Xt + ((b0 + b + 1) * (size_t)K + k0) * 64);
+        const u32x4* gs = (const u32x4*)(Gt + ((b0 + b + 1) * (size_t)N + n0) * 64);
+#pragma unroll
+        for (int q = 0; q < PPT; ++q) { rx[q] = xs[px[q] < 0 ? 0 : px[q]]; rg[q] = gs[pg[q] < 0 ? 0 : pg[q]]; }
+      }
+#pragma unroll
+      for (int i = 0; i < G_EPT; ++i) {
+        if (ee[i] < 0) continue;
+        const u32x4* xl = (const u32x4*)(Xs + kl[i] * GP);
+        const u32x4* gl = (const u32x4*)(Gs + nl[i] * GP);
+        float a = acc[i];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const u32x4 xv = xl[j], gv = gl[j];
+#pragma unroll
+          for (int h = 0; h < 4; ++h) {
+            a = fmaf(__uint_as_float(xv[h] << 16), __uint_as_float(gv[h] << 16), a);
+            a = fmaf(__uint_as_float(xv[h] & 0xffff0000u), __uint_as_float(gv[h] & 0xffff0000u), a);
+          }
+        }
+        acc[i] = a;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < G_EPT; ++i)
+      if (ee[i] >= 0) tk.dA[ee[i]] = accumulate ? tk.dA[ee[i]] + acc[i] : acc[i];
+  }
+}
+
+// Merged weight of one Diff-Pruning task (bf16): Wm = W + M_t * delta_t, rounded once.  A workgroup copies MR rows of W
+// (16-byte pieces; N a multiple of 8, W and Wm 16-byte aligned with the same row pitch) and then, behind a workgroup
+// barrier, rewrites the masked entries of those rows -- the entries of consecutive rows are consecutive in the row
+// listing.  grid = (ceil(K / MR), tasks).  (Reading W once for all tasks in one workgroup was slower: fewer
+// workgroups, 82 against 61 us for two tasks.)
+constexpr int MR = 8;
+__global__ __launch_bounds__(256) void k_diff_merge(const DevTask* __restrict__ tasks, const bf16_t* __restrict__ W,
+                                                    bf16_t* __restrict__ Wm_all, int64_t stride, int K, int N, int64_t ldw) {
+  const DevTask tk = tasks[blockIdx.y];
+  if (tk.kind != MUX_ADAPTER_DIFF || tk.rank < 0) return;
+  bf16_t* Wm = Wm_all + (size_t)tk.rank * (size_t)stride;
+  const int k0 = blockIdx.x * MR;
+  const int rows = K - k0 < MR ? K - k0 : MR;
+  const int ppr = N / 8;                                  // 16-byte pieces per row
+  const int n_pieces = rows * ppr;
+  constexpr int UNR = 4;
+  for (int e0 = threadIdx.x; e0 < n_pieces; e0 += 256 * UNR) {
+    uint4 v[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int e = e0 + 256 * u;
+      if (e < n_pieces) v[u] = *(const uint4*)(W + (size_t)(k0 + e / ppr) * ldw + (e % ppr) * 8);
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int e = e0 + 256 * u;
+      if (e < n_pieces) *(uint4*)(Wm + (size_t)(k0 + e / ppr) * ldw + (e % ppr) * 8) = v[u];
+    }
+  }
+  __syncthreads();                                        // the copies of these rows are ordered before the entries' stores
+  const int32_t* row_ptr = (const int32_t*)tk.B;
+  const int32_t* col_idx = (const int32_t*)tk.L;
+  const bf16_t* val = (const bf16_t*)tk.A;
+  const int e_begin = row_ptr[k0], e_end = row_ptr[k0 + rows];
+  for (int e = e_begin + threadIdx.x; e < e_end; e += 256) {
+    int k = k0;
+    while (k + 1 < k0 + rows && row_ptr[k + 1] <= e) ++k;
+    const size_t o = (size_t)k * ldw + col_idx[e];
+    Store<bf16_t>::st(Wm, o, Store<bf16_t>::ld(W, o) + Store<bf16_t>::ld(val, (size_t)e));
+  }
+}
+
+constexpr int kTiledMinBlocks = 48;
+// the tiled kernel's LDS is above the default limit of a launch: raised once per process
+bool tiled_grad_ready() {
+  static const bool ok = hipFuncSetAttribute((const void*)k_diff_grad_tiled, hipFuncAttributeMaxDynamicSharedMemorySize, G_SMEM) == hipSuccess;
+  return ok;
+}
+
 template <class S>
 void transpose(const CallCtx& c, const void* In, void* Out, int C, const char* name) {
   const int n_items = (int)c.st->items[TS64].size();
@@ -201,6 +376,7 @@ void transpose(const CallCtx& c, const void* In, void* Out, int C, const char* n
 
 template <class S>
 void forward(const CallCtx& c, const void* X, void* Y) {
+  if (c.diffW) return;                       // the backbone product read W + M_t * delta_t for these rows
   const int n_items = (int)c.st->items[TS64].size();
   transpose<S>(c, X, c.diffT[0], c.K, "diff_xt");
   constexpr int CPW = 256 / Piece<S>::LPL;
@@ -212,10 +388,17 @@ template <class S>
 void backward(const CallCtx& c, const void* X, const void* dY, void* dX, int accumulate) {
   const int n_items = (int)c.st->items[TS64].size();
   transpose<S>(c, dY, c.diffT[1], c.N, "diff_gt");
-  if (dX)
+  if (dX && !c.diffW)                        // else the backbone product read W + M_t * delta_t for these rows
     MUX_LAUNCH("diff_bwd", k_diff_apply<S>, dim3((unsigned)n_items * (unsigned)((c.K + (256 / Piece<S>::LPL) - 1) / (256 / Piece<S>::LPL))), dim3(256), 0, c.stream, c.dtab, c.dtasks,
                (const S*)c.diffT[1], (S*)dX, c.N, c.K, 1);
   transpose<S>(c, X, c.diffT[0], c.K, "diff_xt");
+  // by blocks of the mask where there are enough of them to occupy the compute units (bf16), else by entries
+  const int blocks = ((c.K + GB - 1) / GB) * ((c.N + GB - 1) / GB);
+  if (std::is_same<S, bf16_t>::value && blocks * c.st->n_diff >= kTiledMinBlocks && tiled_grad_ready()) {
+    MUX_LAUNCH("diff_grad", k_diff_grad_tiled, dim3((unsigned)blocks, (unsigned)c.st->n_tasks), dim3(G_THREADS), G_SMEM, c.stream,
+               c.dtasks, (const bf16_t*)c.diffT[0], (const bf16_t*)c.diffT[1], c.K, c.N, accumulate);
+    return;
+  }
   MUX_LAUNCH("diff_grad", k_diff_grad<S>, dim3(c.st->n_tasks, (c.diff_max_nnz + 255) / 256), dim3(256), 0, c.stream,
              c.dtasks, (const S*)c.diffT[0], (const S*)c.diffT[1], c.K, c.N, accumulate);
 }
@@ -224,6 +407,17 @@ void backward(const CallCtx& c, const void* X, const void* dY, void* dX, int acc
 
 size_t diff_transposed_bytes(int K, int N, const mux_segtab* st, size_t esz) {
   return st->n_diff > 0 ? align256((size_t)st->d_rows * (size_t)(K > N ? K : N) * esz) : 0;
+}
+
+size_t diff_merged_bytes(int K, int64_t ldw) { return align256((size_t)K * (size_t)ldw * 2); }
+
+// The merged weights of the Diff-Pruning tasks that have entries, when the call has room for them (matrix-core path):
+// W in and one copy out per such task.
+void diff_merge(const CallCtx& c, int slots) {
+  if (!c.diffW || slots <= 0) return;
+  prof_note_bytes(4.0 * c.K * c.N * slots);
+  MUX_LAUNCH("diff_merge", k_diff_merge, dim3((unsigned)((c.K + MR - 1) / MR), (unsigned)c.st->n_tasks), dim3(256), 0, c.stream,
+             c.dtasks, (const bf16_t*)c.W, (bf16_t*)c.diffW, c.diffW_stride, c.K, c.N, c.ldw);
 }
 
 void diff_forward(const CallCtx& c, int dtype, const void* X, void* Y) {

@@ -29,6 +29,7 @@ mux_status fast_forward(const CallCtx& c, const void* X, void* Y, void* H, void*
   const bool fuse_down = pipelined && gemm_dma_fuses_down(c);
   if (!fuse_down)
     if (mux_status s = adapter_down_x(c, X, H)) return s;
+  diff_merge(c, c.diffW_slots);           // Diff-Pruning tasks: their rows meet W + M_t * delta_t in the backbone product
   mux_status s;
   if (pipelined) s = gemm_dma_forward(c, X, H, Y, Z, fuse_down);
   else s = gemm_mfma_forward(c, X, H, Y, Z);
@@ -49,6 +50,7 @@ mux_status fast_backward(const CallCtx& c, const void* X, const void* dY, const 
   if (mux_status s = adapter_tune_add(c, dY, G, c.dYs, 1)) return s;
   if (mux_status s = adapter_grads(c, X, dY, H, G, Z, part, accumulate)) return s;
   if (!dX) return MUX_OK;
+  diff_merge(c, c.diffW_slots);
   if (gemm_dma_supported(c, true) && !regstaged()) {
     // IA3_OUT rows read dY * l_t, written by the dl kernel above
     return gemm_dma_backward(c, dY, G, dX);

@@ -56,6 +56,8 @@ struct GemmParams {
   int n_full;              // workgroups that compute full tiles (a multiple of 8); the rest compute pieces of tiles
   int tail_split;          // pieces per tile after the full ones: 2 (halves) or 4 (quarters)
   unsigned long long* clk;  // diagnostic: counters workgroup 0 adds its elapsed cycles and 100 MHz ticks to (null: off)
+  const bf16_t* Wdiff;      // merged weights W + M_t * delta_t of the Diff-Pruning tasks, `wdiff_stride` elements apart (or null)
+  int64_t wdiff_stride;
   const bf16_t* AinScaled;  // backward: prepared input rows (IA3_OUT: dY * l_t; TUNING: dY + p D_t^T), [z_rows, Kc], indexed like the saved x W
   TaskRef tasks;
 };
@@ -218,7 +220,7 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   const bf16_t* a_base = (NT && (ia3 || tuning)) ? p.AinScaled + (size_t)(tk.zrow0 + row0 - tk.row_begin) * p.Kc
                                      : p.Ain + (size_t)row0 * p.Kc;
   const rsrc_t rA = make_rsrc(a_base, a_rows_bytes);
-  const rsrc_t rW = make_rsrc(p.W, (uint32_t)((size_t)(NT ? p.Nc : p.Kc) * p.ldw * 2));
+  const rsrc_t rW = make_rsrc(task_weight(tk, p.W, p.Wdiff, p.wdiff_stride), (uint32_t)((size_t)(NT ? p.Nc : p.Kc) * p.ldw * 2));
   const rsrc_t rE = make_rsrc(lora ? p.Ext + (size_t)row0 * p.RP : p.Ain, lora ? (uint32_t)nrows * (uint32_t)p.RP * 2u : 0u);
   const rsrc_t rP = make_rsrc(lora ? adapterB : p.Ain, lora ? (uint32_t)(NT ? (size_t)p.Nc * rank : (size_t)rank * p.Nc) * 2u : 0u);
 
@@ -736,6 +738,7 @@ mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t
   const TilePlan t = plan_tiles(c, Kc, Nc);
   p.n_m = t.n_m; p.n_n = t.n_n; p.per_xcd = t.per_xcd; p.n_full = t.n_full; p.tail_split = t.tail_split;
   p.AinScaled = (const bf16_t*)c.dYs;
+  p.Wdiff = (const bf16_t*)c.diffW; p.wdiff_stride = c.diffW_stride;
   p.clk = diag_clock_buffer();
   if (t.n_m * t.n_n == 0) return MUX_OK;
   if (fuse_down && (NT || t.narrow || t.n_full != 0)) return fail(MUX_ERR_UNSUPPORTED, "gemm: this launch cannot carry the down-projection");

@@ -43,6 +43,8 @@ struct GemmParams {
   int Kc, Nc, RP;
   int n_m, n_n, per_xcd;
   int only_ia3;        // process IA3_OUT items only (the pipelined kernel took the rest)
+  const bf16_t* Wdiff; // merged weights W + M_t * delta_t of the Diff-Pruning tasks, `wdiff_stride` elements apart (or null)
+  int64_t wdiff_stride;
   const bf16_t* Prep;  // backward: prepared input rows of the TUNING tasks (dY + p D_t^T), [z_rows, Kc], indexed like the saved x W
   TaskRef tasks;
 };
@@ -155,8 +157,9 @@ __global__ __launch_bounds__(256, 1) void k_gemm(const GemmParams p) {
   // buffer resources (byte offsets must stay below 2^31: checked on the host)
   const rsrc_t rA = make_rsrc((NT && tuning) ? p.Prep + (size_t)(tk.zrow0 + it.row0 - tk.row_begin) * p.Kc : p.Ain + (size_t)it.row0 * p.Kc,
                               (uint32_t)it.nrows * (uint32_t)p.Kc * 2u);
-  const rsrc_t rW = NT ? make_rsrc(p.W + (size_t)c0 * p.ldw, (uint32_t)((size_t)(p.Nc - c0 < BN ? p.Nc - c0 : BN) * p.ldw * 2))
-                       : make_rsrc(p.W + c0, (uint32_t)(((size_t)(p.Kc - 1) * p.ldw + (p.Nc - c0)) * 2));
+  const bf16_t* Wt = task_weight(tk, p.W, p.Wdiff, p.wdiff_stride);
+  const rsrc_t rW = NT ? make_rsrc(Wt + (size_t)c0 * p.ldw, (uint32_t)((size_t)(p.Nc - c0 < BN ? p.Nc - c0 : BN) * p.ldw * 2))
+                       : make_rsrc(Wt + c0, (uint32_t)(((size_t)(p.Kc - 1) * p.ldw + (p.Nc - c0)) * 2));
   const rsrc_t rE = make_rsrc(lora ? p.Ext + (size_t)it.row0 * p.RP : p.Ain, lora ? (uint32_t)it.nrows * (uint32_t)p.RP * 2u : 0u);
   const rsrc_t rP = NT ? make_rsrc(lora ? adapterB + (size_t)c0 * rank : p.Ain,
                                    lora ? (uint32_t)(p.Nc - c0 < BN ? p.Nc - c0 : BN) * (uint32_t)rank * 2u : 0u)
@@ -351,6 +354,7 @@ mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t
   GemmParams p;
   p.dtab = c.dtab; p.tasks = *c.tref; p.Ain = Ain; p.W = (const bf16_t*)c.W; p.ldw = c.ldw; p.Ext = Ext; p.Out = Out;
   p.Zsave = Zsave; p.Kc = Kc; p.Nc = Nc; p.RP = c.RP;
+  p.Wdiff = (const bf16_t*)c.diffW; p.wdiff_stride = c.diffW_stride;
   p.n_m = (int)c.st->items[TS256].size();
   p.n_n = (Nc + BN - 1) / BN;
   const int total = p.n_m * p.n_n;

@@ -52,7 +52,8 @@ struct DevTask {
                       // block-transposed copies (DIFF, a multiple of 64), else -1
   int64_t at_off;     // element offset of this task's transposed A_t inside the workspace region
                       // DIFF tasks: A = values, dA = their gradient, B = row_ptr, L = col_idx, dB = col_ptr, dL = col_ent
-                      // (all int32 arrays), at_off = number of masked entries
+                      // (all int32 arrays), at_off = number of masked entries; rank = index of the task's merged
+                      // weight W + M_t * delta_t in the workspace when the call builds them, else -1
 };
 static_assert(sizeof(DevTask) == 80, "DevTask layout");
 
@@ -136,6 +137,10 @@ struct CallCtx {
   bool lora_natural;       // every LoRA rank is a multiple of 8: the down-projection reads A_t [K, r] as it is
   int diff_max_nnz;        // largest mask of the DIFF tasks of this call
   void* diffT[2];          // workspace: block-transposed copies of the DIFF rows of X ([0]) and of dY ([1])
+  void* diffW;             // workspace: per DIFF task with entries, W + M_t * delta_t [K][ldw] bf16 (matrix-core path;
+                           // null: the sparse updates run after the backbone products instead)
+  int64_t diffW_stride;    // elements between the merged weights of two tasks
+  int diffW_slots;         // how many tasks have one
 };
 
 // H / G row pitch in elements
@@ -160,6 +165,8 @@ void ref_steps(const CallCtx& c, int dtype, unsigned which, const void* X, const
 
 // Diff-Pruning tasks, both storage types: the masked sparse update after the backbone GEMM, and the masked gradient
 size_t diff_transposed_bytes(int K, int N, const mux_segtab* st, size_t esz);
+size_t diff_merged_bytes(int K, int64_t ldw);      // one task's merged weight, bf16
+void diff_merge(const CallCtx& c, int slots);                                                                        // W + M_t * delta_t per task
 void diff_forward(const CallCtx& c, int dtype, const void* X, void* Y);                                       // Y += x (M_t * delta_t)
 void diff_backward(const CallCtx& c, int dtype, const void* X, const void* dY, void* dX, int accumulate);     // dX, d delta_t
 

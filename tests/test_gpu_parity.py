@@ -205,6 +205,37 @@ def test_diff_pruning_kind(env, mode, seg_flags):
     run_case(env, diff_workload(K=104, N=328, chunk=16, density=0.05), dtype=dtype, seg_flags=seg_flags, layer_flags=lf, seed=8)
 
 
+def test_diff_pruning_merged_weight_or_sparse_updates(env):
+    """The matrix-core path serves Diff-Pruning rows in one of two ways, by cost: the backbone products read a merged
+    weight W + M_t * delta_t built for the call (many rows, dense masks), or sparse updates follow the products (few
+    rows, thin masks).  Both against the oracle, forward and backward, and the kernel list shows which one ran."""
+    mx, torch = env
+    for density, merged in ((0.02, True), (0.002, False)):
+        for seg_flags in (0, 1):
+            g, got, ref, errs = run_case(env, diff_workload(K=256, N=384, density=density), seed=9, seg_flags=seg_flags)
+            mx.mux_profile_enable(1)
+            mx.mux_profile_collect()
+            g.forward(); g.backward()
+            torch.cuda.synchronize()
+            names = [e["name"] for e in mx.mux_profile_collect()]
+            mx.mux_profile_enable(0)
+            assert ("diff_merge" in names) == merged and ("diff_fwd" in names) == (not merged), (density, names)
+            assert ("diff_bwd" in names) == (not merged) and "diff_grad" in names, (density, names)
+
+
+def test_diff_pruning_gradient_by_mask_blocks(env):
+    """On shapes with enough 512 x 512 blocks of the mask the masked gradient is summed block by block (the lines of
+    a row block staged once per mask block): ragged last blocks in both directions, blocks with more entries than one
+    pass holds, a task with an empty mask and one without rows, with and without accumulation."""
+    mx, torch = env
+    g, got, ref, errs = run_case(env, diff_workload(K=2112, N=1600, chunk=64, density=0.01), seed=11)
+    first = [None if t is None else t.clone() for t in g.dA]
+    g.backward(accumulate=1)
+    torch.cuda.synchronize()
+    for a, b in zip(first, g.dA):
+        assert a is None or torch.allclose(b, 2 * a, rtol=1e-6, atol=0)
+
+
 @pytest.mark.parametrize("which", ["mixed", "tuning", "diff"])
 def test_accumulate_and_determinism(env, which):
     mx, torch = env
