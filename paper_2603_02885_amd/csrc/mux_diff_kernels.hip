@@ -200,10 +200,10 @@ __global__ __launch_bounds__(256) void k_diff_grad(const DevTask* __restrict__ t
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int GB = 512;                 // edge of a mask block
 constexpr int GP = 72;                  // LDS pitch (elements) of a line of 64 rows: 144 bytes
-constexpr int G_EPT = 4;                // entries per thread and pass
-constexpr int G_THREADS = 512;
+constexpr int G_EPT = 2;                // entries per thread and pass
+constexpr int G_THREADS = 1024;
 constexpr int G_SMEM = 2 * GB * GP * 2 + (GB + 1) * 4 + GB * 4;
-__global__ __launch_bounds__(G_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_diff_grad_tiled(const DevTask* __restrict__ tasks, const bf16_t* __restrict__ Xt,
+__global__ __launch_bounds__(G_THREADS) void k_diff_grad_tiled(const DevTask* __restrict__ tasks, const bf16_t* __restrict__ Xt,
                                                                const bf16_t* __restrict__ Gt, int K, int N, int accumulate) {
   extern __shared__ __align__(16) unsigned char g_smem[];
   bf16_t* Xs = (bf16_t*)g_smem;
@@ -212,29 +212,36 @@ __global__ __launch_bounds__(G_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)
   int* start = offs + GB + 1;           // GB: index (in the row listing) of row i's first entry inside the block
   const DevTask tk = tasks[blockIdx.y];
   if (tk.kind != MUX_ADAPTER_DIFF || tk.dA == nullptr || tk.at_off == 0) return;
-  const int n_nb = (N + GB - 1) / GB;
-  const int k0 = (int)(blockIdx.x / n_nb) * GB, n0 = (int)(blockIdx.x % n_nb) * GB;
+  // Workgroups go to the eight XCDs round-robin: XCD x takes a contiguous stretch of the blocks in row-major order, so
+  // that the blocks running on it at one time share their lines of Xt in its L2.
+  const int n_nb = (N + GB - 1) / GB, n_blocks = ((K + GB - 1) / GB) * n_nb;
+  const int per_xcd = (n_blocks + 7) / 8;
+  const int block = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+  if ((int)(blockIdx.x >> 3) >= per_xcd || block >= n_blocks) return;
+  const int k0 = (block / n_nb) * GB, n0 = (block % n_nb) * GB;
   const int tid = threadIdx.x;
   const int32_t* row_ptr = (const int32_t*)tk.B;
   const int32_t* col_idx = (const int32_t*)tk.L;
-  int my_start = 0, my_cnt = 0;
-  if (k0 + tid < K) {
-    int a = row_ptr[k0 + tid], b = row_ptr[k0 + tid + 1];
-    const int hi = b;
-    while (a < b) { const int m = (a + b) >> 1; if (col_idx[m] < n0) a = m + 1; else b = m; }
-    my_start = a;
-    b = hi;
-    while (a < b) { const int m = (a + b) >> 1; if (col_idx[m] < n0 + GB) a = m + 1; else b = m; }
-    my_cnt = a - my_start;
+  if (tid < GB) {
+    int my_start = 0, my_cnt = 0;
+    if (k0 + tid < K) {
+      int a = row_ptr[k0 + tid], b = row_ptr[k0 + tid + 1];
+      const int hi = b;
+      while (a < b) { const int m = (a + b) >> 1; if (col_idx[m] < n0) a = m + 1; else b = m; }
+      my_start = a;
+      b = hi;
+      while (a < b) { const int m = (a + b) >> 1; if (col_idx[m] < n0 + GB) a = m + 1; else b = m; }
+      my_cnt = a - my_start;
+    }
+    start[tid] = my_start;
+    offs[tid + 1] = my_cnt;             // inclusive prefix sums in offs[1 .. GB]
+    if (tid == 0) offs[0] = 0;
   }
-  start[tid] = my_start;
-  offs[tid + 1] = my_cnt;               // inclusive prefix sums in offs[1 .. GB]
-  if (tid == 0) offs[0] = 0;
   __syncthreads();
   for (int d = 1; d < GB; d <<= 1) {
-    const int v = tid >= d ? offs[tid + 1 - d] : 0;
+    const int v = (tid < GB && tid >= d) ? offs[tid + 1 - d] : 0;
     __syncthreads();
-    offs[tid + 1] += v;
+    if (tid < GB) offs[tid + 1] += v;
     __syncthreads();
   }
   const int total = offs[GB];
@@ -245,13 +252,7 @@ __global__ __launch_bounds__(G_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)
   constexpr int PPT = GB * 8 / G_THREADS;            // 16-byte pieces per thread and operand
   // piece q of this thread: index tid + q * G_THREADS of the stretch (a line that does not exist reads line 0 instead
   // and is never staged)
-  int px[PPT], pg[PPT];
-#pragma unroll
-  for (int q = 0; q < PPT; ++q) {
-    const int p = tid + q * G_THREADS;
-    px[q] = p < lx * 8 ? p : -1;
-    pg[q] = p < lg * 8 ? p : -1;
-  }
+  const int lx8 = lx * 8, lg8 = lg * 8;
   for (int f0 = 0; f0 < total; f0 += G_THREADS * G_EPT) {
     int kl[G_EPT], nl[G_EPT], ee[G_EPT];
     float acc[G_EPT];
@@ -268,45 +269,51 @@ __global__ __launch_bounds__(G_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)
         nl[i] = col_idx[ee[i]] - n0;
       }
     }
-    u32x4 rx[PPT], rg[PPT];
-    {
-      const u32x4* xs = (const u32x4*)(Xt + (b0 * (size_t)K + k0) * 64);
-      const u32x4* gs = (const u32x4*)(Gt + (b0 * (size_t)N + n0) * 64);
-#pragma unroll
-      for (int q = 0; q < PPT; ++q) { rx[q] = xs[px[q] < 0 ? 0 : px[q]]; rg[q] = gs[pg[q] < 0 ? 0 : pg[q]]; }
+    // two sets of staging registers: the lines of row blocks b + 1 and b + 2 are in flight while block b is summed
+    u32x4 rx0[PPT], rg0[PPT], rx1[PPT], rg1[PPT];
+#define DIFF_FETCH(RX, RG, B)                                                                  \
+    if ((B) < nbk) {                                                                             \
+      const u32x4* xs_ = (const u32x4*)(Xt + ((b0 + (B)) * (size_t)K + k0) * 64);                \
+      const u32x4* gs_ = (const u32x4*)(Gt + ((b0 + (B)) * (size_t)N + n0) * 64);                \
+      _Pragma("unroll") for (int q = 0; q < PPT; ++q) {                                          \
+        const int p_ = tid + q * G_THREADS;                                                      \
+        RX[q] = xs_[p_ < lx8 ? p_ : 0];                                                          \
+        RG[q] = gs_[p_ < lg8 ? p_ : 0];                                                          \
+      }                                                                                          \
     }
-    for (int b = 0; b < nbk; ++b) {
-      __syncthreads();                               // every read of the previous row block is done
-#pragma unroll
-      for (int q = 0; q < PPT; ++q) {
-        if (px[q] >= 0) *(u32x4*)(Xs + (px[q] >> 3) * GP + (px[q] & 7) * 8) = rx[q];
-        if (pg[q] >= 0) *(u32x4*)(Gs + (pg[q] >> 3) * GP + (pg[q] & 7) * 8) = rg[q];
-      }
-      __syncthreads();
-      if (b + 1 < nbk) {                             // the next row block's lines, in flight while this one is summed
-        const u32x4* xs = (const u32x4*)(Xt + ((b0 + b + 1) * (size_t)K + k0) * 64);
-        const u32x4* gs = (const u32x4*)(Gt + ((b0 + b + 1) * (size_t)N + n0) * 64);
-#pragma unroll
-        for (int q = 0; q < PPT; ++q) { rx[q] = xs[px[q] < 0 ? 0 : px[q]]; rg[q] = gs[pg[q] < 0 ? 0 : pg[q]]; }
-      }
-#pragma unroll
-      for (int i = 0; i < G_EPT; ++i) {
-        if (ee[i] < 0) continue;
-        const u32x4* xl = (const u32x4*)(Xs + kl[i] * GP);
-        const u32x4* gl = (const u32x4*)(Gs + nl[i] * GP);
-        float a = acc[i];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const u32x4 xv = xl[j], gv = gl[j];
-#pragma unroll
-          for (int h = 0; h < 4; ++h) {
-            a = fmaf(__uint_as_float(xv[h] << 16), __uint_as_float(gv[h] << 16), a);
-            a = fmaf(__uint_as_float(xv[h] & 0xffff0000u), __uint_as_float(gv[h] & 0xffff0000u), a);
-          }
-        }
-        acc[i] = a;
-      }
+#define DIFF_STEP(RX, RG, B)                                                                   \
+    {                                                                                            \
+      __syncthreads(); /* every read of the previous row block is done */                        \
+      _Pragma("unroll") for (int q = 0; q < PPT; ++q) {                                          \
+        const int p_ = tid + q * G_THREADS;                                                      \
+        if (p_ < lx8) *(u32x4*)(Xs + (p_ >> 3) * GP + (p_ & 7) * 8) = RX[q];                     \
+        if (p_ < lg8) *(u32x4*)(Gs + (p_ >> 3) * GP + (p_ & 7) * 8) = RG[q];                     \
+      }                                                                                          \
+      __syncthreads();                                                                           \
+      DIFF_FETCH(RX, RG, (B) + 2)                                                                \
+      _Pragma("unroll") for (int i = 0; i < G_EPT; ++i) {                                        \
+        if (ee[i] < 0) continue;                                                                 \
+        const u32x4* xl = (const u32x4*)(Xs + kl[i] * GP);                                       \
+        const u32x4* gl = (const u32x4*)(Gs + nl[i] * GP);                                       \
+        float a = acc[i];                                                                        \
+        _Pragma("unroll 2") for (int j = 0; j < 8; ++j) {                                        \
+          const u32x4 xv = xl[j], gv = gl[j];                                                    \
+          _Pragma("unroll") for (int h = 0; h < 4; ++h) {                                        \
+            a = fmaf(__uint_as_float(xv[h] << 16), __uint_as_float(gv[h] << 16), a);             \
+            a = fmaf(__uint_as_float(xv[h] & 0xffff0000u), __uint_as_float(gv[h] & 0xffff0000u), a); \
+          }                                                                                      \
+        }                                                                                        \
+        acc[i] = a;                                                                              \
+      }                                                                                          \
     }
+    DIFF_FETCH(rx0, rg0, 0)
+    DIFF_FETCH(rx1, rg1, 1)
+    for (int b = 0; b < nbk; b += 2) {
+      DIFF_STEP(rx0, rg0, b)
+      if (b + 1 < nbk) DIFF_STEP(rx1, rg1, b + 1)
+    }
+#undef DIFF_FETCH
+#undef DIFF_STEP
 #pragma unroll
     for (int i = 0; i < G_EPT; ++i)
       if (ee[i] >= 0) tk.dA[ee[i]] = accumulate ? tk.dA[ee[i]] + acc[i] : acc[i];
@@ -395,7 +402,7 @@ void backward(const CallCtx& c, const void* X, const void* dY, void* dX, int acc
   // by blocks of the mask where there are enough of them to occupy the compute units (bf16), else by entries
   const int blocks = ((c.K + GB - 1) / GB) * ((c.N + GB - 1) / GB);
   if (std::is_same<S, bf16_t>::value && blocks * c.st->n_diff >= kTiledMinBlocks && tiled_grad_ready()) {
-    MUX_LAUNCH("diff_grad", k_diff_grad_tiled, dim3((unsigned)blocks, (unsigned)c.st->n_tasks), dim3(G_THREADS), G_SMEM, c.stream,
+    MUX_LAUNCH("diff_grad", k_diff_grad_tiled, dim3((unsigned)(8 * ((blocks + 7) / 8)), (unsigned)c.st->n_tasks), dim3(G_THREADS), G_SMEM, c.stream,
                c.dtasks, (const bf16_t*)c.diffT[0], (const bf16_t*)c.diffT[1], c.K, c.N, accumulate);
     return;
   }
