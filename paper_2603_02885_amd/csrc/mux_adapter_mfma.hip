@@ -777,41 +777,47 @@ __global__ __launch_bounds__(256) void k_tune_add(const TuneAddParams p) {
 
 // ------------------------------------------------------------------------------------------------
 // IA3_OUT: part[item][n] = sum_{rows} g[i][n] * z[i][n], and dYs[i][n] = g[i][n] * l_t[n] (the operand of the
-// backbone backward for these rows).  grid = (64-row items, ceil(N/1024)); 8 columns per thread, 8 rows in flight.
-__global__ __launch_bounds__(128) void k_dl(const int32_t* __restrict__ dtab, const TaskRef tasks,
+// backbone backward for these rows).  grid = (64-row items, ceil(N/1024)), 512 threads: 128 column threads of 8
+// columns, times four quarters of the item's rows (16 rows each, all 32 loads of a thread issued before the first
+// sum), the quarters' sums added through LDS in the order of the rows.
+__global__ __launch_bounds__(512) void k_dl(const int32_t* __restrict__ dtab, const TaskRef tasks,
                                            const bf16_t* __restrict__ dY, const bf16_t* __restrict__ Z, float* __restrict__ part,
-                                           bf16_t* __restrict__ dYs, int N) {
-  const ItemView it = load_item(dtab, TS64, blockIdx.x);
-  if (it.task < 0 || it.nvalid == 0) return;
-  const DevTask tk = get_task(tasks, it.task);
-  if (tk.kind != MUX_ADAPTER_IA3_OUT) return;
-  const int n0 = (blockIdx.y * 128 + threadIdx.x) * 8;
-  if (n0 >= N) return;
-  constexpr int RF = 8;     // rows per batch; two batches in flight
+                                           bf16_t* __restrict__ dYs, int N, int items_off, int bits_off) {
+  __shared__ float sq[3][128][9];
+  const int item = blockIdx.x;
+  const int4 iw = *(const int4*)(dtab + items_off + item * DI_WORDS);
+  const int task = iw.x, row0 = iw.y, nrows = iw.z;
+  if (task < 0 || iw.w == 0) return;
+  if (get_task_kind(tasks, task) != MUX_ADAPTER_IA3_OUT) return;
+  const DevTask tk = get_task(tasks, task);
+  const uint32_t* bw = (const uint32_t*)(dtab + bits_off) + 2 * item;
+  const int ct = threadIdx.x & 127, rq = threadIdx.x >> 7;
+  const uint32_t bits = (rq < 2 ? bw[0] : bw[1]) >> (16 * (rq & 1)) & 0xffffu;    // validity of this quarter's 16 rows
+  const int n0 = (blockIdx.y * 128 + ct) * 8;
+  const bool cols = n0 < N;
+  constexpr int RQ = 16;
   float s[8], lv[8];
-  {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { s[e] = 0.f; lv[e] = 0.f; }
+  if (cols) {
     const uint4 l4 = *(const uint4*)((const bf16_t*)tk.L + n0);
     const uint32_t* pl = (const uint32_t*)&l4;
 #pragma unroll
     for (int e = 0; e < 4; ++e) { lv[2 * e] = __uint_as_float(pl[e] << 16); lv[2 * e + 1] = __uint_as_float(pl[e] & 0xffff0000u); }
-  }
+    // every thread issues the same 2 RQ loads (a row that does not count reads the item's first row instead and is
+    // dropped afterwards)
+    uint4 gv[RQ], zv[RQ];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) s[e] = 0.f;
-  // Every batch issues the same 2 RF loads (a row that does not count reads the item's first row instead and is
-  // dropped afterwards), so that the batch being summed can be waited for while the next one is still in flight.
-  auto fetch = [&](int m0, uint4 (&gv)[RF], uint4 (&zv)[RF]) {
-#pragma unroll
-    for (int u = 0; u < RF; ++u) {
-      const int row = it.row0 + (m0 + u < it.nrows ? m0 + u : 0);
+    for (int u = 0; u < RQ; ++u) {
+      const int m = rq * RQ + u;
+      const int row = row0 + (m < nrows ? m : 0);
       gv[u] = *(const uint4*)(dY + (size_t)row * N + n0);
       zv[u] = *(const uint4*)(Z + (size_t)(tk.zrow0 + row - tk.row_begin) * N + n0);
     }
-  };
-  auto consume = [&](int m0, const uint4 (&gv)[RF], const uint4 (&zv)[RF]) {
 #pragma unroll
-    for (int u = 0; u < RF; ++u) {
-      const int row = it.row0 + m0 + u;
-      if (!(m0 + u < it.nrows && row_is_valid(dtab, row))) continue;
+    for (int u = 0; u < RQ; ++u) {
+      const int m = rq * RQ + u;
+      if (!(m < nrows && ((bits >> u) & 1u))) continue;
       const uint32_t* pg = (const uint32_t*)&gv[u];
       const uint32_t* pz = (const uint32_t*)&zv[u];
       uint4 sv;
@@ -823,33 +829,35 @@ __global__ __launch_bounds__(128) void k_dl(const int32_t* __restrict__ dtab, co
         s[2 * e + 1] = fmaf(g1, __uint_as_float(pz[e] & 0xffff0000u), s[2 * e + 1]);
         ps[e] = pack_bf16x2(g0 * lv[2 * e], g1 * lv[2 * e + 1]);
       }
-      *(uint4*)(dYs + (size_t)(tk.zrow0 + row - tk.row_begin) * N + n0) = sv;
+      *(uint4*)(dYs + (size_t)(tk.zrow0 + row0 + m - tk.row_begin) * N + n0) = sv;
     }
-  };
-  uint4 ga[RF], za[RF], gb[RF], zb[RF];
-  fetch(0, ga, za);
-  for (int m0 = 0; m0 < it.nrows; m0 += 2 * RF) {
-    fetch(m0 + RF, gb, zb);
-    consume(m0, ga, za);
-    fetch(m0 + 2 * RF, ga, za);
-    consume(m0 + RF, gb, zb);
   }
-  float* dst = part + (size_t)blockIdx.x * N + n0;
+  if (rq > 0) {
 #pragma unroll
-  for (int e = 0; e < 8; ++e) dst[e] = s[e];
+    for (int e = 0; e < 8; ++e) sq[rq - 1][ct][e] = s[e];
+  }
+  __syncthreads();
+  if (rq == 0 && cols) {
+    float* dst = part + (size_t)item * N + n0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dst[e] = ((s[e] + sq[0][ct][e]) + sq[1][ct][e]) + sq[2][ct][e];
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
 // out_t = (accumulate ? out_t : 0) + sum over the task's items, ascending.  grid = (tasks, blocks over the elements).
-// mode 0: LoRA, elements [0, r*N) are dB_t [r][N] from part0, elements [r*N, r*(N+K)) are dA_t from part1, stored
-// transposed as [K][r].  mode 1: IA3_OUT, dl_t [N] from part0 (one row per item).
+// LoRA and Adapter-Tuning tasks: elements [0, r*N) are dB_t [r][N] from part0, elements [r*N, r*(N+K)) are dA_t from
+// part1, stored transposed as [K][r].  IA3_OUT tasks: dl_t [N] from part_ia3 (one row per 64-row item).
 __global__ __launch_bounds__(256) void k_reduce(const int32_t* __restrict__ dtab, const TaskRef tasks,
-                                               const float* __restrict__ part0, const float* __restrict__ part1, int N, int K,
-                                               int RP, int ts0, int ts1, int mode, int accumulate, size_t slot0, size_t slot1) {
+                                               const float* __restrict__ part0, const float* __restrict__ part1,
+                                               const float* __restrict__ part_ia3, int N, int K,
+                                               int RP, int ts0, int ts1, int accumulate, size_t slot0, size_t slot1) {
   const int t = blockIdx.x;
   const DevTask tk = get_task(tasks, t);
   const bool ranked = tk.kind == MUX_ADAPTER_LORA || tk.kind == MUX_ADAPTER_TUNING;
-  if (mode == 1 ? tk.kind != MUX_ADAPTER_IA3_OUT : !ranked) return;
+  if (!ranked && tk.kind != MUX_ADAPTER_IA3_OUT) return;
+  const int mode = ranked ? 0 : 1;
+  if (mode == 1) { part0 = part_ia3; slot0 = (size_t)N; ts0 = TS64; }
   if (tk.kind == MUX_ADAPTER_TUNING) K = N;    // its first gradient is dD_t [N][r]
   const int rows = mode == 1 ? 1 : tk.rank;
   size_t e = ((size_t)blockIdx.y * 256 + threadIdx.x) * 4;     // four consecutive elements of one row (N, K multiples of 4)
@@ -929,8 +937,7 @@ PartLayout part_layout(int K, int N, const mux_segtab* st) {
     o.part1 = align256((size_t)st->items[TS256].size() * RP * K1 * 4);
   }
   o.ia3 = st->n_ia3 > 0 ? align256((size_t)st->items[TS64].size() * N * 4) : 0;
-  const size_t lora = o.gpart + o.part0 + o.part1;
-  o.total = lora > o.ia3 ? lora : o.ia3;
+  o.total = o.gpart + o.part0 + o.part1 + o.ia3;     // the IA3 partials lie behind the others: one reduction takes both
   return o;
 }
 
@@ -996,39 +1003,43 @@ mux_status adapter_grads(const CallCtx& c, const void* X, const void* dY, const 
                          void* part, int accumulate) {
   const int M = c.st->n_tasks;
   const PartLayout pl = part_layout(c.K, c.N, c.st);
-  if (c.st->n_lora + c.st->n_tuning > 0) {
-    const int K1 = (c.st->n_tuning > 0 && c.N > c.K) ? c.N : c.K;
-    const int ts_b = s4_group(c.st, c.N), ts_a = da_group(c.st, K1);
-    float* part0 = (float*)((char*)part + pl.gpart);
-    float* part1 = (float*)((char*)part + pl.gpart + pl.part0);
+  const bool ranked = c.st->n_lora + c.st->n_tuning > 0;
+  const int K1 = (c.st->n_tuning > 0 && c.N > c.K) ? c.N : c.K;
+  const int ts_b = s4_group(c.st, c.N), ts_a = da_group(c.st, K1);
+  float* part0 = (float*)((char*)part + pl.gpart);
+  float* part1 = (float*)((char*)part + pl.gpart + pl.part0);
+  float* part_ia3 = (float*)((char*)part + pl.gpart + pl.part0 + pl.part1);
+  const size_t slot0 = (size_t)c.RP * c.N, slot1 = (size_t)c.RP * K1;
+  double moved = 0.0;       // what the reduction moves: every row group's partials once in, the gradients once out
+  size_t elems = 0;
+  if (ranked) {
     GradParams p{c.dtab, {(const bf16_t*)Hs, (const bf16_t*)Gs}, {(const bf16_t*)dY, (const bf16_t*)X}, {part0, part1},
-                 {c.N, c.K}, c.RP, ts_a, (const bf16_t*)Z, {(size_t)c.RP * c.N, (size_t)c.RP * K1}, 1,
+                 {c.N, c.K}, c.RP, ts_a, (const bf16_t*)Z, {slot0, slot1}, 1,
                  c.st->dev_image[DH_NITEMS0 + 3 * ts_a + 1], c.st->dev_image[DH_OFF_ROWBITS], c.st->T};
     p.tasks = *c.tref;
     launch_grad(c, "grad_da", p, dim3((unsigned)c.st->items[ts_a].size(), (K1 + 255) / 256, 1));
-    const size_t elems = (size_t)c.st->r_max * ((size_t)c.N + K1);
-    // moved: every row group's partials once in (rows of the ranked tasks only), both gradients once out
-    double moved = 0.0;
+    elems = (size_t)c.st->r_max * ((size_t)c.N + K1);
     for (const HostTask& ht : c.st->tasks)
       if (ht.kind == MUX_ADAPTER_LORA || ht.kind == MUX_ADAPTER_TUNING) {
         const double kk = ht.kind == MUX_ADAPTER_TUNING ? c.N : c.K;
         const double gb = (ht.row_count + kTileRows[ts_b] - 1) / kTileRows[ts_b], ga = (ht.row_count + kTileRows[ts_a] - 1) / kTileRows[ts_a];
         moved += 4.0 * ht.rank * (gb * c.N + ga * kk) + 4.0 * ht.rank * (c.N + kk) * (accumulate ? 2 : 1);
       }
-    prof_note_bytes(moved);
-    MUX_LAUNCH("reduce_dbda", k_reduce, dim3(M, (unsigned)((elems + 1023) / 1024)), dim3(256), 0, c.stream, c.dtab, *c.tref,
-               (const float*)part0, (const float*)part1, c.N, c.K, c.RP, ts_b, ts_a, 0, accumulate, p.slot[0], p.slot[1]);
   }
   if (c.st->n_ia3 > 0) {
-    // the IA3_OUT partials share the region with the (finished) LoRA ones only in time: the launches are in stream order
-    MUX_LAUNCH("grad_dl", k_dl, dim3((unsigned)c.st->items[TS64].size(), (c.N + 1023) / 1024), dim3(128), 0, c.stream,
-               c.dtab, *c.tref, (const bf16_t*)dY, (const bf16_t*)Z, (float*)part, (bf16_t*)c.dYs, c.N);
-    double moved = 0.0;
+    MUX_LAUNCH("grad_dl", k_dl, dim3((unsigned)c.st->items[TS64].size(), (c.N + 1023) / 1024), dim3(512), 0, c.stream,
+               c.dtab, *c.tref, (const bf16_t*)dY, (const bf16_t*)Z, part_ia3, (bf16_t*)c.dYs, c.N,
+               c.st->dev_image[DH_NITEMS0 + 3 * TS64 + 1], c.st->dev_image[DH_OFF_ITEM_BITS]);
+    if ((size_t)c.N > elems) elems = (size_t)c.N;
     for (const HostTask& ht : c.st->tasks)
       if (ht.kind == MUX_ADAPTER_IA3_OUT) moved += 4.0 * c.N * ((ht.row_count + 63) / 64) + 4.0 * c.N * (accumulate ? 2 : 1);
+  }
+  if (elems > 0) {
+    // one reduction for every kind: a task's workgroups take the sums its kind has
     prof_note_bytes(moved);
-    MUX_LAUNCH("reduce_dl", k_reduce, dim3(M, (c.N + 1023) / 1024), dim3(256), 0, c.stream, c.dtab, *c.tref,
-               (const float*)part, (const float*)nullptr, c.N, c.K, 1, TS64, TS64, 1, accumulate, (size_t)c.N, (size_t)0);
+    MUX_LAUNCH("reduce_grads", k_reduce, dim3(M, (unsigned)((elems + 1023) / 1024)), dim3(256), 0, c.stream, c.dtab, *c.tref,
+               (const float*)part0, (const float*)part1, (const float*)part_ia3, c.N, c.K, c.RP, ts_b, ts_a, accumulate,
+               slot0, slot1);
   }
   return MUX_OK;
 }
