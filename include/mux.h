@@ -131,13 +131,22 @@ mux_status mux_segtab_upload(const mux_segtab* st, void* dev_dst, size_t cap, vo
  * are numbered in row-major order (by k, then n, no duplicates): entry e of row k has column col_idx[e],
  * row_ptr[k] <= e < row_ptr[k+1].  The same entries are listed a second time column by column:
  * col_ent[2*i] = row k and col_ent[2*i+1] = number e of the i-th listed entry, col_ptr[n] <= i < col_ptr[n+1],
- * k ascending inside a column.  The mask is fixed during training, so both listings are built once. */
+ * k ascending inside a column.  The mask is fixed during training, so both listings are built once.
+ * Optional (all four or none; NULL: the library takes another route for this task's rows): the entries once more by
+ * tiles, for the backbone products that add them to their tiles of W on the way.  Forward: bucket (k / 64, n / 128)
+ * has number (k / 64) * ceil(N / 128) + n / 128 and holds the entries i with fwd_ptr[b] <= i < fwd_ptr[b+1],
+ * fwd_ent[2*i] = number e, fwd_ent[2*i+1] = (k % 64) << 7 | (n % 128).  Backward: bucket (n / 64, k / 128) has number
+ * (n / 64) * ceil(K / 128) + k / 128, bwd_ent[2*i] = e, bwd_ent[2*i+1] = (n % 64) << 7 | (k % 128). */
 typedef struct mux_sparse_mask {
   int32_t nnz;
   const int32_t* row_ptr;  /* device, K+1 */
   const int32_t* col_idx;  /* device, nnz */
   const int32_t* col_ptr;  /* device, N+1 */
   const int32_t* col_ent;  /* device, 2*nnz */
+  const int32_t* fwd_ptr;  /* device, ceil(K/64)*ceil(N/128)+1, or NULL */
+  const int32_t* fwd_ent;  /* device, 2*nnz */
+  const int32_t* bwd_ptr;  /* device, ceil(N/64)*ceil(K/128)+1, or NULL */
+  const int32_t* bwd_ent;  /* device, 2*nnz */
 } mux_sparse_mask;
 
 /* Lays out both listings of a mask on the host from its entries (k[e], n[e]), e = 0 .. nnz-1, which must be sorted
@@ -146,6 +155,12 @@ typedef struct mux_sparse_mask {
  * only; nothing is launched. */
 mux_status mux_sparse_mask_layout(const int32_t* k, const int32_t* n, int32_t nnz, int32_t K, int32_t N,
                                   int32_t* row_ptr, int32_t* col_idx, int32_t* col_ptr, int32_t* col_ent);
+
+/* The listing by tiles of the same entries (same preconditions): fwd_ptr [ceil(K/64)*ceil(N/128)+1], fwd_ent [2 nnz],
+ * bwd_ptr [ceil(N/64)*ceil(K/128)+1], bwd_ent [2 nnz], host arrays of the caller.  Inside a bucket the entries keep
+ * their (k, n) order.  Index work only; nothing is launched. */
+mux_status mux_sparse_mask_tile_layout(const int32_t* k, const int32_t* n, int32_t nnz, int32_t K, int32_t N,
+                                       int32_t* fwd_ptr, int32_t* fwd_ent, int32_t* bwd_ptr, int32_t* bwd_ent);
 
 /* One multiplexed layer call.  All pointers inside are device pointers, except the three
  * arrays A, B, L themselves, which are host arrays of n_tasks device pointers (entry NULL

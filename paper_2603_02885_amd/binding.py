@@ -19,7 +19,7 @@ __all__ = [
     "library_path", "load_library", "mux_choose_chunk_size", "mux_segtab_build", "mux_segtab_free",
     "mux_segtab_rows", "mux_segtab_n_chunks", "mux_segtab_n_tasks", "mux_segtab_valid_tokens",
     "mux_segtab_serialized_bytes", "mux_segtab_serialize", "mux_segtab_row_task", "mux_segtab_device_bytes",
-    "mux_segtab_upload", "mux_sparse_mask_layout", "mux_lora_saved_bytes", "mux_lora_workspace_bytes", "mux_lora_forward",
+    "mux_segtab_upload", "mux_sparse_mask_layout", "mux_sparse_mask_tile_layout", "mux_lora_saved_bytes", "mux_lora_workspace_bytes", "mux_lora_forward",
     "mux_lora_backward", "mux_lora_backward_static_ws", "MUX_STATIC_WS_BYTES", "mux_last_error", "mux_version", "mux_profile_enable", "mux_profile_collect",
     "CostModel", "mux_plan_stage_latency", "mux_plan_htask_latency", "mux_plan_fusion",
     "mux_dispatch_gather", "mux_dispatch_scatter",
@@ -53,7 +53,8 @@ class _TaskDescC(ctypes.Structure):
 
 class _SparseMaskC(ctypes.Structure):
     _fields_ = [("nnz", c_int32), ("row_ptr", c_void_p), ("col_idx", c_void_p), ("col_ptr", c_void_p),
-                ("col_ent", c_void_p)]
+                ("col_ent", c_void_p), ("fwd_ptr", c_void_p), ("fwd_ent", c_void_p), ("bwd_ptr", c_void_p),
+                ("bwd_ent", c_void_p)]
 
 
 class _LayerDescC(ctypes.Structure):
@@ -162,6 +163,8 @@ def load_library() -> ctypes.CDLL:
         "mux_segtab_upload": (c_int, [vp, vp, c_size_t, vp]),
         "mux_sparse_mask_layout": (c_int, [POINTER(c_int32), POINTER(c_int32), c_int32, c_int32, c_int32, POINTER(c_int32),
                                            POINTER(c_int32), POINTER(c_int32), POINTER(c_int32)]),
+        "mux_sparse_mask_tile_layout": (c_int, [POINTER(c_int32), POINTER(c_int32), c_int32, c_int32, c_int32,
+                                                POINTER(c_int32), POINTER(c_int32), POINTER(c_int32), POINTER(c_int32)]),
         "mux_lora_saved_bytes": (c_size_t, [POINTER(_LayerDescC), vp]),
         "mux_lora_workspace_bytes": (c_size_t, [POINTER(_LayerDescC), vp]),
         "mux_lora_forward": (c_int, [POINTER(_LayerDescC), vp, vp, vp, vp, vp, vp, c_size_t, vp]),
@@ -264,18 +267,41 @@ def mux_sparse_mask_layout(k, n, K: int, N: int):
     return row_ptr, col_idx, col_ptr, col_ent
 
 
+def mux_sparse_mask_tile_layout(k, n, K: int, N: int):
+    """The listing by tiles of a mask as host arrays (fwd_ptr, fwd_ent [2 nnz], bwd_ptr, bwd_ent [2 nnz]), laid out by
+    the library from the entries (k[e], n[e]) sorted by (k, n)."""
+    k = np.ascontiguousarray(k, dtype=np.int32)
+    n = np.ascontiguousarray(n, dtype=np.int32)
+    if k.shape != n.shape or k.ndim != 1:
+        raise ValueError("k and n must be one-dimensional arrays of the same length")
+    nnz = int(k.size)
+    fwd_ptr = np.zeros(((K + 63) // 64) * ((N + 127) // 128) + 1, dtype=np.int32)
+    bwd_ptr = np.zeros(((N + 63) // 64) * ((K + 127) // 128) + 1, dtype=np.int32)
+    fwd_ent = np.zeros(max(2 * nnz, 2), dtype=np.int32)
+    bwd_ent = np.zeros(max(2 * nnz, 2), dtype=np.int32)
+    ip = lambda a: a.ctypes.data_as(POINTER(c_int32))
+    _check(load_library().mux_sparse_mask_tile_layout(ip(k), ip(n), nnz, int(K), int(N), ip(fwd_ptr), ip(fwd_ent),
+                                                      ip(bwd_ptr), ip(bwd_ent)))
+    return fwd_ptr, fwd_ent, bwd_ptr, bwd_ent
+
+
 class SparseMask:
     """Mirror of mux_sparse_mask.  Built from the masked entries (k[nnz], n[nnz]) sorted by (k, n): the library lays the
-    row-major listing (row_ptr, col_idx) and the column-by-column listing (col_ptr, col_ent) out on the host
-    (mux_sparse_mask_layout); `to_device` is a callable that turns an int32 numpy array into an object with a device
-    pointer (for instance lambda a: torch.from_numpy(a).cuda())."""
+    row-major listing (row_ptr, col_idx), the column-by-column listing (col_ptr, col_ent) and, unless `tiles` is False,
+    the listing by tiles out on the host (mux_sparse_mask_layout, mux_sparse_mask_tile_layout); `to_device` is a
+    callable that turns an int32 numpy array into an object with a device pointer (for instance
+    lambda a: torch.from_numpy(a).cuda())."""
 
-    def __init__(self, k, n, K: int, N: int, to_device):
+    def __init__(self, k, n, K: int, N: int, to_device, tiles: bool = True):
         row_ptr, col_idx, col_ptr, col_ent = mux_sparse_mask_layout(k, n, K, N)
         self.nnz = int(np.asarray(k).size)
         self._bufs = [to_device(row_ptr), to_device(col_idx), to_device(col_ptr), to_device(col_ent)]
         self.c = _SparseMaskC(nnz=self.nnz, row_ptr=_ptr(self._bufs[0]), col_idx=_ptr(self._bufs[1]),
                               col_ptr=_ptr(self._bufs[2]), col_ent=_ptr(self._bufs[3]))
+        if tiles:
+            self._bufs += [to_device(a) for a in mux_sparse_mask_tile_layout(k, n, K, N)]
+            self.c.fwd_ptr, self.c.fwd_ent = _ptr(self._bufs[4]), _ptr(self._bufs[5])
+            self.c.bwd_ptr, self.c.bwd_ent = _ptr(self._bufs[6]), _ptr(self._bufs[7])
 
 
 class LayerDesc:

@@ -63,7 +63,7 @@ struct Layout {
   size_t esz;          // bytes per stored element
   int RP;              // H / G row pitch in elements
   size_t h_bytes, z_bytes, u2_bytes, saved_bytes;
-  size_t tasks_bytes, g_bytes, at_bytes, dys_bytes, part_bytes, dt_bytes, dw_bytes, ws_bytes;
+  size_t tasks_bytes, g_bytes, at_bytes, dys_bytes, part_bytes, dt_bytes, dw_bytes, dp_bytes, ws_bytes;
   int dw_slots;        // DIFF tasks with entries: each gets room for its merged weight (matrix-core path)
 };
 
@@ -85,11 +85,27 @@ Layout make_layout(const mux_layer_desc* L, const mux_segtab* st) {
   o.part_bytes = L->dtype == MUX_DT_BF16 ? fast_partial_bytes(L->K, L->N, st) : 0;
   o.dys_bytes = (L->dtype == MUX_DT_BF16 || st->n_tuning > 0) ? o.z_bytes : 0;
   o.dt_bytes = diff_transposed_bytes(L->K, L->N, st, o.esz);
-  // Diff-Pruning on the matrix-core path: the sparse updates after the backbone products cost about 0.65 us per
+  // Diff-Pruning on the matrix-core path.  Where the shapes allow it (see fast_gemm_patches_diff) the backbone product
+  // adds the masked entries to its tiles of W in LDS and the call only packs them: 4 bytes an entry.
+  bool patchable = false;
+  if (L->dtype == MUX_DT_BF16 && !(L->flags & MUX_LAYER_REFERENCE_KERNELS) && st->n_diff > 0 && L->masks &&
+      L->K < 65536 && L->N < 65536 && (L->K % 64 == 0 || L->N % 64 == 0)) {
+    size_t nnz = 0;
+    bool listed = true;                                // every mask brings its listing by tiles
+    for (int t = 0; t < st->n_tasks; ++t)
+      if (st->tasks[t].kind == MUX_ADAPTER_DIFF && L->masks[t] && L->masks[t]->nnz > 0) {
+        const mux_sparse_mask* m = L->masks[t];
+        nnz += (size_t)m->nnz;
+        listed = listed && m->fwd_ptr && m->fwd_ent && m->bwd_ptr && m->bwd_ent;
+      }
+    o.dp_bytes = (nnz > 0 && listed) ? align256(nnz * 4) : 0;
+    patchable = o.dp_bytes > 0 && L->K % 64 == 0 && L->N % 64 == 0;   // both directions: no call of this layer needs another route
+  }
+  // Otherwise: the sparse updates after the backbone products cost about 0.65 us per
   // million (row, entry) pairs, a merged weight W + M_t * delta_t per task about 2.3 us per million elements of W and
   // nothing per row; the call merges when that is the cheaper of the two (measured on 4096 x 4096 with masks of 0.5 %:
   // from about 700 rows a task on).
-  if (L->dtype == MUX_DT_BF16 && !(L->flags & MUX_LAYER_REFERENCE_KERNELS) && st->n_diff > 0 && L->masks) {
+  if (!patchable && L->dtype == MUX_DT_BF16 && !(L->flags & MUX_LAYER_REFERENCE_KERNELS) && st->n_diff > 0 && L->masks) {
     int slots = 0;
     double pairs = 0.0;
     for (int t = 0; t < st->n_tasks; ++t)
@@ -100,7 +116,7 @@ Layout make_layout(const mux_layer_desc* L, const mux_segtab* st) {
     if (0.65 * pairs > 2.3 * (double)slots * (double)L->K * (double)L->N) o.dw_slots = slots;
   }
   o.dw_bytes = (size_t)o.dw_slots * diff_merged_bytes(L->K, L->ldw);
-  o.ws_bytes = o.tasks_bytes + o.g_bytes + o.at_bytes + o.dys_bytes + o.part_bytes + 2 * o.dt_bytes + o.dw_bytes;
+  o.ws_bytes = o.tasks_bytes + o.g_bytes + o.at_bytes + o.dys_bytes + o.part_bytes + 2 * o.dt_bytes + o.dw_bytes + o.dp_bytes;
   return o;
 }
 
@@ -151,10 +167,10 @@ inline bool lora_a_natural(const HostTask& ht) { return (ht.rank & 7) == 0; }
 // The per-call task parameters, laid out on the host.  at_off: element offset of the task's transposed operand in the
 // workspace region, -1 for a LoRA task whose A_t is read as it is.
 void build_tasks(const mux_layer_desc* L, const mux_segtab* st, void* const* dA, void* const* dB, void* const* dL,
-                 bool fast, bool merged, std::vector<DevTask>& out) {
+                 bool fast, int diff_route, bool backward, std::vector<DevTask>& out) {
   out.assign((size_t)st->n_tasks, DevTask{});
   int64_t at_off = 0;
-  int slot = 0;
+  int slot = 0;         // diff_route 1: index of the next merged weight; 2: element offset of the next packed list
   for (int t = 0; t < st->n_tasks; ++t) {
     const HostTask& ht = st->tasks[t];
     const int kind = ht.kind;
@@ -176,7 +192,13 @@ void build_tasks(const mux_layer_desc* L, const mux_segtab* st, void* const* dA,
       d.B = m->row_ptr; d.L = m->col_idx;
       d.dB = (float*)m->col_ptr; d.dL = (float*)m->col_ent;
       d.at_off = m->nnz;
-      d.rank = (merged && m->nnz > 0) ? slot++ : -1;
+      d.rank = -1;
+      if (m->nnz > 0 && diff_route == 1) d.rank = slot++;
+      if (m->nnz > 0 && diff_route == 2) {              // the listing by tiles of this direction instead of the column listing
+        d.rank = slot; slot += m->nnz;
+        d.dB = (float*)(backward ? m->bwd_ptr : m->fwd_ptr);
+        d.dL = (float*)(backward ? m->bwd_ent : m->fwd_ent);
+      }
     }
     if (kind == MUX_ADAPTER_LORA) {
       if (fast && lora_a_natural(ht)) d.at_off = -1;
@@ -248,9 +270,10 @@ CallCtx make_ctx(const mux_layer_desc* layer, const mux_segtab* st, const void* 
   c.stream = stream;
   c.U2 = (saved && lo.u2_bytes) ? (char*)saved + lo.h_bytes + lo.z_bytes : nullptr;
   c.diff_max_nnz = diff_max_nnz(layer, st);
-  c.diffT[0] = (char*)ws + lo.ws_bytes - lo.dw_bytes - 2 * lo.dt_bytes;
-  c.diffT[1] = (char*)ws + lo.ws_bytes - lo.dw_bytes - lo.dt_bytes;
+  c.diffT[0] = (char*)ws + lo.ws_bytes - lo.dp_bytes - lo.dw_bytes - 2 * lo.dt_bytes;
+  c.diffT[1] = (char*)ws + lo.ws_bytes - lo.dp_bytes - lo.dw_bytes - lo.dt_bytes;
   c.diffW = nullptr;
+  c.diffPack = nullptr;
   c.diffW_stride = (int64_t)(diff_merged_bytes(layer->K, layer->ldw) / 2);
   c.diffW_slots = lo.dw_slots;
   return c;
@@ -276,9 +299,10 @@ extern "C" mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_se
   const bool fast = layer->dtype == MUX_DT_BF16 && !(layer->flags & MUX_LAYER_REFERENCE_KERNELS) &&
                     fast_supported(c, X, Y, H, Z, nullptr, nullptr);
   c.lora_natural = fast && !any_packed_lora(st);
-  if (fast && lo.dw_bytes > 0) c.diffW = (char*)ws + lo.ws_bytes - lo.dw_bytes;
+  if (fast && lo.dp_bytes > 0 && fast_gemm_patches_diff(c, false)) c.diffPack = (char*)ws + lo.ws_bytes - lo.dp_bytes;
+  else if (fast && lo.dw_bytes > 0) c.diffW = (char*)ws + lo.ws_bytes - lo.dp_bytes - lo.dw_bytes;
   std::vector<DevTask> tasks;
-  build_tasks(layer, st, nullptr, nullptr, nullptr, c.lora_natural, c.diffW != nullptr, tasks);
+  build_tasks(layer, st, nullptr, nullptr, nullptr, c.lora_natural, c.diffPack ? 2 : (c.diffW ? 1 : 0), false, tasks);
   TaskRef tref;
   const int pack = !fast ? 0 : ((st->n_lora > 0 && !c.lora_natural) ? 1 : (st->n_tuning > 0 ? 2 : 0));
   publish_tasks(layer, st, tasks, !fast || st->n_diff > 0, (DevTask*)ws, tref, pack, c.AT, stream);
@@ -315,9 +339,10 @@ static mux_status backward_impl(const char* fn, const mux_layer_desc* layer, con
   const bool fast = layer->dtype == MUX_DT_BF16 && !(layer->flags & MUX_LAYER_REFERENCE_KERNELS) &&
                     fast_supported(c, X, dY, dX, G, H, Z);
   c.lora_natural = fast && !any_packed_lora(st);
-  if (fast && lo.dw_bytes > 0 && dX) c.diffW = (char*)ws + lo.ws_bytes - lo.dw_bytes;
+  if (fast && lo.dp_bytes > 0 && dX && fast_gemm_patches_diff(c, true)) c.diffPack = (char*)ws + lo.ws_bytes - lo.dp_bytes;
+  else if (fast && lo.dw_bytes > 0 && dX) c.diffW = (char*)ws + lo.ws_bytes - lo.dp_bytes - lo.dw_bytes;
   std::vector<DevTask> tasks;
-  build_tasks(layer, st, dA, dB, dL, c.lora_natural, c.diffW != nullptr, tasks);
+  build_tasks(layer, st, dA, dB, dL, c.lora_natural, c.diffPack ? 2 : (c.diffW ? 1 : 0), true, tasks);
   TaskRef tref;
   publish_tasks(layer, st, tasks, !fast || st->n_diff > 0, (DevTask*)ws, tref, (fast && st->n_tuning > 0) ? 2 : 0, c.AT, stream);
   c.tref = &tref;

@@ -383,7 +383,7 @@ void transpose(const CallCtx& c, const void* In, void* Out, int C, const char* n
 
 template <class S>
 void forward(const CallCtx& c, const void* X, void* Y) {
-  if (c.diffW) return;                       // the backbone product read W + M_t * delta_t for these rows
+  if (c.diffW || c.diffPack) return;         // the backbone product read W + M_t * delta_t for these rows
   const int n_items = (int)c.st->items[TS64].size();
   transpose<S>(c, X, c.diffT[0], c.K, "diff_xt");
   constexpr int CPW = 256 / Piece<S>::LPL;
@@ -395,7 +395,7 @@ template <class S>
 void backward(const CallCtx& c, const void* X, const void* dY, void* dX, int accumulate) {
   const int n_items = (int)c.st->items[TS64].size();
   transpose<S>(c, dY, c.diffT[1], c.N, "diff_gt");
-  if (dX && !c.diffW)                        // else the backbone product read W + M_t * delta_t for these rows
+  if (dX && !c.diffW && !c.diffPack)         // else the backbone product read W + M_t * delta_t for these rows
     MUX_LAUNCH("diff_bwd", k_diff_apply<S>, dim3((unsigned)n_items * (unsigned)((c.K + (256 / Piece<S>::LPL) - 1) / (256 / Piece<S>::LPL))), dim3(256), 0, c.stream, c.dtab, c.dtasks,
                (const S*)c.diffT[1], (S*)dX, c.N, c.K, 1);
   transpose<S>(c, X, c.diffT[0], c.K, "diff_xt");
@@ -414,6 +414,27 @@ void backward(const CallCtx& c, const void* X, const void* dY, void* dX, int acc
 
 size_t diff_transposed_bytes(int K, int N, const mux_segtab* st, size_t esz) {
   return st->n_diff > 0 ? align256((size_t)st->d_rows * (size_t)(K > N ? K : N) * esz) : 0;
+}
+
+// The entries of every Diff-Pruning mask in the order of the listing by tiles of this call's direction (tk.dB, tk.dL),
+// with their values: (position inside the bucket's tile) << 16 | bf16(delta).  A task's list starts at element tk.rank
+// of `out`.  grid = (tasks, ceil(max nnz / 256)).
+namespace {
+__global__ __launch_bounds__(256) void k_diff_pack(const DevTask* __restrict__ tasks, uint32_t* __restrict__ out, int backward) {
+  const DevTask tk = tasks[blockIdx.x];
+  if (tk.kind != MUX_ADAPTER_DIFF || tk.rank < 0) return;
+  const int pos = blockIdx.y * 256 + threadIdx.x;
+  if (pos >= tk.at_off) return;
+  const bf16_t* val = (const bf16_t*)tk.A;
+  const int2 ent = ((const int2*)tk.dL)[pos];        // (number of the entry, position inside the tile)
+  out[(size_t)tk.rank + pos] = (uint32_t)ent.y << 16 | (uint32_t)val[ent.x];
+}
+}  // namespace
+
+void diff_pack(const CallCtx& c, bool backward) {
+  if (!c.diffPack || c.diff_max_nnz == 0) return;
+  MUX_LAUNCH("diff_pack", k_diff_pack, dim3((unsigned)c.st->n_tasks, (unsigned)((c.diff_max_nnz + 255) / 256)), dim3(256), 0,
+             c.stream, c.dtasks, (uint32_t*)c.diffPack, backward ? 1 : 0);
 }
 
 size_t diff_merged_bytes(int K, int64_t ldw) { return align256((size_t)K * (size_t)ldw * 2); }

@@ -22,6 +22,14 @@ bool fast_supported(const CallCtx& c, const void* p0, const void* p1, const void
          aligned16(p5);
 }
 
+// Diff-Pruning rows through the pipelined kernel's 64-deep tile loop, which adds the masked entries to the tiles of W
+// in LDS: 16-bit indices and a contraction length that is a multiple of 64.
+bool fast_gemm_patches_diff(const CallCtx& c, bool backward) {
+  if (regstaged() || !gemm_dma_supported(c, backward)) return false;
+  static const bool narrow = getenv("MUX_GEMM_BK32") != nullptr;      // measurement switch, read once: 32-deep stages everywhere
+  return !narrow && c.K < 65536 && c.N < 65536 && (backward ? c.N : c.K) % 64 == 0;
+}
+
 // The caller has checked fast_supported for the shapes and pointers of this call.
 mux_status fast_forward(const CallCtx& c, const void* X, void* Y, void* H, void* Z, void*) {
   // small launches form Hs = s_t X A_t inside the backbone tile loop; the others stream X once more for it
@@ -29,7 +37,8 @@ mux_status fast_forward(const CallCtx& c, const void* X, void* Y, void* H, void*
   const bool fuse_down = pipelined && gemm_dma_fuses_down(c);
   if (!fuse_down)
     if (mux_status s = adapter_down_x(c, X, H)) return s;
-  diff_merge(c, c.diffW_slots);           // Diff-Pruning tasks: their rows meet W + M_t * delta_t in the backbone product
+  // Diff-Pruning tasks: their rows meet W + M_t * delta_t in the backbone product (entries added in LDS, or a copy)
+  if (c.diffPack) diff_pack(c, false); else diff_merge(c, c.diffW_slots);
   mux_status s;
   if (pipelined) s = gemm_dma_forward(c, X, H, Y, Z, fuse_down);
   else s = gemm_mfma_forward(c, X, H, Y, Z);
@@ -50,7 +59,7 @@ mux_status fast_backward(const CallCtx& c, const void* X, const void* dY, const 
   if (mux_status s = adapter_tune_add(c, dY, G, c.dYs, 1)) return s;
   if (mux_status s = adapter_grads(c, X, dY, H, G, Z, part, accumulate)) return s;
   if (!dX) return MUX_OK;
-  diff_merge(c, c.diffW_slots);
+  if (c.diffPack) diff_pack(c, true); else diff_merge(c, c.diffW_slots);
   if (gemm_dma_supported(c, true) && !regstaged()) {
     // IA3_OUT rows read dY * l_t, written by the dl kernel above
     return gemm_dma_backward(c, dY, G, dX);

@@ -56,6 +56,7 @@ struct GemmParams {
   int n_full;              // workgroups that compute full tiles (a multiple of 8); the rest compute pieces of tiles
   int tail_split;          // pieces per tile after the full ones: 2 (halves) or 4 (quarters)
   unsigned long long* clk;  // diagnostic: counters workgroup 0 adds its elapsed cycles and 100 MHz ticks to (null: off)
+  const uint32_t* DiffPack; // entries of the Diff-Pruning masks packed for this launch (index << 16 | bf16 value), or null
   const bf16_t* Wdiff;      // merged weights W + M_t * delta_t of the Diff-Pruning tasks, `wdiff_stride` elements apart (or null)
   int64_t wdiff_stride;
   const bf16_t* AinScaled;  // backward: prepared input rows (IA3_OUT: dY * l_t; TUNING: dY + p D_t^T), [z_rows, Kc], indexed like the saved x W
@@ -76,6 +77,13 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void* p, uint32_t bytes) {
 __device__ __forceinline__ void dma16(rsrc_t r, bf16_t* lds_dst_uniform, uint32_t byte_off) {
   const uint32_t lds_addr = (uint32_t)(uintptr_t)(lds_void_ptr)lds_dst_uniform;
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :
+               : "s"(lds_addr), "v"(byte_off), "s"(r)
+               : "m0");
+}
+// The same with 4 bytes a lane: lane l's dword lands at LDS byte address lds_addr + 4*l.
+__device__ __forceinline__ void dma4(rsrc_t r, uint32_t lds_addr, uint32_t byte_off) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
                :
                : "s"(lds_addr), "v"(byte_off), "s"(r)
                : "m0");
@@ -103,6 +111,8 @@ struct Smem {
   bf16_t *a0, *a1, *a2, *a3, *b0, *b1, *b2, *b3;
   int* row;
   bf16_t *e0, *e1, *e2, *e3;     // FUSE: stages of the [64][rank] slabs of A_t
+  uint32_t pk_lds;               // DIFFP: LDS byte address of the stages' slots for 256 packed entries of the masks each
+  int* off;                      //        per K-tile, where the entries of this tile's buckets begin, split and end
 };
 
 // One output tile.  WNW = waves along N, MI x NI = 32x32 MFMA tiles per wave; 2*WNW waves on a
@@ -120,10 +130,18 @@ struct Smem {
 // rounded to bf16, straight into the A side of the adapter K-tile (and, from the tiles of the first column, to
 // memory for the backward): no separate pass over X, no launch for it.  Every column tile redoes the product for
 // its rows, which is why this is for launches that do not fill the compute units anyway.
-template <bool NT, int WNW, int MI, int NI, int BK, bool FUSE = false>
+// DIFFP (64-deep stages): the rows of a Diff-Pruning task meet W + M_t * delta_t without a copy of W: once a tile of W
+// has landed in LDS, the masked entries that fall into it are added in place (one bf16 read-modify-write each) and a
+// second barrier follows before the tile is read.  The mask lists its entries by tiles -- buckets of 64 of the
+// contraction index by 128 lines of the W side, numbered so that the one or two buckets of a tile are neighbours --
+// and the launch brings them packed, (contraction index % 64) << 23 | (line % 128) << 16 | bf16 value.  The entries
+// of a K-tile travel with it: every loading wave fetches 64 of them straight into LDS with the tile's other loads
+// (256 a tile; a bucket pair with more reads the rest from memory when the tile is patched).
+template <bool NT, int WNW, int MI, int NI, int BK, bool FUSE = false, bool DIFFP = false>
 __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slot, const int half, const int mhalf,
                                           const Smem sm) {
   static_assert(!FUSE || (!NT && BK == 64 && WNW == MI && !(MI == 4 && NI == 2)), "FUSE: forward, 64-deep, half or quarter tiles");
+  static_assert(!DIFFP || (BK == 64 && !FUSE), "DIFFP: 64-deep stages");
   constexpr int BN = WNW * NI * 32;
   constexpr int BMT = 2 * MI * 32;
   static_assert(BN == 256 || BN == 128, "tile width");
@@ -142,7 +160,8 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   constexpr int LW = NW == 8 ? NW / 2 : NW;       // four waves: one per SIMD, all of them load
   constexpr int ACH = (A_ELEMS / 512) / LW, BCH = (BN * BK / 512) / LW;   // 1 KB chunks a loading wave fetches per K-tile
   constexpr int ECH = FUSE ? 1 : 0;               // FUSE: and one of the (up to) 4 KB of the slab of A_t
-  constexpr int NLD = ACH + BCH + ECH;            // loads a loading wave issues per K-tile
+  constexpr int DCH = DIFFP ? 1 : 0;              // DIFFP: and 64 packed entries of the mask
+  constexpr int NLD = ACH + BCH + ECH + DCH;      // loads a loading wave issues per K-tile
   static_assert(ACH >= 1 && BCH >= 1, "every loading wave fetches at least one chunk of each tile");
   static_assert(!FUSE || LW == 4, "FUSE: four loading waves bring the four chunks of a slab");
   constexpr int LPR = BK / 8;                     // [rows][BK] tiles: lanes (16-byte pieces) per row
@@ -210,7 +229,39 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   const int KT_ext = lora ? (rank + BK - 1) / BK : 0;
   const int KT_total = KT + KT_ext;
   const bool fuse_h = FUSE && lora;                 // this tile forms Hs of its rows in the K loop
-  if (FUSE && !lora) zero_hs_rows();
+  // DIFFP: the bucket offsets of this task's listing for this direction, the buckets of this tile in a K-tile's row
+  // of buckets, and per stage the entries of the tile it holds: first, first of the second bucket, end
+  const bool patch = DIFFP && tk.kind == MUX_ADAPTER_DIFF && tk.rank >= 0 && p.DiffPack != nullptr && c0 < p.Nc;
+  constexpr int SPAN = BN / 128;
+  const int32_t* bptr = (const int32_t*)tk.dB;
+  const int nbk = (p.Nc + 127) >> 7, bcol = c0 >> 7;
+  const int bspan = bcol + SPAN <= nbk ? SPAN : nbk - bcol;      // a ragged last tile may hold one bucket only
+  const uint32_t* dlist = p.DiffPack + (patch ? tk.rank : 0);
+  const rsrc_t rPk = make_rsrc(patch ? (const void*)dlist : (const void*)p.Ain, patch ? (uint32_t)tk.at_off * 4u : 0u);
+  int ps0[NST], ps1[NST], ps2[NST];
+#pragma unroll
+  for (int q = 0; q < NST; ++q) { ps0[q] = 0; ps1[q] = 0; ps2[q] = 0; }
+  int nx0 = 0, nx1 = 0, nx2 = 0;                   // the same for the tile after the ones in flight
+  // The offsets of every K-tile's entries go to LDS once (a load from the listing inside the loop would have the loop
+  // wait for it, and for the tiles in flight with it, at every K-tile).
+  if (DIFFP && patch) {
+    for (int t = tid; t < KT; t += NTHR) {
+      const int32_t* q = bptr + (size_t)t * nbk + bcol;
+      sm.off[3 * t] = q[0];
+      sm.off[3 * t + 1] = q[1];
+      sm.off[3 * t + 2] = q[bspan];
+    }
+    __syncthreads();
+  }
+  // offsets of the entries of K-tile t (none past the backbone tiles, none without a mask)
+  auto bucket_offsets = [&](int t, int& o0, int& o1, int& o2) {
+    o0 = 0; o1 = 0; o2 = 0;
+    if (DIFFP && patch && t < KT) {
+      o0 = __builtin_amdgcn_readfirstlane(sm.off[3 * t]);
+      o1 = __builtin_amdgcn_readfirstlane(sm.off[3 * t + 1]);
+      o2 = __builtin_amdgcn_readfirstlane(sm.off[3 * t + 2]);
+    }
+  };
 
   // ---- DMA geometry.  A wave instruction fills 1 KB: RPC rows x 2 BK bytes of a [rows][BK] tile
   // (lane -> row lane/LPR, physical piece lane%LPR), or RPCB k-rows of the forward's [BK][BN] tile of W
@@ -299,16 +350,18 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
     }
   };
   // one load of the tile being fetched: i = 0 .. NLD-1, the A pieces first, then W, then (FUSE) the slab of A_t
-  auto issue_one = [&](bf16_t* dA, bf16_t* dB, bf16_t* dE, int i) {
+  // (DIFFP: the last load brings entries o0 + 64 lw .. of the tile's buckets, below o2, into the stage's entry slots)
+  auto issue_one = [&](bf16_t* dA, bf16_t* dB, bf16_t* dE, int i, uint32_t dP = 0, int o0 = 0, int o2 = 0) {
     if (!loader) return;
     if (i < ACH) dma16(curA, dA + (lw * ACH + i) * 512, offA[i] + kA);
     else if (i < ACH + BCH) dma16(curB, dB + (lw * BCH + (i - ACH)) * 512, offB[i - ACH] + kB);
+    else if (DIFFP) dma4(rPk, dP + lw * 256, (o0 + lw * 64 + lane < o2) ? (uint32_t)(o0 + lw * 64 + lane) * 4u : OOB);
     else dma16(rAt, dE + lw * 512, (offE == OOB || kE == OOB) ? OOB : offE + kE);
   };
   auto issue_done = [&]() { kA += stepA; kB += stepB; if (FUSE && kE != OOB) kE += stepE; ++next_tile; };
-  auto issue = [&](bf16_t* dA, bf16_t* dB, bf16_t* dE) {
+  auto issue = [&](bf16_t* dA, bf16_t* dB, bf16_t* dE, uint32_t dP = 0, int o0 = 0, int o2 = 0) {
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) issue_one(dA, dB, dE, i);
+    for (int i = 0; i < NLD; ++i) issue_one(dA, dB, dE, i, dP, o0, o2);
     issue_done();
   };
 
@@ -430,7 +483,8 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
   // next step's fragment en of the slab cE.
   auto fused_step = [&](const bf16x8 (&a)[MI], const bf16x8 (&b)[NI], const bf16_t* cA, const bf16_t* cB, int ks_next,
                         bf16x8 (&an)[MI], bf16x8 (&bn)[NI], bool rd, auto LOADS, bf16_t* dA, bf16_t* dB,
-                        const bf16x8& e, bf16x8& en, const bf16_t* cE, bf16_t* dE) {
+                        const bf16x8& e, bf16x8& en, const bf16_t* cE, bf16_t* dE, uint32_t dP = 0, int o0 = 0,
+                        int o2 = 0) {
     constexpr bool loads = decltype(LOADS)::value;
     constexpr int NM = MI * NI, NR = MI + NI, NL = NLD;
     if (FUSE && fuse_h) en = read_e(cE, ks_next);
@@ -446,7 +500,7 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
       }
       if (loads) {
 #pragma unroll
-        for (int d = (m * NL) / NM; d < ((m + 1) * NL) / NM; ++d) issue_one(dA, dB, dE, d);
+        for (int d = (m * NL) / NM; d < ((m + 1) * NL) / NM; ++d) issue_one(dA, dB, dE, d, dP, o0, o2);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -472,13 +526,42 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
     asm volatile("" ::: "memory");
   };
 
+  auto ldsP = [&](int st) -> uint32_t { return sm.pk_lds + (uint32_t)st * 1024u; };
+  typedef __attribute__((address_space(3))) uint32_t lds_u32;
+  // DIFFP: the entries o0 .. o2 - 1 of a tile (o1: the first of its second bucket), the first 256 of them in cP, added to
+  // the W side of the tile in stage cB (landed, visible to the workgroup)
+  auto patch_tile = [&](bf16_t* cB, uint32_t cP, int o0, int o1, int o2) {
+    auto add_entry = [&](uint32_t w, int pos) {
+      const int j = (int)(w >> 23), line = (int)((w >> 16) & 127u) + ((SPAN == 2 && o0 + pos >= o1) ? 128 : 0);
+      bf16_t* e = NT ? cB + line * BK + (((j >> 3) ^ swz_row<BK>(line)) * 8) + (j & 7)
+                     : cB + j * BN + (((line >> 4) ^ ((j & 3) << 1)) * 16) + (line & 15);
+      // (the packed bf16 add of the LDS atomic unit in place of this read-modify-write was 5 % slower)
+      *e = f32_to_bf16(bf16_to_f32(*e) + __uint_as_float(w << 16));
+    };
+    static_assert(NTHR >= 256, "one entry a thread covers what was staged");
+    if (tid < o2 - o0 && tid < 256) add_entry(*(const lds_u32*)(uintptr_t)(cP + 4u * (uint32_t)tid), tid);   // (an LDS address, said as such)
+    // a bucket pair with more entries than were staged: the rest from memory, in a loop of its own so that the usual case
+    // holds no memory load whose wait would also wait for the tiles in flight
+    if (o2 - o0 > 256)
+      for (int pos = 256 + tid; pos < o2 - o0; pos += NTHR) add_entry(dlist[o0 + pos], pos);
+  };
   // ---- prologue: tiles 0 .. PRE-1 in flight; tile 0 landed and visible; its first operands in registers
   constexpr int PRE = BK == 64 ? NST : NST - 1;
 #pragma unroll
-  for (int s0 = 0; s0 < PRE; ++s0) { prepare(); issue(stA(s0), stB(s0), stE(s0)); }
+  for (int s0 = 0; s0 < PRE; ++s0) {
+    prepare();
+    if (DIFFP) bucket_offsets(s0, ps0[s0], ps1[s0], ps2[s0]);
+    issue(stA(s0), stB(s0), stE(s0), ldsP(s0), ps0[s0], ps2[s0]);
+  }
+  if (DIFFP) bucket_offsets(PRE, nx0, nx1, nx2);
   wait_vmcnt<(PRE - 1) * NLD>();
   wait_lgkm0();
   tile_barrier();
+  if (DIFFP && patch && ps2[0] > ps0[0]) {
+    patch_tile(sB0, ldsP(0), ps0[0], ps1[0], ps2[0]);
+    wait_lgkm0();
+    tile_barrier();
+  }
 
   bf16x8 a0[MI], b0[NI], a1[MI], b1[NI];
   bf16x8 e0 = {}, e1 = {};
@@ -509,8 +592,22 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
           wait_lgkm0();
           tile_barrier();
           __builtin_amdgcn_sched_barrier(0);
+          if (DIFFP) {
+            // Tile kt + 1 has landed: its masked entries, then a second barrier, then it may be read.  (Waiting for the
+            // tile one step earlier and adding the entries under the MFMAs of the third step was slower.)
+            const int un = (u + 1) % NST;
+            if (patch && ps2[un] > ps0[un]) {
+              patch_tile(stB(un), ldsP(un), ps0[un], ps1[un], ps2[un]);
+              wait_lgkm0();
+              tile_barrier();
+            }
+            // this stage is refilled with tile kt + NST (PRE == NST here): its entries, and the offsets of the tile after
+            ps0[u] = nx0; ps1[u] = nx1; ps2[u] = nx2;
+            bucket_offsets(kt + NST + 1, nx0, nx1, nx2);
+            __builtin_amdgcn_sched_barrier(0);
+          }
           fused_step(a1, b1, stA((u + 1) % NST), stB((u + 1) % NST), 0, a0, b0, true, std::true_type{}, cA, cB, e1, e0,
-                     stE((u + 1) % NST), cE);   // past the last tile: read, unused
+                     stE((u + 1) % NST), cE, ldsP(u), ps0[u], ps2[u]);   // past the last tile: read, unused
           issue_done();
         }
       }
@@ -656,7 +753,7 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, const int xcd_slo
 // The workgroups after them compute the remaining tiles in pieces (tail_split = 2: two half-width tiles each;
 // 4: four 128 x 128 quarters each); all pieces of a tile run on the same XCD.  The dispatcher hands out workgroups
 // in index order, so the pieces start as the compute units finish their last full tile.
-template <bool NT, int BK, bool FUSE>
+template <bool NT, int BK, bool FUSE, bool DIFFP>
 __global__ __launch_bounds__(512, 1) void k_gemm_dma(const GemmParams p) {
   constexpr int STAGE_ELEMS = BM * BK;            // 16 KB (BK = 32, four stages) or 32 KB (BK = 64, two) per operand
   __shared__ __attribute__((aligned(1024))) bf16_t sA0[STAGE_ELEMS];
@@ -671,19 +768,21 @@ __global__ __launch_bounds__(512, 1) void k_gemm_dma(const GemmParams p) {
   __shared__ __attribute__((aligned(1024))) bf16_t sE1[FUSE ? 2048 : 8];
   __shared__ __attribute__((aligned(1024))) bf16_t sE2[FUSE ? 2048 : 8];
   __shared__ __attribute__((aligned(1024))) bf16_t sE3[FUSE ? 2048 : 8];
+  __shared__ __attribute__((aligned(1024))) uint32_t sP[DIFFP ? 4 * 256 : 2];   // DIFFP: 256 packed entries a stage
+  __shared__ int sOff[DIFFP ? 3 * 1024 : 2];                                      // DIFFP: K < 65536, so at most 1023 K-tiles
   __shared__ int sRow[256];
-  const Smem sm = {sA0, sA1, sA2, sA3, sB0, sB1, sB2, sB3, sRow, sE0, sE1, sE2, sE3};
+  const Smem sm = {sA0, sA1, sA2, sA3, sB0, sB1, sB2, sB3, sRow, sE0, sE1, sE2, sE3, (uint32_t)(uintptr_t)(lds_void_ptr)sP, sOff};
   const int b = blockIdx.x;
   // the start stamps wait in the buffer itself (words 2, 3), so that nothing stays live across the tile
   if (p.clk != nullptr && b == 0 && threadIdx.x == 0) { p.clk[2] = clock64(); p.clk[3] = wall_clock64(); }
   if (!FUSE && b < p.n_full) {                    // a launch with the down-projection in the loop has pieces only
-    gemm_tile<NT, 4, 4, 2, BK, false>(p, b, 0, 0, sm);
+    gemm_tile<NT, 4, 4, 2, BK, false, DIFFP>(p, b, 0, 0, sm);
   } else if (p.tail_split == 2) {
     const int t = b - p.n_full;                                       // n_full is a multiple of 8
-    gemm_tile<NT, 4, 4, 1, BK, FUSE>(p, p.n_full + (((t >> 4) << 3) | (t & 7)), (t >> 3) & 1, 0, sm);
+    gemm_tile<NT, 4, 4, 1, BK, FUSE, DIFFP>(p, p.n_full + (((t >> 4) << 3) | (t & 7)), (t >> 3) & 1, 0, sm);
   } else {
     const int t = b - p.n_full;
-    gemm_tile<NT, 2, 2, 2, BK, FUSE>(p, p.n_full + (((t >> 5) << 3) | (t & 7)), (t >> 3) & 1, (t >> 4) & 1, sm);
+    gemm_tile<NT, 2, 2, 2, BK, FUSE, DIFFP>(p, p.n_full + (((t >> 5) << 3) | (t & 7)), (t >> 3) & 1, (t >> 4) & 1, sm);
   }
   if (p.clk != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
     atomicAdd(p.clk, (unsigned long long)clock64() - p.clk[2]);
@@ -739,14 +838,17 @@ mux_status launch(const CallCtx& c, const bf16_t* Ain, const bf16_t* Ext, bf16_t
   p.n_m = t.n_m; p.n_n = t.n_n; p.per_xcd = t.per_xcd; p.n_full = t.n_full; p.tail_split = t.tail_split;
   p.AinScaled = (const bf16_t*)c.dYs;
   p.Wdiff = (const bf16_t*)c.diffW; p.wdiff_stride = c.diffW_stride;
+  p.DiffPack = (const uint32_t*)c.diffPack;
   p.clk = diag_clock_buffer();
   if (t.n_m * t.n_n == 0) return MUX_OK;
   if (fuse_down && (NT || t.narrow || t.n_full != 0)) return fail(MUX_ERR_UNSUPPORTED, "gemm: this launch cannot carry the down-projection");
+  if (p.DiffPack != nullptr && (t.narrow || fuse_down)) return fail(MUX_ERR_UNSUPPORTED, "gemm: this launch cannot add masked entries in the tile loop");
   if (!t.narrow) {
-    if (!NT && fuse_down) MUX_LAUNCH("gemm_nn", (k_gemm_dma<false, 64, true>), dim3(t.grid), dim3(512), 0, c.stream, p);
-    else MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", (k_gemm_dma<NT, 64, false>), dim3(t.grid), dim3(512), 0, c.stream, p);
+    if (!NT && fuse_down) MUX_LAUNCH("gemm_nn", (k_gemm_dma<false, 64, true, false>), dim3(t.grid), dim3(512), 0, c.stream, p);
+    else if (p.DiffPack != nullptr) MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", (k_gemm_dma<NT, 64, false, true>), dim3(t.grid), dim3(512), 0, c.stream, p);
+    else MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", (k_gemm_dma<NT, 64, false, false>), dim3(t.grid), dim3(512), 0, c.stream, p);
   } else {
-    MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", (k_gemm_dma<NT, 32, false>), dim3(t.grid), dim3(512), 0, c.stream, p);
+    MUX_LAUNCH(NT ? "gemm_nt" : "gemm_nn", (k_gemm_dma<NT, 32, false, false>), dim3(t.grid), dim3(512), 0, c.stream, p);
   }
   return MUX_OK;
 }
@@ -773,7 +875,7 @@ bool gemm_dma_supported(const CallCtx& c, bool backward) {
 bool gemm_dma_fuses_down(const CallCtx& c) {
   static const int mode = [] { const char* e = getenv("MUX_GEMM_FUSE_DOWN"); return e == nullptr ? 1 : atoi(e); }();
   if (mode == 0 || !gemm_dma_supported(c, false)) return false;
-  if (c.st->n_lora == 0 || c.st->n_tuning > 0 || !c.lora_natural || c.st->r_max > 32) return false;
+  if (c.st->n_lora == 0 || c.st->n_tuning > 0 || !c.lora_natural || c.st->r_max > 32 || c.diffPack != nullptr) return false;
   const TilePlan t = plan_tiles(c, c.K, c.N);
   if (t.narrow || t.n_full != 0 || t.n_m * t.n_n == 0) return false;
   return t.tail_split == 4 || mode == 2;

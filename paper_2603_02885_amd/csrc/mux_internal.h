@@ -53,7 +53,8 @@ struct DevTask {
   int64_t at_off;     // element offset of this task's transposed A_t inside the workspace region
                       // DIFF tasks: A = values, dA = their gradient, B = row_ptr, L = col_idx, dB = col_ptr, dL = col_ent
                       // (all int32 arrays), at_off = number of masked entries; rank = index of the task's merged
-                      // weight W + M_t * delta_t in the workspace when the call builds them, else -1
+                      // weight W + M_t * delta_t in the workspace when the call builds them, or the element offset of
+                      // the task's packed entries when the backbone product adds them in LDS, else -1
 };
 static_assert(sizeof(DevTask) == 80, "DevTask layout");
 
@@ -141,6 +142,8 @@ struct CallCtx {
                            // null: the sparse updates run after the backbone products instead)
   int64_t diffW_stride;    // elements between the merged weights of two tasks
   int diffW_slots;         // how many tasks have one
+  void* diffPack;          // workspace: the masks' entries packed for the backbone product of this call, which adds
+                           // them to the tiles of W in LDS (index << 16 | bf16 value; null: another route is taken)
 };
 
 // H / G row pitch in elements
@@ -166,6 +169,7 @@ void ref_steps(const CallCtx& c, int dtype, unsigned which, const void* X, const
 // Diff-Pruning tasks, both storage types: the masked sparse update after the backbone GEMM, and the masked gradient
 size_t diff_transposed_bytes(int K, int N, const mux_segtab* st, size_t esz);
 size_t diff_merged_bytes(int K, int64_t ldw);      // one task's merged weight, bf16
+void diff_pack(const CallCtx& c, bool backward);   // the packed entries the backbone product of this call adds in LDS
 void diff_merge(const CallCtx& c, int slots);                                                                        // W + M_t * delta_t per task
 void diff_forward(const CallCtx& c, int dtype, const void* X, void* Y);                                       // Y += x (M_t * delta_t)
 void diff_backward(const CallCtx& c, int dtype, const void* X, const void* dY, void* dX, int accumulate);     // dX, d delta_t
@@ -176,6 +180,7 @@ mux_status gemm_mfma_forward(const CallCtx& c, const void* X, const void* Hs, vo
 mux_status gemm_mfma_backward(const CallCtx& c, const void* dY, const void* Gs, void* dX, int only_ia3);
 // pipelined variant (direct-to-LDS loads, 4 stages)
 bool gemm_dma_supported(const CallCtx& c, bool backward);
+bool fast_gemm_patches_diff(const CallCtx& c, bool backward);   // the backbone product of this call can add masked entries in LDS
 bool gemm_dma_fuses_down(const CallCtx& c);   // the forward launch would be half / quarter tiles only: Hs is formed in its K loop
 mux_status gemm_dma_forward(const CallCtx& c, const void* X, const void* Hs, void* Y, void* Z, bool fuse_down);
 mux_status gemm_dma_backward(const CallCtx& c, const void* dY, const void* Gs, void* dX);

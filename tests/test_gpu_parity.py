@@ -205,22 +205,27 @@ def test_diff_pruning_kind(env, mode, seg_flags):
     run_case(env, diff_workload(K=104, N=328, chunk=16, density=0.05), dtype=dtype, seg_flags=seg_flags, layer_flags=lf, seed=8)
 
 
-def test_diff_pruning_merged_weight_or_sparse_updates(env):
-    """The matrix-core path serves Diff-Pruning rows in one of two ways, by cost: the backbone products read a merged
-    weight W + M_t * delta_t built for the call (many rows, dense masks), or sparse updates follow the products (few
-    rows, thin masks).  Both against the oracle, forward and backward, and the kernel list shows which one ran."""
+def test_diff_pruning_routes(env):
+    """The matrix-core path serves Diff-Pruning rows in one of three ways: where both contraction lengths are multiples
+    of 64 the backbone products add the masked entries to their tiles of W in LDS (only a packing kernel runs beside
+    them); else, by cost, the products read a merged weight W + M_t * delta_t built for the call (many rows, dense
+    masks) or sparse updates follow them (few rows, thin masks).  All against the oracle, forward and backward, thin
+    and dense masks (a column with many entries in one K-tile), and the kernel list shows which route ran."""
     mx, torch = env
-    for density, merged in ((0.02, True), (0.002, False)):
+    for K, N, density, route in ((256, 384, 0.02, "patch"), (256, 384, 0.3, "patch"), (1024, 192, 0.002, "patch"),
+                                 (264, 392, 0.02, "merged"), (264, 392, 0.002, "updates")):
         for seg_flags in (0, 1):
-            g, got, ref, errs = run_case(env, diff_workload(K=256, N=384, density=density), seed=9, seg_flags=seg_flags)
+            g, got, ref, errs = run_case(env, diff_workload(K=K, N=N, density=density), seed=9, seg_flags=seg_flags)
             mx.mux_profile_enable(1)
             mx.mux_profile_collect()
             g.forward(); g.backward()
             torch.cuda.synchronize()
             names = [e["name"] for e in mx.mux_profile_collect()]
             mx.mux_profile_enable(0)
-            assert ("diff_merge" in names) == merged and ("diff_fwd" in names) == (not merged), (density, names)
-            assert ("diff_bwd" in names) == (not merged) and "diff_grad" in names, (density, names)
+            assert ("diff_pack" in names) == (route == "patch"), (K, N, density, names)
+            assert ("diff_merge" in names) == (route == "merged"), (K, N, density, names)
+            assert ("diff_fwd" in names) == (route == "updates") and ("diff_bwd" in names) == (route == "updates"), (K, N, density, names)
+            assert "diff_grad" in names, names
 
 
 def test_diff_pruning_gradient_by_mask_blocks(env):

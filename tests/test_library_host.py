@@ -117,8 +117,9 @@ def test_empty_table(mx):
 
 
 def test_sparse_mask_layout_against_a_direct_listing(mx):
-    """mux_sparse_mask_layout against both listings written down directly from the entries (pure Python), on random
-    masks with empty rows and columns; unsorted, duplicated and out-of-range entries are refused."""
+    """mux_sparse_mask_layout and mux_sparse_mask_tile_layout against the listings written down directly from the
+    entries (pure Python), on random masks with empty rows and columns, and shapes with several buckets of 64 x 128 and
+    ragged last ones; unsorted, duplicated and out-of-range entries are refused."""
     import ctypes
     rng = np.random.default_rng(5)
 
@@ -129,12 +130,12 @@ def test_sparse_mask_layout_against_a_direct_listing(mx):
         def data_ptr(self):
             return self.a.ctypes.data
 
-    for K, N, dens in ((7, 5, 0.4), (33, 64, 0.05), (16, 9, 0.0), (5, 300, 0.3)):
+    for K, N, dens in ((7, 5, 0.4), (33, 64, 0.05), (16, 9, 0.0), (5, 300, 0.3), (200, 300, 0.02), (130, 129, 0.1)):
         flat = np.flatnonzero(rng.random(K * N) < dens)
         k, n = (flat // N).astype(np.int32), (flat % N).astype(np.int32)
         held = []
         m = mx.SparseMask(k, n, K, N, lambda a: held.append(Keep(a.copy())) or held[-1])
-        row_ptr, col_idx, col_ptr, col_ent = (h.a for h in held)
+        row_ptr, col_idx, col_ptr, col_ent, fwd_ptr, fwd_ent, bwd_ptr, bwd_ent = (h.a for h in held)
         assert m.nnz == flat.size
         by_row = [[int(n[e]) for e in range(flat.size) if k[e] == r] for r in range(K)]
         assert list(row_ptr) == [sum(len(x) for x in by_row[:r]) for r in range(K + 1)]
@@ -142,6 +143,17 @@ def test_sparse_mask_layout_against_a_direct_listing(mx):
         by_col = [[(int(k[e]), e) for e in range(flat.size) if n[e] == c] for c in range(N)]
         assert list(col_ptr) == [sum(len(x) for x in by_col[:c]) for c in range(N + 1)]
         assert list(col_ent[:2 * flat.size]) == [v for x in by_col for pair in x for v in pair]
+        # by tiles: forward buckets (k / 64, n / 128), backward buckets (n / 64, k / 128), (k, n) order inside a bucket
+        nbn, nbk = (N + 127) // 128, (K + 127) // 128
+        fwd = [[] for _ in range(((K + 63) // 64) * nbn)]
+        bwd = [[] for _ in range(((N + 63) // 64) * nbk)]
+        for e in range(flat.size):
+            fwd[(k[e] // 64) * nbn + n[e] // 128] += [e, (int(k[e]) % 64) << 7 | int(n[e]) % 128]
+            bwd[(n[e] // 64) * nbk + k[e] // 128] += [e, (int(n[e]) % 64) << 7 | int(k[e]) % 128]
+        assert list(fwd_ptr) == [sum(len(x) // 2 for x in fwd[:b]) for b in range(len(fwd) + 1)]
+        assert list(bwd_ptr) == [sum(len(x) // 2 for x in bwd[:b]) for b in range(len(bwd) + 1)]
+        assert list(fwd_ent[:2 * flat.size]) == [v for x in fwd for v in x]
+        assert list(bwd_ent[:2 * flat.size]) == [v for x in bwd for v in x]
     for k, n in (([1, 0], [0, 0]), ([0, 0], [2, 2]), ([0], [9]), ([-1], [0])):
         with pytest.raises(mx.MuxError):
             mx.SparseMask(np.array(k), np.array(n), 4, 4, lambda a: Keep(a))
