@@ -807,8 +807,8 @@ def main():
     if diff_rows:
         nnz = [sum(m.nnz for m in L.masks if m is not None) for L in layers]
         stream_bytes.update({
-            "diff_xt": sum(8.0 * diff_rows * K for K, N in dims),      # launched forward and backward
-            "diff_gt": sum(4.0 * diff_rows * N for K, N in dims),
+            "diff_xt": sum(4.0 * diff_rows * K for K, N in dims),      # forward, when the sparse updates follow the product
+            "diff_gxt": sum(4.0 * diff_rows * (K + N) for K, N in dims),   # backward: both copies in one launch
             "diff_fwd": sum(2.0 * diff_rows * K + 4.0 * diff_rows * N + 10.0 * z for (K, N), z in zip(dims, nnz)),
             "diff_bwd": sum(2.0 * diff_rows * N + 4.0 * diff_rows * K + 6.0 * z for (K, N), z in zip(dims, nnz)),
             "diff_grad": sum(2.0 * diff_rows * (K + N) + 8.0 * z for (K, N), z in zip(dims, nnz)),

@@ -305,7 +305,7 @@ extern "C" mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_se
   build_tasks(layer, st, nullptr, nullptr, nullptr, c.lora_natural, c.diffPack ? 2 : (c.diffW ? 1 : 0), false, tasks);
   TaskRef tref;
   const int pack = !fast ? 0 : ((st->n_lora > 0 && !c.lora_natural) ? 1 : (st->n_tuning > 0 ? 2 : 0));
-  publish_tasks(layer, st, tasks, !fast || st->n_diff > 0, (DevTask*)ws, tref, pack, c.AT, stream);
+  publish_tasks(layer, st, tasks, !fast, (DevTask*)ws, tref, pack, c.AT, stream);
   c.tref = &tref;
   c.dtasks = tref.mem;
   mux_status s;
@@ -344,7 +344,7 @@ static mux_status backward_impl(const char* fn, const mux_layer_desc* layer, con
   std::vector<DevTask> tasks;
   build_tasks(layer, st, dA, dB, dL, c.lora_natural, c.diffPack ? 2 : (c.diffW ? 1 : 0), true, tasks);
   TaskRef tref;
-  publish_tasks(layer, st, tasks, !fast || st->n_diff > 0, (DevTask*)ws, tref, (fast && st->n_tuning > 0) ? 2 : 0, c.AT, stream);
+  publish_tasks(layer, st, tasks, !fast, (DevTask*)ws, tref, (fast && st->n_tuning > 0) ? 2 : 0, c.AT, stream);
   c.tref = &tref;
   c.dtasks = tref.mem;
   if (st->T == 0) {                 // no rows at all: zero gradients (or leave the accumulators as they are)

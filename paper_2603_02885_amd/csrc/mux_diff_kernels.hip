@@ -45,16 +45,23 @@ template <> struct Piece<bf16_t> {
 };
 
 // Block-transposed copy of the Diff-Pruning rows of In [T, C]:  Out[(block * C + c) * 64 + r] = In[row0 + r][c], zero
-// for padding rows and for r beyond the item.  grid = (64-row items, ceil(C / 64)).  VEC: the rows of In can be read
+// for padding rows and for r beyond the item.  grid = (64-row items, ceil(C / 64), matrices): the launch copies one
+// matrix or two (blockIdx.z picks; the backward copies dY and X together).  VEC: the rows of every In can be read
 // 16 bytes at a time (C a multiple of 16 bytes' worth of elements, In 16-byte aligned).
+template <class S>
+struct TransposeSrc { const S* In; S* Out; int C; };
 template <class S, bool VEC>
-__global__ __launch_bounds__(256) void k_diff_transpose(const int32_t* __restrict__ dtab, const DevTask* __restrict__ tasks,
-                                                        const S* __restrict__ In, S* __restrict__ Out, int C) {
+__global__ __launch_bounds__(256) void k_diff_transpose(const int32_t* __restrict__ dtab, const TaskRef tasks,
+                                                        const TransposeSrc<S> s0, const TransposeSrc<S> s1) {
   constexpr int VE = 16 / (int)sizeof(S);          // elements per 16-byte vector
   __shared__ __align__(16) S tile[64][64 + VE];
+  const S* __restrict__ In = blockIdx.z == 0 ? s0.In : s1.In;
+  S* __restrict__ Out = blockIdx.z == 0 ? s0.Out : s1.Out;
+  const int C = blockIdx.z == 0 ? s0.C : s1.C;
+  if ((int)blockIdx.y * 64 >= C) return;
   const ItemView it = load_item(dtab, TS64, blockIdx.x);
-  if (it.task < 0 || tasks[it.task].kind != MUX_ADAPTER_DIFF) return;
-  const DevTask tk = tasks[it.task];
+  if (it.task < 0 || get_task_kind(tasks, it.task) != MUX_ADAPTER_DIFF) return;
+  const DevTask tk = get_task(tasks, it.task);
   if (tk.at_off == 0) return;
   const int c0 = blockIdx.y * 64;
   {
@@ -88,14 +95,14 @@ __global__ __launch_bounds__(256) void k_diff_transpose(const int32_t* __restric
 // LPL lanes share one output column, each with RPL of the 64 row sums; grid = items x ceil(Cout / (256 / LPL))
 // workgroups, the column blocks of one item next to each other so that they find the item's block in the L2 caches.
 template <class S>
-__global__ __launch_bounds__(256) void k_diff_apply(const int32_t* __restrict__ dtab, const DevTask* __restrict__ tasks,
+__global__ __launch_bounds__(256) void k_diff_apply(const int32_t* __restrict__ dtab, const TaskRef tasks,
                                                     const S* __restrict__ Tin, S* __restrict__ Out, int Cin, int Cout,
                                                     int backward) {
   constexpr int LPL = Piece<S>::LPL, RPL = Piece<S>::RPL, CPW = 256 / LPL;
   const int ncb = (Cout + CPW - 1) / CPW;
   const ItemView it = load_item(dtab, TS64, blockIdx.x / ncb);
-  if (it.task < 0 || it.nvalid == 0 || tasks[it.task].kind != MUX_ADAPTER_DIFF) return;
-  const DevTask tk = tasks[it.task];
+  if (it.task < 0 || it.nvalid == 0 || get_task_kind(tasks, it.task) != MUX_ADAPTER_DIFF) return;
+  const DevTask tk = get_task(tasks, it.task);
   const int sub = threadIdx.x % LPL;
   const int c = (blockIdx.x % ncb) * CPW + threadIdx.x / LPL;
   if (tk.at_off == 0 || c >= Cout) return;
@@ -133,10 +140,10 @@ __global__ __launch_bounds__(256) void k_diff_apply(const int32_t* __restrict__ 
 // rows over the blocks in ascending order; the LPL partial sums are then added in a fixed tree.
 // grid = (tasks, ceil(max nnz / 256)).
 template <class S>
-__global__ __launch_bounds__(256) void k_diff_grad(const DevTask* __restrict__ tasks, const S* __restrict__ Xt,
+__global__ __launch_bounds__(256) void k_diff_grad(const TaskRef tasks, const S* __restrict__ Xt,
                                                    const S* __restrict__ Gt, int K, int N, int accumulate) {
   constexpr int LPL = Piece<S>::LPL, RPL = Piece<S>::RPL, EPI = 64 / LPL;    // EPI: entries per load instruction
-  const DevTask tk = tasks[blockIdx.x];
+  const DevTask tk = get_task(tasks, (int)blockIdx.x);
   if (tk.kind != MUX_ADAPTER_DIFF || tk.dA == nullptr) return;
   const int lane = threadIdx.x & 63;
   const int wave_e0 = blockIdx.y * 256 + (threadIdx.x & ~63);
@@ -203,14 +210,14 @@ constexpr int GP = 72;                  // LDS pitch (elements) of a line of 64 
 constexpr int G_EPT = 2;                // entries per thread and pass
 constexpr int G_THREADS = 1024;
 constexpr int G_SMEM = 2 * GB * GP * 2 + (GB + 1) * 4 + GB * 4;
-__global__ __launch_bounds__(G_THREADS) void k_diff_grad_tiled(const DevTask* __restrict__ tasks, const bf16_t* __restrict__ Xt,
+__global__ __launch_bounds__(G_THREADS) void k_diff_grad_tiled(const TaskRef tasks, const bf16_t* __restrict__ Xt,
                                                                const bf16_t* __restrict__ Gt, int K, int N, int accumulate) {
   extern __shared__ __align__(16) unsigned char g_smem[];
   bf16_t* Xs = (bf16_t*)g_smem;
   bf16_t* Gs = Xs + GB * GP;
   int* offs = (int*)(Gs + GB * GP);     // GB + 1: entries of the block before row i
   int* start = offs + GB + 1;           // GB: index (in the row listing) of row i's first entry inside the block
-  const DevTask tk = tasks[blockIdx.y];
+  const DevTask tk = get_task(tasks, (int)blockIdx.y);
   if (tk.kind != MUX_ADAPTER_DIFF || tk.dA == nullptr || tk.at_off == 0) return;
   // Workgroups go to the eight XCDs round-robin: XCD x takes a contiguous stretch of the blocks in row-major order, so
   // that the blocks running on it at one time share their lines of Xt in its L2.
@@ -326,9 +333,9 @@ __global__ __launch_bounds__(G_THREADS) void k_diff_grad_tiled(const DevTask* __
 // listing.  grid = (ceil(K / MR), tasks).  (Reading W once for all tasks in one workgroup was slower: fewer
 // workgroups, 82 against 61 us for two tasks.)
 constexpr int MR = 8;
-__global__ __launch_bounds__(256) void k_diff_merge(const DevTask* __restrict__ tasks, const bf16_t* __restrict__ W,
+__global__ __launch_bounds__(256) void k_diff_merge(const TaskRef tasks, const bf16_t* __restrict__ W,
                                                     bf16_t* __restrict__ Wm_all, int64_t stride, int K, int N, int64_t ldw) {
-  const DevTask tk = tasks[blockIdx.y];
+  const DevTask tk = get_task(tasks, (int)blockIdx.y);
   if (tk.kind != MUX_ADAPTER_DIFF || tk.rank < 0) return;
   bf16_t* Wm = Wm_all + (size_t)tk.rank * (size_t)stride;
   const int k0 = blockIdx.x * MR;
@@ -369,45 +376,46 @@ bool tiled_grad_ready() {
   return ok;
 }
 
+// One matrix (In1 null) or two in one launch.
 template <class S>
-void transpose(const CallCtx& c, const void* In, void* Out, int C, const char* name) {
+void transpose(const CallCtx& c, const char* name, const void* In0, void* Out0, int C0, const void* In1 = nullptr,
+               void* Out1 = nullptr, int C1 = 0) {
   const int n_items = (int)c.st->items[TS64].size();
-  const bool vec = C % (16 / (int)sizeof(S)) == 0 && ((uintptr_t)In & 15) == 0;
-  if (vec)
-    MUX_LAUNCH(name, (k_diff_transpose<S, true>), dim3(n_items, (C + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks,
-               (const S*)In, (S*)Out, C);
-  else
-    MUX_LAUNCH(name, (k_diff_transpose<S, false>), dim3(n_items, (C + 63) / 64), dim3(256), 0, c.stream, c.dtab, c.dtasks,
-               (const S*)In, (S*)Out, C);
+  constexpr int VE = 16 / (int)sizeof(S);
+  const bool vec = C0 % VE == 0 && ((uintptr_t)In0 & 15) == 0 && (!In1 || (C1 % VE == 0 && ((uintptr_t)In1 & 15) == 0));
+  const TransposeSrc<S> s0{(const S*)In0, (S*)Out0, C0}, s1{(const S*)In1, (S*)Out1, C1};
+  const int cmax = C0 > C1 ? C0 : C1;
+  const dim3 grid(n_items, (cmax + 63) / 64, In1 ? 2 : 1);
+  if (vec) MUX_LAUNCH(name, (k_diff_transpose<S, true>), grid, dim3(256), 0, c.stream, c.dtab, *c.tref, s0, s1);
+  else MUX_LAUNCH(name, (k_diff_transpose<S, false>), grid, dim3(256), 0, c.stream, c.dtab, *c.tref, s0, s1);
 }
 
 template <class S>
 void forward(const CallCtx& c, const void* X, void* Y) {
   if (c.diffW || c.diffPack) return;         // the backbone product read W + M_t * delta_t for these rows
   const int n_items = (int)c.st->items[TS64].size();
-  transpose<S>(c, X, c.diffT[0], c.K, "diff_xt");
+  transpose<S>(c, "diff_xt", X, c.diffT[0], c.K);
   constexpr int CPW = 256 / Piece<S>::LPL;
-  MUX_LAUNCH("diff_fwd", k_diff_apply<S>, dim3((unsigned)n_items * (unsigned)((c.N + CPW - 1) / CPW)), dim3(256), 0, c.stream, c.dtab, c.dtasks,
+  MUX_LAUNCH("diff_fwd", k_diff_apply<S>, dim3((unsigned)n_items * (unsigned)((c.N + CPW - 1) / CPW)), dim3(256), 0, c.stream, c.dtab, *c.tref,
              (const S*)c.diffT[0], (S*)Y, c.K, c.N, 0);
 }
 
 template <class S>
 void backward(const CallCtx& c, const void* X, const void* dY, void* dX, int accumulate) {
   const int n_items = (int)c.st->items[TS64].size();
-  transpose<S>(c, dY, c.diffT[1], c.N, "diff_gt");
+  transpose<S>(c, "diff_gxt", dY, c.diffT[1], c.N, X, c.diffT[0], c.K);     // both copies the gradient needs
   if (dX && !c.diffW && !c.diffPack)         // else the backbone product read W + M_t * delta_t for these rows
-    MUX_LAUNCH("diff_bwd", k_diff_apply<S>, dim3((unsigned)n_items * (unsigned)((c.K + (256 / Piece<S>::LPL) - 1) / (256 / Piece<S>::LPL))), dim3(256), 0, c.stream, c.dtab, c.dtasks,
+    MUX_LAUNCH("diff_bwd", k_diff_apply<S>, dim3((unsigned)n_items * (unsigned)((c.K + (256 / Piece<S>::LPL) - 1) / (256 / Piece<S>::LPL))), dim3(256), 0, c.stream, c.dtab, *c.tref,
                (const S*)c.diffT[1], (S*)dX, c.N, c.K, 1);
-  transpose<S>(c, X, c.diffT[0], c.K, "diff_xt");
   // by blocks of the mask where there are enough of them to occupy the compute units (bf16), else by entries
   const int blocks = ((c.K + GB - 1) / GB) * ((c.N + GB - 1) / GB);
   if (std::is_same<S, bf16_t>::value && blocks * c.st->n_diff >= kTiledMinBlocks && tiled_grad_ready()) {
     MUX_LAUNCH("diff_grad", k_diff_grad_tiled, dim3((unsigned)(8 * ((blocks + 7) / 8)), (unsigned)c.st->n_tasks), dim3(G_THREADS), G_SMEM, c.stream,
-               c.dtasks, (const bf16_t*)c.diffT[0], (const bf16_t*)c.diffT[1], c.K, c.N, accumulate);
+               *c.tref, (const bf16_t*)c.diffT[0], (const bf16_t*)c.diffT[1], c.K, c.N, accumulate);
     return;
   }
   MUX_LAUNCH("diff_grad", k_diff_grad<S>, dim3(c.st->n_tasks, (c.diff_max_nnz + 255) / 256), dim3(256), 0, c.stream,
-             c.dtasks, (const S*)c.diffT[0], (const S*)c.diffT[1], c.K, c.N, accumulate);
+             *c.tref, (const S*)c.diffT[0], (const S*)c.diffT[1], c.K, c.N, accumulate);
 }
 
 }  // namespace
@@ -420,8 +428,8 @@ size_t diff_transposed_bytes(int K, int N, const mux_segtab* st, size_t esz) {
 // with their values: (position inside the bucket's tile) << 16 | bf16(delta).  A task's list starts at element tk.rank
 // of `out`.  grid = (tasks, ceil(max nnz / 256)).
 namespace {
-__global__ __launch_bounds__(256) void k_diff_pack(const DevTask* __restrict__ tasks, uint32_t* __restrict__ out, int backward) {
-  const DevTask tk = tasks[blockIdx.x];
+__global__ __launch_bounds__(256) void k_diff_pack(const TaskRef tasks, uint32_t* __restrict__ out, int backward) {
+  const DevTask tk = get_task(tasks, (int)blockIdx.x);
   if (tk.kind != MUX_ADAPTER_DIFF || tk.rank < 0) return;
   const int pos = blockIdx.y * 256 + threadIdx.x;
   if (pos >= tk.at_off) return;
@@ -434,7 +442,7 @@ __global__ __launch_bounds__(256) void k_diff_pack(const DevTask* __restrict__ t
 void diff_pack(const CallCtx& c, bool backward) {
   if (!c.diffPack || c.diff_max_nnz == 0) return;
   MUX_LAUNCH("diff_pack", k_diff_pack, dim3((unsigned)c.st->n_tasks, (unsigned)((c.diff_max_nnz + 255) / 256)), dim3(256), 0,
-             c.stream, c.dtasks, (uint32_t*)c.diffPack, backward ? 1 : 0);
+             c.stream, *c.tref, (uint32_t*)c.diffPack, backward ? 1 : 0);
 }
 
 size_t diff_merged_bytes(int K, int64_t ldw) { return align256((size_t)K * (size_t)ldw * 2); }
@@ -445,7 +453,7 @@ void diff_merge(const CallCtx& c, int slots) {
   if (!c.diffW || slots <= 0) return;
   prof_note_bytes(4.0 * c.K * c.N * slots);
   MUX_LAUNCH("diff_merge", k_diff_merge, dim3((unsigned)((c.K + MR - 1) / MR), (unsigned)c.st->n_tasks), dim3(256), 0, c.stream,
-             c.dtasks, (const bf16_t*)c.W, (bf16_t*)c.diffW, c.diffW_stride, c.K, c.N, c.ldw);
+             *c.tref, (const bf16_t*)c.W, (bf16_t*)c.diffW, c.diffW_stride, c.K, c.N, c.ldw);
 }
 
 void diff_forward(const CallCtx& c, int dtype, const void* X, void* Y) {
