@@ -196,8 +196,8 @@ __global__ __launch_bounds__(256) void k_diff_grad(const TaskRef tasks, const S*
   if (e_w < tk.at_off) tk.dA[e_w] = accumulate ? tk.dA[e_w] + mine : mine;
 }
 
-// The masked gradient by blocks of the mask (bf16).  A workgroup owns the entries of one GB x GB block of one task's mask
-// and walks the task's 64-row blocks: the GB lines of Xt and the GB lines of Gt of a row block (two contiguous
+// The masked gradient by blocks of the mask (bf16).  A workgroup owns the entries of one GBK x GBN block of one task's mask
+// and walks the task's 64-row blocks: the GBK lines of Xt and the GBN lines of Gt of a row block (two contiguous
 // stretches of the transposed copies) are staged in LDS once and serve all entries of the mask block, so a line is
 // fetched once per mask block instead of once per entry; the loads of the next row block are in flight (in registers)
 // while the entries are summed.  The entries of the block come from the row listing: thread i looks up, by two binary
@@ -205,31 +205,31 @@ __global__ __launch_bounds__(256) void k_diff_grad(const TaskRef tasks, const S*
 // them, and a thread holds G_EPT of them per pass (more entries: more passes over the row blocks).  Every entry has one
 // owner and a fixed order of summation (row blocks ascending, rows ascending).  grid = (mask blocks, tasks).
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-constexpr int GB = 512;                 // edge of a mask block
+constexpr int GBK = 512, GBN = 256;     // rows and columns of a mask block
 constexpr int GP = 72;                  // LDS pitch (elements) of a line of 64 rows: 144 bytes
 constexpr int G_EPT = 2;                // entries per thread and pass
 constexpr int G_THREADS = 1024;
-constexpr int G_SMEM = 2 * GB * GP * 2 + (GB + 1) * 4 + GB * 4;
+constexpr int G_SMEM = (GBK + GBN) * GP * 2 + (GBK + 1) * 4 + GBK * 4;
 __global__ __launch_bounds__(G_THREADS) void k_diff_grad_tiled(const TaskRef tasks, const bf16_t* __restrict__ Xt,
                                                                const bf16_t* __restrict__ Gt, int K, int N, int accumulate) {
   extern __shared__ __align__(16) unsigned char g_smem[];
   bf16_t* Xs = (bf16_t*)g_smem;
-  bf16_t* Gs = Xs + GB * GP;
-  int* offs = (int*)(Gs + GB * GP);     // GB + 1: entries of the block before row i
-  int* start = offs + GB + 1;           // GB: index (in the row listing) of row i's first entry inside the block
+  bf16_t* Gs = Xs + GBK * GP;
+  int* offs = (int*)(Gs + GBN * GP);    // GBK + 1: entries of the block before row i
+  int* start = offs + GBK + 1;          // GBK: index (in the row listing) of row i's first entry inside the block
   const DevTask tk = get_task(tasks, (int)blockIdx.y);
   if (tk.kind != MUX_ADAPTER_DIFF || tk.dA == nullptr || tk.at_off == 0) return;
   // Workgroups go to the eight XCDs round-robin: XCD x takes a contiguous stretch of the blocks in row-major order, so
   // that the blocks running on it at one time share their lines of Xt in its L2.
-  const int n_nb = (N + GB - 1) / GB, n_blocks = ((K + GB - 1) / GB) * n_nb;
+  const int n_nb = (N + GBN - 1) / GBN, n_blocks = ((K + GBK - 1) / GBK) * n_nb;
   const int per_xcd = (n_blocks + 7) / 8;
   const int block = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
   if ((int)(blockIdx.x >> 3) >= per_xcd || block >= n_blocks) return;
-  const int k0 = (block / n_nb) * GB, n0 = (block % n_nb) * GB;
+  const int k0 = (block / n_nb) * GBK, n0 = (block % n_nb) * GBN;
   const int tid = threadIdx.x;
   const int32_t* row_ptr = (const int32_t*)tk.B;
   const int32_t* col_idx = (const int32_t*)tk.L;
-  if (tid < GB) {
+  if (tid < GBK) {
     int my_start = 0, my_cnt = 0;
     if (k0 + tid < K) {
       int a = row_ptr[k0 + tid], b = row_ptr[k0 + tid + 1];
@@ -237,26 +237,26 @@ __global__ __launch_bounds__(G_THREADS) void k_diff_grad_tiled(const TaskRef tas
       while (a < b) { const int m = (a + b) >> 1; if (col_idx[m] < n0) a = m + 1; else b = m; }
       my_start = a;
       b = hi;
-      while (a < b) { const int m = (a + b) >> 1; if (col_idx[m] < n0 + GB) a = m + 1; else b = m; }
+      while (a < b) { const int m = (a + b) >> 1; if (col_idx[m] < n0 + GBN) a = m + 1; else b = m; }
       my_cnt = a - my_start;
     }
     start[tid] = my_start;
-    offs[tid + 1] = my_cnt;             // inclusive prefix sums in offs[1 .. GB]
+    offs[tid + 1] = my_cnt;             // inclusive prefix sums in offs[1 .. GBK]
     if (tid == 0) offs[0] = 0;
   }
   __syncthreads();
-  for (int d = 1; d < GB; d <<= 1) {
-    const int v = (tid < GB && tid >= d) ? offs[tid + 1 - d] : 0;
+  for (int d = 1; d < GBK; d <<= 1) {
+    const int v = (tid < GBK && tid >= d) ? offs[tid + 1 - d] : 0;
     __syncthreads();
-    if (tid < GB) offs[tid + 1] += v;
+    if (tid < GBK) offs[tid + 1] += v;
     __syncthreads();
   }
-  const int total = offs[GB];
+  const int total = offs[GBK];
   if (total == 0) return;               // whole workgroup
-  const int lx = K - k0 < GB ? K - k0 : GB, lg = N - n0 < GB ? N - n0 : GB;   // lines of this block that exist
+  const int lx = K - k0 < GBK ? K - k0 : GBK, lg = N - n0 < GBN ? N - n0 : GBN;   // lines of this block that exist
   const int nbk = (tk.row_count + 63) >> 6;
   const size_t b0 = (size_t)tk.zrow0 >> 6;
-  constexpr int PPT = GB * 8 / G_THREADS;            // 16-byte pieces per thread and operand
+  constexpr int PPTX = GBK * 8 / G_THREADS, PPTG = GBN * 8 / G_THREADS;   // 16-byte pieces per thread of either operand
   // piece q of this thread: index tid + q * G_THREADS of the stretch (a line that does not exist reads line 0 instead
   // and is never staged)
   const int lx8 = lx * 8, lg8 = lg * 8;
@@ -269,7 +269,7 @@ __global__ __launch_bounds__(G_THREADS) void k_diff_grad_tiled(const TaskRef tas
       acc[i] = 0.f;
       kl[i] = 0; nl[i] = 0; ee[i] = -1;
       if (f < total) {
-        int lo = 0, hi = GB;                        // the row r with offs[r] <= f < offs[r + 1]
+        int lo = 0, hi = GBK;                       // the row r with offs[r] <= f < offs[r + 1]
         while (hi - lo > 1) { const int m = (lo + hi) >> 1; if (offs[m] <= f) lo = m; else hi = m; }
         kl[i] = lo;
         ee[i] = start[lo] + (f - offs[lo]);
@@ -277,23 +277,29 @@ __global__ __launch_bounds__(G_THREADS) void k_diff_grad_tiled(const TaskRef tas
       }
     }
     // two sets of staging registers: the lines of row blocks b + 1 and b + 2 are in flight while block b is summed
-    u32x4 rx0[PPT], rg0[PPT], rx1[PPT], rg1[PPT];
+    u32x4 rx0[PPTX], rg0[PPTG], rx1[PPTX], rg1[PPTG];
 #define DIFF_FETCH(RX, RG, B)                                                                  \
     if ((B) < nbk) {                                                                             \
       const u32x4* xs_ = (const u32x4*)(Xt + ((b0 + (B)) * (size_t)K + k0) * 64);                \
       const u32x4* gs_ = (const u32x4*)(Gt + ((b0 + (B)) * (size_t)N + n0) * 64);                \
-      _Pragma("unroll") for (int q = 0; q < PPT; ++q) {                                          \
+      _Pragma("unroll") for (int q = 0; q < PPTX; ++q) {                                         \
         const int p_ = tid + q * G_THREADS;                                                      \
         RX[q] = xs_[p_ < lx8 ? p_ : 0];                                                          \
+      }                                                                                          \
+      _Pragma("unroll") for (int q = 0; q < PPTG; ++q) {                                         \
+        const int p_ = tid + q * G_THREADS;                                                      \
         RG[q] = gs_[p_ < lg8 ? p_ : 0];                                                          \
       }                                                                                          \
     }
 #define DIFF_STEP(RX, RG, B)                                                                   \
     {                                                                                            \
       __syncthreads(); /* every read of the previous row block is done */                        \
-      _Pragma("unroll") for (int q = 0; q < PPT; ++q) {                                          \
+      _Pragma("unroll") for (int q = 0; q < PPTX; ++q) {                                         \
         const int p_ = tid + q * G_THREADS;                                                      \
         if (p_ < lx8) *(u32x4*)(Xs + (p_ >> 3) * GP + (p_ & 7) * 8) = RX[q];                     \
+      }                                                                                          \
+      _Pragma("unroll") for (int q = 0; q < PPTG; ++q) {                                         \
+        const int p_ = tid + q * G_THREADS;                                                      \
         if (p_ < lg8) *(u32x4*)(Gs + (p_ >> 3) * GP + (p_ & 7) * 8) = RG[q];                     \
       }                                                                                          \
       __syncthreads();                                                                           \
@@ -408,7 +414,7 @@ void backward(const CallCtx& c, const void* X, const void* dY, void* dX, int acc
     MUX_LAUNCH("diff_bwd", k_diff_apply<S>, dim3((unsigned)n_items * (unsigned)((c.K + (256 / Piece<S>::LPL) - 1) / (256 / Piece<S>::LPL))), dim3(256), 0, c.stream, c.dtab, *c.tref,
                (const S*)c.diffT[1], (S*)dX, c.N, c.K, 1);
   // by blocks of the mask where there are enough of them to occupy the compute units (bf16), else by entries
-  const int blocks = ((c.K + GB - 1) / GB) * ((c.N + GB - 1) / GB);
+  const int blocks = ((c.K + GBK - 1) / GBK) * ((c.N + GBN - 1) / GBN);
   if (std::is_same<S, bf16_t>::value && blocks * c.st->n_diff >= kTiledMinBlocks && tiled_grad_ready()) {
     MUX_LAUNCH("diff_grad", k_diff_grad_tiled, dim3((unsigned)(8 * ((blocks + 7) / 8)), (unsigned)c.st->n_tasks), dim3(G_THREADS), G_SMEM, c.stream,
                *c.tref, (const bf16_t*)c.diffT[0], (const bf16_t*)c.diffT[1], c.K, c.N, accumulate);
