@@ -229,7 +229,7 @@ def test_diff_pruning_routes(env):
 
 
 def test_diff_pruning_gradient_by_mask_blocks(env):
-    """On shapes with enough 512 x 512 blocks of the mask the masked gradient is summed block by block (the lines of
+    """On shapes with enough 512 x 256 blocks of the mask the masked gradient is summed block by block (the lines of
     a row block staged once per mask block): ragged last blocks in both directions, blocks with more entries than one
     pass holds, a task with an empty mask and one without rows, with and without accumulation."""
     mx, torch = env
