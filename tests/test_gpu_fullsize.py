@@ -25,7 +25,7 @@ def stratified_columns(rng, n, piece=128):
 
 CASES = [(1, 0), (1, 4), (1, 6), (2, 0), (2, 4), (2, 6), (3, 0), (3, 4), (3, 6), (4, 0), (4, 3), (4, 4), (4, 6),
          (5, 0),     # 5: the extra workload with two Adapter-Tuning tasks (their rows need x W in full: one projection)
-         (6, 0), (6, 6),   # 6: the extra workload with two Diff-Pruning tasks (d delta_t in full)
+         (6, 0), (6, 4), (6, 6),   # 6: the extra workload with two Diff-Pruning tasks (d delta_t in full); whole, half and quarter tiles
          (9, 0), (9, 4), (9, 5)]   # 9: Table 2's mix A (eight small tasks) on GPT3-2.7B shapes
 
 
