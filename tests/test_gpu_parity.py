@@ -385,18 +385,19 @@ def test_leading_dimension_packs_and_skipped_outputs(env):
 
 
 def test_task_table_by_value_and_in_memory(env):
-    """Up to 32 tasks travel in the kernel arguments; more than that (here 40, all kinds but the selective one, some
-    without rows) make the kernels read the table a small kernel wrote into the workspace.  Both against the oracle,
-    and bit-identical repeats."""
+    """Up to 32 tasks travel in the kernel arguments; more than that (here 40, every kind, some without rows) make the
+    kernels read the table a small kernel wrote into the workspace.  Both against the oracle, and bit-identical
+    repeats."""
     mx, torch = env
     rng = np.random.default_rng(77)
-    kinds = [wlm.KIND_LORA, wlm.KIND_LORA, wlm.KIND_IA3, wlm.KIND_ADAPTER, wlm.KIND_NONE]
+    kinds = [wlm.KIND_LORA, wlm.KIND_LORA, wlm.KIND_IA3, wlm.KIND_ADAPTER, wlm.KIND_NONE, wlm.KIND_DIFF]
     for n_tasks in (32, 40):
         tasks = []
         for t in range(n_tasks):
             kind = kinds[t % len(kinds)]
             rank = int(rng.choice([8, 16, 24])) if kind in (wlm.KIND_LORA, wlm.KIND_ADAPTER) else 0
-            tasks.append(wlm.Task(kind, rank, 1.5, [] if t % 11 == 7 else [int(rng.integers(5, 90))]))
+            tasks.append(wlm.Task(kind, rank, 1.5, [] if t % 11 == 7 else [int(rng.integers(5, 90))],
+                                  **({"density": 0.03} if kind == wlm.KIND_DIFF else {})))
         wl = wlm.Workload(name=f"many{n_tasks}", layers=[("w", 256, 192)], tasks=tasks, chunk=32, sigma_w=0.05, sigma_ab=0.05)
         g, got, ref, errs = run_case(env, wl, seed=n_tasks)
         keep = [t.clone() for t in [g.Y, g.dX] + [x for x in g.dA + g.dB + g.dL if x is not None]]
