@@ -228,6 +228,23 @@ def test_diff_pruning_routes(env):
             assert "diff_grad" in names, names
 
 
+def test_diff_pruning_routes_differ_by_direction(env):
+    """A LoRA rank that is not a multiple of 8 sends the backward to the register-staged GEMM: the forward still adds
+    the masked entries in its tile loop, the backward runs the sparse update after its product."""
+    mx, torch = env
+    tasks = [wlm.Task(wlm.KIND_LORA, 12, 2.0, [100]), wlm.Task(wlm.KIND_DIFF, 0, 1.0, [70, 45], density=0.02),
+             wlm.Task(wlm.KIND_DIFF, 0, 1.0, [150, 21], density=0.08), wlm.Task(wlm.KIND_IA3, 0, 1.0, [33])]
+    wl = wlm.Workload(name="diffdir", layers=[("w", 256, 384)], tasks=tasks, chunk=32, sigma_w=0.08, sigma_ab=0.08)
+    g, got, ref, errs = run_case(env, wl, seed=13)
+    mx.mux_profile_enable(1)
+    mx.mux_profile_collect()
+    g.forward(); g.backward()
+    torch.cuda.synchronize()
+    names = [e["name"] for e in mx.mux_profile_collect()]
+    mx.mux_profile_enable(0)
+    assert names.count("diff_pack") == 1 and "diff_bwd" in names and "diff_fwd" not in names and "diff_merge" not in names, names
+
+
 def test_diff_pruning_gradient_by_mask_blocks(env):
     """On shapes with enough 512 x 256 blocks of the mask the masked gradient is summed block by block (the lines of
     a row block staged once per mask block): ragged last blocks in both directions, blocks with more entries than one
