@@ -452,7 +452,7 @@ __global__ __launch_bounds__(512) void k_s4(const S4Params p) {
           float v = 0.f;
 #pragma unroll
           for (int w = 0; w < NWV; ++w) v += ((const float*)lds[w])[j * RPITCH + m];
-          const bool ok = base + m < it.nrows && j < p.RP;
+          const bool ok = base + m < it.nrows && j < 16 * NJ;     // (the reduction reads the task's rank pieces only)
           buf_store4(rG, ok ? (uint32_t)(((base + m) * p.RP + j) * 4) : OOB, v);
         }
         lds_barrier();
@@ -969,8 +969,11 @@ mux_status adapter_dy_pass(const CallCtx& c, const void* dY, const void* Hs, voi
   if (c.st->r_max <= 16) MUX_LAUNCH("s4_dy_pass", (k_s4<1, 2, 2>), grid, dim3(512), 0, c.stream, p);
   else if (c.st->r_max <= 32) MUX_LAUNCH("s4_dy_pass", (k_s4<2, 2, 1>), grid, dim3(512), 0, c.stream, p);
   else MUX_LAUNCH("s4_dy_pass", (k_s4<4, 1, 1>), grid, dim3(512), 0, c.stream, p);
-  // moved: the partials of every slab once in, Gs once out
-  prof_note_bytes((double)slabs * c.st->T * c.RP * 4 + (double)c.st->T * c.RP * 2);
+  // moved: the partials of every slab once in (a task's real tokens, its rank rounded up to four columns), Gs once out
+  double moved = (double)c.st->T * c.RP * 2;
+  for (const HostTask& ht : c.st->tasks)
+    if (ht.kind == MUX_ADAPTER_LORA || ht.kind == MUX_ADAPTER_TUNING) moved += (double)slabs * ht.valid * round_up(ht.rank, 4) * 4;
+  prof_note_bytes(moved);
   MUX_LAUNCH("gs_reduce", k_gs_reduce, dim3((unsigned)c.st->items[TS64].size()), dim3(256), 0, c.stream, c.dtab, *c.tref,
              (const float*)gpart, slabs, c.st->T, c.RP, (const bf16_t*)c.U2, (bf16_t*)Gs,
              c.st->dev_image[DH_NITEMS0 + 3 * TS64 + 1], c.st->dev_image[DH_OFF_ITEM_BITS]);
