@@ -670,6 +670,7 @@ struct TuneAddParams {
   bf16_t* Out;
   const bf16_t* AT;      // backward: base of the transposed region (D_t^T); forward: null (U_t = tk.B)
   int N, RP, backward;
+  int natural;           // backward: D_t [N][r] is read as it is (every rank a multiple of 8), nothing was transposed
   TaskRef tasks;
 };
 
@@ -691,14 +692,17 @@ __global__ __launch_bounds__(256) void k_tune_add(const TuneAddParams p) {
   float* sc = sC[wave];
 
   // P slab [NKS*32][64] -> LDS, natural layout; rows beyond the rank read as zero
+  const bool direct = p.backward && p.natural;      // D_t [N][r]: a lane's eight k of one column lie together in memory
   const rsrc_t rP = make_rsrc(P, (uint32_t)prow * (uint32_t)p.N * 2u);
   const int b_row = lane >> 3, b_pc = (lane & 7) * 8;
+  if (!direct) {
 #pragma unroll
-  for (int q = 0; q < NKS * 4; ++q) {
-    const int j = b_row + 8 * q;
-    const bool ok = j < prow && cw0 + b_pc < p.N;
-    const u32x4 v = buf_load16(rP, ok ? (uint32_t)(((size_t)j * p.N + cw0 + b_pc) * 2) : OOB);
-    *(u32x4*)(sp + j * GP + b_pc) = v;
+    for (int q = 0; q < NKS * 4; ++q) {
+      const int j = b_row + 8 * q;
+      const bool ok = j < prow && cw0 + b_pc < p.N;
+      const u32x4 v = buf_load16(rP, ok ? (uint32_t)(((size_t)j * p.N + cw0 + b_pc) * 2) : OOB);
+      *(u32x4*)(sp + j * GP + b_pc) = v;
+    }
   }
   // Small rows in the A-operand layout straight from global memory: row = 16 rt + lane%16, k = 32 ks + 8 (lane/16)
   const int i = lane & 15, g = lane >> 4;
@@ -715,13 +719,24 @@ __global__ __launch_bounds__(256) void k_tune_add(const TuneAddParams p) {
   __builtin_amdgcn_wave_barrier();
   const int tr_off = (8 * g + (i >> 2)) * GP + 4 * (i & 3);
   bf16x8 b[4][NKS];
+  if (direct) {
+    const rsrc_t rD = make_rsrc(tk.A, (uint32_t)p.N * (uint32_t)rank * 2u);
 #pragma unroll
-  for (int ct = 0; ct < 4; ++ct)
+    for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      const bf16x4 lo = lds_read_tr(sp + ks * 32 * GP + tr_off + ct * 16), hi = lds_read_tr(sp + ks * 32 * GP + tr_off + 4 * GP + ct * 16);
-      b[ct][ks] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    }
+      for (int ks = 0; ks < NKS; ++ks) {
+        const int col = cw0 + ct * 16 + i, k = ks * 32 + 8 * g;
+        b[ct][ks] = as_bf16x8(buf_load16(rD, (col < p.N && k < rank) ? (uint32_t)(((size_t)col * rank + k) * 2) : OOB));
+      }
+  } else {
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        const bf16x4 lo = lds_read_tr(sp + ks * 32 * GP + tr_off + ct * 16), hi = lds_read_tr(sp + ks * 32 * GP + tr_off + 4 * GP + ct * 16);
+        b[ct][ks] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+  }
 
   const uint32_t vbits_lo = row_valid_bits32(p.dtab, it.row0);
   const uint32_t vbits_hi = it.nrows > 32 ? row_valid_bits32(p.dtab, it.row0 + 32) : 0u;
@@ -983,7 +998,8 @@ mux_status adapter_dy_pass(const CallCtx& c, const void* dY, const void* Hs, voi
 // Adapter-Tuning: Y = z + Hs U_t (forward) or dYs = dY + Gs D_t^T (backward, D_t^T from the transposed region)
 mux_status adapter_tune_add(const CallCtx& c, const void* In, const void* Small, void* Out, int backward) {
   if (c.st->n_tuning == 0) return MUX_OK;
-  TuneAddParams p{c.dtab, (const bf16_t*)In, (const bf16_t*)Small, (bf16_t*)Out, (const bf16_t*)c.AT, c.N, c.RP, backward};
+  TuneAddParams p{c.dtab, (const bf16_t*)In, (const bf16_t*)Small, (bf16_t*)Out, (const bf16_t*)c.AT, c.N, c.RP, backward,
+                  c.tune_natural ? 1 : 0};
   p.tasks = *c.tref;
   const dim3 grid((unsigned)c.st->items[TS64].size(), (c.N + 255) / 256);
   if (c.RP <= 32) MUX_LAUNCH(backward ? "tune_dz" : "tune_up", (k_tune_add<1>), grid, dim3(256), 0, c.stream, p);
@@ -991,12 +1007,12 @@ mux_status adapter_tune_add(const CallCtx& c, const void* In, const void* Small,
   return MUX_OK;
 }
 
-// Adapter-Tuning forward, after the backbone GEMM saved z = x W: u = z D_t, Hs = s_t gelu(u).  D_t^T was laid into
-// c.AT by the packing kernel of this call.
+// Adapter-Tuning forward, after the backbone GEMM saved z = x W: u = z D_t, Hs = s_t gelu(u).  D_t [N, r] is read as it
+// is when every such rank is a multiple of 8; else D_t^T was laid into c.AT by the packing kernel of this call.
 mux_status adapter_down_tune(const CallCtx& c, const void* Z, void* Hs) {
   if (c.st->n_tuning == 0) return MUX_OK;
-  DownParams p{c.dtab, (const bf16_t*)Z, (bf16_t*)Hs, (const bf16_t*)c.AT, (bf16_t*)c.U2, c.N, c.RP, DOWN_TUNE};
-  launch_down(c, "tune_down", p, false);
+  DownParams p{c.dtab, (const bf16_t*)Z, (bf16_t*)Hs, c.tune_natural ? nullptr : (const bf16_t*)c.AT, (bf16_t*)c.U2, c.N, c.RP, DOWN_TUNE};
+  launch_down(c, "tune_down", p, c.tune_natural);
   return MUX_OK;
 }
 

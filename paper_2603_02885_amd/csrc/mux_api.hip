@@ -239,6 +239,11 @@ bool any_packed_lora(const mux_segtab* st) {
     if (ht.kind == MUX_ADAPTER_LORA && !lora_a_natural(ht)) return true;
   return false;
 }
+bool any_packed_tuning(const mux_segtab* st) {
+  for (const HostTask& ht : st->tasks)
+    if (ht.kind == MUX_ADAPTER_TUNING && (ht.rank & 7) != 0) return true;
+  return false;
+}
 
 }  // namespace
 }  // namespace mux
@@ -304,7 +309,8 @@ extern "C" mux_status mux_lora_forward(const mux_layer_desc* layer, const mux_se
   std::vector<DevTask> tasks;
   build_tasks(layer, st, nullptr, nullptr, nullptr, c.lora_natural, c.diffPack ? 2 : (c.diffW ? 1 : 0), false, tasks);
   TaskRef tref;
-  const int pack = !fast ? 0 : ((st->n_lora > 0 && !c.lora_natural) ? 1 : (st->n_tuning > 0 ? 2 : 0));
+  c.tune_natural = fast && !any_packed_tuning(st);
+  const int pack = !fast ? 0 : ((st->n_lora > 0 && !c.lora_natural) ? 1 : ((st->n_tuning > 0 && !c.tune_natural) ? 2 : 0));
   publish_tasks(layer, st, tasks, !fast, (DevTask*)ws, tref, pack, c.AT, stream);
   c.tref = &tref;
   c.dtasks = tref.mem;
@@ -344,7 +350,8 @@ static mux_status backward_impl(const char* fn, const mux_layer_desc* layer, con
   std::vector<DevTask> tasks;
   build_tasks(layer, st, dA, dB, dL, c.lora_natural, c.diffPack ? 2 : (c.diffW ? 1 : 0), true, tasks);
   TaskRef tref;
-  publish_tasks(layer, st, tasks, !fast, (DevTask*)ws, tref, (fast && st->n_tuning > 0) ? 2 : 0, c.AT, stream);
+  c.tune_natural = fast && !any_packed_tuning(st);
+  publish_tasks(layer, st, tasks, !fast, (DevTask*)ws, tref, (fast && st->n_tuning > 0 && !c.tune_natural) ? 2 : 0, c.AT, stream);
   c.tref = &tref;
   c.dtasks = tref.mem;
   if (st->T == 0) {                 // no rows at all: zero gradients (or leave the accumulators as they are)

@@ -136,6 +136,7 @@ struct CallCtx {
   hipStream_t stream;
   void* U2;                // saved: pre-activations z D_t of the TUNING rows, [T][RP] (null without such tasks)
   bool lora_natural;       // every LoRA rank is a multiple of 8: the down-projection reads A_t [K, r] as it is
+  bool tune_natural;       // likewise every Adapter-Tuning rank: D_t [N, r] is read as it is, forward and backward
   int diff_max_nnz;        // largest mask of the DIFF tasks of this call
   void* diffT[2];          // workspace: block-transposed copies of the DIFF rows of X ([0]) and of dY ([1])
   void* diffW;             // workspace: per DIFF task with entries, W + M_t * delta_t [K][ldw] bf16 (matrix-core path;

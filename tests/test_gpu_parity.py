@@ -163,10 +163,11 @@ def test_read_probe_runs(env):
         mx.mux_probe_read(None, 1024, sink, None)
 
 
-def tuning_workload(K=192, N=160, chunk=32):
-    """The additive bottleneck kind between the others: ragged ranks and token counts, padding, an empty task."""
-    tasks = [wlm.Task(wlm.KIND_LORA, 16, 2.0, [100]), wlm.Task(wlm.KIND_ADAPTER, 8, 1.5, [70, 45]),
-             wlm.Task(wlm.KIND_IA3, 0, 1.0, [33]), wlm.Task(wlm.KIND_ADAPTER, 24, 0.5, [150, 21]),
+def tuning_workload(K=192, N=160, chunk=32, ranks=(8, 24)):
+    """The additive bottleneck kind between the others: ragged ranks and token counts, padding, an empty task.  With
+    every bottleneck width a multiple of 8 the matrix-core path reads D_t as it is stored, else a transposed copy."""
+    tasks = [wlm.Task(wlm.KIND_LORA, 16, 2.0, [100]), wlm.Task(wlm.KIND_ADAPTER, ranks[0], 1.5, [70, 45]),
+             wlm.Task(wlm.KIND_IA3, 0, 1.0, [33]), wlm.Task(wlm.KIND_ADAPTER, ranks[1], 0.5, [150, 21]),
              wlm.Task(wlm.KIND_NONE, 0, 1.0, [64]), wlm.Task(wlm.KIND_ADAPTER, 64, 1.0, [5]),
              wlm.Task(wlm.KIND_ADAPTER, 16, 2.0, [])]
     return wlm.Workload(name="tuning", layers=[("w", K, N)], tasks=tasks, chunk=chunk, sigma_w=0.08, sigma_ab=0.08)
@@ -182,6 +183,7 @@ def test_adapter_tuning_kind(env, mode, seg_flags):
     lf = mx.MUX_LAYER_REFERENCE_KERNELS if mode == "bf16_ref" else 0
     run_case(env, tuning_workload(), dtype=dtype, seg_flags=seg_flags, layer_flags=lf, seed=5)
     run_case(env, tuning_workload(K=104, N=232, chunk=16), dtype=dtype, seg_flags=seg_flags, layer_flags=lf, seed=6)
+    run_case(env, tuning_workload(K=256, N=192, ranks=(12, 20)), dtype=dtype, seg_flags=seg_flags, layer_flags=lf, seed=7)
 
 
 def diff_workload(K=192, N=160, chunk=32, density=0.02):
