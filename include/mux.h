@@ -183,7 +183,9 @@ typedef struct {
 
 /* Bytes of `saved` (forward -> backward: scaled adapter activations s_t (x A_t); x W of the
  * IA3_OUT and TUNING rows; the pre-activations z D_t of the TUNING rows) and of `ws` (scratch,
- * contents undefined between calls). */
+ * contents undefined between calls).  Both follow from the layer description and the table alone
+ * (for DIFF tasks also from what their masks bring: with the listing by tiles the call packs the
+ * entries, 4 bytes each; without it, it may hold a copy of W per such task). */
 size_t mux_lora_saved_bytes(const mux_layer_desc* layer, const mux_segtab* st);
 size_t mux_lora_workspace_bytes(const mux_layer_desc* layer, const mux_segtab* st);
 
